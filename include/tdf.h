@@ -1,0 +1,223 @@
+/* tdf — tagged static-dataflow execution of recursive function definitions on one GPU.
+ *
+ * C ABI of libtdf.  A program is a set of function graphs, one of them the `result`
+ * graph (paper Section 2.4).  tdf_graph_build turns it into one static graph with
+ * Call_i / Return_i nodes (Section 3) and, on request, joins every function with its
+ * gradient under shared call labels (Section 4).  tdf_eval / tdf_eval_grad execute the
+ * static graph over a batch of instances: tokens carry call-context tags
+ * (Call_i <t,d> = <i:t,d>, Return_i <i:t,d> = <t,d>), tokens are matched by tag, and a
+ * node body fires over every matched tag of a step at once.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory on the current device, owned by the caller
+ *     for the whole call; "host" pointers are ordinary process memory.
+ *   - The library allocates no device memory.  All transient device state lives in the
+ *     caller's workspace (tdf_workspace_size bytes, 256-byte aligned).
+ *   - Work is enqueued on the caller's HIP stream.  The evaluation calls synchronise that
+ *     stream before returning (the step count of a recursion is data dependent and is
+ *     read back).
+ *   - Every function returns a tdf_status; a message for the last failure on the calling
+ *     thread is available from tdf_last_error().  No exception crosses the ABI.
+ */
+#ifndef TDF_H
+#define TDF_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tdf_graph tdf_graph; /* opaque, library-owned host object */
+
+typedef enum {
+  TDF_OK = 0,
+  TDF_ERR_BAD_PROGRAM = -1, /* malformed program description                         */
+  TDF_ERR_BAD_ARG = -2,     /* NULL / inconsistent argument                           */
+  TDF_ERR_WORKSPACE = -3,   /* workspace too small or misaligned                      */
+  TDF_ERR_TABLE_FULL = -4,  /* more tags, tokens or state rows than max_tags allows   */
+  TDF_ERR_STEP_LIMIT = -5,  /* recursion did not finish within step_limit steps       */
+  TDF_ERR_DEVICE = -6       /* a HIP call failed                                      */
+} tdf_status;
+
+/* ---- program description (host memory, read only during tdf_graph_build) ------------
+ * Node operators.  The first group is the paper's language (Sections 2.2 and 2.4); the
+ * TREE_* group reads the forest arrays of tdf_inputs at a node-index value; the last group
+ * are vector-valued operators whose results live in the state table and travel through the
+ * graph as row references.  */
+typedef enum {
+  TDF_OP_IN = 0,      /* formal parameter; imm = parameter index                        */
+  TDF_OP_OUT,         /* the function's single output; in[0] = value                    */
+  TDF_OP_CONST,       /* imm = int64 value                                              */
+  TDF_OP_ADD, TDF_OP_SUB, TDF_OP_MUL, /* int64 arithmetic, wrapping                     */
+  TDF_OP_EQ, TDF_OP_LT,               /* int64 comparison, result 0/1                   */
+  TDF_OP_ID,
+  TDF_OP_SWITCH,      /* in[0] = predicate, in[1] = data; port 0 = true, 1 = false side */
+  TDF_OP_MERGE,       /* forwards the live input (2..4 inputs)                          */
+  TDF_OP_CALLFN,      /* imm = callee function index; in[k] = argument k                */
+  TDF_OP_TREE_ISLEAF, /* left[v] < 0                                                    */
+  TDF_OP_TREE_LEFT, TDF_OP_TREE_RIGHT, TDF_OP_TREE_TOKEN,
+  TDF_OP_EMBED,       /* in[0] = token id -> row E[token] (TreeLSTM: cell state 0)      */
+  TDF_OP_RNN_CELL,    /* in[0], in[1] = child rows -> tanh(W [h_l; h_r] + b)            */
+  TDF_OP_LSTM_CELL,   /* binary TreeLSTM, gate row blocks (i, f_l, f_r, o, u) of W      */
+  TDF_OP_CE_HEAD,     /* in[0] = row, in[1] = label -> -log softmax(U h + u0)[label]    */
+  TDF_OP_COUNT
+} tdf_op;
+
+#define TDF_MAX_INPUTS 4
+
+typedef struct {
+  int32_t node; /* index of the producing node inside the same function */
+  int32_t port; /* 0, or 1 for the false side of a SWITCH               */
+} tdf_ref;
+
+typedef struct {
+  int32_t op;   /* tdf_op */
+  int32_t n_in; /* number of inputs used */
+  tdf_ref in[TDF_MAX_INPUTS];
+  int64_t imm;
+} tdf_node_desc;
+
+typedef struct {
+  const char* name;
+  int32_t n_params;
+  int32_t n_nodes;
+  const tdf_node_desc* nodes; /* inputs must refer to earlier nodes (topological order) */
+} tdf_function_desc;
+
+typedef struct {
+  int32_t n_functions;
+  const tdf_function_desc* functions;
+  int32_t result_fn; /* index of the `result` graph; its parameters are the program inputs */
+} tdf_program_desc;
+
+/* Section 3 (and Section 4 when want_grad != 0): validate the program, number the call
+ * nodes, build the static graph, and compile the per-function firing tables used on the
+ * device.  Host only.  Rejected with TDF_ERR_BAD_PROGRAM: undefined callee, arity
+ * mismatch, forward reference, more or fewer than one OUT per function, an operator
+ * whose inputs are all constants outside `result`, more than 64 nodes in a function, a
+ * gradient request for a program without vector operators.  *out is owned by the library
+ * until tdf_graph_destroy. */
+tdf_status tdf_graph_build(const tdf_program_desc* prog, int want_grad, tdf_graph** out);
+void tdf_graph_destroy(tdf_graph* g);
+
+/* ---- the static graph, for inspection (Section 3, figure "The transformed graph of
+ * fact").  Node kinds: the tdf_op values for ordinary nodes, plus the three below.  */
+#define TDF_SNODE_MERGE_ENTRY 100 /* Merge that replaced a callee's input node          */
+#define TDF_SNODE_CALL 101        /* Call_i for one formal parameter                    */
+#define TDF_SNODE_RETURN 102      /* Return_i                                           */
+
+typedef struct {
+  int32_t kind;    /* tdf_op or TDF_SNODE_*                                             */
+  int32_t fn;      /* function graph the node came from                                 */
+  int32_t label;   /* call label i for CALL / RETURN, else -1                           */
+  int32_t param;   /* parameter index for CALL / MERGE_ENTRY / IN, else -1              */
+  int32_t is_grad; /* 1 for nodes of the gradient half of a joint function              */
+  int64_t imm;     /* CONST value                                                       */
+} tdf_snode;
+
+typedef struct {
+  int32_t src, src_port, dst, dst_slot;
+  int32_t is_control; /* 1 for the Call_i -> Return_i synchronising edges               */
+} tdf_sedge;
+
+typedef struct {
+  int32_t n_nodes, n_edges, n_labels;
+  const tdf_snode* nodes; /* library-owned, valid until tdf_graph_destroy               */
+  const tdf_sedge* edges;
+} tdf_graph_info_t;
+
+tdf_status tdf_graph_info(const tdf_graph* g, tdf_graph_info_t* out);
+
+/* ---- evaluation ------------------------------------------------------------------- */
+typedef enum { TDF_F32 = 0, TDF_BF16 = 1 } tdf_dtype;
+
+typedef struct {
+  int32_t n_instances; /* B: the batch; instance b runs under root tag (b)              */
+  int32_t n_args;      /* = n_params of `result`                                        */
+  const int64_t* args; /* device int64[B * n_args], instance-major                      */
+  /* forest, used by the TREE_* operators (may be NULL for integer programs)            */
+  int32_t n_tree_nodes;
+  const int32_t* left;  /* device int32[n_tree_nodes], -1 at a leaf                     */
+  const int32_t* right; /* device int32[n_tree_nodes]                                   */
+  const int32_t* token; /* device int32[n_tree_nodes], token id at a leaf               */
+  /* parameters of the vector operators (may be NULL / 0 for integer programs)          */
+  int32_t dtype;  /* tdf_dtype of E, W and of the hidden-state rows                     */
+  int32_t hidden; /* H                                                                  */
+  int32_t vocab;
+  const void* E;  /* device [vocab x H], dtype, row-major                               */
+  const void* W;  /* device [R x 2H], dtype, row-major; R = H (RNN) or 5H (LSTM)        */
+  const float* b; /* device float[R]                                                    */
+  int32_t n_classes;
+  const float* U;  /* device float[n_classes x H]   (CE_HEAD)                           */
+  const float* u0; /* device float[n_classes]                                           */
+  /* capacities */
+  int64_t max_tags;   /* upper bound on call-context tags (= invocations) of one call   */
+  int32_t step_limit; /* 0 = default (1<<20)                                            */
+} tdf_inputs;
+
+typedef struct {
+  int64_t* out_i64; /* device int64[B]: integer result                                  */
+  float* out_f32;   /* device float[B]: scalar float result (CE_HEAD loss per instance) */
+  float* out_h;     /* device float[B x H]: vector result, h of the root                */
+  float* out_c;     /* device float[B x H]: TreeLSTM cell state of the root, or NULL    */
+} tdf_outputs;      /* only the member matching the result type is written; others may be NULL */
+
+typedef struct {
+  const float* dy; /* device: float[B] for a scalar result, float[B x H] (dL/dh of each
+                      root) for a vector result                                         */
+} tdf_seed;
+
+typedef struct {
+  float* dW; /* device float[R x 2H]  } overwritten with the gradients                  */
+  float* db; /* device float[R]       }                                                 */
+  float* dE; /* device float[vocab x H], rows of tokens that do not occur are set to 0  */
+} tdf_grads;
+
+#define TDF_STATS_MAX_COUNTS 256
+
+typedef struct {
+  int64_t n_tags;         /* call-context tags created = function invocations           */
+  int64_t n_steps;        /* match/fire steps of the tag machine                        */
+  int64_t n_tokens;       /* Call and Return tokens delivered                           */
+  int64_t n_leaf_rows;    /* EMBED firings                                              */
+  int64_t n_cell_rows;    /* RNN_CELL / LSTM_CELL firings                               */
+  int64_t n_waves;        /* dependency levels of the cell firings                      */
+  int64_t n_grad_firings; /* gradient-body firings (one per tag) in tdf_eval_grad       */
+  int64_t max_tag_depth;  /* longest list of call labels                                */
+  int64_t table_capacity; /* slots of the tag-hash table                                */
+  int64_t max_probe;      /* longest probe sequence                                     */
+  int32_t device_status;  /* tdf_status raised on the device                            */
+  int32_t n_counts;       /* entries used in fire_count                                 */
+  /* live firings per static-graph node, indexed like tdf_graph_info_t.nodes            */
+  int64_t fire_count[TDF_STATS_MAX_COUNTS];
+} tdf_stats;
+
+/* Bytes of workspace needed by tdf_eval (with_grad = 0) or tdf_eval_grad (1) for these
+ * inputs (only sizes and capacities are read, no device memory is touched). */
+tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* in, int with_grad, size_t* bytes);
+
+/* Forward evaluation of `result` for every instance (Sections 2.2, 3, 5.1).
+ *   workspace: device, >= tdf_workspace_size bytes, 256-byte aligned, contents ignored.
+ *   hip_stream: a hipStream_t (NULL = the default stream).
+ *   stats: host, may be NULL.
+ * Device-detected conditions (capacity, step limit) end the evaluation cleanly and are
+ * returned as the status. */
+tdf_status tdf_eval(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* workspace,
+                    size_t workspace_bytes, void* hip_stream, tdf_stats* stats);
+
+/* Forward and gradient in one call (Section 4: the joint graph computes the forward values
+ * and the gradients; gradient operators meet the retained forward values under equal tags).
+ * dy seeds the gradient of the result of each instance; grads receives the sums over all
+ * tags of the parameter-gradient terms.  The graph must have been built with want_grad. */
+tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out,
+                         tdf_grads* grads, void* workspace, size_t workspace_bytes,
+                         void* hip_stream, tdf_stats* stats);
+
+const char* tdf_last_error(void); /* thread-local, static storage */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TDF_H */

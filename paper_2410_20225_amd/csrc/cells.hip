@@ -1,0 +1,615 @@
+// Node bodies of the vector operators, fired over all tags of a dependency level at once:
+// leaf rows (EMBED), the tree cells as gathered-operand MFMA GEMMs with fused epilogues,
+// the classification head, and their gradient operators (Section 4: op^grad takes the
+// forward inputs and the output gradient).  Parameter gradients are sums over all tags,
+// formed without floating-point atomics: one split GEMM over the tag dimension with an
+// ordered reduction of the partial tiles, and a segmented sum over leaves sorted by token.
+#include <algorithm>
+
+#include "engine.h"
+
+namespace tdf {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+namespace {
+
+// ---- element traits --------------------------------------------------------------------
+template <typename T> struct El;
+template <> struct El<__bf16> {
+  static constexpr int BK = 32;      // k extent of one LDS tile
+  static constexpr int PAD = 8;      // row padding in elements
+  static constexpr int MK = 16;      // k extent of one MFMA
+  static constexpr int CH = 8;       // elements per 16-byte chunk
+  typedef bf16x8 Frag;
+  static __device__ __forceinline__ Frag frag(const __bf16* row, int ks, int lane) {
+    return *reinterpret_cast<const Frag*>(row + ks * MK + (lane >> 5) * 8);
+  }
+  static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct El<float> {
+  static constexpr int BK = 16;
+  static constexpr int PAD = 4;
+  static constexpr int MK = 2;
+  static constexpr int CH = 4;
+  typedef float Frag;
+  static __device__ __forceinline__ Frag frag(const float* row, int ks, int lane) {
+    return row[ks * MK + (lane >> 5)];
+  }
+  static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+  }
+};
+
+__device__ __forceinline__ float to_f(float x) { return x; }
+__device__ __forceinline__ float to_f(__bf16 x) { return (float)x; }
+template <typename T> __device__ __forceinline__ T from_f(float x) { return (T)x; }
+
+__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+// ---- GEMM  C[M x N] = A[M x K] * B[N x K]^T, both operands k-contiguous ----------------------
+enum GemmMode { RNN_FWD = 0, LSTM_FWD = 1, DX_BWD = 2, DW_SPLIT = 3 };
+
+struct GemmArgs {
+  int M, N, K;               // N, K multiples of 32
+  const void* A;             // dense A (DX_BWD: Dz + q0 rows; DW_SPLIT: DzT)
+  size_t lda;
+  const void* B;
+  size_t ldb;
+  // gathered A rows for the forward cells: row m = [Hs[l[m]]; Hs[r[m]]]
+  const void* Hs;
+  int Hp;
+  const uint32_t *out, *l, *r;   // already offset to the level's first cell
+  const float* bias;
+  void* Hs_out;              // state rows written by the forward cells
+  float* Cs;                 // LSTM cell state rows
+  void* gates;               // LSTM activations, row m of this level
+  size_t ldg;
+  float* C;                  // fp32 output (DX_BWD: dH; DW_SPLIT: partial tiles)
+  size_t ldc;
+  int k_per_split;           // DW_SPLIT: k range of one blockIdx.z
+  int save_gates;
+};
+
+constexpr int GEMM_THREADS = 256;
+constexpr int BM = 128;
+
+template <typename T, int MODE>
+__global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
+  typedef El<T> E;
+  constexpr int WN = MODE == LSTM_FWD ? 5 : 2;   // 32-wide column blocks per wave
+  constexpr int BN = 2 * WN * 32;                // columns per workgroup
+  constexpr int LDT = E::BK + E::PAD;            // LDS row stride
+  constexpr int CPR = E::BK / E::CH;             // 16-byte chunks per tile row
+  constexpr int A_CHUNKS = BM * CPR / GEMM_THREADS;
+  constexpr int B_CHUNKS = BN * CPR / GEMM_THREADS;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  T* sA = reinterpret_cast<T*>(smem);                  // [2][BM][LDT]
+  T* sB = sA + 2 * BM * LDT;                           // [2][BN][LDT]
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int m0 = blockIdx.x * BM;
+  int k_begin = 0, k_end = g.K;
+  if (MODE == DW_SPLIT) {
+    k_begin = blockIdx.z * g.k_per_split;
+    k_end = min(g.K, k_begin + g.k_per_split);
+  }
+
+  // global row of B held by tile row `br`
+  auto b_row = [&](int br) -> int {
+    if (MODE == LSTM_FWD) {
+      const int w = br / 160, gate = (br % 160) / 32, jj = br % 32;
+      int jb = blockIdx.y * 2 + w;
+      jb = min(jb, g.Hp / 32 - 1);
+      return gate * g.Hp + jb * 32 + jj;
+    }
+    return min((int)blockIdx.y * BN + br, g.N - 1);
+  };
+
+  // per-thread source pointers of the chunks it copies each k-tile
+  const T* a_src[A_CHUNKS];
+  const T* a_src2[A_CHUNKS];   // second half of a gathered row
+  int a_dst[A_CHUNKS];
+  for (int c = 0; c < A_CHUNKS; ++c) {
+    const int id = tid + c * GEMM_THREADS, row = id / CPR, ch = id % CPR;
+    const int m = min(m0 + row, g.M - 1);
+    a_dst[c] = row * LDT + ch * E::CH;
+    if (MODE == RNN_FWD || MODE == LSTM_FWD) {
+      a_src[c] = reinterpret_cast<const T*>(g.Hs) + (size_t)g.l[m] * g.Hp + ch * E::CH;
+      a_src2[c] = reinterpret_cast<const T*>(g.Hs) + (size_t)g.r[m] * g.Hp + ch * E::CH;
+    } else {
+      a_src[c] = reinterpret_cast<const T*>(g.A) + (size_t)m * g.lda + ch * E::CH;
+      a_src2[c] = a_src[c];
+    }
+  }
+  const T* b_src[B_CHUNKS];
+  int b_dst[B_CHUNKS];
+  for (int c = 0; c < B_CHUNKS; ++c) {
+    const int id = tid + c * GEMM_THREADS, row = id / CPR, ch = id % CPR;
+    b_dst[c] = row * LDT + ch * E::CH;
+    b_src[c] = reinterpret_cast<const T*>(g.B) + (size_t)b_row(row) * g.ldb + ch * E::CH;
+  }
+
+  uint4 ra[A_CHUNKS], rb[B_CHUNKS];
+  auto load_global = [&](int k0) {
+    for (int c = 0; c < A_CHUNKS; ++c) {
+      const T* p;
+      if (MODE == RNN_FWD || MODE == LSTM_FWD) p = k0 < g.Hp ? a_src[c] + k0 : a_src2[c] + (k0 - g.Hp);
+      else p = a_src[c] + k0;
+      ra[c] = *reinterpret_cast<const uint4*>(p);
+    }
+    for (int c = 0; c < B_CHUNKS; ++c) rb[c] = *reinterpret_cast<const uint4*>(b_src[c] + k0);
+  };
+  auto store_lds = [&](int buf) {
+    for (int c = 0; c < A_CHUNKS; ++c) *reinterpret_cast<uint4*>(sA + buf * BM * LDT + a_dst[c]) = ra[c];
+    for (int c = 0; c < B_CHUNKS; ++c) *reinterpret_cast<uint4*>(sB + buf * BN * LDT + b_dst[c]) = rb[c];
+  };
+
+  f32x16 acc[2][WN];
+  for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < WN; ++j)
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  int buf = 0;
+  if (k_begin < k_end) {
+    load_global(k_begin);
+    store_lds(0);
+  }
+  __syncthreads();
+  for (int k0 = k_begin; k0 < k_end; k0 += E::BK) {
+    const bool more = k0 + E::BK < k_end;
+    if (more) load_global(k0 + E::BK);
+    const T* tA = sA + buf * BM * LDT + (wm * 64 + (lane & 31)) * LDT;
+    const T* tB = sB + buf * BN * LDT + (wn * WN * 32 + (lane & 31)) * LDT;
+#pragma unroll
+    for (int ks = 0; ks < E::BK / E::MK; ++ks) {
+      typename E::Frag fa[2], fb[WN];
+      for (int i = 0; i < 2; ++i) fa[i] = E::frag(tA + i * 32 * LDT, ks, lane);
+      for (int j = 0; j < WN; ++j) fb[j] = E::frag(tB + j * 32 * LDT, ks, lane);
+      for (int i = 0; i < 2; ++i)
+        for (int j = 0; j < WN; ++j) acc[i][j] = E::mma(fa[i], fb[j], acc[i][j]);
+    }
+    if (more) store_lds(buf ^ 1);
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // ---- epilogue.  acc[i][j][r]: row = i*32 + (r/4)*8 + (lane/32)*4 + r%4, column = lane%32
+  const int col = lane & 31;
+  for (int i = 0; i < 2; ++i) {
+    for (int r = 0; r < 16; ++r) {
+      const int m = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+      if (m >= g.M) continue;
+      if constexpr (MODE == RNN_FWD) {
+        for (int j = 0; j < WN; ++j) {
+          const int n = blockIdx.y * BN + (wn * WN + j) * 32 + col;
+          if (n >= g.N) continue;
+          const float h = tanhf(acc[i][j][r] + g.bias[n]);
+          reinterpret_cast<T*>(g.Hs_out)[(size_t)g.out[m] * g.Hp + n] = from_f<T>(h);
+        }
+      } else if constexpr (MODE == LSTM_FWD) {
+        const int jb = blockIdx.y * 2 + wn;
+        if (jb * 32 >= g.Hp) continue;
+        const int n = jb * 32 + col;   // hidden unit
+        const float gi = sigmoidf_(acc[i][0][r] + g.bias[n]);
+        const float gfl = sigmoidf_(acc[i][1][r] + g.bias[g.Hp + n]);
+        const float gfr = sigmoidf_(acc[i][2][r] + g.bias[2 * g.Hp + n]);
+        const float go = sigmoidf_(acc[i][3][r] + g.bias[3 * g.Hp + n]);
+        const float gu = tanhf(acc[i][4][r] + g.bias[4 * g.Hp + n]);
+        const float cl = g.Cs[(size_t)g.l[m] * g.Hp + n], cr = g.Cs[(size_t)g.r[m] * g.Hp + n];
+        const float c = gi * gu + gfl * cl + gfr * cr;
+        const size_t o = (size_t)g.out[m] * g.Hp + n;
+        g.Cs[o] = c;
+        reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * tanhf(c));
+        if (g.save_gates) {
+          T* gr = reinterpret_cast<T*>(g.gates) + (size_t)m * g.ldg;
+          gr[n] = from_f<T>(gi);
+          gr[g.Hp + n] = from_f<T>(gfl);
+          gr[2 * g.Hp + n] = from_f<T>(gfr);
+          gr[3 * g.Hp + n] = from_f<T>(go);
+          gr[4 * g.Hp + n] = from_f<T>(gu);
+        }
+      } else if constexpr (MODE == DX_BWD) {
+        for (int j = 0; j < WN; ++j) {
+          const int n = blockIdx.y * BN + (wn * WN + j) * 32 + col;
+          if (n >= g.N) continue;
+          // column n of [dh_l; dh_r]: each child row has exactly one consumer, plain store
+          if (n < g.Hp) g.C[(size_t)g.l[m] * g.Hp + n] = acc[i][j][r];
+          else g.C[(size_t)g.r[m] * g.Hp + (n - g.Hp)] = acc[i][j][r];
+        }
+      } else {
+        for (int j = 0; j < WN; ++j) {
+          const int n = blockIdx.y * BN + (wn * WN + j) * 32 + col;
+          if (n >= g.N) continue;
+          g.C[(size_t)blockIdx.z * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
+        }
+      }
+    }
+  }
+}
+
+template <typename T, int MODE> size_t gemm_lds_bytes() {
+  constexpr int WN = MODE == LSTM_FWD ? 5 : 2;
+  return (size_t)2 * (BM + 2 * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
+}
+
+template <typename T, int MODE> void launch_gemm(const GemmArgs& g, int n_tiles_y, int splits, hipStream_t s) {
+  if (g.M <= 0) return;
+  dim3 grid((g.M + BM - 1) / BM, n_tiles_y, splits);
+  static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
+  if (!lds_opt_in) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<T, MODE>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE>());
+    lds_opt_in = true;
+  }
+  const size_t lds = gemm_lds_bytes<T, MODE>();
+  hipLaunchKernelGGL((k_gemm<T, MODE>), grid, dim3(GEMM_THREADS), lds, s, g);
+}
+
+// ---- packing of W: padded, k-contiguous [Np x Kp], and its transpose [Kp x Np] ---------------
+template <typename T>
+__global__ void k_pack_w(VecArgs v) {
+  const int total = v.Np * v.Kp;
+  for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
+    const int np = idx / v.Kp, kp = idx % v.Kp;
+    const int gate = np / v.Hp, j = np % v.Hp, half = kp / v.Hp, i = kp % v.Hp;
+    T w = from_f<T>(0.f);
+    if (j < v.H && i < v.H)
+      w = reinterpret_cast<const T*>(v.W)[(size_t)(gate * v.H + j) * (2 * v.H) + half * v.H + i];
+    reinterpret_cast<T*>(v.Wp)[idx] = w;
+    if (v.WpT) reinterpret_cast<T*>(v.WpT)[(size_t)kp * v.Np + np] = w;
+    if (kp == 0) v.bp[np] = j < v.H ? v.b[gate * v.H + j] : 0.f;
+  }
+}
+
+// ---- leaves: state row = E[token], zero padding, zero cell state -----------------------------
+template <typename T>
+__global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  const int n_waves = (gridDim.x * blockDim.x) >> 6;
+  for (uint32_t i = wave; i < n_leaf; i += n_waves) {
+    const uint32_t row = e.leaf_row[i], tok = e.leaf_tok[i];
+    const T* src = reinterpret_cast<const T*>(v.E) + (size_t)(tok < (uint32_t)v.vocab ? tok : 0) * v.H;
+    T* dst = reinterpret_cast<T*>(v.Hs) + (size_t)row * v.Hp;
+    for (int n = lane; n < v.Hp; n += 64) dst[n] = n < v.H ? src[n] : from_f<T>(0.f);
+    if (v.cell_kind == 2)
+      for (int n = lane; n < v.Hp; n += 64) v.Cs[(size_t)row * v.Hp + n] = 0.f;
+  }
+}
+
+// ---- classification head: loss_b = -log softmax(U h + u0)[label]; dh = U^T (p - onehot) dloss ---
+template <typename T>
+__global__ void k_head(VecArgs v, Engine e, const float* dy, int with_grad) {
+  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  if (wave >= (int)e.n_inst) return;
+  const uint32_t row = e.head_row[wave];
+  const int label = (int)e.head_label[wave];
+  const T* h = reinterpret_cast<const T*>(v.Hs) + (size_t)row * v.Hp;
+  float logit[16];
+  float mx = -3.0e38f;
+  for (int c = 0; c < v.n_classes; ++c) {
+    float s = 0.f;
+    for (int n = lane; n < v.H; n += 64) s += v.U[c * v.H + n] * to_f(h[n]);
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    logit[c] = s + v.u0[c];
+    mx = fmaxf(mx, logit[c]);
+  }
+  float z = 0.f;
+  for (int c = 0; c < v.n_classes; ++c) z += expf(logit[c] - mx);
+  const float lse = mx + logf(z);
+  if (lane == 0) v.loss[wave] = lse - logit[label < v.n_classes ? label : 0];
+  if (with_grad) {
+    const float d = dy[wave];
+    for (int n = lane; n < v.Hp; n += 64) {
+      float s = 0.f;
+      if (n < v.H)
+        for (int c = 0; c < v.n_classes; ++c)
+          s += (expf(logit[c] - lse) - (c == label ? 1.f : 0.f)) * v.U[c * v.H + n];
+      v.dH[(size_t)row * v.Hp + n] = s * d;
+      if (v.cell_kind == 2) v.dC[(size_t)row * v.Hp + n] = 0.f;
+    }
+  }
+}
+
+// vector result: seed dH of each root row with the caller's dy; copy the root rows out
+__global__ void k_seed_dy(VecArgs v, Engine e, const float* dy) {
+  const int b = blockIdx.x;
+  const uint32_t row = e.root_ref[b];
+  for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
+    v.dH[(size_t)row * v.Hp + n] = n < v.H ? dy[(size_t)b * v.H + n] : 0.f;
+    if (v.cell_kind == 2) v.dC[(size_t)row * v.Hp + n] = 0.f;
+  }
+}
+
+template <typename T>
+__global__ void k_out_rows(VecArgs v, Engine e, float* out_h, float* out_c) {
+  const int b = blockIdx.x;
+  const uint32_t row = e.root_ref[b];
+  for (int n = threadIdx.x; n < v.H; n += blockDim.x) {
+    if (out_h) out_h[(size_t)b * v.H + n] = to_f(reinterpret_cast<const T*>(v.Hs)[(size_t)row * v.Hp + n]);
+    if (out_c && v.cell_kind == 2) out_c[(size_t)b * v.H + n] = v.Cs[(size_t)row * v.Hp + n];
+  }
+}
+
+// ---- pre-activation gradients of one level ------------------------------------------------------
+// TreeRNN: delta = dh * (1 - h^2).  TreeLSTM: the gate gradients (i, f_l, f_r, o, u) and the
+// cell-state gradients handed to the two children.
+template <typename T>
+__global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
+  const uint32_t m = blockIdx.x;
+  if (m >= count) return;
+  const uint32_t q = q0 + m;
+  const size_t o = (size_t)e.q_out[q] * v.Hp;
+  T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)q * v.Np;
+  if (v.cell_kind == 1) {
+    for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
+      const float h = to_f(reinterpret_cast<const T*>(v.Hs)[o + n]);
+      dz[n] = from_f<T>(v.dH[o + n] * (1.f - h * h));
+    }
+  } else {
+    const size_t ol = (size_t)e.q_l[q] * v.Hp, orr = (size_t)e.q_r[q] * v.Hp;
+    const T* gt = reinterpret_cast<const T*>(v.gates) + (size_t)q * v.Np;
+    for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
+      const float gi = to_f(gt[n]), gfl = to_f(gt[v.Hp + n]), gfr = to_f(gt[2 * v.Hp + n]);
+      const float go = to_f(gt[3 * v.Hp + n]), gu = to_f(gt[4 * v.Hp + n]);
+      const float tc = tanhf(v.Cs[o + n]);
+      const float dh = v.dH[o + n];
+      const float dc = v.dC[o + n] + dh * go * (1.f - tc * tc);
+      const float cl = v.Cs[ol + n], cr = v.Cs[orr + n];
+      dz[n] = from_f<T>(dc * gu * gi * (1.f - gi));
+      dz[v.Hp + n] = from_f<T>(dc * cl * gfl * (1.f - gfl));
+      dz[2 * v.Hp + n] = from_f<T>(dc * cr * gfr * (1.f - gfr));
+      dz[3 * v.Hp + n] = from_f<T>(dh * tc * go * (1.f - go));
+      dz[4 * v.Hp + n] = from_f<T>(dc * gi * (1.f - gu * gu));
+      v.dC[ol + n] = dc * gfl;
+      v.dC[orr + n] = dc * gfr;
+    }
+  }
+}
+
+// ---- transposes feeding the weight-gradient GEMM (reduction over tags must be k-contiguous) -----
+// out[c][q] = in_row(q)[c] for q < n_q, 0 for n_q <= q < q_stride.  GATHER: in_row(q) is
+// [Hs[l[q]]; Hs[r[q]]], else row q of Dz.
+template <typename T, bool GATHER>
+__global__ void k_transpose(VecArgs v, Engine e, uint32_t n_q, int n_cols, T* out) {
+  __shared__ T tile[32][33];
+  const uint32_t q0 = blockIdx.x * 32;
+  const int c0 = blockIdx.y * 32;
+  for (int r = threadIdx.y; r < 32; r += blockDim.y) {
+    const uint32_t q = q0 + r;
+    const int c = c0 + threadIdx.x;
+    T x = from_f<T>(0.f);
+    if (q < n_q && c < n_cols) {
+      if (GATHER) {
+        const uint32_t row = c < v.Hp ? e.q_l[q] : e.q_r[q];
+        x = reinterpret_cast<const T*>(v.Hs)[(size_t)row * v.Hp + (c < v.Hp ? c : c - v.Hp)];
+      } else {
+        x = reinterpret_cast<const T*>(v.Dz)[(size_t)q * v.Np + c];
+      }
+    }
+    tile[r][threadIdx.x] = x;
+  }
+  __syncthreads();
+  for (int r = threadIdx.y; r < 32; r += blockDim.y) {
+    const int c = c0 + r;
+    const uint32_t q = q0 + threadIdx.x;
+    if (c < n_cols && q < v.q_stride) out[(size_t)c * v.q_stride + q] = tile[threadIdx.x][r];
+  }
+}
+
+// dW[n][k] = sum over splits, in split order; written in the caller's unpadded layout
+__global__ void k_reduce_dw(VecArgs v, float* dW, int splits) {
+  const int R = v.N, K2 = 2 * v.H;
+  for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < R * K2; idx += gridDim.x * blockDim.x) {
+    const int n = idx / K2, k = idx % K2;
+    const int np = (n / v.H) * v.Hp + n % v.H, kp = (k / v.H) * v.Hp + k % v.H;
+    float s = 0.f;
+    for (int z = 0; z < splits; ++z) s += v.dW_part[((size_t)z * v.Np + np) * v.Kp + kp];
+    dW[idx] = s;
+  }
+}
+
+// db[n] = sum_q Dz[q][n]: fixed chunks of tags, partial sums combined in chunk order
+template <typename T>
+__global__ void k_db_partial(VecArgs v, uint32_t n_q, uint32_t chunk, float* part) {
+  const uint32_t q_lo = blockIdx.x * chunk, q_hi = min(n_q, q_lo + chunk);
+  for (int n = threadIdx.x; n < v.Np; n += blockDim.x) {
+    float s = 0.f;
+    for (uint32_t q = q_lo; q < q_hi; ++q) s += to_f(reinterpret_cast<const T*>(v.Dz)[(size_t)q * v.Np + n]);
+    part[(size_t)blockIdx.x * v.Np + n] = s;
+  }
+}
+__global__ void k_db_final(VecArgs v, const float* part, int n_parts, float* db) {
+  for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < v.N; n += gridDim.x * blockDim.x) {
+    const int np = (n / v.H) * v.Hp + n % v.H;
+    float s = 0.f;
+    for (int p = 0; p < n_parts; ++p) s += part[(size_t)p * v.Np + np];
+    db[n] = s;
+  }
+}
+
+// ---- embedding gradient: leaves grouped by token, segments summed without atomics ---------------
+__global__ void k_tok_hist(Engine e, uint32_t n_leaf, uint32_t* count, int vocab) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_leaf; i += gridDim.x * blockDim.x) {
+    const uint32_t t = e.leaf_tok[i];
+    if (t < (uint32_t)vocab) atomicAdd(&count[t], 1u);
+  }
+}
+// single block: exclusive scans of the per-token leaf counts and chunk counts
+__global__ void k_tok_scan(const uint32_t* count, uint32_t* seg_off, uint32_t* chunk_off, int vocab, uint32_t chunk) {
+  __shared__ uint32_t carry[2];
+  __shared__ uint32_t bufa[1024], bufb[1024];
+  if (threadIdx.x == 0) carry[0] = carry[1] = 0;
+  __syncthreads();
+  for (int base = 0; base <= vocab; base += 1024) {
+    const int i = base + threadIdx.x;
+    const uint32_t a = i < vocab ? count[i] : 0, b = (a + chunk - 1) / chunk;
+    bufa[threadIdx.x] = a;
+    bufb[threadIdx.x] = b;
+    __syncthreads();
+    for (int off = 1; off < 1024; off <<= 1) {
+      const uint32_t ta = threadIdx.x >= (unsigned)off ? bufa[threadIdx.x - off] : 0;
+      const uint32_t tb = threadIdx.x >= (unsigned)off ? bufb[threadIdx.x - off] : 0;
+      __syncthreads();
+      bufa[threadIdx.x] += ta;
+      bufb[threadIdx.x] += tb;
+      __syncthreads();
+    }
+    if (i <= vocab) {
+      seg_off[i] = carry[0] + bufa[threadIdx.x] - a;
+      chunk_off[i] = carry[1] + bufb[threadIdx.x] - b;
+    }
+    __syncthreads();
+    if (threadIdx.x == 1023) {
+      carry[0] += bufa[1023];
+      carry[1] += bufb[1023];
+    }
+    __syncthreads();
+  }
+}
+__global__ void k_tok_scatter(Engine e, uint32_t n_leaf, const uint32_t* seg_off, uint32_t* fill,
+                              uint32_t* sorted_row, int vocab) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_leaf; i += gridDim.x * blockDim.x) {
+    const uint32_t t = e.leaf_tok[i];
+    if (t < (uint32_t)vocab) sorted_row[seg_off[t] + atomicAdd(&fill[t], 1u)] = e.leaf_row[i];
+  }
+}
+// one wave per (token, chunk): partial[chunk] = sum of dH rows of the chunk's leaves
+__global__ void k_de_partial(VecArgs v, const uint32_t* seg_off, const uint32_t* chunk_off,
+                             const uint32_t* sorted_row, uint32_t chunk, float* part) {
+  const int tok = blockIdx.x;
+  const uint32_t lo = seg_off[tok], hi = seg_off[tok + 1];
+  const uint32_t c_lo = chunk_off[tok], n_chunks = chunk_off[tok + 1] - c_lo;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+  for (uint32_t c = wave; c < n_chunks; c += n_waves) {
+    const uint32_t p_lo = lo + c * chunk, p_hi = min(hi, p_lo + chunk);
+    for (int n = lane; n < v.H; n += 64) {
+      float s = 0.f;
+      for (uint32_t p = p_lo; p < p_hi; ++p) s += v.dH[(size_t)sorted_row[p] * v.Hp + n];
+      part[(size_t)(c_lo + c) * v.H + n] = s;
+    }
+  }
+}
+__global__ void k_de_final(VecArgs v, const uint32_t* chunk_off, const float* part, float* dE) {
+  const int tok = blockIdx.x;
+  const uint32_t c_lo = chunk_off[tok], c_hi = chunk_off[tok + 1];
+  for (int n = threadIdx.x; n < v.H; n += blockDim.x) {
+    float s = 0.f;
+    for (uint32_t c = c_lo; c < c_hi; ++c) s += part[(size_t)c * v.H + n];
+    dE[(size_t)tok * v.H + n] = s;
+  }
+}
+
+}  // namespace
+
+// ---- host entry points used by eval.hip ------------------------------------------------------
+template <typename T> static void pack_w_t(const VecArgs& v, hipStream_t s) {
+  hipLaunchKernelGGL(k_pack_w<T>, dim3(1024), dim3(256), 0, s, v);
+}
+void vec_pack_w(const VecArgs& v, hipStream_t s) {
+  if (v.dtype == TDF_BF16) pack_w_t<__bf16>(v, s); else pack_w_t<float>(v, s);
+}
+
+void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s) {
+  if (!n_leaf) return;
+  int blocks = (int)std::min<uint32_t>((n_leaf + 3) / 4, 8192u);
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_embed<__bf16>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
+  else hipLaunchKernelGGL(k_embed<float>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
+}
+
+template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count,
+                                             int save_gates, hipStream_t s) {
+  GemmArgs g{};
+  g.M = (int)count; g.N = v.Np; g.K = v.Kp;
+  g.B = v.Wp; g.ldb = v.Kp;
+  g.Hs = v.Hs; g.Hp = v.Hp;
+  g.out = e.q_out + q0; g.l = e.q_l + q0; g.r = e.q_r + q0;
+  g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
+  g.gates = v.gates ? reinterpret_cast<T*>(v.gates) + (size_t)q0 * v.Np : nullptr;
+  g.ldg = v.Np; g.save_gates = save_gates && v.gates;
+  if (v.cell_kind == 2) launch_gemm<T, LSTM_FWD>(g, (v.Hp / 32 + 1) / 2, 1, s);
+  else launch_gemm<T, RNN_FWD>(g, (v.Np + 127) / 128, 1, s);
+}
+void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, int save_gates, hipStream_t s) {
+  if (v.dtype == TDF_BF16) cell_fwd_t<__bf16>(v, e, q0, count, save_gates, s);
+  else cell_fwd_t<float>(v, e, q0, count, save_gates, s);
+}
+
+template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s) {
+  if (!count) return;
+  hipLaunchKernelGGL(k_dz<T>, dim3(count), dim3(256), 0, s, v, e, q0, count);
+  GemmArgs g{};
+  g.M = (int)count; g.N = v.Kp; g.K = v.Np;
+  g.A = reinterpret_cast<const T*>(v.Dz) + (size_t)q0 * v.Np; g.lda = v.Np;
+  g.B = v.WpT; g.ldb = v.Np;
+  g.Hp = v.Hp; g.l = e.q_l + q0; g.r = e.q_r + q0;
+  g.C = v.dH;
+  launch_gemm<T, DX_BWD>(g, (v.Kp + 127) / 128, 1, s);
+}
+void vec_cell_bwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s) {
+  if (v.dtype == TDF_BF16) cell_bwd_t<__bf16>(v, e, q0, count, s); else cell_bwd_t<float>(v, e, q0, count, s);
+}
+
+void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s) {
+  int blocks = ((int)e.n_inst + 3) / 4;
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_head<__bf16>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
+  else hipLaunchKernelGGL(k_head<float>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
+}
+void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s) {
+  hipLaunchKernelGGL(k_seed_dy, dim3(e.n_inst), dim3(128), 0, s, v, e, dy);
+}
+void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s) {
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_out_rows<__bf16>, dim3(e.n_inst), dim3(128), 0, s, v, e, out_h, out_c);
+  else hipLaunchKernelGGL(k_out_rows<float>, dim3(e.n_inst), dim3(128), 0, s, v, e, out_h, out_c);
+}
+
+int vec_dw_splits(uint32_t q_stride) {
+  int s = (int)((q_stride + 4095) / 4096);
+  return s < 1 ? 1 : (s > 64 ? 64 : s);
+}
+
+template <typename T> static void weight_grads_t(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db,
+                                                 float* db_part, hipStream_t s) {
+  // transposed copies so that the reduction over tags is k-contiguous for both operands
+  dim3 tb(32, 8);
+  hipLaunchKernelGGL((k_transpose<T, false>), dim3(v.q_stride / 32, v.Np / 32), tb, 0, s, v, e, n_q, v.Np,
+                     reinterpret_cast<T*>(v.DzT));
+  hipLaunchKernelGGL((k_transpose<T, true>), dim3(v.q_stride / 32, v.Kp / 32), tb, 0, s, v, e, n_q, v.Kp,
+                     reinterpret_cast<T*>(v.XT));
+  const int splits = vec_dw_splits(v.q_stride);
+  int kps = (int)((v.q_stride / 32 + splits - 1) / splits) * 32;
+  GemmArgs g{};
+  g.M = v.Np; g.N = v.Kp; g.K = (int)v.q_stride;
+  g.A = v.DzT; g.lda = v.q_stride;
+  g.B = v.XT; g.ldb = v.q_stride;
+  g.C = v.dW_part; g.ldc = v.Kp;
+  g.k_per_split = kps;
+  launch_gemm<T, DW_SPLIT>(g, (v.Kp + 127) / 128, splits, s);
+  hipLaunchKernelGGL(k_reduce_dw, dim3(512), dim3(256), 0, s, v, dW, splits);
+  const uint32_t chunk = 512;
+  const int parts = (int)((n_q + chunk - 1) / chunk);
+  hipLaunchKernelGGL(k_db_partial<T>, dim3(parts), dim3(256), 0, s, v, n_q, chunk, db_part);
+  hipLaunchKernelGGL(k_db_final, dim3(8), dim3(256), 0, s, v, db_part, parts, db);
+}
+void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {
+  if (v.dtype == TDF_BF16) weight_grads_t<__bf16>(v, e, n_q, dW, db, db_part, s);
+  else weight_grads_t<float>(v, e, n_q, dW, db, db_part, s);
+}
+
+void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t* count, uint32_t* seg_off,
+                    uint32_t* chunk_off, uint32_t* fill, uint32_t* sorted_row, float* part, float* dE,
+                    uint32_t chunk, hipStream_t s) {
+  int g = (int)std::min<uint32_t>((n_leaf + 255) / 256, 2048u);
+  if (g < 1) g = 1;
+  hipLaunchKernelGGL(k_tok_hist, dim3(g), dim3(256), 0, s, e, n_leaf, count, v.vocab);
+  hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);
+  hipLaunchKernelGGL(k_tok_scatter, dim3(g), dim3(256), 0, s, e, n_leaf, seg_off, fill, sorted_row, v.vocab);
+  hipLaunchKernelGGL(k_de_partial, dim3(v.vocab), dim3(256), 0, s, v, seg_off, chunk_off, sorted_row, chunk, part);
+  hipLaunchKernelGGL(k_de_final, dim3(v.vocab), dim3(128), 0, s, v, chunk_off, part, dE);
+}
+
+}  // namespace tdf

@@ -1,0 +1,116 @@
+// Device-side data layout of one evaluation, shared by the tag machine (tag_machine.hip),
+// the vector kernels (cells.hip) and the host driver (eval.hip).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "tdf_internal.h"
+
+namespace tdf {
+
+// Control block at the head of the workspace.  Counters are bumped with device-scope
+// atomics; everything else is ordered by kernel boundaries.
+struct Ctrl {
+  uint32_t q_count;          // tokens waiting for the next match step
+  uint32_t touched_count[2]; // frames that received a token (double-buffered by step parity)
+  uint32_t step;
+  uint32_t n_rows;           // state rows handed out (leaves and cells share the row space)
+  uint32_t n_leaf;           // EMBED firings
+  uint32_t n_cell;           // cell firings
+  uint32_t n_head;           // CE_HEAD firings
+  uint32_t status;           // 0, or -(tdf_status) raised on the device
+  uint32_t done;
+  uint32_t max_probe, max_depth, max_level;
+  uint32_t pad0;
+  unsigned long long n_tags, n_tokens;
+};
+
+// Frame record = one slot of the tag-hash table = one call-context tag (Section 5.1: a
+// frame holds the label i of the Call_i that created it and a reference to the previous
+// scope).  The key packs (parent frame + 1, label + 1); 0 means empty.  The slot index is
+// the frame id, so inserting a tag and allocating its frame are one compare-and-swap.
+struct FrameHdr {
+  unsigned long long key;
+  unsigned long long fired;   // firing-table entries that have fired live under this tag
+  uint32_t present_fn;        // bits 0..23: stored values present; bits 24..31: function
+  uint32_t touched;           // step+1 of the last step that delivered a token here
+  uint32_t depth;             // length of the tag (number of call labels)
+  uint32_t pad;
+  // followed by int64 stored[n_stored]
+};
+static_assert(sizeof(FrameHdr) == 32, "FrameHdr must be 32 bytes");
+
+struct Token {
+  uint32_t a;      // CALL: parent frame; RETURN: returning frame
+  uint32_t b;      // CALL: 0x80000000 | label | param << 8; RETURN: 0
+  long long value;
+};
+static_assert(sizeof(Token) == 16, "Token must be 16 bytes");
+
+// Pointers into the workspace and to the caller's buffers, passed to kernels by value.
+struct Engine {
+  Ctrl* ctrl;
+  unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
+  char* frames;                     // (cap + B) records of frame_stride bytes
+  uint32_t cap, cap_mask, n_inst, max_tags;
+  Token* queue;
+  uint32_t q_cap;
+  uint32_t* touched;
+  uint32_t touched_cap;
+  uint32_t step_limit;
+  // forest
+  const int32_t *left, *right, *token;
+  int32_t n_tree_nodes;
+  // program inputs / outputs
+  const long long* args;
+  int32_t n_args;
+  long long* out_i64;
+  uint32_t* root_ref;               // [B] row of the vector result of instance b
+  // schedule log written by the fire kernel
+  uint32_t row_cap;                 // state rows available
+  uint32_t *leaf_row, *leaf_tok;    // [n_leaf]
+  uint32_t *cell_out, *cell_l, *cell_r, *cell_lvl;   // [n_cell], in firing order
+  uint32_t *head_row, *head_label;  // [B]
+  // cells bucketed by dependency level
+  uint32_t *level_count, *level_off, *level_fill;    // [max_levels + 2]
+  uint32_t max_levels;
+  uint32_t *q_out, *q_l, *q_r;      // [n_cell], sorted by level
+};
+
+inline __device__ FrameHdr* frame_at(const Engine& e, int stride, uint32_t f) {
+  return reinterpret_cast<FrameHdr*>(e.frames + (size_t)f * stride);
+}
+inline __device__ long long* frame_slots(FrameHdr* h) {
+  return reinterpret_cast<long long*>(h + 1);
+}
+
+// ---- vector side ----------------------------------------------------------------------
+struct VecArgs {
+  int dtype;        // tdf_dtype
+  int cell_kind;    // 1 RNN, 2 LSTM
+  int H, Hp;        // hidden size and padded row stride (multiple of 32)
+  int N, Np;        // gate rows of W: H or 5H; padded: Hp or 5*Hp
+  int Kp;           // 2*Hp
+  int vocab, n_classes;
+  const void* E;
+  const void* W;
+  const float* b;
+  const float *U, *u0;
+  void* Hs;         // state rows [row_cap x Hp], dtype
+  float* Cs;        // LSTM cell state [row_cap x Hp]
+  void* Wp;         // packed W [Np x Kp], dtype (k contiguous)
+  float* bp;        // [Np]
+  // gradient side
+  float* dH;        // [row_cap x Hp]
+  float* dC;        // [row_cap x Hp]
+  void* gates;      // LSTM activations (i,f_l,f_r,o,u) [n_cell x Np], dtype, by level order q
+  void* Dz;         // pre-activation gradients [n_cell x Np], dtype, by q
+  void* DzT;        // [Np x q_stride]
+  void* XT;         // [Kp x q_stride]  (gathered [h_l;h_r] transposed)
+  void* WpT;        // packed W transposed [Kp x Np]
+  float* dW_part;   // split partial sums [n_split x Np x Kp]
+  uint32_t q_stride;
+  float* loss;      // [B]
+};
+
+}  // namespace tdf

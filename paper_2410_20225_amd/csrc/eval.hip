@@ -1,0 +1,356 @@
+// Host driver of tdf_eval / tdf_eval_grad: workspace layout, the step loop of the tag machine,
+// the level-by-level execution of the cell firings, and the reversed schedule of the
+// gradient pass.
+#include <algorithm>
+#include <string.h>
+#include <string>
+#include <vector>
+
+#include "engine.h"
+
+namespace tdf {
+
+void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
+void launch_step(const DevProgram& P, const Engine& e, int parity, int max_values, int blocks, hipStream_t s);
+void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s);
+void vec_pack_w(const VecArgs& v, hipStream_t s);
+void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s);
+void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, int save_gates, hipStream_t s);
+void vec_cell_bwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s);
+void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s);
+void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s);
+void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s);
+int vec_dw_splits(uint32_t q_stride);
+void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s);
+void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t* count, uint32_t* seg_off,
+                    uint32_t* chunk_off, uint32_t* fill, uint32_t* sorted_row, float* part, float* dE,
+                    uint32_t chunk, hipStream_t s);
+
+namespace {
+
+constexpr uint32_t DE_CHUNK = 128;
+constexpr uint32_t DB_CHUNK = 512;
+
+struct Layout {
+  size_t total = 0;
+  size_t zero_begin = 0, zero_end = 0;   // region cleared at the start of every call
+  size_t take(size_t bytes) {
+    size_t off = total;
+    total += (bytes + 255) / 256 * 256;
+    return off;
+  }
+};
+
+struct Plan {
+  Layout L;
+  Engine e{};
+  VecArgs v{};
+  bool vec = false, grad = false;
+  size_t off_ctrl, off_fire, off_frames;
+  // embedding-gradient and bias-gradient scratch
+  size_t off_tok_count, off_tok_fill, off_seg_off, off_chunk_off, off_sorted, off_de_part, off_db_part;
+  uint32_t max_cells;
+};
+
+uint32_t pow2_at_least(uint64_t x) {
+  uint64_t p = 64;
+  while (p < x) p <<= 1;
+  return (uint32_t)p;
+}
+
+// Sizes and offsets only; `base` may be null (tdf_workspace_size).
+tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char* base, Plan& P) {
+  if (!in) { set_error("inputs is NULL"); return TDF_ERR_BAD_ARG; }
+  if (in->n_instances < 1) { set_error("n_instances must be positive"); return TDF_ERR_BAD_ARG; }
+  if (in->n_args != G.n_result_params) { set_error("n_args does not match the parameters of result"); return TDF_ERR_BAD_ARG; }
+  if (in->max_tags < in->n_instances || in->max_tags > (1ll << 30)) { set_error("max_tags out of range"); return TDF_ERR_BAD_ARG; }
+  P.vec = G.has_embed || G.cell_kind != 0;
+  P.grad = with_grad;
+  if (with_grad && !G.want_grad) { set_error("graph was built without gradients"); return TDF_ERR_BAD_ARG; }
+  if (P.vec) {
+    if (in->hidden < 1 || in->hidden > 8192 || in->vocab < 1) { set_error("bad hidden / vocab"); return TDF_ERR_BAD_ARG; }
+    if (in->dtype != TDF_F32 && in->dtype != TDF_BF16) { set_error("bad dtype"); return TDF_ERR_BAD_ARG; }
+    if (G.has_head && (in->n_classes < 1 || in->n_classes > 16)) { set_error("n_classes must be 1..16"); return TDF_ERR_BAD_ARG; }
+  }
+  Layout& L = P.L;
+  Engine& e = P.e;
+  const uint32_t B = (uint32_t)in->n_instances;
+  const uint32_t T = (uint32_t)in->max_tags;
+  e.n_inst = B;
+  e.max_tags = T;
+  e.cap = pow2_at_least(2ull * T);
+  e.cap_mask = e.cap - 1;
+  e.step_limit = in->step_limit > 0 ? (uint32_t)in->step_limit : (1u << 20);
+  int max_params = 1;
+  for (int f = 0; f < G.prog.n_fn; ++f) max_params = std::max<int>(max_params, G.prog.fn[f].n_params);
+  e.q_cap = T * (uint32_t)max_params + B;
+  e.touched_cap = T + B;
+  e.row_cap = P.vec ? T : 0;
+  e.max_levels = e.row_cap;
+  P.max_cells = e.row_cap;
+
+  auto at = [&](size_t off) { return base ? base + off : nullptr; };
+  // --- cleared region: control block, counters, level histograms, token histograms, frames
+  L.zero_begin = L.total;
+  P.off_ctrl = L.take(sizeof(Ctrl));
+  P.off_fire = L.take(sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS);
+  size_t off_lcount = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
+  size_t off_lfill = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
+  P.off_tok_count = P.off_tok_fill = 0;
+  if (P.vec && with_grad) {
+    P.off_tok_count = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
+    P.off_tok_fill = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
+  }
+  P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));
+  L.zero_end = L.total;
+  // --- the rest is written before it is read
+  size_t off_queue = L.take(sizeof(Token) * (size_t)e.q_cap);
+  size_t off_touched = L.take(sizeof(uint32_t) * (size_t)e.touched_cap);
+  size_t off_root = L.take(sizeof(uint32_t) * B);
+  size_t off_hrow = L.take(sizeof(uint32_t) * B);
+  size_t off_hlab = L.take(sizeof(uint32_t) * B);
+  size_t off_loff = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
+  size_t rc = std::max<size_t>(e.row_cap, 1);
+  size_t off_leaf_row = L.take(4 * rc), off_leaf_tok = L.take(4 * rc);
+  size_t off_c_out = L.take(4 * rc), off_c_l = L.take(4 * rc), off_c_r = L.take(4 * rc), off_c_lvl = L.take(4 * rc);
+  size_t off_q_out = L.take(4 * rc), off_q_l = L.take(4 * rc), off_q_r = L.take(4 * rc);
+
+  e.ctrl = (Ctrl*)at(P.off_ctrl);
+  e.fire_count = (unsigned long long*)at(P.off_fire);
+  e.level_count = (uint32_t*)at(off_lcount);
+  e.level_fill = (uint32_t*)at(off_lfill);
+  e.level_off = (uint32_t*)at(off_loff);
+  e.frames = at(P.off_frames);
+  e.queue = (Token*)at(off_queue);
+  e.touched = (uint32_t*)at(off_touched);
+  e.root_ref = (uint32_t*)at(off_root);
+  e.head_row = (uint32_t*)at(off_hrow);
+  e.head_label = (uint32_t*)at(off_hlab);
+  e.leaf_row = (uint32_t*)at(off_leaf_row);
+  e.leaf_tok = (uint32_t*)at(off_leaf_tok);
+  e.cell_out = (uint32_t*)at(off_c_out);
+  e.cell_l = (uint32_t*)at(off_c_l);
+  e.cell_r = (uint32_t*)at(off_c_r);
+  e.cell_lvl = (uint32_t*)at(off_c_lvl);
+  e.q_out = (uint32_t*)at(off_q_out);
+  e.q_l = (uint32_t*)at(off_q_l);
+  e.q_r = (uint32_t*)at(off_q_r);
+  e.left = in->left;
+  e.right = in->right;
+  e.token = in->token;
+  e.n_tree_nodes = in->n_tree_nodes;
+  e.args = (const long long*)in->args;
+  e.n_args = in->n_args;
+
+  if (P.vec) {
+    VecArgs& v = P.v;
+    v.dtype = in->dtype;
+    v.cell_kind = G.cell_kind;
+    v.H = in->hidden;
+    v.Hp = (in->hidden + 31) / 32 * 32;
+    const int gates = G.cell_kind == 2 ? 5 : 1;
+    v.N = gates * v.H;
+    v.Np = gates * v.Hp;
+    v.Kp = 2 * v.Hp;
+    v.vocab = in->vocab;
+    v.n_classes = in->n_classes;
+    v.E = in->E; v.W = in->W; v.b = in->b; v.U = in->U; v.u0 = in->u0;
+    const size_t el = in->dtype == TDF_BF16 ? 2 : 4;
+    const size_t R = e.row_cap;
+    size_t off_Hs = L.take(R * v.Hp * el);
+    size_t off_Cs = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
+    size_t off_Wp = L.take((size_t)v.Np * v.Kp * el);
+    size_t off_bp = L.take((size_t)v.Np * 4);
+    size_t off_loss = L.take((size_t)B * 4);
+    v.Hs = at(off_Hs);
+    v.Cs = G.cell_kind == 2 ? (float*)at(off_Cs) : nullptr;
+    v.Wp = at(off_Wp);
+    v.bp = (float*)at(off_bp);
+    v.loss = (float*)at(off_loss);
+    if (with_grad) {
+      v.q_stride = (uint32_t)((P.max_cells + 31) / 32 * 32);
+      size_t off_dH = L.take(R * v.Hp * 4);
+      size_t off_dC = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
+      size_t off_gates = G.cell_kind == 2 ? L.take((size_t)P.max_cells * v.Np * el) : 0;
+      size_t off_Dz = L.take((size_t)P.max_cells * v.Np * el);
+      size_t off_DzT = L.take((size_t)v.Np * v.q_stride * el);
+      size_t off_XT = L.take((size_t)v.Kp * v.q_stride * el);
+      size_t off_WpT = L.take((size_t)v.Np * v.Kp * el);
+      size_t off_part = L.take((size_t)vec_dw_splits(v.q_stride) * v.Np * v.Kp * 4);
+      P.off_db_part = L.take(((size_t)P.max_cells / DB_CHUNK + 2) * v.Np * 4);
+      P.off_seg_off = L.take(4 * ((size_t)v.vocab + 2));
+      P.off_chunk_off = L.take(4 * ((size_t)v.vocab + 2));
+      P.off_sorted = L.take(4 * rc);
+      P.off_de_part = L.take(((size_t)R / DE_CHUNK + v.vocab + 2) * v.H * 4);
+      v.dH = (float*)at(off_dH);
+      v.dC = G.cell_kind == 2 ? (float*)at(off_dC) : nullptr;
+      v.gates = G.cell_kind == 2 ? at(off_gates) : nullptr;
+      v.Dz = at(off_Dz);
+      v.DzT = at(off_DzT);
+      v.XT = at(off_XT);
+      v.WpT = at(off_WpT);
+      v.dW_part = (float*)at(off_part);
+    }
+  }
+  return TDF_OK;
+}
+
+#define HIP_TRY(expr)                                                                   \
+  do {                                                                                  \
+    hipError_t err__ = (expr);                                                          \
+    if (err__ != hipSuccess) {                                                          \
+      set_error(std::string(#expr) + ": " + hipGetErrorString(err__));                  \
+      return TDF_ERR_DEVICE;                                                            \
+    }                                                                                   \
+  } while (0)
+
+tdf_status status_from_device(uint32_t st) {
+  if (st == 0) return TDF_OK;
+  int code = -(int)st;
+  switch (code) {
+    case TDF_ERR_TABLE_FULL: set_error("device: tag table, token queue or state rows exhausted (raise max_tags)"); break;
+    case TDF_ERR_STEP_LIMIT: set_error("device: step limit reached before the recursion finished"); break;
+    case TDF_ERR_BAD_ARG: set_error("device: tree node index or token id out of range"); break;
+    default: set_error("device: unknown status"); code = TDF_ERR_DEVICE; break;
+  }
+  return (tdf_status)code;
+}
+
+tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out, tdf_grads* grads,
+               void* workspace, size_t workspace_bytes, void* hip_stream, tdf_stats* stats, bool with_grad) {
+  if (!gr || !out) { set_error("NULL graph or outputs"); return TDF_ERR_BAD_ARG; }
+  const Graph& G = gr->g;
+  Plan P;
+  tdf_status st = make_plan(G, in, with_grad, (char*)workspace, P);
+  if (st != TDF_OK) return st;
+  if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < P.L.total) {
+    set_error("workspace is NULL, misaligned or smaller than tdf_workspace_size");
+    return TDF_ERR_WORKSPACE;
+  }
+  if (!in->args && G.n_result_params > 0) { set_error("args is NULL"); return TDF_ERR_BAD_ARG; }
+  if (P.vec) {
+    if (!in->left || !in->right || !in->token || !in->E || (G.cell_kind && (!in->W || !in->b))) {
+      set_error("forest or parameter pointer is NULL");
+      return TDF_ERR_BAD_ARG;
+    }
+    if (G.has_head && (!in->U || !in->u0)) { set_error("U / u0 is NULL"); return TDF_ERR_BAD_ARG; }
+  }
+  if (G.out_type == T_INT && !out->out_i64) { set_error("out_i64 is NULL"); return TDF_ERR_BAD_ARG; }
+  if (G.out_type == T_LOSS && !out->out_f32) { set_error("out_f32 is NULL"); return TDF_ERR_BAD_ARG; }
+  if (G.out_type == T_VEC && !out->out_h) { set_error("out_h is NULL"); return TDF_ERR_BAD_ARG; }
+  if (with_grad && (!dy || !dy->dy || !grads || !grads->dW || !grads->db || !grads->dE)) {
+    set_error("dy or a gradient buffer is NULL");
+    return TDF_ERR_BAD_ARG;
+  }
+  hipStream_t s = (hipStream_t)hip_stream;
+  Engine& e = P.e;
+  VecArgs& v = P.v;
+  e.out_i64 = (long long*)out->out_i64;
+  char* base = (char*)workspace;
+
+  HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
+  launch_seed(G.prog, e, s);
+
+  // ---- the tag machine: fire / match steps until no token is in flight -------------------
+  int max_values = 1;
+  for (int f = 0; f < G.prog.n_fn; ++f) max_values = std::max<int>(max_values, G.prog.fn[f].n_values);
+  const int blocks = 1024;
+  Ctrl hc{};
+  uint32_t step = 0;
+  const uint32_t poll = 32;
+  for (;;) {
+    for (uint32_t i = 0; i < poll; ++i, ++step) launch_step(G.prog, e, (int)(step & 1), max_values, blocks, s);
+    HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (hc.done) break;
+  }
+  tdf_status dev = status_from_device(hc.status);
+
+  std::vector<uint32_t> level_off;
+  if (dev == TDF_OK && P.vec) {
+    // ---- vector operators: leaves at once, cells level by level --------------------------
+    vec_pack_w(v, s);
+    vec_embed(v, e, hc.n_leaf, s);
+    if (hc.n_cell) {
+      launch_levels(e, hc.n_cell, s);
+      level_off.resize((size_t)hc.max_level + 2);
+      HIP_TRY(hipMemcpyAsync(level_off.data(), e.level_off, level_off.size() * 4, hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipStreamSynchronize(s));
+      for (uint32_t lvl = 1; lvl <= hc.max_level; ++lvl)
+        vec_cell_fwd(v, e, level_off[lvl], level_off[lvl + 1] - level_off[lvl], with_grad, s);
+    }
+    if (G.has_head) {
+      vec_head(v, e, with_grad ? dy->dy : nullptr, with_grad, s);
+      HIP_TRY(hipMemcpyAsync(out->out_f32, v.loss, sizeof(float) * e.n_inst, hipMemcpyDeviceToDevice, s));
+    } else if (G.out_type == T_VEC) {
+      vec_out_rows(v, e, out->out_h, out->out_c, s);
+      if (with_grad) vec_seed_dy(v, e, dy->dy, s);
+    }
+    if (with_grad) {
+      // ---- gradient pass: the level schedule walked backwards -----------------------------
+      for (uint32_t lvl = hc.max_level; lvl >= 1 && hc.n_cell; --lvl)
+        vec_cell_bwd(v, e, level_off[lvl], level_off[lvl + 1] - level_off[lvl], s);
+      if (hc.n_cell) {
+        v.q_stride = (hc.n_cell + 31) / 32 * 32;   // only the cells that fired
+        vec_weight_grads(v, e, hc.n_cell, grads->dW, grads->db, (float*)(base + P.off_db_part), s);
+      } else {
+        HIP_TRY(hipMemsetAsync(grads->dW, 0, sizeof(float) * (size_t)v.N * 2 * v.H, s));
+        HIP_TRY(hipMemsetAsync(grads->db, 0, sizeof(float) * (size_t)v.N, s));
+      }
+      vec_embed_grad(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
+                     (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
+                     (uint32_t*)(base + P.off_sorted), (float*)(base + P.off_de_part), grads->dE, DE_CHUNK, s);
+    }
+    HIP_TRY(hipGetLastError());
+    HIP_TRY(hipStreamSynchronize(s));
+  }
+  HIP_TRY(hipGetLastError());
+
+  if (stats) {
+    memset(stats, 0, sizeof(*stats));
+    stats->n_tags = (int64_t)hc.n_tags;
+    stats->n_steps = (int64_t)hc.step;
+    stats->n_tokens = (int64_t)hc.n_tokens;
+    stats->n_leaf_rows = hc.n_leaf;
+    stats->n_cell_rows = hc.n_cell;
+    stats->n_waves = hc.max_level;
+    stats->n_grad_firings = with_grad && dev == TDF_OK ? (int64_t)hc.n_leaf + hc.n_cell : 0;
+    stats->max_tag_depth = hc.max_depth;
+    stats->table_capacity = e.cap;
+    stats->max_probe = hc.max_probe;
+    stats->device_status = -(int32_t)hc.status;
+    stats->n_counts = (int32_t)G.snodes.size();
+    std::vector<unsigned long long> fc(TDF_STATS_MAX_COUNTS);
+    HIP_TRY(hipMemcpy(fc.data(), e.fire_count, sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS, hipMemcpyDeviceToHost));
+    for (int i = 0; i < TDF_STATS_MAX_COUNTS; ++i) stats->fire_count[i] = (int64_t)fc[i];
+  }
+  return dev;
+}
+
+}  // namespace
+}  // namespace tdf
+
+using namespace tdf;
+
+extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* in, int with_grad, size_t* bytes) {
+  if (!g || !bytes) {
+    set_error("tdf_workspace_size: NULL argument");
+    return TDF_ERR_BAD_ARG;
+  }
+  Plan P;
+  tdf_status st = make_plan(g->g, in, with_grad != 0, nullptr, P);
+  if (st != TDF_OK) return st;
+  *bytes = P.L.total;
+  return TDF_OK;
+}
+
+extern "C" tdf_status tdf_eval(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* workspace,
+                               size_t workspace_bytes, void* hip_stream, tdf_stats* stats) {
+  return run(g, in, nullptr, out, nullptr, workspace, workspace_bytes, hip_stream, stats, false);
+}
+
+extern "C" tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out,
+                                    tdf_grads* grads, void* workspace, size_t workspace_bytes,
+                                    void* hip_stream, tdf_stats* stats) {
+  return run(g, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, true);
+}

@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, builds and rejects programs, and its Section-3 transformation reproduces the
+paper's transformed factorial graph."""
+import os
+import re
+from collections import Counter
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+tdf = pytest.importorskip("paper_2410_20225_amd.tdf")
+from paper_2410_20225_amd import programs  # noqa: E402
+
+
+def test_every_declared_symbol_is_exported():
+    header = open(os.path.join(ROOT, "include", "tdf.h")).read()
+    names = set(re.findall(r"\b(tdf_[a-z_]+)\s*\(", header))
+    assert {"tdf_graph_build", "tdf_eval", "tdf_eval_grad", "tdf_workspace_size", "tdf_graph_info",
+            "tdf_graph_destroy", "tdf_last_error"} <= names
+    for n in names:
+        assert hasattr(tdf.lib, n), n
+
+
+_NAMES = {tdf.OP_EQ: "=", tdf.OP_SWITCH: "Switch", tdf.OP_SUB: "-", tdf.OP_MUL: "*", tdf.OP_ADD: "+",
+          tdf.OP_ID: "id", tdf.OP_MERGE: "Merge", tdf.SNODE_MERGE_ENTRY: "Merge", tdf.OP_OUT: "out"}
+
+
+def _label(n):
+    if n["kind"] == tdf.SNODE_CALL:
+        return "Call_%d" % n["label"]
+    if n["kind"] == tdf.SNODE_RETURN:
+        return "Return_%d" % n["label"]
+    if n["kind"] == tdf.OP_CONST:
+        return str(n["imm"])
+    return _NAMES[n["kind"]]
+
+
+def test_transformed_factorial_graph_matches_the_figure():
+    want = Counter()
+    for line in open(os.path.join(ROOT, "tests", "golden", "fact_transformed_graph.txt")):
+        line = line.strip()
+        if line and not line.startswith("#"):
+            want[tuple(line.split())] += 1
+    # constants are immediates of their consumers: the figure's Merge->constant control edges
+    # have no counterpart
+    assert want.pop(("Merge", "1", "control-to-constant")) == 2
+    fns, r = programs.fact()
+    info = tdf.graph_info(tdf.graph_build(fns, r))
+    nodes = info["nodes"]
+    got = Counter((_label(nodes[e["src"]]), _label(nodes[e["dst"]]), "control" if e["is_control"] else "data")
+                  for e in info["edges"])
+    assert got == want
+    assert info["n_labels"] == 2
+
+
+def test_joint_gradient_graph_shares_labels():
+    fns, r = programs.tree("rnn", head=True)
+    info = tdf.graph_info(tdf.graph_build(fns, r, want_grad=True))
+    fwd = sorted(n["label"] for n in info["nodes"] if n["kind"] == tdf.SNODE_CALL and not n["is_grad"])
+    bwd = sorted(n["label"] for n in info["nodes"] if n["kind"] == tdf.SNODE_CALL and n["is_grad"])
+    assert fwd == bwd == [0, 1, 2]
+    entries = [i for i, n in enumerate(info["nodes"]) if n["kind"] == tdf.SNODE_MERGE_ENTRY and n["is_grad"]]
+    assert len(entries) == 1
+    assert sum(1 for e in info["edges"] if e["dst"] == entries[0]) == 3      # fed by the three Call^grad
+    cell_grad = [i for i, n in enumerate(info["nodes"]) if n["kind"] == tdf.OP_RNN_CELL and n["is_grad"]]
+    assert len(cell_grad) == 1
+    assert sum(1 for e in info["edges"] if e["dst"] == cell_grad[0]) == 3    # (x_l, x_r, dy)
+
+
+@pytest.mark.parametrize("functions,why", [
+    ([("result", 0, [(tdf.OP_CONST, [], 1)])], "no OUT"),
+    ([("result", 1, [(tdf.OP_IN, [], 0), (tdf.OP_CALLFN, [(0, 0)], 3), (tdf.OP_OUT, [(1, 0)], 0)])], "undefined callee"),
+    ([("result", 1, [(tdf.OP_IN, [], 0), (tdf.OP_CALLFN, [(0, 0)], 1), (tdf.OP_OUT, [(1, 0)], 0)]),
+      ("g", 2, [(tdf.OP_IN, [], 0), (tdf.OP_IN, [], 1), (tdf.OP_ADD, [(0, 0), (1, 0)], 0), (tdf.OP_OUT, [(2, 0)], 0)])],
+     "arity mismatch"),
+    ([("result", 1, [(tdf.OP_IN, [], 0), (tdf.OP_ADD, [(0, 0), (2, 0)], 0), (tdf.OP_OUT, [(1, 0)], 0)])], "forward reference"),
+    ([("result", 1, [(tdf.OP_IN, [], 0), (tdf.OP_OUT, [(0, 0)], 0), (tdf.OP_OUT, [(0, 0)], 0)])], "two OUT"),
+])
+def test_malformed_programs_are_rejected(functions, why):
+    with pytest.raises(tdf.TdfError) as ei:
+        tdf.graph_build(functions, 0)
+    assert ei.value.status == tdf.ERR_BAD_PROGRAM, why
+
+
+def test_gradient_of_integer_program_is_rejected():
+    fns, r = programs.fib()
+    with pytest.raises(tdf.TdfError):
+        tdf.graph_build(fns, r, want_grad=True)
+
+
+def test_workspace_size_grows_with_capacity():
+    fns, r = programs.tree("lstm", head=True)
+    g = tdf.graph_build(fns, r, want_grad=True)
+    small = tdf.workspace_size(g, tdf.make_inputs(8, n_args=2, dtype=tdf.BF16, hidden=64, vocab=100,
+                                                  n_classes=5, max_tags=1000), True)
+    big = tdf.workspace_size(g, tdf.make_inputs(8, n_args=2, dtype=tdf.BF16, hidden=64, vocab=100,
+                                                n_classes=5, max_tags=100000), True)
+    assert 0 < small < big
+    with pytest.raises(tdf.TdfError):
+        tdf.workspace_size(g, tdf.make_inputs(8, n_args=1, max_tags=1000), True)   # wrong n_args
