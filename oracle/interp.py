@@ -319,6 +319,8 @@ class Interpreter:
         out = {}
         for nd, c in zip(self.g.nodes, self.fire_count):
             name = nd.op
+            if nd.op == "merge_entry" and nd.attr["kind"] == "gin":
+                name = "merge_entry_grad"
             if nd.op in ("call", "return"):
                 name = "%s_%d" % (nd.op, nd.attr["label"])
                 if nd.attr["kind"] != ("in" if nd.op == "call" else "out"):
