@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the tagged-dataflow hot path on one MI355X.
+
+A step is one tdf_eval_grad (or tdf_eval for forward-only workloads) over the whole synthetic
+batch: tag machine, cell firings level by level, and the reversed gradient schedule.  Inputs
+are resident in HBM before the timed region.  Prints one JSON line.
+
+  metric  tagged node firings/s: one body firing per call-context tag per pass
+          (forward: n_tags per step; forward + gradient: 2 n_tags per step)
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+PEAK_BF16 = 2.5e15      # dense bf16 MFMA, FLOP/s
+PEAK_F32 = 157.3e12     # fp32 MFMA / vector
+PEAK_HBM = 8.0e12       # B/s
+
+
+def cpu_baseline(cfg, budget_trees):
+    """The oracle, as it stands, on the first trees of the same workload."""
+    import numpy as np
+    import oracle
+    from oracle import programs as oprog
+    from tdf_workloads import make_config
+    try:
+        from threadpoolctl import threadpool_info
+        blas = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        blas = 1
+    if cfg == 1:
+        it = oracle.Interpreter(oracle.transform(oprog.fib_program()))
+        t0 = time.perf_counter()
+        it.run({("in", 0): list(range(21))}, 21)
+        dt = time.perf_counter() - t0
+        return {"value": len(it.tags) / dt, "unit": "firings/s", "cores": 1, "kind": "oracle",
+                "sample": "fib(0..20), one batch, %d tags, %.1f s" % (len(it.tags), dt)}
+    c = make_config(cfg)
+    F = c["forest"].subset(range(budget_trees))
+    grad = c["grad"]
+    prog = oprog.tree_program(c["cell"], head=grad)
+    if grad:
+        prog = oracle.differentiate(prog)
+    env = dict(left=F.left, right=F.right, token=F.token, E=c["E"], W=c["W"], b=c["b"], U=c["U"], u0=c["u0"])
+    it = oracle.Interpreter(oracle.transform(prog), env)
+    B = F.n_trees
+    inputs = {("in", 0): F.roots.tolist()}
+    if grad:
+        inputs[("in", 1)] = c["labels"][:B].tolist()
+        inputs[("gin", 0)] = [1.0 / B] * B
+    t0 = time.perf_counter()
+    it.run(inputs, B)
+    dt = time.perf_counter() - t0
+    firings = F.n_nodes * (2 if grad else 1)
+    return {"value": firings / dt, "unit": "firings/s", "cores": blas, "kind": "oracle",
+            "sample": "first %d trees of the workload (%d tags), %s, %.1f s; interpreter single-threaded, "
+                      "BLAS threads %d of %d host cores" % (B, F.n_nodes, "forward+gradient" if grad else "forward",
+                                                            dt, blas, len(os.sched_getaffinity(0)))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4: TreeLSTM forward+gradient)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle's sample (0 = auto)")
+    a = ap.parse_args()
+    if a.gpus != 1:
+        print("bench.py measures one GPU: this engine has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2410_20225_amd import tdf, programs
+    from tdf_workloads import make_config, CONFIG_NAMES
+
+    cfg = a.config
+    dev = "cuda:0"
+    if cfg == 1:
+        fns, r = programs.fib()
+        g = tdf.graph_build(fns, r)
+        args = torch.arange(0, 21, dtype=torch.int64, device=dev)
+        inp = tdf.make_inputs(21, args=args, n_args=1, max_tags=57291)
+        ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=dev)
+        out = torch.zeros(21, dtype=torch.int64, device=dev)
+        step = lambda: tdf.eval(g, inp, ws, out_i64=out)[1]
+        passes, dtype, flops_fwd, cell = 1, "int64", 0.0, None
+    else:
+        from gpu_util import TreeRun
+        c = make_config(cfg)
+        grad = c["grad"]
+        run = TreeRun(c, head=grad, grad=grad)
+        B = run.B
+        dy = np.full(B, 1.0 / B)
+        step = lambda: run.run(dy if grad else None)[1]
+        passes = 2 if grad else 1
+        dtype = "bf16" if c["bf16"] else "f32"
+        cell = c["cell"]
+        rows = (5 if cell == "lstm" else 1) * c["H"]
+        n_cell = int(c["forest"].n_leaves.sum()) - B
+        flops_fwd = 2.0 * n_cell * rows * 2 * c["H"]
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    phase = np.zeros(8)
+    launches = np.zeros(8)
+    t0 = time.perf_counter()
+    for _ in range(a.steps):
+        st = step()
+        phase += np.array(list(st.phase_ms))
+        launches += np.array(list(st.phase_launches))
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    n_tags = int(st.n_tags)
+    firings = n_tags * passes
+    value = firings * a.steps / dt
+    phase_ms = {n: round(float(p) / a.steps, 4) for n, p in zip(tdf.PHASES, phase)}
+
+    if cfg == 1:
+        # tag machine: bytes the method itself moves per tag (key+frame write, argument, return
+        # delivery, touched-list entry, token write+read), see the design doc
+        algo = 128.0 * n_tags
+        ms = phase[0] / a.steps
+        roof = {"bound": "hbm", "kernel": "k_fire+k_match (all steps)", "achieved": algo / (ms * 1e-3) / 1e9,
+                "peak": PEAK_HBM / 1e9, "unit": "GB/s", "traffic": None}
+    else:
+        ms = phase[3] / a.steps
+        n_launch = launches[3] / a.steps
+        peak = PEAK_BF16 if dtype == "bf16" else PEAK_F32
+        roof = {"bound": "mfma", "kernel": "k_gemm<%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
+                "achieved": flops_fwd / (ms * 1e-3) / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
+                "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1), "traffic": None}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+
+    rec = {"metric": "tagged node firings/sec at 1 GPU", "value": value, "unit": "firings/s", "n_gpus": 1,
+           "steps": a.steps, "warmup": a.warmup, "ms_per_step": 1e3 * dt / a.steps, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+           "config": {"workload": "config %d: %s" % (cfg, CONFIG_NAMES[cfg]), "n_tags": n_tags,
+                      "firings_per_step": firings, "n_steps_tag_machine": int(st.n_steps),
+                      "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth)},
+           "phase_ms": phase_ms, "roofline": roof}
+    if not a.no_cpu_baseline:
+        trees = a.cpu_trees or {1: 0, 2: 256, 3: 256, 4: 48, 5: 2}[cfg]
+        rec["cpu_baseline"] = cpu_baseline(cfg, trees)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

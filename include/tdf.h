@@ -177,6 +177,19 @@ typedef struct {
 
 #define TDF_STATS_MAX_COUNTS 256
 
+/* Phases of one evaluation, timed on the caller's stream with HIP events. */
+enum {
+  TDF_PHASE_TAGS = 0,    /* tag machine: clear, seed, all match/fire steps                 */
+  TDF_PHASE_LEAVES,      /* weight packing and EMBED rows                                  */
+  TDF_PHASE_LEVELS,      /* bucketing of the cell firings by dependency level              */
+  TDF_PHASE_CELLS_FWD,   /* cell GEMMs, one launch per level                               */
+  TDF_PHASE_HEAD,        /* head / result rows / gradient seeds                            */
+  TDF_PHASE_CELLS_BWD,   /* gradient bodies of the cells, levels in reverse                */
+  TDF_PHASE_WEIGHT_GRAD, /* dW, db                                                         */
+  TDF_PHASE_EMBED_GRAD,  /* dE                                                             */
+  TDF_PHASE_COUNT
+};
+
 typedef struct {
   int64_t n_tags;         /* call-context tags created = function invocations           */
   int64_t n_steps;        /* match/fire steps of the tag machine                        */
@@ -188,6 +201,8 @@ typedef struct {
   int64_t max_tag_depth;  /* longest list of call labels                                */
   int64_t table_capacity; /* slots of the tag-hash table                                */
   int64_t max_probe;      /* longest probe sequence                                     */
+  double phase_ms[TDF_PHASE_COUNT];        /* device time of each phase                */
+  int64_t phase_launches[TDF_PHASE_COUNT]; /* kernel launches of each phase            */
   int32_t device_status;  /* tdf_status raised on the device                            */
   int32_t n_counts;       /* entries used in fire_count                                 */
   /* live firings per static-graph node, indexed like tdf_graph_info_t.nodes            */

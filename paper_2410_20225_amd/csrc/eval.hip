@@ -243,11 +243,21 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     return TDF_ERR_BAD_ARG;
   }
   hipStream_t s = (hipStream_t)hip_stream;
+  // phase timing: event pairs on the caller's stream, only when statistics are requested
+  const bool timed = stats != nullptr;
+  int64_t launches[TDF_PHASE_COUNT] = {0};
+  bool phase_used[TDF_PHASE_COUNT] = {false};
+  if (timed)
+    for (int i = 0; i < 2 * TDF_PHASE_COUNT; ++i)
+      if (!gr->events[i]) HIP_TRY(hipEventCreate((hipEvent_t*)&gr->events[i]));
+  auto begin = [&](int ph) { if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * ph], s); phase_used[ph] = true; } };
+  auto end = [&](int ph, int64_t n) { if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * ph + 1], s); launches[ph] += n; };
   Engine& e = P.e;
   VecArgs& v = P.v;
   e.out_i64 = (long long*)out->out_i64;
   char* base = (char*)workspace;
 
+  begin(TDF_PHASE_TAGS);
   HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
   launch_seed(G.prog, e, s);
 
@@ -264,21 +274,29 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     HIP_TRY(hipStreamSynchronize(s));
     if (hc.done) break;
   }
+  end(TDF_PHASE_TAGS, 2 + 3ll * step);
   tdf_status dev = status_from_device(hc.status);
 
   std::vector<uint32_t> level_off;
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
+    begin(TDF_PHASE_LEAVES);
     vec_pack_w(v, s);
     vec_embed(v, e, hc.n_leaf, s);
+    end(TDF_PHASE_LEAVES, 2);
     if (hc.n_cell) {
+      begin(TDF_PHASE_LEVELS);
       launch_levels(e, hc.n_cell, s);
       level_off.resize((size_t)hc.max_level + 2);
       HIP_TRY(hipMemcpyAsync(level_off.data(), e.level_off, level_off.size() * 4, hipMemcpyDeviceToHost, s));
+      end(TDF_PHASE_LEVELS, 3);
       HIP_TRY(hipStreamSynchronize(s));
+      begin(TDF_PHASE_CELLS_FWD);
       for (uint32_t lvl = 1; lvl <= hc.max_level; ++lvl)
         vec_cell_fwd(v, e, level_off[lvl], level_off[lvl + 1] - level_off[lvl], with_grad, s);
+      end(TDF_PHASE_CELLS_FWD, hc.max_level);
     }
+    begin(TDF_PHASE_HEAD);
     if (G.has_head) {
       vec_head(v, e, with_grad ? dy->dy : nullptr, with_grad, s);
       HIP_TRY(hipMemcpyAsync(out->out_f32, v.loss, sizeof(float) * e.n_inst, hipMemcpyDeviceToDevice, s));
@@ -286,10 +304,14 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       vec_out_rows(v, e, out->out_h, out->out_c, s);
       if (with_grad) vec_seed_dy(v, e, dy->dy, s);
     }
+    end(TDF_PHASE_HEAD, 2);
     if (with_grad) {
       // ---- gradient pass: the level schedule walked backwards -----------------------------
+      begin(TDF_PHASE_CELLS_BWD);
       for (uint32_t lvl = hc.max_level; lvl >= 1 && hc.n_cell; --lvl)
         vec_cell_bwd(v, e, level_off[lvl], level_off[lvl + 1] - level_off[lvl], s);
+      end(TDF_PHASE_CELLS_BWD, 2ll * hc.max_level);
+      begin(TDF_PHASE_WEIGHT_GRAD);
       if (hc.n_cell) {
         v.q_stride = (hc.n_cell + 31) / 32 * 32;   // only the cells that fired
         vec_weight_grads(v, e, hc.n_cell, grads->dW, grads->db, (float*)(base + P.off_db_part), s);
@@ -297,9 +319,12 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         HIP_TRY(hipMemsetAsync(grads->dW, 0, sizeof(float) * (size_t)v.N * 2 * v.H, s));
         HIP_TRY(hipMemsetAsync(grads->db, 0, sizeof(float) * (size_t)v.N, s));
       }
+      end(TDF_PHASE_WEIGHT_GRAD, 6);
+      begin(TDF_PHASE_EMBED_GRAD);
       vec_embed_grad(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
                      (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
                      (uint32_t*)(base + P.off_sorted), (float*)(base + P.off_de_part), grads->dE, DE_CHUNK, s);
+      end(TDF_PHASE_EMBED_GRAD, 5);
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(s));
@@ -318,6 +343,12 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->max_tag_depth = hc.max_depth;
     stats->table_capacity = e.cap;
     stats->max_probe = hc.max_probe;
+    for (int ph = 0; ph < TDF_PHASE_COUNT; ++ph) {
+      float ms = 0.f;
+      if (phase_used[ph] && hipEventElapsedTime(&ms, (hipEvent_t)gr->events[2 * ph], (hipEvent_t)gr->events[2 * ph + 1]) == hipSuccess)
+        stats->phase_ms[ph] = ms;
+      stats->phase_launches[ph] = launches[ph];
+    }
     stats->device_status = -(int32_t)hc.status;
     stats->n_counts = (int32_t)G.snodes.size();
     std::vector<unsigned long long> fc(TDF_STATS_MAX_COUNTS);
@@ -331,6 +362,11 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
 }  // namespace tdf
 
 using namespace tdf;
+
+tdf_graph::~tdf_graph() {
+  for (void* ev : events)
+    if (ev) (void)hipEventDestroy((hipEvent_t)ev);
+}
 
 extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* in, int with_grad, size_t* bytes) {
   if (!g || !bytes) {

@@ -495,7 +495,7 @@ extern "C" tdf_status tdf_graph_build(const tdf_program_desc* prog, int want_gra
   return TDF_OK;
 }
 
-extern "C" void tdf_graph_destroy(tdf_graph* g) { delete g; }
+extern "C" void tdf_graph_destroy(tdf_graph* g) { delete g; }   // ~tdf_graph is in eval.hip
 
 extern "C" tdf_status tdf_graph_info(const tdf_graph* g, tdf_graph_info_t* out) {
   if (!g || !out) {

@@ -83,4 +83,6 @@ void set_error(const std::string& msg);
 
 struct tdf_graph {
   tdf::Graph g;
+  void* events[2 * TDF_PHASE_COUNT] = {nullptr};   // hipEvent_t pairs, created on first use
+  ~tdf_graph();
 };

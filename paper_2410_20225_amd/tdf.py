@@ -6,6 +6,10 @@ HIP stream.  No computation happens here.
 import ctypes as C
 import os
 
+# torch ships its own copy of the HIP runtime; it must be loaded before libtdf.so so that the
+# library binds to the same runtime (one context, shared streams) instead of loading a second one
+import torch  # noqa: F401
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libtdf.so")
 if not os.path.exists(_LIB_PATH):
@@ -21,6 +25,7 @@ F32, BF16 = 0, 1
 SNODE_MERGE_ENTRY, SNODE_CALL, SNODE_RETURN = 100, 101, 102
 MAX_INPUTS = 4
 STATS_MAX_COUNTS = 256
+PHASES = ("tags", "leaves", "levels", "cells_fwd", "head", "cells_bwd", "weight_grad", "embed_grad")
 
 
 class Ref(C.Structure):
@@ -80,7 +85,8 @@ class Stats(C.Structure):
     _fields_ = [("n_tags", C.c_int64), ("n_steps", C.c_int64), ("n_tokens", C.c_int64),
                 ("n_leaf_rows", C.c_int64), ("n_cell_rows", C.c_int64), ("n_waves", C.c_int64),
                 ("n_grad_firings", C.c_int64), ("max_tag_depth", C.c_int64), ("table_capacity", C.c_int64),
-                ("max_probe", C.c_int64), ("device_status", C.c_int32), ("n_counts", C.c_int32),
+                ("max_probe", C.c_int64), ("phase_ms", C.c_double * 8), ("phase_launches", C.c_int64 * 8),
+                ("device_status", C.c_int32), ("n_counts", C.c_int32),
                 ("fire_count", C.c_int64 * STATS_MAX_COUNTS)]
 
 
@@ -179,7 +185,6 @@ def workspace_size(graph, inputs, with_grad=False):
 
 
 def _stream():
-    import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
