@@ -12,13 +12,14 @@ namespace tdf {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
 
 namespace {
 
 // ---- element traits --------------------------------------------------------------------
 template <typename T> struct El;
 template <> struct El<__bf16> {
-  static constexpr int BK = 32;      // k extent of one LDS tile
+  static constexpr int BK = 64;      // k extent of one LDS tile
   static constexpr int PAD = 8;      // row padding in elements
   static constexpr int MK = 16;      // k extent of one MFMA
   static constexpr int CH = 8;       // elements per 16-byte chunk
@@ -31,7 +32,7 @@ template <> struct El<__bf16> {
   }
 };
 template <> struct El<float> {
-  static constexpr int BK = 16;
+  static constexpr int BK = 32;
   static constexpr int PAD = 4;
   static constexpr int MK = 2;
   static constexpr int CH = 4;
@@ -48,7 +49,22 @@ __device__ __forceinline__ float to_f(float x) { return x; }
 __device__ __forceinline__ float to_f(__bf16 x) { return (float)x; }
 template <typename T> __device__ __forceinline__ T from_f(float x) { return (T)x; }
 
-__device__ __forceinline__ float sigmoidf_(float x) { return 1.0f / (1.0f + expf(-x)); }
+// Activations.  The fp32 path uses the accurate library functions; the bf16 path, whose
+// results are rounded to 8 bits of mantissa anyway, uses the hardware exponential.
+template <typename T> struct Act {
+  static __device__ __forceinline__ float sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
+  static __device__ __forceinline__ float tanh(float x) { return tanhf(x); }
+};
+template <> struct Act<__bf16> {
+  static __device__ __forceinline__ float sigmoid(float x) {
+    return __builtin_amdgcn_rcpf(1.0f + __expf(-x));
+  }
+  static __device__ __forceinline__ float tanh(float x) {
+    const float xc = fminf(fmaxf(x, -15.f), 15.f);
+    const float e = __expf(2.0f * xc);
+    return (e - 1.0f) * __builtin_amdgcn_rcpf(e + 1.0f);
+  }
+};
 
 // ---- GEMM  C[M x N] = A[M x K] * B[N x K]^T, both operands k-contiguous ----------------------
 enum GemmMode { RNN_FWD = 0, LSTM_FWD = 1, DX_BWD = 2, DW_SPLIT = 3 };
@@ -71,12 +87,17 @@ struct GemmArgs {
   float* C;                  // fp32 output (DX_BWD: dH; DW_SPLIT: partial tiles)
   size_t ldc;
   int k_per_split;           // DW_SPLIT: k range of one blockIdx.z
+  int n_tiles_n;             // column tiles of the launch
   int save_gates;
 };
 
 constexpr int GEMM_THREADS = 256;
 constexpr int BM = 128;
 
+// Workgroup tile BM x BN, four waves as 2 x 2, each wave 64 rows x WN column blocks of 32.
+// One LDS stage of BK columns; the next stage travels global -> registers while the current
+// one is multiplied.  LSTM_FWD gives every wave the five gate blocks of the same 32 hidden
+// units, so the gate epilogue needs no exchange between lanes.
 template <typename T, int MODE>
 __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
   typedef El<T> E;
@@ -87,124 +108,142 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
   constexpr int A_CHUNKS = BM * CPR / GEMM_THREADS;
   constexpr int B_CHUNKS = BN * CPR / GEMM_THREADS;
   extern __shared__ __attribute__((aligned(16))) char smem[];
-  T* sA = reinterpret_cast<T*>(smem);                  // [2][BM][LDT]
-  T* sB = sA + 2 * BM * LDT;                           // [2][BN][LDT]
+  T* sA = reinterpret_cast<T*>(smem);            // [BM][LDT]
+  T* sB = sA + BM * LDT;                         // [BN][LDT]
+
+  // tile coordinates: the column tiles of one row tile run back to back on one XCD
+  // (workgroups are dealt round-robin to the 8 XCDs), so the gathered rows are shared in its L2
+  const int n_mt = (g.M + BM - 1) / BM;
+  const int xcd = blockIdx.x & 7, u = blockIdx.x >> 3;
+  const int nt = u % g.n_tiles_n, mt = (u / g.n_tiles_n) * 8 + xcd;
+  if (mt >= n_mt) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int m0 = blockIdx.x * BM;
+  const int m0 = mt * BM;
   int k_begin = 0, k_end = g.K;
   if (MODE == DW_SPLIT) {
     k_begin = blockIdx.z * g.k_per_split;
     k_end = min(g.K, k_begin + g.k_per_split);
   }
 
-  // global row of B held by tile row `br`
-  auto b_row = [&](int br) -> int {
-    if (MODE == LSTM_FWD) {
-      const int w = br / 160, gate = (br % 160) / 32, jj = br % 32;
-      int jb = blockIdx.y * 2 + w;
-      jb = min(jb, g.Hp / 32 - 1);
-      return gate * g.Hp + jb * 32 + jj;
-    }
-    return min((int)blockIdx.y * BN + br, g.N - 1);
-  };
-
-  // per-thread source pointers of the chunks it copies each k-tile
-  const T* a_src[A_CHUNKS];
-  const T* a_src2[A_CHUNKS];   // second half of a gathered row
-  int a_dst[A_CHUNKS];
+  // element offsets of the 16-byte chunks this thread copies in every k-tile
+  uint32_t a_off[A_CHUNKS], a_off2[A_CHUNKS], b_off[B_CHUNKS];
+#pragma unroll
   for (int c = 0; c < A_CHUNKS; ++c) {
     const int id = tid + c * GEMM_THREADS, row = id / CPR, ch = id % CPR;
     const int m = min(m0 + row, g.M - 1);
-    a_dst[c] = row * LDT + ch * E::CH;
     if (MODE == RNN_FWD || MODE == LSTM_FWD) {
-      a_src[c] = reinterpret_cast<const T*>(g.Hs) + (size_t)g.l[m] * g.Hp + ch * E::CH;
-      a_src2[c] = reinterpret_cast<const T*>(g.Hs) + (size_t)g.r[m] * g.Hp + ch * E::CH;
+      a_off[c] = g.l[m] * (uint32_t)g.Hp + ch * E::CH;
+      a_off2[c] = g.r[m] * (uint32_t)g.Hp + ch * E::CH;
     } else {
-      a_src[c] = reinterpret_cast<const T*>(g.A) + (size_t)m * g.lda + ch * E::CH;
-      a_src2[c] = a_src[c];
+      a_off[c] = a_off2[c] = (uint32_t)m * (uint32_t)g.lda + ch * E::CH;
     }
   }
-  const T* b_src[B_CHUNKS];
-  int b_dst[B_CHUNKS];
+#pragma unroll
   for (int c = 0; c < B_CHUNKS; ++c) {
     const int id = tid + c * GEMM_THREADS, row = id / CPR, ch = id % CPR;
-    b_dst[c] = row * LDT + ch * E::CH;
-    b_src[c] = reinterpret_cast<const T*>(g.B) + (size_t)b_row(row) * g.ldb + ch * E::CH;
-  }
-
-  uint4 ra[A_CHUNKS], rb[B_CHUNKS];
-  auto load_global = [&](int k0) {
-    for (int c = 0; c < A_CHUNKS; ++c) {
-      const T* p;
-      if (MODE == RNN_FWD || MODE == LSTM_FWD) p = k0 < g.Hp ? a_src[c] + k0 : a_src2[c] + (k0 - g.Hp);
-      else p = a_src[c] + k0;
-      ra[c] = *reinterpret_cast<const uint4*>(p);
+    int brow;
+    if (MODE == LSTM_FWD) {
+      const int w = row / 160, gate = (row % 160) / 32, jj = row % 32;
+      brow = gate * g.Hp + min(nt * 2 + w, g.Hp / 32 - 1) * 32 + jj;
+    } else {
+      brow = min(nt * BN + row, g.N - 1);
     }
-    for (int c = 0; c < B_CHUNKS; ++c) rb[c] = *reinterpret_cast<const uint4*>(b_src[c] + k0);
-  };
-  auto store_lds = [&](int buf) {
-    for (int c = 0; c < A_CHUNKS; ++c) *reinterpret_cast<uint4*>(sA + buf * BM * LDT + a_dst[c]) = ra[c];
-    for (int c = 0; c < B_CHUNKS; ++c) *reinterpret_cast<uint4*>(sB + buf * BN * LDT + b_dst[c]) = rb[c];
-  };
+    b_off[c] = (uint32_t)brow * (uint32_t)g.ldb + ch * E::CH;
+  }
+  const T* Abase = reinterpret_cast<const T*>((MODE == RNN_FWD || MODE == LSTM_FWD) ? g.Hs : g.A);
+  const T* Bbase = reinterpret_cast<const T*>(g.B);
+
+  // staging registers of the next k-tile (global -> registers -> LDS)
+  u32x4 ra[A_CHUNKS], rb[B_CHUNKS];
+#define TDF_LOAD_TILE(K0)                                                                        \
+  _Pragma("unroll") for (int c = 0; c < A_CHUNKS; ++c) {                                         \
+    uint32_t off;                                                                                \
+    if (MODE == RNN_FWD || MODE == LSTM_FWD)                                                     \
+      off = (K0) < g.Hp ? a_off[c] + (K0) : a_off2[c] + ((K0) - g.Hp);                           \
+    else                                                                                         \
+      off = a_off[c] + (K0);                                                                     \
+    ra[c] = *reinterpret_cast<const u32x4*>(Abase + off);                                        \
+  }                                                                                              \
+  _Pragma("unroll") for (int c = 0; c < B_CHUNKS; ++c)                                           \
+    rb[c] = *reinterpret_cast<const u32x4*>(Bbase + b_off[c] + (K0));
 
   f32x16 acc[2][WN];
+#pragma unroll
   for (int i = 0; i < 2; ++i)
+#pragma unroll
     for (int j = 0; j < WN; ++j)
+#pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  int buf = 0;
+  const T* tA = sA + (wm * 64 + (lane & 31)) * LDT;
+  const T* tB = sB + (wn * WN * 32 + (lane & 31)) * LDT;
   if (k_begin < k_end) {
-    load_global(k_begin);
-    store_lds(0);
+    TDF_LOAD_TILE(k_begin)
   }
-  __syncthreads();
   for (int k0 = k_begin; k0 < k_end; k0 += E::BK) {
-    const bool more = k0 + E::BK < k_end;
-    if (more) load_global(k0 + E::BK);
-    const T* tA = sA + buf * BM * LDT + (wm * 64 + (lane & 31)) * LDT;
-    const T* tB = sB + buf * BN * LDT + (wn * WN * 32 + (lane & 31)) * LDT;
+#pragma unroll
+    for (int c = 0; c < A_CHUNKS; ++c) {
+      const int id = tid + c * GEMM_THREADS;
+      *reinterpret_cast<u32x4*>(sA + (id / CPR) * LDT + (id % CPR) * E::CH) = ra[c];
+    }
+#pragma unroll
+    for (int c = 0; c < B_CHUNKS; ++c) {
+      const int id = tid + c * GEMM_THREADS;
+      *reinterpret_cast<u32x4*>(sB + (id / CPR) * LDT + (id % CPR) * E::CH) = rb[c];
+    }
+    __syncthreads();
+    if (k0 + E::BK < k_end) {
+      TDF_LOAD_TILE(k0 + E::BK)
+    }
 #pragma unroll
     for (int ks = 0; ks < E::BK / E::MK; ++ks) {
       typename E::Frag fa[2], fb[WN];
+#pragma unroll
       for (int i = 0; i < 2; ++i) fa[i] = E::frag(tA + i * 32 * LDT, ks, lane);
+#pragma unroll
       for (int j = 0; j < WN; ++j) fb[j] = E::frag(tB + j * 32 * LDT, ks, lane);
+#pragma unroll
       for (int i = 0; i < 2; ++i)
+#pragma unroll
         for (int j = 0; j < WN; ++j) acc[i][j] = E::mma(fa[i], fb[j], acc[i][j]);
     }
-    if (more) store_lds(buf ^ 1);
     __syncthreads();
-    buf ^= 1;
   }
+#undef TDF_LOAD_TILE
 
   // ---- epilogue.  acc[i][j][r]: row = i*32 + (r/4)*8 + (lane/32)*4 + r%4, column = lane%32
   const int col = lane & 31;
+#pragma unroll
   for (int i = 0; i < 2; ++i) {
+#pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int m = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
       if (m >= g.M) continue;
       if constexpr (MODE == RNN_FWD) {
+        const size_t o = (size_t)g.out[m] * g.Hp;
+#pragma unroll
         for (int j = 0; j < WN; ++j) {
-          const int n = blockIdx.y * BN + (wn * WN + j) * 32 + col;
+          const int n = nt * BN + (wn * WN + j) * 32 + col;
           if (n >= g.N) continue;
-          const float h = tanhf(acc[i][j][r] + g.bias[n]);
-          reinterpret_cast<T*>(g.Hs_out)[(size_t)g.out[m] * g.Hp + n] = from_f<T>(h);
+          const float h = Act<T>::tanh(acc[i][j][r] + g.bias[n]);
+          reinterpret_cast<T*>(g.Hs_out)[o + n] = from_f<T>(h);
         }
       } else if constexpr (MODE == LSTM_FWD) {
-        const int jb = blockIdx.y * 2 + wn;
+        const int jb = nt * 2 + wn;
         if (jb * 32 >= g.Hp) continue;
         const int n = jb * 32 + col;   // hidden unit
-        const float gi = sigmoidf_(acc[i][0][r] + g.bias[n]);
-        const float gfl = sigmoidf_(acc[i][1][r] + g.bias[g.Hp + n]);
-        const float gfr = sigmoidf_(acc[i][2][r] + g.bias[2 * g.Hp + n]);
-        const float go = sigmoidf_(acc[i][3][r] + g.bias[3 * g.Hp + n]);
-        const float gu = tanhf(acc[i][4][r] + g.bias[4 * g.Hp + n]);
+        const float gi = Act<T>::sigmoid(acc[i][0][r] + g.bias[n]);
+        const float gfl = Act<T>::sigmoid(acc[i][1][r] + g.bias[g.Hp + n]);
+        const float gfr = Act<T>::sigmoid(acc[i][2][r] + g.bias[2 * g.Hp + n]);
+        const float go = Act<T>::sigmoid(acc[i][3][r] + g.bias[3 * g.Hp + n]);
+        const float gu = Act<T>::tanh(acc[i][4][r] + g.bias[4 * g.Hp + n]);
         const float cl = g.Cs[(size_t)g.l[m] * g.Hp + n], cr = g.Cs[(size_t)g.r[m] * g.Hp + n];
         const float c = gi * gu + gfl * cl + gfr * cr;
         const size_t o = (size_t)g.out[m] * g.Hp + n;
         g.Cs[o] = c;
-        reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * tanhf(c));
+        reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh(c));
         if (g.save_gates) {
           T* gr = reinterpret_cast<T*>(g.gates) + (size_t)m * g.ldg;
           gr[n] = from_f<T>(gi);
@@ -214,16 +253,18 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
           gr[4 * g.Hp + n] = from_f<T>(gu);
         }
       } else if constexpr (MODE == DX_BWD) {
+#pragma unroll
         for (int j = 0; j < WN; ++j) {
-          const int n = blockIdx.y * BN + (wn * WN + j) * 32 + col;
+          const int n = nt * BN + (wn * WN + j) * 32 + col;
           if (n >= g.N) continue;
           // column n of [dh_l; dh_r]: each child row has exactly one consumer, plain store
           if (n < g.Hp) g.C[(size_t)g.l[m] * g.Hp + n] = acc[i][j][r];
           else g.C[(size_t)g.r[m] * g.Hp + (n - g.Hp)] = acc[i][j][r];
         }
       } else {
+#pragma unroll
         for (int j = 0; j < WN; ++j) {
-          const int n = blockIdx.y * BN + (wn * WN + j) * 32 + col;
+          const int n = nt * BN + (wn * WN + j) * 32 + col;
           if (n >= g.N) continue;
           g.C[(size_t)blockIdx.z * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
         }
@@ -234,12 +275,14 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
 
 template <typename T, int MODE> size_t gemm_lds_bytes() {
   constexpr int WN = MODE == LSTM_FWD ? 5 : 2;
-  return (size_t)2 * (BM + 2 * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
+  return (size_t)(BM + 2 * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
 }
 
-template <typename T, int MODE> void launch_gemm(const GemmArgs& g, int n_tiles_y, int splits, hipStream_t s) {
+template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
   if (g.M <= 0) return;
-  dim3 grid((g.M + BM - 1) / BM, n_tiles_y, splits);
+  g.n_tiles_n = n_tiles_n;
+  const int n_mt = (g.M + BM - 1) / BM;
+  dim3 grid((n_mt + 7) / 8 * 8 * n_tiles_n, 1, splits);
   static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
   if (!lds_opt_in) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<T, MODE>),
@@ -356,7 +399,7 @@ __global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
     for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
       const float gi = to_f(gt[n]), gfl = to_f(gt[v.Hp + n]), gfr = to_f(gt[2 * v.Hp + n]);
       const float go = to_f(gt[3 * v.Hp + n]), gu = to_f(gt[4 * v.Hp + n]);
-      const float tc = tanhf(v.Cs[o + n]);
+      const float tc = Act<T>::tanh(v.Cs[o + n]);
       const float dh = v.dH[o + n];
       const float dc = v.dC[o + n] + dh * go * (1.f - tc * tc);
       const float cl = v.Cs[ol + n], cr = v.Cs[orr + n];
@@ -413,30 +456,47 @@ __global__ void k_reduce_dw(VecArgs v, float* dW, int splits) {
   }
 }
 
-// db[n] = sum_q Dz[q][n]: fixed chunks of tags, partial sums combined in chunk order
+// db[n] = sum_q Dz[q][n]: fixed chunks of 64 tags, partial sums combined in chunk order
 template <typename T>
-__global__ void k_db_partial(VecArgs v, uint32_t n_q, uint32_t chunk, float* part) {
-  const uint32_t q_lo = blockIdx.x * chunk, q_hi = min(n_q, q_lo + chunk);
-  for (int n = threadIdx.x; n < v.Np; n += blockDim.x) {
-    float s = 0.f;
-    for (uint32_t q = q_lo; q < q_hi; ++q) s += to_f(reinterpret_cast<const T*>(v.Dz)[(size_t)q * v.Np + n]);
-    part[(size_t)blockIdx.x * v.Np + n] = s;
+__global__ void k_db_partial(VecArgs v, uint32_t n_q, float* part) {
+  constexpr int CH = El<T>::CH;
+  const uint32_t q_lo = blockIdx.x * 64, q_hi = min(n_q, q_lo + 64);
+  for (int n = threadIdx.x * CH; n < v.Np; n += blockDim.x * CH) {
+    float s[CH];
+#pragma unroll
+    for (int i = 0; i < CH; ++i) s[i] = 0.f;
+    for (uint32_t q = q_lo; q < q_hi; ++q) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(v.Dz) + (size_t)q * v.Np + n);
+      const T* x = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+      for (int i = 0; i < CH; ++i) s[i] += to_f(x[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < CH; ++i) part[(size_t)blockIdx.x * v.Np + n + i] = s[i];
   }
 }
+// 64 columns per block, four groups of partials reduced through LDS in a fixed order
 __global__ void k_db_final(VecArgs v, const float* part, int n_parts, float* db) {
-  for (int n = blockIdx.x * blockDim.x + threadIdx.x; n < v.N; n += gridDim.x * blockDim.x) {
-    const int np = (n / v.H) * v.Hp + n % v.H;
-    float s = 0.f;
-    for (int p = 0; p < n_parts; ++p) s += part[(size_t)p * v.Np + np];
-    db[n] = s;
+  __shared__ float red[4][64];
+  const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int np = blockIdx.x * 64 + c;
+  float s = 0.f;
+  if (np < v.Np)
+    for (int p = grp; p < n_parts; p += 4) s += part[(size_t)p * v.Np + np];
+  red[grp][c] = s;
+  __syncthreads();
+  if (grp == 0 && np < v.Np) {
+    const int gate = np / v.Hp, j = np % v.Hp;
+    if (j < v.H) db[gate * v.H + j] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
   }
 }
 
 // ---- embedding gradient: leaves grouped by token, segments summed without atomics ---------------
 __global__ void k_tok_hist(Engine e, uint32_t n_leaf, uint32_t* count, int vocab) {
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_leaf; i += gridDim.x * blockDim.x) {
-    const uint32_t t = e.leaf_tok[i];
-    if (t < (uint32_t)vocab) atomicAdd(&count[t], 1u);
+  for (uint32_t base = blockIdx.x * blockDim.x; base < n_leaf; base += gridDim.x * blockDim.x) {
+    const uint32_t i = base + threadIdx.x;
+    const uint32_t t = i < n_leaf ? e.leaf_tok[i] : 0xFFFFFFFFu;
+    (void)wave_alloc_keyed(t < (uint32_t)vocab, t, count);
   }
 }
 // single block: exclusive scans of the per-token leaf counts and chunk counts
@@ -473,24 +533,36 @@ __global__ void k_tok_scan(const uint32_t* count, uint32_t* seg_off, uint32_t* c
 }
 __global__ void k_tok_scatter(Engine e, uint32_t n_leaf, const uint32_t* seg_off, uint32_t* fill,
                               uint32_t* sorted_row, int vocab) {
-  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_leaf; i += gridDim.x * blockDim.x) {
-    const uint32_t t = e.leaf_tok[i];
-    if (t < (uint32_t)vocab) sorted_row[seg_off[t] + atomicAdd(&fill[t], 1u)] = e.leaf_row[i];
+  for (uint32_t base = blockIdx.x * blockDim.x; base < n_leaf; base += gridDim.x * blockDim.x) {
+    const uint32_t i = base + threadIdx.x;
+    const uint32_t t = i < n_leaf ? e.leaf_tok[i] : 0xFFFFFFFFu;
+    const bool on = t < (uint32_t)vocab;
+    const uint32_t rank = wave_alloc_keyed(on, t, fill);
+    if (on) sorted_row[seg_off[t] + rank] = e.leaf_row[i];
   }
 }
-// one wave per (token, chunk): partial[chunk] = sum of dH rows of the chunk's leaves
+// one wave per chunk of at most `chunk` leaves of one token: partial[chunk] = sum of their dH rows
 __global__ void k_de_partial(VecArgs v, const uint32_t* seg_off, const uint32_t* chunk_off,
                              const uint32_t* sorted_row, uint32_t chunk, float* part) {
-  const int tok = blockIdx.x;
-  const uint32_t lo = seg_off[tok], hi = seg_off[tok + 1];
-  const uint32_t c_lo = chunk_off[tok], n_chunks = chunk_off[tok + 1] - c_lo;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, n_waves = blockDim.x >> 6;
+  const uint32_t n_chunks = chunk_off[v.vocab];
+  const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  const uint32_t n_waves = (gridDim.x * blockDim.x) >> 6;
   for (uint32_t c = wave; c < n_chunks; c += n_waves) {
-    const uint32_t p_lo = lo + c * chunk, p_hi = min(hi, p_lo + chunk);
-    for (int n = lane; n < v.H; n += 64) {
-      float s = 0.f;
-      for (uint32_t p = p_lo; p < p_hi; ++p) s += v.dH[(size_t)sorted_row[p] * v.Hp + n];
-      part[(size_t)(c_lo + c) * v.H + n] = s;
+    // token owning chunk c: the last t with chunk_off[t] <= c
+    uint32_t lo = 0, hi = (uint32_t)v.vocab;
+    while (hi - lo > 1) {
+      const uint32_t mid = (lo + hi) >> 1;
+      if (chunk_off[mid] <= c) lo = mid; else hi = mid;
+    }
+    const uint32_t p_lo = seg_off[lo] + (c - chunk_off[lo]) * chunk;
+    const uint32_t p_hi = min(seg_off[lo + 1], p_lo + chunk);
+    for (int n = lane * 4; n < v.Hp; n += 256) {
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (uint32_t p = p_lo; p < p_hi; ++p) {
+        const float4 x = *reinterpret_cast<const float4*>(v.dH + (size_t)sorted_row[p] * v.Hp + n);
+        s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+      }
+      *reinterpret_cast<float4*>(part + (size_t)c * v.Hp + n) = s;
     }
   }
 }
@@ -499,7 +571,7 @@ __global__ void k_de_final(VecArgs v, const uint32_t* chunk_off, const float* pa
   const uint32_t c_lo = chunk_off[tok], c_hi = chunk_off[tok + 1];
   for (int n = threadIdx.x; n < v.H; n += blockDim.x) {
     float s = 0.f;
-    for (uint32_t c = c_lo; c < c_hi; ++c) s += part[(size_t)c * v.H + n];
+    for (uint32_t c = c_lo; c < c_hi; ++c) s += part[(size_t)c * v.Hp + n];
     dE[(size_t)tok * v.H + n] = s;
   }
 }
@@ -581,7 +653,7 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   hipLaunchKernelGGL((k_transpose<T, true>), dim3(v.q_stride / 32, v.Kp / 32), tb, 0, s, v, e, n_q, v.Kp,
                      reinterpret_cast<T*>(v.XT));
   const int splits = vec_dw_splits(v.q_stride);
-  int kps = (int)((v.q_stride / 32 + splits - 1) / splits) * 32;
+  int kps = (int)((v.q_stride / 64 + splits - 1) / splits) * 64;
   GemmArgs g{};
   g.M = v.Np; g.N = v.Kp; g.K = (int)v.q_stride;
   g.A = v.DzT; g.lda = v.q_stride;
@@ -590,10 +662,9 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   g.k_per_split = kps;
   launch_gemm<T, DW_SPLIT>(g, (v.Kp + 127) / 128, splits, s);
   hipLaunchKernelGGL(k_reduce_dw, dim3(512), dim3(256), 0, s, v, dW, splits);
-  const uint32_t chunk = 512;
-  const int parts = (int)((n_q + chunk - 1) / chunk);
-  hipLaunchKernelGGL(k_db_partial<T>, dim3(parts), dim3(256), 0, s, v, n_q, chunk, db_part);
-  hipLaunchKernelGGL(k_db_final, dim3(8), dim3(256), 0, s, v, db_part, parts, db);
+  const int parts = (int)((n_q + 63) / 64);
+  hipLaunchKernelGGL(k_db_partial<T>, dim3(parts), dim3(256), 0, s, v, n_q, db_part);
+  hipLaunchKernelGGL(k_db_final, dim3(v.Np / 64), dim3(256), 0, s, v, db_part, parts, db);
 }
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {
   if (v.dtype == TDF_BF16) weight_grads_t<__bf16>(v, e, n_q, dW, db, db_part, s);
@@ -608,7 +679,9 @@ void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t
   hipLaunchKernelGGL(k_tok_hist, dim3(g), dim3(256), 0, s, e, n_leaf, count, v.vocab);
   hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);
   hipLaunchKernelGGL(k_tok_scatter, dim3(g), dim3(256), 0, s, e, n_leaf, seg_off, fill, sorted_row, v.vocab);
-  hipLaunchKernelGGL(k_de_partial, dim3(v.vocab), dim3(256), 0, s, v, seg_off, chunk_off, sorted_row, chunk, part);
+  const uint32_t max_chunks = n_leaf / chunk + std::min<uint32_t>((uint32_t)v.vocab, n_leaf) + 1;
+  hipLaunchKernelGGL(k_de_partial, dim3(std::min<uint32_t>((max_chunks + 3) / 4, 16384u)), dim3(256), 0, s, v, seg_off,
+                     chunk_off, sorted_row, chunk, part);
   hipLaunchKernelGGL(k_de_final, dim3(v.vocab), dim3(128), 0, s, v, chunk_off, part, dE);
 }
 

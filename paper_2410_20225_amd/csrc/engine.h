@@ -21,7 +21,7 @@ struct Ctrl {
   uint32_t status;           // 0, or -(tdf_status) raised on the device
   uint32_t done;
   uint32_t max_probe, max_depth, max_level;
-  uint32_t pad0;
+  uint32_t blocks_done;      // workgroups of the running match kernel that have finished
   unsigned long long n_tags, n_tokens;
 };
 
@@ -84,11 +84,72 @@ inline __device__ long long* frame_slots(FrameHdr* h) {
   return reinterpret_cast<long long*>(h + 1);
 }
 
+// ---- wave-level helpers (64-wide wavefronts) ------------------------------------------------
+inline __device__ unsigned lane_id() { return __lane_id(); }
+
+inline __device__ unsigned long long lanemask_lt() {
+  return (1ull << lane_id()) - 1ull;
+}
+
+// fmix64 of MurmurHash3 (Appleby, public domain).
+inline __device__ unsigned long long mix64(unsigned long long x) {
+  x ^= x >> 33;
+  x *= 0xff51afd7ed558ccdULL;
+  x ^= x >> 33;
+  x *= 0xc4ceb9fe1a85ec53ULL;
+  x ^= x >> 33;
+  return x;
+}
+
+// Wave-level compaction: lanes with `take` get consecutive positions from *counter.
+// Must be reached by every lane of the wave.
+inline __device__ uint32_t wave_alloc(bool take, uint32_t* counter) {
+  unsigned long long m = __ballot(take);
+  if (m == 0) return 0;
+  int leader = __ffsll((long long)m) - 1;
+  uint32_t base = 0;
+  if ((int)lane_id() == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+  base = __shfl(base, leader);
+  return base + (uint32_t)__popcll(m & lanemask_lt());
+}
+
+// Lanes with `take` get unique consecutive positions in counters[key]; lanes of the wave
+// that share a key are served by one atomic.  Must be reached by every lane of the wave.
+inline __device__ uint32_t wave_alloc_keyed(bool take, uint32_t key, uint32_t* counters) {
+  uint32_t pos = 0;
+  unsigned long long todo = __ballot(take);
+  while (todo) {
+    const int leader = __ffsll((long long)todo) - 1;
+    const uint32_t k0 = __shfl(key, leader);
+    const unsigned long long same = __ballot(take && key == k0) & todo;
+    uint32_t base = 0;
+    if ((int)lane_id() == leader) base = atomicAdd(&counters[k0], (uint32_t)__popcll(same));
+    base = __shfl(base, leader);
+    if ((same >> lane_id()) & 1) pos = base + (uint32_t)__popcll(same & lanemask_lt());
+    todo &= ~same;
+  }
+  return pos;
+}
+
+inline __device__ void wave_count(bool take, unsigned long long* counter) {
+  unsigned long long m = __ballot(take);
+  if (m && (int)lane_id() == __ffsll((long long)m) - 1)
+    atomicAdd(counter, (unsigned long long)__popcll(m));
+}
+
+inline __device__ void wave_max(uint32_t v, uint32_t* target) {
+  for (int off = 32; off > 0; off >>= 1) {
+    uint32_t o = __shfl_xor(v, off);
+    v = o > v ? o : v;
+  }
+  if (lane_id() == 0 && v > *target) atomicMax(target, v);
+}
+
 // ---- vector side ----------------------------------------------------------------------
 struct VecArgs {
   int dtype;        // tdf_dtype
   int cell_kind;    // 1 RNN, 2 LSTM
-  int H, Hp;        // hidden size and padded row stride (multiple of 32)
+  int H, Hp;        // hidden size and padded row stride (multiple of 64)
   int N, Np;        // gate rows of W: H or 5H; padded: Hp or 5*Hp
   int Kp;           // 2*Hp
   int vocab, n_classes;

@@ -29,7 +29,7 @@ void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t
 namespace {
 
 constexpr uint32_t DE_CHUNK = 128;
-constexpr uint32_t DB_CHUNK = 512;
+constexpr uint32_t DB_CHUNK = 64;
 
 struct Layout {
   size_t total = 0;
@@ -147,7 +147,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.dtype = in->dtype;
     v.cell_kind = G.cell_kind;
     v.H = in->hidden;
-    v.Hp = (in->hidden + 31) / 32 * 32;
+    v.Hp = (in->hidden + 63) / 64 * 64;
     const int gates = G.cell_kind == 2 ? 5 : 1;
     v.N = gates * v.H;
     v.Np = gates * v.Hp;
@@ -168,7 +168,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.bp = (float*)at(off_bp);
     v.loss = (float*)at(off_loss);
     if (with_grad) {
-      v.q_stride = (uint32_t)((P.max_cells + 31) / 32 * 32);
+      v.q_stride = (uint32_t)((P.max_cells + 63) / 64 * 64);
       size_t off_dH = L.take(R * v.Hp * 4);
       size_t off_dC = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
       size_t off_gates = G.cell_kind == 2 ? L.take((size_t)P.max_cells * v.Np * el) : 0;
@@ -181,7 +181,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       P.off_seg_off = L.take(4 * ((size_t)v.vocab + 2));
       P.off_chunk_off = L.take(4 * ((size_t)v.vocab + 2));
       P.off_sorted = L.take(4 * rc);
-      P.off_de_part = L.take(((size_t)R / DE_CHUNK + v.vocab + 2) * v.H * 4);
+      P.off_de_part = L.take(((size_t)R / DE_CHUNK + v.vocab + 2) * v.Hp * 4);
       v.dH = (float*)at(off_dH);
       v.dC = G.cell_kind == 2 ? (float*)at(off_dC) : nullptr;
       v.gates = G.cell_kind == 2 ? at(off_gates) : nullptr;
@@ -264,7 +264,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
   int max_values = 1;
   for (int f = 0; f < G.prog.n_fn; ++f) max_values = std::max<int>(max_values, G.prog.fn[f].n_values);
-  const int blocks = 1024;
+  const int blocks = 256;
   Ctrl hc{};
   uint32_t step = 0;
   const uint32_t poll = 32;
@@ -274,7 +274,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     HIP_TRY(hipStreamSynchronize(s));
     if (hc.done) break;
   }
-  end(TDF_PHASE_TAGS, 2 + 3ll * step);
+  end(TDF_PHASE_TAGS, 2 + 2ll * step);
   tdf_status dev = status_from_device(hc.status);
 
   std::vector<uint32_t> level_off;
@@ -313,7 +313,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       end(TDF_PHASE_CELLS_BWD, 2ll * hc.max_level);
       begin(TDF_PHASE_WEIGHT_GRAD);
       if (hc.n_cell) {
-        v.q_stride = (hc.n_cell + 31) / 32 * 32;   // only the cells that fired
+        v.q_stride = (hc.n_cell + 63) / 64 * 64;   // only the cells that fired
         vec_weight_grads(v, e, hc.n_cell, grads->dW, grads->db, (float*)(base + P.off_db_part), s);
       } else {
         HIP_TRY(hipMemsetAsync(grads->dW, 0, sizeof(float) * (size_t)v.N * 2 * v.H, s));

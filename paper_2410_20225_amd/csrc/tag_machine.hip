@@ -20,48 +20,6 @@ namespace {
 constexpr int FIRE_BLOCK = 128;
 constexpr int MATCH_BLOCK = 256;
 
-__device__ __forceinline__ unsigned lane_id() { return __lane_id(); }
-
-__device__ __forceinline__ unsigned long long lanemask_lt() {
-  return (1ull << lane_id()) - 1ull;
-}
-
-// fmix64 of MurmurHash3 (Appleby, public domain).
-__device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
-  x ^= x >> 33;
-  x *= 0xff51afd7ed558ccdULL;
-  x ^= x >> 33;
-  x *= 0xc4ceb9fe1a85ec53ULL;
-  x ^= x >> 33;
-  return x;
-}
-
-// Wave-level compaction: lanes with `take` get consecutive positions from *counter.
-// Must be reached by every lane of the wave.
-__device__ __forceinline__ uint32_t wave_alloc(bool take, uint32_t* counter) {
-  unsigned long long m = __ballot(take);
-  if (m == 0) return 0;
-  int leader = __ffsll((long long)m) - 1;
-  uint32_t base = 0;
-  if ((int)lane_id() == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
-  base = __shfl(base, leader);
-  return base + (uint32_t)__popcll(m & lanemask_lt());
-}
-
-__device__ __forceinline__ void wave_count(bool take, unsigned long long* counter) {
-  unsigned long long m = __ballot(take);
-  if (m && (int)lane_id() == __ffsll((long long)m) - 1)
-    atomicAdd(counter, (unsigned long long)__popcll(m));
-}
-
-__device__ __forceinline__ void wave_max(uint32_t v, uint32_t* target) {
-  for (int off = 32; off > 0; off >>= 1) {
-    uint32_t o = __shfl_xor(v, off);
-    v = o > v ? o : v;
-  }
-  if (lane_id() == 0 && v > *target) atomicMax(target, v);
-}
-
 __device__ __forceinline__ void raise(Ctrl* c, int status) {
   atomicCAS(&c->status, 0u, (uint32_t)(-status));
 }
@@ -336,6 +294,26 @@ __global__ void __launch_bounds__(FIRE_BLOCK) k_fire(DevProgram P, Engine e, int
   }
 }
 
+// ---- step bookkeeping: reset the consumed lists, count the step, detect the end -------------
+__device__ void advance(const Engine& e, int parity) {
+  Ctrl* c = e.ctrl;
+  const uint32_t next = __atomic_load_n(&c->touched_count[parity ^ 1], __ATOMIC_RELAXED);
+  const unsigned long long n_tags = __atomic_load_n(&c->n_tags, __ATOMIC_RELAXED);
+  uint32_t status = __atomic_load_n(&c->status, __ATOMIC_RELAXED);
+  c->q_count = 0;
+  c->touched_count[parity] = 0;
+  c->step += 1;
+  if (n_tags > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
+  if (c->step >= e.step_limit && next != 0 && status == 0) status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
+  if (status != 0) {
+    c->status = status;
+    c->touched_count[parity ^ 1] = 0;   // drain: nothing more fires
+    c->done = 1;
+  } else if (next == 0) {
+    c->done = 1;
+  }
+}
+
 // ---- match -------------------------------------------------------------------------------
 __global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e, int parity) {
   Ctrl* c = e.ctrl;
@@ -414,32 +392,31 @@ __global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e, i
       wave_max(depth, &c->max_depth);
     }
   }
-}
-
-// ---- step bookkeeping ----------------------------------------------------------------------
-__global__ void k_advance(Engine e, int parity) {
-  Ctrl* c = e.ctrl;
-  c->q_count = 0;
-  c->touched_count[parity] = 0;
-  c->step += 1;
-  if (c->n_tags > e.max_tags && c->status == 0) c->status = (uint32_t)(-TDF_ERR_TABLE_FULL);
-  if (c->step >= e.step_limit && c->touched_count[parity ^ 1] != 0 && c->status == 0)
-    c->status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
-  if (c->status != 0) {
-    c->touched_count[parity ^ 1] = 0;   // drain: nothing more fires
-    c->done = 1;
-  } else if (c->touched_count[parity ^ 1] == 0) {
-    c->done = 1;
+  // the last workgroup to finish closes the step
+  __shared__ bool last;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    last = atomicAdd(&c->blocks_done, 1u) == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (last && threadIdx.x == 0) {
+    __threadfence();
+    c->blocks_done = 0;
+    advance(e, parity);
   }
 }
+
 
 // ---- cells by dependency level --------------------------------------------------------------
 // A cell's level is 1 + the larger level of its two operands (leaves are level 0); cells of
 // one level are independent of each other.  Counting sort of the firing log by level.
 __global__ void k_level_hist(Engine e) {
   const uint32_t n = e.ctrl->n_cell;
-  for (uint32_t j = blockIdx.x * blockDim.x + threadIdx.x; j < n; j += gridDim.x * blockDim.x)
-    atomicAdd(&e.level_count[e.cell_lvl[j]], 1u);
+  for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
+    const uint32_t j = base + threadIdx.x;
+    (void)wave_alloc_keyed(j < n, j < n ? e.cell_lvl[j] : 0, e.level_count);
+  }
 }
 
 __global__ void k_level_scan(Engine e) {
@@ -469,12 +446,17 @@ __global__ void k_level_scan(Engine e) {
 
 __global__ void k_level_scatter(Engine e) {
   const uint32_t n = e.ctrl->n_cell;
-  for (uint32_t j = blockIdx.x * blockDim.x + threadIdx.x; j < n; j += gridDim.x * blockDim.x) {
-    const uint32_t lvl = e.cell_lvl[j];
-    const uint32_t q = e.level_off[lvl] + atomicAdd(&e.level_fill[lvl], 1u);
-    e.q_out[q] = e.cell_out[j];
-    e.q_l[q] = e.cell_l[j];
-    e.q_r[q] = e.cell_r[j];
+  for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
+    const uint32_t j = base + threadIdx.x;
+    const bool on = j < n;
+    const uint32_t lvl = on ? e.cell_lvl[j] : 0;
+    const uint32_t rank = wave_alloc_keyed(on, lvl, e.level_fill);
+    if (on) {
+      const uint32_t q = e.level_off[lvl] + rank;
+      e.q_out[q] = e.cell_out[j];
+      e.q_l[q] = e.cell_l[j];
+      e.q_r[q] = e.cell_r[j];
+    }
   }
 }
 
@@ -497,7 +479,6 @@ void launch_step(const DevProgram& P, const Engine& e, int parity, int max_value
   size_t lds = (size_t)max_values * FIRE_BLOCK * sizeof(long long);
   hipLaunchKernelGGL(k_fire, dim3(blocks), dim3(FIRE_BLOCK), lds, s, P, e, parity);
   hipLaunchKernelGGL(k_match, dim3(blocks), dim3(MATCH_BLOCK), 0, s, P, e, parity);
-  hipLaunchKernelGGL(k_advance, dim3(1), dim3(1), 0, s, e, parity);
 }
 
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s) {
