@@ -214,59 +214,80 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
 #undef TDF_LOAD_TILE
 
   // ---- epilogue.  acc[i][j][r]: row = i*32 + (r/4)*8 + (lane/32)*4 + r%4, column = lane%32
+  // Row indices of the tile go through LDS so that no store waits on an index load.
+  uint32_t* sOut = reinterpret_cast<uint32_t*>(smem);
+  uint32_t* sL = sOut + BM;
+  uint32_t* sR = sL + BM;
+  if (MODE != DW_SPLIT && tid < BM) {
+    const int m = min(m0 + tid, g.M - 1);
+    if (MODE != DX_BWD) sOut[tid] = g.out[m];
+    sL[tid] = g.l[m];
+    sR[tid] = g.r[m];
+  }
+  __syncthreads();
   const int col = lane & 31;
+  auto row_of = [&](int i, int r) { return wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); };
+  if constexpr (MODE == LSTM_FWD) {
+    const int jb = nt * 2 + wn;
+    if (jb * 32 < g.Hp) {
+      const int n = jb * 32 + col;   // hidden unit
+      const float bi = g.bias[n], bfl = g.bias[g.Hp + n], bfr = g.bias[2 * g.Hp + n];
+      const float bo = g.bias[3 * g.Hp + n], bu = g.bias[4 * g.Hp + n];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < 2; ++i) {
+        float cl[16], cr[16];   // children's cell states: all loads in flight before any store
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = m0 + wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-      if (m >= g.M) continue;
-      if constexpr (MODE == RNN_FWD) {
-        const size_t o = (size_t)g.out[m] * g.Hp;
-#pragma unroll
-        for (int j = 0; j < WN; ++j) {
-          const int n = nt * BN + (wn * WN + j) * 32 + col;
-          if (n >= g.N) continue;
-          const float h = Act<T>::tanh(acc[i][j][r] + g.bias[n]);
-          reinterpret_cast<T*>(g.Hs_out)[o + n] = from_f<T>(h);
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_of(i, r);
+          cl[r] = g.Cs[(size_t)sL[row] * g.Hp + n];
+          cr[r] = g.Cs[(size_t)sR[row] * g.Hp + n];
         }
-      } else if constexpr (MODE == LSTM_FWD) {
-        const int jb = nt * 2 + wn;
-        if (jb * 32 >= g.Hp) continue;
-        const int n = jb * 32 + col;   // hidden unit
-        const float gi = Act<T>::sigmoid(acc[i][0][r] + g.bias[n]);
-        const float gfl = Act<T>::sigmoid(acc[i][1][r] + g.bias[g.Hp + n]);
-        const float gfr = Act<T>::sigmoid(acc[i][2][r] + g.bias[2 * g.Hp + n]);
-        const float go = Act<T>::sigmoid(acc[i][3][r] + g.bias[3 * g.Hp + n]);
-        const float gu = Act<T>::tanh(acc[i][4][r] + g.bias[4 * g.Hp + n]);
-        const float cl = g.Cs[(size_t)g.l[m] * g.Hp + n], cr = g.Cs[(size_t)g.r[m] * g.Hp + n];
-        const float c = gi * gu + gfl * cl + gfr * cr;
-        const size_t o = (size_t)g.out[m] * g.Hp + n;
-        g.Cs[o] = c;
-        reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh(c));
-        if (g.save_gates) {
-          T* gr = reinterpret_cast<T*>(g.gates) + (size_t)m * g.ldg;
-          gr[n] = from_f<T>(gi);
-          gr[g.Hp + n] = from_f<T>(gfl);
-          gr[2 * g.Hp + n] = from_f<T>(gfr);
-          gr[3 * g.Hp + n] = from_f<T>(go);
-          gr[4 * g.Hp + n] = from_f<T>(gu);
-        }
-      } else if constexpr (MODE == DX_BWD) {
 #pragma unroll
-        for (int j = 0; j < WN; ++j) {
-          const int n = nt * BN + (wn * WN + j) * 32 + col;
-          if (n >= g.N) continue;
-          // column n of [dh_l; dh_r]: each child row has exactly one consumer, plain store
-          if (n < g.Hp) g.C[(size_t)g.l[m] * g.Hp + n] = acc[i][j][r];
-          else g.C[(size_t)g.r[m] * g.Hp + (n - g.Hp)] = acc[i][j][r];
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_of(i, r), m = m0 + row;
+          if (m >= g.M) continue;
+          const float gi = Act<T>::sigmoid(acc[i][0][r] + bi);
+          const float gfl = Act<T>::sigmoid(acc[i][1][r] + bfl);
+          const float gfr = Act<T>::sigmoid(acc[i][2][r] + bfr);
+          const float go = Act<T>::sigmoid(acc[i][3][r] + bo);
+          const float gu = Act<T>::tanh(acc[i][4][r] + bu);
+          const float c = gi * gu + gfl * cl[r] + gfr * cr[r];
+          const size_t o = (size_t)sOut[row] * g.Hp + n;
+          g.Cs[o] = c;
+          reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh(c));
+          if (g.save_gates) {
+            T* gr = reinterpret_cast<T*>(g.gates) + (size_t)m * g.ldg;
+            gr[n] = from_f<T>(gi);
+            gr[g.Hp + n] = from_f<T>(gfl);
+            gr[2 * g.Hp + n] = from_f<T>(gfr);
+            gr[3 * g.Hp + n] = from_f<T>(go);
+            gr[4 * g.Hp + n] = from_f<T>(gu);
+          }
         }
-      } else {
+      }
+    }
+  } else {
 #pragma unroll
-        for (int j = 0; j < WN; ++j) {
-          const int n = nt * BN + (wn * WN + j) * 32 + col;
-          if (n >= g.N) continue;
-          g.C[(size_t)blockIdx.z * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
+    for (int j = 0; j < WN; ++j) {
+      const int n = nt * BN + (wn * WN + j) * 32 + col;
+      if (n >= g.N) continue;
+      float bias = 0.f;
+      if (MODE == RNN_FWD) bias = g.bias[n];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int row = row_of(i, r), m = m0 + row;
+          if (m >= g.M) continue;
+          if constexpr (MODE == RNN_FWD) {
+            reinterpret_cast<T*>(g.Hs_out)[(size_t)sOut[row] * g.Hp + n] = from_f<T>(Act<T>::tanh(acc[i][j][r] + bias));
+          } else if constexpr (MODE == DX_BWD) {
+            // column n of [dh_l; dh_r]: each child row has exactly one consumer, plain store
+            if (n < g.Hp) g.C[(size_t)sL[row] * g.Hp + n] = acc[i][j][r];
+            else g.C[(size_t)sR[row] * g.Hp + (n - g.Hp)] = acc[i][j][r];
+          } else {
+            g.C[(size_t)blockIdx.z * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
+          }
         }
       }
     }

@@ -58,6 +58,7 @@ struct Engine {
   uint32_t* touched;
   uint32_t touched_cap;
   uint32_t step_limit;
+  uint32_t small_limit;             // steps with at most this many touched frames run in one workgroup
   // forest
   const int32_t *left, *right, *token;
   int32_t n_tree_nodes;

@@ -11,7 +11,8 @@
 namespace tdf {
 
 void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
-void launch_step(const DevProgram& P, const Engine& e, int parity, int max_values, int blocks, hipStream_t s);
+void launch_round(const DevProgram& P, const Engine& e, int max_values, int blocks, int small_block,
+                  int small_steps, hipStream_t s);
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s);
 void vec_pack_w(const VecArgs& v, hipStream_t s);
 void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s);
@@ -264,17 +265,19 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
   int max_values = 1;
   for (int f = 0; f < G.prog.n_fn; ++f) max_values = std::max<int>(max_values, G.prog.fn[f].n_values);
-  const int blocks = 256;
+  const int blocks = 768;
+  const int small_block = max_values <= 32 ? 512 : 256;   // the value file must fit in LDS
+  e.small_limit = 2u * (uint32_t)small_block;
   Ctrl hc{};
-  uint32_t step = 0;
-  const uint32_t poll = 32;
+  uint32_t rounds = 0;
+  const uint32_t poll = 16;
   for (;;) {
-    for (uint32_t i = 0; i < poll; ++i, ++step) launch_step(G.prog, e, (int)(step & 1), max_values, blocks, s);
+    for (uint32_t i = 0; i < poll; ++i, ++rounds) launch_round(G.prog, e, max_values, blocks, small_block, 64, s);
     HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (hc.done) break;
   }
-  end(TDF_PHASE_TAGS, 2 + 2ll * step);
+  end(TDF_PHASE_TAGS, 2 + 3ll * rounds);
   tdf_status dev = status_from_device(hc.status);
 
   std::vector<uint32_t> level_off;

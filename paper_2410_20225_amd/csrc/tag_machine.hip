@@ -48,12 +48,14 @@ struct Src {
   bool p, d;   // present, dead
 };
 
-__global__ void __launch_bounds__(FIRE_BLOCK) k_fire(DevProgram P, Engine e, int parity) {
-  extern __shared__ long long regs[];   // [value][lane of the block]
+// One pass over the touched frames [0, n): lane `first + tid` takes frame i, i + stride, ...
+// regs is the block's value file in LDS, [value][lane of the block].
+__device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint32_t first, uint32_t stride,
+                          long long* regs) {
   Ctrl* c = e.ctrl;
-  const uint32_t n = c->touched_count[parity];
   const int tid = threadIdx.x;
-  for (uint32_t base = blockIdx.x * FIRE_BLOCK; base < n; base += gridDim.x * FIRE_BLOCK) {
+  const int FIRE_BLOCK = blockDim.x;
+  for (uint32_t base = first; base < n; base += stride) {
     const uint32_t i = base + tid;
     const bool active = i < n;
     const uint32_t frame = active ? e.touched[i] : 0;
@@ -64,8 +66,10 @@ __global__ void __launch_bounds__(FIRE_BLOCK) k_fire(DevProgram P, Engine e, int
     int myfn = -1;
     if (active) {
       fired = h->fired;
-      present = h->present_fn & 0xFFFFFFu;
-      myfn = (int)(h->present_fn >> 24);
+      // present_fn is updated with atomics by the match pass: read it the same way
+      const uint32_t pf = __atomic_load_n(&h->present_fn, __ATOMIC_RELAXED);
+      present = pf & 0xFFFFFFu;
+      myfn = (int)(pf >> 24);
     }
     const unsigned long long fired_in = fired;
     const uint32_t present_in = present;
@@ -289,9 +293,21 @@ __global__ void __launch_bounds__(FIRE_BLOCK) k_fire(DevProgram P, Engine e, int
     }
     if (active && (fired != fired_in || present != present_in)) {
       h->fired = fired;
-      if (present != present_in) h->present_fn = present | ((uint32_t)myfn << 24);
+      if (present != present_in) atomicOr(&h->present_fn, present & ~present_in);
     }
   }
+}
+
+// A step is "small" when its touched frames fit a few passes of one workgroup; small steps
+// run in k_steps_small, the others in the grid-wide k_fire / k_match pair.
+__device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
+
+__global__ void k_fire(DevProgram P, Engine e) {
+  extern __shared__ long long regs[];
+  Ctrl* c = e.ctrl;
+  const uint32_t n = __atomic_load_n(&c->touched_count[c->step & 1], __ATOMIC_RELAXED);
+  if (c->done || n == 0 || step_is_small(e, n)) return;
+  fire_pass(P, e, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, regs);
 }
 
 // ---- step bookkeeping: reset the consumed lists, count the step, detect the end -------------
@@ -300,14 +316,14 @@ __device__ void advance(const Engine& e, int parity) {
   const uint32_t next = __atomic_load_n(&c->touched_count[parity ^ 1], __ATOMIC_RELAXED);
   const unsigned long long n_tags = __atomic_load_n(&c->n_tags, __ATOMIC_RELAXED);
   uint32_t status = __atomic_load_n(&c->status, __ATOMIC_RELAXED);
-  c->q_count = 0;
-  c->touched_count[parity] = 0;
+  __atomic_store_n(&c->q_count, 0u, __ATOMIC_RELAXED);
+  __atomic_store_n(&c->touched_count[parity], 0u, __ATOMIC_RELAXED);
   c->step += 1;
   if (n_tags > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
   if (c->step >= e.step_limit && next != 0 && status == 0) status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
   if (status != 0) {
-    c->status = status;
-    c->touched_count[parity ^ 1] = 0;   // drain: nothing more fires
+    __atomic_store_n(&c->status, status, __ATOMIC_RELAXED);
+    __atomic_store_n(&c->touched_count[parity ^ 1], 0u, __ATOMIC_RELAXED);   // drain: nothing more fires
     c->done = 1;
   } else if (next == 0) {
     c->done = 1;
@@ -315,12 +331,12 @@ __device__ void advance(const Engine& e, int parity) {
 }
 
 // ---- match -------------------------------------------------------------------------------
-__global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e, int parity) {
+// One pass over the tokens [0, n) of the queue.
+__device__ void match_pass(const DevProgram& P, const Engine& e, int parity, uint32_t n, uint32_t stamp,
+                           uint32_t first, uint32_t lane_stride) {
   Ctrl* c = e.ctrl;
-  const uint32_t n = c->q_count;
-  const uint32_t stamp = c->step + 1;
   const int stride = P.frame_stride;
-  for (uint32_t base = blockIdx.x * MATCH_BLOCK; base < n; base += gridDim.x * MATCH_BLOCK) {
+  for (uint32_t base = first; base < n; base += lane_stride) {
     const uint32_t i = base + threadIdx.x;
     const bool active = i < n;
     bool inserted = false, deliver = false;
@@ -367,7 +383,7 @@ __global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e, i
       } else {
         // Return_i: <i:t,d> -> <t,d>.  The frame's own key names its label i and the frame
         // of t, so only the Return_i of the call that created the frame produces output.
-        const unsigned long long key = frame_at(e, stride, t.a)->key;
+        const unsigned long long key = __atomic_load_n(&frame_at(e, stride, t.a)->key, __ATOMIC_RELAXED);
         const uint32_t parent = (uint32_t)(key >> 32) - 1u, label = (uint32_t)key - 1u;
         FrameHdr* h = frame_at(e, stride, parent);
         const uint32_t slot = P.label_ret_slot[label];
@@ -392,6 +408,16 @@ __global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e, i
       wave_max(depth, &c->max_depth);
     }
   }
+}
+
+__global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e) {
+  Ctrl* c = e.ctrl;
+  const uint32_t step = c->step;
+  const int parity = (int)(step & 1);
+  const uint32_t n_touched = __atomic_load_n(&c->touched_count[parity], __ATOMIC_RELAXED);
+  if (c->done || n_touched == 0 || step_is_small(e, n_touched)) return;   // same test as k_fire
+  const uint32_t n = __atomic_load_n(&c->q_count, __ATOMIC_RELAXED);
+  match_pass(P, e, parity, n, step + 1, blockIdx.x * blockDim.x, gridDim.x * blockDim.x);
   // the last workgroup to finish closes the step
   __shared__ bool last;
   __syncthreads();
@@ -402,8 +428,39 @@ __global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e, i
   __syncthreads();
   if (last && threadIdx.x == 0) {
     __threadfence();
-    c->blocks_done = 0;
+    __atomic_store_n(&c->blocks_done, 0u, __ATOMIC_RELAXED);
     advance(e, parity);
+  }
+}
+
+// Small steps: one workgroup runs fire and match back to back, step after step, with workgroup
+// barriers only.  Returns when the recursion is finished, when a step is too large for one
+// workgroup, or after max_steps steps.
+__global__ void k_steps_small(DevProgram P, Engine e, int max_steps) {
+  extern __shared__ long long regs[];
+  __shared__ uint32_t sh[3];
+  Ctrl* c = e.ctrl;
+  for (int it = 0; it < max_steps; ++it) {
+    if (threadIdx.x == 0) {
+      const uint32_t step = c->step;
+      sh[0] = step;
+      sh[1] = __atomic_load_n(&c->touched_count[step & 1], __ATOMIC_RELAXED);
+      sh[2] = c->done;
+    }
+    __syncthreads();
+    const uint32_t step = sh[0], n = sh[1], stop = sh[2];
+    __syncthreads();
+    if (stop || n == 0 || !step_is_small(e, n)) return;
+    const int parity = (int)(step & 1);
+    fire_pass(P, e, n, 0, blockDim.x, regs);
+    __threadfence();
+    __syncthreads();
+    const uint32_t qn = __atomic_load_n(&c->q_count, __ATOMIC_RELAXED);
+    match_pass(P, e, parity, qn, step + 1, 0, blockDim.x);
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) advance(e, parity);
+    __syncthreads();
   }
 }
 
@@ -473,12 +530,18 @@ void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s) {
   hipLaunchKernelGGL(k_seed, dim3(grid_for(e.n_inst, 256, 1 << 20)), dim3(256), 0, s, P, e);
 }
 
-// One step of the tag machine: fire the touched frames, match the emitted tokens.
-void launch_step(const DevProgram& P, const Engine& e, int parity, int max_values, int blocks,
-                 hipStream_t s) {
-  size_t lds = (size_t)max_values * FIRE_BLOCK * sizeof(long long);
-  hipLaunchKernelGGL(k_fire, dim3(blocks), dim3(FIRE_BLOCK), lds, s, P, e, parity);
-  hipLaunchKernelGGL(k_match, dim3(blocks), dim3(MATCH_BLOCK), 0, s, P, e, parity);
+// One round of the tag machine: as many small steps as fit (one workgroup), then one
+// grid-wide step if the next step is large.  Each kernel decides on the device whether the
+// current step is its own.
+void launch_round(const DevProgram& P, const Engine& e, int max_values, int blocks, int small_block,
+                  int small_steps, hipStream_t s) {
+  const size_t small_lds = (size_t)max_values * small_block * sizeof(long long);
+  if (small_lds > 48 * 1024)   // large value files need the LDS opt-in
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_small),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds);
+  hipLaunchKernelGGL(k_steps_small, dim3(1), dim3(small_block), small_lds, s, P, e, small_steps);
+  hipLaunchKernelGGL(k_fire, dim3(blocks), dim3(FIRE_BLOCK), (size_t)max_values * FIRE_BLOCK * sizeof(long long), s, P, e);
+  hipLaunchKernelGGL(k_match, dim3(blocks), dim3(MATCH_BLOCK), 0, s, P, e);
 }
 
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s) {
