@@ -88,7 +88,7 @@ def main():
         fns, r = programs.fib()
         g = tdf.graph_build(fns, r)
         args = torch.arange(0, 21, dtype=torch.int64, device=dev)
-        inp = tdf.make_inputs(21, args=args, n_args=1, max_tags=57291)
+        inp = tdf.make_inputs(21, args=args, n_args=1, max_tags=57291, stats_level=0)
         ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=dev)
         out = torch.zeros(21, dtype=torch.int64, device=dev)
         step = lambda: tdf.eval(g, inp, ws, out_i64=out)[1]
@@ -97,7 +97,7 @@ def main():
         from gpu_util import TreeRun
         c = make_config(cfg)
         grad = c["grad"]
-        run = TreeRun(c, head=grad, grad=grad)
+        run = TreeRun(c, head=grad, grad=grad, stats_level=0)
         B = run.B
         dy = np.full(B, 1.0 / B)
         step = lambda: run.run(dy if grad else None)[1]

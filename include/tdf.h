@@ -155,6 +155,8 @@ typedef struct {
   /* capacities */
   int64_t max_tags;   /* upper bound on call-context tags (= invocations) of one call   */
   int32_t step_limit; /* 0 = default (1<<20)                                            */
+  int32_t stats_level; /* 0: counters and phase times; 1: also tdf_stats.fire_count (one
+                          extra pass over the frame table after the evaluation)           */
 } tdf_inputs;
 
 typedef struct {

@@ -45,6 +45,14 @@ template <> struct El<float> {
   }
 };
 
+// Kernels are instantiated on the tdf_dtype value (readable names in profiles), not on the type.
+template <int DT> struct TypeOf;
+template <> struct TypeOf<TDF_F32> { typedef float type; };
+template <> struct TypeOf<TDF_BF16> { typedef __bf16 type; };
+template <typename T> struct DtOf;
+template <> struct DtOf<float> { static constexpr int value = TDF_F32; };
+template <> struct DtOf<__bf16> { static constexpr int value = TDF_BF16; };
+
 __device__ __forceinline__ float to_f(float x) { return x; }
 __device__ __forceinline__ float to_f(__bf16 x) { return (float)x; }
 template <typename T> __device__ __forceinline__ T from_f(float x) { return (T)x; }
@@ -98,8 +106,9 @@ constexpr int BM = 128;
 // One LDS stage of BK columns; the next stage travels global -> registers while the current
 // one is multiplied.  LSTM_FWD gives every wave the five gate blocks of the same 32 hidden
 // units, so the gate epilogue needs no exchange between lanes.
-template <typename T, int MODE>
+template <int DT, int MODE>
 __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
+  typedef typename TypeOf<DT>::type T;
   typedef El<T> E;
   constexpr int WN = MODE == LSTM_FWD ? 5 : 2;   // 32-wide column blocks per wave
   constexpr int BN = 2 * WN * 32;                // columns per workgroup
@@ -306,17 +315,18 @@ template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int 
   dim3 grid((n_mt + 7) / 8 * 8 * n_tiles_n, 1, splits);
   static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
   if (!lds_opt_in) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<T, MODE>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE>());
     lds_opt_in = true;
   }
   const size_t lds = gemm_lds_bytes<T, MODE>();
-  hipLaunchKernelGGL((k_gemm<T, MODE>), grid, dim3(GEMM_THREADS), lds, s, g);
+  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE>), grid, dim3(GEMM_THREADS), lds, s, g);
 }
 
 // ---- packing of W: padded, k-contiguous [Np x Kp], and its transpose [Kp x Np] ---------------
-template <typename T>
+template <int DT>
 __global__ void k_pack_w(VecArgs v) {
+  typedef typename TypeOf<DT>::type T;
   const int total = v.Np * v.Kp;
   for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
     const int np = idx / v.Kp, kp = idx % v.Kp;
@@ -331,8 +341,9 @@ __global__ void k_pack_w(VecArgs v) {
 }
 
 // ---- leaves: state row = E[token], zero padding, zero cell state -----------------------------
-template <typename T>
+template <int DT>
 __global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
+  typedef typename TypeOf<DT>::type T;
   const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   const int n_waves = (gridDim.x * blockDim.x) >> 6;
   for (uint32_t i = wave; i < n_leaf; i += n_waves) {
@@ -346,8 +357,9 @@ __global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
 }
 
 // ---- classification head: loss_b = -log softmax(U h + u0)[label]; dh = U^T (p - onehot) dloss ---
-template <typename T>
+template <int DT>
 __global__ void k_head(VecArgs v, Engine e, const float* dy, int with_grad) {
+  typedef typename TypeOf<DT>::type T;
   const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   if (wave >= (int)e.n_inst) return;
   const uint32_t row = e.head_row[wave];
@@ -389,8 +401,9 @@ __global__ void k_seed_dy(VecArgs v, Engine e, const float* dy) {
   }
 }
 
-template <typename T>
+template <int DT>
 __global__ void k_out_rows(VecArgs v, Engine e, float* out_h, float* out_c) {
+  typedef typename TypeOf<DT>::type T;
   const int b = blockIdx.x;
   const uint32_t row = e.root_ref[b];
   for (int n = threadIdx.x; n < v.H; n += blockDim.x) {
@@ -402,8 +415,9 @@ __global__ void k_out_rows(VecArgs v, Engine e, float* out_h, float* out_c) {
 // ---- pre-activation gradients of one level ------------------------------------------------------
 // TreeRNN: delta = dh * (1 - h^2).  TreeLSTM: the gate gradients (i, f_l, f_r, o, u) and the
 // cell-state gradients handed to the two children.
-template <typename T>
+template <int DT>
 __global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
+  typedef typename TypeOf<DT>::type T;
   const uint32_t m = blockIdx.x;
   if (m >= count) return;
   const uint32_t q = q0 + m;
@@ -438,8 +452,10 @@ __global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
 // ---- transposes feeding the weight-gradient GEMM (reduction over tags must be k-contiguous) -----
 // out[c][q] = in_row(q)[c] for q < n_q, 0 for n_q <= q < q_stride.  GATHER: in_row(q) is
 // [Hs[l[q]]; Hs[r[q]]], else row q of Dz.
-template <typename T, bool GATHER>
-__global__ void k_transpose(VecArgs v, Engine e, uint32_t n_q, int n_cols, T* out) {
+template <int DT, bool GATHER>
+__global__ void k_transpose(VecArgs v, Engine e, uint32_t n_q, int n_cols, void* out_) {
+  typedef typename TypeOf<DT>::type T;
+  T* out = reinterpret_cast<T*>(out_);
   __shared__ T tile[32][33];
   const uint32_t q0 = blockIdx.x * 32;
   const int c0 = blockIdx.y * 32;
@@ -478,8 +494,9 @@ __global__ void k_reduce_dw(VecArgs v, float* dW, int splits) {
 }
 
 // db[n] = sum_q Dz[q][n]: fixed chunks of 64 tags, partial sums combined in chunk order
-template <typename T>
+template <int DT>
 __global__ void k_db_partial(VecArgs v, uint32_t n_q, float* part) {
+  typedef typename TypeOf<DT>::type T;
   constexpr int CH = El<T>::CH;
   const uint32_t q_lo = blockIdx.x * 64, q_hi = min(n_q, q_lo + 64);
   for (int n = threadIdx.x * CH; n < v.Np; n += blockDim.x * CH) {
@@ -601,7 +618,7 @@ __global__ void k_de_final(VecArgs v, const uint32_t* chunk_off, const float* pa
 
 // ---- host entry points used by eval.hip ------------------------------------------------------
 template <typename T> static void pack_w_t(const VecArgs& v, hipStream_t s) {
-  hipLaunchKernelGGL(k_pack_w<T>, dim3(1024), dim3(256), 0, s, v);
+  hipLaunchKernelGGL(k_pack_w<DtOf<T>::value>, dim3(1024), dim3(256), 0, s, v);
 }
 void vec_pack_w(const VecArgs& v, hipStream_t s) {
   if (v.dtype == TDF_BF16) pack_w_t<__bf16>(v, s); else pack_w_t<float>(v, s);
@@ -610,8 +627,8 @@ void vec_pack_w(const VecArgs& v, hipStream_t s) {
 void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s) {
   if (!n_leaf) return;
   int blocks = (int)std::min<uint32_t>((n_leaf + 3) / 4, 8192u);
-  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_embed<__bf16>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
-  else hipLaunchKernelGGL(k_embed<float>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_embed<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
+  else hipLaunchKernelGGL(k_embed<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
 }
 
 template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count,
@@ -634,7 +651,7 @@ void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count
 
 template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s) {
   if (!count) return;
-  hipLaunchKernelGGL(k_dz<T>, dim3(count), dim3(256), 0, s, v, e, q0, count);
+  hipLaunchKernelGGL(k_dz<DtOf<T>::value>, dim3(count), dim3(256), 0, s, v, e, q0, count);
   GemmArgs g{};
   g.M = (int)count; g.N = v.Kp; g.K = v.Np;
   g.A = reinterpret_cast<const T*>(v.Dz) + (size_t)q0 * v.Np; g.lda = v.Np;
@@ -649,15 +666,15 @@ void vec_cell_bwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count
 
 void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s) {
   int blocks = ((int)e.n_inst + 3) / 4;
-  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_head<__bf16>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
-  else hipLaunchKernelGGL(k_head<float>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_head<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
+  else hipLaunchKernelGGL(k_head<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
 }
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s) {
   hipLaunchKernelGGL(k_seed_dy, dim3(e.n_inst), dim3(128), 0, s, v, e, dy);
 }
 void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s) {
-  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_out_rows<__bf16>, dim3(e.n_inst), dim3(128), 0, s, v, e, out_h, out_c);
-  else hipLaunchKernelGGL(k_out_rows<float>, dim3(e.n_inst), dim3(128), 0, s, v, e, out_h, out_c);
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_out_rows<TDF_BF16>, dim3(e.n_inst), dim3(128), 0, s, v, e, out_h, out_c);
+  else hipLaunchKernelGGL(k_out_rows<TDF_F32>, dim3(e.n_inst), dim3(128), 0, s, v, e, out_h, out_c);
 }
 
 int vec_dw_splits(uint32_t q_stride) {
@@ -669,10 +686,10 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
                                                  float* db_part, hipStream_t s) {
   // transposed copies so that the reduction over tags is k-contiguous for both operands
   dim3 tb(32, 8);
-  hipLaunchKernelGGL((k_transpose<T, false>), dim3(v.q_stride / 32, v.Np / 32), tb, 0, s, v, e, n_q, v.Np,
-                     reinterpret_cast<T*>(v.DzT));
-  hipLaunchKernelGGL((k_transpose<T, true>), dim3(v.q_stride / 32, v.Kp / 32), tb, 0, s, v, e, n_q, v.Kp,
-                     reinterpret_cast<T*>(v.XT));
+  hipLaunchKernelGGL((k_transpose<DtOf<T>::value, false>), dim3(v.q_stride / 32, v.Np / 32), tb, 0, s, v, e, n_q, v.Np,
+                     v.DzT);
+  hipLaunchKernelGGL((k_transpose<DtOf<T>::value, true>), dim3(v.q_stride / 32, v.Kp / 32), tb, 0, s, v, e, n_q, v.Kp,
+                     v.XT);
   const int splits = vec_dw_splits(v.q_stride);
   int kps = (int)((v.q_stride / 64 + splits - 1) / splits) * 64;
   GemmArgs g{};
@@ -684,7 +701,7 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   launch_gemm<T, DW_SPLIT>(g, (v.Kp + 127) / 128, splits, s);
   hipLaunchKernelGGL(k_reduce_dw, dim3(512), dim3(256), 0, s, v, dW, splits);
   const int parts = (int)((n_q + 63) / 64);
-  hipLaunchKernelGGL(k_db_partial<T>, dim3(parts), dim3(256), 0, s, v, n_q, db_part);
+  hipLaunchKernelGGL(k_db_partial<DtOf<T>::value>, dim3(parts), dim3(256), 0, s, v, n_q, db_part);
   hipLaunchKernelGGL(k_db_final, dim3(v.Np / 64), dim3(256), 0, s, v, db_part, parts, db);
 }
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {

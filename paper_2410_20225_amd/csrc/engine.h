@@ -11,7 +11,6 @@ namespace tdf {
 // Control block at the head of the workspace.  Counters are bumped with device-scope
 // atomics; everything else is ordered by kernel boundaries.
 struct Ctrl {
-  uint32_t q_count;          // tokens waiting for the next match step
   uint32_t touched_count[2]; // frames that received a token (double-buffered by step parity)
   uint32_t step;
   uint32_t n_rows;           // state rows handed out (leaves and cells share the row space)
@@ -27,25 +26,22 @@ struct Ctrl {
 
 // Frame record = one slot of the tag-hash table = one call-context tag (Section 5.1: a
 // frame holds the label i of the Call_i that created it and a reference to the previous
-// scope).  The key packs (parent frame + 1, label + 1); 0 means empty.  The slot index is
-// the frame id, so inserting a tag and allocating its frame are one compare-and-swap.
+// scope).  The key packs (parent frame + 1, tag length, label + 1); 0 means empty.  The slot
+// index is the frame id, so inserting a tag and allocating its frame are one compare-and-swap.
+//
+// Tokens delivered during step s set bits in arrived[(s+1)&1]; the sweep of step s+1 takes
+// that word (exchange with 0) and folds it into present_fn, which only the sweeping lane
+// writes.  Values delivered in one step are read in a later one, so only key, touched and
+// arrived[] are ever accessed concurrently and need atomics.
 struct FrameHdr {
-  unsigned long long key;
+  unsigned long long key;     // (parent + 1) << 32 | depth << 8 | (label + 1)
   unsigned long long fired;   // firing-table entries that have fired live under this tag
   uint32_t present_fn;        // bits 0..23: stored values present; bits 24..31: function
-  uint32_t touched;           // step+1 of the last step that delivered a token here
-  uint32_t depth;             // length of the tag (number of call labels)
-  uint32_t pad;
+  uint32_t touched;           // stamp of the last step that delivered a token here
+  uint32_t arrived[2];        // same layout as present_fn, by parity of the consuming step
   // followed by int64 stored[n_stored]
 };
 static_assert(sizeof(FrameHdr) == 32, "FrameHdr must be 32 bytes");
-
-struct Token {
-  uint32_t a;      // CALL: parent frame; RETURN: returning frame
-  uint32_t b;      // CALL: 0x80000000 | label | param << 8; RETURN: 0
-  long long value;
-};
-static_assert(sizeof(Token) == 16, "Token must be 16 bytes");
 
 // Pointers into the workspace and to the caller's buffers, passed to kernels by value.
 struct Engine {
@@ -53,9 +49,7 @@ struct Engine {
   unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
   char* frames;                     // (cap + B) records of frame_stride bytes
   uint32_t cap, cap_mask, n_inst, max_tags;
-  Token* queue;
-  uint32_t q_cap;
-  uint32_t* touched;
+  uint32_t* touched;                // two lists of touched_cap frame ids, by step parity
   uint32_t touched_cap;
   uint32_t step_limit;
   uint32_t small_limit;             // steps with at most this many touched frames run in one workgroup

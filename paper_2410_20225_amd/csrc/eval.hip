@@ -11,9 +11,10 @@
 namespace tdf {
 
 void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
-void launch_round(const DevProgram& P, const Engine& e, int max_values, int blocks, int small_block,
-                  int small_steps, hipStream_t s);
+void launch_round(const DevProgram& P, const Engine& e, int max_values, int max_stored, int blocks,
+                  int small_block, int small_steps, hipStream_t s);
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s);
+void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s);
 void vec_pack_w(const VecArgs& v, hipStream_t s);
 void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s);
 void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, int save_gates, hipStream_t s);
@@ -82,9 +83,6 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.cap = pow2_at_least(2ull * T);
   e.cap_mask = e.cap - 1;
   e.step_limit = in->step_limit > 0 ? (uint32_t)in->step_limit : (1u << 20);
-  int max_params = 1;
-  for (int f = 0; f < G.prog.n_fn; ++f) max_params = std::max<int>(max_params, G.prog.fn[f].n_params);
-  e.q_cap = T * (uint32_t)max_params + B;
   e.touched_cap = T + B;
   e.row_cap = P.vec ? T : 0;
   e.max_levels = e.row_cap;
@@ -105,8 +103,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));
   L.zero_end = L.total;
   // --- the rest is written before it is read
-  size_t off_queue = L.take(sizeof(Token) * (size_t)e.q_cap);
-  size_t off_touched = L.take(sizeof(uint32_t) * (size_t)e.touched_cap);
+  size_t off_touched = L.take(sizeof(uint32_t) * 2 * (size_t)e.touched_cap);
   size_t off_root = L.take(sizeof(uint32_t) * B);
   size_t off_hrow = L.take(sizeof(uint32_t) * B);
   size_t off_hlab = L.take(sizeof(uint32_t) * B);
@@ -122,7 +119,6 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.level_fill = (uint32_t*)at(off_lfill);
   e.level_off = (uint32_t*)at(off_loff);
   e.frames = at(P.off_frames);
-  e.queue = (Token*)at(off_queue);
   e.touched = (uint32_t*)at(off_touched);
   e.root_ref = (uint32_t*)at(off_root);
   e.head_row = (uint32_t*)at(off_hrow);
@@ -209,7 +205,7 @@ tdf_status status_from_device(uint32_t st) {
   if (st == 0) return TDF_OK;
   int code = -(int)st;
   switch (code) {
-    case TDF_ERR_TABLE_FULL: set_error("device: tag table, token queue or state rows exhausted (raise max_tags)"); break;
+    case TDF_ERR_TABLE_FULL: set_error("device: tag table, frame list or state rows exhausted (raise max_tags)"); break;
     case TDF_ERR_STEP_LIMIT: set_error("device: step limit reached before the recursion finished"); break;
     case TDF_ERR_BAD_ARG: set_error("device: tree node index or token id out of range"); break;
     default: set_error("device: unknown status"); code = TDF_ERR_DEVICE; break;
@@ -263,21 +259,24 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   launch_seed(G.prog, e, s);
 
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
-  int max_values = 1;
-  for (int f = 0; f < G.prog.n_fn; ++f) max_values = std::max<int>(max_values, G.prog.fn[f].n_values);
+  int max_values = 1, max_stored = 1;
+  for (int f = 0; f < G.prog.n_fn; ++f) {
+    max_values = std::max<int>(max_values, G.prog.fn[f].n_values);
+    max_stored = std::max<int>(max_stored, G.prog.fn[f].n_stored);
+  }
   const int blocks = 768;
-  const int small_block = max_values <= 32 ? 512 : 256;   // the value file must fit in LDS
+  const int small_block = max_values + max_stored <= 32 ? 512 : 128;   // the value file must fit in LDS
   e.small_limit = 2u * (uint32_t)small_block;
   Ctrl hc{};
   uint32_t rounds = 0;
   const uint32_t poll = 16;
   for (;;) {
-    for (uint32_t i = 0; i < poll; ++i, ++rounds) launch_round(G.prog, e, max_values, blocks, small_block, 64, s);
+    for (uint32_t i = 0; i < poll; ++i, ++rounds) launch_round(G.prog, e, max_values, max_stored, blocks, small_block, 64, s);
     HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (hc.done) break;
   }
-  end(TDF_PHASE_TAGS, 2 + 3ll * rounds);
+  end(TDF_PHASE_TAGS, 2 + 2ll * rounds);
   tdf_status dev = status_from_device(hc.status);
 
   std::vector<uint32_t> level_off;
@@ -355,6 +354,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->device_status = -(int32_t)hc.status;
     stats->n_counts = (int32_t)G.snodes.size();
     std::vector<unsigned long long> fc(TDF_STATS_MAX_COUNTS);
+    if (in->stats_level >= 1) {
+      launch_count_fired(G.prog, e, s);
+      HIP_TRY(hipStreamSynchronize(s));
+    }
     HIP_TRY(hipMemcpy(fc.data(), e.fire_count, sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS, hipMemcpyDeviceToHost));
     for (int i = 0; i < TDF_STATS_MAX_COUNTS; ++i) stats->fire_count[i] = (int64_t)fc[i];
   }

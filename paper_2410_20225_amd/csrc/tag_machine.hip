@@ -1,27 +1,67 @@
-// The tag machine: match tokens by call-context tag, compact the frames that received a
-// token, and fire the node bodies of every such frame at once.
+// The tag machine: tokens are matched by call-context tag, the frames that received a token
+// are compacted into a list, and the node bodies of every listed frame fire at once.
 //
-//   fire   one lane per touched frame walks the firing table of the frame's function; an
-//          entry fires when its sources are present under that tag (Section 2.2).  Call_i
-//          entries emit <i:t,d> tokens, the function output emits the Return token, vector
-//          operators append to the schedule log and yield a row reference.
-//   match  one lane per token.  Call tokens find-or-insert the key (parent frame, label) in
-//          the tag-hash table (Section 3: Call_i <t,d> = <i:t,d>; Section 5.1: a new frame
-//          that stores the label); Return tokens read the frame's key back, which is the
-//          label check of Return_i, and deliver the value to the caller's frame (Return_i
-//          <i:t,d> = <t,d>).  Frames that received a token are compacted into the touched
-//          list with wave ballots and one counter bump per wave.
+// One step = one pass over the touched list, one lane per frame (= per tag):
+//   fire    the lane walks the firing table of the frame's function; an entry fires when its
+//           sources are present under that tag (Section 2.2: all inputs hold tokens with the
+//           same tag).  Dead values (hiatons) propagate; Switch, Merge and dead calls follow
+//           the paper's equations.
+//   match   every token the sweep emits is delivered on the spot:
+//           Call_i  <t,d> -> <i:t,d>: find-or-insert the key (frame of t, i) in the tag-hash
+//                   table (Section 3; Section 5.1: a new frame that stores the label i), write
+//                   the argument into that frame;
+//           Return_i <i:t,d> -> <t,d>: the frame's own key names its label i and the frame of
+//                   t, which is the label check of Section 5.1 (only the Return_i of the call
+//                   that created the frame produces output); the value goes to the caller's
+//                   frame.
+//   compact the first token that reaches a frame in a step appends it to the next step's list
+//           (wave ballot + prefix sum, one counter bump per wave).
+//
+// A frame that is being swept may receive a token in the same step from another lane.  Such
+// a token sets a bit in the frame's arrival word of the *next* step and puts the frame on the
+// next list; the running sweep neither sees the bit nor reads the value.  Only the key, the
+// step stamp and the arrival words are written concurrently, with device-scope atomics.
 #include "engine.h"
 
 namespace tdf {
 
 namespace {
 
-constexpr int FIRE_BLOCK = 128;
-constexpr int MATCH_BLOCK = 256;
+constexpr int FIRE_BLOCK = 128;   // grid-wide kernel
 
 __device__ __forceinline__ void raise(Ctrl* c, int status) {
   atomicCAS(&c->status, 0u, (uint32_t)(-status));
+}
+
+template <typename T> __device__ __forceinline__ T ld(const T* p) { return __atomic_load_n(p, __ATOMIC_RELAXED); }
+template <typename T> __device__ __forceinline__ void st(T* p, T v) { __atomic_store_n(p, v, __ATOMIC_RELAXED); }
+
+// Atomics on frame words at the scope of the running kernel: device scope when the whole grid
+// works on a step, workgroup scope when a single workgroup does (its atomics then stay in the
+// local L2; kernel boundaries make them visible to whoever runs the next step).
+template <int SCOPE> __device__ __forceinline__ uint32_t a_or(uint32_t* p, uint32_t v) {
+  return __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, SCOPE);
+}
+template <int SCOPE> __device__ __forceinline__ uint32_t a_exch(uint32_t* p, uint32_t v) {
+  return __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, SCOPE);
+}
+template <int SCOPE> __device__ __forceinline__ unsigned long long a_cas(unsigned long long* p, unsigned long long expect,
+                                                                        unsigned long long v) {
+  __hip_atomic_compare_exchange_strong(p, &expect, v, __ATOMIC_RELAXED, __ATOMIC_RELAXED, SCOPE);
+  return expect;
+}
+template <int SCOPE> __device__ __forceinline__ unsigned long long a_ld(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE);
+}
+
+// fmix64 of MurmurHash3 (Appleby, public domain).
+__device__ __forceinline__ unsigned long long mix64(unsigned long long x) {
+  x ^= x >> 33;
+  x *= 0xff51afd7ed558ccdULL;
+  x ^= x >> 33;
+  x *= 0xc4ceb9fe1a85ec53ULL;
+  x ^= x >> 33;
+  return x;
 }
 
 // ---- seed: one root frame per instance, holding the arguments of `result` ---------------
@@ -36,61 +76,106 @@ __global__ void k_seed(DevProgram P, Engine e) {
   h->key = 0;
   h->fired = 0;
   h->present_fn = ((1u << np) - 1u) | ((uint32_t)P.result_fn << 24);
-  h->touched = 0;
-  h->depth = 0;
+  h->touched = 1;
+  h->arrived[0] = h->arrived[1] = 0;
   e.touched[b] = f;
   if (b == 0) e.ctrl->touched_count[0] = e.n_inst;
 }
 
-// ---- fire --------------------------------------------------------------------------------
 struct Src {
   long long v;
   bool p, d;   // present, dead
 };
 
-// One pass over the touched frames [0, n): lane `first + tid` takes frame i, i + stride, ...
-// regs is the block's value file in LDS, [value][lane of the block].
-__device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint32_t first, uint32_t stride,
-                          long long* regs) {
-  Ctrl* c = e.ctrl;
+// Deliver one value to slot `slot` of frame `target`, and put the frame on the next list if
+// this is the first token to reach it in this step.  Must be reached by the whole wave.
+template <int SCOPE>
+__device__ __forceinline__ void deliver(const Engine& e, Ctrl* c, int stride, bool go, uint32_t target,
+                                        uint32_t slot, long long value, uint32_t or_bits, uint32_t stamp,
+                                        uint32_t* next_list, uint32_t* next_count) {
+  bool first = false;
+  if (go) {
+    FrameHdr* h = frame_at(e, stride, target);
+    frame_slots(h)[slot] = value;                     // read in a later step only
+    a_or<SCOPE>(&h->arrived[stamp & 1], or_bits);     // stamp = consuming step + 1
+    first = a_exch<SCOPE>(&h->touched, stamp) != stamp;
+  }
+  const uint32_t pos = wave_alloc(first, next_count);
+  if (first) {
+    if (pos < e.touched_cap) next_list[pos] = target;
+    else raise(c, TDF_ERR_TABLE_FULL);
+  }
+}
+
+// One pass over the touched frames [0, n) of the current list; lane `first + tid` takes frames
+// i, i + lane_stride, ...  `lds` holds the block's value file [value][lane] followed by the
+// preloaded stored values [slot][lane].  `c` is the control block the pass counts in: the
+// global one, or a workgroup's LDS copy.
+template <int SCOPE>
+__device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_t step, uint32_t n,
+                          uint32_t first, uint32_t lane_stride, long long* lds, int max_values) {
   const int tid = threadIdx.x;
-  const int FIRE_BLOCK = blockDim.x;
-  for (uint32_t base = first; base < n; base += stride) {
+  const int RB = blockDim.x;
+  long long* regs = lds;
+  long long* stv = lds + (size_t)max_values * RB;
+  const int stride = P.frame_stride;
+  const uint32_t* cur_list = e.touched + (size_t)(step & 1) * e.touched_cap;
+  uint32_t* next_list = e.touched + (size_t)((step & 1) ^ 1) * e.touched_cap;
+  uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
+  const uint32_t stamp = step + 2;   // frames on the list of step s carry stamp s + 1
+  int n_st = 0;
+  for (int f = 0; f < P.n_fn; ++f) n_st = max(n_st, (int)P.fn[f].n_stored);
+
+  for (uint32_t base = first; base < n; base += lane_stride) {
     const uint32_t i = base + tid;
     const bool active = i < n;
-    const uint32_t frame = active ? e.touched[i] : 0;
-    FrameHdr* h = frame_at(e, P.frame_stride, frame);
+    const uint32_t frame = active ? cur_list[i] : 0;
+    FrameHdr* h = frame_at(e, stride, frame);
     long long* slots = frame_slots(h);
-    unsigned long long fired = 0;
-    uint32_t present = 0;
+    unsigned long long fired = 0, key = 0;
+    uint32_t present = 0, depth = 0;
     int myfn = -1;
+    uint32_t pf_in = 0;
     if (active) {
+      // tokens that arrived for this step; the word of the other parity belongs to the next
+      const uint32_t arr = a_exch<SCOPE>(&h->arrived[(step + 1) & 1], 0u);
+      pf_in = h->present_fn;
+      const uint32_t pf = pf_in | arr;
+      key = a_ld<SCOPE>(&h->key);
       fired = h->fired;
-      // present_fn is updated with atomics by the match pass: read it the same way
-      const uint32_t pf = __atomic_load_n(&h->present_fn, __ATOMIC_RELAXED);
+      depth = (uint32_t)(key >> 8) & 0xFFFFFFu;
       present = pf & 0xFFFFFFu;
       myfn = (int)(pf >> 24);
     }
     const unsigned long long fired_in = fired;
-    const uint32_t present_in = present;
+    // stored values, all loads in flight at once
+    for (int k0 = 0; k0 < n_st; k0 += 8) {
+      long long sv[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        sv[k] = (active && k0 + k < n_st && ((present >> (k0 + k)) & 1)) ? slots[k0 + k] : 0;
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (k0 + k < n_st) stv[(k0 + k) * RB + tid] = sv[k];
+    }
 
     for (int f = 0; f < P.n_fn; ++f) {
       const bool on = myfn == f;
       if (__ballot(on) == 0) continue;
-      const int first = P.fn[f].first, count = P.fn[f].count;
+      const int first_i = P.fn[f].first, count = P.fn[f].count;
       const bool is_result = f == P.result_fn;
       unsigned long long pres = 0, dead = 0;   // over value ids
 
       for (int ip = 0; ip < count; ++ip) {
-        const Instr I = P.instr[first + ip];
+        const Instr I = P.instr[first_i + ip];
         const unsigned long long ibit = 1ull << ip;
         auto src = [&](int k) -> Src {
           const uint8_t s = I.src[k];
           if (s == SRC_IMM) return Src{I.imm, true, false};
-          return Src{regs[(int)s * FIRE_BLOCK + tid], ((pres >> s) & 1) != 0, ((dead >> s) & 1) != 0};
+          return Src{regs[(int)s * RB + tid], ((pres >> s) & 1) != 0, ((dead >> s) & 1) != 0};
         };
         auto put = [&](int dst, long long v, bool p, bool d) {
-          regs[dst * FIRE_BLOCK + tid] = v;
+          regs[dst * RB + tid] = v;
           if (p) pres |= 1ull << dst;
           if (d) dead |= 1ull << dst;
         };
@@ -98,7 +183,7 @@ __device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint
         switch (I.op) {
           case D_IN: {
             const bool p = on && ((present >> I.aux) & 1);
-            put(I.dst, p ? slots[I.aux] : 0, p, false);
+            put(I.dst, stv[I.aux * RB + tid], p, false);
             live = p;
             break;
           }
@@ -112,7 +197,7 @@ __device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint
               any_d = any_d || ((dead >> I.src[k]) & 1);
             }
             const bool is_dead = on && !p && any_arg && all_p && any_d;   // the call never happened
-            put(I.dst, p ? slots[I.aux] : 0, p || is_dead, is_dead);
+            put(I.dst, stv[I.aux * RB + tid], p || is_dead, is_dead);
             live = p;
             break;
           }
@@ -181,14 +266,43 @@ __device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint
             break;
           }
           case D_CALL: {
+            // Call_i: <t,d> -> <i:t,d>.  The tag i:t is the key (this frame, i).
             const Src a = src(0);
             const bool go = on && a.p && !a.d && !(fired & ibit);
-            const uint32_t pos = wave_alloc(go, &c->q_count);
+            const uint32_t label = I.aux, param = I.aux2;
+            uint32_t child = 0, probes = 0;
+            bool found = false, inserted = false;
             if (go) {
-              if (pos < e.q_cap)
-                e.queue[pos] = Token{frame, 0x80000000u | I.aux | ((uint32_t)I.aux2 << 8), a.v};
-              else
-                raise(c, TDF_ERR_TABLE_FULL);
+              const unsigned long long ckey =
+                  ((unsigned long long)(frame + 1u) << 32) | ((unsigned long long)(depth + 1u) << 8) | (label + 1u);
+              uint32_t s = (uint32_t)mix64(ckey) & e.cap_mask;
+              const uint32_t probe_limit = e.cap < 8192u ? e.cap : 8192u;
+              for (probes = 1; probes <= probe_limit; ++probes) {
+                FrameHdr* ch = frame_at(e, stride, s);
+                unsigned long long cur = a_ld<SCOPE>(&ch->key);
+                if (cur == 0) {
+                  cur = a_cas<SCOPE>(&ch->key, 0ull, ckey);
+                  if (cur == 0) {
+                    inserted = found = true;
+                    break;
+                  }
+                }
+                if (cur == ckey) {
+                  found = true;
+                  break;
+                }
+                s = (s + 1) & e.cap_mask;
+              }
+              child = s;
+              if (!found) raise(c, TDF_ERR_TABLE_FULL);
+            }
+            deliver<SCOPE>(e, c, stride, go && found, child, param, a.v,
+                    (1u << param) | ((uint32_t)P.label_callee[label] << 24), stamp, next_list, next_count);
+            wave_count(inserted, &c->n_tags);
+            wave_count(go && found, &c->n_tokens);
+            if (__ballot(inserted)) {
+              wave_max(inserted ? probes : 0, &c->max_probe);
+              wave_max(inserted ? depth + 1 : 0, &c->max_depth);
             }
             live = on && a.p && !a.d;
             break;
@@ -203,11 +317,11 @@ __device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint
                 else if (I.aux == T_VEC) e.root_ref[b] = (uint32_t)a.v;
               }
             } else {
-              const uint32_t pos = wave_alloc(go, &c->q_count);
-              if (go) {
-                if (pos < e.q_cap) e.queue[pos] = Token{frame, 0u, a.v};
-                else raise(c, TDF_ERR_TABLE_FULL);
-              }
+              // Return_i: <i:t,d> -> <t,d>; i and the frame of t are in this frame's key
+              const uint32_t parent = (uint32_t)(key >> 32) - 1u, label = ((uint32_t)key & 0xFFu) - 1u;
+              const uint32_t slot = go ? P.label_ret_slot[label] : 0;
+              deliver<SCOPE>(e, c, stride, go, parent, slot, a.v, 1u << slot, stamp, next_list, next_count);
+              wave_count(go, &c->n_tokens);
             }
             live = on && a.p && !a.d;
             break;
@@ -218,7 +332,7 @@ __device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint
             const bool go = on && a.p && !a.d && !had;
             const uint32_t idx = wave_alloc(go, &c->n_leaf);
             const uint32_t row = wave_alloc(go, &c->n_rows);
-            long long r = had ? slots[I.aux] : 0;
+            long long r = stv[I.aux * RB + tid];
             bool ok = go;
             if (go) {
               if (row < e.row_cap && idx < e.row_cap && a.v >= 0) {
@@ -242,7 +356,7 @@ __device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint
             const bool go = on && a.p && b.p && !a.d && !b.d && !had;
             const uint32_t j = wave_alloc(go, &c->n_cell);
             const uint32_t row = wave_alloc(go, &c->n_rows);
-            long long r = had ? slots[I.aux] : 0;
+            long long r = stv[I.aux * RB + tid];
             bool ok = go;
             uint32_t lvl = 0;
             if (go) {
@@ -278,146 +392,52 @@ __device__ void fire_pass(const DevProgram& P, const Engine& e, uint32_t n, uint
               present |= 1u << I.aux;
             }
             (void)wave_alloc(go, &c->n_head);
-            put(I.dst, had ? slots[I.aux] : (long long)(frame - e.cap), had || go, false);
+            put(I.dst, (long long)(frame - e.cap), had || go, false);
             live = had || go;
             break;
           }
           default: break;
         }
-        // live firings per static-graph node: counted the first time the entry is live
-        const bool first_time = live && !(fired & ibit);
-        if (first_time) fired |= ibit;
-        const uint16_t st = P.stat_idx[first + ip];
-        if (st != 0xFFFF) wave_count(first_time, &e.fire_count[st]);
+        if (live) fired |= ibit;   // counted after the run, from the fired masks
       }
     }
-    if (active && (fired != fired_in || present != present_in)) {
-      h->fired = fired;
-      if (present != present_in) atomicOr(&h->present_fn, present & ~present_in);
+    if (active) {
+      if (fired != fired_in) h->fired = fired;
+      const uint32_t pf_out = present | ((uint32_t)myfn << 24);
+      if (pf_out != pf_in) h->present_fn = pf_out;
     }
   }
 }
 
-// A step is "small" when its touched frames fit a few passes of one workgroup; small steps
-// run in k_steps_small, the others in the grid-wide k_fire / k_match pair.
-__device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
-
-__global__ void k_fire(DevProgram P, Engine e) {
-  extern __shared__ long long regs[];
-  Ctrl* c = e.ctrl;
-  const uint32_t n = __atomic_load_n(&c->touched_count[c->step & 1], __ATOMIC_RELAXED);
-  if (c->done || n == 0 || step_is_small(e, n)) return;
-  fire_pass(P, e, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, regs);
-}
-
-// ---- step bookkeeping: reset the consumed lists, count the step, detect the end -------------
-__device__ void advance(const Engine& e, int parity) {
-  Ctrl* c = e.ctrl;
-  const uint32_t next = __atomic_load_n(&c->touched_count[parity ^ 1], __ATOMIC_RELAXED);
-  const unsigned long long n_tags = __atomic_load_n(&c->n_tags, __ATOMIC_RELAXED);
-  uint32_t status = __atomic_load_n(&c->status, __ATOMIC_RELAXED);
-  __atomic_store_n(&c->q_count, 0u, __ATOMIC_RELAXED);
-  __atomic_store_n(&c->touched_count[parity], 0u, __ATOMIC_RELAXED);
-  c->step += 1;
-  if (n_tags > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
-  if (c->step >= e.step_limit && next != 0 && status == 0) status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
+// ---- step bookkeeping: reset the consumed list, count the step, detect the end ---------------
+__device__ void advance(const Engine& e, Ctrl* c, uint32_t step) {
+  const int parity = (int)(step & 1);
+  const uint32_t next = ld(&c->touched_count[parity ^ 1]);
+  uint32_t status = ld(&c->status);
+  st(&c->touched_count[parity], 0u);
+  c->step = step + 1;
+  if (ld(&c->n_tags) > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
+  if (step + 1 >= e.step_limit && next != 0 && status == 0) status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
   if (status != 0) {
-    __atomic_store_n(&c->status, status, __ATOMIC_RELAXED);
-    __atomic_store_n(&c->touched_count[parity ^ 1], 0u, __ATOMIC_RELAXED);   // drain: nothing more fires
+    st(&c->status, status);
+    st(&c->touched_count[parity ^ 1], 0u);   // drain: nothing more fires
     c->done = 1;
   } else if (next == 0) {
     c->done = 1;
   }
 }
 
-// ---- match -------------------------------------------------------------------------------
-// One pass over the tokens [0, n) of the queue.
-__device__ void match_pass(const DevProgram& P, const Engine& e, int parity, uint32_t n, uint32_t stamp,
-                           uint32_t first, uint32_t lane_stride) {
-  Ctrl* c = e.ctrl;
-  const int stride = P.frame_stride;
-  for (uint32_t base = first; base < n; base += lane_stride) {
-    const uint32_t i = base + threadIdx.x;
-    const bool active = i < n;
-    bool inserted = false, deliver = false;
-    uint32_t target = 0, probes = 0, depth = 0;
-    if (active) {
-      const Token t = e.queue[i];
-      if (t.b & 0x80000000u) {
-        // Call_i: <t,d> -> <i:t,d>.  The tag i:t is the key (frame of t, i).
-        const uint32_t label = t.b & 0xFFu, param = (t.b >> 8) & 0xFFu;
-        const unsigned long long key = ((unsigned long long)(t.a + 1u) << 32) | (label + 1u);
-        uint32_t s = (uint32_t)mix64(key) & e.cap_mask;
-        bool found = false;
-        const uint32_t probe_limit = e.cap < 8192u ? e.cap : 8192u;
-        for (probes = 1; probes <= probe_limit; ++probes) {
-          FrameHdr* h = frame_at(e, stride, s);
-          unsigned long long cur = __atomic_load_n(&h->key, __ATOMIC_RELAXED);
-          if (cur == 0) {
-            cur = atomicCAS(&h->key, 0ull, key);
-            if (cur == 0) {
-              inserted = found = true;
-              break;
-            }
-          }
-          if (cur == key) {
-            found = true;
-            break;
-          }
-          s = (s + 1) & e.cap_mask;
-        }
-        if (found) {
-          FrameHdr* h = frame_at(e, stride, s);
-          const uint32_t fn = P.label_callee[label];
-          if (inserted) {
-            depth = frame_at(e, stride, t.a)->depth + 1;
-            h->depth = depth;
-          }
-          frame_slots(h)[param] = t.value;
-          atomicOr(&h->present_fn, (1u << param) | (fn << 24));
-          target = s;
-          deliver = true;
-        } else {
-          raise(c, TDF_ERR_TABLE_FULL);
-        }
-      } else {
-        // Return_i: <i:t,d> -> <t,d>.  The frame's own key names its label i and the frame
-        // of t, so only the Return_i of the call that created the frame produces output.
-        const unsigned long long key = __atomic_load_n(&frame_at(e, stride, t.a)->key, __ATOMIC_RELAXED);
-        const uint32_t parent = (uint32_t)(key >> 32) - 1u, label = (uint32_t)key - 1u;
-        FrameHdr* h = frame_at(e, stride, parent);
-        const uint32_t slot = P.label_ret_slot[label];
-        frame_slots(h)[slot] = t.value;
-        atomicOr(&h->present_fn, 1u << slot);
-        target = parent;
-        deliver = true;
-      }
-    }
-    // ready-frame compaction: the first token to reach a frame in this step appends it
-    bool first = false;
-    if (deliver) first = atomicExch(&frame_at(e, stride, target)->touched, stamp) != stamp;
-    const uint32_t pos = wave_alloc(first, &c->touched_count[parity ^ 1]);
-    if (first) {
-      if (pos < e.touched_cap) e.touched[pos] = target;
-      else raise(c, TDF_ERR_TABLE_FULL);
-    }
-    wave_count(inserted, &c->n_tags);
-    wave_count(active, &c->n_tokens);
-    if (__ballot(inserted)) {
-      wave_max(inserted ? probes : 0, &c->max_probe);
-      wave_max(depth, &c->max_depth);
-    }
-  }
-}
+// A step is "small" when its frames fit two passes of one workgroup; small steps run in
+// k_steps_small, the others in the grid-wide k_step.
+__device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
 
-__global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e) {
+__global__ void __launch_bounds__(FIRE_BLOCK) k_step(DevProgram P, Engine e, int max_values) {
+  extern __shared__ long long lds[];
   Ctrl* c = e.ctrl;
   const uint32_t step = c->step;
-  const int parity = (int)(step & 1);
-  const uint32_t n_touched = __atomic_load_n(&c->touched_count[parity], __ATOMIC_RELAXED);
-  if (c->done || n_touched == 0 || step_is_small(e, n_touched)) return;   // same test as k_fire
-  const uint32_t n = __atomic_load_n(&c->q_count, __ATOMIC_RELAXED);
-  match_pass(P, e, parity, n, step + 1, blockIdx.x * blockDim.x, gridDim.x * blockDim.x);
+  const uint32_t n = ld(&c->touched_count[step & 1]);
+  if (c->done || n == 0 || step_is_small(e, n)) return;
+  step_pass<__HIP_MEMORY_SCOPE_AGENT>(P, e, c, step, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, lds, max_values);
   // the last workgroup to finish closes the step
   __shared__ bool last;
   __syncthreads();
@@ -428,42 +448,89 @@ __global__ void __launch_bounds__(MATCH_BLOCK) k_match(DevProgram P, Engine e) {
   __syncthreads();
   if (last && threadIdx.x == 0) {
     __threadfence();
-    __atomic_store_n(&c->blocks_done, 0u, __ATOMIC_RELAXED);
-    advance(e, parity);
+    st(&c->blocks_done, 0u);
+    advance(e, c, step);
   }
 }
 
-// Small steps: one workgroup runs fire and match back to back, step after step, with workgroup
-// barriers only.  Returns when the recursion is finished, when a step is too large for one
-// workgroup, or after max_steps steps.
-__global__ void k_steps_small(DevProgram P, Engine e, int max_steps) {
-  extern __shared__ long long regs[];
-  __shared__ uint32_t sh[3];
-  Ctrl* c = e.ctrl;
+// Small steps: one workgroup runs step after step with workgroup barriers only and keeps the
+// control block (all list and log counters) in LDS.  Returns when the recursion is finished,
+// when a step is too large for one workgroup, or after max_steps steps.
+__global__ void k_steps_small(DevProgram P, Engine e, int max_values, int max_steps) {
+  extern __shared__ long long lds[];
+  __shared__ Ctrl lc;
+  Ctrl* g = e.ctrl;
+  if (threadIdx.x == 0) {
+    lc.touched_count[0] = ld(&g->touched_count[0]);
+    lc.touched_count[1] = ld(&g->touched_count[1]);
+    lc.step = g->step;
+    lc.n_rows = ld(&g->n_rows);
+    lc.n_leaf = ld(&g->n_leaf);
+    lc.n_cell = ld(&g->n_cell);
+    lc.n_head = ld(&g->n_head);
+    lc.status = ld(&g->status);
+    lc.done = g->done;
+    lc.max_probe = ld(&g->max_probe);
+    lc.max_depth = ld(&g->max_depth);
+    lc.max_level = ld(&g->max_level);
+    lc.blocks_done = 0;
+    lc.n_tags = ld(&g->n_tags);
+    lc.n_tokens = ld(&g->n_tokens);
+  }
+  __syncthreads();
   for (int it = 0; it < max_steps; ++it) {
-    if (threadIdx.x == 0) {
-      const uint32_t step = c->step;
-      sh[0] = step;
-      sh[1] = __atomic_load_n(&c->touched_count[step & 1], __ATOMIC_RELAXED);
-      sh[2] = c->done;
-    }
+    const uint32_t step = lc.step;
+    const uint32_t n = lc.touched_count[step & 1];
+    const bool stop = lc.done || n == 0 || !step_is_small(e, n);
     __syncthreads();
-    const uint32_t step = sh[0], n = sh[1], stop = sh[2];
+    if (stop) break;
+    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP>(P, e, &lc, step, n, 0, blockDim.x, lds, max_values);
     __syncthreads();
-    if (stop || n == 0 || !step_is_small(e, n)) return;
-    const int parity = (int)(step & 1);
-    fire_pass(P, e, n, 0, blockDim.x, regs);
-    __threadfence();
+    if (threadIdx.x == 0) advance(e, &lc, step);
     __syncthreads();
-    const uint32_t qn = __atomic_load_n(&c->q_count, __ATOMIC_RELAXED);
-    match_pass(P, e, parity, qn, step + 1, 0, blockDim.x);
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) advance(e, parity);
-    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    st(&g->touched_count[0], lc.touched_count[0]);
+    st(&g->touched_count[1], lc.touched_count[1]);
+    g->step = lc.step;
+    st(&g->n_rows, lc.n_rows);
+    st(&g->n_leaf, lc.n_leaf);
+    st(&g->n_cell, lc.n_cell);
+    st(&g->n_head, lc.n_head);
+    st(&g->status, lc.status);
+    g->done = lc.done;
+    st(&g->max_probe, lc.max_probe);
+    st(&g->max_depth, lc.max_depth);
+    st(&g->max_level, lc.max_level);
+    st(&g->n_tags, lc.n_tags);
+    st(&g->n_tokens, lc.n_tokens);
   }
 }
 
+// ---- statistics: live firings per static-graph node, counted from the fired masks -------------
+__global__ void k_count_fired(DevProgram P, Engine e) {
+  __shared__ uint32_t cnt[MAX_INSTR];
+  for (int i = threadIdx.x; i < MAX_INSTR; i += blockDim.x) cnt[i] = 0;
+  __syncthreads();
+  const uint32_t total = e.cap + e.n_inst;
+  for (uint32_t f = blockIdx.x * blockDim.x + threadIdx.x; f < total; f += gridDim.x * blockDim.x) {
+    const FrameHdr* h = frame_at(e, P.frame_stride, f);
+    unsigned long long fired = h->fired;
+    if (fired == 0) continue;
+    const int fn = (int)(h->present_fn >> 24);
+    const int first = P.fn[fn].first;
+    while (fired) {
+      const int ip = __ffsll((long long)fired) - 1;
+      fired &= fired - 1;
+      atomicAdd(&cnt[first + ip], 1u);
+    }
+  }
+  __syncthreads();
+  for (int i = threadIdx.x; i < MAX_INSTR; i += blockDim.x) {
+    const uint16_t st_idx = P.stat_idx[i];
+    if (cnt[i] && st_idx != 0xFFFF) atomicAdd(&e.fire_count[st_idx], (unsigned long long)cnt[i]);
+  }
+}
 
 // ---- cells by dependency level --------------------------------------------------------------
 // A cell's level is 1 + the larger level of its two operands (leaves are level 0); cells of
@@ -533,15 +600,19 @@ void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s) {
 // One round of the tag machine: as many small steps as fit (one workgroup), then one
 // grid-wide step if the next step is large.  Each kernel decides on the device whether the
 // current step is its own.
-void launch_round(const DevProgram& P, const Engine& e, int max_values, int blocks, int small_block,
-                  int small_steps, hipStream_t s) {
-  const size_t small_lds = (size_t)max_values * small_block * sizeof(long long);
+void launch_round(const DevProgram& P, const Engine& e, int max_values, int max_stored, int blocks,
+                  int small_block, int small_steps, hipStream_t s) {
+  const size_t per_lane = (size_t)(max_values + max_stored) * sizeof(long long);
+  const size_t small_lds = per_lane * small_block;
   if (small_lds > 48 * 1024)   // large value files need the LDS opt-in
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_small),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds);
-  hipLaunchKernelGGL(k_steps_small, dim3(1), dim3(small_block), small_lds, s, P, e, small_steps);
-  hipLaunchKernelGGL(k_fire, dim3(blocks), dim3(FIRE_BLOCK), (size_t)max_values * FIRE_BLOCK * sizeof(long long), s, P, e);
-  hipLaunchKernelGGL(k_match, dim3(blocks), dim3(MATCH_BLOCK), 0, s, P, e);
+  hipLaunchKernelGGL(k_steps_small, dim3(1), dim3(small_block), small_lds, s, P, e, max_values, small_steps);
+  hipLaunchKernelGGL(k_step, dim3(blocks), dim3(FIRE_BLOCK), per_lane * FIRE_BLOCK, s, P, e, max_values);
+}
+
+void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s) {
+  hipLaunchKernelGGL(k_count_fired, dim3(grid_for(e.cap + e.n_inst, 256, 1024)), dim3(256), 0, s, P, e);
 }
 
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s) {

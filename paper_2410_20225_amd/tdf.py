@@ -66,7 +66,7 @@ class Inputs(C.Structure):
                 ("dtype", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32),
                 ("E", C.c_void_p), ("W", C.c_void_p), ("b", C.c_void_p),
                 ("n_classes", C.c_int32), ("U", C.c_void_p), ("u0", C.c_void_p),
-                ("max_tags", C.c_int64), ("step_limit", C.c_int32)]
+                ("max_tags", C.c_int64), ("step_limit", C.c_int32), ("stats_level", C.c_int32)]
 
 
 class Outputs(C.Structure):
@@ -170,10 +170,10 @@ def graph_info(graph):
 
 
 def make_inputs(n_instances, args=None, n_args=0, left=None, right=None, token=None, dtype=F32, hidden=0,
-                vocab=0, E=None, W=None, b=None, U=None, u0=None, n_classes=0, max_tags=0, step_limit=0):
+                vocab=0, E=None, W=None, b=None, U=None, u0=None, n_classes=0, max_tags=0, step_limit=0, stats_level=1):
     n_tree = 0 if left is None else int(left.numel())
     return Inputs(n_instances, n_args, _ptr(args), n_tree, _ptr(left), _ptr(right), _ptr(token), dtype, hidden,
-                  vocab, _ptr(E), _ptr(W), _ptr(b), n_classes, _ptr(U), _ptr(u0), max_tags, step_limit)
+                  vocab, _ptr(E), _ptr(W), _ptr(b), n_classes, _ptr(U), _ptr(u0), max_tags, step_limit, stats_level)
 
 
 def workspace_size(graph, inputs, with_grad=False):

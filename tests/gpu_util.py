@@ -40,7 +40,7 @@ def run_oracle_tree(c, head, grad, dy=None):
 class TreeRun:
     """One workload resident on the GPU plus the buffers of one evaluation."""
 
-    def __init__(self, c, head, grad, max_tags=None, step_limit=0):
+    def __init__(self, c, head, grad, max_tags=None, step_limit=0, stats_level=1):
         F = c["forest"]
         self.c, self.head, self.grad = c, head, grad
         self.B, self.H = F.n_trees, c["H"]
@@ -59,7 +59,7 @@ class TreeRun:
                                       right=self.t_right, token=self.t_token,
                                       dtype=tdf.BF16 if c["bf16"] else tdf.F32, hidden=self.H, vocab=c["V"],
                                       E=self.t_E, W=self.t_W, b=self.t_b, U=self.t_U, u0=self.t_u0,
-                                      n_classes=5, max_tags=self.max_tags, step_limit=step_limit)
+                                      n_classes=5, max_tags=self.max_tags, step_limit=step_limit, stats_level=stats_level)
         nbytes = tdf.workspace_size(self.graph, self.inputs, grad)
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
         self.out_f32 = torch.zeros(self.B, dtype=torch.float32, device=DEV)
