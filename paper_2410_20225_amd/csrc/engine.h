@@ -13,7 +13,6 @@ namespace tdf {
 struct Ctrl {
   uint32_t touched_count[2]; // frames that received a token (double-buffered by step parity)
   uint32_t step;
-  uint32_t n_rows;           // state rows handed out (leaves and cells share the row space)
   uint32_t n_leaf;           // EMBED firings
   uint32_t n_cell;           // cell firings
   uint32_t n_head;           // CE_HEAD firings
@@ -61,8 +60,9 @@ struct Engine {
   int32_t n_args;
   long long* out_i64;
   uint32_t* root_ref;               // [B] row of the vector result of instance b
-  // schedule log written by the fire kernel
-  uint32_t row_cap;                 // state rows available
+  // schedule log written by the step kernels; a vector value lives in the state row of the
+  // frame that produced it (row id = frame id)
+  uint32_t log_cap;                 // entries of the leaf / cell logs (0: no vector operators)
   uint32_t *leaf_row, *leaf_tok;    // [n_leaf]
   uint32_t *cell_out, *cell_l, *cell_r, *cell_lvl;   // [n_cell], in firing order
   uint32_t *head_row, *head_label;  // [B]
@@ -152,13 +152,13 @@ struct VecArgs {
   const void* W;
   const float* b;
   const float *U, *u0;
-  void* Hs;         // state rows [row_cap x Hp], dtype
-  float* Cs;        // LSTM cell state [row_cap x Hp]
+  void* Hs;         // state rows [(cap + B) x Hp], dtype, indexed by frame id
+  float* Cs;        // LSTM cell state [(cap + B) x Hp]
   void* Wp;         // packed W [Np x Kp], dtype (k contiguous)
   float* bp;        // [Np]
   // gradient side
-  float* dH;        // [row_cap x Hp]
-  float* dC;        // [row_cap x Hp]
+  float* dH;        // [(cap + B) x Hp]
+  float* dC;        // [(cap + B) x Hp]
   void* gates;      // LSTM activations (i,f_l,f_r,o,u) [n_cell x Np], dtype, by level order q
   void* Dz;         // pre-activation gradients [n_cell x Np], dtype, by q
   void* DzT;        // [Np x q_stride]

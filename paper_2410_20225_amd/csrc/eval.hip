@@ -11,8 +11,8 @@
 namespace tdf {
 
 void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
-void launch_round(const DevProgram& P, const Engine& e, int max_values, int max_stored, int blocks,
-                  int small_block, int small_steps, hipStream_t s);
+void launch_round(const DevProgram& P, const Engine& e, int blocks, int small_block, int small_steps, hipStream_t s);
+int tag_machine_small_block(const DevProgram& P);
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s);
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s);
 void vec_pack_w(const VecArgs& v, hipStream_t s);
@@ -84,9 +84,9 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.cap_mask = e.cap - 1;
   e.step_limit = in->step_limit > 0 ? (uint32_t)in->step_limit : (1u << 20);
   e.touched_cap = T + B;
-  e.row_cap = P.vec ? T : 0;
-  e.max_levels = e.row_cap;
-  P.max_cells = e.row_cap;
+  e.log_cap = P.vec ? T : 0;
+  e.max_levels = e.log_cap;
+  P.max_cells = e.log_cap;
 
   auto at = [&](size_t off) { return base ? base + off : nullptr; };
   // --- cleared region: control block, counters, level histograms, token histograms, frames
@@ -108,7 +108,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_hrow = L.take(sizeof(uint32_t) * B);
   size_t off_hlab = L.take(sizeof(uint32_t) * B);
   size_t off_loff = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
-  size_t rc = std::max<size_t>(e.row_cap, 1);
+  size_t rc = std::max<size_t>(e.log_cap, 1);
   size_t off_leaf_row = L.take(4 * rc), off_leaf_tok = L.take(4 * rc);
   size_t off_c_out = L.take(4 * rc), off_c_l = L.take(4 * rc), off_c_r = L.take(4 * rc), off_c_lvl = L.take(4 * rc);
   size_t off_q_out = L.take(4 * rc), off_q_l = L.take(4 * rc), off_q_r = L.take(4 * rc);
@@ -153,7 +153,8 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.n_classes = in->n_classes;
     v.E = in->E; v.W = in->W; v.b = in->b; v.U = in->U; v.u0 = in->u0;
     const size_t el = in->dtype == TDF_BF16 ? 2 : 4;
-    const size_t R = e.row_cap;
+    const size_t R = (size_t)e.cap + B;   // one state row per frame
+    if (R * (size_t)((in->hidden + 63) / 64 * 64) >= (1ull << 32)) { set_error("max_tags x hidden too large for 32-bit row offsets"); return TDF_ERR_BAD_ARG; }
     size_t off_Hs = L.take(R * v.Hp * el);
     size_t off_Cs = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
     size_t off_Wp = L.take((size_t)v.Np * v.Kp * el);
@@ -178,7 +179,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       P.off_seg_off = L.take(4 * ((size_t)v.vocab + 2));
       P.off_chunk_off = L.take(4 * ((size_t)v.vocab + 2));
       P.off_sorted = L.take(4 * rc);
-      P.off_de_part = L.take(((size_t)R / DE_CHUNK + v.vocab + 2) * v.Hp * 4);
+      P.off_de_part = L.take(((size_t)e.log_cap / DE_CHUNK + v.vocab + 2) * v.Hp * 4);
       v.dH = (float*)at(off_dH);
       v.dC = G.cell_kind == 2 ? (float*)at(off_dC) : nullptr;
       v.gates = G.cell_kind == 2 ? at(off_gates) : nullptr;
@@ -259,19 +260,14 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   launch_seed(G.prog, e, s);
 
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
-  int max_values = 1, max_stored = 1;
-  for (int f = 0; f < G.prog.n_fn; ++f) {
-    max_values = std::max<int>(max_values, G.prog.fn[f].n_values);
-    max_stored = std::max<int>(max_stored, G.prog.fn[f].n_stored);
-  }
   const int blocks = 768;
-  const int small_block = max_values + max_stored <= 32 ? 512 : 128;   // the value file must fit in LDS
+  const int small_block = tag_machine_small_block(G.prog);
   e.small_limit = 2u * (uint32_t)small_block;
   Ctrl hc{};
   uint32_t rounds = 0;
   const uint32_t poll = 16;
   for (;;) {
-    for (uint32_t i = 0; i < poll; ++i, ++rounds) launch_round(G.prog, e, max_values, max_stored, blocks, small_block, 64, s);
+    for (uint32_t i = 0; i < poll; ++i, ++rounds) launch_round(G.prog, e, blocks, small_block, 64, s);
     HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (hc.done) break;

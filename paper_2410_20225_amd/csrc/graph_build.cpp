@@ -450,6 +450,9 @@ struct Builder {
       D.fn[f].n_stored = (uint8_t)n_stored;
       D.fn[f].out_type = (uint8_t)ret_type[f];
       D.fn[f].n_params = (uint8_t)fn.n_params;
+      int n_emit = 0;
+      for (int q = first; q < n_instr; ++q) n_emit += D.instr[q].op == D_CALL || D.instr[q].op == D_OUT;
+      D.fn[f].n_emit = (uint8_t)n_emit;
       if (n_stored > max_stored) max_stored = n_stored;
     }
     D.frame_stride = (32 + 8 * max_stored + 31) / 32 * 32;

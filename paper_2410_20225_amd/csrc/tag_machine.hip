@@ -87,12 +87,38 @@ struct Src {
   bool p, d;   // present, dead
 };
 
-// Deliver one value to slot `slot` of frame `target`, and put the frame on the next list if
+// Per-workgroup staging of one pass.  Lanes take positions in these LDS lists with wave ballots;
+// the workgroup reserves its ranges of the global lists with one atomic per list when the pass
+// ends and copies the entries out.
+struct Stage {
+  uint32_t n_touched, n_leaf, n_cell, n_head, n_tags, n_tokens;
+  uint32_t max_probe, max_depth, max_level;
+  uint32_t base_touched, base_leaf, base_cell;
+};
+
+struct Sizes {
+  int max_values, max_stored, max_emit;
+};
+__host__ __device__ inline Sizes sizes_of(const DevProgram& P) {
+  Sizes z{1, 1, 1};
+  for (int f = 0; f < P.n_fn; ++f) {
+    z.max_values = z.max_values > P.fn[f].n_values ? z.max_values : P.fn[f].n_values;
+    z.max_stored = z.max_stored > P.fn[f].n_stored ? z.max_stored : P.fn[f].n_stored;
+    z.max_emit = z.max_emit > P.fn[f].n_emit ? z.max_emit : P.fn[f].n_emit;
+  }
+  return z;
+}
+// dynamic LDS of a step kernel with `rb` lanes
+__host__ __device__ inline size_t step_lds_bytes(const Sizes& z, int rb) {
+  return (size_t)rb * ((size_t)(z.max_values + z.max_stored) * 8 + (size_t)z.max_emit * 4 + 8 + 16) + sizeof(Stage);
+}
+
+// Deliver one value to slot `slot` of frame `target`, and stage the frame for the next list if
 // this is the first token to reach it in this step.  Must be reached by the whole wave.
 template <int SCOPE>
-__device__ __forceinline__ void deliver(const Engine& e, Ctrl* c, int stride, bool go, uint32_t target,
-                                        uint32_t slot, long long value, uint32_t or_bits, uint32_t stamp,
-                                        uint32_t* next_list, uint32_t* next_count) {
+__device__ __forceinline__ void deliver(const Engine& e, int stride, bool go, uint32_t target, uint32_t slot,
+                                        long long value, uint32_t or_bits, uint32_t stamp, Stage* S,
+                                        uint32_t* stg_touched) {
   bool first = false;
   if (go) {
     FrameHdr* h = frame_at(e, stride, target);
@@ -100,64 +126,67 @@ __device__ __forceinline__ void deliver(const Engine& e, Ctrl* c, int stride, bo
     a_or<SCOPE>(&h->arrived[stamp & 1], or_bits);     // stamp = consuming step + 1
     first = a_exch<SCOPE>(&h->touched, stamp) != stamp;
   }
-  const uint32_t pos = wave_alloc(first, next_count);
-  if (first) {
-    if (pos < e.touched_cap) next_list[pos] = target;
-    else raise(c, TDF_ERR_TABLE_FULL);
-  }
+  const uint32_t pos = wave_alloc(first, &S->n_touched);
+  if (first) stg_touched[pos] = target;
 }
 
 // One pass over the touched frames [0, n) of the current list; lane `first + tid` takes frames
-// i, i + lane_stride, ...  `lds` holds the block's value file [value][lane] followed by the
-// preloaded stored values [slot][lane].  `c` is the control block the pass counts in: the
-// global one, or a workgroup's LDS copy.
+// i, i + lane_stride, ...  `c` is the control block the pass counts in: the global one, or a
+// workgroup's LDS copy.  The loop over passes is uniform for the workgroup.
 template <int SCOPE>
 __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_t step, uint32_t n,
-                          uint32_t first, uint32_t lane_stride, long long* lds, int max_values) {
+                          uint32_t first, uint32_t lane_stride, char* lds) {
   const int tid = threadIdx.x;
   const int RB = blockDim.x;
-  long long* regs = lds;
-  long long* stv = lds + (size_t)max_values * RB;
+  const Sizes z = sizes_of(P);
+  long long* regs = reinterpret_cast<long long*>(lds);                 // [value][lane]
+  long long* stv = regs + (size_t)z.max_values * RB;                   // [stored slot][lane]
+  uint4* stg_cell = reinterpret_cast<uint4*>(stv + (size_t)z.max_stored * RB);
+  uint2* stg_leaf = reinterpret_cast<uint2*>(stg_cell + RB);
+  uint32_t* stg_touched = reinterpret_cast<uint32_t*>(stg_leaf + RB);  // [max_emit * RB]
+  Stage* S = reinterpret_cast<Stage*>(stg_touched + (size_t)z.max_emit * RB);
   const int stride = P.frame_stride;
   const uint32_t* cur_list = e.touched + (size_t)(step & 1) * e.touched_cap;
   uint32_t* next_list = e.touched + (size_t)((step & 1) ^ 1) * e.touched_cap;
   uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
   const uint32_t stamp = step + 2;   // frames on the list of step s carry stamp s + 1
-  int n_st = 0;
-  for (int f = 0; f < P.n_fn; ++f) n_st = max(n_st, (int)P.fn[f].n_stored);
+  const int n_st = z.max_stored;
 
   for (uint32_t base = first; base < n; base += lane_stride) {
+    if (tid == 0) *S = Stage{};
+    __syncthreads();
     const uint32_t i = base + tid;
     const bool active = i < n;
     const uint32_t frame = active ? cur_list[i] : 0;
     FrameHdr* h = frame_at(e, stride, frame);
     long long* slots = frame_slots(h);
     unsigned long long fired = 0, key = 0;
-    uint32_t present = 0, depth = 0;
+    uint32_t present = 0, depth = 0, pf_in = 0;
     int myfn = -1;
-    uint32_t pf_in = 0;
     if (active) {
       // tokens that arrived for this step; the word of the other parity belongs to the next
       const uint32_t arr = a_exch<SCOPE>(&h->arrived[(step + 1) & 1], 0u);
       pf_in = h->present_fn;
-      const uint32_t pf = pf_in | arr;
-      key = a_ld<SCOPE>(&h->key);
+      key = h->key;
       fired = h->fired;
+      const uint32_t pf = pf_in | arr;
       depth = (uint32_t)(key >> 8) & 0xFFFFFFu;
       present = pf & 0xFFFFFFu;
       myfn = (int)(pf >> 24);
     }
     const unsigned long long fired_in = fired;
-    // stored values, all loads in flight at once
+    // stored values (meaningful where the present bit is set), all loads in flight at once
     for (int k0 = 0; k0 < n_st; k0 += 8) {
       long long sv[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
-        sv[k] = (active && k0 + k < n_st && ((present >> (k0 + k)) & 1)) ? slots[k0 + k] : 0;
+      for (int k = 0; k < 8; ++k) sv[k] = (active && k0 + k < n_st) ? slots[k0 + k] : 0;
 #pragma unroll
       for (int k = 0; k < 8; ++k)
         if (k0 + k < n_st) stv[(k0 + k) * RB + tid] = sv[k];
     }
+    // forest entries of the last node looked at: one round trip serves isleaf/left/right/token
+    long long tc_v = -1;
+    int tc_left = 0, tc_right = 0, tc_token = 0;
 
     for (int f = 0; f < P.n_fn; ++f) {
       const bool on = myfn == f;
@@ -230,10 +259,18 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               if (a.v < 0 || a.v >= e.n_tree_nodes || e.left == nullptr) {
                 raise(c, TDF_ERR_BAD_ARG);
                 d = true;
-              } else if (I.op == D_ISLEAF) r = e.left[a.v] < 0;
-              else if (I.op == D_LEFT) r = e.left[a.v];
-              else if (I.op == D_RIGHT) r = e.right[a.v];
-              else r = e.token[a.v];
+              } else {
+                if (tc_v != a.v) {
+                  tc_left = e.left[a.v];
+                  tc_right = e.right[a.v];
+                  tc_token = e.token[a.v];
+                  tc_v = a.v;
+                }
+                if (I.op == D_ISLEAF) r = tc_left < 0;
+                else if (I.op == D_LEFT) r = tc_left;
+                else if (I.op == D_RIGHT) r = tc_right;
+                else r = tc_token;
+              }
             }
             put(I.dst, r, p, p && d);
             live = p && !d;
@@ -266,7 +303,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
             break;
           }
           case D_CALL: {
-            // Call_i: <t,d> -> <i:t,d>.  The tag i:t is the key (this frame, i).
+            // Call_i: <t,d> -> <i:t,d>.  The tag i:t is the key (this frame, tag length, i).
             const Src a = src(0);
             const bool go = on && a.p && !a.d && !(fired & ibit);
             const uint32_t label = I.aux, param = I.aux2;
@@ -296,13 +333,13 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               child = s;
               if (!found) raise(c, TDF_ERR_TABLE_FULL);
             }
-            deliver<SCOPE>(e, c, stride, go && found, child, param, a.v,
-                    (1u << param) | ((uint32_t)P.label_callee[label] << 24), stamp, next_list, next_count);
-            wave_count(inserted, &c->n_tags);
-            wave_count(go && found, &c->n_tokens);
+            deliver<SCOPE>(e, stride, go && found, child, param, a.v,
+                           (1u << param) | ((uint32_t)P.label_callee[label] << 24), stamp, S, stg_touched);
+            (void)wave_alloc(inserted, &S->n_tags);
+            (void)wave_alloc(go && found, &S->n_tokens);
             if (__ballot(inserted)) {
-              wave_max(inserted ? probes : 0, &c->max_probe);
-              wave_max(inserted ? depth + 1 : 0, &c->max_depth);
+              wave_max(inserted ? probes : 0, &S->max_probe);
+              wave_max(inserted ? depth + 1 : 0, &S->max_depth);
             }
             live = on && a.p && !a.d;
             break;
@@ -320,33 +357,26 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               // Return_i: <i:t,d> -> <t,d>; i and the frame of t are in this frame's key
               const uint32_t parent = (uint32_t)(key >> 32) - 1u, label = ((uint32_t)key & 0xFFu) - 1u;
               const uint32_t slot = go ? P.label_ret_slot[label] : 0;
-              deliver<SCOPE>(e, c, stride, go, parent, slot, a.v, 1u << slot, stamp, next_list, next_count);
-              wave_count(go, &c->n_tokens);
+              deliver<SCOPE>(e, stride, go, parent, slot, a.v, 1u << slot, stamp, S, stg_touched);
+              (void)wave_alloc(go, &S->n_tokens);
             }
             live = on && a.p && !a.d;
             break;
           }
           case D_EMBED: {
+            // the leaf's state row is the row of this frame; level 0
             const Src a = src(0);
             const bool had = on && ((present >> I.aux) & 1);
             const bool go = on && a.p && !a.d && !had;
-            const uint32_t idx = wave_alloc(go, &c->n_leaf);
-            const uint32_t row = wave_alloc(go, &c->n_rows);
-            long long r = stv[I.aux * RB + tid];
-            bool ok = go;
-            if (go) {
-              if (row < e.row_cap && idx < e.row_cap && a.v >= 0) {
-                e.leaf_row[idx] = row;
-                e.leaf_tok[idx] = (uint32_t)a.v;
-                r = (long long)row;   // level 0
-                slots[I.aux] = r;
-                present |= 1u << I.aux;
-              } else {
-                raise(c, a.v < 0 ? TDF_ERR_BAD_ARG : TDF_ERR_TABLE_FULL);
-                ok = false;
-              }
+            const bool ok = go && a.v >= 0;
+            if (go && !ok) raise(c, TDF_ERR_BAD_ARG);
+            const uint32_t pos = wave_alloc(ok, &S->n_leaf);
+            if (ok) {
+              stg_leaf[pos] = make_uint2(frame, (uint32_t)a.v);
+              slots[I.aux] = (long long)frame;
+              present |= 1u << I.aux;
             }
-            put(I.dst, r, had || ok, false);
+            put(I.dst, had ? stv[I.aux * RB + tid] : (long long)frame, had || ok, false);
             live = had || ok;
             break;
           }
@@ -354,30 +384,20 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
             const Src a = src(0), b = src(1);
             const bool had = on && ((present >> I.aux) & 1);
             const bool go = on && a.p && b.p && !a.d && !b.d && !had;
-            const uint32_t j = wave_alloc(go, &c->n_cell);
-            const uint32_t row = wave_alloc(go, &c->n_rows);
+            const uint32_t pos = wave_alloc(go, &S->n_cell);
             long long r = stv[I.aux * RB + tid];
-            bool ok = go;
             uint32_t lvl = 0;
             if (go) {
-              if (row < e.row_cap && j < e.row_cap) {
-                const uint32_t la = (uint32_t)(a.v >> 32), lb = (uint32_t)(b.v >> 32);
-                lvl = 1 + (la > lb ? la : lb);
-                e.cell_out[j] = row;
-                e.cell_l[j] = (uint32_t)a.v;
-                e.cell_r[j] = (uint32_t)b.v;
-                e.cell_lvl[j] = lvl;
-                r = (long long)row | ((long long)lvl << 32);
-                slots[I.aux] = r;
-                present |= 1u << I.aux;
-              } else {
-                raise(c, TDF_ERR_TABLE_FULL);
-                ok = false;
-              }
+              const uint32_t la = (uint32_t)(a.v >> 32), lb = (uint32_t)(b.v >> 32);
+              lvl = 1 + (la > lb ? la : lb);
+              stg_cell[pos] = make_uint4(frame, (uint32_t)a.v, (uint32_t)b.v, lvl);
+              r = (long long)frame | ((long long)lvl << 32);
+              slots[I.aux] = r;
+              present |= 1u << I.aux;
             }
-            if (__ballot(go)) wave_max(ok ? lvl : 0, &c->max_level);
-            put(I.dst, r, had || ok, false);
-            live = had || ok;
+            if (__ballot(go)) wave_max(lvl, &S->max_level);
+            put(I.dst, r, had || go, false);
+            live = had || go;
             break;
           }
           case D_HEAD: {
@@ -391,7 +411,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               slots[I.aux] = inst;
               present |= 1u << I.aux;
             }
-            (void)wave_alloc(go, &c->n_head);
+            (void)wave_alloc(go, &S->n_head);
             put(I.dst, (long long)(frame - e.cap), had || go, false);
             live = had || go;
             break;
@@ -406,6 +426,44 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       const uint32_t pf_out = present | ((uint32_t)myfn << 24);
       if (pf_out != pf_in) h->present_fn = pf_out;
     }
+
+    // ---- the workgroup reserves its ranges of the global lists and copies the entries out ---
+    __syncthreads();
+    if (tid == 0) {
+      S->base_touched = S->n_touched ? atomicAdd(next_count, S->n_touched) : 0;
+      S->base_leaf = S->n_leaf ? atomicAdd(&c->n_leaf, S->n_leaf) : 0;
+      S->base_cell = S->n_cell ? atomicAdd(&c->n_cell, S->n_cell) : 0;
+      if (S->n_head) atomicAdd(&c->n_head, S->n_head);
+      if (S->n_tags) atomicAdd(&c->n_tags, (unsigned long long)S->n_tags);
+      if (S->n_tokens) atomicAdd(&c->n_tokens, (unsigned long long)S->n_tokens);
+      if (S->max_probe > c->max_probe) atomicMax(&c->max_probe, S->max_probe);
+      if (S->max_depth > c->max_depth) atomicMax(&c->max_depth, S->max_depth);
+      if (S->max_level > c->max_level) atomicMax(&c->max_level, S->max_level);
+      if (S->base_touched + S->n_touched > e.touched_cap || S->base_leaf + S->n_leaf > e.log_cap ||
+          S->base_cell + S->n_cell > e.log_cap)
+        raise(c, TDF_ERR_TABLE_FULL);
+    }
+    __syncthreads();
+    for (uint32_t k = tid; k < S->n_touched; k += RB)
+      if (S->base_touched + k < e.touched_cap) next_list[S->base_touched + k] = stg_touched[k];
+    for (uint32_t k = tid; k < S->n_leaf; k += RB) {
+      const uint32_t j = S->base_leaf + k;
+      if (j < e.log_cap) {
+        e.leaf_row[j] = stg_leaf[k].x;
+        e.leaf_tok[j] = stg_leaf[k].y;
+      }
+    }
+    for (uint32_t k = tid; k < S->n_cell; k += RB) {
+      const uint32_t j = S->base_cell + k;
+      if (j < e.log_cap) {
+        const uint4 x = stg_cell[k];
+        e.cell_out[j] = x.x;
+        e.cell_l[j] = x.y;
+        e.cell_r[j] = x.z;
+        e.cell_lvl[j] = x.w;
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -431,13 +489,13 @@ __device__ void advance(const Engine& e, Ctrl* c, uint32_t step) {
 // k_steps_small, the others in the grid-wide k_step.
 __device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
 
-__global__ void __launch_bounds__(FIRE_BLOCK) k_step(DevProgram P, Engine e, int max_values) {
-  extern __shared__ long long lds[];
+__global__ void __launch_bounds__(FIRE_BLOCK) k_step(DevProgram P, Engine e) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
   Ctrl* c = e.ctrl;
   const uint32_t step = c->step;
   const uint32_t n = ld(&c->touched_count[step & 1]);
   if (c->done || n == 0 || step_is_small(e, n)) return;
-  step_pass<__HIP_MEMORY_SCOPE_AGENT>(P, e, c, step, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, lds, max_values);
+  step_pass<__HIP_MEMORY_SCOPE_AGENT>(P, e, c, step, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, lds);
   // the last workgroup to finish closes the step
   __shared__ bool last;
   __syncthreads();
@@ -456,15 +514,14 @@ __global__ void __launch_bounds__(FIRE_BLOCK) k_step(DevProgram P, Engine e, int
 // Small steps: one workgroup runs step after step with workgroup barriers only and keeps the
 // control block (all list and log counters) in LDS.  Returns when the recursion is finished,
 // when a step is too large for one workgroup, or after max_steps steps.
-__global__ void k_steps_small(DevProgram P, Engine e, int max_values, int max_steps) {
-  extern __shared__ long long lds[];
+__global__ void k_steps_small(DevProgram P, Engine e, int max_steps) {
+  extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ Ctrl lc;
   Ctrl* g = e.ctrl;
   if (threadIdx.x == 0) {
     lc.touched_count[0] = ld(&g->touched_count[0]);
     lc.touched_count[1] = ld(&g->touched_count[1]);
     lc.step = g->step;
-    lc.n_rows = ld(&g->n_rows);
     lc.n_leaf = ld(&g->n_leaf);
     lc.n_cell = ld(&g->n_cell);
     lc.n_head = ld(&g->n_head);
@@ -481,19 +538,16 @@ __global__ void k_steps_small(DevProgram P, Engine e, int max_values, int max_st
   for (int it = 0; it < max_steps; ++it) {
     const uint32_t step = lc.step;
     const uint32_t n = lc.touched_count[step & 1];
-    const bool stop = lc.done || n == 0 || !step_is_small(e, n);
-    __syncthreads();
-    if (stop) break;
-    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP>(P, e, &lc, step, n, 0, blockDim.x, lds, max_values);
-    __syncthreads();
+    if (lc.done || n == 0 || !step_is_small(e, n)) break;   // uniform: lc changes only between barriers
+    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP>(P, e, &lc, step, n, 0, blockDim.x, lds);
     if (threadIdx.x == 0) advance(e, &lc, step);
     __syncthreads();
   }
+  __syncthreads();
   if (threadIdx.x == 0) {
     st(&g->touched_count[0], lc.touched_count[0]);
     st(&g->touched_count[1], lc.touched_count[1]);
     g->step = lc.step;
-    st(&g->n_rows, lc.n_rows);
     st(&g->n_leaf, lc.n_leaf);
     st(&g->n_cell, lc.n_cell);
     st(&g->n_head, lc.n_head);
@@ -597,18 +651,26 @@ void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s) {
   hipLaunchKernelGGL(k_seed, dim3(grid_for(e.n_inst, 256, 1 << 20)), dim3(256), 0, s, P, e);
 }
 
+// Lanes of the single-workgroup kernel: as many as the per-lane LDS footprint allows.
+int tag_machine_small_block(const DevProgram& P) {
+  const Sizes z = sizes_of(P);
+  int rb = 512;
+  while (rb > 64 && step_lds_bytes(z, rb) > 120 * 1024) rb >>= 1;
+  return rb;
+}
+
 // One round of the tag machine: as many small steps as fit (one workgroup), then one
 // grid-wide step if the next step is large.  Each kernel decides on the device whether the
 // current step is its own.
-void launch_round(const DevProgram& P, const Engine& e, int max_values, int max_stored, int blocks,
-                  int small_block, int small_steps, hipStream_t s) {
-  const size_t per_lane = (size_t)(max_values + max_stored) * sizeof(long long);
-  const size_t small_lds = per_lane * small_block;
+void launch_round(const DevProgram& P, const Engine& e, int blocks, int small_block, int small_steps,
+                  hipStream_t s) {
+  const Sizes z = sizes_of(P);
+  const size_t small_lds = step_lds_bytes(z, small_block);
   if (small_lds > 48 * 1024)   // large value files need the LDS opt-in
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_small),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds);
-  hipLaunchKernelGGL(k_steps_small, dim3(1), dim3(small_block), small_lds, s, P, e, max_values, small_steps);
-  hipLaunchKernelGGL(k_step, dim3(blocks), dim3(FIRE_BLOCK), per_lane * FIRE_BLOCK, s, P, e, max_values);
+  hipLaunchKernelGGL(k_steps_small, dim3(1), dim3(small_block), small_lds, s, P, e, small_steps);
+  hipLaunchKernelGGL(k_step, dim3(blocks), dim3(FIRE_BLOCK), step_lds_bytes(z, FIRE_BLOCK), s, P, e);
 }
 
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s) {

@@ -52,6 +52,7 @@ enum ValueType : uint8_t { T_INT = 0, T_VEC = 1, T_LOSS = 2 };
 struct DevFn {
   uint16_t first, count;   // instruction range
   uint8_t n_values, n_stored, out_type, n_params;
+  uint8_t n_emit, pad[3];  // entries that emit a token (Call_i per parameter, function output)
 };
 
 // Passed to the kernels by value (kernel-argument segment: uniform, scalar-cached reads).
