@@ -28,15 +28,16 @@ struct Ctrl {
 // scope).  The key packs (parent frame + 1, tag length, label + 1); 0 means empty.  The slot
 // index is the frame id, so inserting a tag and allocating its frame are one compare-and-swap.
 //
-// Tokens delivered during step s set bits in arrived[(s+1)&1]; the sweep of step s+1 takes
-// that word (exchange with 0) and folds it into present_fn, which only the sweeping lane
-// writes.  Values delivered in one step are read in a later one, so only key, touched and
-// arrived[] are ever accessed concurrently and need atomics.
+// Tokens delivered during step s set bits in the arrival word of step s+1; the sweep of step
+// s+1 takes that word (exchange with 0) and folds it into present_fn, which only the sweeping
+// lane writes.  The delivery that finds the word empty is the first to reach the frame in that
+// step and puts it on the next list.  Values delivered in one step are read in a later one, so
+// only key and arrived[] are ever accessed concurrently and need atomics.
 struct FrameHdr {
   unsigned long long key;     // (parent + 1) << 32 | depth << 8 | (label + 1)
   unsigned long long fired;   // firing-table entries that have fired live under this tag
   uint32_t present_fn;        // bits 0..23: stored values present; bits 24..31: function
-  uint32_t touched;           // stamp of the last step that delivered a token here
+  uint32_t pad;
   uint32_t arrived[2];        // same layout as present_fn, by parity of the consuming step
   // followed by int64 stored[n_stored]
 };
@@ -44,6 +45,7 @@ static_assert(sizeof(FrameHdr) == 32, "FrameHdr must be 32 bytes");
 
 // Pointers into the workspace and to the caller's buffers, passed to kernels by value.
 struct Engine {
+  const DevProgram* prog;           // firing tables in the workspace (copied there once per call)
   Ctrl* ctrl;
   unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
   char* frames;                     // (cap + B) records of frame_stride bytes

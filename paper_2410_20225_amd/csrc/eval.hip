@@ -103,6 +103,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));
   L.zero_end = L.total;
   // --- the rest is written before it is read
+  size_t off_prog = L.take(sizeof(DevProgram));
   size_t off_touched = L.take(sizeof(uint32_t) * 2 * (size_t)e.touched_cap);
   size_t off_root = L.take(sizeof(uint32_t) * B);
   size_t off_hrow = L.take(sizeof(uint32_t) * B);
@@ -113,6 +114,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_c_out = L.take(4 * rc), off_c_l = L.take(4 * rc), off_c_r = L.take(4 * rc), off_c_lvl = L.take(4 * rc);
   size_t off_q_out = L.take(4 * rc), off_q_l = L.take(4 * rc), off_q_r = L.take(4 * rc);
 
+  e.prog = (const DevProgram*)at(off_prog);
   e.ctrl = (Ctrl*)at(P.off_ctrl);
   e.fire_count = (unsigned long long*)at(P.off_fire);
   e.level_count = (uint32_t*)at(off_lcount);
@@ -257,6 +259,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
 
   begin(TDF_PHASE_TAGS);
   HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
+  HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
   launch_seed(G.prog, e, s);
 
   // ---- the tag machine: fire / match steps until no token is in flight -------------------

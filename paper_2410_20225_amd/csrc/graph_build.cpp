@@ -453,6 +453,10 @@ struct Builder {
       int n_emit = 0;
       for (int q = first; q < n_instr; ++q) n_emit += D.instr[q].op == D_CALL || D.instr[q].op == D_OUT;
       D.fn[f].n_emit = (uint8_t)n_emit;
+      int n_cl = 0;
+      for (int q = first; q < n_instr && n_cl < 6; ++q)
+        if (D.instr[q].op == D_CALL && D.instr[q].aux2 == 0) D.fn[f].call_labels[n_cl++] = D.instr[q].aux;
+      D.fn[f].n_call_labels = (uint8_t)n_cl;
       if (n_stored > max_stored) max_stored = n_stored;
     }
     D.frame_stride = (32 + 8 * max_stored + 31) / 32 * 32;

@@ -76,7 +76,6 @@ __global__ void k_seed(DevProgram P, Engine e) {
   h->key = 0;
   h->fired = 0;
   h->present_fn = ((1u << np) - 1u) | ((uint32_t)P.result_fn << 24);
-  h->touched = 1;
   h->arrived[0] = h->arrived[1] = 0;
   e.touched[b] = f;
   if (b == 0) e.ctrl->touched_count[0] = e.n_inst;
@@ -86,6 +85,24 @@ struct Src {
   long long v;
   bool p, d;   // present, dead
 };
+
+// The firing tables are copied into LDS by every workgroup; a table entry read from there is
+// the same in all lanes and is moved to scalar registers, so that the dispatch on it and the
+// indexing of the register value file stay wave-uniform.
+__device__ __forceinline__ uint32_t uni(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ Instr fetch(const DevProgram& P, int idx) {
+  union { Instr i; uint32_t w[4]; } u;
+  u.i = P.instr[idx];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) u.w[k] = uni(u.w[k]);
+  return u.i;
+}
+__device__ __forceinline__ void load_program(DevProgram* dst, const DevProgram* src) {
+  const uint32_t* s = reinterpret_cast<const uint32_t*>(src);
+  uint32_t* d = reinterpret_cast<uint32_t*>(dst);
+  for (int i = threadIdx.x; i < (int)(sizeof(DevProgram) / 4); i += blockDim.x) d[i] = s[i];
+  __syncthreads();
+}
 
 // Per-workgroup staging of one pass.  Lanes take positions in these LDS lists with wave ballots;
 // the workgroup reserves its ranges of the global lists with one atomic per list when the pass
@@ -114,17 +131,23 @@ __host__ __device__ inline size_t step_lds_bytes(const Sizes& z, int rb) {
 }
 
 // Deliver one value to slot `slot` of frame `target`, and stage the frame for the next list if
-// this is the first token to reach it in this step.  Must be reached by the whole wave.
+// this is the first token to reach it in this step.  `exclusive`: the frame was created by this
+// lane and no other token can reach it before its first sweep (single-parameter callee), so
+// plain stores do.  Must be reached by the whole wave.
 template <int SCOPE>
 __device__ __forceinline__ void deliver(const Engine& e, int stride, bool go, uint32_t target, uint32_t slot,
-                                        long long value, uint32_t or_bits, uint32_t stamp, Stage* S,
-                                        uint32_t* stg_touched) {
+                                        long long value, uint32_t or_bits, uint32_t word, bool exclusive,
+                                        Stage* S, uint32_t* stg_touched) {
   bool first = false;
   if (go) {
     FrameHdr* h = frame_at(e, stride, target);
     frame_slots(h)[slot] = value;                     // read in a later step only
-    a_or<SCOPE>(&h->arrived[stamp & 1], or_bits);     // stamp = consuming step + 1
-    first = a_exch<SCOPE>(&h->touched, stamp) != stamp;
+    if (exclusive) {
+      h->arrived[word] = or_bits;
+      first = true;
+    } else {
+      first = a_or<SCOPE>(&h->arrived[word], or_bits) == 0;
+    }
   }
   const uint32_t pos = wave_alloc(first, &S->n_touched);
   if (first) stg_touched[pos] = target;
@@ -133,24 +156,38 @@ __device__ __forceinline__ void deliver(const Engine& e, int stride, bool go, ui
 // One pass over the touched frames [0, n) of the current list; lane `first + tid` takes frames
 // i, i + lane_stride, ...  `c` is the control block the pass counts in: the global one, or a
 // workgroup's LDS copy.  The loop over passes is uniform for the workgroup.
-template <int SCOPE>
+// NV > 0: the value file of a sweep (at most NV values, 8 stored values) lives in registers,
+// indexed with the wave-uniform value ids of the firing table; NV == 0: it lives in LDS.
+template <int SCOPE, int NV>
 __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_t step, uint32_t n,
                           uint32_t first, uint32_t lane_stride, char* lds) {
   const int tid = threadIdx.x;
   const int RB = blockDim.x;
-  const Sizes z = sizes_of(P);
+  Sizes z = sizes_of(P);
+  if (NV > 0) z.max_values = z.max_stored = 0;   // no LDS value file
+  long long rloc[NV > 0 ? NV : 1], sloc[NV > 0 ? 8 : 1];
+  auto rd = [&](int idx) -> long long {
+    if constexpr (NV > 0) return rloc[idx]; else return reinterpret_cast<long long*>(lds)[idx * RB + tid];
+  };
+  auto wr = [&](int idx, long long v) {
+    if constexpr (NV > 0) rloc[idx] = v; else reinterpret_cast<long long*>(lds)[idx * RB + tid] = v;
+  };
+  auto rd_st = [&](int idx) -> long long {
+    if constexpr (NV > 0) return sloc[idx];
+    else return reinterpret_cast<long long*>(lds)[(z.max_values + idx) * RB + tid];
+  };
   long long* regs = reinterpret_cast<long long*>(lds);                 // [value][lane]
   long long* stv = regs + (size_t)z.max_values * RB;                   // [stored slot][lane]
   uint4* stg_cell = reinterpret_cast<uint4*>(stv + (size_t)z.max_stored * RB);
   uint2* stg_leaf = reinterpret_cast<uint2*>(stg_cell + RB);
   uint32_t* stg_touched = reinterpret_cast<uint32_t*>(stg_leaf + RB);  // [max_emit * RB]
   Stage* S = reinterpret_cast<Stage*>(stg_touched + (size_t)z.max_emit * RB);
-  const int stride = P.frame_stride;
+  const int stride = (int)uni((uint32_t)P.frame_stride);
   const uint32_t* cur_list = e.touched + (size_t)(step & 1) * e.touched_cap;
   uint32_t* next_list = e.touched + (size_t)((step & 1) ^ 1) * e.touched_cap;
   uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
-  const uint32_t stamp = step + 2;   // frames on the list of step s carry stamp s + 1
-  const int n_st = z.max_stored;
+  const uint32_t word = step & 1;    // arrival word of the next step (this step reads word ^ 1)
+  const int n_st = sizes_of(P).max_stored;
 
   for (uint32_t base = first; base < n; base += lane_stride) {
     if (tid == 0) *S = Stage{};
@@ -165,7 +202,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     int myfn = -1;
     if (active) {
       // tokens that arrived for this step; the word of the other parity belongs to the next
-      const uint32_t arr = a_exch<SCOPE>(&h->arrived[(step + 1) & 1], 0u);
+      const uint32_t arr = a_exch<SCOPE>(&h->arrived[word ^ 1], 0u);
       pf_in = h->present_fn;
       key = h->key;
       fired = h->fired;
@@ -176,35 +213,58 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     }
     const unsigned long long fired_in = fired;
     // stored values (meaningful where the present bit is set), all loads in flight at once
-    for (int k0 = 0; k0 < n_st; k0 += 8) {
-      long long sv[8];
+    if constexpr (NV > 0) {
 #pragma unroll
-      for (int k = 0; k < 8; ++k) sv[k] = (active && k0 + k < n_st) ? slots[k0 + k] : 0;
+      for (int k = 0; k < 8; ++k) sloc[k] = (active && k < n_st) ? slots[k] : 0;
+    } else {
+      for (int k0 = 0; k0 < n_st; k0 += 8) {
+        long long sv[8];
 #pragma unroll
-      for (int k = 0; k < 8; ++k)
-        if (k0 + k < n_st) stv[(k0 + k) * RB + tid] = sv[k];
+        for (int k = 0; k < 8; ++k) sv[k] = (active && k0 + k < n_st) ? slots[k0 + k] : 0;
+#pragma unroll
+        for (int k = 0; k < 8; ++k)
+          if (k0 + k < n_st) stv[(k0 + k) * RB + tid] = sv[k];
+      }
+    }
+    // Warm the lines this sweep may write to: the frames of the calls it can make (their keys
+    // depend only on this frame and the label) on a first sweep, the caller's frame otherwise.
+    // The loaded words are only folded into `warm`, which is never acted on.
+    unsigned long long warm = 0;
+    if (active && myfn >= 0) {
+      if (fired == 0) {
+        const int ncl = P.fn[myfn].n_call_labels;
+        for (int k = 0; k < ncl; ++k) {
+          const unsigned long long ckey = ((unsigned long long)(frame + 1u) << 32) |
+                                          ((unsigned long long)(depth + 1u) << 8) | (P.fn[myfn].call_labels[k] + 1u);
+          warm += frame_at(e, stride, (uint32_t)mix64(ckey) & e.cap_mask)->fired;
+        }
+      }
+      if (key != 0) warm += frame_at(e, stride, (uint32_t)(key >> 32) - 1u)->fired;
     }
     // forest entries of the last node looked at: one round trip serves isleaf/left/right/token
     long long tc_v = -1;
     int tc_left = 0, tc_right = 0, tc_token = 0;
 
-    for (int f = 0; f < P.n_fn; ++f) {
+    const int n_fn = (int)uni((uint32_t)P.n_fn);
+    for (int f = 0; f < n_fn; ++f) {
       const bool on = myfn == f;
       if (__ballot(on) == 0) continue;
-      const int first_i = P.fn[f].first, count = P.fn[f].count;
-      const bool is_result = f == P.result_fn;
+      const int first_i = (int)uni(P.fn[f].first), count = (int)uni(P.fn[f].count);
+      const bool is_result = f == (int)uni((uint32_t)P.result_fn);
       unsigned long long pres = 0, dead = 0;   // over value ids
 
+      Instr I_next = fetch(P, first_i);
       for (int ip = 0; ip < count; ++ip) {
-        const Instr I = P.instr[first_i + ip];
+        const Instr I = I_next;
+        if (ip + 1 < count) I_next = fetch(P, first_i + ip + 1);   // fetched while this entry runs
         const unsigned long long ibit = 1ull << ip;
         auto src = [&](int k) -> Src {
           const uint8_t s = I.src[k];
           if (s == SRC_IMM) return Src{I.imm, true, false};
-          return Src{regs[(int)s * RB + tid], ((pres >> s) & 1) != 0, ((dead >> s) & 1) != 0};
+          return Src{rd(s), ((pres >> s) & 1) != 0, ((dead >> s) & 1) != 0};
         };
         auto put = [&](int dst, long long v, bool p, bool d) {
-          regs[dst * RB + tid] = v;
+          wr(dst, v);
           if (p) pres |= 1ull << dst;
           if (d) dead |= 1ull << dst;
         };
@@ -212,7 +272,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         switch (I.op) {
           case D_IN: {
             const bool p = on && ((present >> I.aux) & 1);
-            put(I.dst, stv[I.aux * RB + tid], p, false);
+            put(I.dst, rd_st(I.aux), p, false);
             live = p;
             break;
           }
@@ -226,7 +286,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               any_d = any_d || ((dead >> I.src[k]) & 1);
             }
             const bool is_dead = on && !p && any_arg && all_p && any_d;   // the call never happened
-            put(I.dst, stv[I.aux * RB + tid], p || is_dead, is_dead);
+            put(I.dst, rd_st(I.aux), p || is_dead, is_dead);
             live = p;
             break;
           }
@@ -316,13 +376,10 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               const uint32_t probe_limit = e.cap < 8192u ? e.cap : 8192u;
               for (probes = 1; probes <= probe_limit; ++probes) {
                 FrameHdr* ch = frame_at(e, stride, s);
-                unsigned long long cur = a_ld<SCOPE>(&ch->key);
+                const unsigned long long cur = a_cas<SCOPE>(&ch->key, 0ull, ckey);
                 if (cur == 0) {
-                  cur = a_cas<SCOPE>(&ch->key, 0ull, ckey);
-                  if (cur == 0) {
-                    inserted = found = true;
-                    break;
-                  }
+                  inserted = found = true;
+                  break;
                 }
                 if (cur == ckey) {
                   found = true;
@@ -333,8 +390,9 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               child = s;
               if (!found) raise(c, TDF_ERR_TABLE_FULL);
             }
-            deliver<SCOPE>(e, stride, go && found, child, param, a.v,
-                           (1u << param) | ((uint32_t)P.label_callee[label] << 24), stamp, S, stg_touched);
+            const uint32_t callee = P.label_callee[label];
+            deliver<SCOPE>(e, stride, go && found, child, param, a.v, (1u << param) | (callee << 24), word,
+                           inserted && P.fn[callee].n_params == 1, S, stg_touched);
             (void)wave_alloc(inserted, &S->n_tags);
             (void)wave_alloc(go && found, &S->n_tokens);
             if (__ballot(inserted)) {
@@ -357,7 +415,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               // Return_i: <i:t,d> -> <t,d>; i and the frame of t are in this frame's key
               const uint32_t parent = (uint32_t)(key >> 32) - 1u, label = ((uint32_t)key & 0xFFu) - 1u;
               const uint32_t slot = go ? P.label_ret_slot[label] : 0;
-              deliver<SCOPE>(e, stride, go, parent, slot, a.v, 1u << slot, stamp, S, stg_touched);
+              deliver<SCOPE>(e, stride, go, parent, slot, a.v, 1u << slot, word, false, S, stg_touched);
               (void)wave_alloc(go, &S->n_tokens);
             }
             live = on && a.p && !a.d;
@@ -376,7 +434,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               slots[I.aux] = (long long)frame;
               present |= 1u << I.aux;
             }
-            put(I.dst, had ? stv[I.aux * RB + tid] : (long long)frame, had || ok, false);
+            put(I.dst, had ? rd_st(I.aux) : (long long)frame, had || ok, false);
             live = had || ok;
             break;
           }
@@ -385,7 +443,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
             const bool had = on && ((present >> I.aux) & 1);
             const bool go = on && a.p && b.p && !a.d && !b.d && !had;
             const uint32_t pos = wave_alloc(go, &S->n_cell);
-            long long r = stv[I.aux * RB + tid];
+            long long r = rd_st(I.aux);
             uint32_t lvl = 0;
             if (go) {
               const uint32_t la = (uint32_t)(a.v >> 32), lb = (uint32_t)(b.v >> 32);
@@ -421,6 +479,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         if (live) fired |= ibit;   // counted after the run, from the fired masks
       }
     }
+    if (warm == 0xFEEDFACECAFEBEEFull) raise(c, TDF_ERR_DEVICE);   // keeps the warming loads alive
     if (active) {
       if (fired != fired_in) h->fired = fired;
       const uint32_t pf_out = present | ((uint32_t)myfn << 24);
@@ -489,13 +548,18 @@ __device__ void advance(const Engine& e, Ctrl* c, uint32_t step) {
 // k_steps_small, the others in the grid-wide k_step.
 __device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
 
-__global__ void __launch_bounds__(FIRE_BLOCK) k_step(DevProgram P, Engine e) {
+template <int NV>
+__global__ void __launch_bounds__(FIRE_BLOCK) k_step(Engine e) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
+  __shared__ DevProgram P;
   Ctrl* c = e.ctrl;
   const uint32_t step = c->step;
   const uint32_t n = ld(&c->touched_count[step & 1]);
   if (c->done || n == 0 || step_is_small(e, n)) return;
-  step_pass<__HIP_MEMORY_SCOPE_AGENT>(P, e, c, step, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, lds);
+  if (blockIdx.x * blockDim.x < n) {   // workgroups without frames only take part in closing the step
+    load_program(&P, e.prog);
+    step_pass<__HIP_MEMORY_SCOPE_AGENT, NV>(P, e, c, step, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, lds);
+  }
   // the last workgroup to finish closes the step
   __shared__ bool last;
   __syncthreads();
@@ -514,10 +578,17 @@ __global__ void __launch_bounds__(FIRE_BLOCK) k_step(DevProgram P, Engine e) {
 // Small steps: one workgroup runs step after step with workgroup barriers only and keeps the
 // control block (all list and log counters) in LDS.  Returns when the recursion is finished,
 // when a step is too large for one workgroup, or after max_steps steps.
-__global__ void k_steps_small(DevProgram P, Engine e, int max_steps) {
+template <int NV>
+__global__ void __launch_bounds__(512) k_steps_small(Engine e, int max_steps) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
+  __shared__ DevProgram P;
   __shared__ Ctrl lc;
   Ctrl* g = e.ctrl;
+  {
+    const uint32_t n0 = ld(&g->touched_count[g->step & 1]);
+    if (g->done || n0 == 0 || !step_is_small(e, n0)) return;   // nothing to do for this kernel
+  }
+  load_program(&P, e.prog);
   if (threadIdx.x == 0) {
     lc.touched_count[0] = ld(&g->touched_count[0]);
     lc.touched_count[1] = ld(&g->touched_count[1]);
@@ -539,7 +610,7 @@ __global__ void k_steps_small(DevProgram P, Engine e, int max_steps) {
     const uint32_t step = lc.step;
     const uint32_t n = lc.touched_count[step & 1];
     if (lc.done || n == 0 || !step_is_small(e, n)) break;   // uniform: lc changes only between barriers
-    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP>(P, e, &lc, step, n, 0, blockDim.x, lds);
+    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP, NV>(P, e, &lc, step, n, 0, blockDim.x, lds);
     if (threadIdx.x == 0) advance(e, &lc, step);
     __syncthreads();
   }
@@ -651,9 +722,17 @@ void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s) {
   hipLaunchKernelGGL(k_seed, dim3(grid_for(e.n_inst, 256, 1 << 20)), dim3(256), 0, s, P, e);
 }
 
+// Register value file when every function has at most 16 values and 8 stored values.
+static bool fits_registers(const Sizes& z) { return z.max_values <= 16 && z.max_stored <= 8; }
+static Sizes lds_sizes(const DevProgram& P) {
+  Sizes z = sizes_of(P);
+  if (fits_registers(z)) z.max_values = z.max_stored = 0;
+  return z;
+}
+
 // Lanes of the single-workgroup kernel: as many as the per-lane LDS footprint allows.
 int tag_machine_small_block(const DevProgram& P) {
-  const Sizes z = sizes_of(P);
+  const Sizes z = lds_sizes(P);
   int rb = 512;
   while (rb > 64 && step_lds_bytes(z, rb) > 120 * 1024) rb >>= 1;
   return rb;
@@ -664,13 +743,19 @@ int tag_machine_small_block(const DevProgram& P) {
 // current step is its own.
 void launch_round(const DevProgram& P, const Engine& e, int blocks, int small_block, int small_steps,
                   hipStream_t s) {
-  const Sizes z = sizes_of(P);
+  const Sizes z = lds_sizes(P);
+  const bool in_regs = fits_registers(sizes_of(P));
   const size_t small_lds = step_lds_bytes(z, small_block);
   if (small_lds > 48 * 1024)   // large value files need the LDS opt-in
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_small),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_small<0>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds);
-  hipLaunchKernelGGL(k_steps_small, dim3(1), dim3(small_block), small_lds, s, P, e, small_steps);
-  hipLaunchKernelGGL(k_step, dim3(blocks), dim3(FIRE_BLOCK), step_lds_bytes(z, FIRE_BLOCK), s, P, e);
+  if (in_regs) {
+    hipLaunchKernelGGL(k_steps_small<16>, dim3(1), dim3(small_block), small_lds, s, e, small_steps);
+    hipLaunchKernelGGL(k_step<16>, dim3(blocks), dim3(FIRE_BLOCK), step_lds_bytes(z, FIRE_BLOCK), s, e);
+  } else {
+    hipLaunchKernelGGL(k_steps_small<0>, dim3(1), dim3(small_block), small_lds, s, e, small_steps);
+    hipLaunchKernelGGL(k_step<0>, dim3(blocks), dim3(FIRE_BLOCK), step_lds_bytes(z, FIRE_BLOCK), s, e);
+  }
 }
 
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s) {

@@ -52,7 +52,9 @@ enum ValueType : uint8_t { T_INT = 0, T_VEC = 1, T_LOSS = 2 };
 struct DevFn {
   uint16_t first, count;   // instruction range
   uint8_t n_values, n_stored, out_type, n_params;
-  uint8_t n_emit, pad[3];  // entries that emit a token (Call_i per parameter, function output)
+  uint8_t n_emit;          // entries that emit a token (Call_i per parameter, function output)
+  uint8_t n_call_labels;   // distinct call labels in the body (capped at 6), for prefetching
+  uint8_t call_labels[6];
 };
 
 // Passed to the kernels by value (kernel-argument segment: uniform, scalar-cached reads).
