@@ -22,7 +22,9 @@
 #ifndef TDF_H
 #define TDF_H
 
+#ifndef __HIPCC_RTC__ /* the run-time compiler has size_t built in and no <stddef.h> */
 #include <stddef.h>
+#endif
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -38,7 +40,8 @@ typedef enum {
   TDF_ERR_WORKSPACE = -3,   /* workspace too small or misaligned                      */
   TDF_ERR_TABLE_FULL = -4,  /* more tags, tokens or state rows than max_tags allows   */
   TDF_ERR_STEP_LIMIT = -5,  /* recursion did not finish within step_limit steps       */
-  TDF_ERR_DEVICE = -6       /* a HIP call failed                                      */
+  TDF_ERR_DEVICE = -6,      /* a HIP call failed                                      */
+  TDF_ERR_UNSUPPORTED = -7  /* optional facility not available                        */
 } tdf_status;
 
 /* ---- program description (host memory, read only during tdf_graph_build) ------------
@@ -129,6 +132,15 @@ typedef struct {
 } tdf_graph_info_t;
 
 tdf_status tdf_graph_info(const tdf_graph* g, tdf_graph_info_t* out);
+
+/* Section 5 (the firing rule of the transformed graph, specialised): the per-function firing
+ * tables of `g` are turned into straight-line device code and compiled for the GPU
+ * architecture `arch` (e.g. "gfx950") with the HIP run-time compiler; tdf_eval does the same
+ * on first use for the current device, so calling this is optional and only moves the
+ * compile time.  Host only, needs no GPU.  *code_bytes (may be NULL) receives the size of
+ * the code object.  TDF_ERR_UNSUPPORTED when the run-time compiler is missing or the
+ * program does not fit the generated form; evaluation then uses the table interpreter. */
+tdf_status tdf_graph_precompile(const tdf_graph* g, const char* arch, size_t* code_bytes);
 
 /* ---- evaluation ------------------------------------------------------------------- */
 typedef enum { TDF_F32 = 0, TDF_BF16 = 1 } tdf_dtype;

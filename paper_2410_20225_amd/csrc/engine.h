@@ -1,10 +1,12 @@
 // Device-side data layout of one evaluation, shared by the tag machine (tag_machine.hip),
 // the vector kernels (cells.hip) and the host driver (eval.hip).
 #pragma once
+#ifndef __HIPCC_RTC__ /* the run-time compiler provides the HIP device API implicitly */
 #include <hip/hip_runtime.h>
+#endif
 #include <stdint.h>
 
-#include "tdf_internal.h"
+#include "tdf_tables.h"
 
 namespace tdf {
 
@@ -126,6 +128,11 @@ inline __device__ uint32_t wave_alloc_keyed(bool take, uint32_t key, uint32_t* c
     todo &= ~same;
   }
   return pos;
+}
+
+inline __device__ void wave_count32(bool take, uint32_t* counter) {
+  unsigned long long m = __ballot(take);
+  if (m && (int)lane_id() == __ffsll((long long)m) - 1) atomicAdd(counter, (uint32_t)__popcll(m));
 }
 
 inline __device__ void wave_count(bool take, unsigned long long* counter) {

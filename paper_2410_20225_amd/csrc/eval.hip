@@ -2,17 +2,21 @@
 // the level-by-level execution of the cell firings, and the reversed schedule of the
 // gradient pass.
 #include <algorithm>
+#include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 #include <string>
 #include <vector>
 
 #include "engine.h"
+#include "tdf_internal.h"
 
 namespace tdf {
 
 void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
-void launch_round(const DevProgram& P, const Engine& e, int blocks, int small_block, int small_steps, hipStream_t s);
-int tag_machine_small_block(const DevProgram& P);
+tdf_status launch_round(const DevProgram& P, const Engine& e, int blocks, int small_block, int small_steps,
+                        void* jit_small, void* jit_step, hipStream_t s);
+int tag_machine_small_block(const DevProgram& P, bool jit);
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s);
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s);
 void vec_pack_w(const VecArgs& v, hipStream_t s);
@@ -264,13 +268,23 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
 
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
   const int blocks = 768;
-  const int small_block = tag_machine_small_block(G.prog);
+  // step kernels generated for this program (first call only; falls back to the interpreter)
+  if (!gr->jit.tried) {
+    gr->jit.tried = true;
+    std::string log;
+    if (!jit_compile(G.prog, gr->jit, log) && getenv("TDF_JIT_VERBOSE")) fprintf(stderr, "tdf: no generated kernels: %s\n", log.c_str());
+  }
+  const bool use_jit = gr->jit.step && gr->jit.small;
+  const int small_block = tag_machine_small_block(G.prog, use_jit);
   e.small_limit = 2u * (uint32_t)small_block;
   Ctrl hc{};
   uint32_t rounds = 0;
   const uint32_t poll = 16;
   for (;;) {
-    for (uint32_t i = 0; i < poll; ++i, ++rounds) launch_round(G.prog, e, blocks, small_block, 64, s);
+    for (uint32_t i = 0; i < poll; ++i, ++rounds) {
+      tdf_status lr = launch_round(G.prog, e, blocks, small_block, 64, gr->jit.small, gr->jit.step, s);
+      if (lr != TDF_OK) return lr;
+    }
     HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (hc.done) break;
@@ -369,6 +383,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
 using namespace tdf;
 
 tdf_graph::~tdf_graph() {
+  jit_release(jit);
   for (void* ev : events)
     if (ev) (void)hipEventDestroy((hipEvent_t)ev);
 }

@@ -1,0 +1,681 @@
+// Device side of the tag machine: one step = one pass over the frames that received a token.
+//
+//   fire    one lane per frame (= per call-context tag) evaluates the firing table of the
+//           frame's function; an entry fires when its sources are present under that tag
+//           (Section 2.2: all inputs hold tokens with the same tag).  Dead values (hiatons)
+//           propagate; Switch, Merge and dead calls follow the paper's equations.
+//   match   the tokens a sweep emits are delivered right after it:
+//           Call_i  <t,d> -> <i:t,d>: find-or-insert the key (frame of t, tag length, i) in
+//                   the tag-hash table (Section 3; Section 5.1: a new frame that stores the
+//                   label i) and write the argument into that frame;
+//           Return_i <i:t,d> -> <t,d>: the frame's own key names its label i and the frame of
+//                   t, which is the label check of Section 5.1 (only the Return_i of the call
+//                   that created the frame produces output); the value goes to the caller's
+//                   frame.
+//   compact the first token that reaches a frame in a step puts it on the next step's list;
+//           list and log entries are staged in LDS (wave ballot + prefix sum) and the
+//           workgroup reserves its range of each global list with one atomic per pass.
+//
+// A frame that is being swept may receive a token in the same step from another lane.  Such
+// a token sets a bit in the frame's arrival word of the *next* step and puts the frame on the
+// next list; the running sweep neither sees the bit nor reads the value.  Only the key and
+// the arrival words are written concurrently, with atomics.
+//
+// The sweep itself is a policy: the table interpreter below, or straight-line code generated
+// from the firing tables by the run-time compiler (jit.cpp).  Both use the same helpers.
+#pragma once
+#include "engine.h"
+
+namespace tdf {
+
+__device__ __forceinline__ void raise(Ctrl* c, int status) {
+  atomicCAS(&c->status, 0u, (uint32_t)(-status));
+}
+
+template <typename T> __device__ __forceinline__ T ld(const T* p) { return __atomic_load_n(p, __ATOMIC_RELAXED); }
+template <typename T> __device__ __forceinline__ void st(T* p, T v) { __atomic_store_n(p, v, __ATOMIC_RELAXED); }
+
+// Atomics on frame words at the scope of the running kernel: device scope when the whole grid
+// works on a step, workgroup scope when a single workgroup does (its atomics then stay in the
+// local L2; kernel boundaries make them visible to whoever runs the next step).
+template <int SCOPE> __device__ __forceinline__ uint32_t a_or(uint32_t* p, uint32_t v) {
+  return __hip_atomic_fetch_or(p, v, __ATOMIC_RELAXED, SCOPE);
+}
+template <int SCOPE> __device__ __forceinline__ uint32_t a_exch(uint32_t* p, uint32_t v) {
+  return __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, SCOPE);
+}
+template <int SCOPE> __device__ __forceinline__ unsigned long long a_cas(unsigned long long* p, unsigned long long expect,
+                                                                        unsigned long long v) {
+  __hip_atomic_compare_exchange_strong(p, &expect, v, __ATOMIC_RELAXED, __ATOMIC_RELAXED, SCOPE);
+  return expect;
+}
+
+// Per-workgroup staging of one pass.
+struct Stage {
+  uint32_t n_touched, n_leaf, n_cell, n_head, n_tags, n_tokens;
+  uint32_t max_probe, max_depth, max_level;
+  uint32_t base_touched, base_leaf, base_cell;
+};
+
+struct Sizes {
+  int max_values, max_stored, max_emit;
+};
+__host__ __device__ inline Sizes sizes_of(const DevProgram& P) {
+  Sizes z{1, 1, 1};
+  for (int f = 0; f < P.n_fn; ++f) {
+    z.max_values = z.max_values > P.fn[f].n_values ? z.max_values : P.fn[f].n_values;
+    z.max_stored = z.max_stored > P.fn[f].n_stored ? z.max_stored : P.fn[f].n_stored;
+    z.max_emit = z.max_emit > P.fn[f].n_emit ? z.max_emit : P.fn[f].n_emit;
+  }
+  return z;
+}
+// Dynamic LDS of a step kernel with `rb` lanes: value file (LDS sweeps only), cell / leaf /
+// touched staging, and the tokens a sweep has emitted but not yet delivered.
+__host__ __device__ inline size_t step_lds_bytes(const Sizes& z, int rb, bool lds_values) {
+  const size_t vals = lds_values ? (size_t)(z.max_values + z.max_stored) * 8 : 0;
+  return (size_t)rb * (vals + (size_t)z.max_emit * (4 + 8 + 4) + 8 + 16) + sizeof(Stage);
+}
+
+// ---- what a sweep sees of its lane ------------------------------------------------------------
+struct LaneCtx {
+  const Engine* e;
+  Ctrl* c;
+  Stage* S;
+  uint4* stg_cell;
+  uint2* stg_leaf;
+  long long* pend_val;     // [emission][lane]
+  uint32_t* pend_meta;
+  long long* lds_vals;     // LDS value file [value][lane] then [stored][lane] (LDS sweeps only)
+  int lds_stored_base;     // first stored row in lds_vals
+  int RB, tid;
+  bool active;
+  uint32_t frame;
+  int myfn, result_fn;
+  long long* slots;        // stored values of the frame (global memory)
+  unsigned long long fired;
+  uint32_t present;
+  int n_pend;
+  long long sv[8];         // the first eight stored values, loaded before the sweep
+  long long tc_v;          // forest entries of the last node looked at
+  int tc_left, tc_right, tc_token;
+};
+
+// ---- helpers shared by the interpreter and by generated sweeps ----------------------------------
+// The token emitted by a Call_i entry (meta = 0x80000000 | label | param << 8) or by the function
+// output (meta = 0: the Return token); delivered after the sweep.
+__device__ __forceinline__ void sw_emit(LaneCtx& x, bool go, uint32_t meta, long long v) {
+  if (go) {
+    x.pend_val[x.n_pend * x.RB + x.tid] = v;
+    x.pend_meta[x.n_pend * x.RB + x.tid] = meta;
+    ++x.n_pend;
+  }
+}
+// output of `result`
+__device__ __forceinline__ void sw_result(LaneCtx& x, bool go, int type, long long v) {
+  if (go) {
+    const uint32_t b = x.frame - x.e->cap;
+    if (type == T_INT) { if (x.e->out_i64) x.e->out_i64[b] = v; }
+    else if (type == T_VEC) x.e->root_ref[b] = (uint32_t)v;
+  }
+}
+// forest accessors at node index v: which = 0 isleaf, 1 left, 2 right, 3 token; sets `dead` and
+// raises an error for an index outside the forest
+__device__ __forceinline__ long long sw_tree(LaneCtx& x, long long v, int which, bool& dead) {
+  const Engine& e = *x.e;
+  if (v < 0 || v >= e.n_tree_nodes || e.left == nullptr) {
+    raise(x.c, TDF_ERR_BAD_ARG);
+    dead = true;
+    return 0;
+  }
+  if (x.tc_v != v) {   // one round trip serves isleaf / left / right / token of the same node
+    x.tc_left = e.left[v];
+    x.tc_right = e.right[v];
+    x.tc_token = e.token[v];
+    x.tc_v = v;
+  }
+  return which == 0 ? (long long)(x.tc_left < 0) : which == 1 ? x.tc_left : which == 2 ? x.tc_right : x.tc_token;
+}
+// EMBED: the leaf's state row is the row of this frame, level 0.  Whole wave must call.
+__device__ __forceinline__ void sw_embed(LaneCtx& x, bool on, int slot, long long stored, bool ap, bool ad, long long av,
+                                         long long& v, bool& p, bool& live) {
+  const bool had = on && ((x.present >> slot) & 1);
+  const bool go = on && ap && !ad && !had;
+  const bool ok = go && av >= 0;
+  if (go && !ok) raise(x.c, TDF_ERR_BAD_ARG);
+  const uint32_t pos = wave_alloc(ok, &x.S->n_leaf);
+  if (ok) {
+    x.stg_leaf[pos] = make_uint2(x.frame, (uint32_t)av);
+    x.slots[slot] = (long long)x.frame;
+    x.present |= 1u << slot;
+  }
+  v = had ? stored : (long long)x.frame;
+  p = had || ok;
+  live = p;
+}
+// RNN / LSTM cell: appended to the schedule log with its dependency level.  Whole wave must call.
+__device__ __forceinline__ void sw_cell(LaneCtx& x, bool on, int slot, long long stored, bool ap, bool ad, long long av,
+                                        bool bp, bool bd, long long bv, long long& v, bool& p, bool& live) {
+  const bool had = on && ((x.present >> slot) & 1);
+  const bool go = on && ap && bp && !ad && !bd && !had;
+  const uint32_t pos = wave_alloc(go, &x.S->n_cell);
+  long long r = stored;
+  if (go) {
+    const uint32_t la = (uint32_t)(av >> 32), lb = (uint32_t)(bv >> 32);
+    const uint32_t lvl = 1 + (la > lb ? la : lb);
+    x.stg_cell[pos] = make_uint4(x.frame, (uint32_t)av, (uint32_t)bv, lvl);
+    r = (long long)x.frame | ((long long)lvl << 32);
+    x.slots[slot] = r;
+    x.present |= 1u << slot;
+    atomicMax(&x.S->max_level, lvl);
+  }
+  v = r;
+  p = had || go;
+  live = p;
+}
+// CE_HEAD of `result`
+__device__ __forceinline__ void sw_head(LaneCtx& x, bool on, int slot, bool ap, bool ad, long long av, bool bp, bool bd,
+                                        long long bv, long long& v, bool& p, bool& live) {
+  const bool had = on && ((x.present >> slot) & 1);
+  const bool go = on && ap && bp && !ad && !bd && !had && x.myfn == x.result_fn;
+  if (go) {
+    const uint32_t inst = x.frame - x.e->cap;
+    x.e->head_row[inst] = (uint32_t)av;
+    x.e->head_label[inst] = (uint32_t)bv;
+    x.slots[slot] = inst;
+    x.present |= 1u << slot;
+  }
+  wave_count32(go, &x.S->n_head);
+  v = (long long)(x.frame - x.e->cap);
+  p = had || go;
+  live = p;
+}
+
+// ---- the table interpreter -------------------------------------------------------------------
+// NV > 0: the value file of a sweep (at most NV values, 8 stored values) lives in registers,
+// indexed with the wave-uniform value ids of the firing table; NV == 0: it lives in LDS.
+__device__ __forceinline__ uint32_t uni(uint32_t x) { return __builtin_amdgcn_readfirstlane(x); }
+__device__ __forceinline__ Instr fetch(const DevProgram& P, int idx) {
+  union { Instr i; uint32_t w[4]; } u;
+  u.i = P.instr[idx];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) u.w[k] = uni(u.w[k]);
+  return u.i;
+}
+
+struct Src {
+  long long v;
+  bool p, d;   // present, dead
+};
+
+template <int NV>
+struct InterpSweep {
+  static constexpr bool kLdsValues = NV == 0;
+  static __device__ void run(LaneCtx& x, const DevProgram& P) {
+    const int RB = x.RB, tid = x.tid;
+    long long rloc[NV > 0 ? NV : 1];
+    auto rd = [&](int idx) -> long long {
+      if constexpr (NV > 0) return rloc[idx]; else return x.lds_vals[idx * RB + tid];
+    };
+    auto wr = [&](int idx, long long v) {
+      if constexpr (NV > 0) rloc[idx] = v; else x.lds_vals[idx * RB + tid] = v;
+    };
+    auto rd_st = [&](int idx) -> long long {
+      if constexpr (NV > 0) return x.sv[idx]; else return x.lds_vals[(x.lds_stored_base + idx) * RB + tid];
+    };
+    const int n_fn = (int)uni((uint32_t)P.n_fn);
+    for (int f = 0; f < n_fn; ++f) {
+      const bool on = x.myfn == f;
+      if (__ballot(on) == 0) continue;
+      const int first_i = (int)uni(P.fn[f].first), count = (int)uni(P.fn[f].count);
+      const bool is_result = f == x.result_fn;
+      unsigned long long pres = 0, dead = 0;   // over value ids
+      Instr I_next = fetch(P, first_i);
+      for (int ip = 0; ip < count; ++ip) {
+        const Instr I = I_next;
+        if (ip + 1 < count) I_next = fetch(P, first_i + ip + 1);   // fetched while this entry runs
+        const unsigned long long ibit = 1ull << ip;
+        auto src = [&](int k) -> Src {
+          const uint8_t s = I.src[k];
+          if (s == SRC_IMM) return Src{I.imm, true, false};
+          return Src{rd(s), ((pres >> s) & 1) != 0, ((dead >> s) & 1) != 0};
+        };
+        auto put = [&](int dst, long long v, bool p, bool d) {
+          wr(dst, v);
+          if (p) pres |= 1ull << dst;
+          if (d) dead |= 1ull << dst;
+        };
+        bool live = false;   // this entry holds a live value under this tag
+        switch (I.op) {
+          case D_IN: {
+            const bool p = on && ((x.present >> I.aux) & 1);
+            put(I.dst, rd_st(I.aux), p, false);
+            live = p;
+            break;
+          }
+          case D_RET: {
+            const bool p = on && ((x.present >> I.aux) & 1);
+            bool all_p = true, any_d = false, any_arg = false;
+            for (int k = 0; k < 4; ++k) {
+              if (I.src[k] == SRC_NONE) continue;
+              any_arg = true;
+              all_p = all_p && ((pres >> I.src[k]) & 1);
+              any_d = any_d || ((dead >> I.src[k]) & 1);
+            }
+            const bool is_dead = on && !p && any_arg && all_p && any_d;   // the call never happened
+            put(I.dst, rd_st(I.aux), p || is_dead, is_dead);
+            live = p;
+            break;
+          }
+          case D_ADD: case D_SUB: case D_MUL: case D_EQ: case D_LT: {
+            const Src a = src(0), b = src(1);
+            const bool p = on && a.p && b.p, d = a.d || b.d;
+            const unsigned long long ua = (unsigned long long)a.v, ub = (unsigned long long)b.v;
+            long long r = 0;
+            if (I.op == D_ADD) r = (long long)(ua + ub);
+            else if (I.op == D_SUB) r = (long long)(ua - ub);
+            else if (I.op == D_MUL) r = (long long)(ua * ub);
+            else if (I.op == D_EQ) r = a.v == b.v;
+            else r = a.v < b.v;
+            put(I.dst, r, p, p && d);
+            live = p && !d;
+            break;
+          }
+          case D_ID: {
+            const Src a = src(0);
+            put(I.dst, a.v, on && a.p, on && a.p && a.d);
+            live = on && a.p && !a.d;
+            break;
+          }
+          case D_ISLEAF: case D_LEFT: case D_RIGHT: case D_TOKEN: {
+            const Src a = src(0);
+            const bool p = on && a.p;
+            bool d = a.d;
+            long long r = 0;
+            if (p && !d) r = sw_tree(x, a.v, I.op - D_ISLEAF, d);
+            put(I.dst, r, p, p && d);
+            live = p && !d;
+            break;
+          }
+          case D_SWITCH: {
+            const Src pr = src(0), da = src(1);
+            const bool p = on && pr.p && da.p, d = pr.d || da.d;
+            const bool t = pr.v != 0;
+            put(I.dst, da.v, p, p && (d || !t));
+            put(I.dst + 1, da.v, p, p && (d || t));
+            live = p && !d;
+            break;
+          }
+          case D_MERGE: {
+            bool any_live = false, all_p = true;
+            long long r = 0;
+            for (int k = 0; k < 4; ++k) {
+              if (I.src[k] == SRC_NONE) continue;
+              const Src a = src(k);
+              if (a.p && !a.d && !any_live) {
+                any_live = true;
+                r = a.v;
+              }
+              all_p = all_p && a.p;
+            }
+            const bool p = on && (any_live || all_p);
+            put(I.dst, r, p, p && !any_live);
+            live = on && any_live;
+            break;
+          }
+          case D_CALL: {
+            const Src a = src(0);
+            sw_emit(x, on && a.p && !a.d && !(x.fired & ibit), 0x80000000u | I.aux | ((uint32_t)I.aux2 << 8), a.v);
+            live = on && a.p && !a.d;
+            break;
+          }
+          case D_OUT: {
+            const Src a = src(0);
+            const bool go = on && a.p && !a.d && !(x.fired & ibit);
+            if (is_result) sw_result(x, go, I.aux, a.v);
+            else sw_emit(x, go, 0u, a.v);
+            live = on && a.p && !a.d;
+            break;
+          }
+          case D_EMBED: {
+            const Src a = src(0);
+            long long v;
+            bool p;
+            sw_embed(x, on, I.aux, rd_st(I.aux), a.p, a.d, a.v, v, p, live);
+            put(I.dst, v, p, false);
+            break;
+          }
+          case D_CELL: {
+            const Src a = src(0), b = src(1);
+            long long v;
+            bool p;
+            sw_cell(x, on, I.aux, rd_st(I.aux), a.p, a.d, a.v, b.p, b.d, b.v, v, p, live);
+            put(I.dst, v, p, false);
+            break;
+          }
+          case D_HEAD: {
+            const Src a = src(0), b = src(1);
+            long long v;
+            bool p;
+            sw_head(x, on, I.aux, a.p, a.d, a.v, b.p, b.d, b.v, v, p, live);
+            put(I.dst, v, p, false);
+            break;
+          }
+          default: break;
+        }
+        if (live) x.fired |= ibit;   // counted after the run, from the fired masks
+      }
+    }
+  }
+};
+
+// A token emitted by a sweep, while it is being delivered.
+struct Emission {
+  bool has, is_call;
+  uint32_t target, slot, bits, callee;
+  unsigned long long ckey, res;
+  long long val;
+};
+
+__device__ __forceinline__ void load_program(DevProgram* dst, const DevProgram* src) {
+  const uint32_t* s = reinterpret_cast<const uint32_t*>(src);
+  uint32_t* d = reinterpret_cast<uint32_t*>(dst);
+  for (int i = threadIdx.x; i < (int)(sizeof(DevProgram) / 4); i += blockDim.x) d[i] = s[i];
+  __syncthreads();
+}
+
+// One pass over the touched frames [0, n) of the current list; lane `first + tid` takes frames
+// i, i + lane_stride, ...  `c` is the control block the pass counts in: the global one, or a
+// workgroup's LDS copy.  The loop over passes is uniform for the workgroup.
+template <int SCOPE, class SW>
+__device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_t step, uint32_t n,
+                          uint32_t first, uint32_t lane_stride, char* lds) {
+  const int tid = threadIdx.x;
+  const int RB = blockDim.x;
+  Sizes z = sizes_of(P);
+  const int n_st = z.max_stored;
+  if (!SW::kLdsValues) z.max_values = z.max_stored = 0;   // no LDS value file
+  long long* lds_vals = reinterpret_cast<long long*>(lds);
+  uint4* stg_cell = reinterpret_cast<uint4*>(lds_vals + (size_t)(z.max_values + z.max_stored) * RB);
+  uint2* stg_leaf = reinterpret_cast<uint2*>(stg_cell + RB);
+  long long* pend_val = reinterpret_cast<long long*>(stg_leaf + RB);   // [max_emit][lane]
+  uint32_t* pend_meta = reinterpret_cast<uint32_t*>(pend_val + (size_t)z.max_emit * RB);
+  uint32_t* stg_touched = pend_meta + (size_t)z.max_emit * RB;         // [max_emit * RB]
+  Stage* S = reinterpret_cast<Stage*>(stg_touched + (size_t)z.max_emit * RB);
+  const int stride = (int)uni((uint32_t)P.frame_stride);
+  const uint32_t* cur_list = e.touched + (size_t)(step & 1) * e.touched_cap;
+  uint32_t* next_list = e.touched + (size_t)((step & 1) ^ 1) * e.touched_cap;
+  uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
+  const uint32_t word = step & 1;    // arrival word of the next step (this step reads word ^ 1)
+
+  for (uint32_t base = first; base < n; base += lane_stride) {
+    if (tid == 0) *S = Stage{};
+    __syncthreads();
+    LaneCtx x;
+    x.e = &e; x.c = c; x.S = S;
+    x.stg_cell = stg_cell; x.stg_leaf = stg_leaf; x.pend_val = pend_val; x.pend_meta = pend_meta;
+    x.lds_vals = lds_vals; x.lds_stored_base = z.max_values;
+    x.RB = RB; x.tid = tid;
+    const uint32_t i = base + tid;
+    x.active = i < n;
+    x.frame = x.active ? cur_list[i] : 0;
+    x.result_fn = (int)uni((uint32_t)P.result_fn);
+    FrameHdr* h = frame_at(e, stride, x.frame);
+    x.slots = frame_slots(h);
+    x.fired = 0; x.present = 0; x.myfn = -1; x.n_pend = 0; x.tc_v = -1;
+    x.tc_left = x.tc_right = x.tc_token = 0;
+    unsigned long long key = 0;
+    uint32_t depth = 0, pf_in = 0;
+    if (x.active) {
+      // tokens that arrived for this step; the word of the other parity belongs to the next
+      const uint32_t arr = a_exch<SCOPE>(&h->arrived[word ^ 1], 0u);
+      pf_in = h->present_fn;
+      key = h->key;
+      x.fired = h->fired;
+      const uint32_t pf = pf_in | arr;
+      depth = (uint32_t)(key >> 8) & 0xFFFFFFu;
+      x.present = pf & 0xFFFFFFu;
+      x.myfn = (int)(pf >> 24);
+    }
+    const unsigned long long fired_in = x.fired;
+    // stored values (meaningful where the present bit is set), all loads in flight at once
+#pragma unroll
+    for (int k = 0; k < 8; ++k) x.sv[k] = (x.active && k < n_st) ? x.slots[k] : 0;
+    if (SW::kLdsValues) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (k < n_st) lds_vals[(z.max_values + k) * RB + tid] = x.sv[k];
+      for (int k = 8; k < n_st; ++k) lds_vals[(z.max_values + k) * RB + tid] = x.active ? x.slots[k] : 0;
+    }
+
+    SW::run(x, P);   // ---- fire
+
+    // ---- match: deliver the emitted tokens, two at a time so that their atomics overlap ------
+    for (int e0 = 0; __ballot(x.active && e0 < x.n_pend) != 0; e0 += 2) {
+      Emission em[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        Emission& m = em[q];
+        m = Emission{};
+        m.has = x.active && e0 + q < x.n_pend;
+        if (m.has) {
+          const uint32_t meta = pend_meta[(e0 + q) * RB + tid];
+          m.val = pend_val[(e0 + q) * RB + tid];
+          m.is_call = (meta >> 31) != 0;
+          if (m.is_call) {
+            const uint32_t label = meta & 0xFFu, param = (meta >> 8) & 0xFFu;
+            m.callee = P.label_callee[label];
+            m.ckey = ((unsigned long long)(x.frame + 1u) << 32) | ((unsigned long long)(depth + 1u) << 8) | (label + 1u);
+            m.target = (uint32_t)mix64(m.ckey) & e.cap_mask;
+            m.slot = param;
+            m.bits = (1u << param) | (m.callee << 24);
+          } else {
+            m.target = (uint32_t)(key >> 32) - 1u;
+            m.slot = P.label_ret_slot[((uint32_t)key & 0xFFu) - 1u];
+            m.bits = 1u << m.slot;
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {   // both atomics in flight
+        Emission& m = em[q];
+        if (m.has) {
+          FrameHdr* th = frame_at(e, stride, m.target);
+          if (m.is_call) {
+            m.res = a_cas<SCOPE>(&th->key, 0ull, m.ckey);
+          } else {
+            frame_slots(th)[m.slot] = m.val;                    // read in a later step only
+            m.res = a_or<SCOPE>(&th->arrived[word], m.bits);
+          }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        Emission& m = em[q];
+        bool first_tok = false, inserted = false;
+        uint32_t probes = 1;
+        if (m.has && m.is_call) {
+          unsigned long long cur = m.res;
+          const uint32_t probe_limit = e.cap < 8192u ? e.cap : 8192u;
+          while (cur != 0 && cur != m.ckey && probes < probe_limit) {   // collisions: linear probing
+            m.target = (m.target + 1) & e.cap_mask;
+            ++probes;
+            cur = a_cas<SCOPE>(&frame_at(e, stride, m.target)->key, 0ull, m.ckey);
+          }
+          inserted = cur == 0;
+          if (cur == 0 || cur == m.ckey) {
+            FrameHdr* th = frame_at(e, stride, m.target);
+            frame_slots(th)[m.slot] = m.val;
+            if (inserted && P.fn[m.callee].n_params == 1) {
+              th->arrived[word] = m.bits;   // nobody else can reach a fresh single-parameter frame
+              first_tok = true;
+            } else {
+              first_tok = a_or<SCOPE>(&th->arrived[word], m.bits) == 0;
+            }
+          } else {
+            raise(c, TDF_ERR_TABLE_FULL);
+            m.has = false;
+          }
+        } else if (m.has) {
+          first_tok = m.res == 0;   // the arrival word was empty: first token for that frame in this step
+        }
+        const uint32_t pos = wave_alloc(first_tok, &S->n_touched);
+        if (first_tok) stg_touched[pos] = m.target;
+        wave_count32(inserted, &S->n_tags);
+        wave_count32(m.has, &S->n_tokens);
+        if (inserted) {
+          atomicMax(&S->max_probe, probes);
+          atomicMax(&S->max_depth, depth + 1);
+        }
+      }
+    }
+    if (x.active) {
+      if (x.fired != fired_in) h->fired = x.fired;
+      const uint32_t pf_out = x.present | ((uint32_t)x.myfn << 24);
+      if (pf_out != pf_in) h->present_fn = pf_out;
+    }
+
+    // ---- the workgroup reserves its ranges of the global lists and copies the entries out ---
+    __syncthreads();
+    if (tid == 0) {
+      S->base_touched = S->n_touched ? atomicAdd(next_count, S->n_touched) : 0;
+      S->base_leaf = S->n_leaf ? atomicAdd(&c->n_leaf, S->n_leaf) : 0;
+      S->base_cell = S->n_cell ? atomicAdd(&c->n_cell, S->n_cell) : 0;
+      if (S->n_head) atomicAdd(&c->n_head, S->n_head);
+      if (S->n_tags) atomicAdd(&c->n_tags, (unsigned long long)S->n_tags);
+      if (S->n_tokens) atomicAdd(&c->n_tokens, (unsigned long long)S->n_tokens);
+      if (S->max_probe > c->max_probe) atomicMax(&c->max_probe, S->max_probe);
+      if (S->max_depth > c->max_depth) atomicMax(&c->max_depth, S->max_depth);
+      if (S->max_level > c->max_level) atomicMax(&c->max_level, S->max_level);
+      if (S->base_touched + S->n_touched > e.touched_cap || S->base_leaf + S->n_leaf > e.log_cap ||
+          S->base_cell + S->n_cell > e.log_cap)
+        raise(c, TDF_ERR_TABLE_FULL);
+    }
+    __syncthreads();
+    for (uint32_t k = tid; k < S->n_touched; k += RB)
+      if (S->base_touched + k < e.touched_cap) next_list[S->base_touched + k] = stg_touched[k];
+    for (uint32_t k = tid; k < S->n_leaf; k += RB) {
+      const uint32_t j = S->base_leaf + k;
+      if (j < e.log_cap) {
+        e.leaf_row[j] = stg_leaf[k].x;
+        e.leaf_tok[j] = stg_leaf[k].y;
+      }
+    }
+    for (uint32_t k = tid; k < S->n_cell; k += RB) {
+      const uint32_t j = S->base_cell + k;
+      if (j < e.log_cap) {
+        const uint4 v = stg_cell[k];
+        e.cell_out[j] = v.x;
+        e.cell_l[j] = v.y;
+        e.cell_r[j] = v.z;
+        e.cell_lvl[j] = v.w;
+      }
+    }
+    __syncthreads();
+  }
+}
+
+// ---- step bookkeeping: reset the consumed list, count the step, detect the end ---------------
+__device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
+  const int parity = (int)(step & 1);
+  const uint32_t next = ld(&c->touched_count[parity ^ 1]);
+  uint32_t status = ld(&c->status);
+  st(&c->touched_count[parity], 0u);
+  c->step = step + 1;
+  if (ld(&c->n_tags) > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
+  if (step + 1 >= e.step_limit && next != 0 && status == 0) status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
+  if (status != 0) {
+    st(&c->status, status);
+    st(&c->touched_count[parity ^ 1], 0u);   // drain: nothing more fires
+    c->done = 1;
+  } else if (next == 0) {
+    c->done = 1;
+  }
+}
+
+// A step is "small" when its frames fit two passes of one workgroup; small steps run in the
+// single-workgroup kernel, the others in the grid-wide kernel.
+__device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
+
+constexpr int STEP_BLOCK = 128;   // lanes per workgroup of the grid-wide kernel
+
+// Grid-wide step: every workgroup takes a slice of the touched list; the last one to finish
+// closes the step.
+template <class SW>
+__device__ void step_grid(Engine e, char* lds, DevProgram* P_lds, bool* last) {
+  Ctrl* c = e.ctrl;
+  const uint32_t step = c->step;
+  const uint32_t n = ld(&c->touched_count[step & 1]);
+  if (c->done || n == 0 || step_is_small(e, n)) return;
+  if (blockIdx.x * blockDim.x < n) {   // workgroups without frames only take part in closing the step
+    load_program(P_lds, e.prog);
+    step_pass<__HIP_MEMORY_SCOPE_AGENT, SW>(*P_lds, e, c, step, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, lds);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __threadfence();
+    *last = atomicAdd(&c->blocks_done, 1u) == gridDim.x - 1;
+  }
+  __syncthreads();
+  if (*last && threadIdx.x == 0) {
+    __threadfence();
+    st(&c->blocks_done, 0u);
+    advance(e, c, step);
+  }
+}
+
+// Small steps: one workgroup runs step after step with workgroup barriers only and keeps the
+// control block (all list and log counters) in LDS.  Returns when the recursion is finished,
+// when a step is too large for one workgroup, or after max_steps steps.
+template <class SW>
+__device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_lds, Ctrl* lc_) {
+  Ctrl& lc = *lc_;
+  Ctrl* g = e.ctrl;
+  {
+    const uint32_t n0 = ld(&g->touched_count[g->step & 1]);
+    if (g->done || n0 == 0 || !step_is_small(e, n0)) return;   // nothing to do for this kernel
+  }
+  load_program(P_lds, e.prog);
+  if (threadIdx.x == 0) {
+    lc.touched_count[0] = ld(&g->touched_count[0]);
+    lc.touched_count[1] = ld(&g->touched_count[1]);
+    lc.step = g->step;
+    lc.n_leaf = ld(&g->n_leaf);
+    lc.n_cell = ld(&g->n_cell);
+    lc.n_head = ld(&g->n_head);
+    lc.status = ld(&g->status);
+    lc.done = g->done;
+    lc.max_probe = ld(&g->max_probe);
+    lc.max_depth = ld(&g->max_depth);
+    lc.max_level = ld(&g->max_level);
+    lc.blocks_done = 0;
+    lc.n_tags = ld(&g->n_tags);
+    lc.n_tokens = ld(&g->n_tokens);
+  }
+  __syncthreads();
+  for (int it = 0; it < max_steps; ++it) {
+    const uint32_t step = lc.step;
+    const uint32_t n = lc.touched_count[step & 1];
+    if (lc.done || n == 0 || !step_is_small(e, n)) break;   // uniform: lc changes only between barriers
+    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP, SW>(*P_lds, e, &lc, step, n, 0, blockDim.x, lds);
+    if (threadIdx.x == 0) advance(e, &lc, step);
+    __syncthreads();
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    st(&g->touched_count[0], lc.touched_count[0]);
+    st(&g->touched_count[1], lc.touched_count[1]);
+    g->step = lc.step;
+    st(&g->n_leaf, lc.n_leaf);
+    st(&g->n_cell, lc.n_cell);
+    st(&g->n_head, lc.n_head);
+    st(&g->status, lc.status);
+    g->done = lc.done;
+    st(&g->max_probe, lc.max_probe);
+    st(&g->max_depth, lc.max_depth);
+    st(&g->max_level, lc.max_level);
+    st(&g->n_tags, lc.n_tags);
+    st(&g->n_tokens, lc.n_tokens);
+  }
+}
+
+}  // namespace tdf

@@ -1,4 +1,4 @@
-// Internal structures shared by the host compiler (graph_build.cpp) and the device engine.
+// Host-side graph object shared by graph_build.cpp, jit.cpp and eval.hip.
 #pragma once
 #include <stdint.h>
 
@@ -6,67 +6,9 @@
 #include <vector>
 
 #include "tdf.h"
+#include "tdf_tables.h"
 
 namespace tdf {
-
-// ---- device firing tables -------------------------------------------------------------
-// Every function graph is compiled into a straight-line table of instructions in
-// topological order.  One lane evaluates the table for one frame (= one call-context tag):
-// an instruction fires when all its source values are present under that tag (the firing
-// rule of Section 2.2).  Values that arrive from other tags (arguments pushed by Call_i,
-// results popped by Return_i) and row references of vector operators are kept in the frame
-// record; everything else is recomputed from them on each sweep.
-enum DevOp : uint8_t {
-  D_IN = 0,   // aux = stored slot (= parameter index)
-  D_RET,      // Return_i seen from the caller: aux = stored slot, aux2 = label,
-              // src[] = argument values of the call (dead arguments => dead result)
-  D_ADD, D_SUB, D_MUL, D_EQ, D_LT, D_ID,
-  D_SWITCH,   // dst = true side, dst+1 = false side; src[0] = predicate, src[1] = data
-  D_MERGE,
-  D_CALL,     // Call_i for one parameter: src[0] = argument, aux = label, aux2 = parameter
-  D_OUT,      // function output: emits the Return token (or writes the program output)
-  D_ISLEAF, D_LEFT, D_RIGHT, D_TOKEN,
-  D_EMBED,    // aux = stored slot of the row reference
-  D_CELL,     // aux = stored slot
-  D_HEAD,     // aux = stored slot
-};
-
-constexpr uint8_t SRC_IMM = 0xFF;   // source is the instruction's immediate
-constexpr uint8_t SRC_NONE = 0xFE;
-
-struct Instr {
-  uint8_t op, dst, aux, aux2;
-  uint8_t src[4];
-  int64_t imm;
-};
-static_assert(sizeof(Instr) == 16, "Instr must be 16 bytes");
-
-constexpr int MAX_FN = 4;
-constexpr int MAX_INSTR = 176;
-constexpr int MAX_LABELS = 32;
-constexpr int MAX_VALUES = 64;   // per function
-constexpr int MAX_STORED = 24;   // per function
-
-enum ValueType : uint8_t { T_INT = 0, T_VEC = 1, T_LOSS = 2 };
-
-struct DevFn {
-  uint16_t first, count;   // instruction range
-  uint8_t n_values, n_stored, out_type, n_params;
-  uint8_t n_emit;          // entries that emit a token (Call_i per parameter, function output)
-  uint8_t n_call_labels;   // distinct call labels in the body (capped at 6), for prefetching
-  uint8_t call_labels[6];
-};
-
-// Passed to the kernels by value (kernel-argument segment: uniform, scalar-cached reads).
-struct DevProgram {
-  int32_t n_fn, result_fn, n_labels, frame_stride;   // frame_stride in bytes
-  DevFn fn[MAX_FN];
-  uint8_t label_callee[MAX_LABELS];     // function entered by Call_i
-  uint8_t label_ret_slot[MAX_LABELS];   // stored slot of Return_i's value in the caller's frame
-  uint16_t stat_idx[MAX_INSTR];         // static-graph node counted when the instruction fires live
-  Instr instr[MAX_INSTR];
-};
-static_assert(sizeof(DevProgram) <= 3900, "DevProgram must fit the kernel-argument segment");
 
 // ---- host graph object ----------------------------------------------------------------
 struct Graph {
@@ -82,10 +24,23 @@ struct Graph {
 
 void set_error(const std::string& msg);
 
+// Run-time generated step kernels for one program (jit.cpp).  Returns false (and leaves the
+// handles null) when the run-time compiler is unavailable, disabled (TDF_NO_JIT=1) or fails;
+// the table interpreter is used then.
+struct JitKernels {
+  void* module = nullptr;   // hipModule_t
+  void* step = nullptr;     // hipFunction_t of the grid-wide step kernel
+  void* small = nullptr;    // hipFunction_t of the single-workgroup kernel
+  bool tried = false;
+};
+bool jit_compile(const DevProgram& P, JitKernels& out, std::string& log);
+void jit_release(JitKernels& k);
+
 }  // namespace tdf
 
 struct tdf_graph {
   tdf::Graph g;
+  tdf::JitKernels jit;
   void* events[2 * TDF_PHASE_COUNT] = {nullptr};   // hipEvent_t pairs, created on first use
   ~tdf_graph();
 };

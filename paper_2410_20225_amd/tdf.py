@@ -96,6 +96,8 @@ lib.tdf_graph_destroy.argtypes = [C.c_void_p]
 lib.tdf_graph_destroy.restype = None
 lib.tdf_graph_info.argtypes = [C.c_void_p, C.POINTER(GraphInfo)]
 lib.tdf_graph_info.restype = C.c_int
+lib.tdf_graph_precompile.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_size_t)]
+lib.tdf_graph_precompile.restype = C.c_int
 lib.tdf_workspace_size.argtypes = [C.c_void_p, C.POINTER(Inputs), C.c_int, C.POINTER(C.c_size_t)]
 lib.tdf_workspace_size.restype = C.c_int
 lib.tdf_eval.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Outputs), C.c_void_p, C.c_size_t,
@@ -131,7 +133,7 @@ class Graph:
         self.handle = handle
 
     def __del__(self):
-        if getattr(self, "handle", None):
+        if getattr(self, "handle", None) and lib is not None:   # lib is None at interpreter shutdown
             lib.tdf_graph_destroy(self.handle)
             self.handle = None
 
@@ -167,6 +169,15 @@ def graph_info(graph):
     edges = [dict(src=e.src, src_port=e.src_port, dst=e.dst, dst_slot=e.dst_slot, is_control=e.is_control)
              for e in (info.edges[i] for i in range(info.n_edges))]
     return dict(nodes=nodes, edges=edges, n_labels=info.n_labels)
+
+
+def graph_precompile(graph, arch="gfx950"):
+    """Compiles the specialised step kernels of `graph` for `arch`; returns the code size in bytes."""
+    n = C.c_size_t()
+    st = lib.tdf_graph_precompile(graph.handle, arch.encode(), C.byref(n))
+    if st != OK:
+        raise TdfError(st, "tdf_graph_precompile")
+    return n.value
 
 
 def make_inputs(n_instances, args=None, n_args=0, left=None, right=None, token=None, dtype=F32, hidden=0,
