@@ -130,7 +130,7 @@ def main():
         # delivery, touched-list entry, token write+read), see the design doc
         algo = 128.0 * n_tags
         ms = phase[0] / a.steps
-        roof = {"bound": "hbm", "kernel": "k_fire+k_match (all steps)", "achieved": algo / (ms * 1e-3) / 1e9,
+        roof = {"bound": "hbm", "kernel": "tag machine step kernels (all steps)", "achieved": algo / (ms * 1e-3) / 1e9,
                 "peak": PEAK_HBM / 1e9, "unit": "GB/s", "traffic": None}
     else:
         ms = phase[3] / a.steps

@@ -27,8 +27,11 @@ struct Ctrl {
 
 // Frame record = one slot of the tag-hash table = one call-context tag (Section 5.1: a
 // frame holds the label i of the Call_i that created it and a reference to the previous
-// scope).  The key packs (parent frame + 1, tag length, label + 1); 0 means empty.  The slot
-// index is the frame id, so inserting a tag and allocating its frame are one compare-and-swap.
+// scope).  The key packs (parent frame + 1, tag length, label + 1).  The keys of all slots
+// are also kept in a dense array of their own, which is what insertions probe (eight slots
+// per 64-byte line); the slot index is the frame id, so inserting a tag and allocating its
+// frame are one compare-and-swap.  The lane that inserts a key writes the frame's header;
+// frames of empty slots hold stale bytes and are never read.
 //
 // Tokens delivered during step s set bits in the arrival word of step s+1; the sweep of step
 // s+1 takes that word (exchange with 0) and folds it into present_fn, which only the sweeping
@@ -50,6 +53,7 @@ struct Engine {
   const DevProgram* prog;           // firing tables in the workspace (copied there once per call)
   Ctrl* ctrl;
   unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
+  unsigned long long* keys;         // [cap] tag-hash table: the key of slot f, 0 = empty (frame f is then unused)
   char* frames;                     // (cap + B) records of frame_stride bytes
   uint32_t cap, cap_mask, n_inst, max_tags;
   uint32_t* touched;                // two lists of touched_cap frame ids, by step parity
@@ -141,12 +145,21 @@ inline __device__ void wave_count(bool take, unsigned long long* counter) {
     atomicAdd(counter, (unsigned long long)__popcll(m));
 }
 
-inline __device__ void wave_max(uint32_t v, uint32_t* target) {
-  for (int off = 32; off > 0; off >>= 1) {
-    uint32_t o = __shfl_xor(v, off);
-    v = o > v ? o : v;
-  }
-  if (lane_id() == 0 && v > *target) atomicMax(target, v);
+// Maximum over the 64 lanes of a wave (row-wise DPP shifts, then row broadcasts; lane 63 holds
+// the result).  Must be reached by every lane of the wave; lanes without a value pass 0.
+template <int CTRL, int ROW_MASK>
+inline __device__ uint32_t dpp_umax(uint32_t x) {
+  const uint32_t o = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, ROW_MASK, 0xf, false);
+  return o > x ? o : x;
+}
+inline __device__ uint32_t wave_umax(uint32_t v) {
+  v = dpp_umax<0x111, 0xf>(v);   // row_shr:1
+  v = dpp_umax<0x112, 0xf>(v);   // row_shr:2
+  v = dpp_umax<0x114, 0xf>(v);   // row_shr:4
+  v = dpp_umax<0x118, 0xf>(v);   // row_shr:8
+  v = dpp_umax<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
+  v = dpp_umax<0x143, 0xc>(v);   // row_bcast:31 into rows 2 and 3
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 // ---- vector side ----------------------------------------------------------------------

@@ -93,7 +93,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   P.max_cells = e.log_cap;
 
   auto at = [&](size_t off) { return base ? base + off : nullptr; };
-  // --- cleared region: control block, counters, level histograms, token histograms, frames
+  // --- cleared region: control block, counters, level histograms, token histograms, tag keys
   L.zero_begin = L.total;
   P.off_ctrl = L.take(sizeof(Ctrl));
   P.off_fire = L.take(sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS);
@@ -104,8 +104,9 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     P.off_tok_count = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
     P.off_tok_fill = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
   }
-  P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));
+  size_t off_keys = L.take(sizeof(unsigned long long) * (size_t)e.cap);
   L.zero_end = L.total;
+  P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));   // headers are written on insertion
   // --- the rest is written before it is read
   size_t off_prog = L.take(sizeof(DevProgram));
   size_t off_touched = L.take(sizeof(uint32_t) * 2 * (size_t)e.touched_cap);
@@ -124,6 +125,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.level_count = (uint32_t*)at(off_lcount);
   e.level_fill = (uint32_t*)at(off_lfill);
   e.level_off = (uint32_t*)at(off_loff);
+  e.keys = (unsigned long long*)at(off_keys);
   e.frames = at(P.off_frames);
   e.touched = (uint32_t*)at(off_touched);
   e.root_ref = (uint32_t*)at(off_root);
@@ -347,6 +349,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   HIP_TRY(hipGetLastError());
 
   if (stats) {
+    HIP_TRY(hipStreamSynchronize(s));   // the last phase event may still be pending
     memset(stats, 0, sizeof(*stats));
     stats->n_tags = (int64_t)hc.n_tags;
     stats->n_steps = (int64_t)hc.step;

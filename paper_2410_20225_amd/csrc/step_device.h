@@ -44,6 +44,9 @@ template <int SCOPE> __device__ __forceinline__ uint32_t a_or(uint32_t* p, uint3
 template <int SCOPE> __device__ __forceinline__ uint32_t a_exch(uint32_t* p, uint32_t v) {
   return __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, SCOPE);
 }
+template <int SCOPE> __device__ __forceinline__ unsigned long long a_ld(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE);
+}
 template <int SCOPE> __device__ __forceinline__ unsigned long long a_cas(unsigned long long* p, unsigned long long expect,
                                                                         unsigned long long v) {
   __hip_atomic_compare_exchange_strong(p, &expect, v, __ATOMIC_RELAXED, __ATOMIC_RELAXED, SCOPE);
@@ -88,6 +91,7 @@ struct LaneCtx {
   long long* lds_vals;     // LDS value file [value][lane] then [stored][lane] (LDS sweeps only)
   int lds_stored_base;     // first stored row in lds_vals
   int RB, tid;
+  bool direct;             // single-workgroup run: list and log entries go straight to the global arrays
   bool active;
   uint32_t frame;
   int myfn, result_fn;
@@ -96,6 +100,7 @@ struct LaneCtx {
   uint32_t present;
   int n_pend;
   long long sv[8];         // the first eight stored values, loaded before the sweep
+  uint32_t mx_level;       // largest cell level this lane produced in the pass
   long long tc_v;          // forest entries of the last node looked at
   int tc_left, tc_right, tc_token;
 };
@@ -142,9 +147,16 @@ __device__ __forceinline__ void sw_embed(LaneCtx& x, bool on, int slot, long lon
   const bool go = on && ap && !ad && !had;
   const bool ok = go && av >= 0;
   if (go && !ok) raise(x.c, TDF_ERR_BAD_ARG);
-  const uint32_t pos = wave_alloc(ok, &x.S->n_leaf);
+  const uint32_t pos = wave_alloc(ok, x.direct ? &x.c->n_leaf : &x.S->n_leaf);
   if (ok) {
-    x.stg_leaf[pos] = make_uint2(x.frame, (uint32_t)av);
+    if (!x.direct) {
+      x.stg_leaf[pos] = make_uint2(x.frame, (uint32_t)av);
+    } else if (pos < x.e->log_cap) {
+      x.e->leaf_row[pos] = x.frame;
+      x.e->leaf_tok[pos] = (uint32_t)av;
+    } else {
+      raise(x.c, TDF_ERR_TABLE_FULL);
+    }
     x.slots[slot] = (long long)x.frame;
     x.present |= 1u << slot;
   }
@@ -157,16 +169,25 @@ __device__ __forceinline__ void sw_cell(LaneCtx& x, bool on, int slot, long long
                                         bool bp, bool bd, long long bv, long long& v, bool& p, bool& live) {
   const bool had = on && ((x.present >> slot) & 1);
   const bool go = on && ap && bp && !ad && !bd && !had;
-  const uint32_t pos = wave_alloc(go, &x.S->n_cell);
+  const uint32_t pos = wave_alloc(go, x.direct ? &x.c->n_cell : &x.S->n_cell);
   long long r = stored;
   if (go) {
     const uint32_t la = (uint32_t)(av >> 32), lb = (uint32_t)(bv >> 32);
     const uint32_t lvl = 1 + (la > lb ? la : lb);
-    x.stg_cell[pos] = make_uint4(x.frame, (uint32_t)av, (uint32_t)bv, lvl);
+    if (!x.direct) {
+      x.stg_cell[pos] = make_uint4(x.frame, (uint32_t)av, (uint32_t)bv, lvl);
+    } else if (pos < x.e->log_cap) {
+      x.e->cell_out[pos] = x.frame;
+      x.e->cell_l[pos] = (uint32_t)av;
+      x.e->cell_r[pos] = (uint32_t)bv;
+      x.e->cell_lvl[pos] = lvl;
+    } else {
+      raise(x.c, TDF_ERR_TABLE_FULL);
+    }
     r = (long long)x.frame | ((long long)lvl << 32);
     x.slots[slot] = r;
     x.present |= 1u << slot;
-    atomicMax(&x.S->max_level, lvl);
+    x.mx_level = lvl > x.mx_level ? lvl : x.mx_level;
   }
   v = r;
   p = had || go;
@@ -184,7 +205,7 @@ __device__ __forceinline__ void sw_head(LaneCtx& x, bool on, int slot, bool ap, 
     x.slots[slot] = inst;
     x.present |= 1u << slot;
   }
-  wave_count32(go, &x.S->n_head);
+  wave_count32(go, x.direct ? &x.c->n_head : &x.S->n_head);
   v = (long long)(x.frame - x.e->cap);
   p = had || go;
   live = p;
@@ -407,10 +428,18 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
   uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
   const uint32_t word = step & 1;    // arrival word of the next step (this step reads word ^ 1)
 
+  // One workgroup alone (its control block `c` is in LDS): positions in the global lists come
+  // straight from the counters in `c`, without staging and without barriers between passes.
+  constexpr bool kDirect = SCOPE == __HIP_MEMORY_SCOPE_WORKGROUP;
+  uint32_t cnt_tags = 0, cnt_tokens = 0;   // per wave, wave-uniform
+
   for (uint32_t base = first; base < n; base += lane_stride) {
-    if (tid == 0) *S = Stage{};
-    __syncthreads();
+    if (!kDirect) {
+      if (tid == 0) *S = Stage{};
+      __syncthreads();
+    }
     LaneCtx x;
+    x.direct = kDirect;
     x.e = &e; x.c = c; x.S = S;
     x.stg_cell = stg_cell; x.stg_leaf = stg_leaf; x.pend_val = pend_val; x.pend_meta = pend_meta;
     x.lds_vals = lds_vals; x.lds_stored_base = z.max_values;
@@ -421,7 +450,8 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     x.result_fn = (int)uni((uint32_t)P.result_fn);
     FrameHdr* h = frame_at(e, stride, x.frame);
     x.slots = frame_slots(h);
-    x.fired = 0; x.present = 0; x.myfn = -1; x.n_pend = 0; x.tc_v = -1;
+    x.fired = 0; x.present = 0; x.myfn = -1; x.n_pend = 0; x.tc_v = -1; x.mx_level = 0;
+    uint32_t mx_probe = 0, mx_depth = 0;
     x.tc_left = x.tc_right = x.tc_token = 0;
     unsigned long long key = 0;
     uint32_t depth = 0, pf_in = 0;
@@ -475,38 +505,113 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
           }
         }
       }
+      // two parameters of one call: the second token follows the first into its frame
+      const bool same_call = em[0].has && em[1].has && em[0].is_call && em[1].is_call && em[0].ckey == em[1].ckey;
 #pragma unroll
       for (int q = 0; q < 2; ++q) {   // both atomics in flight
         Emission& m = em[q];
         if (m.has) {
-          FrameHdr* th = frame_at(e, stride, m.target);
           if (m.is_call) {
-            m.res = a_cas<SCOPE>(&th->key, 0ull, m.ckey);
+            if (!(q == 1 && same_call)) m.res = a_cas<SCOPE>(&e.keys[m.target], 0ull, m.ckey);
           } else {
+            FrameHdr* th = frame_at(e, stride, m.target);
             frame_slots(th)[m.slot] = m.val;                    // read in a later step only
             m.res = a_or<SCOPE>(&th->arrived[word], m.bits);
           }
         }
       }
+      // collisions at the home slot: linear probing, eight key slots per round trip.  First one
+      // round for both tokens at once (load the next eight keys, claim the first empty one) ...
+      bool need[2], found[2], ins[2];
+      uint32_t probes[2];
+      unsigned long long w[2][8], claim[2];
+      int cj[2];
+#pragma unroll
+      for (int q = 0; q < 2; ++q) {
+        const Emission& m = em[q];
+        const bool own = m.has && m.is_call && !(q == 1 && same_call);
+        ins[q] = own && m.res == 0;
+        found[q] = own && (m.res == 0 || m.res == m.ckey);
+        need[q] = own && !found[q];
+        probes[q] = 1;
+        cj[q] = 8;
+        claim[q] = 1;
+      }
+      if (__ballot(need[0] || need[1]) != 0) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+          if (need[q]) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[q][j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[(em[q].target + 1u + j) & e.cap_mask]);
+          }
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+          if (need[q]) {
+#pragma unroll
+            for (int j = 7; j >= 0; --j)
+              if (w[q][j] == 0 || w[q][j] == em[q].ckey) {   // ends at the first such slot
+                cj[q] = j;
+                claim[q] = w[q][j];
+              }
+            if (cj[q] < 8 && claim[q] == 0)
+              claim[q] = a_cas<SCOPE>(&e.keys[(em[q].target + 1u + cj[q]) & e.cap_mask], 0ull, em[q].ckey);
+          }
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+          if (need[q] && cj[q] < 8 && (claim[q] == 0 || claim[q] == em[q].ckey)) {
+            ins[q] = claim[q] == 0;
+            found[q] = true;
+            need[q] = false;
+            em[q].target = (em[q].target + 1u + cj[q]) & e.cap_mask;
+            probes[q] = 2 + cj[q];
+          }
+      }
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         Emission& m = em[q];
-        bool first_tok = false, inserted = false;
-        uint32_t probes = 1;
+        bool first_tok = false;
         if (m.has && m.is_call) {
-          unsigned long long cur = m.res;
-          const uint32_t probe_limit = e.cap < 8192u ? e.cap : 8192u;
-          while (cur != 0 && cur != m.ckey && probes < probe_limit) {   // collisions: linear probing
-            m.target = (m.target + 1) & e.cap_mask;
-            ++probes;
-            cur = a_cas<SCOPE>(&frame_at(e, stride, m.target)->key, 0ull, m.ckey);
+          if (q == 1 && same_call) {
+            found[1] = em[0].has;       // em[0] failed only if the table is full
+            m.target = em[0].target;
           }
-          inserted = cur == 0;
-          if (cur == 0 || cur == m.ckey) {
+          // ... then, rarely (a lost race, or eight occupied slots in a row), one token at a time
+          const uint32_t probe_limit = e.cap < 8192u ? e.cap : 8192u;
+          while (need[q] && probes[q] < probe_limit) {
+            unsigned long long v[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v[j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[(m.target + 1u + j) & e.cap_mask]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              if (!need[q]) break;
+              if (v[j] == 0) {   // looked empty: claim it, or learn who did
+                v[j] = a_cas<SCOPE>(&e.keys[(m.target + 1u + j) & e.cap_mask], 0ull, m.ckey);
+                ins[q] = v[j] == 0;
+              }
+              if (ins[q] || v[j] == m.ckey) {
+                found[q] = true;
+                need[q] = false;
+                m.target = (m.target + 1u + j) & e.cap_mask;
+                probes[q] += j + 1;
+              }
+            }
+            if (need[q]) {
+              m.target = (m.target + 8u) & e.cap_mask;
+              probes[q] += 8;
+            }
+          }
+          const bool inserted = ins[q];
+          if (found[q]) {
             FrameHdr* th = frame_at(e, stride, m.target);
             frame_slots(th)[m.slot] = m.val;
-            if (inserted && P.fn[m.callee].n_params == 1) {
-              th->arrived[word] = m.bits;   // nobody else can reach a fresh single-parameter frame
+            if (inserted) {
+              // a fresh frame: nobody else can reach it in this step, so its creator writes the header
+              th->key = m.ckey;
+              th->fired = 0;
+              th->present_fn = 0;
+              th->pad = 0;
+              th->arrived[word ^ 1] = 0;
+              th->arrived[word] = m.bits;
               first_tok = true;
             } else {
               first_tok = a_or<SCOPE>(&th->arrived[word], m.bits) == 0;
@@ -518,13 +623,30 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         } else if (m.has) {
           first_tok = m.res == 0;   // the arrival word was empty: first token for that frame in this step
         }
-        const uint32_t pos = wave_alloc(first_tok, &S->n_touched);
-        if (first_tok) stg_touched[pos] = m.target;
-        wave_count32(inserted, &S->n_tags);
-        wave_count32(m.has, &S->n_tokens);
-        if (inserted) {
-          atomicMax(&S->max_probe, probes);
-          atomicMax(&S->max_depth, depth + 1);
+        const uint32_t pos = wave_alloc(first_tok, kDirect ? next_count : &S->n_touched);
+        if (first_tok) {
+          if (!kDirect) stg_touched[pos] = m.target;
+          else if (pos < e.touched_cap) next_list[pos] = m.target;
+          else raise(c, TDF_ERR_TABLE_FULL);
+        }
+        cnt_tags += (uint32_t)__popcll(__ballot(ins[q]));
+        cnt_tokens += (uint32_t)__popcll(__ballot(m.has));
+        if (ins[q]) {
+          mx_probe = probes[q] > mx_probe ? probes[q] : mx_probe;
+          mx_depth = depth + 1;
+        }
+      }
+    }
+    {   // per-wave maxima of the pass
+      const uint32_t wl = wave_umax(x.mx_level), wp = wave_umax(mx_probe), wd = wave_umax(mx_depth);
+      if ((tid & 63) == 0) {
+        if (wl) atomicMax(kDirect ? &c->max_level : &S->max_level, wl);
+        if (wp) atomicMax(kDirect ? &c->max_probe : &S->max_probe, wp);
+        if (wd) atomicMax(kDirect ? &c->max_depth : &S->max_depth, wd);
+        if (!kDirect) {
+          if (cnt_tags) atomicAdd(&S->n_tags, cnt_tags);
+          if (cnt_tokens) atomicAdd(&S->n_tokens, cnt_tokens);
+          cnt_tags = cnt_tokens = 0;
         }
       }
     }
@@ -534,6 +656,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       if (pf_out != pf_in) h->present_fn = pf_out;
     }
 
+    if (kDirect) continue;
     // ---- the workgroup reserves its ranges of the global lists and copies the entries out ---
     __syncthreads();
     if (tid == 0) {
@@ -569,6 +692,13 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         e.cell_r[j] = v.z;
         e.cell_lvl[j] = v.w;
       }
+    }
+    __syncthreads();
+  }
+  if (kDirect) {
+    if ((tid & 63) == 0) {
+      if (cnt_tags) atomicAdd(&c->n_tags, (unsigned long long)cnt_tags);
+      if (cnt_tokens) atomicAdd(&c->n_tokens, (unsigned long long)cnt_tokens);
     }
     __syncthreads();
   }

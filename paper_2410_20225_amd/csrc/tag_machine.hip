@@ -48,6 +48,7 @@ __global__ void k_count_fired(DevProgram P, Engine e) {
   __syncthreads();
   const uint32_t total = e.cap + e.n_inst;
   for (uint32_t f = blockIdx.x * blockDim.x + threadIdx.x; f < total; f += gridDim.x * blockDim.x) {
+    if (f < e.cap && e.keys[f] == 0) continue;   // empty slot: the frame holds stale bytes
     const FrameHdr* h = frame_at(e, P.frame_stride, f);
     unsigned long long fired = h->fired;
     if (fired == 0) continue;
