@@ -21,7 +21,10 @@ struct Ctrl {
   uint32_t status;           // 0, or -(tdf_status) raised on the device
   uint32_t done;
   uint32_t max_probe, max_depth, max_level;
-  uint32_t blocks_done;      // workgroups of the running match kernel that have finished
+  uint32_t bar_count;        // grid barrier of the grid-wide step kernel: arrivals (monotone)
+  uint32_t bar_gen;          // ... and completed barriers
+  uint32_t xcc_mask;         // accelerator dies that ran a die-local grid-wide step kernel
+  uint32_t pad0;
   unsigned long long n_tags, n_tokens;
 };
 

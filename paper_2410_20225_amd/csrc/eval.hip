@@ -14,8 +14,8 @@
 namespace tdf {
 
 void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
-tdf_status launch_round(const DevProgram& P, const Engine& e, int blocks, int small_block, int small_steps,
-                        void* jit_small, void* jit_step, hipStream_t s);
+tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool local, int small_block, int max_steps,
+                        long long spin_ticks, const JitKernels& jit, hipStream_t s);
 int tag_machine_small_block(const DevProgram& P, bool jit);
 void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s);
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s);
@@ -217,6 +217,7 @@ tdf_status status_from_device(uint32_t st) {
     case TDF_ERR_TABLE_FULL: set_error("device: tag table, frame list or state rows exhausted (raise max_tags)"); break;
     case TDF_ERR_STEP_LIMIT: set_error("device: step limit reached before the recursion finished"); break;
     case TDF_ERR_BAD_ARG: set_error("device: tree node index or token id out of range"); break;
+    case TDF_ERR_DEVICE: set_error("device: a workgroup waited too long at the grid barrier of the step kernel"); break;
     default: set_error("device: unknown status"); code = TDF_ERR_DEVICE; break;
   }
   return (tdf_status)code;
@@ -263,33 +264,52 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   e.out_i64 = (long long*)out->out_i64;
   char* base = (char*)workspace;
 
-  begin(TDF_PHASE_TAGS);
-  HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
-  HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
-  launch_seed(G.prog, e, s);
-
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
-  const int blocks = 768;
+  // The grid-wide kernel synchronises its workgroups with a barrier in memory: no more
+  // workgroups than compute units, so that all of them are resident together.
+  int dev_id = 0, cus = 0;
+  HIP_TRY(hipGetDevice(&dev_id));
+  HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev_id));
+  if (cus < 1) { set_error("no compute units"); return TDF_ERR_DEVICE; }
+  // longest wait at that barrier before the run is abandoned (milliseconds; 100 MHz ticks)
+  long long wait_ms = 2000;
+  if (const char* w = getenv("TDF_GRID_WAIT_MS")) wait_ms = atoll(w);
+  const long long spin_ticks = wait_ms * 100000;
+  if (const char* w = getenv("TDF_NO_DIE_LOCAL")) if (w[0] == '1') gr->die_local = false;
   // step kernels generated for this program (first call only; falls back to the interpreter)
   if (!gr->jit.tried) {
     gr->jit.tried = true;
     std::string log;
     if (!jit_compile(G.prog, gr->jit, log) && getenv("TDF_JIT_VERBOSE")) fprintf(stderr, "tdf: no generated kernels: %s\n", log.c_str());
   }
-  const bool use_jit = gr->jit.step && gr->jit.small;
+  const bool use_jit = gr->jit.step && gr->jit.small && gr->jit.step_local;
   const int small_block = tag_machine_small_block(G.prog, use_jit);
   e.small_limit = 2u * (uint32_t)small_block;
   Ctrl hc{};
   uint32_t rounds = 0;
-  const uint32_t poll = 16;
+  const uint32_t poll = 2;          // rounds queued between two looks at the control block
+  const int max_steps = 4096;       // steps per kernel launch
+  begin(TDF_PHASE_TAGS);
   for (;;) {
-    for (uint32_t i = 0; i < poll; ++i, ++rounds) {
-      tdf_status lr = launch_round(G.prog, e, blocks, small_block, 64, gr->jit.small, gr->jit.step, s);
-      if (lr != TDF_OK) return lr;
+    HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
+    HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
+    launch_seed(G.prog, e, s);
+    for (;;) {
+      for (uint32_t i = 0; i < poll; ++i, ++rounds) {
+        tdf_status lr = launch_round(G.prog, e, cus, gr->die_local, small_block, max_steps, spin_ticks, gr->jit, s);
+        if (lr != TDF_OK) return lr;
+      }
+      HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipStreamSynchronize(s));
+      if (hc.done || hc.status) break;
     }
-    HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    if (hc.done) break;
+    // The die-local kernel relies on its workgroups sharing one L2.  If the GPU placed them on
+    // several dies, the run is void: repeat it with the kernel that synchronises through memory.
+    if (gr->die_local && (hc.xcc_mask & (hc.xcc_mask - 1)) != 0) {
+      gr->die_local = false;
+      continue;
+    }
+    break;
   }
   end(TDF_PHASE_TAGS, 2 + 2ll * rounds);
   tdf_status dev = status_from_device(hc.status);

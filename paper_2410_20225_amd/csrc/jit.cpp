@@ -184,10 +184,14 @@ struct Gen {
     o << "    (void)P;\n";
     for (int f = 0; f < P.n_fn; ++f) function(f);
     o << "  }\n};\n}  // namespace tdf\n";
-    o << "extern \"C\" __global__ void __launch_bounds__(128) tdf_generated_step(tdf::Engine e) {\n";
+    o << "extern \"C\" __global__ void __launch_bounds__(256) tdf_generated_step(tdf::Engine e, int max_steps, long long spin_ticks) {\n";
     o << "  extern __shared__ __attribute__((aligned(16))) char lds[];\n";
-    o << "  __shared__ tdf::DevProgram P;\n  __shared__ bool last;\n";
-    o << "  tdf::step_grid<tdf::GeneratedSweep>(e, lds, &P, &last);\n}\n";
+    o << "  __shared__ tdf::DevProgram P;\n  __shared__ uint32_t sh[4];\n";
+    o << "  tdf::steps_grid<false, tdf::GeneratedSweep>(e, max_steps, spin_ticks, lds, &P, sh);\n}\n";
+    o << "extern \"C\" __global__ void __launch_bounds__(512) tdf_generated_step_local(tdf::Engine e, int max_steps, long long spin_ticks) {\n";
+    o << "  extern __shared__ __attribute__((aligned(16))) char lds[];\n";
+    o << "  __shared__ tdf::DevProgram P;\n  __shared__ uint32_t sh[4];\n";
+    o << "  tdf::steps_grid<true, tdf::GeneratedSweep>(e, max_steps, spin_ticks, lds, &P, sh);\n}\n";
     o << "extern \"C\" __global__ void __launch_bounds__(512) tdf_generated_small(tdf::Engine e, int max_steps) {\n";
     o << "  extern __shared__ __attribute__((aligned(16))) char lds[];\n";
     o << "  __shared__ tdf::DevProgram P;\n  __shared__ tdf::Ctrl lc;\n";
@@ -276,8 +280,9 @@ bool jit_compile(const DevProgram& P, JitKernels& out, std::string& log) {
     log = "hipModuleLoadData failed";
     return false;
   }
-  hipFunction_t f_step = nullptr, f_small = nullptr;
+  hipFunction_t f_step = nullptr, f_small = nullptr, f_local = nullptr;
   if (hipModuleGetFunction(&f_step, mod, "tdf_generated_step") != hipSuccess ||
+      hipModuleGetFunction(&f_local, mod, "tdf_generated_step_local") != hipSuccess ||
       hipModuleGetFunction(&f_small, mod, "tdf_generated_small") != hipSuccess) {
     (void)hipModuleUnload(mod);
     log = "generated kernels not found in the module";
@@ -285,6 +290,7 @@ bool jit_compile(const DevProgram& P, JitKernels& out, std::string& log) {
   }
   out.module = mod;
   out.step = f_step;
+  out.step_local = f_local;
   out.small = f_small;
   return true;
 }

@@ -407,7 +407,7 @@ __device__ __forceinline__ void load_program(DevProgram* dst, const DevProgram* 
 // One pass over the touched frames [0, n) of the current list; lane `first + tid` takes frames
 // i, i + lane_stride, ...  `c` is the control block the pass counts in: the global one, or a
 // workgroup's LDS copy.  The loop over passes is uniform for the workgroup.
-template <int SCOPE, class SW>
+template <int SCOPE, bool kDirect, class SW>
 __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_t step, uint32_t n,
                           uint32_t first, uint32_t lane_stride, char* lds) {
   const int tid = threadIdx.x;
@@ -428,9 +428,8 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
   uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
   const uint32_t word = step & 1;    // arrival word of the next step (this step reads word ^ 1)
 
-  // One workgroup alone (its control block `c` is in LDS): positions in the global lists come
-  // straight from the counters in `c`, without staging and without barriers between passes.
-  constexpr bool kDirect = SCOPE == __HIP_MEMORY_SCOPE_WORKGROUP;
+  // kDirect: one workgroup alone (its control block `c` is in LDS): positions in the global lists
+  // come straight from the counters in `c`, without staging and without barriers between passes.
   uint32_t cnt_tags = 0, cnt_tokens = 0;   // per wave, wave-uniform
 
   for (uint32_t base = first; base < n; base += lane_stride) {
@@ -447,6 +446,11 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     const uint32_t i = base + tid;
     x.active = i < n;
     x.frame = x.active ? cur_list[i] : 0;
+    if (x.frame >= e.cap + e.n_inst) {   // never true for a list this engine wrote
+      raise(c, TDF_ERR_DEVICE);
+      x.active = false;
+      x.frame = 0;
+    }
     x.result_fn = (int)uni((uint32_t)P.result_fn);
     FrameHdr* h = frame_at(e, stride, x.frame);
     x.slots = frame_slots(h);
@@ -500,8 +504,12 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
             m.bits = (1u << param) | (m.callee << 24);
           } else {
             m.target = (uint32_t)(key >> 32) - 1u;
-            m.slot = P.label_ret_slot[((uint32_t)key & 0xFFu) - 1u];
+            m.slot = P.label_ret_slot[(((uint32_t)key & 0xFFu) - 1u) & (MAX_LABELS - 1)];
             m.bits = 1u << m.slot;
+            if (m.target >= e.cap + e.n_inst) {   // never true for a key this engine wrote
+              raise(c, TDF_ERR_DEVICE);
+              m.has = false;
+            }
           }
         }
       }
@@ -710,15 +718,15 @@ __device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
   const uint32_t next = ld(&c->touched_count[parity ^ 1]);
   uint32_t status = ld(&c->status);
   st(&c->touched_count[parity], 0u);
-  c->step = step + 1;
+  st(&c->step, step + 1);
   if (ld(&c->n_tags) > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
   if (step + 1 >= e.step_limit && next != 0 && status == 0) status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
   if (status != 0) {
     st(&c->status, status);
     st(&c->touched_count[parity ^ 1], 0u);   // drain: nothing more fires
-    c->done = 1;
+    st(&c->done, 1u);
   } else if (next == 0) {
-    c->done = 1;
+    st(&c->done, 1u);
   }
 }
 
@@ -726,30 +734,93 @@ __device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
 // single-workgroup kernel, the others in the grid-wide kernel.
 __device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
 
-constexpr int STEP_BLOCK = 128;   // lanes per workgroup of the grid-wide kernel
+constexpr int STEP_BLOCK = 256;    // lanes per workgroup of the grid-wide kernel
+constexpr int LOCAL_BLOCK = 512;   // ... and of its variant that keeps to one accelerator die
 
-// Grid-wide step: every workgroup takes a slice of the touched list; the last one to finish
-// closes the step.
-template <class SW>
-__device__ void step_grid(Engine e, char* lds, DevProgram* P_lds, bool* last) {
+// Grid-wide steps: the workgroups of one launch (all resident at once: the host launches no
+// more than the GPU holds) run step after step; each takes a slice of the touched list, and a
+// grid barrier closes the step.  The last workgroup to arrive does the step bookkeeping and
+// releases the others.  A workgroup that waits longer than `spin_ticks` (100 MHz ticks) raises
+// an error and ends the run, so every wave leaves the kernel in any case.  Returns when the
+// recursion is finished, when the next step is small, or after max_steps steps.
+//
+// LOCAL: only every eighth workgroup of the launch takes part.  Workgroups are handed to the
+// eight accelerator dies (XCDs) in turn, so these all run on one die and share its L2: frame
+// atomics then execute in that L2 (workgroup scope) instead of in memory, and a step boundary
+// needs no L2 write-back or invalidation, only an invalidation of the per-CU L1.  The dies seen
+// are recorded in Ctrl::xcc_mask; the host discards the run if there was more than one.
+constexpr uint32_t XCDS = 8;
+
+__device__ __forceinline__ void l1_invalidate() {
+  // what a workgroup-scope acquire is when the waves of a workgroup do not share an L1
+  asm volatile("buffer_inv sc0\n\ts_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// Orders this thread's accesses to the control block, which are all atomic loads, stores and
+// read-modify-writes performed in memory.  Die-local runs must not use a device-scope fence
+// for this: it would also write back and invalidate the L2 that the step kernel relies on.
+template <bool LOCAL> __device__ __forceinline__ void ctrl_fence() {
+  if (LOCAL) __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
+  else __threadfence();
+}
+
+template <bool LOCAL, class SW>
+__device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* lds, DevProgram* P_lds, uint32_t* sh) {
+  constexpr int SCOPE = LOCAL ? __HIP_MEMORY_SCOPE_WORKGROUP : __HIP_MEMORY_SCOPE_AGENT;
   Ctrl* c = e.ctrl;
-  const uint32_t step = c->step;
-  const uint32_t n = ld(&c->touched_count[step & 1]);
-  if (c->done || n == 0 || step_is_small(e, n)) return;
-  if (blockIdx.x * blockDim.x < n) {   // workgroups without frames only take part in closing the step
-    load_program(P_lds, e.prog);
-    step_pass<__HIP_MEMORY_SCOPE_AGENT, SW>(*P_lds, e, c, step, n, blockIdx.x * blockDim.x, gridDim.x * blockDim.x, lds);
+  uint32_t G = gridDim.x, rank = blockIdx.x;
+  if (LOCAL) {
+    if (blockIdx.x % XCDS != 0) return;
+    G = (gridDim.x + XCDS - 1) / XCDS;
+    rank = blockIdx.x / XCDS;
   }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    __threadfence();
-    *last = atomicAdd(&c->blocks_done, 1u) == gridDim.x - 1;
-  }
-  __syncthreads();
-  if (*last && threadIdx.x == 0) {
-    __threadfence();
-    st(&c->blocks_done, 0u);
-    advance(e, c, step);
+  // Nothing changes these before the first barrier completes, and a workgroup reads them before
+  // it arrives there: all workgroups see the same values and take the same way.
+  uint32_t gen = ld(&c->bar_gen);
+  uint32_t step = ld(&c->step);
+  uint32_t n = ld(&c->touched_count[step & 1]);
+  if (ld(&c->done) || n == 0 || step_is_small(e, n)) return;
+  if (LOCAL && threadIdx.x == 0)   // HW_REG_XCC_ID (20), bits 3:0: the die this wave runs on
+    atomicOr(&c->xcc_mask, 1u << (__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15u));
+  load_program(P_lds, e.prog);
+  for (int it = 0; it < max_steps; ++it) {
+    if (rank * blockDim.x < n)
+      step_pass<SCOPE, false, SW>(*P_lds, e, c, step, n, rank * blockDim.x, G * blockDim.x, lds);
+    if (!LOCAL) __threadfence();   // this step's writes, before the arrival below
+    __syncthreads();               // (LOCAL: every wave's stores have reached the shared L2)
+    if (threadIdx.x == 0) {
+      const uint32_t arrived = atomicAdd(&c->bar_count, 1u);   // monotone: G per barrier
+      if (arrived == (gen + 1u) * G - 1u) {
+        ctrl_fence<LOCAL>();
+        advance(e, c, step);
+        ctrl_fence<LOCAL>();
+        st(&c->bar_gen, gen + 1u);
+      } else {
+        const long long t0 = wall_clock64();
+        while (ld(&c->bar_gen) == gen) {
+          __builtin_amdgcn_s_sleep(1);
+          if (wall_clock64() - t0 > spin_ticks) {   // a workgroup is missing: give up
+            raise(c, TDF_ERR_DEVICE);
+            st(&c->done, 1u);
+            break;
+          }
+        }
+      }
+      ctrl_fence<LOCAL>();
+      const uint32_t s1 = ld(&c->step);
+      sh[0] = s1;
+      sh[1] = ld(&c->touched_count[s1 & 1]);
+      sh[2] = ld(&c->done);
+    }
+    __syncthreads();
+    // the other workgroups' writes, before the next step reads them
+    if (LOCAL) l1_invalidate(); else __threadfence();
+    ++gen;
+    step = sh[0];
+    n = sh[1];
+    const bool stop = sh[2] != 0 || n == 0 || step_is_small(e, n);
+    __syncthreads();   // sh is written again in the next round
+    if (stop) break;
   }
 }
 
@@ -777,7 +848,7 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     lc.max_probe = ld(&g->max_probe);
     lc.max_depth = ld(&g->max_depth);
     lc.max_level = ld(&g->max_level);
-    lc.blocks_done = 0;
+    lc.bar_count = lc.bar_gen = 0;
     lc.n_tags = ld(&g->n_tags);
     lc.n_tokens = ld(&g->n_tokens);
   }
@@ -786,7 +857,7 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     const uint32_t step = lc.step;
     const uint32_t n = lc.touched_count[step & 1];
     if (lc.done || n == 0 || !step_is_small(e, n)) break;   // uniform: lc changes only between barriers
-    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP, SW>(*P_lds, e, &lc, step, n, 0, blockDim.x, lds);
+    step_pass<__HIP_MEMORY_SCOPE_WORKGROUP, true, SW>(*P_lds, e, &lc, step, n, 0, blockDim.x, lds);
     if (threadIdx.x == 0) advance(e, &lc, step);
     __syncthreads();
   }

@@ -25,12 +25,12 @@ __global__ void k_seed(DevProgram P, Engine e) {
   if (b == 0) e.ctrl->touched_count[0] = e.n_inst;
 }
 
-template <int NV>
-__global__ void __launch_bounds__(STEP_BLOCK) k_step(Engine e) {
+template <int NV, bool LOCAL>
+__global__ void __launch_bounds__(LOCAL ? LOCAL_BLOCK : STEP_BLOCK) k_steps_grid(Engine e, int max_steps, long long spin_ticks) {
   extern __shared__ __attribute__((aligned(16))) char lds[];
   __shared__ DevProgram P;
-  __shared__ bool last;
-  step_grid<InterpSweep<NV>>(e, lds, &P, &last);
+  __shared__ uint32_t sh[4];
+  steps_grid<LOCAL, InterpSweep<NV>>(e, max_steps, spin_ticks, lds, &P, sh);
 }
 
 template <int NV>
@@ -144,23 +144,30 @@ int tag_machine_small_block(const DevProgram& P, bool jit) {
   return rb;
 }
 
-// One round of the tag machine: as many small steps as fit (one workgroup), then one
-// grid-wide step if the next step is large.  Each kernel decides on the device whether the
-// current step is its own.  jit_small / jit_step: kernels generated for this program by the
-// run-time compiler, or null for the table interpreter.
-tdf_status launch_round(const DevProgram& P, const Engine& e, int blocks, int small_block, int small_steps,
-                        void* jit_small, void* jit_step, hipStream_t s) {
+// One round of the tag machine: a run of small steps (one workgroup), then a run of grid-wide
+// steps.  Each kernel decides on the device whether the current step is its own and returns at
+// once if not.  The workgroups of the grid-wide kernel must all be resident at once: one per
+// compute unit (`cus`); with `local` one per compute unit of a single accelerator die, which is
+// every eighth workgroup of a launch eight times as large.  jit: kernels generated for this
+// program by the run-time compiler (used when all handles are set), else the table
+// interpreter.  spin_ticks bounds the wait at the grid barrier (100 MHz ticks).
+tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool local, int small_block, int max_steps,
+                        long long spin_ticks, const JitKernels& jit, hipStream_t s) {
   const Sizes z = sizes_of(P);
-  if (jit_small && jit_step) {
+  const int per_die = cus / (int)XCDS > 0 ? cus / (int)XCDS : 1;
+  const int grid = local ? per_die * (int)XCDS : cus;
+  if (jit.small && jit.step && jit.step_local) {
     Engine ev = e;
-    int ms = small_steps;
+    int ms = max_steps;
+    long long st = spin_ticks;
     void* a_small[] = {&ev, &ms};
-    void* a_step[] = {&ev};
-    hipError_t r = hipModuleLaunchKernel((hipFunction_t)jit_small, 1, 1, 1, small_block, 1, 1,
+    void* a_step[] = {&ev, &ms, &st};
+    const int gb = local ? LOCAL_BLOCK : STEP_BLOCK;
+    hipError_t r = hipModuleLaunchKernel((hipFunction_t)jit.small, 1, 1, 1, small_block, 1, 1,
                                          (unsigned)step_lds_bytes(z, small_block, false), s, a_small, nullptr);
     if (r == hipSuccess)
-      r = hipModuleLaunchKernel((hipFunction_t)jit_step, blocks, 1, 1, STEP_BLOCK, 1, 1,
-                                (unsigned)step_lds_bytes(z, STEP_BLOCK, false), s, a_step, nullptr);
+      r = hipModuleLaunchKernel((hipFunction_t)(local ? jit.step_local : jit.step), grid, 1, 1, gb, 1, 1,
+                                (unsigned)step_lds_bytes(z, gb, false), s, a_step, nullptr);
     if (r != hipSuccess) {
       set_error(std::string("launch of a generated step kernel failed: ") + hipGetErrorString(r));
       return TDF_ERR_DEVICE;
@@ -173,11 +180,27 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int blocks, int sm
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_small<0>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds);
   if (in_regs) {
-    hipLaunchKernelGGL(k_steps_small<16>, dim3(1), dim3(small_block), small_lds, s, e, small_steps);
-    hipLaunchKernelGGL(k_step<16>, dim3(blocks), dim3(STEP_BLOCK), step_lds_bytes(z, STEP_BLOCK, false), s, e);
+    hipLaunchKernelGGL(k_steps_small<16>, dim3(1), dim3(small_block), small_lds, s, e, max_steps);
+    if (local)
+      hipLaunchKernelGGL((k_steps_grid<16, true>), dim3(grid), dim3(LOCAL_BLOCK), step_lds_bytes(z, LOCAL_BLOCK, false), s, e,
+                         max_steps, spin_ticks);
+    else
+      hipLaunchKernelGGL((k_steps_grid<16, false>), dim3(grid), dim3(STEP_BLOCK), step_lds_bytes(z, STEP_BLOCK, false), s, e,
+                         max_steps, spin_ticks);
   } else {
-    hipLaunchKernelGGL(k_steps_small<0>, dim3(1), dim3(small_block), small_lds, s, e, small_steps);
-    hipLaunchKernelGGL(k_step<0>, dim3(blocks), dim3(STEP_BLOCK), step_lds_bytes(z, STEP_BLOCK, true), s, e);
+    // the LDS value file limits the workgroup to 128 lanes (at most 90 KB)
+    const size_t grid_lds = step_lds_bytes(z, 128, true);
+    if (grid_lds > 48 * 1024) {
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_grid<0, true>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)grid_lds);
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_grid<0, false>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)grid_lds);
+    }
+    hipLaunchKernelGGL(k_steps_small<0>, dim3(1), dim3(small_block), small_lds, s, e, max_steps);
+    if (local)
+      hipLaunchKernelGGL((k_steps_grid<0, true>), dim3(grid), dim3(128), grid_lds, s, e, max_steps, spin_ticks);
+    else
+      hipLaunchKernelGGL((k_steps_grid<0, false>), dim3(grid), dim3(128), grid_lds, s, e, max_steps, spin_ticks);
   }
   return TDF_OK;
 }

@@ -30,6 +30,7 @@ void set_error(const std::string& msg);
 struct JitKernels {
   void* module = nullptr;   // hipModule_t
   void* step = nullptr;     // hipFunction_t of the grid-wide step kernel
+  void* step_local = nullptr;   // ... and of its variant that keeps to one accelerator die
   void* small = nullptr;    // hipFunction_t of the single-workgroup kernel
   bool tried = false;
 };
@@ -41,6 +42,7 @@ void jit_release(JitKernels& k);
 struct tdf_graph {
   tdf::Graph g;
   tdf::JitKernels jit;
+  bool die_local = true;    // grid-wide steps on one accelerator die (cleared if the GPU spreads them)
   void* events[2 * TDF_PHASE_COUNT] = {nullptr};   // hipEvent_t pairs, created on first use
   ~tdf_graph();
 };
