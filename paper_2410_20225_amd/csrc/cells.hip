@@ -4,6 +4,8 @@
 // forward inputs and the output gradient).  Parameter gradients are sums over all tags,
 // formed without floating-point atomics: one split GEMM over the tag dimension with an
 // ordered reduction of the partial tiles, and a segmented sum over leaves sorted by token.
+#include <stdlib.h>
+
 #include <algorithm>
 
 #include "engine.h"
@@ -321,6 +323,195 @@ template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int 
   }
   const size_t lds = gemm_lds_bytes<T, MODE>();
   hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE>), grid, dim3(GEMM_THREADS), lds, s, g);
+}
+
+// ---- small levels ----------------------------------------------------------------------
+// Deep in the recursion a dependency level holds few cells, and a level costs the latency of
+// one kernel.  This variant keeps that chain short: a workgroup owns 32 cells x 32 hidden units
+// (x gates), its four waves split the reduction four ways and load their MFMA operands
+// straight from global memory (the weights come from L2, no LDS staging, few dependent round
+// trips), and the partial tiles meet in LDS; wave w then finishes rows 8w..8w+7 of the tile.
+// Operands are fetched as 16-byte chunks: for bf16 one chunk is one 32x32x16 operand; for fp32
+// a chunk of four k-values feeds four 32x32x2 products, component j of both operands in
+// product j (a fixed permutation of the reduction index).
+template <typename T> struct Chunk;
+template <> struct Chunk<__bf16> {
+  static constexpr int KC = 16;   // reduction indices covered by one chunk step of a wave
+  static __device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+};
+template <> struct Chunk<float> {
+  static constexpr int KC = 8;
+  static __device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
+    typedef __attribute__((ext_vector_type(4))) float f32x4;
+    const f32x4 x = __builtin_bit_cast(f32x4, a), y = __builtin_bit_cast(f32x4, b);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(x.x, y.x, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(x.y, y.y, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(x.z, y.z, c, 0, 0, 0);
+    c = __builtin_amdgcn_mfma_f32_32x32x2f32(x.w, y.w, c, 0, 0, 0);
+    return c;
+  }
+};
+
+template <int DT, int MODE>
+__global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
+  typedef typename TypeOf<DT>::type T;
+  typedef Chunk<T> C;
+  constexpr int G = MODE == LSTM_FWD ? 5 : 1;      // 32-wide column blocks per tile
+  constexpr int BATCH = MODE == LSTM_FWD ? 4 : 8;  // chunk steps in flight
+  constexpr int EPC = 16 / (int)sizeof(T);         // elements per chunk
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  float* part = reinterpret_cast<float*>(smem);    // [wave][G][16][64]
+
+  const int n_ct = g.n_tiles_n;                    // column tiles of 32
+  const int ct = blockIdx.x % n_ct, rt = blockIdx.x / n_ct;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m0 = rt * 32;
+  const int mA = min(m0 + (lane & 31), g.M - 1);   // operand row of this lane
+  const int kw = g.K / 4;                          // reduction range of this wave: [wave * kw, +kw)
+
+  // rows this lane finishes: r = 4 * wave + rr  ->  row = 8 * wave + (lane / 32) * 4 + rr
+  uint32_t o_out[4], o_l[4], o_r[4];
+#pragma unroll
+  for (int rr = 0; rr < 4; ++rr) {
+    const int m = min(m0 + 8 * wave + (lane >> 5) * 4 + rr, g.M - 1);
+    if (MODE != DX_BWD) o_out[rr] = g.out[m];
+    if (MODE != RNN_FWD) { o_l[rr] = g.l[m]; o_r[rr] = g.r[m]; }
+  }
+  // operand bases (elements)
+  const T* Ap;
+  if (MODE == DX_BWD) {
+    Ap = reinterpret_cast<const T*>(g.A) + (size_t)mA * g.lda + wave * kw;
+  } else {
+    const uint32_t child = wave < 2 ? g.l[mA] : g.r[mA];   // waves 0,1: left half of [h_l; h_r]
+    Ap = reinterpret_cast<const T*>(g.Hs) + (size_t)child * g.Hp + (wave & 1) * kw;
+  }
+  Ap += (lane >> 5) * EPC;
+  const T* Bp[G];
+#pragma unroll
+  for (int j = 0; j < G; ++j) {
+    const int brow = (MODE == LSTM_FWD ? j * g.Hp : 0) + ct * 32 + (lane & 31);
+    Bp[j] = reinterpret_cast<const T*>(g.B) + (size_t)brow * g.ldb + wave * kw + (lane >> 5) * EPC;
+  }
+  // children's cell states for the epilogue, requested before the products start
+  float cl[4], cr[4];
+  const int unit = ct * 32 + (lane & 31);
+  if (MODE == LSTM_FWD) {
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      cl[rr] = g.Cs[(size_t)o_l[rr] * g.Hp + unit];
+      cr[rr] = g.Cs[(size_t)o_r[rr] * g.Hp + unit];
+    }
+  }
+
+  f32x16 acc[G];
+#pragma unroll
+  for (int j = 0; j < G; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+  const int steps = kw / C::KC;
+  for (int s0 = 0; s0 < steps; s0 += BATCH) {
+    u32x4 fa[BATCH], fb[BATCH][G];
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+      const int st = min(s0 + b, steps - 1);       // a short last batch repeats its final chunk ...
+#pragma unroll
+      for (int j = 0; j < G; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(Bp[j] + st * C::KC);
+      fa[b] = *reinterpret_cast<const u32x4*>(Ap + st * C::KC);
+    }
+#pragma unroll
+    for (int b = 0; b < BATCH; ++b) {
+      if (s0 + b < steps) {                        // ... and leaves it out of the sum
+#pragma unroll
+        for (int j = 0; j < G; ++j) acc[j] = C::mma(fa[b], fb[b][j], acc[j]);
+      }
+    }
+  }
+
+  // partial tiles -> LDS; wave w sums and finishes r = 4w .. 4w+3
+#pragma unroll
+  for (int j = 0; j < G; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) part[((wave * G + j) * 16 + r) * 64 + lane] = acc[j][r];
+  __syncthreads();
+  float z[G][4];
+#pragma unroll
+  for (int j = 0; j < G; ++j)
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      float t = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) t += part[((w * G + j) * 16 + 4 * wave + rr) * 64 + lane];
+      z[j][rr] = t;
+    }
+
+  if constexpr (MODE == LSTM_FWD) {
+    const float bi = g.bias[unit], bfl = g.bias[g.Hp + unit], bfr = g.bias[2 * g.Hp + unit];
+    const float bo = g.bias[3 * g.Hp + unit], bu = g.bias[4 * g.Hp + unit];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int m = m0 + 8 * wave + (lane >> 5) * 4 + rr;
+      if (m >= g.M) continue;
+      const float gi = Act<T>::sigmoid(z[0][rr] + bi);
+      const float gfl = Act<T>::sigmoid(z[1][rr] + bfl);
+      const float gfr = Act<T>::sigmoid(z[2][rr] + bfr);
+      const float go = Act<T>::sigmoid(z[3][rr] + bo);
+      const float gu = Act<T>::tanh(z[4][rr] + bu);
+      const float c = gi * gu + gfl * cl[rr] + gfr * cr[rr];
+      const size_t o = (size_t)o_out[rr] * g.Hp + unit;
+      g.Cs[o] = c;
+      reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh(c));
+      if (g.save_gates) {
+        T* gr = reinterpret_cast<T*>(g.gates) + (size_t)m * g.ldg;
+        gr[unit] = from_f<T>(gi);
+        gr[g.Hp + unit] = from_f<T>(gfl);
+        gr[2 * g.Hp + unit] = from_f<T>(gfr);
+        gr[3 * g.Hp + unit] = from_f<T>(go);
+        gr[4 * g.Hp + unit] = from_f<T>(gu);
+      }
+    }
+  } else if constexpr (MODE == RNN_FWD) {
+    const float bias = g.bias[unit];
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int m = m0 + 8 * wave + (lane >> 5) * 4 + rr;
+      if (m >= g.M) continue;
+      reinterpret_cast<T*>(g.Hs_out)[(size_t)o_out[rr] * g.Hp + unit] = from_f<T>(Act<T>::tanh(z[0][rr] + bias));
+    }
+  } else {   // DX_BWD: column `unit` of [dh_l; dh_r]; each child row has exactly one consumer
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr) {
+      const int m = m0 + 8 * wave + (lane >> 5) * 4 + rr;
+      if (m >= g.M) continue;
+      if (unit < g.Hp) g.C[(size_t)o_l[rr] * g.Hp + unit] = z[0][rr];
+      else g.C[(size_t)o_r[rr] * g.Hp + (unit - g.Hp)] = z[0][rr];
+    }
+  }
+}
+
+// Levels of at most this many cells take the small-level kernel (TDF_SMALL_LEVEL overrides).
+static uint32_t small_level() {
+  static const uint32_t v = [] {
+    const char* e = getenv("TDF_SMALL_LEVEL");
+    return e ? (uint32_t)atoi(e) : 1024u;
+  }();
+  return v;
+}
+
+template <typename T, int MODE> void launch_cell_small(GemmArgs g, int n_col_tiles, hipStream_t s) {
+  if (g.M <= 0) return;
+  constexpr int G = MODE == LSTM_FWD ? 5 : 1;
+  const size_t lds = (size_t)4 * G * 16 * 64 * sizeof(float);
+  static bool lds_opt_in = false;
+  if (!lds_opt_in && lds > 48 * 1024) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cell_small<DtOf<T>::value, MODE>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    lds_opt_in = true;
+  }
+  g.n_tiles_n = n_col_tiles;
+  const int n_rt = (g.M + 31) / 32;
+  hipLaunchKernelGGL((k_cell_small<DtOf<T>::value, MODE>), dim3(n_rt * n_col_tiles), dim3(256), lds, s, g);
 }
 
 // ---- packing of W: padded, k-contiguous [Np x Kp], and its transpose [Kp x Np] ---------------
@@ -641,8 +832,14 @@ template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, 
   g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
   g.gates = v.gates ? reinterpret_cast<T*>(v.gates) + (size_t)q0 * v.Np : nullptr;
   g.ldg = v.Np; g.save_gates = save_gates && v.gates;
-  if (v.cell_kind == 2) launch_gemm<T, LSTM_FWD>(g, (v.Hp / 32 + 1) / 2, 1, s);
-  else launch_gemm<T, RNN_FWD>(g, (v.Np + 127) / 128, 1, s);
+  if (count <= small_level()) {
+    if (v.cell_kind == 2) launch_cell_small<T, LSTM_FWD>(g, v.Hp / 32, s);
+    else launch_cell_small<T, RNN_FWD>(g, v.Hp / 32, s);
+  } else if (v.cell_kind == 2) {
+    launch_gemm<T, LSTM_FWD>(g, (v.Hp / 32 + 1) / 2, 1, s);
+  } else {
+    launch_gemm<T, RNN_FWD>(g, (v.Np + 127) / 128, 1, s);
+  }
 }
 void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, int save_gates, hipStream_t s) {
   if (v.dtype == TDF_BF16) cell_fwd_t<__bf16>(v, e, q0, count, save_gates, s);
@@ -658,7 +855,8 @@ template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, 
   g.B = v.WpT; g.ldb = v.Np;
   g.Hp = v.Hp; g.l = e.q_l + q0; g.r = e.q_r + q0;
   g.C = v.dH;
-  launch_gemm<T, DX_BWD>(g, (v.Kp + 127) / 128, 1, s);
+  if (count <= small_level()) launch_cell_small<T, DX_BWD>(g, v.Kp / 32, s);
+  else launch_gemm<T, DX_BWD>(g, (v.Kp + 127) / 128, 1, s);
 }
 void vec_cell_bwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s) {
   if (v.dtype == TDF_BF16) cell_bwd_t<__bf16>(v, e, q0, count, s); else cell_bwd_t<float>(v, e, q0, count, s);
