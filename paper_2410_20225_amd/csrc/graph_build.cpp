@@ -459,7 +459,9 @@ struct Builder {
       D.fn[f].n_call_labels = (uint8_t)n_cl;
       if (n_stored > max_stored) max_stored = n_stored;
     }
-    D.frame_stride = (32 + 8 * max_stored + 31) / 32 * 32;
+    // a frame never straddles a 128-byte line: 64 bytes if it fits, else whole lines
+    const int frame_bytes = 32 + 8 * max_stored;
+    D.frame_stride = frame_bytes <= 64 ? 64 : (frame_bytes + 127) / 128 * 128;
     if ((int)G.snodes.size() > TDF_STATS_MAX_COUNTS) bad("static graph too large for tdf_stats");
   }
 };
