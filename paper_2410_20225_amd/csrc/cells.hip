@@ -492,11 +492,8 @@ __global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
 
 // Levels of at most this many cells take the small-level kernel (TDF_SMALL_LEVEL overrides).
 static uint32_t small_level() {
-  static const uint32_t v = [] {
-    const char* e = getenv("TDF_SMALL_LEVEL");
-    return e ? (uint32_t)atoi(e) : 1024u;
-  }();
-  return v;
+  const char* e = getenv("TDF_SMALL_LEVEL");
+  return e ? (uint32_t)atoll(e) : 1024u;
 }
 
 template <typename T, int MODE> void launch_cell_small(GemmArgs g, int n_col_tiles, hipStream_t s) {

@@ -18,6 +18,7 @@ if not os.path.exists(_LIB_PATH):
 lib = C.CDLL(_LIB_PATH)
 
 OK, ERR_BAD_PROGRAM, ERR_BAD_ARG, ERR_WORKSPACE, ERR_TABLE_FULL, ERR_STEP_LIMIT, ERR_DEVICE = 0, -1, -2, -3, -4, -5, -6
+ERR_UNSUPPORTED = -7
 F32, BF16 = 0, 1
 (OP_IN, OP_OUT, OP_CONST, OP_ADD, OP_SUB, OP_MUL, OP_EQ, OP_LT, OP_ID, OP_SWITCH, OP_MERGE, OP_CALLFN,
  OP_TREE_ISLEAF, OP_TREE_LEFT, OP_TREE_RIGHT, OP_TREE_TOKEN, OP_EMBED, OP_RNN_CELL, OP_LSTM_CELL,

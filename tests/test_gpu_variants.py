@@ -1,0 +1,82 @@
+"""GPU parity of the library's alternative code paths, each forced by its environment switch:
+the table interpreter instead of generated step kernels, grid-wide steps synchronised through
+memory instead of one die's L2, and every level through the tiled GEMM or through the
+small-level kernel.  Same bars as the main parity tests: integers and counts bit-exact, bf16
+within rel 2e-2 (Frobenius)."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2410_20225_amd import tdf, programs  # noqa: E402
+import oracle  # noqa: E402
+from oracle import programs as oprog  # noqa: E402
+from tdf_workloads import make_config  # noqa: E402
+from gpu_util import DEV, TreeRun, run_oracle_tree, rel_fro, fire_counts  # noqa: E402
+
+VARIANTS = [{"TDF_NO_JIT": "1"}, {"TDF_NO_DIE_LOCAL": "1"}, {"TDF_NO_JIT": "1", "TDF_NO_DIE_LOCAL": "1"},
+            {"TDF_SMALL_LEVEL": "0"}, {"TDF_SMALL_LEVEL": "100000000"}]
+IDS = ["interpreter", "device_scope", "interpreter_device_scope", "tiled_gemm_only", "small_level_only"]
+
+
+@pytest.fixture(scope="module")
+def lstm_case():
+    # 1500 trees: the first steps touch more than 1024 frames, so the grid-wide kernel runs too
+    c = make_config(4, n_trees=1500, max_leaves=20, hidden=96, vocab=500)
+    B = c["forest"].n_trees
+    dy = np.full(B, 1.0 / B)
+    return c, dy, run_oracle_tree(c, head=True, grad=True, dy=dy)
+
+
+@pytest.mark.parametrize("env", VARIANTS, ids=IDS)
+def test_treelstm_variants(env, lstm_case, monkeypatch):
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    c, dy, ref = lstm_case
+    run = TreeRun(c, head=True, grad=True)          # a fresh graph: the switches are read per graph / per call
+    st, stats = run.run(dy)
+    assert stats.n_tags == c["forest"].n_nodes == len(ref["it"].tags)
+    assert stats.max_tag_depth == ref["it"].max_tag_len
+    assert rel_fro(run.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
+    for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
+        assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-2, name
+    got = fire_counts(run.graph, stats)
+    want = ref["it"].count_by_op()
+    for k in ("merge_entry", "isleaf", "switch", "call_0", "call_1", "return_0", "return_1", "lstm_cell"):
+        assert got[k] == want[k], k
+
+
+@pytest.mark.parametrize("env", VARIANTS[:3], ids=IDS[:3])
+def test_fib_variants(env, monkeypatch):
+    for k, v in env.items():
+        monkeypatch.setenv(k, v)
+    fns, r = programs.fib()
+    g = tdf.graph_build(fns, r)
+    args = torch.arange(0, 21, dtype=torch.int64, device=DEV)
+    inp = tdf.make_inputs(21, args=args, n_args=1, max_tags=57291)
+    ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=DEV)
+    out = torch.full((21,), -1, dtype=torch.int64, device=DEV)
+    st, stats = tdf.eval(g, inp, ws, out_i64=out)
+    it = oracle.Interpreter(oracle.transform(oprog.fib_program()))
+    want = it.run({("in", 0): list(range(21))}, 21)[("out", 0)]
+    assert out.cpu().tolist() == want
+    assert stats.n_tags == len(it.tags)
+    assert fire_counts(g, stats) == {k: v for k, v in it.count_by_op().items() if k != "const"}
+
+
+@pytest.mark.parametrize("local", ["0", "1"], ids=["die_local", "device_scope"])
+def test_grid_barrier_wait_is_bounded(local, lstm_case, monkeypatch):
+    # A wait limit of zero makes every workgroup that has to wait at the grid barrier give up:
+    # the call reports a device error (or finishes, if nobody had to wait), every kernel exits,
+    # and the next call with the normal limit is correct.
+    c, dy, ref = lstm_case
+    monkeypatch.setenv("TDF_NO_DIE_LOCAL", local)
+    monkeypatch.setenv("TDF_GRID_WAIT_MS", "0")
+    run = TreeRun(c, head=True, grad=True)
+    st, stats = run.run(dy, check=False)
+    assert st in (tdf.OK, tdf.ERR_DEVICE)
+    monkeypatch.delenv("TDF_GRID_WAIT_MS")
+    st, stats = run.run(dy)
+    assert st == tdf.OK and stats.n_tags == c["forest"].n_nodes
+    assert rel_fro(run.dW.cpu().numpy(), ref["grads"]["dW"]) < 2e-2

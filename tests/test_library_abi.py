@@ -99,3 +99,29 @@ def test_workspace_size_grows_with_capacity():
     assert 0 < small < big
     with pytest.raises(tdf.TdfError):
         tdf.workspace_size(g, tdf.make_inputs(8, n_args=1, max_tags=1000), True)   # wrong n_args
+
+
+@pytest.mark.parametrize("name,prog,grad", [
+    ("fact", programs.fact, False), ("fib", programs.fib, False),
+    ("treernn", lambda: programs.tree("rnn", False), False),
+    ("treelstm_head_grad", lambda: programs.tree("lstm", True), True),
+])
+def test_generated_step_kernels_compile_for_gfx950(name, prog, grad):
+    # the firing tables of every workload turn into HIP source that the run-time compiler
+    # accepts for gfx950 (no GPU needed); skipped where the run-time compiler is not installed
+    fns, r = prog()
+    g = tdf.graph_build(fns, r, want_grad=grad)
+    try:
+        n = tdf.graph_precompile(g, "gfx950")
+    except tdf.TdfError as ex:
+        if "hiprtc is not available" in str(ex):
+            pytest.skip("hiprtc is not available")
+        raise
+    assert n > 1000
+
+
+def test_precompile_rejects_missing_arguments():
+    fns, r = programs.fib()
+    g = tdf.graph_build(fns, r)
+    with pytest.raises(tdf.TdfError):
+        tdf.graph_precompile(g, "")
