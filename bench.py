@@ -125,18 +125,22 @@ def main():
     value = firings * a.steps / dt
     phase_ms = {n: round(float(p) / a.steps, 4) for n, p in zip(tdf.PHASES, phase)}
 
+    # tag machine: bytes the method itself moves per tag (key and probe window, frame record written
+    # once and read by each sweep, delivered values and arrival words, touched-list entries, forest
+    # entries, schedule-log entry): 280 B for fib's 64-byte frames, 600 B for the tree programs
+    tag_bytes = (280.0 if cfg == 1 else 600.0) * n_tags
+    tag_ms = phase[0] / a.steps
+    roof_tags = {"bound": "hbm", "kernel": "tag machine step kernels (all steps)",
+                 "achieved": tag_bytes / (tag_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                 "launches_per_step": launches[0] / a.steps, "traffic": None}
+    roof_tags["frac"] = roof_tags["achieved"] / roof_tags["peak"]
     if cfg == 1:
-        # tag machine: bytes the method itself moves per tag (key+frame write, argument, return
-        # delivery, touched-list entry, token write+read), see the design doc
-        algo = 128.0 * n_tags
-        ms = phase[0] / a.steps
-        roof = {"bound": "hbm", "kernel": "tag machine step kernels (all steps)", "achieved": algo / (ms * 1e-3) / 1e9,
-                "peak": PEAK_HBM / 1e9, "unit": "GB/s", "traffic": None}
+        roof = roof_tags
     else:
         ms = phase[3] / a.steps
         n_launch = launches[3] / a.steps
         peak = PEAK_BF16 if dtype == "bf16" else PEAK_F32
-        roof = {"bound": "mfma", "kernel": "k_gemm<%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
+        roof = {"bound": "mfma", "kernel": "k_gemm + k_cell_small <%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
                 "achieved": flops_fwd / (ms * 1e-3) / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
                 "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1), "traffic": None}
     roof["frac"] = roof["achieved"] / roof["peak"]
@@ -148,8 +152,10 @@ def main():
                       "firings_per_step": firings, "n_steps_tag_machine": int(st.n_steps),
                       "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth)},
            "phase_ms": phase_ms, "roofline": roof}
+    if cfg != 1:
+        rec["roofline_tag_machine"] = roof_tags
     if not a.no_cpu_baseline:
-        trees = a.cpu_trees or {1: 0, 2: 256, 3: 256, 4: 48, 5: 2}[cfg]
+        trees = a.cpu_trees or {1: 0, 2: 256, 3: 1024, 4: 1024, 5: 2}[cfg]
         rec["cpu_baseline"] = cpu_baseline(cfg, trees)
     print(json.dumps(rec))
 
