@@ -8,6 +8,7 @@
 
 #include <algorithm>
 
+#include "bucket.h"
 #include "engine.h"
 
 namespace tdf {
@@ -681,12 +682,13 @@ __global__ void k_reduce_dw(VecArgs v, float* dW, int splits) {
   }
 }
 
-// db[n] = sum_q Dz[q][n]: fixed chunks of 64 tags, partial sums combined in chunk order
+// db[n] = sum_q Dz[q][n]: fixed chunks of DB_TAGS tags, partial sums combined in a fixed order
+constexpr uint32_t DB_TAGS = 256;
 template <int DT>
 __global__ void k_db_partial(VecArgs v, uint32_t n_q, float* part) {
   typedef typename TypeOf<DT>::type T;
   constexpr int CH = El<T>::CH;
-  const uint32_t q_lo = blockIdx.x * 64, q_hi = min(n_q, q_lo + 64);
+  const uint32_t q_lo = blockIdx.x * DB_TAGS, q_hi = min(n_q, q_lo + DB_TAGS);
   for (int n = threadIdx.x * CH; n < v.Np; n += blockDim.x * CH) {
     float s[CH];
 #pragma unroll
@@ -701,19 +703,21 @@ __global__ void k_db_partial(VecArgs v, uint32_t n_q, float* part) {
     for (int i = 0; i < CH; ++i) part[(size_t)blockIdx.x * v.Np + n + i] = s[i];
   }
 }
-// 64 columns per block, four groups of partials reduced through LDS in a fixed order
+// 16 columns per block; 16 groups of partials, each summed in chunk order, meet in LDS
 __global__ void k_db_final(VecArgs v, const float* part, int n_parts, float* db) {
-  __shared__ float red[4][64];
-  const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int np = blockIdx.x * 64 + c;
+  __shared__ float red[16][17];
+  const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int np = blockIdx.x * 16 + c;
   float s = 0.f;
   if (np < v.Np)
-    for (int p = grp; p < n_parts; p += 4) s += part[(size_t)p * v.Np + np];
+    for (int p = grp; p < n_parts; p += 16) s += part[(size_t)p * v.Np + np];
   red[grp][c] = s;
   __syncthreads();
   if (grp == 0 && np < v.Np) {
+    float t = 0.f;
+    for (int g2 = 0; g2 < 16; ++g2) t += red[g2][c];
     const int gate = np / v.Hp, j = np % v.Hp;
-    if (j < v.H) db[gate * v.H + j] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+    if (j < v.H) db[gate * v.H + j] = t;
   }
 }
 
@@ -767,6 +771,11 @@ __global__ void k_tok_scatter(Engine e, uint32_t n_leaf, const uint32_t* seg_off
     if (on) sorted_row[seg_off[t] + rank] = e.leaf_row[i];
   }
 }
+struct TokenSink {   // leaf rows grouped by token
+  const uint32_t* leaf_row;
+  uint32_t* sorted_row;
+  __device__ void operator()(uint32_t i, uint32_t pos) const { sorted_row[pos] = leaf_row[i]; }
+};
 // one wave per chunk of at most `chunk` leaves of one token: partial[chunk] = sum of their dH rows
 __global__ void k_de_partial(VecArgs v, const uint32_t* seg_off, const uint32_t* chunk_off,
                              const uint32_t* sorted_row, uint32_t chunk, float* part) {
@@ -895,9 +904,9 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   g.k_per_split = kps;
   launch_gemm<T, DW_SPLIT>(g, (v.Kp + 127) / 128, splits, s);
   hipLaunchKernelGGL(k_reduce_dw, dim3(512), dim3(256), 0, s, v, dW, splits);
-  const int parts = (int)((n_q + 63) / 64);
+  const int parts = (int)((n_q + DB_TAGS - 1) / DB_TAGS);
   hipLaunchKernelGGL(k_db_partial<DtOf<T>::value>, dim3(parts), dim3(256), 0, s, v, n_q, db_part);
-  hipLaunchKernelGGL(k_db_final, dim3(v.Np / 64), dim3(256), 0, s, v, db_part, parts, db);
+  hipLaunchKernelGGL(k_db_final, dim3((v.Np + 15) / 16), dim3(256), 0, s, v, db_part, parts, db);
 }
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {
   if (v.dtype == TDF_BF16) weight_grads_t<__bf16>(v, e, n_q, dW, db, db_part, s);
@@ -909,9 +918,20 @@ void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t
                     uint32_t chunk, hipStream_t s) {
   int g = (int)std::min<uint32_t>((n_leaf + 255) / 256, 2048u);
   if (g < 1) g = 1;
-  hipLaunchKernelGGL(k_tok_hist, dim3(g), dim3(256), 0, s, e, n_leaf, count, v.vocab);
-  hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);
-  hipLaunchKernelGGL(k_tok_scatter, dim3(g), dim3(256), 0, s, e, n_leaf, seg_off, fill, sorted_row, v.vocab);
+  if (bucket_fits((uint32_t)v.vocab)) {
+    const uint32_t n_keys = (uint32_t)v.vocab;
+    const size_t lds = (size_t)n_keys * 4;
+    bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_count), n_keys);
+    bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_place<TokenSink>), n_keys);
+    hipLaunchKernelGGL(k_bucket_count, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.leaf_tok, n_leaf, n_keys, count);
+    hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);
+    hipLaunchKernelGGL(k_bucket_place<TokenSink>, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.leaf_tok, n_leaf, n_keys,
+                       seg_off, fill, TokenSink{e.leaf_row, sorted_row});
+  } else {
+    hipLaunchKernelGGL(k_tok_hist, dim3(g), dim3(256), 0, s, e, n_leaf, count, v.vocab);
+    hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);
+    hipLaunchKernelGGL(k_tok_scatter, dim3(g), dim3(256), 0, s, e, n_leaf, seg_off, fill, sorted_row, v.vocab);
+  }
   const uint32_t max_chunks = n_leaf / chunk + std::min<uint32_t>((uint32_t)v.vocab, n_leaf) + 1;
   hipLaunchKernelGGL(k_de_partial, dim3(std::min<uint32_t>((max_chunks + 3) / 4, 16384u)), dim3(256), 0, s, v, seg_off,
                      chunk_off, sorted_row, chunk, part);

@@ -17,7 +17,7 @@ void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
 tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool local, int small_block, int max_steps,
                         long long spin_ticks, const JitKernels& jit, hipStream_t s);
 int tag_machine_small_block(const DevProgram& P, bool jit);
-void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s);
+void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStream_t s);
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s);
 void vec_pack_w(const VecArgs& v, hipStream_t s);
 void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s);
@@ -323,7 +323,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     end(TDF_PHASE_LEAVES, 2);
     if (hc.n_cell) {
       begin(TDF_PHASE_LEVELS);
-      launch_levels(e, hc.n_cell, s);
+      launch_levels(e, hc.n_cell, hc.max_level, s);
       level_off.resize((size_t)hc.max_level + 2);
       HIP_TRY(hipMemcpyAsync(level_off.data(), e.level_off, level_off.size() * 4, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 3);

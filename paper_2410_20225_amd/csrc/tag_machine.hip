@@ -1,6 +1,7 @@
 // Kernels and launchers of the tag machine.  The step logic itself is in step_device.h; this
 // file instantiates it with the table interpreter and adds the seed, the post-run firing
 // counts and the bucketing of the cell log by dependency level.
+#include "bucket.h"
 #include "step_device.h"
 #include "tdf_internal.h"
 
@@ -77,6 +78,15 @@ __global__ void k_level_hist(Engine e) {
     (void)wave_alloc_keyed(j < n, j < n ? e.cell_lvl[j] : 0, e.level_count);
   }
 }
+
+struct LevelSink {   // the level-sorted copy of the cell log
+  Engine e;
+  __device__ void operator()(uint32_t j, uint32_t q) const {
+    e.q_out[q] = e.cell_out[j];
+    e.q_l[q] = e.cell_l[j];
+    e.q_r[q] = e.cell_r[j];
+  }
+};
 
 __global__ void k_level_scan(Engine e) {
   // single block; levels 1..max_level
@@ -209,7 +219,19 @@ void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s) {
   hipLaunchKernelGGL(k_count_fired, dim3(grid_for(e.cap + e.n_inst, 256, 1024)), dim3(256), 0, s, P, e);
 }
 
-void launch_levels(const Engine& e, uint32_t n_cell, hipStream_t s) {
+void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStream_t s) {
+  const uint32_t n_keys = max_level + 2;
+  if (bucket_fits(n_keys)) {
+    const size_t lds = (size_t)n_keys * 4;
+    bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_count), n_keys);
+    bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_place<LevelSink>), n_keys);
+    hipLaunchKernelGGL(k_bucket_count, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.cell_lvl, n_cell, n_keys,
+                       e.level_count);
+    hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e);
+    hipLaunchKernelGGL(k_bucket_place<LevelSink>, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.cell_lvl, n_cell,
+                       n_keys, e.level_off, e.level_fill, LevelSink{e});
+    return;
+  }
   int g = grid_for(n_cell, 256, 2048);
   hipLaunchKernelGGL(k_level_hist, dim3(g), dim3(256), 0, s, e);
   hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e);
