@@ -10,9 +10,10 @@
 
 namespace tdf {
 
-// Control block at the head of the workspace.  Counters are bumped with device-scope
-// atomics; everything else is ordered by kernel boundaries.
-struct Ctrl {
+// Control block of one tag machine, at the head of the workspace.  Counters are bumped with
+// device-scope atomics; everything else is ordered by kernel boundaries.  One 128-byte line per
+// machine: machines run on different dies and must not share a line.
+struct alignas(128) Ctrl {
   uint32_t touched_count[2]; // frames that received a token (double-buffered by step parity)
   uint32_t step;
   uint32_t n_leaf;           // EMBED firings
@@ -52,14 +53,28 @@ struct FrameHdr {
 static_assert(sizeof(FrameHdr) == 32, "FrameHdr must be 32 bytes");
 
 // Pointers into the workspace and to the caller's buffers, passed to kernels by value.
+//
+// The instances of a batch never exchange tokens (their tags differ in the root), so the batch
+// is dealt to n_dies independent tag machines, instance b to machine b % n_dies.  A machine
+// has its own control block, its own part of the key array (its frames are the slots of that
+// part, plus the root records of its instances), its own touched lists and its own schedule
+// log; nothing it touches during the steps is touched by another machine.  Each machine runs
+// on one accelerator die (XCD), so its atomics and step boundaries stay inside that die's L2.
+// Kernels receive the description of the whole engine and take the view of their machine
+// (die_view); after the last step the logs of the machines are merged.
 struct Engine {
   const DevProgram* prog;           // firing tables in the workspace (copied there once per call)
-  Ctrl* ctrl;
+  Ctrl* ctrl;                       // [n_dies]; in a machine's view: its own block
+  uint32_t n_dies;                  // machines: 1, 2, 4 or 8
+  uint32_t die;                     // view: this machine
+  uint32_t key_base, part_mask;     // view: first slot of this machine's part of the table; slots per part - 1
+  // per-machine schedule logs [n_dies][log_cap] (with one machine they are the merged logs below)
+  uint32_t *m_leaf_row, *m_leaf_tok, *m_cell_out, *m_cell_l, *m_cell_r, *m_cell_lvl;
   unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
   unsigned long long* keys;         // [cap] tag-hash table: the key of slot f, 0 = empty (frame f is then unused)
   char* frames;                     // (cap + B) records of frame_stride bytes
   uint32_t cap, cap_mask, n_inst, max_tags;
-  uint32_t* touched;                // two lists of touched_cap frame ids, by step parity
+  uint32_t* touched;                // per machine two lists of touched_cap frame ids, by step parity
   uint32_t touched_cap;
   uint32_t step_limit;
   uint32_t small_limit;             // steps with at most this many touched frames run in one workgroup
@@ -82,6 +97,27 @@ struct Engine {
   uint32_t max_levels;
   uint32_t *q_out, *q_l, *q_r;      // [n_cell], sorted by level
 };
+
+// The engine as machine d sees it.
+inline __host__ __device__ Engine die_view(const Engine& e, uint32_t d) {
+  Engine v = e;
+  v.die = d;
+  v.ctrl = e.ctrl + d;
+  v.key_base = d * (e.part_mask + 1u);
+  v.touched = e.touched + (size_t)d * 2 * e.touched_cap;
+  const size_t o = (size_t)d * e.log_cap;
+  v.leaf_row = e.m_leaf_row + o;
+  v.leaf_tok = e.m_leaf_tok + o;
+  v.cell_out = e.m_cell_out + o;
+  v.cell_l = e.m_cell_l + o;
+  v.cell_r = e.m_cell_r + o;
+  v.cell_lvl = e.m_cell_lvl + o;
+  return v;
+}
+// Slot `off` places after `slot` in its machine's part of the table (linear probing wraps there).
+inline __device__ uint32_t slot_after(const Engine& e, uint32_t slot, uint32_t off) {
+  return e.key_base + ((slot - e.key_base + off) & e.part_mask);
+}
 
 inline __device__ FrameHdr* frame_at(const Engine& e, int stride, uint32_t f) {
   return reinterpret_cast<FrameHdr*>(e.frames + (size_t)f * stride);

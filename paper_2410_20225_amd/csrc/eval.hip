@@ -18,6 +18,7 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
                         long long spin_ticks, const JitKernels& jit, hipStream_t s);
 int tag_machine_small_block(const DevProgram& P, bool jit);
 void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStream_t s);
+void launch_merge_logs(const Engine& e, const uint32_t* leaf_off, const uint32_t* cell_off, hipStream_t s);
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s);
 void vec_pack_w(const VecArgs& v, hipStream_t s);
 void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s);
@@ -64,8 +65,17 @@ uint32_t pow2_at_least(uint64_t x) {
   return (uint32_t)p;
 }
 
-// Sizes and offsets only; `base` may be null (tdf_workspace_size).
-tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char* base, Plan& P) {
+// Machines a batch of B instances is dealt to (a power of two, so that the parts of the tag
+// table are powers of two as well).
+uint32_t dies_for(uint32_t B, uint32_t at_most) {
+  uint32_t d = 1;
+  while (d * 2 <= B && d * 2 <= at_most && d * 2 <= 8) d *= 2;
+  return d;
+}
+
+// Sizes and offsets only; `base` may be null (tdf_workspace_size).  max_dies: upper bound of
+// the number of tag machines; the layout for more machines is never smaller.
+tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char* base, Plan& P, uint32_t max_dies) {
   if (!in) { set_error("inputs is NULL"); return TDF_ERR_BAD_ARG; }
   if (in->n_instances < 1) { set_error("n_instances must be positive"); return TDF_ERR_BAD_ARG; }
   if (in->n_args != G.n_result_params) { set_error("n_args does not match the parameters of result"); return TDF_ERR_BAD_ARG; }
@@ -86,6 +96,10 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.max_tags = T;
   e.cap = pow2_at_least(2ull * T);
   e.cap_mask = e.cap - 1;
+  e.n_dies = dies_for(B, max_dies);
+  e.part_mask = e.cap / e.n_dies - 1;
+  e.die = 0;
+  e.key_base = 0;
   e.step_limit = in->step_limit > 0 ? (uint32_t)in->step_limit : (1u << 20);
   e.touched_cap = T + B;
   e.log_cap = P.vec ? T : 0;
@@ -95,7 +109,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   auto at = [&](size_t off) { return base ? base + off : nullptr; };
   // --- cleared region: control block, counters, level histograms, token histograms, tag keys
   L.zero_begin = L.total;
-  P.off_ctrl = L.take(sizeof(Ctrl));
+  P.off_ctrl = L.take(sizeof(Ctrl) * 8);
   P.off_fire = L.take(sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS);
   size_t off_lcount = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
   size_t off_lfill = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
@@ -109,7 +123,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));   // headers are written on insertion
   // --- the rest is written before it is read
   size_t off_prog = L.take(sizeof(DevProgram));
-  size_t off_touched = L.take(sizeof(uint32_t) * 2 * (size_t)e.touched_cap);
+  size_t off_touched = L.take(sizeof(uint32_t) * 2 * (size_t)e.touched_cap * e.n_dies);
   size_t off_root = L.take(sizeof(uint32_t) * B);
   size_t off_hrow = L.take(sizeof(uint32_t) * B);
   size_t off_hlab = L.take(sizeof(uint32_t) * B);
@@ -118,6 +132,10 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_leaf_row = L.take(4 * rc), off_leaf_tok = L.take(4 * rc);
   size_t off_c_out = L.take(4 * rc), off_c_l = L.take(4 * rc), off_c_r = L.take(4 * rc), off_c_lvl = L.take(4 * rc);
   size_t off_q_out = L.take(4 * rc), off_q_l = L.take(4 * rc), off_q_r = L.take(4 * rc);
+  // logs of the single machines, merged into the arrays above after the last step
+  size_t off_m[6] = {off_leaf_row, off_leaf_tok, off_c_out, off_c_l, off_c_r, off_c_lvl};
+  if (e.n_dies > 1)
+    for (int i = 0; i < 6; ++i) off_m[i] = L.take(4 * rc * e.n_dies);
 
   e.prog = (const DevProgram*)at(off_prog);
   e.ctrl = (Ctrl*)at(P.off_ctrl);
@@ -137,6 +155,12 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.cell_l = (uint32_t*)at(off_c_l);
   e.cell_r = (uint32_t*)at(off_c_r);
   e.cell_lvl = (uint32_t*)at(off_c_lvl);
+  e.m_leaf_row = (uint32_t*)at(off_m[0]);
+  e.m_leaf_tok = (uint32_t*)at(off_m[1]);
+  e.m_cell_out = (uint32_t*)at(off_m[2]);
+  e.m_cell_l = (uint32_t*)at(off_m[3]);
+  e.m_cell_r = (uint32_t*)at(off_m[4]);
+  e.m_cell_lvl = (uint32_t*)at(off_m[5]);
   e.q_out = (uint32_t*)at(off_q_out);
   e.q_l = (uint32_t*)at(off_q_l);
   e.q_r = (uint32_t*)at(off_q_r);
@@ -210,6 +234,8 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     }                                                                                   \
   } while (0)
 
+bool status_is(uint32_t st, tdf_status code) { return st != 0 && -(int)st == (int)code; }
+
 tdf_status status_from_device(uint32_t st) {
   if (st == 0) return TDF_OK;
   int code = -(int)st;
@@ -228,7 +254,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   if (!gr || !out) { set_error("NULL graph or outputs"); return TDF_ERR_BAD_ARG; }
   const Graph& G = gr->g;
   Plan P;
-  tdf_status st = make_plan(G, in, with_grad, (char*)workspace, P);
+  tdf_status st = make_plan(G, in, with_grad, (char*)workspace, P, 8);   // the largest layout
   if (st != TDF_OK) return st;
   if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < P.L.total) {
     set_error("workspace is NULL, misaligned or smaller than tdf_workspace_size");
@@ -276,6 +302,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   if (const char* w = getenv("TDF_GRID_WAIT_MS")) wait_ms = atoll(w);
   const long long spin_ticks = wait_ms * 100000;
   if (const char* w = getenv("TDF_NO_DIE_LOCAL")) if (w[0] == '1') gr->die_local = false;
+  if (const char* w = getenv("TDF_DIES")) gr->max_dies = (uint32_t)std::max(1, atoi(w));
   // step kernels generated for this program (first call only; falls back to the interpreter)
   if (!gr->jit.tried) {
     gr->jit.tried = true;
@@ -284,31 +311,71 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   }
   const bool use_jit = gr->jit.step && gr->jit.small && gr->jit.step_local;
   const int small_block = tag_machine_small_block(G.prog, use_jit);
-  e.small_limit = 2u * (uint32_t)small_block;
   Ctrl hc{};
   uint32_t rounds = 0;
-  const uint32_t poll = 2;          // rounds queued between two looks at the control block
+  const uint32_t poll = 2;          // rounds queued between two looks at the control blocks
   const int max_steps = 4096;       // steps per kernel launch
   begin(TDF_PHASE_TAGS);
   for (;;) {
+    // several machines only where each keeps to its own die; the device-scope kernel runs one
+    const uint32_t want_dies = gr->die_local ? gr->max_dies : 1;
+    if (dies_for(e.n_inst, want_dies) != e.n_dies) {
+      P = Plan();
+      st = make_plan(G, in, with_grad, (char*)workspace, P, want_dies);
+      if (st != TDF_OK) return st;
+      e.out_i64 = (long long*)out->out_i64;
+    }
+    e.small_limit = 2u * (uint32_t)small_block;
     HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
     HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
     launch_seed(G.prog, e, s);
+    Ctrl hcs[8];
     for (;;) {
       for (uint32_t i = 0; i < poll; ++i, ++rounds) {
         tdf_status lr = launch_round(G.prog, e, cus, gr->die_local, small_block, max_steps, spin_ticks, gr->jit, s);
         if (lr != TDF_OK) return lr;
       }
-      HIP_TRY(hipMemcpyAsync(&hc, e.ctrl, sizeof(Ctrl), hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipMemcpyAsync(hcs, e.ctrl, sizeof(Ctrl) * e.n_dies, hipMemcpyDeviceToHost, s));
       HIP_TRY(hipStreamSynchronize(s));
-      if (hc.done || hc.status) break;
+      bool all_done = true, any_status = false;
+      for (uint32_t d = 0; d < e.n_dies; ++d) {
+        all_done = all_done && hcs[d].done;
+        any_status = any_status || hcs[d].status;
+      }
+      if (all_done || any_status) break;
     }
-    // The die-local kernel relies on its workgroups sharing one L2.  If the GPU placed them on
+    // totals over the machines
+    hc = Ctrl{};
+    bool mixed_dies = false;
+    uint32_t leaf_off[9] = {0}, cell_off[9] = {0};
+    for (uint32_t d = 0; d < e.n_dies; ++d) {
+      const Ctrl& c = hcs[d];
+      hc.n_leaf += c.n_leaf; hc.n_cell += c.n_cell; hc.n_head += c.n_head;
+      hc.n_tags += c.n_tags; hc.n_tokens += c.n_tokens;
+      hc.step = std::max(hc.step, c.step);
+      hc.max_probe = std::max(hc.max_probe, c.max_probe);
+      hc.max_depth = std::max(hc.max_depth, c.max_depth);
+      hc.max_level = std::max(hc.max_level, c.max_level);
+      if (!hc.status) hc.status = c.status;
+      hc.done = 1;
+      mixed_dies = mixed_dies || (c.xcc_mask & (c.xcc_mask - 1)) != 0;
+      leaf_off[d + 1] = leaf_off[d] + c.n_leaf;
+      cell_off[d + 1] = cell_off[d] + c.n_cell;
+    }
+    // A die-local machine relies on its workgroups sharing one L2.  If the GPU placed them on
     // several dies, the run is void: repeat it with the kernel that synchronises through memory.
-    if (gr->die_local && (hc.xcc_mask & (hc.xcc_mask - 1)) != 0) {
+    if (gr->die_local && mixed_dies) {
       gr->die_local = false;
       continue;
     }
+    // A part of the tag table can fill up although the whole table would not (instances of very
+    // different sizes): repeat with one machine, which owns the whole table.
+    if (e.n_dies > 1 && status_is(hc.status, TDF_ERR_TABLE_FULL) && hc.n_tags <= (unsigned long long)e.max_tags) {
+      gr->max_dies = 1;
+      continue;
+    }
+    if (hc.n_tags > (unsigned long long)e.max_tags && !hc.status) hc.status = (uint32_t)(-TDF_ERR_TABLE_FULL);
+    if (!hc.status) launch_merge_logs(e, leaf_off, cell_off, s);
     break;
   }
   end(TDF_PHASE_TAGS, 2 + 2ll * rounds);
@@ -417,7 +484,7 @@ extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* i
     return TDF_ERR_BAD_ARG;
   }
   Plan P;
-  tdf_status st = make_plan(g->g, in, with_grad != 0, nullptr, P);
+  tdf_status st = make_plan(g->g, in, with_grad != 0, nullptr, P, 8);
   if (st != TDF_OK) return st;
   *bytes = P.L.total;
   return TDF_OK;

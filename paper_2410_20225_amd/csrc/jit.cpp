@@ -188,11 +188,11 @@ struct Gen {
     o << "  extern __shared__ __attribute__((aligned(16))) char lds[];\n";
     o << "  __shared__ tdf::DevProgram P;\n  __shared__ uint32_t sh[4];\n";
     o << "  tdf::steps_grid<false, tdf::GeneratedSweep>(e, max_steps, spin_ticks, lds, &P, sh);\n}\n";
-    o << "extern \"C\" __global__ void __launch_bounds__(512) tdf_generated_step_local(tdf::Engine e, int max_steps, long long spin_ticks) {\n";
+    o << "extern \"C\" __global__ void __launch_bounds__(tdf::GEN_LOCAL_BLOCK) tdf_generated_step_local(tdf::Engine e, int max_steps, long long spin_ticks) {\n";
     o << "  extern __shared__ __attribute__((aligned(16))) char lds[];\n";
     o << "  __shared__ tdf::DevProgram P;\n  __shared__ uint32_t sh[4];\n";
     o << "  tdf::steps_grid<true, tdf::GeneratedSweep>(e, max_steps, spin_ticks, lds, &P, sh);\n}\n";
-    o << "extern \"C\" __global__ void __launch_bounds__(512) tdf_generated_small(tdf::Engine e, int max_steps) {\n";
+    o << "extern \"C\" __global__ void __launch_bounds__(tdf::GEN_SMALL_BLOCK) tdf_generated_small(tdf::Engine e, int max_steps) {\n";
     o << "  extern __shared__ __attribute__((aligned(16))) char lds[];\n";
     o << "  __shared__ tdf::DevProgram P;\n  __shared__ tdf::Ctrl lc;\n";
     o << "  tdf::steps_small<tdf::GeneratedSweep>(e, max_steps, lds, &P, &lc);\n}\n";

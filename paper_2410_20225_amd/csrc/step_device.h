@@ -499,7 +499,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
             const uint32_t label = meta & 0xFFu, param = (meta >> 8) & 0xFFu;
             m.callee = P.label_callee[label];
             m.ckey = ((unsigned long long)(x.frame + 1u) << 32) | ((unsigned long long)(depth + 1u) << 8) | (label + 1u);
-            m.target = (uint32_t)mix64(m.ckey) & e.cap_mask;
+            m.target = e.key_base + ((uint32_t)mix64(m.ckey) & e.part_mask);
             m.slot = param;
             m.bits = (1u << param) | (m.callee << 24);
           } else {
@@ -550,7 +550,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         for (int q = 0; q < 2; ++q)
           if (need[q]) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) w[q][j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[(em[q].target + 1u + j) & e.cap_mask]);
+            for (int j = 0; j < 8; ++j) w[q][j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[slot_after(e, em[q].target, 1u + j)]);
           }
 #pragma unroll
         for (int q = 0; q < 2; ++q)
@@ -562,7 +562,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
                 claim[q] = w[q][j];
               }
             if (cj[q] < 8 && claim[q] == 0)
-              claim[q] = a_cas<SCOPE>(&e.keys[(em[q].target + 1u + cj[q]) & e.cap_mask], 0ull, em[q].ckey);
+              claim[q] = a_cas<SCOPE>(&e.keys[slot_after(e, em[q].target, 1u + cj[q])], 0ull, em[q].ckey);
           }
 #pragma unroll
         for (int q = 0; q < 2; ++q)
@@ -570,7 +570,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
             ins[q] = claim[q] == 0;
             found[q] = true;
             need[q] = false;
-            em[q].target = (em[q].target + 1u + cj[q]) & e.cap_mask;
+            em[q].target = slot_after(e, em[q].target, 1u + cj[q]);
             probes[q] = 2 + cj[q];
           }
       }
@@ -584,27 +584,27 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
             m.target = em[0].target;
           }
           // ... then, rarely (a lost race, or eight occupied slots in a row), one token at a time
-          const uint32_t probe_limit = e.cap < 8192u ? e.cap : 8192u;
+          const uint32_t probe_limit = e.part_mask < 8192u ? e.part_mask + 1u : 8192u;
           while (need[q] && probes[q] < probe_limit) {
             unsigned long long v[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[(m.target + 1u + j) & e.cap_mask]);
+            for (int j = 0; j < 8; ++j) v[j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[slot_after(e, m.target, 1u + j)]);
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
               if (!need[q]) break;
               if (v[j] == 0) {   // looked empty: claim it, or learn who did
-                v[j] = a_cas<SCOPE>(&e.keys[(m.target + 1u + j) & e.cap_mask], 0ull, m.ckey);
+                v[j] = a_cas<SCOPE>(&e.keys[slot_after(e, m.target, 1u + j)], 0ull, m.ckey);
                 ins[q] = v[j] == 0;
               }
               if (ins[q] || v[j] == m.ckey) {
                 found[q] = true;
                 need[q] = false;
-                m.target = (m.target + 1u + j) & e.cap_mask;
+                m.target = slot_after(e, m.target, 1u + j);
                 probes[q] += j + 1;
               }
             }
             if (need[q]) {
-              m.target = (m.target + 8u) & e.cap_mask;
+              m.target = slot_after(e, m.target, 8u);
               probes[q] += 8;
             }
           }
@@ -736,6 +736,7 @@ __device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { ret
 
 constexpr int STEP_BLOCK = 256;    // lanes per workgroup of the grid-wide kernel
 constexpr int LOCAL_BLOCK = 512;   // ... and of its variant that keeps to one accelerator die
+constexpr int GEN_SMALL_BLOCK = 512, GEN_LOCAL_BLOCK = 512;   // launch bounds of the generated kernels
 
 // Grid-wide steps: the workgroups of one launch (all resident at once: the host launches no
 // more than the GPU holds) run step after step; each takes a slice of the touched list, and a
@@ -744,11 +745,13 @@ constexpr int LOCAL_BLOCK = 512;   // ... and of its variant that keeps to one a
 // an error and ends the run, so every wave leaves the kernel in any case.  Returns when the
 // recursion is finished, when the next step is small, or after max_steps steps.
 //
-// LOCAL: only every eighth workgroup of the launch takes part.  Workgroups are handed to the
-// eight accelerator dies (XCDs) in turn, so these all run on one die and share its L2: frame
-// atomics then execute in that L2 (workgroup scope) instead of in memory, and a step boundary
-// needs no L2 write-back or invalidation, only an invalidation of the per-CU L1.  The dies seen
-// are recorded in Ctrl::xcc_mask; the host discards the run if there was more than one.
+// LOCAL: workgroups are handed to the eight accelerator dies (XCDs) in turn, so workgroups
+// i, i + 8, i + 16, ... of a launch run on one die and share its L2; they serve machine i % 8
+// (machines beyond n_dies have none: their workgroups return at once).  The frame atomics of a
+// machine then execute in that L2 (workgroup scope) instead of in memory, and a step boundary
+// needs no L2 write-back or invalidation, only an invalidation of the per-CU L1.  The dies a
+// machine ran on are recorded in its Ctrl::xcc_mask; the host discards the run if any machine
+// saw more than one.  Not LOCAL: one machine, all workgroups, device scope.
 constexpr uint32_t XCDS = 8;
 
 __device__ __forceinline__ void l1_invalidate() {
@@ -767,13 +770,15 @@ template <bool LOCAL> __device__ __forceinline__ void ctrl_fence() {
 template <bool LOCAL, class SW>
 __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* lds, DevProgram* P_lds, uint32_t* sh) {
   constexpr int SCOPE = LOCAL ? __HIP_MEMORY_SCOPE_WORKGROUP : __HIP_MEMORY_SCOPE_AGENT;
-  Ctrl* c = e.ctrl;
-  uint32_t G = gridDim.x, rank = blockIdx.x;
-  if (LOCAL) {
-    if (blockIdx.x % XCDS != 0) return;
-    G = (gridDim.x + XCDS - 1) / XCDS;
+  uint32_t G = gridDim.x, rank = blockIdx.x, die = 0;
+  if (LOCAL) {   // workgroup i runs on die i % 8 and serves machine i % 8
+    die = blockIdx.x % XCDS;
+    if (die >= e.n_dies) return;
+    G = gridDim.x / XCDS;
     rank = blockIdx.x / XCDS;
   }
+  e = die_view(e, die);
+  Ctrl* c = e.ctrl;
   // Nothing changes these before the first barrier completes, and a workgroup reads them before
   // it arrives there: all workgroups see the same values and take the same way.
   uint32_t gen = ld(&c->bar_gen);
@@ -829,6 +834,7 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
 // when a step is too large for one workgroup, or after max_steps steps.
 template <class SW>
 __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_lds, Ctrl* lc_) {
+  e = die_view(e, blockIdx.x);   // one workgroup per machine
   Ctrl& lc = *lc_;
   Ctrl* g = e.ctrl;
   {

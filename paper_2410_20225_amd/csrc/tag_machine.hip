@@ -1,6 +1,8 @@
 // Kernels and launchers of the tag machine.  The step logic itself is in step_device.h; this
 // file instantiates it with the table interpreter and adds the seed, the post-run firing
 // counts and the bucketing of the cell log by dependency level.
+#include <stdlib.h>
+
 #include "bucket.h"
 #include "step_device.h"
 #include "tdf_internal.h"
@@ -22,8 +24,30 @@ __global__ void k_seed(DevProgram P, Engine e) {
   h->fired = 0;
   h->present_fn = ((1u << np) - 1u) | ((uint32_t)P.result_fn << 24);
   h->arrived[0] = h->arrived[1] = 0;
-  e.touched[b] = f;
-  if (b == 0) e.ctrl->touched_count[0] = e.n_inst;
+  // instance b belongs to machine b % n_dies
+  const uint32_t d = b % e.n_dies, pos = b / e.n_dies;
+  e.touched[(size_t)d * 2 * e.touched_cap + pos] = f;
+  if (pos == 0) e.ctrl[d].touched_count[0] = (e.n_inst - d + e.n_dies - 1) / e.n_dies;
+}
+
+// ---- after the last step: the machines' schedule logs, one after the other ------------------
+struct LogOffsets {
+  uint32_t leaf[9], cell[9];   // first entry of machine d in the merged logs; [n_dies] = totals
+};
+__global__ void k_merge_logs(Engine e, LogOffsets o) {
+  const uint32_t d = blockIdx.y;
+  const Engine m = die_view(e, d);
+  const uint32_t n_leaf = o.leaf[d + 1] - o.leaf[d], n_cell = o.cell[d + 1] - o.cell[d];
+  for (uint32_t j = blockIdx.x * blockDim.x + threadIdx.x; j < n_leaf; j += gridDim.x * blockDim.x) {
+    e.leaf_row[o.leaf[d] + j] = m.leaf_row[j];
+    e.leaf_tok[o.leaf[d] + j] = m.leaf_tok[j];
+  }
+  for (uint32_t j = blockIdx.x * blockDim.x + threadIdx.x; j < n_cell; j += gridDim.x * blockDim.x) {
+    e.cell_out[o.cell[d] + j] = m.cell_out[j];
+    e.cell_l[o.cell[d] + j] = m.cell_l[j];
+    e.cell_r[o.cell[d] + j] = m.cell_r[j];
+    e.cell_lvl[o.cell[d] + j] = m.cell_lvl[j];
+  }
 }
 
 template <int NV, bool LOCAL>
@@ -71,8 +95,7 @@ __global__ void k_count_fired(DevProgram P, Engine e) {
 // ---- cells by dependency level --------------------------------------------------------------
 // A cell's level is 1 + the larger level of its two operands (leaves are level 0); cells of
 // one level are independent of each other.  Counting sort of the firing log by level.
-__global__ void k_level_hist(Engine e) {
-  const uint32_t n = e.ctrl->n_cell;
+__global__ void k_level_hist(Engine e, uint32_t n) {
   for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
     const uint32_t j = base + threadIdx.x;
     (void)wave_alloc_keyed(j < n, j < n ? e.cell_lvl[j] : 0, e.level_count);
@@ -88,11 +111,11 @@ struct LevelSink {   // the level-sorted copy of the cell log
   }
 };
 
-__global__ void k_level_scan(Engine e) {
+__global__ void k_level_scan(Engine e, uint32_t max_level) {
   // single block; levels 1..max_level
   __shared__ uint32_t carry;
   __shared__ uint32_t buf[1024];
-  const uint32_t L = e.ctrl->max_level + 2;
+  const uint32_t L = max_level + 2;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
   for (uint32_t base = 0; base < L; base += 1024) {
@@ -113,8 +136,7 @@ __global__ void k_level_scan(Engine e) {
   }
 }
 
-__global__ void k_level_scatter(Engine e) {
-  const uint32_t n = e.ctrl->n_cell;
+__global__ void k_level_scatter(Engine e, uint32_t n) {
   for (uint32_t base = blockIdx.x * blockDim.x; base < n; base += gridDim.x * blockDim.x) {
     const uint32_t j = base + threadIdx.x;
     const bool on = j < n;
@@ -145,11 +167,20 @@ void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s) {
 // Register value file when every function has at most 16 values and 8 stored values.
 static bool fits_registers(const Sizes& z) { return z.max_values <= 16 && z.max_stored <= 8; }
 
+// Workgroup size of a generated kernel: `name` in the environment (a multiple of 64 up to the
+// kernel's launch bound), else `def`.
+static int env_block(const char* name, int def, int max) {
+  const char* e = getenv(name);
+  const int v = e ? atoi(e) : def;
+  return v >= 64 && v <= max && v % 64 == 0 ? v : def;
+}
+
 // Lanes of the single-workgroup kernel: as many as the per-lane LDS footprint allows.
 int tag_machine_small_block(const DevProgram& P, bool jit) {
   const Sizes z = sizes_of(P);
   const bool lds_values = !jit && !fits_registers(z);
   int rb = 512;
+  if (jit) rb = env_block("TDF_SMALL_BLOCK", 512, GEN_SMALL_BLOCK);
   while (rb > 64 && step_lds_bytes(z, rb, lds_values) > 120 * 1024) rb >>= 1;
   return rb;
 }
@@ -172,8 +203,8 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
     long long st = spin_ticks;
     void* a_small[] = {&ev, &ms};
     void* a_step[] = {&ev, &ms, &st};
-    const int gb = local ? LOCAL_BLOCK : STEP_BLOCK;
-    hipError_t r = hipModuleLaunchKernel((hipFunction_t)jit.small, 1, 1, 1, small_block, 1, 1,
+    const int gb = local ? env_block("TDF_LOCAL_BLOCK", 512, GEN_LOCAL_BLOCK) : STEP_BLOCK;
+    hipError_t r = hipModuleLaunchKernel((hipFunction_t)jit.small, e.n_dies, 1, 1, small_block, 1, 1,
                                          (unsigned)step_lds_bytes(z, small_block, false), s, a_small, nullptr);
     if (r == hipSuccess)
       r = hipModuleLaunchKernel((hipFunction_t)(local ? jit.step_local : jit.step), grid, 1, 1, gb, 1, 1,
@@ -190,7 +221,7 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_small<0>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)small_lds);
   if (in_regs) {
-    hipLaunchKernelGGL(k_steps_small<16>, dim3(1), dim3(small_block), small_lds, s, e, max_steps);
+    hipLaunchKernelGGL(k_steps_small<16>, dim3(e.n_dies), dim3(small_block), small_lds, s, e, max_steps);
     if (local)
       hipLaunchKernelGGL((k_steps_grid<16, true>), dim3(grid), dim3(LOCAL_BLOCK), step_lds_bytes(z, LOCAL_BLOCK, false), s, e,
                          max_steps, spin_ticks);
@@ -206,13 +237,24 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_steps_grid<0, false>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)grid_lds);
     }
-    hipLaunchKernelGGL(k_steps_small<0>, dim3(1), dim3(small_block), small_lds, s, e, max_steps);
+    hipLaunchKernelGGL(k_steps_small<0>, dim3(e.n_dies), dim3(small_block), small_lds, s, e, max_steps);
     if (local)
       hipLaunchKernelGGL((k_steps_grid<0, true>), dim3(grid), dim3(128), grid_lds, s, e, max_steps, spin_ticks);
     else
       hipLaunchKernelGGL((k_steps_grid<0, false>), dim3(grid), dim3(128), grid_lds, s, e, max_steps, spin_ticks);
   }
   return TDF_OK;
+}
+
+// Copies the machines' logs into the merged logs; leaf_off / cell_off: n_dies + 1 prefix sums.
+void launch_merge_logs(const Engine& e, const uint32_t* leaf_off, const uint32_t* cell_off, hipStream_t s) {
+  if (e.n_dies <= 1) return;   // one machine writes the merged logs directly
+  LogOffsets o{};
+  for (uint32_t d = 0; d <= e.n_dies; ++d) {
+    o.leaf[d] = leaf_off[d];
+    o.cell[d] = cell_off[d];
+  }
+  hipLaunchKernelGGL(k_merge_logs, dim3(64, e.n_dies), dim3(256), 0, s, e, o);
 }
 
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s) {
@@ -227,15 +269,15 @@ void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStre
     bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_place<LevelSink>), n_keys);
     hipLaunchKernelGGL(k_bucket_count, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.cell_lvl, n_cell, n_keys,
                        e.level_count);
-    hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e);
+    hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e, max_level);
     hipLaunchKernelGGL(k_bucket_place<LevelSink>, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.cell_lvl, n_cell,
                        n_keys, e.level_off, e.level_fill, LevelSink{e});
     return;
   }
   int g = grid_for(n_cell, 256, 2048);
-  hipLaunchKernelGGL(k_level_hist, dim3(g), dim3(256), 0, s, e);
-  hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e);
-  hipLaunchKernelGGL(k_level_scatter, dim3(g), dim3(256), 0, s, e);
+  hipLaunchKernelGGL(k_level_hist, dim3(g), dim3(256), 0, s, e, n_cell);
+  hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e, max_level);
+  hipLaunchKernelGGL(k_level_scatter, dim3(g), dim3(256), 0, s, e, n_cell);
 }
 
 }  // namespace tdf

@@ -42,7 +42,8 @@ void jit_release(JitKernels& k);
 struct tdf_graph {
   tdf::Graph g;
   tdf::JitKernels jit;
-  bool die_local = true;    // grid-wide steps on one accelerator die (cleared if the GPU spreads them)
+  bool die_local = true;    // tag machines keep to one accelerator die each (cleared if the GPU spreads them)
+  uint32_t max_dies = 8;    // tag machines a batch is dealt to (set to 1 after a part of the table overflowed)
   void* events[2 * TDF_PHASE_COUNT] = {nullptr};   // hipEvent_t pairs, created on first use
   ~tdf_graph();
 };
