@@ -8,7 +8,7 @@
 namespace tdf {
 namespace {   // every translation unit that includes this header gets its own copy of the kernels
 
-constexpr uint32_t BUCKET_MAX_KEYS = 32768;   // LDS histogram entries (128 KB)
+constexpr uint32_t BUCKET_MAX_KEYS = 40000;   // LDS histogram entries (156 KB of the 160)
 constexpr int BUCKET_BLOCKS = 256;
 constexpr int BUCKET_THREADS = 512;
 

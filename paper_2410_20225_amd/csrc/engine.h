@@ -52,6 +52,8 @@ struct FrameHdr {
 };
 static_assert(sizeof(FrameHdr) == 32, "FrameHdr must be 32 bytes");
 
+constexpr uint32_t LEVEL_KEY_DIES = 8;
+
 // Pointers into the workspace and to the caller's buffers, passed to kernels by value.
 //
 // The instances of a batch never exchange tokens (their tags differ in the root), so the batch
@@ -90,10 +92,12 @@ struct Engine {
   // frame that produced it (row id = frame id)
   uint32_t log_cap;                 // entries of the leaf / cell logs (0: no vector operators)
   uint32_t *leaf_row, *leaf_tok;    // [n_leaf]
-  uint32_t *cell_out, *cell_l, *cell_r, *cell_lvl;   // [n_cell], in firing order
+  uint32_t *cell_out, *cell_l, *cell_r, *cell_lvl;   // [n_cell], in firing order; cell_lvl holds the sort key
   uint32_t *head_row, *head_label;  // [B]
   // cells bucketed by dependency level
-  uint32_t *level_count, *level_off, *level_fill;    // [max_levels + 2]
+  // The log's sort key is level * LEVEL_KEY_DIES + machine: a level is one contiguous range of
+  // the sorted log, and inside it the cells of every machine (die) are contiguous too.
+  uint32_t *level_count, *level_off, *level_fill;    // [(max_levels + 2) * LEVEL_KEY_DIES]
   uint32_t max_levels;
   uint32_t *q_out, *q_l, *q_r;      // [n_cell], sorted by level
 };

@@ -111,8 +111,6 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   L.zero_begin = L.total;
   P.off_ctrl = L.take(sizeof(Ctrl) * 8);
   P.off_fire = L.take(sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS);
-  size_t off_lcount = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
-  size_t off_lfill = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
   P.off_tok_count = P.off_tok_fill = 0;
   if (P.vec && with_grad) {
     P.off_tok_count = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
@@ -127,7 +125,10 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_root = L.take(sizeof(uint32_t) * B);
   size_t off_hrow = L.take(sizeof(uint32_t) * B);
   size_t off_hlab = L.take(sizeof(uint32_t) * B);
-  size_t off_loff = L.take(sizeof(uint32_t) * ((size_t)e.max_levels + 2));
+  const size_t level_keys = ((size_t)e.max_levels + 2) * LEVEL_KEY_DIES;   // cleared as far as used, after the steps
+  size_t off_lcount = L.take(sizeof(uint32_t) * level_keys);
+  size_t off_lfill = L.take(sizeof(uint32_t) * level_keys);
+  size_t off_loff = L.take(sizeof(uint32_t) * level_keys);
   size_t rc = std::max<size_t>(e.log_cap, 1);
   size_t off_leaf_row = L.take(4 * rc), off_leaf_tok = L.take(4 * rc);
   size_t off_c_out = L.take(4 * rc), off_c_l = L.take(4 * rc), off_c_r = L.take(4 * rc), off_c_lvl = L.take(4 * rc);
@@ -381,7 +382,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   end(TDF_PHASE_TAGS, 2 + 2ll * rounds);
   tdf_status dev = status_from_device(hc.status);
 
-  std::vector<uint32_t> level_off;
+  std::vector<uint32_t> level_off;   // by sort key (level, machine)
+  auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
     begin(TDF_PHASE_LEAVES);
@@ -391,13 +393,13 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (hc.n_cell) {
       begin(TDF_PHASE_LEVELS);
       launch_levels(e, hc.n_cell, hc.max_level, s);
-      level_off.resize((size_t)hc.max_level + 2);
+      level_off.resize(((size_t)hc.max_level + 2) * LEVEL_KEY_DIES);
       HIP_TRY(hipMemcpyAsync(level_off.data(), e.level_off, level_off.size() * 4, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 3);
       HIP_TRY(hipStreamSynchronize(s));
       begin(TDF_PHASE_CELLS_FWD);
       for (uint32_t lvl = 1; lvl <= hc.max_level; ++lvl)
-        vec_cell_fwd(v, e, level_off[lvl], level_off[lvl + 1] - level_off[lvl], with_grad, s);
+        vec_cell_fwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), with_grad, s);
       end(TDF_PHASE_CELLS_FWD, hc.max_level);
     }
     begin(TDF_PHASE_HEAD);
@@ -413,7 +415,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       // ---- gradient pass: the level schedule walked backwards -----------------------------
       begin(TDF_PHASE_CELLS_BWD);
       for (uint32_t lvl = hc.max_level; lvl >= 1 && hc.n_cell; --lvl)
-        vec_cell_bwd(v, e, level_off[lvl], level_off[lvl + 1] - level_off[lvl], s);
+        vec_cell_bwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), s);
       end(TDF_PHASE_CELLS_BWD, 2ll * hc.max_level);
       begin(TDF_PHASE_WEIGHT_GRAD);
       if (hc.n_cell) {

@@ -175,12 +175,12 @@ __device__ __forceinline__ void sw_cell(LaneCtx& x, bool on, int slot, long long
     const uint32_t la = (uint32_t)(av >> 32), lb = (uint32_t)(bv >> 32);
     const uint32_t lvl = 1 + (la > lb ? la : lb);
     if (!x.direct) {
-      x.stg_cell[pos] = make_uint4(x.frame, (uint32_t)av, (uint32_t)bv, lvl);
+      x.stg_cell[pos] = make_uint4(x.frame, (uint32_t)av, (uint32_t)bv, lvl * LEVEL_KEY_DIES + x.e->die);
     } else if (pos < x.e->log_cap) {
       x.e->cell_out[pos] = x.frame;
       x.e->cell_l[pos] = (uint32_t)av;
       x.e->cell_r[pos] = (uint32_t)bv;
-      x.e->cell_lvl[pos] = lvl;
+      x.e->cell_lvl[pos] = lvl * LEVEL_KEY_DIES + x.e->die;
     } else {
       raise(x.c, TDF_ERR_TABLE_FULL);
     }

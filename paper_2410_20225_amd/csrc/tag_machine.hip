@@ -115,7 +115,7 @@ __global__ void k_level_scan(Engine e, uint32_t max_level) {
   // single block; levels 1..max_level
   __shared__ uint32_t carry;
   __shared__ uint32_t buf[1024];
-  const uint32_t L = max_level + 2;
+  const uint32_t L = (max_level + 2) * LEVEL_KEY_DIES;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
   for (uint32_t base = 0; base < L; base += 1024) {
@@ -203,7 +203,7 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
     long long st = spin_ticks;
     void* a_small[] = {&ev, &ms};
     void* a_step[] = {&ev, &ms, &st};
-    const int gb = local ? env_block("TDF_LOCAL_BLOCK", 512, GEN_LOCAL_BLOCK) : STEP_BLOCK;
+    const int gb = local ? env_block("TDF_LOCAL_BLOCK", 256, GEN_LOCAL_BLOCK) : STEP_BLOCK;
     hipError_t r = hipModuleLaunchKernel((hipFunction_t)jit.small, e.n_dies, 1, 1, small_block, 1, 1,
                                          (unsigned)step_lds_bytes(z, small_block, false), s, a_small, nullptr);
     if (r == hipSuccess)
@@ -262,7 +262,9 @@ void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s) {
 }
 
 void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStream_t s) {
-  const uint32_t n_keys = max_level + 2;
+  const uint32_t n_keys = (max_level + 2) * LEVEL_KEY_DIES;
+  (void)hipMemsetAsync(e.level_count, 0, sizeof(uint32_t) * n_keys, s);
+  (void)hipMemsetAsync(e.level_fill, 0, sizeof(uint32_t) * n_keys, s);
   if (bucket_fits(n_keys)) {
     const size_t lds = (size_t)n_keys * 4;
     bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_count), n_keys);
