@@ -9,6 +9,7 @@
 #include <algorithm>
 
 #include "bucket.h"
+#include "die_sync.h"
 #include "engine.h"
 
 namespace tdf {
@@ -86,6 +87,7 @@ struct GemmArgs {
   size_t lda;
   const void* B;
   size_t ldb;
+  const void* Bf;            // B in operand order (frag_offset), for the small-level kernel
   // gathered A rows for the forward cells: row m = [Hs[l[m]]; Hs[r[m]]]
   const void* Hs;
   int Hp;
@@ -335,6 +337,16 @@ template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int 
 // Operands are fetched as 16-byte chunks: for bf16 one chunk is one 32x32x16 operand; for fp32
 // a chunk of four k-values feeds four 32x32x2 products, component j of both operands in
 // product j (a fixed permutation of the reduction index).
+// Operand order of a k-contiguous matrix [rows x K] for 32-row MFMA operands: the 16-byte chunks
+// that the 64 lanes of a wave feed into one product step are stored one after the other (lane l
+// holds row 32 rt + l % 32, reduction indices s * KC + (l / 32) * EPC ...), so a wave fetches an
+// operand with one fully coalesced 1 KB load instead of touching 32 rows.
+template <typename T> __host__ __device__ inline size_t frag_offset(int row, int k, int K) {
+  constexpr int EPC = 16 / (int)sizeof(T), KC = 2 * EPC;
+  const int rt = row >> 5, r = row & 31, st = k / KC, kk = k % KC, half = kk / EPC, el = kk % EPC;
+  return (((size_t)rt * (K / KC) + st) * 64 + half * 32 + r) * EPC + el;
+}
+
 template <typename T> struct Chunk;
 template <> struct Chunk<__bf16> {
   static constexpr int KC = 16;   // reduction indices covered by one chunk step of a wave
@@ -355,18 +367,15 @@ template <> struct Chunk<float> {
   }
 };
 
+// One tile: rows 32 rt .. 32 rt + 31 of the level, hidden units (output columns) 32 ct .. 32 ct + 31.
+// Called by all 256 threads of a workgroup; `part` is its LDS scratch [wave][G][16][64].
 template <int DT, int MODE>
-__global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
+__device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int ct, float* part) {
   typedef typename TypeOf<DT>::type T;
   typedef Chunk<T> C;
   constexpr int G = MODE == LSTM_FWD ? 5 : 1;      // 32-wide column blocks per tile
   constexpr int BATCH = MODE == LSTM_FWD ? 4 : 8;  // chunk steps in flight
   constexpr int EPC = 16 / (int)sizeof(T);         // elements per chunk
-  extern __shared__ __attribute__((aligned(16))) char smem[];
-  float* part = reinterpret_cast<float*>(smem);    // [wave][G][16][64]
-
-  const int n_ct = g.n_tiles_n;                    // column tiles of 32
-  const int ct = blockIdx.x % n_ct, rt = blockIdx.x / n_ct;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m0 = rt * 32;
   const int mA = min(m0 + (lane & 31), g.M - 1);   // operand row of this lane
@@ -389,11 +398,11 @@ __global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
     Ap = reinterpret_cast<const T*>(g.Hs) + (size_t)child * g.Hp + (wave & 1) * kw;
   }
   Ap += (lane >> 5) * EPC;
-  const T* Bp[G];
+  const T* Bp[G];   // operand order: chunk step st of this wave is 64 * EPC elements further on
 #pragma unroll
   for (int j = 0; j < G; ++j) {
-    const int brow = (MODE == LSTM_FWD ? j * g.Hp : 0) + ct * 32 + (lane & 31);
-    Bp[j] = reinterpret_cast<const T*>(g.B) + (size_t)brow * g.ldb + wave * kw + (lane >> 5) * EPC;
+    const int brt = (MODE == LSTM_FWD ? j * (g.Hp / 32) : 0) + ct;
+    Bp[j] = reinterpret_cast<const T*>(g.Bf) + (((size_t)brt * (g.K / C::KC) + wave * (kw / C::KC)) * 64 + lane) * EPC;
   }
   // children's cell states for the epilogue, requested before the products start
   float cl[4], cr[4];
@@ -418,7 +427,7 @@ __global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
     for (int b = 0; b < BATCH; ++b) {
       const int st = min(s0 + b, steps - 1);       // a short last batch repeats its final chunk ...
 #pragma unroll
-      for (int j = 0; j < G; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(Bp[j] + st * C::KC);
+      for (int j = 0; j < G; ++j) fb[b][j] = *reinterpret_cast<const u32x4*>(Bp[j] + (size_t)st * 64 * EPC);
       fa[b] = *reinterpret_cast<const u32x4*>(Ap + st * C::KC);
     }
 #pragma unroll
@@ -489,6 +498,14 @@ __global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
       else g.C[(size_t)o_r[rr] * g.Hp + (unit - g.Hp)] = z[0][rr];
     }
   }
+  __syncthreads();   // `part` is free for the workgroup's next tile
+}
+
+template <int DT, int MODE>
+__global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  const int n_ct = g.n_tiles_n;                    // column tiles of 32
+  cell_small_tile<DT, MODE>(g, blockIdx.x / n_ct, blockIdx.x % n_ct, reinterpret_cast<float*>(smem));
 }
 
 // Levels of at most this many cells take the small-level kernel (TDF_SMALL_LEVEL overrides).
@@ -524,7 +541,11 @@ __global__ void k_pack_w(VecArgs v) {
     if (j < v.H && i < v.H)
       w = reinterpret_cast<const T*>(v.W)[(size_t)(gate * v.H + j) * (2 * v.H) + half * v.H + i];
     reinterpret_cast<T*>(v.Wp)[idx] = w;
-    if (v.WpT) reinterpret_cast<T*>(v.WpT)[(size_t)kp * v.Np + np] = w;
+    reinterpret_cast<T*>(v.Wf)[frag_offset<T>(np, kp, v.Kp)] = w;
+    if (v.WpT) {
+      reinterpret_cast<T*>(v.WpT)[(size_t)kp * v.Np + np] = w;
+      reinterpret_cast<T*>(v.WfT)[frag_offset<T>(kp, np, v.Np)] = w;
+    }
     if (kp == 0) v.bp[np] = j < v.H ? v.b[gate * v.H + j] : 0.f;
   }
 }
@@ -605,11 +626,8 @@ __global__ void k_out_rows(VecArgs v, Engine e, float* out_h, float* out_c) {
 // TreeRNN: delta = dh * (1 - h^2).  TreeLSTM: the gate gradients (i, f_l, f_r, o, u) and the
 // cell-state gradients handed to the two children.
 template <int DT>
-__global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
+__device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32_t q) {
   typedef typename TypeOf<DT>::type T;
-  const uint32_t m = blockIdx.x;
-  if (m >= count) return;
-  const uint32_t q = q0 + m;
   const size_t o = (size_t)e.q_out[q] * v.Hp;
   T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)q * v.Np;
   if (v.cell_kind == 1) {
@@ -635,6 +653,81 @@ __global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
       v.dC[ol + n] = dc * gfl;
       v.dC[orr + n] = dc * gfr;
     }
+  }
+}
+template <int DT>
+__global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
+  if (blockIdx.x < count) dz_row<DT>(v, e, q0 + blockIdx.x);
+}
+
+// ---- the tail of the level schedule in one launch ------------------------------------------------
+// The cells of a level are sorted by the tag machine (= die) their instance was dealt to, and a
+// cell depends only on cells of its own instance.  So each die can walk the levels on its own:
+// workgroups i, i + 8, ... of the launch take the tiles of machine i % 8's cells, level after
+// level, with a barrier among themselves (die_sync.h) where a launch boundary would be.  Used
+// for the deep levels, where a level is a few tiles per die and costs one barrier (~2 us)
+// instead of one launch (~10 us).
+struct TailArgs {
+  const uint32_t* level_off;   // first cell of (level, machine) in the sorted log, by sort key
+  uint32_t lvl_first, lvl_last;
+  uint32_t n_dies;
+  DieSync* sync;               // [8], zero on entry
+  long long spin_ticks;
+};
+
+template <int DT, int MODE>
+__global__ void __launch_bounds__(256) k_tail_fwd(GemmArgs g, TailArgs t) {
+  typedef typename TypeOf<DT>::type T;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ uint32_t sh_ok;
+  float* part = reinterpret_cast<float*>(smem);
+  const uint32_t die = blockIdx.x % XCDS, rank = blockIdx.x / XCDS, G = gridDim.x / XCDS;
+  if (die >= t.n_dies) return;
+  DieSync* sy = t.sync + die;
+  if (threadIdx.x == 0) atomicOr(&sy->xcc_mask, 1u << xcc_id());
+  const int n_ct = g.n_tiles_n;
+  uint32_t gen = 0;
+  for (uint32_t lvl = t.lvl_first; lvl <= t.lvl_last; ++lvl) {
+    const uint32_t q0 = t.level_off[lvl * LEVEL_KEY_DIES + die];
+    const uint32_t cnt = t.level_off[lvl * LEVEL_KEY_DIES + die + 1] - q0;
+    GemmArgs gl = g;
+    gl.M = (int)cnt;
+    gl.out = g.out + q0; gl.l = g.l + q0; gl.r = g.r + q0;
+    gl.gates = g.gates ? reinterpret_cast<T*>(g.gates) + (size_t)q0 * g.ldg : nullptr;
+    const uint32_t tiles = (cnt + 31) / 32 * (uint32_t)n_ct;
+    for (uint32_t tile = rank; tile < tiles; tile += G)
+      cell_small_tile<DT, MODE>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+    if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
+  }
+}
+
+// Gradient pass over the same levels, deepest first: dz of the die's cells of a level, barrier,
+// their input gradients, barrier.
+template <int DT>
+__global__ void __launch_bounds__(256) k_tail_bwd(GemmArgs g, VecArgs v, Engine e, TailArgs t) {
+  typedef typename TypeOf<DT>::type T;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+  __shared__ uint32_t sh_ok;
+  float* part = reinterpret_cast<float*>(smem);
+  const uint32_t die = blockIdx.x % XCDS, rank = blockIdx.x / XCDS, G = gridDim.x / XCDS;
+  if (die >= t.n_dies) return;
+  DieSync* sy = t.sync + die;
+  if (threadIdx.x == 0) atomicOr(&sy->xcc_mask, 1u << xcc_id());
+  const int n_ct = g.n_tiles_n;
+  uint32_t gen = 0;
+  for (uint32_t lvl = t.lvl_last; lvl >= t.lvl_first; --lvl) {
+    const uint32_t q0 = t.level_off[lvl * LEVEL_KEY_DIES + die];
+    const uint32_t cnt = t.level_off[lvl * LEVEL_KEY_DIES + die + 1] - q0;
+    for (uint32_t m = rank; m < cnt; m += G) dz_row<DT>(v, e, q0 + m);
+    if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
+    GemmArgs gl = g;
+    gl.M = (int)cnt;
+    gl.A = reinterpret_cast<const T*>(g.A) + (size_t)q0 * g.lda;
+    gl.l = g.l + q0; gl.r = g.r + q0;
+    const uint32_t tiles = (cnt + 31) / 32 * (uint32_t)n_ct;
+    for (uint32_t tile = rank; tile < tiles; tile += G)
+      cell_small_tile<DT, DX_BWD>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+    if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
   }
 }
 
@@ -832,7 +925,7 @@ template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, 
                                              int save_gates, hipStream_t s) {
   GemmArgs g{};
   g.M = (int)count; g.N = v.Np; g.K = v.Kp;
-  g.B = v.Wp; g.ldb = v.Kp;
+  g.B = v.Wp; g.ldb = v.Kp; g.Bf = v.Wf;
   g.Hs = v.Hs; g.Hp = v.Hp;
   g.out = e.q_out + q0; g.l = e.q_l + q0; g.r = e.q_r + q0;
   g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
@@ -858,7 +951,7 @@ template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, 
   GemmArgs g{};
   g.M = (int)count; g.N = v.Kp; g.K = v.Np;
   g.A = reinterpret_cast<const T*>(v.Dz) + (size_t)q0 * v.Np; g.lda = v.Np;
-  g.B = v.WpT; g.ldb = v.Np;
+  g.B = v.WpT; g.ldb = v.Np; g.Bf = v.WfT;
   g.Hp = v.Hp; g.l = e.q_l + q0; g.r = e.q_r + q0;
   g.C = v.dH;
   if (count <= small_level()) launch_cell_small<T, DX_BWD>(g, v.Kp / 32, s);
@@ -866,6 +959,55 @@ template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, 
 }
 void vec_cell_bwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s) {
   if (v.dtype == TDF_BF16) cell_bwd_t<__bf16>(v, e, q0, count, s); else cell_bwd_t<float>(v, e, q0, count, s);
+}
+
+uint32_t vec_small_level() { return small_level(); }
+
+// The levels lvl_first .. lvl_last in one launch, every die walking its own cells (k_tail_fwd).
+// level_off: device array of first cells by sort key; sync: eight zeroed DieSync records.
+template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, const TailArgs& t, int cus, int save_gates,
+                                             hipStream_t s) {
+  GemmArgs g{};
+  g.N = v.Np; g.K = v.Kp;
+  g.B = v.Wp; g.ldb = v.Kp; g.Bf = v.Wf;
+  g.Hs = v.Hs; g.Hp = v.Hp;
+  g.out = e.q_out; g.l = e.q_l; g.r = e.q_r;
+  g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
+  g.gates = v.gates; g.ldg = v.Np; g.save_gates = save_gates && v.gates;
+  g.n_tiles_n = v.Hp / 32;
+  const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
+  if (v.cell_kind == 2) {
+    const size_t lds = (size_t)4 * 5 * 16 * 64 * sizeof(float);
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_fwd<DtOf<T>::value, LSTM_FWD>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, LSTM_FWD>), dim3(grid), dim3(256), lds, s, g, t);
+  } else {
+    const size_t lds = (size_t)4 * 16 * 64 * sizeof(float);
+    hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, RNN_FWD>), dim3(grid), dim3(256), lds, s, g, t);
+  }
+}
+void vec_tail_fwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
+                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, int save_gates, hipStream_t s) {
+  TailArgs t{level_off, lvl_first, lvl_last, n_dies, (DieSync*)sync, spin_ticks};
+  if (v.dtype == TDF_BF16) tail_fwd_t<__bf16>(v, e, t, cus, save_gates, s); else tail_fwd_t<float>(v, e, t, cus, save_gates, s);
+}
+
+template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, const TailArgs& t, int cus, hipStream_t s) {
+  GemmArgs g{};
+  g.N = v.Kp; g.K = v.Np;
+  g.A = v.Dz; g.lda = v.Np;
+  g.B = v.WpT; g.ldb = v.Np; g.Bf = v.WfT;
+  g.Hp = v.Hp; g.l = e.q_l; g.r = e.q_r;
+  g.C = v.dH;
+  g.n_tiles_n = v.Kp / 32;
+  const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
+  const size_t lds = (size_t)4 * 16 * 64 * sizeof(float);
+  hipLaunchKernelGGL((k_tail_bwd<DtOf<T>::value>), dim3(grid), dim3(256), lds, s, g, v, e, t);
+}
+void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
+                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, hipStream_t s) {
+  TailArgs t{level_off, lvl_first, lvl_last, n_dies, (DieSync*)sync, spin_ticks};
+  if (v.dtype == TDF_BF16) tail_bwd_t<__bf16>(v, e, t, cus, s); else tail_bwd_t<float>(v, e, t, cus, s);
 }
 
 void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s) {

@@ -229,6 +229,8 @@ struct VecArgs {
   void* DzT;        // [Np x q_stride]
   void* XT;         // [Kp x q_stride]  (gathered [h_l;h_r] transposed)
   void* WpT;        // packed W transposed [Kp x Np]
+  void* Wf;         // Wp and WpT in MFMA operand order, for the small-level kernel
+  void* WfT;
   float* dW_part;   // split partial sums [n_split x Np x Kp]
   uint32_t q_stride;
   float* loss;      // [B]

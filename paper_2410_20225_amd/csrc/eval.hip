@@ -8,6 +8,7 @@
 #include <string>
 #include <vector>
 
+#include "die_sync.h"
 #include "engine.h"
 #include "tdf_internal.h"
 
@@ -24,6 +25,11 @@ void vec_pack_w(const VecArgs& v, hipStream_t s);
 void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s);
 void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, int save_gates, hipStream_t s);
 void vec_cell_bwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s);
+uint32_t vec_small_level();
+void vec_tail_fwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
+                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, int save_gates, hipStream_t s);
+void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
+                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, hipStream_t s);
 void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s);
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s);
 void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s);
@@ -53,7 +59,7 @@ struct Plan {
   Engine e{};
   VecArgs v{};
   bool vec = false, grad = false;
-  size_t off_ctrl, off_fire, off_frames;
+  size_t off_ctrl, off_fire, off_frames, off_tail_sync;
   // embedding-gradient and bias-gradient scratch
   size_t off_tok_count, off_tok_fill, off_seg_off, off_chunk_off, off_sorted, off_de_part, off_db_part;
   uint32_t max_cells;
@@ -116,6 +122,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     P.off_tok_count = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
     P.off_tok_fill = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
   }
+  P.off_tail_sync = L.take(sizeof(DieSync) * 16);   // forward and gradient tail launches
   size_t off_keys = L.take(sizeof(unsigned long long) * (size_t)e.cap);
   L.zero_end = L.total;
   P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));   // headers are written on insertion
@@ -191,11 +198,14 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     size_t off_Hs = L.take(R * v.Hp * el);
     size_t off_Cs = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
     size_t off_Wp = L.take((size_t)v.Np * v.Kp * el);
+    size_t off_Wf = L.take((size_t)v.Np * v.Kp * el);
     size_t off_bp = L.take((size_t)v.Np * 4);
     size_t off_loss = L.take((size_t)B * 4);
     v.Hs = at(off_Hs);
     v.Cs = G.cell_kind == 2 ? (float*)at(off_Cs) : nullptr;
     v.Wp = at(off_Wp);
+    v.Wf = at(off_Wf);
+    v.WfT = nullptr;
     v.bp = (float*)at(off_bp);
     v.loss = (float*)at(off_loss);
     if (with_grad) {
@@ -207,6 +217,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       size_t off_DzT = L.take((size_t)v.Np * v.q_stride * el);
       size_t off_XT = L.take((size_t)v.Kp * v.q_stride * el);
       size_t off_WpT = L.take((size_t)v.Np * v.Kp * el);
+      size_t off_WfT = L.take((size_t)v.Np * v.Kp * el);
       size_t off_part = L.take((size_t)vec_dw_splits(v.q_stride) * v.Np * v.Kp * 4);
       P.off_db_part = L.take(((size_t)P.max_cells / DB_CHUNK + 2) * v.Np * 4);
       P.off_seg_off = L.take(4 * ((size_t)v.vocab + 2));
@@ -220,6 +231,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       v.DzT = at(off_DzT);
       v.XT = at(off_XT);
       v.WpT = at(off_WpT);
+      v.WfT = at(off_WfT);
       v.dW_part = (float*)at(off_part);
     }
   }
@@ -382,6 +394,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   end(TDF_PHASE_TAGS, 2 + 2ll * rounds);
   tdf_status dev = status_from_device(hc.status);
 
+  uint32_t tail_first = 0;
+  bool use_tail = false;
   std::vector<uint32_t> level_off;   // by sort key (level, machine)
   auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
@@ -397,10 +411,18 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       HIP_TRY(hipMemcpyAsync(level_off.data(), e.level_off, level_off.size() * 4, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 3);
       HIP_TRY(hipStreamSynchronize(s));
+      // the deep levels, each small, go into one launch in which every die walks its own cells
+      tail_first = hc.max_level + 1;
+      while (tail_first > 1 && lvl_begin(tail_first) - lvl_begin(tail_first - 1) <= vec_small_level()) --tail_first;
+      use_tail = gr->die_local && hc.max_level + 1 - tail_first >= 4;
+      if (!use_tail) tail_first = hc.max_level + 1;
       begin(TDF_PHASE_CELLS_FWD);
-      for (uint32_t lvl = 1; lvl <= hc.max_level; ++lvl)
+      for (uint32_t lvl = 1; lvl < tail_first; ++lvl)
         vec_cell_fwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), with_grad, s);
-      end(TDF_PHASE_CELLS_FWD, hc.max_level);
+      if (use_tail)
+        vec_tail_fwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync, spin_ticks, cus,
+                     with_grad, s);
+      end(TDF_PHASE_CELLS_FWD, tail_first - 1 + (use_tail ? 1 : 0));
     }
     begin(TDF_PHASE_HEAD);
     if (G.has_head) {
@@ -414,9 +436,12 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (with_grad) {
       // ---- gradient pass: the level schedule walked backwards -----------------------------
       begin(TDF_PHASE_CELLS_BWD);
-      for (uint32_t lvl = hc.max_level; lvl >= 1 && hc.n_cell; --lvl)
+      if (use_tail && hc.n_cell)
+        vec_tail_bwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync + 8 * sizeof(DieSync),
+                     spin_ticks, cus, s);
+      for (uint32_t lvl = tail_first - 1; lvl >= 1 && hc.n_cell; --lvl)
         vec_cell_bwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), s);
-      end(TDF_PHASE_CELLS_BWD, 2ll * hc.max_level);
+      end(TDF_PHASE_CELLS_BWD, 2ll * (tail_first - 1) + (use_tail ? 1 : 0));
       begin(TDF_PHASE_WEIGHT_GRAD);
       if (hc.n_cell) {
         v.q_stride = (hc.n_cell + 63) / 64 * 64;   // only the cells that fired
@@ -434,6 +459,23 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(s));
+    if (use_tail) {
+      DieSync ts[16];
+      HIP_TRY(hipMemcpy(ts, base + P.off_tail_sync, sizeof(ts), hipMemcpyDeviceToHost));
+      bool mixed = false, gave_up = false;
+      for (const DieSync& d : ts) {
+        mixed = mixed || (d.xcc_mask & (d.xcc_mask - 1)) != 0;
+        gave_up = gave_up || d.abort != 0;
+      }
+      if (gave_up) {
+        set_error("device: a workgroup waited too long at a die barrier of the level tail");
+        return TDF_ERR_DEVICE;
+      }
+      if (mixed) {   // the die-private launches did not keep to their dies: the results are void
+        gr->die_local = false;
+        return run(gr, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, with_grad);
+      }
+    }
   }
   HIP_TRY(hipGetLastError());
 

@@ -24,6 +24,7 @@
 // The sweep itself is a policy: the table interpreter below, or straight-line code generated
 // from the firing tables by the run-time compiler (jit.cpp).  Both use the same helpers.
 #pragma once
+#include "die_sync.h"
 #include "engine.h"
 
 namespace tdf {
@@ -752,13 +753,6 @@ constexpr int GEN_SMALL_BLOCK = 512, GEN_LOCAL_BLOCK = 512;   // launch bounds o
 // needs no L2 write-back or invalidation, only an invalidation of the per-CU L1.  The dies a
 // machine ran on are recorded in its Ctrl::xcc_mask; the host discards the run if any machine
 // saw more than one.  Not LOCAL: one machine, all workgroups, device scope.
-constexpr uint32_t XCDS = 8;
-
-__device__ __forceinline__ void l1_invalidate() {
-  // what a workgroup-scope acquire is when the waves of a workgroup do not share an L1
-  asm volatile("buffer_inv sc0\n\ts_waitcnt vmcnt(0)" ::: "memory");
-}
-
 // Orders this thread's accesses to the control block, which are all atomic loads, stores and
 // read-modify-writes performed in memory.  Die-local runs must not use a device-scope fence
 // for this: it would also write back and invalidate the L2 that the step kernel relies on.
@@ -785,8 +779,8 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
   uint32_t step = ld(&c->step);
   uint32_t n = ld(&c->touched_count[step & 1]);
   if (ld(&c->done) || n == 0 || step_is_small(e, n)) return;
-  if (LOCAL && threadIdx.x == 0)   // HW_REG_XCC_ID (20), bits 3:0: the die this wave runs on
-    atomicOr(&c->xcc_mask, 1u << (__builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15u));
+  if (LOCAL && threadIdx.x == 0)
+    atomicOr(&c->xcc_mask, 1u << xcc_id());
   load_program(P_lds, e.prog);
   for (int it = 0; it < max_steps; ++it) {
     if (rank * blockDim.x < n)
