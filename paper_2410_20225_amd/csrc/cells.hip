@@ -374,7 +374,7 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
   typedef typename TypeOf<DT>::type T;
   typedef Chunk<T> C;
   constexpr int G = MODE == LSTM_FWD ? 5 : 1;      // 32-wide column blocks per tile
-  constexpr int BATCH = MODE == LSTM_FWD ? 4 : 8;  // chunk steps in flight
+  constexpr int BATCH = 8;                          // chunk steps in flight
   constexpr int EPC = 16 / (int)sizeof(T);         // elements per chunk
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m0 = rt * 32;
