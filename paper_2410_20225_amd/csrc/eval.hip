@@ -338,7 +338,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       if (st != TDF_OK) return st;
       e.out_i64 = (long long*)out->out_i64;
     }
-    e.small_limit = 2u * (uint32_t)small_block;
+    e.small_limit = (uint32_t)small_block;   // one pass of the single workgroup
+    if (const char* w = getenv("TDF_SMALL_LIMIT")) e.small_limit = (uint32_t)std::max(1, atoi(w));
     HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
     HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
     launch_seed(G.prog, e, s);
@@ -467,7 +468,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         mixed = mixed || (d.xcc_mask & (d.xcc_mask - 1)) != 0;
         gave_up = gave_up || d.abort != 0;
       }
-      if (gave_up) {
+      if (gave_up && !mixed) {
         set_error("device: a workgroup waited too long at a die barrier of the level tail");
         return TDF_ERR_DEVICE;
       }
