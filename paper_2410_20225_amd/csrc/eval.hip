@@ -443,6 +443,23 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       for (uint32_t lvl = tail_first - 1; lvl >= 1 && hc.n_cell; --lvl)
         vec_cell_bwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), s);
       end(TDF_PHASE_CELLS_BWD, 2ll * (tail_first - 1) + (use_tail ? 1 : 0));
+      // The embedding gradient and the weight gradients depend on the gradient pass only, not on
+      // each other: the former runs on a second stream beside the latter.
+      if (!gr->side_stream) {
+        HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
+        HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)&gr->fork_event, hipEventDisableTiming));
+        HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)&gr->join_event, hipEventDisableTiming));
+      }
+      hipStream_t s2 = (hipStream_t)gr->side_stream;
+      HIP_TRY(hipEventRecord((hipEvent_t)gr->fork_event, s));
+      HIP_TRY(hipStreamWaitEvent(s2, (hipEvent_t)gr->fork_event, 0));
+      if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * TDF_PHASE_EMBED_GRAD], s2); phase_used[TDF_PHASE_EMBED_GRAD] = true; }
+      vec_embed_grad(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
+                     (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
+                     (uint32_t*)(base + P.off_sorted), (float*)(base + P.off_de_part), grads->dE, DE_CHUNK, s2);
+      if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * TDF_PHASE_EMBED_GRAD + 1], s2);
+      launches[TDF_PHASE_EMBED_GRAD] += 5;
+      HIP_TRY(hipEventRecord((hipEvent_t)gr->join_event, s2));
       begin(TDF_PHASE_WEIGHT_GRAD);
       if (hc.n_cell) {
         v.q_stride = (hc.n_cell + 63) / 64 * 64;   // only the cells that fired
@@ -452,11 +469,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         HIP_TRY(hipMemsetAsync(grads->db, 0, sizeof(float) * (size_t)v.N, s));
       }
       end(TDF_PHASE_WEIGHT_GRAD, 6);
-      begin(TDF_PHASE_EMBED_GRAD);
-      vec_embed_grad(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
-                     (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
-                     (uint32_t*)(base + P.off_sorted), (float*)(base + P.off_de_part), grads->dE, DE_CHUNK, s);
-      end(TDF_PHASE_EMBED_GRAD, 5);
+      HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->join_event, 0));
     }
     HIP_TRY(hipGetLastError());
     HIP_TRY(hipStreamSynchronize(s));
@@ -521,6 +534,12 @@ tdf_graph::~tdf_graph() {
   jit_release(jit);
   for (void* ev : events)
     if (ev) (void)hipEventDestroy((hipEvent_t)ev);
+  if (side_stream) {
+    (void)hipStreamSynchronize((hipStream_t)side_stream);
+    (void)hipStreamDestroy((hipStream_t)side_stream);
+  }
+  if (fork_event) (void)hipEventDestroy((hipEvent_t)fork_event);
+  if (join_event) (void)hipEventDestroy((hipEvent_t)join_event);
 }
 
 extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* in, int with_grad, size_t* bytes) {

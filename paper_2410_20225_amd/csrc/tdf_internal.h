@@ -45,5 +45,7 @@ struct tdf_graph {
   bool die_local = true;    // tag machines keep to one accelerator die each (cleared if the GPU spreads them)
   uint32_t max_dies = 8;    // tag machines a batch is dealt to (set to 1 after a part of the table overflowed)
   void* events[2 * TDF_PHASE_COUNT] = {nullptr};   // hipEvent_t pairs, created on first use
+  void* side_stream = nullptr;                     // hipStream_t for work beside the caller's stream
+  void* fork_event = nullptr, *join_event = nullptr;
   ~tdf_graph();
 };
