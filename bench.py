@@ -140,7 +140,7 @@ def main():
         ms = phase[3] / a.steps
         n_launch = launches[3] / a.steps
         peak = PEAK_BF16 if dtype == "bf16" else PEAK_F32
-        roof = {"bound": "mfma", "kernel": "k_gemm + k_cell_small <%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
+        roof = {"bound": "mfma", "kernel": "k_gemm + k_tail_fwd <%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
                 "achieved": flops_fwd / (ms * 1e-3) / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
                 "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1), "traffic": None}
     roof["frac"] = roof["achieved"] / roof["peak"]
