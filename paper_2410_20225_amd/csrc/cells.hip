@@ -735,31 +735,44 @@ __global__ void __launch_bounds__(256) k_tail_bwd(GemmArgs g, VecArgs v, Engine 
 // out[c][q] = in_row(q)[c] for q < n_q, 0 for n_q <= q < q_stride.  GATHER: in_row(q) is
 // [Hs[l[q]]; Hs[r[q]]], else row q of Dz.
 template <int DT, bool GATHER>
-__global__ void k_transpose(VecArgs v, Engine e, uint32_t n_q, int n_cols, void* out_) {
+__global__ void __launch_bounds__(256) k_transpose(VecArgs v, Engine e, uint32_t n_q, int n_cols, void* out_) {
   typedef typename TypeOf<DT>::type T;
+  constexpr int CH = El<T>::CH;          // elements per 16-byte chunk
+  constexpr int TQ = 64, TC = 64;        // tile: 64 tags x 64 columns
+  constexpr int CPR = TC / CH;           // chunks per tile row
   T* out = reinterpret_cast<T*>(out_);
-  __shared__ T tile[32][33];
-  const uint32_t q0 = blockIdx.x * 32;
-  const int c0 = blockIdx.y * 32;
-  for (int r = threadIdx.y; r < 32; r += blockDim.y) {
+  __shared__ T tile[TQ][TC + 2];
+  const uint32_t q0 = blockIdx.x * TQ;
+  const int c0 = blockIdx.y * TC;
+  // in: 16 bytes per thread along the columns (rows of 128 B / 256 B, coalesced)
+  for (int id = threadIdx.x; id < TQ * CPR; id += blockDim.x) {
+    const int r = id / CPR, cc = (id % CPR) * CH;
     const uint32_t q = q0 + r;
-    const int c = c0 + threadIdx.x;
-    T x = from_f<T>(0.f);
+    const int c = c0 + cc;
+    u32x4 raw = {0u, 0u, 0u, 0u};
     if (q < n_q && c < n_cols) {
       if (GATHER) {
         const uint32_t row = c < v.Hp ? e.q_l[q] : e.q_r[q];
-        x = reinterpret_cast<const T*>(v.Hs)[(size_t)row * v.Hp + (c < v.Hp ? c : c - v.Hp)];
+        raw = *reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(v.Hs) + (size_t)row * v.Hp + (c < v.Hp ? c : c - v.Hp));
       } else {
-        x = reinterpret_cast<const T*>(v.Dz)[(size_t)q * v.Np + c];
+        raw = *reinterpret_cast<const u32x4*>(reinterpret_cast<const T*>(v.Dz) + (size_t)q * v.Np + c);
       }
     }
-    tile[r][threadIdx.x] = x;
+    const T* x = reinterpret_cast<const T*>(&raw);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) tile[r][cc + i] = x[i];
   }
   __syncthreads();
-  for (int r = threadIdx.y; r < 32; r += blockDim.y) {
-    const int c = c0 + r;
-    const uint32_t q = q0 + threadIdx.x;
-    if (c < n_cols && q < v.q_stride) out[(size_t)c * v.q_stride + q] = tile[threadIdx.x][r];
+  // out: 16 bytes per thread along the tags
+  constexpr int QPR = TQ / CH;           // chunks per output row
+  for (int id = threadIdx.x; id < TC * QPR; id += blockDim.x) {
+    const int c = id / QPR, qq = (id % QPR) * CH;
+    if (c0 + c >= n_cols || q0 + qq >= v.q_stride) continue;
+    u32x4 raw;
+    T* x = reinterpret_cast<T*>(&raw);
+#pragma unroll
+    for (int i = 0; i < CH; ++i) x[i] = tile[qq + i][c];
+    *reinterpret_cast<u32x4*>(out + (size_t)(c0 + c) * v.q_stride + q0 + qq) = raw;
   }
 }
 
@@ -1031,10 +1044,10 @@ int vec_dw_splits(uint32_t q_stride) {
 template <typename T> static void weight_grads_t(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db,
                                                  float* db_part, hipStream_t s) {
   // transposed copies so that the reduction over tags is k-contiguous for both operands
-  dim3 tb(32, 8);
-  hipLaunchKernelGGL((k_transpose<DtOf<T>::value, false>), dim3(v.q_stride / 32, v.Np / 32), tb, 0, s, v, e, n_q, v.Np,
+  dim3 tb(256);
+  hipLaunchKernelGGL((k_transpose<DtOf<T>::value, false>), dim3(v.q_stride / 64, v.Np / 64), tb, 0, s, v, e, n_q, v.Np,
                      v.DzT);
-  hipLaunchKernelGGL((k_transpose<DtOf<T>::value, true>), dim3(v.q_stride / 32, v.Kp / 32), tb, 0, s, v, e, n_q, v.Kp,
+  hipLaunchKernelGGL((k_transpose<DtOf<T>::value, true>), dim3(v.q_stride / 64, v.Kp / 64), tb, 0, s, v, e, n_q, v.Kp,
                      v.XT);
   const int splits = vec_dw_splits(v.q_stride);
   int kps = (int)((v.q_stride / 64 + splits - 1) / splits) * 64;
