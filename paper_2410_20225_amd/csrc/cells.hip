@@ -368,24 +368,30 @@ template <> struct Chunk<float> {
 };
 
 // One tile: rows 32 rt .. 32 rt + 31 of the level, hidden units (output columns) 32 ct .. 32 ct + 31.
-// Called by all 256 threads of a workgroup; `part` is its LDS scratch [wave][G][16][64].
-template <int DT, int MODE>
+// Called by all NW * 64 threads of a workgroup (NW = 4 or 8 waves split the reduction); `part` is
+// its LDS scratch [wave][G][16][64].
+template <int DT, int MODE, int NW>
 __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int ct, float* part) {
   typedef typename TypeOf<DT>::type T;
   typedef Chunk<T> C;
   constexpr int G = MODE == LSTM_FWD ? 5 : 1;      // 32-wide column blocks per tile
   constexpr int BATCH = 8;                          // chunk steps in flight
   constexpr int EPC = 16 / (int)sizeof(T);         // elements per chunk
+  constexpr int RPW = 16 / NW;                     // accumulator registers (rows of a lane) a wave finishes
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m0 = rt * 32;
   const int mA = min(m0 + (lane & 31), g.M - 1);   // operand row of this lane
-  const int kw = g.K / 4;                          // reduction range of this wave: [wave * kw, +kw)
+  const int kw = g.K / NW;                         // reduction range of this wave: [wave * kw, +kw)
 
-  // rows this lane finishes: r = 4 * wave + rr  ->  row = 8 * wave + (lane / 32) * 4 + rr
-  uint32_t o_out[4], o_l[4], o_r[4];
+  // rows this lane finishes: accumulator register r = RPW * wave + rr holds row (r / 4) * 8 + (lane / 32) * 4 + r % 4
+  auto row_of = [&](int rr) {
+    const int r = RPW * wave + rr;
+    return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+  };
+  uint32_t o_out[RPW], o_l[RPW], o_r[RPW];
 #pragma unroll
-  for (int rr = 0; rr < 4; ++rr) {
-    const int m = min(m0 + 8 * wave + (lane >> 5) * 4 + rr, g.M - 1);
+  for (int rr = 0; rr < RPW; ++rr) {
+    const int m = min(m0 + row_of(rr), g.M - 1);
     if (MODE != DX_BWD) o_out[rr] = g.out[m];
     if (MODE != RNN_FWD) { o_l[rr] = g.l[m]; o_r[rr] = g.r[m]; }
   }
@@ -394,8 +400,8 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
   if (MODE == DX_BWD) {
     Ap = reinterpret_cast<const T*>(g.A) + (size_t)mA * g.lda + wave * kw;
   } else {
-    const uint32_t child = wave < 2 ? g.l[mA] : g.r[mA];   // waves 0,1: left half of [h_l; h_r]
-    Ap = reinterpret_cast<const T*>(g.Hs) + (size_t)child * g.Hp + (wave & 1) * kw;
+    const uint32_t child = wave < NW / 2 ? g.l[mA] : g.r[mA];   // first half of the waves: h_l of [h_l; h_r]
+    Ap = reinterpret_cast<const T*>(g.Hs) + (size_t)child * g.Hp + (wave % (NW / 2)) * kw;
   }
   Ap += (lane >> 5) * EPC;
   const T* Bp[G];   // operand order: chunk step st of this wave is 64 * EPC elements further on
@@ -405,11 +411,11 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
     Bp[j] = reinterpret_cast<const T*>(g.Bf) + (((size_t)brt * (g.K / C::KC) + wave * (kw / C::KC)) * 64 + lane) * EPC;
   }
   // children's cell states for the epilogue, requested before the products start
-  float cl[4], cr[4];
+  float cl[RPW], cr[RPW];
   const int unit = ct * 32 + (lane & 31);
   if (MODE == LSTM_FWD) {
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
+    for (int rr = 0; rr < RPW; ++rr) {
       cl[rr] = g.Cs[(size_t)o_l[rr] * g.Hp + unit];
       cr[rr] = g.Cs[(size_t)o_r[rr] * g.Hp + unit];
     }
@@ -445,14 +451,14 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
 #pragma unroll
     for (int r = 0; r < 16; ++r) part[((wave * G + j) * 16 + r) * 64 + lane] = acc[j][r];
   __syncthreads();
-  float z[G][4];
+  float z[G][RPW];
 #pragma unroll
   for (int j = 0; j < G; ++j)
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
+    for (int rr = 0; rr < RPW; ++rr) {
       float t = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) t += part[((w * G + j) * 16 + 4 * wave + rr) * 64 + lane];
+      for (int w = 0; w < NW; ++w) t += part[((w * G + j) * 16 + RPW * wave + rr) * 64 + lane];
       z[j][rr] = t;
     }
 
@@ -460,8 +466,8 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
     const float bi = g.bias[unit], bfl = g.bias[g.Hp + unit], bfr = g.bias[2 * g.Hp + unit];
     const float bo = g.bias[3 * g.Hp + unit], bu = g.bias[4 * g.Hp + unit];
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int m = m0 + 8 * wave + (lane >> 5) * 4 + rr;
+    for (int rr = 0; rr < RPW; ++rr) {
+      const int m = m0 + row_of(rr);
       if (m >= g.M) continue;
       const float gi = Act<T>::sigmoid(z[0][rr] + bi);
       const float gfl = Act<T>::sigmoid(z[1][rr] + bfl);
@@ -484,15 +490,15 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
   } else if constexpr (MODE == RNN_FWD) {
     const float bias = g.bias[unit];
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int m = m0 + 8 * wave + (lane >> 5) * 4 + rr;
+    for (int rr = 0; rr < RPW; ++rr) {
+      const int m = m0 + row_of(rr);
       if (m >= g.M) continue;
       reinterpret_cast<T*>(g.Hs_out)[(size_t)o_out[rr] * g.Hp + unit] = from_f<T>(Act<T>::tanh(z[0][rr] + bias));
     }
   } else {   // DX_BWD: column `unit` of [dh_l; dh_r]; each child row has exactly one consumer
 #pragma unroll
-    for (int rr = 0; rr < 4; ++rr) {
-      const int m = m0 + 8 * wave + (lane >> 5) * 4 + rr;
+    for (int rr = 0; rr < RPW; ++rr) {
+      const int m = m0 + row_of(rr);
       if (m >= g.M) continue;
       if (unit < g.Hp) g.C[(size_t)o_l[rr] * g.Hp + unit] = z[0][rr];
       else g.C[(size_t)o_r[rr] * g.Hp + (unit - g.Hp)] = z[0][rr];
@@ -501,11 +507,11 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
   __syncthreads();   // `part` is free for the workgroup's next tile
 }
 
-template <int DT, int MODE>
-__global__ void __launch_bounds__(256) k_cell_small(GemmArgs g) {
+template <int DT, int MODE, int NW>
+__global__ void __launch_bounds__(NW * 64) k_cell_small(GemmArgs g) {
   extern __shared__ __attribute__((aligned(16))) char smem[];
   const int n_ct = g.n_tiles_n;                    // column tiles of 32
-  cell_small_tile<DT, MODE>(g, blockIdx.x / n_ct, blockIdx.x % n_ct, reinterpret_cast<float*>(smem));
+  cell_small_tile<DT, MODE, NW>(g, blockIdx.x / n_ct, blockIdx.x % n_ct, reinterpret_cast<float*>(smem));
 }
 
 // Levels of at most this many cells take the small-level kernel (TDF_SMALL_LEVEL overrides).
@@ -514,19 +520,31 @@ static uint32_t small_level() {
   return e ? (uint32_t)atoll(e) : 1024u;
 }
 
-template <typename T, int MODE> void launch_cell_small(GemmArgs g, int n_col_tiles, hipStream_t s) {
-  if (g.M <= 0) return;
+// Waves that split the reduction of a small-level tile: eight where the tile has one column
+// block (RNN forward, input gradient) and the reduction divides evenly, else four.
+template <typename T, int MODE> int small_tile_waves(int K) {
+  return MODE != LSTM_FWD && (K / 8) % Chunk<T>::KC == 0 && K / 8 >= Chunk<T>::KC ? 8 : 4;
+}
+
+template <typename T, int MODE, int NW> void launch_cell_small_nw(GemmArgs g, int n_col_tiles, hipStream_t s) {
   constexpr int G = MODE == LSTM_FWD ? 5 : 1;
-  const size_t lds = (size_t)4 * G * 16 * 64 * sizeof(float);
+  const size_t lds = (size_t)NW * G * 16 * 64 * sizeof(float);
   static bool lds_opt_in = false;
   if (!lds_opt_in && lds > 48 * 1024) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cell_small<DtOf<T>::value, MODE>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_cell_small<DtOf<T>::value, MODE, NW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     lds_opt_in = true;
   }
   g.n_tiles_n = n_col_tiles;
   const int n_rt = (g.M + 31) / 32;
-  hipLaunchKernelGGL((k_cell_small<DtOf<T>::value, MODE>), dim3(n_rt * n_col_tiles), dim3(256), lds, s, g);
+  hipLaunchKernelGGL((k_cell_small<DtOf<T>::value, MODE, NW>), dim3(n_rt * n_col_tiles), dim3(NW * 64), lds, s, g);
+}
+template <typename T, int MODE> void launch_cell_small(GemmArgs g, int n_col_tiles, hipStream_t s) {
+  if (g.M <= 0) return;
+  if constexpr (MODE != LSTM_FWD) {
+    if (small_tile_waves<T, MODE>(g.K) == 8) return launch_cell_small_nw<T, MODE, 8>(g, n_col_tiles, s);
+  }
+  launch_cell_small_nw<T, MODE, 4>(g, n_col_tiles, s);
 }
 
 // ---- packing of W: padded, k-contiguous [Np x Kp], and its transpose [Kp x Np] ---------------
@@ -675,8 +693,8 @@ struct TailArgs {
   long long spin_ticks;
 };
 
-template <int DT, int MODE>
-__global__ void __launch_bounds__(256) k_tail_fwd(GemmArgs g, TailArgs t) {
+template <int DT, int MODE, int NW>
+__global__ void __launch_bounds__(NW * 64) k_tail_fwd(GemmArgs g, TailArgs t) {
   typedef typename TypeOf<DT>::type T;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ uint32_t sh_ok;
@@ -696,15 +714,15 @@ __global__ void __launch_bounds__(256) k_tail_fwd(GemmArgs g, TailArgs t) {
     gl.gates = g.gates ? reinterpret_cast<T*>(g.gates) + (size_t)q0 * g.ldg : nullptr;
     const uint32_t tiles = (cnt + 31) / 32 * (uint32_t)n_ct;
     for (uint32_t tile = rank; tile < tiles; tile += G)
-      cell_small_tile<DT, MODE>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+      cell_small_tile<DT, MODE, NW>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
     if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
   }
 }
 
 // Gradient pass over the same levels, deepest first: dz of the die's cells of a level, barrier,
 // their input gradients, barrier.
-template <int DT>
-__global__ void __launch_bounds__(256) k_tail_bwd(GemmArgs g, VecArgs v, Engine e, TailArgs t) {
+template <int DT, int NW>
+__global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Engine e, TailArgs t) {
   typedef typename TypeOf<DT>::type T;
   extern __shared__ __attribute__((aligned(16))) char smem[];
   __shared__ uint32_t sh_ok;
@@ -726,7 +744,7 @@ __global__ void __launch_bounds__(256) k_tail_bwd(GemmArgs g, VecArgs v, Engine 
     gl.l = g.l + q0; gl.r = g.r + q0;
     const uint32_t tiles = (cnt + 31) / 32 * (uint32_t)n_ct;
     for (uint32_t tile = rank; tile < tiles; tile += G)
-      cell_small_tile<DT, DX_BWD>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+      cell_small_tile<DT, DX_BWD, NW>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
     if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
   }
 }
@@ -991,12 +1009,15 @@ template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, 
   const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
   if (v.cell_kind == 2) {
     const size_t lds = (size_t)4 * 5 * 16 * 64 * sizeof(float);
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_fwd<DtOf<T>::value, LSTM_FWD>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_fwd<DtOf<T>::value, LSTM_FWD, 4>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, LSTM_FWD>), dim3(grid), dim3(256), lds, s, g, t);
+    hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, LSTM_FWD, 4>), dim3(grid), dim3(256), lds, s, g, t);
+  } else if (small_tile_waves<T, RNN_FWD>(g.K) == 8) {
+    const size_t lds = (size_t)8 * 16 * 64 * sizeof(float);
+    hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, RNN_FWD, 8>), dim3(grid), dim3(512), lds, s, g, t);
   } else {
     const size_t lds = (size_t)4 * 16 * 64 * sizeof(float);
-    hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, RNN_FWD>), dim3(grid), dim3(256), lds, s, g, t);
+    hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, RNN_FWD, 4>), dim3(grid), dim3(256), lds, s, g, t);
   }
 }
 void vec_tail_fwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
@@ -1014,8 +1035,13 @@ template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, 
   g.C = v.dH;
   g.n_tiles_n = v.Kp / 32;
   const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
-  const size_t lds = (size_t)4 * 16 * 64 * sizeof(float);
-  hipLaunchKernelGGL((k_tail_bwd<DtOf<T>::value>), dim3(grid), dim3(256), lds, s, g, v, e, t);
+  if (small_tile_waves<T, DX_BWD>(g.K) == 8) {
+    const size_t lds = (size_t)8 * 16 * 64 * sizeof(float);
+    hipLaunchKernelGGL((k_tail_bwd<DtOf<T>::value, 8>), dim3(grid), dim3(512), lds, s, g, v, e, t);
+  } else {
+    const size_t lds = (size_t)4 * 16 * 64 * sizeof(float);
+    hipLaunchKernelGGL((k_tail_bwd<DtOf<T>::value, 4>), dim3(grid), dim3(256), lds, s, g, v, e, t);
+  }
 }
 void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
                   uint32_t n_dies, void* sync, long long spin_ticks, int cus, hipStream_t s) {

@@ -18,7 +18,7 @@ constexpr uint32_t XCDS = 8;
 
 struct alignas(128) DieSync {
   uint32_t count;      // arrivals (monotone: G per barrier)
-  uint32_t gen;        // completed barriers
+  uint32_t pad;
   uint32_t xcc_mask;   // dies the workgroups of this group actually ran on
   uint32_t abort;      // a workgroup gave up waiting
 };
@@ -38,19 +38,16 @@ __device__ inline bool die_barrier(DieSync* sy, uint32_t G, uint32_t gen, long l
   __syncthreads();   // every wave's stores have reached the shared L2 (the barrier waits for them)
   if (threadIdx.x == 0) {
     bool ok = true;
-    const uint32_t arrived = atomicAdd(&sy->count, 1u);
-    if (arrived == (gen + 1u) * G - 1u) {
-      __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "workgroup");
-      __atomic_store_n(&sy->gen, gen + 1u, __ATOMIC_RELAXED);
-    } else {
-      const long long t0 = wall_clock64();
-      while (__atomic_load_n(&sy->gen, __ATOMIC_RELAXED) == gen) {
-        __builtin_amdgcn_s_sleep(1);
-        if (wall_clock64() - t0 > spin_ticks) {
-          __atomic_store_n(&sy->abort, 1u, __ATOMIC_RELAXED);
-          ok = false;
-          break;
-        }
+    // arrive without waiting for the old value; the count itself says when all G have arrived
+    __hip_atomic_fetch_add(&sy->count, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t full = (gen + 1u) * G;
+    const long long t0 = wall_clock64();
+    while (__atomic_load_n(&sy->count, __ATOMIC_RELAXED) < full) {
+      __builtin_amdgcn_s_sleep(1);
+      if (wall_clock64() - t0 > spin_ticks) {
+        __atomic_store_n(&sy->abort, 1u, __ATOMIC_RELAXED);
+        ok = false;
+        break;
       }
     }
     if (__atomic_load_n(&sy->abort, __ATOMIC_RELAXED)) ok = false;
