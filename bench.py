@@ -21,6 +21,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 PEAK_BF16 = 2.5e15      # dense bf16 MFMA, FLOP/s
 PEAK_F32 = 157.3e12     # fp32 MFMA / vector
 PEAK_HBM = 8.0e12       # B/s
+COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 
 
 def cpu_baseline(cfg, budget_trees):
@@ -108,11 +109,26 @@ def main():
         n_cell = int(c["forest"].n_leaves.sum()) - B
         flops_fwd = 2.0 * n_cell * rows * 2 * c["H"]
 
+    # a plain device copy of known size, outside the timed region: what this machine's HBM delivers to a
+    # simple kernel, and the reference that the FETCH_SIZE / WRITE_SIZE counter passes are scaled by
+    copy_src = torch.empty(COPY_BYTES, dtype=torch.uint8, device=dev)
+    copy_dst = torch.empty_like(copy_src)
+    copy_dst.copy_(copy_src)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        copy_dst.copy_(copy_src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2.0 * COPY_BYTES / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del copy_src, copy_dst
+
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
-    phase = np.zeros(8)
-    launches = np.zeros(8)
+    phase = np.zeros(len(tdf.PHASES))
+    launches = np.zeros(len(tdf.PHASES))
     t0 = time.perf_counter()
     for _ in range(a.steps):
         st = step()
@@ -125,24 +141,35 @@ def main():
     value = firings * a.steps / dt
     phase_ms = {n: round(float(p) / a.steps, 4) for n, p in zip(tdf.PHASES, phase)}
 
-    # tag machine: bytes the method itself moves per tag (key and probe window, frame record written
-    # once and read by each sweep, delivered values and arrival words, touched-list entries, forest
-    # entries, schedule-log entry): 280 B for fib's 64-byte frames, 600 B for the tree programs
-    tag_bytes = (280.0 if cfg == 1 else 600.0) * n_tags
+    # tag machine: algorithmic bytes per tag of matching + compaction (table entry and frame record
+    # written, frame read on return, operand slot, arrival word, ready id, schedule-log entry): 72 B
+    tag_bytes = 72.0 * n_tags
     tag_ms = phase[0] / a.steps
     roof_tags = {"bound": "hbm", "kernel": "tag machine step kernels (all steps)",
                  "achieved": tag_bytes / (tag_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
                  "launches_per_step": launches[0] / a.steps, "traffic": None}
     roof_tags["frac"] = roof_tags["achieved"] / roof_tags["peak"]
+    roof_tags["copy_kernel_GBps"] = copy_gbps   # measured read + write rate of a plain 1 GiB device copy
     if cfg == 1:
         roof = roof_tags
     else:
-        ms = phase[3] / a.steps
-        n_launch = launches[3] / a.steps
+        i_fwd, i_tail = tdf.PHASES.index("cells_fwd"), tdf.PHASES.index("tail_fwd")
+        ms = (phase[i_fwd] + phase[i_tail]) / a.steps
+        n_launch = (launches[i_fwd] + launches[i_tail]) / a.steps
         peak = PEAK_BF16 if dtype == "bf16" else PEAK_F32
+        per_cell = 2.0 * rows * 2 * c["H"]
         roof = {"bound": "mfma", "kernel": "k_gemm + k_tail_fwd <%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
                 "achieved": flops_fwd / (ms * 1e-3) / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
                 "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1), "traffic": None}
+        # the same, split by level width: one launch per wide level, one launch for the whole narrow tail
+        wide_ms, tail_ms = phase[i_fwd] / a.steps, phase[i_tail] / a.steps
+        wide_cells = int(st.n_wide_cells)
+        roof["wide_levels"] = {"levels": int(st.n_wide_waves), "cells": wide_cells, "ms": wide_ms,
+                               "achieved": per_cell * wide_cells / max(wide_ms, 1e-9) / 1e9,
+                               "frac": per_cell * wide_cells / max(wide_ms, 1e-9) / 1e9 / (peak / 1e12)}
+        roof["narrow_tail"] = {"levels": int(st.n_waves) - int(st.n_wide_waves), "cells": n_cell - wide_cells, "ms": tail_ms,
+                               "achieved": per_cell * (n_cell - wide_cells) / max(tail_ms, 1e-9) / 1e9,
+                               "frac": per_cell * (n_cell - wide_cells) / max(tail_ms, 1e-9) / 1e9 / (peak / 1e12)}
     roof["frac"] = roof["achieved"] / roof["peak"]
 
     rec = {"metric": "tagged node firings/sec at 1 GPU", "value": value, "unit": "firings/s", "n_gpus": 1,

@@ -196,11 +196,13 @@ enum {
   TDF_PHASE_TAGS = 0,    /* tag machine: clear, seed, all match/fire steps                 */
   TDF_PHASE_LEAVES,      /* weight packing and EMBED rows                                  */
   TDF_PHASE_LEVELS,      /* bucketing of the cell firings by dependency level              */
-  TDF_PHASE_CELLS_FWD,   /* cell GEMMs, one launch per level                               */
+  TDF_PHASE_CELLS_FWD,   /* cell GEMMs of the wide levels, one launch per level            */
   TDF_PHASE_HEAD,        /* head / result rows / gradient seeds                            */
-  TDF_PHASE_CELLS_BWD,   /* gradient bodies of the cells, levels in reverse                */
+  TDF_PHASE_CELLS_BWD,   /* gradient bodies of the cells of the wide levels, in reverse    */
   TDF_PHASE_WEIGHT_GRAD, /* dW, db                                                         */
-  TDF_PHASE_EMBED_GRAD,  /* dE                                                             */
+  TDF_PHASE_EMBED_GRAD,  /* dE (runs beside the weight gradients)                          */
+  TDF_PHASE_TAIL_FWD,    /* cells of the deep, narrow levels: one launch for all of them   */
+  TDF_PHASE_TAIL_BWD,    /* ... and their gradient bodies                                  */
   TDF_PHASE_COUNT
 };
 
@@ -211,6 +213,8 @@ typedef struct {
   int64_t n_leaf_rows;    /* EMBED firings                                              */
   int64_t n_cell_rows;    /* RNN_CELL / LSTM_CELL firings                               */
   int64_t n_waves;        /* dependency levels of the cell firings                      */
+  int64_t n_wide_waves;   /* ... of which the first this many ran one launch per level  */
+  int64_t n_wide_cells;   /* cell firings in those levels                               */
   int64_t n_grad_firings; /* gradient-body firings (one per tag) in tdf_eval_grad       */
   int64_t max_tag_depth;  /* longest list of call labels                                */
   int64_t table_capacity; /* slots of the tag-hash table                                */

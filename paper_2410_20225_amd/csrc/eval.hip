@@ -420,10 +420,13 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       begin(TDF_PHASE_CELLS_FWD);
       for (uint32_t lvl = 1; lvl < tail_first; ++lvl)
         vec_cell_fwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), with_grad, s);
-      if (use_tail)
+      end(TDF_PHASE_CELLS_FWD, tail_first - 1);
+      if (use_tail) {
+        begin(TDF_PHASE_TAIL_FWD);
         vec_tail_fwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync, spin_ticks, cus,
                      with_grad, s);
-      end(TDF_PHASE_CELLS_FWD, tail_first - 1 + (use_tail ? 1 : 0));
+        end(TDF_PHASE_TAIL_FWD, 1);
+      }
     }
     begin(TDF_PHASE_HEAD);
     if (G.has_head) {
@@ -436,13 +439,16 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     end(TDF_PHASE_HEAD, 2);
     if (with_grad) {
       // ---- gradient pass: the level schedule walked backwards -----------------------------
-      begin(TDF_PHASE_CELLS_BWD);
-      if (use_tail && hc.n_cell)
+      if (use_tail && hc.n_cell) {
+        begin(TDF_PHASE_TAIL_BWD);
         vec_tail_bwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync + 8 * sizeof(DieSync),
                      spin_ticks, cus, s);
+        end(TDF_PHASE_TAIL_BWD, 1);
+      }
+      begin(TDF_PHASE_CELLS_BWD);
       for (uint32_t lvl = tail_first - 1; lvl >= 1 && hc.n_cell; --lvl)
         vec_cell_bwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), s);
-      end(TDF_PHASE_CELLS_BWD, 2ll * (tail_first - 1) + (use_tail ? 1 : 0));
+      end(TDF_PHASE_CELLS_BWD, 2ll * (tail_first - 1));
       // The embedding gradient and the weight gradients depend on the gradient pass only, not on
       // each other: the former runs on a second stream beside the latter.
       if (!gr->side_stream) {
@@ -502,6 +508,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->n_leaf_rows = hc.n_leaf;
     stats->n_cell_rows = hc.n_cell;
     stats->n_waves = hc.max_level;
+    stats->n_wide_waves = hc.n_cell && tail_first ? tail_first - 1 : 0;
+    stats->n_wide_cells = hc.n_cell && tail_first ? lvl_begin(tail_first) : 0;
     stats->n_grad_firings = with_grad && dev == TDF_OK ? (int64_t)hc.n_leaf + hc.n_cell : 0;
     stats->max_tag_depth = hc.max_depth;
     stats->table_capacity = e.cap;

@@ -26,7 +26,7 @@ F32, BF16 = 0, 1
 SNODE_MERGE_ENTRY, SNODE_CALL, SNODE_RETURN = 100, 101, 102
 MAX_INPUTS = 4
 STATS_MAX_COUNTS = 256
-PHASES = ("tags", "leaves", "levels", "cells_fwd", "head", "cells_bwd", "weight_grad", "embed_grad")
+PHASES = ("tags", "leaves", "levels", "cells_fwd", "head", "cells_bwd", "weight_grad", "embed_grad", "tail_fwd", "tail_bwd")
 
 
 class Ref(C.Structure):
@@ -85,8 +85,9 @@ class Grads(C.Structure):
 class Stats(C.Structure):
     _fields_ = [("n_tags", C.c_int64), ("n_steps", C.c_int64), ("n_tokens", C.c_int64),
                 ("n_leaf_rows", C.c_int64), ("n_cell_rows", C.c_int64), ("n_waves", C.c_int64),
+                ("n_wide_waves", C.c_int64), ("n_wide_cells", C.c_int64),
                 ("n_grad_firings", C.c_int64), ("max_tag_depth", C.c_int64), ("table_capacity", C.c_int64),
-                ("max_probe", C.c_int64), ("phase_ms", C.c_double * 8), ("phase_launches", C.c_int64 * 8),
+                ("max_probe", C.c_int64), ("phase_ms", C.c_double * len(PHASES)), ("phase_launches", C.c_int64 * len(PHASES)),
                 ("device_status", C.c_int32), ("n_counts", C.c_int32),
                 ("fire_count", C.c_int64 * STATS_MAX_COUNTS)]
 
