@@ -99,7 +99,8 @@ struct GemmArgs {
   size_t ldg;
   float* C;                  // fp32 output (DX_BWD: dH; DW_SPLIT: partial tiles)
   size_t ldc;
-  int k_per_split;           // DW_SPLIT: k range of one blockIdx.z
+  int k_per_split;           // DW_SPLIT: k range of one split
+  int n_splits;
   int n_tiles_n;             // column tiles of the launch
   int save_gates;
 };
@@ -129,15 +130,27 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
   // (workgroups are dealt round-robin to the 8 XCDs), so the gathered rows are shared in its L2
   const int n_mt = (g.M + BM - 1) / BM;
   const int xcd = blockIdx.x & 7, u = blockIdx.x >> 3;
-  const int nt = u % g.n_tiles_n, mt = (u / g.n_tiles_n) * 8 + xcd;
-  if (mt >= n_mt) return;
+  int nt, mt, split = 0;
+  if (MODE == DW_SPLIT) {
+    // all tiles of one split of the reduction run on one XCD, side by side: they walk the same
+    // slices of both operands in step, so each slice comes from HBM once
+    const int tiles = n_mt * g.n_tiles_n;
+    split = (u / tiles) * 8 + xcd;
+    if (split >= g.n_splits) return;
+    mt = (u % tiles) / g.n_tiles_n;
+    nt = (u % tiles) % g.n_tiles_n;
+  } else {
+    nt = u % g.n_tiles_n;
+    mt = (u / g.n_tiles_n) * 8 + xcd;
+    if (mt >= n_mt) return;
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
   const int m0 = mt * BM;
   int k_begin = 0, k_end = g.K;
   if (MODE == DW_SPLIT) {
-    k_begin = blockIdx.z * g.k_per_split;
+    k_begin = split * g.k_per_split;
     k_end = min(g.K, k_begin + g.k_per_split);
   }
 
@@ -300,7 +313,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
             if (n < g.Hp) g.C[(size_t)sL[row] * g.Hp + n] = acc[i][j][r];
             else g.C[(size_t)sR[row] * g.Hp + (n - g.Hp)] = acc[i][j][r];
           } else {
-            g.C[(size_t)blockIdx.z * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
+            g.C[(size_t)split * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
           }
         }
       }
@@ -317,7 +330,8 @@ template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int 
   if (g.M <= 0) return;
   g.n_tiles_n = n_tiles_n;
   const int n_mt = (g.M + BM - 1) / BM;
-  dim3 grid((n_mt + 7) / 8 * 8 * n_tiles_n, 1, splits);
+  g.n_splits = splits;
+  dim3 grid(MODE == DW_SPLIT ? 8 * n_mt * n_tiles_n * ((splits + 7) / 8) : (n_mt + 7) / 8 * 8 * n_tiles_n);
   static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
   if (!lds_opt_in) {
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE>),
