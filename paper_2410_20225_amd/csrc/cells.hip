@@ -767,7 +767,7 @@ __global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Eng
 // out[c][q] = in_row(q)[c] for q < n_q, 0 for n_q <= q < q_stride.  GATHER: in_row(q) is
 // [Hs[l[q]]; Hs[r[q]]], else row q of Dz.
 template <int DT, bool GATHER>
-__global__ void __launch_bounds__(256) k_transpose(VecArgs v, Engine e, uint32_t n_q, int n_cols, void* out_) {
+__global__ void __launch_bounds__(256) k_transpose(VecArgs v, Engine e, uint32_t n_q, int n_cols, void* out_, float* col_sums) {
   typedef typename TypeOf<DT>::type T;
   constexpr int CH = El<T>::CH;          // elements per 16-byte chunk
   constexpr int TQ = 64, TC = 64;        // tile: 64 tags x 64 columns
@@ -795,6 +795,12 @@ __global__ void __launch_bounds__(256) k_transpose(VecArgs v, Engine e, uint32_t
     for (int i = 0; i < CH; ++i) tile[r][cc + i] = x[i];
   }
   __syncthreads();
+  // column sums of the tile (db = sum over tags of Dz: one partial per 64 tags, summed in tag order)
+  if (!GATHER && col_sums && threadIdx.x < TC && c0 + (int)threadIdx.x < n_cols) {
+    float sum = 0.f;
+    for (int r = 0; r < TQ; ++r) sum += to_f(tile[r][threadIdx.x]);
+    col_sums[(size_t)blockIdx.x * v.Np + c0 + threadIdx.x] = sum;
+  }
   // out: 16 bytes per thread along the tags
   constexpr int QPR = TQ / CH;           // chunks per output row
   for (int id = threadIdx.x; id < TC * QPR; id += blockDim.x) {
@@ -820,27 +826,7 @@ __global__ void k_reduce_dw(VecArgs v, float* dW, int splits) {
   }
 }
 
-// db[n] = sum_q Dz[q][n]: fixed chunks of DB_TAGS tags, partial sums combined in a fixed order
-constexpr uint32_t DB_TAGS = 256;
-template <int DT>
-__global__ void k_db_partial(VecArgs v, uint32_t n_q, float* part) {
-  typedef typename TypeOf<DT>::type T;
-  constexpr int CH = El<T>::CH;
-  const uint32_t q_lo = blockIdx.x * DB_TAGS, q_hi = min(n_q, q_lo + DB_TAGS);
-  for (int n = threadIdx.x * CH; n < v.Np; n += blockDim.x * CH) {
-    float s[CH];
-#pragma unroll
-    for (int i = 0; i < CH; ++i) s[i] = 0.f;
-    for (uint32_t q = q_lo; q < q_hi; ++q) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(reinterpret_cast<const T*>(v.Dz) + (size_t)q * v.Np + n);
-      const T* x = reinterpret_cast<const T*>(&raw);
-#pragma unroll
-      for (int i = 0; i < CH; ++i) s[i] += to_f(x[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < CH; ++i) part[(size_t)blockIdx.x * v.Np + n + i] = s[i];
-  }
-}
+// db[n] = sum_q Dz[q][n]: partial sums over 64 tags each come from the transpose of Dz
 // 16 columns per block; 16 groups of partials, each summed in chunk order, meet in LDS
 __global__ void k_db_final(VecArgs v, const float* part, int n_parts, float* db) {
   __shared__ float red[16][17];
@@ -1086,9 +1072,9 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   // transposed copies so that the reduction over tags is k-contiguous for both operands
   dim3 tb(256);
   hipLaunchKernelGGL((k_transpose<DtOf<T>::value, false>), dim3(v.q_stride / 64, v.Np / 64), tb, 0, s, v, e, n_q, v.Np,
-                     v.DzT);
+                     v.DzT, db_part);
   hipLaunchKernelGGL((k_transpose<DtOf<T>::value, true>), dim3(v.q_stride / 64, v.Kp / 64), tb, 0, s, v, e, n_q, v.Kp,
-                     v.XT);
+                     v.XT, (float*)nullptr);
   const int splits = vec_dw_splits(v.q_stride);
   int kps = (int)((v.q_stride / 64 + splits - 1) / splits) * 64;
   GemmArgs g{};
@@ -1099,8 +1085,7 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   g.k_per_split = kps;
   launch_gemm<T, DW_SPLIT>(g, (v.Kp + 127) / 128, splits, s);
   hipLaunchKernelGGL(k_reduce_dw, dim3(512), dim3(256), 0, s, v, dW, splits);
-  const int parts = (int)((n_q + DB_TAGS - 1) / DB_TAGS);
-  hipLaunchKernelGGL(k_db_partial<DtOf<T>::value>, dim3(parts), dim3(256), 0, s, v, n_q, db_part);
+  const int parts = (int)(v.q_stride / 64);   // written by the transpose of Dz above
   hipLaunchKernelGGL(k_db_final, dim3((v.Np + 15) / 16), dim3(256), 0, s, v, db_part, parts, db);
 }
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {
