@@ -2,9 +2,10 @@
 // MI355X hands the workgroups of a launch to its eight dies in turn, so workgroups i, i + 8,
 // i + 16, ... share a die and its L2.  Work that is private to a die (the instances dealt to
 // one tag machine, and the cells of those instances) can therefore run as a persistent loop
-// with this barrier between dependent phases: stores reach the shared L2 before the arrival,
-// and the per-CU L1 is invalidated after the release; no L2 write-back or invalidation and no
-// kernel boundary is needed.  The barrier words themselves are accessed at device scope, so the
+// with this barrier between dependent phases: stores reach the shared L2 before the arrival, so
+// no L2 write-back or invalidation and no kernel boundary is needed.  The per-CU L1 is NOT
+// invalidated: what crosses the barrier must be data the consumer's CU cannot hold an older copy
+// of (rows written once per launch and read only afterwards), or be read past the L1.  The barrier words themselves are accessed at device scope, so the
 // barrier completes wherever the workgroups run; every wait is bounded.
 #pragma once
 #ifndef __HIPCC_RTC__
@@ -22,11 +23,6 @@ struct alignas(128) DieSync {
   uint32_t xcc_mask;   // dies the workgroups of this group actually ran on
   uint32_t abort;      // a workgroup gave up waiting
 };
-
-__device__ __forceinline__ void l1_invalidate() {
-  // what a workgroup-scope acquire is when the waves of a workgroup do not share an L1
-  asm volatile("buffer_inv sc0\n\ts_waitcnt vmcnt(0)" ::: "memory");
-}
 
 // HW_REG_XCC_ID (20), bits 3:0: the die this wave runs on
 __device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg(20 | (0 << 6) | (3 << 11)) & 15u; }
@@ -54,7 +50,6 @@ __device__ inline bool die_barrier(DieSync* sy, uint32_t G, uint32_t gen, long l
     *sh_ok = ok ? 1u : 0u;
   }
   __syncthreads();
-  l1_invalidate();
   return *sh_ok != 0;
 }
 

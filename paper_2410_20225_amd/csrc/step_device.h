@@ -45,6 +45,17 @@ template <int SCOPE> __device__ __forceinline__ uint32_t a_or(uint32_t* p, uint3
 template <int SCOPE> __device__ __forceinline__ uint32_t a_exch(uint32_t* p, uint32_t v) {
   return __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, SCOPE);
 }
+// Reads of data that another compute unit of the same die may have rewritten since this one
+// last read it (frame records, which are swept again and again, and the touched lists, whose
+// storage is reused every other step).  COHERENT: a device-scope load, which goes past this
+// CU's L1 to the die's L2, where the other CU's store is.  An L1 invalidation per step would do
+// too, but its workgroup-scope form does not drop these lines and its device-scope form also
+// drops the L2's.
+template <bool COHERENT, typename T> __device__ __forceinline__ T ld_shared(const T* p) {
+  if (COHERENT) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  return *p;
+}
+
 template <int SCOPE> __device__ __forceinline__ unsigned long long a_ld(const unsigned long long* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, SCOPE);
 }
@@ -431,6 +442,8 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
 
   // kDirect: one workgroup alone (its control block `c` is in LDS): positions in the global lists
   // come straight from the counters in `c`, without staging and without barriers between passes.
+  // several compute units of one die on one machine: see ld_shared
+  constexpr bool kCoherent = SCOPE == __HIP_MEMORY_SCOPE_WORKGROUP && !kDirect;
   uint32_t cnt_tags = 0, cnt_tokens = 0;   // per wave, wave-uniform
 
   for (uint32_t base = first; base < n; base += lane_stride) {
@@ -446,7 +459,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     x.RB = RB; x.tid = tid;
     const uint32_t i = base + tid;
     x.active = i < n;
-    x.frame = x.active ? cur_list[i] : 0;
+    x.frame = x.active ? ld_shared<kCoherent>(&cur_list[i]) : 0;
     if (x.frame >= e.cap + e.n_inst) {   // never true for a list this engine wrote
       raise(c, TDF_ERR_DEVICE);
       x.active = false;
@@ -463,9 +476,9 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     if (x.active) {
       // tokens that arrived for this step; the word of the other parity belongs to the next
       const uint32_t arr = a_exch<SCOPE>(&h->arrived[word ^ 1], 0u);
-      pf_in = h->present_fn;
-      key = h->key;
-      x.fired = h->fired;
+      pf_in = ld_shared<kCoherent>(&h->present_fn);
+      key = ld_shared<kCoherent>(&h->key);
+      x.fired = ld_shared<kCoherent>(&h->fired);
       const uint32_t pf = pf_in | arr;
       depth = (uint32_t)(key >> 8) & 0xFFFFFFu;
       x.present = pf & 0xFFFFFFu;
@@ -474,12 +487,12 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     const unsigned long long fired_in = x.fired;
     // stored values (meaningful where the present bit is set), all loads in flight at once
 #pragma unroll
-    for (int k = 0; k < 8; ++k) x.sv[k] = (x.active && k < n_st) ? x.slots[k] : 0;
+    for (int k = 0; k < 8; ++k) x.sv[k] = (x.active && k < n_st) ? ld_shared<kCoherent>(&x.slots[k]) : 0;
     if (SW::kLdsValues) {
 #pragma unroll
       for (int k = 0; k < 8; ++k)
         if (k < n_st) lds_vals[(z.max_values + k) * RB + tid] = x.sv[k];
-      for (int k = 8; k < n_st; ++k) lds_vals[(z.max_values + k) * RB + tid] = x.active ? x.slots[k] : 0;
+      for (int k = 8; k < n_st; ++k) lds_vals[(z.max_values + k) * RB + tid] = x.active ? ld_shared<kCoherent>(&x.slots[k]) : 0;
     }
 
     SW::run(x, P);   // ---- fire
@@ -620,7 +633,9 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               th->present_fn = 0;
               th->pad = 0;
               th->arrived[word ^ 1] = 0;
-              th->arrived[word] = m.bits;
+              // an atomic, not a store: further parameters of the same call follow with atomics on
+              // this word in this very step, and only atomics on one address keep their order
+              (void)a_exch<SCOPE>(&th->arrived[word], m.bits);
               first_tok = true;
             } else {
               first_tok = a_or<SCOPE>(&th->arrived[word], m.bits) == 0;
@@ -813,7 +828,7 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
     }
     __syncthreads();
     // the other workgroups' writes, before the next step reads them
-    if (LOCAL) l1_invalidate(); else __threadfence();
+    if (!LOCAL) __threadfence();   // (LOCAL: the next step reads them past the L1, see ld_shared)
     ++gen;
     step = sh[0];
     n = sh[1];

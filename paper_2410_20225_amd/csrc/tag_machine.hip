@@ -181,7 +181,9 @@ int tag_machine_small_block(const DevProgram& P, bool jit) {
   const bool lds_values = !jit && !fits_registers(z);
   int rb = 512;
   if (jit) rb = env_block("TDF_SMALL_BLOCK", 512, GEN_SMALL_BLOCK);
-  while (rb > 64 && step_lds_bytes(z, rb, lds_values) > 120 * 1024) rb >>= 1;
+  // generated kernels are module functions, launched without an LDS opt-in: 64 KB at most
+  const size_t lds_limit = jit ? 64 * 1024 : 120 * 1024;
+  while (rb > 64 && step_lds_bytes(z, rb, lds_values) > lds_limit) rb >>= 1;
   return rb;
 }
 
@@ -203,7 +205,8 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
     long long st = spin_ticks;
     void* a_small[] = {&ev, &ms};
     void* a_step[] = {&ev, &ms, &st};
-    const int gb = local ? env_block("TDF_LOCAL_BLOCK", 256, GEN_LOCAL_BLOCK) : STEP_BLOCK;
+    int gb = local ? env_block("TDF_LOCAL_BLOCK", 256, GEN_LOCAL_BLOCK) : STEP_BLOCK;
+    while (gb > 64 && step_lds_bytes(z, gb, false) > 64 * 1024) gb >>= 1;   // no LDS opt-in for module functions
     hipError_t r = hipModuleLaunchKernel((hipFunction_t)jit.small, e.n_dies, 1, 1, small_block, 1, 1,
                                          (unsigned)step_lds_bytes(z, small_block, false), s, a_small, nullptr);
     if (r == hipSuccess)

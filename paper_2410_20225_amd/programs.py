@@ -45,6 +45,45 @@ def fib():
     return [r.desc(), f.desc()], 0
 
 
+def ack():
+    """result(m,n) = ack(m,n); ack(m,n) = n+1 if m==0; ack(m-1,1) if n==0; else ack(m-1, ack(m,n-1))."""
+    r = _Fn("result", 2)
+    r.add(T.OP_OUT, [r.add(T.OP_CALLFN, [r.add(T.OP_IN, imm=0), r.add(T.OP_IN, imm=1)], imm=1)])
+    f = _Fn("ack", 2)
+    m, n = f.add(T.OP_IN, imm=0), f.add(T.OP_IN, imm=1)
+    one, zero = f.add(T.OP_CONST, imm=1), f.add(T.OP_CONST, imm=0)
+    p0 = f.add(T.OP_EQ, [m, zero])
+    sm, sn = f.add(T.OP_SWITCH, [p0, m]), f.add(T.OP_SWITCH, [p0, n])
+    m_e, n_t, n_e = (sm[0], 1), (sn[0], 0), (sn[0], 1)
+    r0 = f.add(T.OP_ADD, [n_t, one])
+    p1 = f.add(T.OP_EQ, [n_e, zero])
+    sm1, sn1 = f.add(T.OP_SWITCH, [p1, m_e]), f.add(T.OP_SWITCH, [p1, n_e])
+    m_et, m_ee, n_et, n_ee = (sm1[0], 0), (sm1[0], 1), (sn1[0], 0), (sn1[0], 1)
+    r1 = f.add(T.OP_CALLFN, [f.add(T.OP_SUB, [m_et, one]), f.add(T.OP_ADD, [n_et, one])], imm=1)
+    inner = f.add(T.OP_CALLFN, [m_ee, f.add(T.OP_SUB, [n_ee, one])], imm=1)
+    r2 = f.add(T.OP_CALLFN, [f.add(T.OP_SUB, [m_ee, one]), inner], imm=1)
+    f.add(T.OP_OUT, [f.add(T.OP_MERGE, [r0, f.add(T.OP_MERGE, [r1, r2])])])
+    return [r.desc(), f.desc()], 0
+
+
+def tak():
+    """result(x,y,z) = tak(x,y,z); tak(x,y,z) = if y<x then tak(tak(x-1,y,z), tak(y-1,z,x), tak(z-1,x,y)) else z."""
+    r = _Fn("result", 3)
+    r.add(T.OP_OUT, [r.add(T.OP_CALLFN, [r.add(T.OP_IN, imm=k) for k in range(3)], imm=1)])
+    f = _Fn("tak", 3)
+    x, y, z = (f.add(T.OP_IN, imm=k) for k in range(3))
+    one = f.add(T.OP_CONST, imm=1)
+    p = f.add(T.OP_LT, [y, x])
+    sx, sy, sz = (f.add(T.OP_SWITCH, [p, v]) for v in (x, y, z))
+    x_t, y_t, z_t, z_e = (sx[0], 0), (sy[0], 0), (sz[0], 0), (sz[0], 1)
+    a = f.add(T.OP_CALLFN, [f.add(T.OP_SUB, [x_t, one]), y_t, z_t], imm=1)
+    b = f.add(T.OP_CALLFN, [f.add(T.OP_SUB, [y_t, one]), z_t, x_t], imm=1)
+    c = f.add(T.OP_CALLFN, [f.add(T.OP_SUB, [z_t, one]), x_t, y_t], imm=1)
+    top = f.add(T.OP_CALLFN, [a, b, c], imm=1)
+    f.add(T.OP_OUT, [f.add(T.OP_MERGE, [top, f.add(T.OP_ID, [z_e])])])
+    return [r.desc(), f.desc()], 0
+
+
 def tree(cell="rnn", head=False):
     """f(v) = if isleaf(v) then embed(token(v)) else cell(f(left v), f(right v));
     result(v) = f(v), or result(v, label) = ce_head(f(v), label)."""

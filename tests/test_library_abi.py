@@ -105,6 +105,7 @@ def test_workspace_size_grows_with_capacity():
     ("fact", programs.fact, False), ("fib", programs.fib, False),
     ("treernn", lambda: programs.tree("rnn", False), False),
     ("treelstm_head_grad", lambda: programs.tree("lstm", True), True),
+    ("ack", programs.ack, False), ("tak", programs.tak, False),
 ])
 def test_generated_step_kernels_compile_for_gfx950(name, prog, grad):
     # the firing tables of every workload turn into HIP source that the run-time compiler
