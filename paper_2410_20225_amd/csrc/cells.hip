@@ -384,8 +384,41 @@ template <> struct Chunk<float> {
 // One tile: rows 32 rt .. 32 rt + 31 of the level, hidden units (output columns) 32 ct .. 32 ct + 31.
 // Called by all NW * 64 threads of a workgroup (NW = 4 or 8 waves split the reduction); `part` is
 // its LDS scratch [wave][G][16][64].
+// Weight operands of a wave for one column tile, kept in registers across tiles by the tail
+// kernels (a workgroup there always works on the same column tile): RES chunk steps.
+template <int MODE, int RES> struct ResidentB {
+  static constexpr int G = MODE == LSTM_FWD ? 5 : 1;
+  u32x4 f[RES > 0 ? RES : 1][G];
+};
+
 template <int DT, int MODE, int NW>
-__device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int ct, float* part) {
+__device__ __forceinline__ const typename TypeOf<DT>::type* tile_b_base(const GemmArgs& g, int ct, int j) {
+  typedef typename TypeOf<DT>::type T;
+  constexpr int EPC = 16 / (int)sizeof(T);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int brt = (MODE == LSTM_FWD ? j * (g.Hp / 32) : 0) + ct;
+  // operand order: chunk step st of this wave is 64 * EPC elements further on
+  return reinterpret_cast<const T*>(g.Bf) + (((size_t)brt * (g.K / Chunk<T>::KC) + wave * (g.K / NW / Chunk<T>::KC)) * 64 + lane) * EPC;
+}
+
+template <int DT, int MODE, int NW, int RES>
+__device__ __forceinline__ void load_resident_b(const GemmArgs& g, int ct, ResidentB<MODE, RES>& rb) {
+  typedef typename TypeOf<DT>::type T;
+  constexpr int EPC = 16 / (int)sizeof(T);
+  const int steps = g.K / NW / Chunk<T>::KC;
+#pragma unroll
+  for (int j = 0; j < ResidentB<MODE, RES>::G; ++j) {
+    const T* bp = tile_b_base<DT, MODE, NW>(g, ct, j);
+#pragma unroll
+    for (int st = 0; st < RES; ++st) rb.f[st][j] = *reinterpret_cast<const u32x4*>(bp + (size_t)min(st, steps - 1) * 64 * EPC);
+  }
+}
+
+// RES > 0: the weight operands come from `rb` (which holds all chunk steps of this wave: the
+// caller checked steps <= RES); RES == 0: they are fetched here.
+template <int DT, int MODE, int NW, int RES = 0>
+__device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int ct, float* part,
+                                                const ResidentB<MODE, RES>* rb = nullptr) {
   typedef typename TypeOf<DT>::type T;
   typedef Chunk<T> C;
   constexpr int G = MODE == LSTM_FWD ? 5 : 1;      // 32-wide column blocks per tile
@@ -418,12 +451,9 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
     Ap = reinterpret_cast<const T*>(g.Hs) + (size_t)child * g.Hp + (wave % (NW / 2)) * kw;
   }
   Ap += (lane >> 5) * EPC;
-  const T* Bp[G];   // operand order: chunk step st of this wave is 64 * EPC elements further on
+  const T* Bp[G];
 #pragma unroll
-  for (int j = 0; j < G; ++j) {
-    const int brt = (MODE == LSTM_FWD ? j * (g.Hp / 32) : 0) + ct;
-    Bp[j] = reinterpret_cast<const T*>(g.Bf) + (((size_t)brt * (g.K / C::KC) + wave * (kw / C::KC)) * 64 + lane) * EPC;
-  }
+  for (int j = 0; j < G; ++j) Bp[j] = tile_b_base<DT, MODE, NW>(g, ct, j);
   // children's cell states for the epilogue, requested before the products start
   float cl[RPW], cr[RPW];
   const int unit = ct * 32 + (lane & 31);
@@ -441,6 +471,18 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
   const int steps = kw / C::KC;
+  if constexpr (RES > 0) {
+    u32x4 fa[RES];
+#pragma unroll
+    for (int st = 0; st < RES; ++st) fa[st] = *reinterpret_cast<const u32x4*>(Ap + min(st, steps - 1) * C::KC);
+#pragma unroll
+    for (int st = 0; st < RES; ++st) {
+      if (st < steps) {
+#pragma unroll
+        for (int j = 0; j < G; ++j) acc[j] = C::mma(fa[st], rb->f[st][j], acc[j]);
+      }
+    }
+  } else
   for (int s0 = 0; s0 < steps; s0 += BATCH) {
     u32x4 fa[BATCH], fb[BATCH][G];
 #pragma unroll
@@ -718,6 +760,12 @@ __global__ void __launch_bounds__(NW * 64) k_tail_fwd(GemmArgs g, TailArgs t) {
   DieSync* sy = t.sync + die;
   if (threadIdx.x == 0) atomicOr(&sy->xcc_mask, 1u << xcc_id());
   const int n_ct = g.n_tiles_n;
+  // A workgroup keeps to one column tile where the tiles divide evenly among the workgroups,
+  // and then holds that tile's weight operands in registers for the whole launch.
+  constexpr int RES = 8;
+  const bool resident = G % (uint32_t)n_ct == 0 && g.K / NW / Chunk<T>::KC <= RES;
+  ResidentB<MODE, RES> rb;
+  if (resident) load_resident_b<DT, MODE, NW, RES>(g, (int)(rank % n_ct), rb);
   uint32_t gen = 0;
   for (uint32_t lvl = t.lvl_first; lvl <= t.lvl_last; ++lvl) {
     const uint32_t q0 = t.level_off[lvl * LEVEL_KEY_DIES + die];
@@ -726,9 +774,14 @@ __global__ void __launch_bounds__(NW * 64) k_tail_fwd(GemmArgs g, TailArgs t) {
     gl.M = (int)cnt;
     gl.out = g.out + q0; gl.l = g.l + q0; gl.r = g.r + q0;
     gl.gates = g.gates ? reinterpret_cast<T*>(g.gates) + (size_t)q0 * g.ldg : nullptr;
-    const uint32_t tiles = (cnt + 31) / 32 * (uint32_t)n_ct;
-    for (uint32_t tile = rank; tile < tiles; tile += G)
-      cell_small_tile<DT, MODE, NW>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+    const uint32_t n_rt = (cnt + 31) / 32;
+    if (resident) {
+      for (uint32_t rt = rank / n_ct; rt < n_rt; rt += G / n_ct)
+        cell_small_tile<DT, MODE, NW, RES>(gl, (int)rt, (int)(rank % n_ct), part, &rb);
+    } else {
+      for (uint32_t tile = rank; tile < n_rt * n_ct; tile += G)
+        cell_small_tile<DT, MODE, NW>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+    }
     if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
   }
 }
@@ -746,6 +799,10 @@ __global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Eng
   DieSync* sy = t.sync + die;
   if (threadIdx.x == 0) atomicOr(&sy->xcc_mask, 1u << xcc_id());
   const int n_ct = g.n_tiles_n;
+  constexpr int RES = 10;
+  const bool resident = G % (uint32_t)n_ct == 0 && g.K / NW / Chunk<T>::KC <= RES;
+  ResidentB<DX_BWD, RES> rb;
+  if (resident) load_resident_b<DT, DX_BWD, NW, RES>(g, (int)(rank % n_ct), rb);
   uint32_t gen = 0;
   for (uint32_t lvl = t.lvl_last; lvl >= t.lvl_first; --lvl) {
     const uint32_t q0 = t.level_off[lvl * LEVEL_KEY_DIES + die];
@@ -756,9 +813,14 @@ __global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Eng
     gl.M = (int)cnt;
     gl.A = reinterpret_cast<const T*>(g.A) + (size_t)q0 * g.lda;
     gl.l = g.l + q0; gl.r = g.r + q0;
-    const uint32_t tiles = (cnt + 31) / 32 * (uint32_t)n_ct;
-    for (uint32_t tile = rank; tile < tiles; tile += G)
-      cell_small_tile<DT, DX_BWD, NW>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+    const uint32_t n_rt = (cnt + 31) / 32;
+    if (resident) {
+      for (uint32_t rt = rank / n_ct; rt < n_rt; rt += G / n_ct)
+        cell_small_tile<DT, DX_BWD, NW, RES>(gl, (int)rt, (int)(rank % n_ct), part, &rb);
+    } else {
+      for (uint32_t tile = rank; tile < n_rt * n_ct; tile += G)
+        cell_small_tile<DT, DX_BWD, NW>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+    }
     if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
   }
 }
