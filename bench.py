@@ -23,6 +23,27 @@ PEAK_F32 = 157.3e12     # fp32 MFMA / vector
 PEAK_HBM = 8.0e12       # B/s
 COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 
+# HBM bytes per evaluation from the FETCH_SIZE / WRITE_SIZE counter passes (see
+# profiles/bench_workload4_hbm_traffic.md), with the hash of the kernel source they were taken on:
+# reported as `traffic` only while that source is unchanged.
+MEASURED_TRAFFIC = {
+    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "121d91d0d2110eb1", 2228715124.3),
+        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "fabaa146e1a56d88", 369899053.7)},
+}
+
+
+def measured_traffic(cfg, which):
+    import hashlib
+    ent = MEASURED_TRAFFIC.get(cfg, {}).get(which)
+    if not ent:
+        return None
+    path, sha, nbytes = ent
+    try:
+        now = hashlib.sha256(open(os.path.join(ROOT, path), "rb").read()).hexdigest()[:16]
+    except OSError:
+        return None
+    return nbytes if now == sha else None
+
 
 def cpu_baseline(cfg, budget_trees):
     """The oracle, as it stands, on the first trees of the same workload."""
@@ -147,7 +168,7 @@ def main():
     tag_ms = phase[0] / a.steps
     roof_tags = {"bound": "hbm", "kernel": "tag machine step kernels (all steps)",
                  "achieved": tag_bytes / (tag_ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
-                 "launches_per_step": launches[0] / a.steps, "traffic": None}
+                 "launches_per_step": launches[0] / a.steps, "traffic": measured_traffic(cfg, "steps")}
     roof_tags["frac"] = roof_tags["achieved"] / roof_tags["peak"]
     roof_tags["copy_kernel_GBps"] = copy_gbps   # measured read + write rate of a plain 1 GiB device copy
     if cfg == 1:
@@ -160,7 +181,8 @@ def main():
         per_cell = 2.0 * rows * 2 * c["H"]
         roof = {"bound": "mfma", "kernel": "k_gemm + k_tail_fwd <%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
                 "achieved": flops_fwd / (ms * 1e-3) / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
-                "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1), "traffic": None}
+                "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1),
+                "traffic": measured_traffic(cfg, "cells")}
         # the same, split by level width: one launch per wide level, one launch for the whole narrow tail
         wide_ms, tail_ms = phase[i_fwd] / a.steps, phase[i_tail] / a.steps
         wide_cells = int(st.n_wide_cells)
