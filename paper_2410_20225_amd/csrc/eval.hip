@@ -101,8 +101,12 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.n_inst = B;
   e.max_tags = T;
   e.cap = pow2_at_least(2ull * T);
-  e.cap_mask = e.cap - 1;
   e.n_dies = dies_for(B, max_dies);
+  // Without vector operators a table slot costs one frame record and no state rows: every
+  // machine's part is then as large as the whole table would be, so that instances of very
+  // different sizes (fib(20) beside fib(3)) cannot overflow a part.
+  if (!P.vec && (uint64_t)e.cap * e.n_dies <= (1ull << 26)) e.cap *= e.n_dies;
+  e.cap_mask = e.cap - 1;
   e.part_mask = e.cap / e.n_dies - 1;
   e.die = 0;
   e.key_base = 0;
