@@ -83,3 +83,26 @@ def test_grid_barrier_wait_is_bounded(local, lstm_case, monkeypatch):
     st, stats = run.run(dy)
     assert st == tdf.OK and stats.n_tags == c["forest"].n_nodes
     assert rel_fro(run.dW.cpu().numpy(), ref["grads"]["dW"]) < 2e-2
+
+
+def test_one_huge_instance_among_small_ones():
+    # Eight trees dealt to eight machines, one of them holding nearly all tags: that machine's
+    # part of the tag table fills up although the whole table has room.  The library repeats the
+    # run with one machine; values and counts are the oracle's.
+    from tdf_workloads import SplitMix64
+    from tdf_workloads.trees import left_chain_tree, random_split_tree, build_forest
+    c = make_config(3, n_trees=8, max_leaves=6, hidden=64, vocab=200)
+    rng = SplitMix64(77)
+    shapes = [left_chain_tree(300)] + [random_split_tree(3 + b % 3, rng.fork(b)) for b in range(7)]
+    c["forest"] = build_forest(shapes, lambda n: rng.randint(0, 199, n))
+    B = 8
+    dy = np.full(B, 1.0 / B)
+    ref = run_oracle_tree(c, head=True, grad=True, dy=dy)
+    run = TreeRun(c, head=True, grad=True)                 # max_tags = exactly the number of tags
+    for _ in range(2):                                     # the second call starts with one machine
+        st, stats = run.run(dy)
+        assert stats.n_tags == c["forest"].n_nodes == len(ref["it"].tags)
+        assert stats.max_tag_depth == ref["it"].max_tag_len
+        assert rel_fro(run.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
+        for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
+            assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-2, name
