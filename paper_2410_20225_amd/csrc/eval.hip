@@ -344,6 +344,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     e.small_limit = (uint32_t)small_block;   // one pass of the single workgroup
     if (const char* w = getenv("TDF_SMALL_LIMIT")) e.small_limit = (uint32_t)std::max(1, atoi(w));
+    e.follow_limit = e.small_limit;
+    if (const char* w = getenv("TDF_FOLLOW_LIMIT")) e.follow_limit = (uint32_t)std::max(0, atoi(w));
     HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
     HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
     launch_seed(G.prog, e, s);

@@ -484,7 +484,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       x.present = pf & 0xFFFFFFu;
       x.myfn = (int)(pf >> 24);
     }
-    const unsigned long long fired_in = x.fired;
+    unsigned long long fired_in = x.fired;
     // stored values (meaningful where the present bit is set), all loads in flight at once
 #pragma unroll
     for (int k = 0; k < 8; ++k) x.sv[k] = (x.active && k < n_st) ? ld_shared<kCoherent>(&x.slots[k]) : 0;
@@ -494,6 +494,26 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         if (k < n_st) lds_vals[(z.max_values + k) * RB + tid] = x.sv[k];
       for (int k = 8; k < n_st; ++k) lds_vals[(z.max_values + k) * RB + tid] = x.active ? ld_shared<kCoherent>(&x.slots[k]) : 0;
     }
+
+    // A lane that creates the frame of a one-parameter call goes on with that frame in the same
+    // step instead of putting it on the next list (kDirect only): nobody else can reach a fresh
+    // frame, its only argument is at hand, so its first sweep needs no loads of the header.  A
+    // chain of such calls is descended by one lane at two round trips per call instead of one
+    // step per call.  Of several calls of one sweep the lane follows the first and lists the
+    // others, so the descent that gets shorter is the one along first calls (f(n-1) of fib, the
+    // left spine of a tree).  While the machine's steps still grow, all descents advance together
+    // one call per step anyway and a long sweep would only hold the others up: lanes follow only
+    // in a step with exactly as many frames as the step before (chains descending side by side)
+    // or with fewer, once the steps are down to a quarter of the machine's largest (the tail of
+    // a batch, where the deep stragglers decide the number of steps).  Bounded, so that a
+    // recursion without a base case still meets the step limit.
+    constexpr int FOLLOW_DEPTH = 256;
+    const bool may_follow = kDirect && n <= e.follow_limit && (n == c->prev_count || (n < c->prev_count && n * 4u <= c->peak_count));
+    for (int follow = 0;; ++follow) {
+    bool has_next = false;
+    uint32_t nx_frame = 0, nx_bits = 0, nx_slot = 0;
+    unsigned long long nx_key = 0;
+    long long nx_val = 0;
 
     SW::run(x, P);   // ---- fire
 
@@ -626,7 +646,17 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
           if (found[q]) {
             FrameHdr* th = frame_at(e, stride, m.target);
             frame_slots(th)[m.slot] = m.val;
-            if (inserted) {
+            if (inserted && may_follow && !has_next && follow + 1 < FOLLOW_DEPTH && P.fn[m.callee].n_params == 1) {
+              // the frame this lane goes on with: complete header, nothing pending, not listed
+              th->key = m.ckey;
+              th->fired = 0;
+              th->present_fn = m.bits;
+              th->pad = 0;
+              th->arrived[0] = 0;
+              th->arrived[1] = 0;
+              has_next = true;
+              nx_frame = m.target; nx_bits = m.bits; nx_slot = m.slot; nx_key = m.ckey; nx_val = m.val;
+            } else if (inserted) {
               // a fresh frame: nobody else can reach it in this step, so its creator writes the header
               th->key = m.ckey;
               th->fired = 0;
@@ -657,10 +687,39 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         cnt_tokens += (uint32_t)__popcll(__ballot(m.has));
         if (ins[q]) {
           mx_probe = probes[q] > mx_probe ? probes[q] : mx_probe;
-          mx_depth = depth + 1;
+          mx_depth = depth + 1 > mx_depth ? depth + 1 : mx_depth;
         }
       }
     }
+    if (x.active) {
+      if (x.fired != fired_in) h->fired = x.fired;
+      const uint32_t pf_out = x.present | ((uint32_t)x.myfn << 24);
+      if (pf_out != pf_in) h->present_fn = pf_out;
+    }
+    if (!kDirect || __ballot(has_next) == 0) break;
+    // go on with the frame just created
+    x.active = has_next;
+    x.frame = has_next ? nx_frame : 0;
+    h = frame_at(e, stride, x.frame);
+    x.slots = frame_slots(h);
+    x.fired = 0;
+    fired_in = 0;
+    pf_in = nx_bits;
+    x.present = nx_bits & 0xFFFFFFu;
+    x.myfn = has_next ? (int)(nx_bits >> 24) : -1;
+    key = nx_key;
+    depth = (uint32_t)(nx_key >> 8) & 0xFFFFFFu;
+    x.n_pend = 0;
+    x.tc_v = -1;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) x.sv[k] = (has_next && (uint32_t)k == nx_slot) ? nx_val : 0;
+    if (SW::kLdsValues) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        if (k < n_st) lds_vals[(z.max_values + k) * RB + tid] = x.sv[k];
+      for (int k = 8; k < n_st; ++k) lds_vals[(z.max_values + k) * RB + tid] = 0;
+    }
+    }   // follow
     {   // per-wave maxima of the pass
       const uint32_t wl = wave_umax(x.mx_level), wp = wave_umax(mx_probe), wd = wave_umax(mx_depth);
       if ((tid & 63) == 0) {
@@ -674,12 +733,6 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         }
       }
     }
-    if (x.active) {
-      if (x.fired != fired_in) h->fired = x.fired;
-      const uint32_t pf_out = x.present | ((uint32_t)x.myfn << 24);
-      if (pf_out != pf_in) h->present_fn = pf_out;
-    }
-
     if (kDirect) continue;
     // ---- the workgroup reserves its ranges of the global lists and copies the entries out ---
     __syncthreads();
@@ -733,6 +786,11 @@ __device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
   const int parity = (int)(step & 1);
   const uint32_t next = ld(&c->touched_count[parity ^ 1]);
   uint32_t status = ld(&c->status);
+  {
+    const uint32_t n = ld(&c->touched_count[parity]);
+    st(&c->prev_count, n);
+    if (n > ld(&c->peak_count)) st(&c->peak_count, n);
+  }
   st(&c->touched_count[parity], 0u);
   st(&c->step, step + 1);
   if (ld(&c->n_tags) > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
@@ -855,6 +913,8 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     lc.touched_count[0] = ld(&g->touched_count[0]);
     lc.touched_count[1] = ld(&g->touched_count[1]);
     lc.step = g->step;
+    lc.prev_count = ld(&g->prev_count);
+    lc.peak_count = ld(&g->peak_count);
     lc.n_leaf = ld(&g->n_leaf);
     lc.n_cell = ld(&g->n_cell);
     lc.n_head = ld(&g->n_head);
@@ -881,6 +941,8 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     st(&g->touched_count[0], lc.touched_count[0]);
     st(&g->touched_count[1], lc.touched_count[1]);
     g->step = lc.step;
+    st(&g->prev_count, lc.prev_count);
+    st(&g->peak_count, lc.peak_count);
     st(&g->n_leaf, lc.n_leaf);
     st(&g->n_cell, lc.n_cell);
     st(&g->n_head, lc.n_head);

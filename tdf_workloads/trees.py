@@ -75,6 +75,11 @@ def left_chain_tree(n_leaves):
     return _shape_from_splits(n_leaves, lambda L: L - 1)
 
 
+def right_chain_tree(n_leaves):
+    """The left child of every internal node is a single leaf (depth n_leaves-1)."""
+    return _shape_from_splits(n_leaves, lambda L: 1)
+
+
 def complete_tree(n_leaves):
     """Halving split; n_leaves is a power of two."""
     assert n_leaves & (n_leaves - 1) == 0

@@ -2,7 +2,7 @@
 the table interpreter instead of generated step kernels, grid-wide steps synchronised through
 memory instead of one die's L2, every level through the tiled GEMM or through the small-level
 kernel, and every step through the grid-wide kernel (on eight machines and on one) or through
-the single-workgroup kernel.  Same bars as the main parity tests: integers and counts bit-exact, bf16
+the single-workgroup kernel, and steps in which no lane goes on with the frame it created.  Same bars as the main parity tests: integers and counts bit-exact, bf16
 within rel 2e-2 (Frobenius)."""
 import numpy as np
 import pytest
@@ -18,9 +18,10 @@ from gpu_util import DEV, TreeRun, run_oracle_tree, rel_fro, fire_counts  # noqa
 
 VARIANTS = [{"TDF_NO_JIT": "1"}, {"TDF_NO_DIE_LOCAL": "1"}, {"TDF_NO_JIT": "1", "TDF_NO_DIE_LOCAL": "1"},
             {"TDF_SMALL_LEVEL": "0"}, {"TDF_SMALL_LEVEL": "100000000"},
-            {"TDF_SMALL_LIMIT": "1"}, {"TDF_SMALL_LIMIT": "1", "TDF_DIES": "1"}, {"TDF_SMALL_LIMIT": "100000000"}]
+            {"TDF_SMALL_LIMIT": "1"}, {"TDF_SMALL_LIMIT": "1", "TDF_DIES": "1"}, {"TDF_SMALL_LIMIT": "100000000"},
+            {"TDF_FOLLOW_LIMIT": "0"}]
 IDS = ["interpreter", "device_scope", "interpreter_device_scope", "tiled_gemm_only", "small_level_only",
-       "grid_kernel_only", "grid_kernel_only_one_machine", "single_workgroup_only"]
+       "grid_kernel_only", "grid_kernel_only_one_machine", "single_workgroup_only", "no_follow"]
 
 
 @pytest.fixture(scope="module")
@@ -50,7 +51,7 @@ def test_treelstm_variants(env, lstm_case, monkeypatch):
         assert got[k] == want[k], k
 
 
-@pytest.mark.parametrize("env", VARIANTS[:3], ids=IDS[:3])
+@pytest.mark.parametrize("env", VARIANTS[:3] + VARIANTS[-1:], ids=IDS[:3] + IDS[-1:])
 def test_fib_variants(env, monkeypatch):
     for k, v in env.items():
         monkeypatch.setenv(k, v)
@@ -106,3 +107,33 @@ def test_one_huge_instance_among_small_ones():
         assert rel_fro(run.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
         for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
             assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-2, name
+
+
+@pytest.mark.parametrize("follow", ["default", "0"])
+def test_chains_leaning_either_way(follow, monkeypatch):
+    # Chains deeper than one lane follows in a step (256), leaning left (the first call of a frame
+    # is the deep one) and right (the second is), next to bushy trees.
+    if follow != "default":
+        monkeypatch.setenv("TDF_FOLLOW_LIMIT", follow)
+    from tdf_workloads import SplitMix64
+    from tdf_workloads.trees import left_chain_tree, right_chain_tree, random_split_tree, build_forest
+    c = make_config(3, n_trees=12, max_leaves=6, hidden=64, vocab=200)
+    rng = SplitMix64(78)
+    shapes = [left_chain_tree(300), right_chain_tree(290), left_chain_tree(2), right_chain_tree(3)]
+    shapes += [random_split_tree(10 + 5 * b, rng.fork(b)) for b in range(8)]
+    c["forest"] = build_forest(shapes, lambda n: rng.randint(0, 199, n))
+    B = len(shapes)
+    c["labels"] = rng.randint(0, 4, B)
+    dy = np.full(B, 1.0 / B)
+    ref = run_oracle_tree(c, head=True, grad=True, dy=dy)
+    run = TreeRun(c, head=True, grad=True)
+    st, stats = run.run(dy)
+    assert stats.n_tags == c["forest"].n_nodes == len(ref["it"].tags)
+    assert stats.max_tag_depth == ref["it"].max_tag_len
+    assert rel_fro(run.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
+    for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
+        assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-2, name
+    got = fire_counts(run.graph, stats)
+    want = ref["it"].count_by_op()
+    for k in ("merge_entry", "isleaf", "switch", "call_0", "call_1", "return_0", "return_1"):
+        assert got[k] == want[k], k
