@@ -12,11 +12,26 @@ parameter, replaces the callee's input nodes by Merge nodes fed by the Call_i no
 hangs Return_0..Return_{n-1} on the callee's output, wires Return_i to wherever call i's
 result went, and adds a control edge from every Call_i to its Return_i.
 
+Tagged iteration (Section 2.3, figure "Dataflow implementation of a while-loop"): a loop is
+written as a graph of its own, the *loop graph*.  Its input nodes are the loop variables of
+the current iteration (the Merge nodes of the figure, fed by Enter and by Next), its `next`
+node takes the variables' values for the following iteration, and its output node is the value
+that leaves the loop (it hangs on the false side of the Switch on the loop condition).  A
+`loop` node in another graph supplies the initial values and stands for the value that leaves.
+The static graph gets one Enter node per variable at the `loop` node's place, one Next node
+per variable, and one Exit node on the loop graph's output value.
+
 Readings where the paper is silent:
   * labels i are unique over the whole program, not per callee;
   * `result` may have input nodes of its own: they are the per-instance program inputs;
   * gradient inputs / outputs of a function (`gin`, `gout`, Section 4) are treated exactly
-    like `in` / `out`, and a `callgrad` node shares the label of the call it belongs to.
+    like `in` / `out`, and a `callgrad` node shares the label of the call it belongs to;
+  * a loop graph belongs to exactly one `loop` node (a while-loop is written in place, it is
+    not a shared definition), so an Exit needs no label check; `loop` nodes are numbered
+    together with the call nodes, the number only names the loop;
+  * values of the enclosing scope that the loop reads are loop variables handed on unchanged;
+  * Enter -> Exit control edges, as between Call_i and Return_i: a loop whose initial values
+    are dead is not entered and its Exit emits a dead token (see interp.py).
 """
 from dataclasses import dataclass, field
 
@@ -67,6 +82,18 @@ class Function:
     def call(self, fn_name, *args):
         return self._add("call", args, fn=fn_name)
 
+    def loop(self, loop_name, *inits):
+        """The while-loop written as loop graph `loop_name`, started with `inits`."""
+        return self._add("loop", inits, fn=loop_name)
+
+    def next(self, *values):
+        """In a loop graph: the loop variables' values for the next iteration."""
+        return self._add("next", values)
+
+    @property
+    def is_loop(self):
+        return any(nd.op == "next" for nd in self.nodes)
+
     def output(self, ref):
         self.out = self._add("out", [ref])[0]
         return self.out
@@ -86,6 +113,27 @@ class Program:
                         raise ValueError("call to undefined function %s" % nd.attr["fn"])
                     if len(nd.ins) != len(g.param_types):
                         raise ValueError("arity mismatch calling %s" % g.name)
+                    if g.is_loop:
+                        raise ValueError("%s is a loop graph: it cannot be called" % g.name)
+        users = {}
+        for f in functions:
+            if sum(nd.op == "next" for nd in f.nodes) > 1:
+                raise ValueError("loop graph %s has two next nodes" % f.name)
+            for nd in f.nodes:
+                if nd.op == "next" and len(nd.ins) != len(f.param_types):
+                    raise ValueError("next of %s needs one value per loop variable" % f.name)
+                if nd.op == "loop":
+                    g = self.functions.get(nd.attr["fn"])
+                    if g is None or not g.is_loop:
+                        raise ValueError("loop over %s, which is not a loop graph" % nd.attr["fn"])
+                    if len(nd.ins) != len(g.param_types):
+                        raise ValueError("loop %s needs one initial value per variable" % g.name)
+                    users[g.name] = users.get(g.name, 0) + 1
+        for f in functions:
+            if f.is_loop and users.get(f.name, 0) != 1:
+                raise ValueError("loop graph %s must belong to exactly one loop node" % f.name)
+            if f.is_loop and f.name == result:
+                raise ValueError("result cannot be a loop graph")
 
 
 # --------------------------------------------------------------------------------------
@@ -140,7 +188,7 @@ def transform(program):
     label_of = {}
     for fname in order:
         for idx, nd in enumerate(fns[fname].nodes):
-            if nd.op == "call":
+            if nd.op in ("call", "loop"):
                 label_of[(fname, idx)] = len(label_of)
                 g.labels[label_of[(fname, idx)]] = (fname, nd.attr["fn"])
 
@@ -157,10 +205,10 @@ def transform(program):
                     s = g.add(nd.op, fname, nd.attr)
                     g.inputs[(nd.op, k)] = s
                 else:
-                    s = g.add("merge_entry", fname, {"k": k, "kind": nd.op})
+                    s = g.add("merge_entry", fname, {"k": k, "kind": "loop" if f.is_loop else nd.op})
                     entry[(fname, nd.op, k)] = s
                 smap[(fname, idx, 0)] = (s, 0)
-            elif nd.op in ("call", "callgrad"):
+            elif nd.op in ("call", "callgrad", "loop", "next"):
                 continue
             else:
                 s = g.add(nd.op, fname, nd.attr)
@@ -188,6 +236,27 @@ def transform(program):
                 call_nodes[(fname, idx)] = cs
                 pending_ret.append((r, callee, "out", 0))
                 smap[(fname, idx, 0)] = (r, 0)
+            elif nd.op == "loop":
+                # Enter (one per loop variable) and Exit; the Exit hangs on the loop graph's output
+                lab, callee = label_of[(fname, idx)], nd.attr["fn"]
+                cs = []
+                for k in range(len(nd.ins)):
+                    c = g.add("enter", fname, {"label": lab, "k": k, "callee": callee})
+                    cs.append(c)
+                    g.nodes[entry[(callee, "in", k)]].ins.append((c, 0))
+                r = g.add("exit", fname, {"label": lab, "callee": callee})
+                g.nodes[r].ctl = list(cs)
+                call_nodes[(fname, idx)] = cs
+                pending_ret.append((r, callee, "out", 0))
+                smap[(fname, idx, 0)] = (r, 0)
+            elif nd.op == "next":
+                # Next (one per loop variable) feeds the variable's Merge
+                cs = []
+                for k in range(len(nd.ins)):
+                    c = g.add("next", fname, {"k": k})
+                    cs.append(c)
+                    g.nodes[entry[(fname, "in", k)]].ins.append((c, 0))
+                call_nodes[(fname, idx)] = cs
             elif nd.op == "callgrad":
                 pair = nd.attr["pair"]
                 lab, callee = label_of[(fname, pair)], f.nodes[pair].attr["fn"]
@@ -204,7 +273,7 @@ def transform(program):
     for fname in order:
         f = fns[fname]
         for idx, nd in enumerate(f.nodes):
-            if nd.op in ("call", "callgrad"):
+            if nd.op in ("call", "callgrad", "loop", "next"):
                 for k, (src, port) in enumerate(nd.ins):
                     g.nodes[call_nodes[(fname, idx)][k]].ins.append(smap[(fname, src, port)])
             elif nd.op not in ("in", "gin"):

@@ -18,7 +18,18 @@ float, a float64 array, or DEAD (the hiaton, written * in the paper).
                   token to Return_i
   Return_i        <i:t,d> -> <t,d> once its control tokens for i:t are there; data whose
                   head label is not i is dropped; DEAD control -> <t,*>
+  Enter           <t,d> -> <0:t,d> into the loop (Section 2.3), plus a control token <t> to
+                  the loop's Exit; a DEAD input sends nothing into the loop and a DEAD control
+                  token to the Exit
+  Next            <n:t,d> -> <(n+1):t,d>; a DEAD input ends there (the iteration after the
+                  last one does not exist)
+  Exit            <n:t,d> -> <t,d> once the control tokens for t are there; DEAD data ends
+                  there (every iteration but the last sends one); DEAD control -> <t,*>
   constants       hold for all tags: they are immediates of the consuming node
+
+A tag is one list for call labels and iteration counters alike (Section 5.1: loop scopes and
+function scopes share one stack); which of the two an element is follows from the node that
+handles the token, as in the paper.
 
 Execution is in synchronous rounds: every (node, tag) that became ready in round r fires
 in round r+1.  The paper's executor is asynchronous; results and counts do not depend on
@@ -70,6 +81,7 @@ class Interpreter:
         self.ready = []
         self.fire_count = [0] * len(self.g.nodes)
         self.tags = set()              # call-context tags created (entry Merge firings)
+        self.iter_tags = set()         # (loop graph, tag) of every iteration entered
         self.fwd_body = {}             # tag -> live firings of the function's result value
         self.bwd_body = {}             # tag -> live firings of the gradient entry
         self.dropped = 0               # Return_i label mismatches
@@ -101,6 +113,18 @@ class Interpreter:
         nd = self.g.nodes[j]
         if nd.op == "return" and not control and tag[0] != nd.attr["label"]:
             self.dropped += 1                       # wrong frame label: no output
+            return
+        if nd.op == "exit":
+            if not control:
+                if value is DEAD:                   # an iteration that goes on: nothing leaves
+                    return
+                tag = tag[1:]                       # pop the iteration counter
+            rec = self._slot(j, tag)
+            (rec[1] if control else rec[0])[slot] = value
+            ctl = rec[1]
+            if all(c is not None for c in ctl):
+                if any(c is DEAD for c in ctl) or rec[0][0] is not None:
+                    self._schedule(j, tag, rec)
             return
         rec = self._slot(j, tag)
         if rec[3] and nd.op in ("merge", "merge_entry"):
@@ -137,7 +161,10 @@ class Interpreter:
             out = live[0] if live else DEAD
             if out is not DEAD:
                 self.fire_count[j] += 1
-                if op == "merge_entry":
+                if op == "merge_entry" and nd.attr["kind"] == "loop":
+                    self.iter_tags.add((nd.fn, tag))
+                    self.max_tag_len = max(self.max_tag_len, len(tag) - 1)
+                elif op == "merge_entry":
                     self.tags.add(tag)
                     self.max_tag_len = max(self.max_tag_len, len(tag) - 1)
                     if nd.attr["kind"] == "gin":
@@ -160,6 +187,26 @@ class Interpreter:
             if not dead:
                 self.fire_count[j] += 1
             self._emit(j, 0, tag[1:], out)
+            return
+        if op == "enter":
+            v = vals[0]
+            if v is not DEAD:
+                self.fire_count[j] += 1
+                self._emit(j, 0, (0,) + tag, v)
+            for dst, cslot in nd.ctl_outs:
+                self._deliver(dst, cslot, tag, DEAD if v is DEAD else True, control=True)
+            return
+        if op == "next":
+            v = vals[0]
+            if v is not DEAD:
+                self.fire_count[j] += 1
+                self._emit(j, 0, (tag[0] + 1,) + tag[1:], v)
+            return
+        if op == "exit":                            # `tag` is the enclosing scope's already
+            dead = any(c is DEAD for c in ctl)
+            if not dead:
+                self.fire_count[j] += 1
+            self._emit(j, 0, tag, DEAD if dead else vals[0])
             return
         if op == "addn":
             live = [v for v in vals if v is not DEAD]
@@ -325,5 +372,9 @@ class Interpreter:
                 name = "%s_%d" % (nd.op, nd.attr["label"])
                 if nd.attr["kind"] != ("in" if nd.op == "call" else "out"):
                     name += "_grad"
+            if nd.op in ("enter", "exit"):
+                name = "%s_%d" % (nd.op, nd.attr["label"])
+            if nd.op == "next":
+                name = "next_" + nd.fn
             out[name] = out.get(name, 0) + c
         return out

@@ -110,3 +110,107 @@ def tree_program(cell="rnn", head=False):
         r = Function("result", [INT], VEC)
         r.output(r.call("f", r.param(0)))
     return Program([r, f])
+
+
+# ---- tagged iteration (Section 2.3) -----------------------------------------------------------
+# A while-loop is a loop graph: its parameters are the loop variables, the Switch on the loop
+# condition sends them into the body (true side) or out of the loop (false side), `next` takes
+# the body's results, the output hangs on the false side.
+def _counting_loop(name, n_vars, step):
+    """while 0 < v0: (v0, v1, ..) = step(g, v0_true, v1_true, ..); leaves with the last
+    variable.  Returns the loop graph."""
+    g = Function(name, [INT] * n_vars, INT)
+    p = g.op("lt", g.const(0), g.param(0))
+    sides = [g.switch(p, g.param(k)) for k in range(n_vars)]
+    g.next(*step(g, *[t for t, _ in sides]))
+    g.output(sides[-1][1])
+    return g
+
+
+def sum_loop_program():
+    """result(n) = { i = n; acc = 0; while 0 < i: acc = acc + i; i = i - 1 } acc."""
+    s = _counting_loop("S", 2, lambda g, i, acc: (g.op("sub", i, g.const(1)), g.op("add", acc, i)))
+    r = Function("result", [INT], INT)
+    r.output(r.loop("S", r.param(0), r.const(0)))
+    return Program([r, s])
+
+
+def fib_loop_program():
+    """result(n) = { i = n; b = 1; a = 0; while 0 < i: (i, b, a) = (i - 1, a + b, b) } a."""
+    f = _counting_loop("F", 3, lambda g, i, b, a: (g.op("sub", i, g.const(1)), g.op("add", a, b), g.op("id", b)))
+    r = Function("result", [INT], INT)
+    r.output(r.loop("F", r.param(0), r.const(1), r.const(0)))
+    return Program([r, f])
+
+
+def gcd_loop_program():
+    """result(a,b) = { while a != b: if a < b then b = b - a else a = a - b } a  (a, b >= 1):
+    a conditional inside the loop body, and a trip count that depends on the data."""
+    g = Function("G", [INT, INT], INT)
+    a, b = g.param(0), g.param(1)
+    p = g.op("eq", g.op("eq", a, b), g.const(0))
+    a_t, a_f = g.switch(p, a)
+    b_t, _ = g.switch(p, b)
+    q = g.op("lt", a_t, b_t)
+    a_lt, a_ge = g.switch(q, a_t)
+    b_lt, b_ge = g.switch(q, b_t)
+    g.next(g.merge(g.op("id", a_lt), g.op("sub", a_ge, b_ge)),
+           g.merge(g.op("sub", b_lt, a_lt), g.op("id", b_ge)))
+    g.output(a_f)
+    r = Function("result", [INT, INT], INT)
+    r.output(r.loop("G", r.param(0), r.param(1)))
+    return Program([r, g])
+
+
+def nested_loop_program():
+    """result(n) = { i = n; acc = 0; while 0 < i: acc = acc + { j = i; c = 0; while 0 < j:
+    c = c + 1; j = j - 1 } c; i = i - 1 } acc: a loop in a loop body, tags two counters long."""
+    inner = _counting_loop("I", 2, lambda g, j, c: (g.op("sub", j, g.const(1)), g.op("add", c, g.const(1))))
+
+    def outer_step(g, i, acc):
+        c = g.loop("I", i, g.op("sub", i, i))
+        return g.op("sub", i, g.const(1)), g.op("add", acc, c)
+    outer = _counting_loop("O", 2, outer_step)
+    r = Function("result", [INT], INT)
+    r.output(r.loop("O", r.param(0), r.const(0)))
+    return Program([r, outer, inner])
+
+
+def loop_of_calls_program():
+    """result(n) = { i = n; acc = 0; while 0 < i: acc = acc + fib(i); i = i - 1 } acc: calls
+    from inside a loop body, call labels pushed on top of an iteration counter."""
+    fib = fib_program().functions["fib"]
+    s = _counting_loop("L", 2, lambda g, i, acc: (g.op("sub", i, g.const(1)), g.op("add", acc, g.call("fib", i))))
+    r = Function("result", [INT], INT)
+    r.output(r.loop("L", r.param(0), r.const(0)))
+    return Program([r, s, fib])
+
+
+def loop_in_function_program():
+    """result(n) = tet(n) ; tet(n) = if n < 1 then n - n else { the sum loop over n } +
+    tet(n - 1): a loop in the body of a recursive function, iteration counters pushed on top
+    of call labels; in the base case the loop's initial values are dead."""
+    s = _counting_loop("S", 2, lambda g, i, acc: (g.op("sub", i, g.const(1)), g.op("add", acc, i)))
+    f = Function("tet", [INT], INT)
+    n = f.param(0)
+    t, e = f.switch(f.op("lt", n, f.const(1)), n)
+    tri = f.loop("S", e, f.op("sub", e, e))
+    rec = f.call("tet", f.op("sub", e, f.const(1)))
+    f.output(f.merge(f.op("sub", t, t), f.op("add", tri, rec)))
+    r = Function("result", [INT], INT)
+    r.output(r.call("tet", r.param(0)))
+    return Program([r, f, s])
+
+
+def sum_recursive_program():
+    """result(n) = s(n, 0) ; s(i, acc) = if 0 < i then s(i - 1, acc + i) else acc: the sum loop
+    written as a tail recursion, for comparison (same values, tags as long as the trip count)."""
+    f = Function("s", [INT, INT], INT)
+    i, acc = f.param(0), f.param(1)
+    p = f.op("lt", f.const(0), i)
+    i_t, _ = f.switch(p, i)
+    a_t, a_f = f.switch(p, acc)
+    f.output(f.merge(f.call("s", f.op("sub", i_t, f.const(1)), f.op("add", a_t, i_t)), f.op("id", a_f)))
+    r = Function("result", [INT], INT)
+    r.output(r.call("s", r.param(0), r.op("sub", r.param(0), r.param(0))))
+    return Program([r, f])
