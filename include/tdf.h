@@ -6,7 +6,9 @@
  * gradient under shared call labels (Section 4).  tdf_eval / tdf_eval_grad execute the
  * static graph over a batch of instances: tokens carry call-context tags
  * (Call_i <t,d> = <i:t,d>, Return_i <i:t,d> = <t,d>), tokens are matched by tag, and a
- * node body fires over every matched tag of a step at once.
+ * node body fires over every matched tag of a step at once.  While-loops (tagged iteration,
+ * Section 2.3: Enter <t,d> = <0:t,d>, Next <n:t,d> = <(n+1):t,d>, Exit <n:t,d> = <t,d>) run on
+ * the same tags: iteration counters and call labels share one tag list (Section 5.1).
  *
  * Conventions
  *   - "device" pointers are HIP device memory on the current device, owned by the caller
@@ -46,9 +48,18 @@ typedef enum {
 
 /* ---- program description (host memory, read only during tdf_graph_build) ------------
  * Node operators.  The first group is the paper's language (Sections 2.2 and 2.4); the
- * TREE_* group reads the forest arrays of tdf_inputs at a node-index value; the last group
+ * TREE_* group reads the forest arrays of tdf_inputs at a node-index value; the next group
  * are vector-valued operators whose results live in the state table and travel through the
- * graph as row references.  */
+ * graph as row references; LOOP / NEXT write a while-loop (Section 2.3).
+ *
+ * A while-loop is a graph of its own, the loop graph: a tdf_function_desc with exactly one
+ * NEXT node.  Its IN nodes are the loop variables in the current iteration (the Merge nodes of
+ * the paper's while-loop figure, fed by Enter and Next), NEXT takes their values for the next
+ * iteration, OUT is the value that leaves the loop.  The program decides by SWITCHes on the loop
+ * condition which of the two is live: in every iteration exactly one of NEXT (all inputs) and
+ * OUT must be.  A LOOP node in another graph supplies the initial values and stands for the
+ * value that leaves.  Values of the enclosing graph that the loop reads are loop variables
+ * handed on unchanged.  A loop graph belongs to exactly one LOOP node.  */
 typedef enum {
   TDF_OP_IN = 0,      /* formal parameter; imm = parameter index                        */
   TDF_OP_OUT,         /* the function's single output; in[0] = value                    */
@@ -65,6 +76,8 @@ typedef enum {
   TDF_OP_RNN_CELL,    /* in[0], in[1] = child rows -> tanh(W [h_l; h_r] + b)            */
   TDF_OP_LSTM_CELL,   /* binary TreeLSTM, gate row blocks (i, f_l, f_r, o, u) of W      */
   TDF_OP_CE_HEAD,     /* in[0] = row, in[1] = label -> -log softmax(U h + u0)[label]    */
+  TDF_OP_LOOP,        /* imm = loop graph index; in[k] = initial value of loop variable k   */
+  TDF_OP_NEXT,        /* in a loop graph: in[k] = loop variable k in the next iteration     */
   TDF_OP_COUNT
 } tdf_op;
 
@@ -100,7 +113,9 @@ typedef struct {
  * device.  Host only.  Rejected with TDF_ERR_BAD_PROGRAM: undefined callee, arity
  * mismatch, forward reference, more or fewer than one OUT per function, an operator
  * whose inputs are all constants outside `result`, more than 64 nodes in a function, a
- * gradient request for a program without vector operators.  *out is owned by the library
+ * gradient request for a program without vector operators or with loops, a loop graph that
+ * is called, is `result`, has two NEXT nodes or belongs to no or several LOOP nodes, a LOOP
+ * over a graph without NEXT.  *out is owned by the library
  * until tdf_graph_destroy. */
 tdf_status tdf_graph_build(const tdf_program_desc* prog, int want_grad, tdf_graph** out);
 void tdf_graph_destroy(tdf_graph* g);
@@ -110,19 +125,22 @@ void tdf_graph_destroy(tdf_graph* g);
 #define TDF_SNODE_MERGE_ENTRY 100 /* Merge that replaced a callee's input node          */
 #define TDF_SNODE_CALL 101        /* Call_i for one formal parameter                    */
 #define TDF_SNODE_RETURN 102      /* Return_i                                           */
+#define TDF_SNODE_ENTER 103       /* Enter of one loop variable; label = number of the LOOP */
+#define TDF_SNODE_NEXT 104        /* Next of one loop variable                          */
+#define TDF_SNODE_EXIT 105        /* Exit; label = number of the LOOP                   */
 
 typedef struct {
   int32_t kind;    /* tdf_op or TDF_SNODE_*                                             */
   int32_t fn;      /* function graph the node came from                                 */
-  int32_t label;   /* call label i for CALL / RETURN, else -1                           */
-  int32_t param;   /* parameter index for CALL / MERGE_ENTRY / IN, else -1              */
+  int32_t label;   /* call label i for CALL / RETURN, the loop's number for ENTER / EXIT, else -1 */
+  int32_t param;   /* parameter index for CALL / MERGE_ENTRY / IN / ENTER / NEXT, else -1 */
   int32_t is_grad; /* 1 for nodes of the gradient half of a joint function              */
   int64_t imm;     /* CONST value                                                       */
 } tdf_snode;
 
 typedef struct {
   int32_t src, src_port, dst, dst_slot;
-  int32_t is_control; /* 1 for the Call_i -> Return_i synchronising edges               */
+  int32_t is_control; /* 1 for the Call_i -> Return_i (Enter -> Exit) synchronising edges */
 } tdf_sedge;
 
 typedef struct {
@@ -207,7 +225,7 @@ enum {
 };
 
 typedef struct {
-  int64_t n_tags;         /* call-context tags created = function invocations           */
+  int64_t n_tags;         /* tags created = function invocations + loop iterations      */
   int64_t n_steps;        /* match/fire steps of the tag machine                        */
   int64_t n_tokens;       /* Call and Return tokens delivered                           */
   int64_t n_leaf_rows;    /* EMBED firings                                              */
@@ -216,7 +234,7 @@ typedef struct {
   int64_t n_wide_waves;   /* ... of which the first this many ran one launch per level  */
   int64_t n_wide_cells;   /* cell firings in those levels                               */
   int64_t n_grad_firings; /* gradient-body firings (one per tag) in tdf_eval_grad       */
-  int64_t max_tag_depth;  /* longest list of call labels                                */
+  int64_t max_tag_depth;  /* longest list of call labels and iteration counters         */
   int64_t table_capacity; /* slots of the tag-hash table                                */
   int64_t max_probe;      /* longest probe sequence                                     */
   double phase_ms[TDF_PHASE_COUNT];        /* device time of each phase                */

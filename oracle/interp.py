@@ -374,7 +374,5 @@ class Interpreter:
                     name += "_grad"
             if nd.op in ("enter", "exit"):
                 name = "%s_%d" % (nd.op, nd.attr["label"])
-            if nd.op == "next":
-                name = "next_" + nd.fn
             out[name] = out.get(name, 0) + c
         return out

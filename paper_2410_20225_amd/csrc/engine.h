@@ -33,7 +33,11 @@ struct alignas(128) Ctrl {
 
 // Frame record = one slot of the tag-hash table = one call-context tag (Section 5.1: a
 // frame holds the label i of the Call_i that created it and a reference to the previous
-// scope).  The key packs (parent frame + 1, tag length, label + 1).  The keys of all slots
+// scope).  The key packs (parent frame + 1, iteration counter, label + 1): a tag of the paper
+// is (iteration number, pointer into the frame stack), and a loop scope is pushed on the same
+// stack as a function scope (Section 5.1).  Enter is the push of a scope with counter 0, so the
+// frame of a call is the frame of "iteration 0" of its label; Next keeps parent and label and
+// adds one to the counter; Exit pops like Return.  The keys of all slots
 // are also kept in a dense array of their own, which is what insertions probe (eight slots
 // per 64-byte line); the slot index is the frame id, so inserting a tag and allocating its
 // frame are one compare-and-swap.  The lane that inserts a key writes the frame's header;
@@ -45,10 +49,10 @@ struct alignas(128) Ctrl {
 // step and puts it on the next list.  Values delivered in one step are read in a later one, so
 // only key and arrived[] are ever accessed concurrently and need atomics.
 struct FrameHdr {
-  unsigned long long key;     // (parent + 1) << 32 | depth << 8 | (label + 1)
+  unsigned long long key;     // (parent + 1) << 32 | iteration << 8 | (label + 1)
   unsigned long long fired;   // firing-table entries that have fired live under this tag
   uint32_t present_fn;        // bits 0..23: stored values present; bits 24..31: function
-  uint32_t pad;
+  uint32_t depth;             // length of the tag: call labels and iteration counters below the root
   uint32_t arrived[2];        // same layout as present_fn, by parity of the consuming step
   // followed by int64 stored[n_stored]
 };

@@ -1,6 +1,7 @@
 // Host side of tdf_graph_build: validation, the transformation of a set of function graphs
-// into one static tagged graph (paper Section 3), the gradient half of the joint functions
-// (Section 4), and the compilation of the per-function firing tables used on the device.
+// into one static tagged graph (paper Section 3; while-loops: Section 2.3), the gradient half
+// of the joint functions (Section 4), and the compilation of the per-function firing tables
+// used on the device.
 #include <string.h>
 
 #include <map>
@@ -29,7 +30,7 @@ int arity_of(int op, int n_in) {
     case TDF_OP_TREE_RIGHT: case TDF_OP_TREE_TOKEN: case TDF_OP_EMBED: return 1;
     case TDF_OP_ADD: case TDF_OP_SUB: case TDF_OP_MUL: case TDF_OP_EQ: case TDF_OP_LT:
     case TDF_OP_SWITCH: case TDF_OP_RNN_CELL: case TDF_OP_LSTM_CELL: case TDF_OP_CE_HEAD: return 2;
-    case TDF_OP_MERGE: case TDF_OP_CALLFN: return n_in;
+    case TDF_OP_MERGE: case TDF_OP_CALLFN: case TDF_OP_LOOP: case TDF_OP_NEXT: return n_in;
   }
   return -1;
 }
@@ -40,7 +41,8 @@ struct Builder {
   Graph& G;
   std::vector<std::vector<int>> type;   // [fn][node] output type
   std::vector<int> ret_type;            // [fn]
-  std::map<std::pair<int, int>, int> label_of;   // (fn, node) -> call label
+  std::map<std::pair<int, int>, int> label_of;   // (fn, node) -> call label (LOOP nodes are numbered with the calls)
+  std::vector<int> is_loop;             // [fn] the graph has a NEXT node: a loop graph
 
   Builder(const tdf_program_desc* p, bool wg, Graph& g) : P(p), want_grad(wg), G(g) {}
 
@@ -52,9 +54,17 @@ struct Builder {
     if (!P || P->n_functions < 1 || !P->functions) bad("empty program");
     if (P->n_functions > MAX_FN) bad("too many functions");
     if (P->result_fn < 0 || P->result_fn >= P->n_functions) bad("result_fn out of range");
+    is_loop.assign(P->n_functions, 0);
+    std::vector<int> loop_users(P->n_functions, 0);
     for (int f = 0; f < P->n_functions; ++f) {
       const auto& fn = F(f);
       if (!fn.nodes || fn.n_nodes < 1) bad("function without nodes");
+      for (int i = 0; i < fn.n_nodes; ++i) is_loop[f] += fn.nodes[i].op == TDF_OP_NEXT;
+      if (is_loop[f] > 1) bad("a loop graph has exactly one NEXT");
+    }
+    if (is_loop[P->result_fn]) bad("result cannot be a loop graph");
+    for (int f = 0; f < P->n_functions; ++f) {
+      const auto& fn = F(f);
       if (fn.n_nodes > MAX_VALUES) bad("more than 64 nodes in a function");
       if (fn.n_params < 0 || fn.n_params > TDF_MAX_INPUTS) bad("a function has at most 4 parameters");
       int n_out = 0;
@@ -71,7 +81,7 @@ struct Builder {
           tdf_ref r = nd.in[k];
           if (r.node < 0 || r.node >= i) bad("input refers to a later node (or itself)");
           int sop = fn.nodes[r.node].op;
-          if (sop == TDF_OP_OUT) bad("OUT has no output");
+          if (sop == TDF_OP_OUT || sop == TDF_OP_NEXT) bad("OUT and NEXT have no output");
           if (r.port != 0 && !(r.port == 1 && sop == TDF_OP_SWITCH)) bad("bad port");
           n_const += sop == TDF_OP_CONST;
         }
@@ -85,15 +95,26 @@ struct Builder {
           if (nd.imm == P->result_fn) bad("result cannot be called");
           if (nd.n_in != F((int)nd.imm).n_params) bad("arity mismatch in a call");
           if (nd.n_in < 1) bad("a called function needs at least one parameter");
+          if (is_loop[nd.imm]) bad("a loop graph cannot be called");
         }
+        if (nd.op == TDF_OP_LOOP) {
+          if (nd.imm < 0 || nd.imm >= P->n_functions || !is_loop[nd.imm]) bad("LOOP over a graph without NEXT");
+          if (nd.n_in != F((int)nd.imm).n_params) bad("LOOP needs one initial value per loop variable");
+          if (want_grad) bad("gradient of a program with loops");
+          ++loop_users[nd.imm];
+        }
+        if (nd.op == TDF_OP_NEXT && (nd.n_in != fn.n_params || nd.n_in < 1)) bad("NEXT needs one value per loop variable");
         if (nd.op == TDF_OP_MERGE && n_const) bad("MERGE of a constant");
         if (nd.op == TDF_OP_SWITCH && is_const(f, nd.in[0])) bad("SWITCH on a constant predicate");
-        if (n_const > 1) bad("operator with two constant inputs: fold it");
+        const bool per_input = nd.op == TDF_OP_CALLFN || nd.op == TDF_OP_LOOP || nd.op == TDF_OP_NEXT;   // one table entry per input
+        if (n_const > 1 && !per_input) bad("operator with two constant inputs: fold it");
         if (nd.n_in > 0 && n_const == nd.n_in && f != P->result_fn)
           bad("operator fed by constants only outside result");
       }
       if (n_out != 1) bad("a function needs exactly one OUT");
     }
+    for (int f = 0; f < P->n_functions; ++f)
+      if (is_loop[f] && loop_users[f] != 1) bad("a loop graph belongs to exactly one LOOP node");
   }
 
   // ---- 2. types: int64 scalars, row references of vector operators, the head's loss ---
@@ -120,7 +141,8 @@ struct Builder {
             case TDF_OP_MERGE:
               for (int k = 0; k < nd.n_in; ++k) if (in_t(k) != T_UNKNOWN) t = in_t(k);
               break;
-            case TDF_OP_CALLFN: t = ret_type[nd.imm]; break;
+            case TDF_OP_CALLFN: case TDF_OP_LOOP: t = ret_type[nd.imm]; break;
+            case TDF_OP_NEXT: t = T_INT; break;   // no value; loop variables are integers
           }
           type[f][i] = t;
           if (nd.op == TDF_OP_OUT) ret_type[f] = t;
@@ -142,7 +164,9 @@ struct Builder {
           case TDF_OP_CE_HEAD: need(0, T_VEC); need(1, T_INT); break;
           case TDF_OP_SWITCH: need(0, T_INT); break;
           case TDF_OP_MERGE: for (int k = 0; k < nd.n_in; ++k) need(k, type[f][i]); break;
-          case TDF_OP_CALLFN: for (int k = 0; k < nd.n_in; ++k) need(k, T_INT); break;
+          case TDF_OP_CALLFN: case TDF_OP_LOOP: case TDF_OP_NEXT:
+            for (int k = 0; k < nd.n_in; ++k) need(k, T_INT);
+            break;
           default: break;
         }
         if (nd.op == TDF_OP_RNN_CELL || nd.op == TDF_OP_LSTM_CELL) {
@@ -172,7 +196,7 @@ struct Builder {
   void number_calls() {
     for (int f : fn_order())
       for (int i = 0; i < F(f).n_nodes; ++i)
-        if (F(f).nodes[i].op == TDF_OP_CALLFN) {
+        if (F(f).nodes[i].op == TDF_OP_CALLFN || F(f).nodes[i].op == TDF_OP_LOOP) {
           int lab = (int)label_of.size();
           label_of[{f, i}] = lab;
         }
@@ -201,8 +225,8 @@ struct Builder {
     for (int f : order)
       for (int i = 0; i < F(f).n_nodes; ++i) {
         const auto& nd = F(f).nodes[i];
-        if (nd.op == TDF_OP_CALLFN) continue;
-        if (nd.op == TDF_OP_OUT && f != P->result_fn) continue;   // absorbed by the Returns
+        if (nd.op == TDF_OP_CALLFN || nd.op == TDF_OP_LOOP || nd.op == TDF_OP_NEXT) continue;
+        if (nd.op == TDF_OP_OUT && f != P->result_fn) continue;   // absorbed by the Returns / the Exit
         int s;
         if (nd.op == TDF_OP_IN && f != P->result_fn) {
           s = add_snode(TDF_SNODE_MERGE_ENTRY, f, -1, (int)nd.imm, 0, 0);
@@ -218,11 +242,18 @@ struct Builder {
     for (int f : order)
       for (int i = 0; i < F(f).n_nodes; ++i) {
         const auto& nd = F(f).nodes[i];
-        if (nd.op != TDF_OP_CALLFN) continue;
-        int lab = label_of[{f, i}], callee = (int)nd.imm;
         std::vector<int> cs;
-        for (int k = 0; k < nd.n_in; ++k) cs.push_back(add_snode(TDF_SNODE_CALL, f, lab, k, 0, callee));
-        int r = add_snode(TDF_SNODE_RETURN, f, lab, -1, 0, callee);
+        if (nd.op == TDF_OP_NEXT) {   // Section 2.3: one Next per loop variable, feeding its Merge
+          for (int k = 0; k < nd.n_in; ++k) cs.push_back(add_snode(TDF_SNODE_NEXT, f, -1, k, 0, 0));
+          call_snodes[{f, i}] = cs;
+          continue;
+        }
+        if (nd.op != TDF_OP_CALLFN && nd.op != TDF_OP_LOOP) continue;
+        const bool loop = nd.op == TDF_OP_LOOP;   // Enter per loop variable and Exit, placed like Call_i and Return_i
+        int lab = label_of[{f, i}], callee = (int)nd.imm;
+        for (int k = 0; k < nd.n_in; ++k)
+          cs.push_back(add_snode(loop ? TDF_SNODE_ENTER : TDF_SNODE_CALL, f, lab, k, 0, callee));
+        int r = add_snode(loop ? TDF_SNODE_EXIT : TDF_SNODE_RETURN, f, lab, -1, 0, callee);
         call_snodes[{f, i}] = cs;
         smap[{f, i, 0}] = r;
       }
@@ -230,7 +261,14 @@ struct Builder {
     for (int f : order)
       for (int i = 0; i < F(f).n_nodes; ++i) {
         const auto& nd = F(f).nodes[i];
-        if (nd.op == TDF_OP_CALLFN) {
+        if (nd.op == TDF_OP_NEXT) {
+          const auto& cs = call_snodes[{f, i}];
+          for (int k = 0; k < nd.n_in; ++k) {
+            add_edge(smap[{f, nd.in[k].node, 0}], nd.in[k].port, cs[k], 0, 0);
+            auto it = entry.find({f, k});   // the Merge's slot after those of the labels
+            if (it != entry.end()) add_edge(cs[k], 0, it->second, G.n_labels, 0);
+          }
+        } else if (nd.op == TDF_OP_CALLFN || nd.op == TDF_OP_LOOP) {
           int lab = label_of[{f, i}], callee = (int)nd.imm;
           const auto& cs = call_snodes[{f, i}];
           int r = smap[{f, i, 0}];
@@ -380,9 +418,26 @@ struct Builder {
             I.src[slot] = (uint8_t)val.at({r.node, r.port});
           }
         };
-        int sn = nd.op == TDF_OP_CALLFN || (nd.op == TDF_OP_OUT && f != P->result_fn)
-                     ? -1 : smap.at({f, i, 0});
-        if (nd.op == TDF_OP_CALLFN) {
+        if (nd.op == TDF_OP_NEXT) {
+          const auto& cs = call_snodes[{f, i}];
+          for (int k = 0; k < nd.n_in; ++k) {
+            Instr C = I;
+            C.op = D_NEXT;
+            C.dst = (uint8_t)new_val();
+            C.aux2 = (uint8_t)k;
+            if (is_const(f, nd.in[k])) {
+              C.src[0] = SRC_IMM;
+              C.imm = fn.nodes[nd.in[k].node].imm;
+            } else {
+              C.src[0] = (uint8_t)val.at({nd.in[k].node, nd.in[k].port});
+            }
+            emit(C, cs[k]);
+          }
+          continue;
+        }
+        const bool is_call = nd.op == TDF_OP_CALLFN || nd.op == TDF_OP_LOOP;
+        int sn = is_call || (nd.op == TDF_OP_OUT && f != P->result_fn) ? -1 : smap.at({f, i, 0});
+        if (is_call) {
           int lab = label_of[{f, i}];
           const auto& cs = call_snodes[{f, i}];
           for (int k = 0; k < nd.n_in; ++k) {
@@ -451,7 +506,8 @@ struct Builder {
       D.fn[f].out_type = (uint8_t)ret_type[f];
       D.fn[f].n_params = (uint8_t)fn.n_params;
       int n_emit = 0;
-      for (int q = first; q < n_instr; ++q) n_emit += D.instr[q].op == D_CALL || D.instr[q].op == D_OUT;
+      for (int q = first; q < n_instr; ++q)
+        n_emit += D.instr[q].op == D_CALL || D.instr[q].op == D_OUT || D.instr[q].op == D_NEXT;
       D.fn[f].n_emit = (uint8_t)n_emit;
       int n_cl = 0;
       for (int q = first; q < n_instr && n_cl < 6; ++q)

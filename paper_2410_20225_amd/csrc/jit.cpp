@@ -149,6 +149,11 @@ struct Gen {
             << (0x80000000u | I.aux | ((uint32_t)I.aux2 << 8)) << "u, " << val(I, 0) << ");\n";
           o << "          live = on && " << pre(I, 0) << " && !" << ded(I, 0) << ";\n";
           break;
+        case D_NEXT:
+          o << "          sw_emit(x, on && " << pre(I, 0) << " && !" << ded(I, 0) << " && !(x.fired & " << bit << "), "
+            << (0xC0000000u | ((uint32_t)I.aux2 << 8)) << "u, " << val(I, 0) << ");\n";
+          o << "          live = on && " << pre(I, 0) << " && !" << ded(I, 0) << ";\n";
+          break;
         case D_OUT:
           o << "          const bool go = on && " << pre(I, 0) << " && !" << ded(I, 0) << " && !(x.fired & " << bit << ");\n";
           if (f == P.result_fn) o << "          sw_result(x, go, " << (int)I.aux << ", " << val(I, 0) << ");\n";

@@ -118,8 +118,9 @@ struct LaneCtx {
 };
 
 // ---- helpers shared by the interpreter and by generated sweeps ----------------------------------
-// The token emitted by a Call_i entry (meta = 0x80000000 | label | param << 8) or by the function
-// output (meta = 0: the Return token); delivered after the sweep.
+// The token emitted by a Call_i entry (meta = 0x80000000 | label | param << 8), by a Next entry
+// (meta = 0xC0000000 | variable << 8) or by the function output (meta = 0: the Return token, or
+// the Exit token of a loop graph); delivered after the sweep.
 __device__ __forceinline__ void sw_emit(LaneCtx& x, bool go, uint32_t meta, long long v) {
   if (go) {
     x.pend_val[x.n_pend * x.RB + x.tid] = v;
@@ -361,6 +362,12 @@ struct InterpSweep {
             live = on && a.p && !a.d;
             break;
           }
+          case D_NEXT: {
+            const Src a = src(0);
+            sw_emit(x, on && a.p && !a.d && !(x.fired & ibit), 0xC0000000u | ((uint32_t)I.aux2 << 8), a.v);
+            live = on && a.p && !a.d;
+            break;
+          }
           case D_OUT: {
             const Src a = src(0);
             const bool go = on && a.p && !a.d && !(x.fired & ibit);
@@ -403,8 +410,8 @@ struct InterpSweep {
 
 // A token emitted by a sweep, while it is being delivered.
 struct Emission {
-  bool has, is_call;
-  uint32_t target, slot, bits, callee;
+  bool has, is_call;   // is_call: the token opens or finds a frame by key (Call_i, Enter, Next)
+  uint32_t target, slot, bits, callee, depth;
   unsigned long long ckey, res;
   long long val;
 };
@@ -480,7 +487,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       key = ld_shared<kCoherent>(&h->key);
       x.fired = ld_shared<kCoherent>(&h->fired);
       const uint32_t pf = pf_in | arr;
-      depth = (uint32_t)(key >> 8) & 0xFFFFFFu;
+      depth = ld_shared<kCoherent>(&h->depth);
       x.present = pf & 0xFFFFFFu;
       x.myfn = (int)(pf >> 24);
     }
@@ -511,7 +518,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     const bool may_follow = kDirect && n <= e.follow_limit && (n == c->prev_count || (n < c->prev_count && n * 4u <= c->peak_count));
     for (int follow = 0;; ++follow) {
     bool has_next = false;
-    uint32_t nx_frame = 0, nx_bits = 0, nx_slot = 0;
+    uint32_t nx_frame = 0, nx_bits = 0, nx_slot = 0, nx_depth = 0;
     unsigned long long nx_key = 0;
     long long nx_val = 0;
 
@@ -531,8 +538,19 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
           m.is_call = (meta >> 31) != 0;
           if (m.is_call) {
             const uint32_t label = meta & 0xFFu, param = (meta >> 8) & 0xFFu;
-            m.callee = P.label_callee[label];
-            m.ckey = ((unsigned long long)(x.frame + 1u) << 32) | ((unsigned long long)(depth + 1u) << 8) | (label + 1u);
+            if ((meta >> 30) & 1u) {   // Next <n:t,d> = <(n+1):t,d>: same scope, same parent, counter + 1
+              m.callee = (uint32_t)x.myfn;
+              m.ckey = key + 0x100ull;
+              m.depth = depth;
+              if (((key >> 8) & 0xFFFFFFull) == 0xFFFFFFull) {   // the counter has 24 bits
+                raise(c, TDF_ERR_STEP_LIMIT);
+                m.has = false;
+              }
+            } else {                   // Call_i <t,d> = <i:t,d>, Enter <t,d> = <0:t,d>
+              m.callee = P.label_callee[label];
+              m.ckey = ((unsigned long long)(x.frame + 1u) << 32) | (label + 1u);
+              m.depth = depth + 1u;
+            }
             m.target = e.key_base + ((uint32_t)mix64(m.ckey) & e.part_mask);
             m.slot = param;
             m.bits = (1u << param) | (m.callee << 24);
@@ -651,17 +669,17 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               th->key = m.ckey;
               th->fired = 0;
               th->present_fn = m.bits;
-              th->pad = 0;
+              th->depth = m.depth;
               th->arrived[0] = 0;
               th->arrived[1] = 0;
               has_next = true;
-              nx_frame = m.target; nx_bits = m.bits; nx_slot = m.slot; nx_key = m.ckey; nx_val = m.val;
+              nx_frame = m.target; nx_bits = m.bits; nx_slot = m.slot; nx_key = m.ckey; nx_val = m.val; nx_depth = m.depth;
             } else if (inserted) {
               // a fresh frame: nobody else can reach it in this step, so its creator writes the header
               th->key = m.ckey;
               th->fired = 0;
               th->present_fn = 0;
-              th->pad = 0;
+              th->depth = m.depth;
               th->arrived[word ^ 1] = 0;
               // an atomic, not a store: further parameters of the same call follow with atomics on
               // this word in this very step, and only atomics on one address keep their order
@@ -687,7 +705,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
         cnt_tokens += (uint32_t)__popcll(__ballot(m.has));
         if (ins[q]) {
           mx_probe = probes[q] > mx_probe ? probes[q] : mx_probe;
-          mx_depth = depth + 1 > mx_depth ? depth + 1 : mx_depth;
+          mx_depth = em[q].depth > mx_depth ? em[q].depth : mx_depth;
         }
       }
     }
@@ -708,7 +726,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     x.present = nx_bits & 0xFFFFFFu;
     x.myfn = has_next ? (int)(nx_bits >> 24) : -1;
     key = nx_key;
-    depth = (uint32_t)(nx_key >> 8) & 0xFFFFFFu;
+    depth = nx_depth;
     x.n_pend = 0;
     x.tc_v = -1;
 #pragma unroll

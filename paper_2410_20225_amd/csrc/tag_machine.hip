@@ -21,6 +21,7 @@ __global__ void k_seed(DevProgram P, Engine e) {
   int np = P.fn[P.result_fn].n_params;
   for (int k = 0; k < np; ++k) s[k] = e.args[(size_t)b * e.n_args + k];
   h->key = 0;
+  h->depth = 0;
   h->fired = 0;
   h->present_fn = ((1u << np) - 1u) | ((uint32_t)P.result_fn << 24);
   h->arrived[0] = h->arrived[1] = 0;

@@ -23,11 +23,13 @@ enum DevOp : uint8_t {
   D_SWITCH,   // dst = true side, dst+1 = false side; src[0] = predicate, src[1] = data
   D_MERGE,
   D_CALL,     // Call_i for one parameter: src[0] = argument, aux = label, aux2 = parameter
+              // (also the Enter of one loop variable: it pushes iteration counter 0)
   D_OUT,      // function output: emits the Return token (or writes the program output)
   D_ISLEAF, D_LEFT, D_RIGHT, D_TOKEN,
   D_EMBED,    // aux = stored slot of the row reference
   D_CELL,     // aux = stored slot
   D_HEAD,     // aux = stored slot
+  D_NEXT,     // Next of one loop variable: src[0] = value, aux2 = variable
 };
 
 constexpr uint8_t SRC_IMM = 0xFF;   // source is the instruction's immediate
@@ -40,7 +42,7 @@ struct Instr {
 };
 static_assert(sizeof(Instr) == 16, "Instr must be 16 bytes");
 
-constexpr int MAX_FN = 4;
+constexpr int MAX_FN = 8;
 constexpr int MAX_INSTR = 176;
 constexpr int MAX_LABELS = 32;
 constexpr int MAX_VALUES = 64;   // per function

@@ -22,8 +22,8 @@ ERR_UNSUPPORTED = -7
 F32, BF16 = 0, 1
 (OP_IN, OP_OUT, OP_CONST, OP_ADD, OP_SUB, OP_MUL, OP_EQ, OP_LT, OP_ID, OP_SWITCH, OP_MERGE, OP_CALLFN,
  OP_TREE_ISLEAF, OP_TREE_LEFT, OP_TREE_RIGHT, OP_TREE_TOKEN, OP_EMBED, OP_RNN_CELL, OP_LSTM_CELL,
- OP_CE_HEAD) = range(20)
-SNODE_MERGE_ENTRY, SNODE_CALL, SNODE_RETURN = 100, 101, 102
+ OP_CE_HEAD, OP_LOOP, OP_NEXT) = range(22)
+SNODE_MERGE_ENTRY, SNODE_CALL, SNODE_RETURN, SNODE_ENTER, SNODE_NEXT, SNODE_EXIT = 100, 101, 102, 103, 104, 105
 MAX_INPUTS = 4
 STATS_MAX_COUNTS = 256
 PHASES = ("tags", "leaves", "levels", "cells_fwd", "head", "cells_bwd", "weight_grad", "embed_grad", "tail_fwd", "tail_bwd")

@@ -97,6 +97,12 @@ def fire_counts(graph, stats):
             name = "call_%d" % n["label"]
         elif n["kind"] == tdf.SNODE_RETURN:
             name = "return_%d" % n["label"]
+        elif n["kind"] == tdf.SNODE_ENTER:
+            name = "enter_%d" % n["label"]
+        elif n["kind"] == tdf.SNODE_EXIT:
+            name = "exit_%d" % n["label"]
+        elif n["kind"] == tdf.SNODE_NEXT:
+            name = "next"
         else:
             name = names[n["kind"]]
         out[name] = out.get(name, 0) + stats.fire_count[i]

@@ -126,3 +126,55 @@ def test_precompile_rejects_missing_arguments():
     g = tdf.graph_build(fns, r)
     with pytest.raises(tdf.TdfError):
         tdf.graph_precompile(g, "")
+
+
+_KIND_NAMES = {tdf.OP_IN: "in", tdf.OP_OUT: "out", tdf.OP_CONST: "const", tdf.OP_ADD: "add", tdf.OP_SUB: "sub",
+               tdf.OP_MUL: "mul", tdf.OP_EQ: "eq", tdf.OP_LT: "lt", tdf.OP_ID: "id", tdf.OP_SWITCH: "switch",
+               tdf.OP_MERGE: "merge", tdf.SNODE_MERGE_ENTRY: "merge_entry", tdf.SNODE_CALL: "call",
+               tdf.SNODE_RETURN: "return", tdf.SNODE_ENTER: "enter", tdf.SNODE_NEXT: "next", tdf.SNODE_EXIT: "exit"}
+
+
+@pytest.mark.parametrize("name", ["sum_loop", "fib_loop", "gcd_loop", "nested_loop", "loop_of_calls", "loop_in_function"])
+def test_static_graph_of_loops_is_the_oracles(name):
+    # Section 2.3, figure of the while-loop: Enter and Next feed the variables' Merges, Exit hangs
+    # on the value that leaves.  Same nodes and edges as the oracle's transformation.
+    import oracle
+    from oracle import programs as oprog
+    from collections import Counter
+    fns, r = getattr(programs, name)()
+    g = tdf.graph_build(fns, r)
+    info = tdf.graph_info(g)
+    nodes = info["nodes"]
+    got = Counter((_KIND_NAMES[nodes[e["src"]]["kind"]], _KIND_NAMES[nodes[e["dst"]]["kind"]],
+                   "control" if e["is_control"] else "data") for e in info["edges"])
+    sg = oracle.transform(getattr(oprog, name + "_program")())
+    want = Counter((sg.nodes[s].op, sg.nodes[d].op, kind) for s, d, kind in sg.edge_list())
+    assert got == want
+    assert Counter(_KIND_NAMES[n["kind"]] for n in nodes) == Counter(nd.op for nd in sg.nodes)
+    assert info["n_labels"] == len(sg.labels)
+    assert tdf.graph_precompile(g, "gfx950") > 0
+
+
+def test_malformed_loops_are_rejected():
+    T = tdf
+
+    def build(result_nodes, loop_nodes, n_vars=2, want_grad=False):
+        fns = [("result", 1, result_nodes), ("S", n_vars, loop_nodes)]
+        with pytest.raises(tdf.TdfError) as e:
+            tdf.graph_build(fns, 0, want_grad=want_grad)
+        assert e.value.status == tdf.ERR_BAD_PROGRAM
+
+    good_loop = programs.sum_loop()[0][1][2]
+    n, zero = (0, 0), (1, 0)
+    head = [(T.OP_IN, [], 0), (T.OP_CONST, [], 0)]
+    build(head + [(T.OP_CALLFN, [n, zero], 1), (T.OP_OUT, [(2, 0)], 0)], good_loop)        # a loop graph is called
+    build(head + [(T.OP_LOOP, [n], 1), (T.OP_OUT, [(2, 0)], 0)], good_loop)                # one initial value too few
+    build(head + [(T.OP_LOOP, [n, zero], 1), (T.OP_LOOP, [n, zero], 1), (T.OP_ADD, [(2, 0), (3, 0)], 0),
+                  (T.OP_OUT, [(4, 0)], 0)], good_loop)                                     # two LOOP nodes on one graph
+    build(head + [(T.OP_OUT, [n], 0)], good_loop)                                          # ... and none
+    no_next = [nd for nd in good_loop if nd[0] != T.OP_NEXT]
+    build(head + [(T.OP_LOOP, [n, zero], 1), (T.OP_OUT, [(2, 0)], 0)], no_next)            # LOOP over a graph without NEXT
+    two_next = good_loop[:-1] + [nd for nd in good_loop if nd[0] == T.OP_NEXT] + good_loop[-1:]
+    build(head + [(T.OP_LOOP, [n, zero], 1), (T.OP_OUT, [(2, 0)], 0)], two_next)           # two NEXT nodes
+    short_next = [(op, ins[:1], imm) if op == T.OP_NEXT else (op, ins, imm) for op, ins, imm in good_loop]
+    build(head + [(T.OP_LOOP, [n, zero], 1), (T.OP_OUT, [(2, 0)], 0)], short_next)         # NEXT without a value for a variable

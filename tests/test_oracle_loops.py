@@ -32,7 +32,7 @@ def test_the_three_equations_on_one_loop():
     assert not it.tags                                   # no call, no call-context tag
     c = it.count_by_op()
     assert c["enter_0"] == 2 and c["exit_0"] == 1        # one Enter per loop variable
-    assert c["next_S"] == 2 * 3                          # three live Next firings per variable
+    assert c["next"] == 2 * 3                          # three live Next firings per variable
     assert c["merge_entry"] == 2 * 4 and c["switch"] == 2 * 4 and c["lt"] == 4
     assert c["add"] == 3 and c["sub"] == 3               # the body is dead in the last iteration
 
