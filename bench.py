@@ -63,6 +63,14 @@ def cpu_baseline(cfg, budget_trees):
         dt = time.perf_counter() - t0
         return {"value": len(it.tags) / dt, "unit": "firings/s", "cores": 1, "kind": "oracle",
                 "sample": "fib(0..20), one batch, %d tags, %.1f s" % (len(it.tags), dt)}
+    if cfg == 6:
+        ab = make_config(6)["args"][:budget_trees]
+        it = oracle.Interpreter(oracle.transform(oprog.gcd_loop_program()))
+        t0 = time.perf_counter()
+        it.run({("in", 0): ab[:, 0].tolist(), ("in", 1): ab[:, 1].tolist()}, len(ab))
+        dt = time.perf_counter() - t0
+        return {"value": len(it.iter_tags) / dt, "unit": "firings/s", "cores": 1, "kind": "oracle",
+                "sample": "first %d instances of the workload, %d loop iterations, %.1f s" % (len(ab), len(it.iter_tags), dt)}
     c = make_config(cfg)
     F = c["forest"].subset(range(budget_trees))
     grad = c["grad"]
@@ -91,7 +99,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4: TreeLSTM forward+gradient)")
+    ap.add_argument("--config", type=int, default=4, help="workload 1..6 (default 4: TreeLSTM forward+gradient)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle's sample (0 = auto)")
     a = ap.parse_args()
@@ -113,6 +121,17 @@ def main():
         inp = tdf.make_inputs(21, args=args, n_args=1, max_tags=57291, stats_level=0)
         ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=dev)
         out = torch.zeros(21, dtype=torch.int64, device=dev)
+        step = lambda: tdf.eval(g, inp, ws, out_i64=out)[1]
+        passes, dtype, flops_fwd, cell = 1, "int64", 0.0, None
+    elif cfg == 6:
+        c = make_config(6)
+        fns, r = programs.gcd_loop()
+        g = tdf.graph_build(fns, r)
+        n_inst = len(c["args"])
+        args = torch.tensor(c["args"], dtype=torch.int64, device=dev).reshape(-1)
+        inp = tdf.make_inputs(n_inst, args=args, n_args=2, max_tags=c["max_tags"], stats_level=0)
+        ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=dev)
+        out = torch.zeros(n_inst, dtype=torch.int64, device=dev)
         step = lambda: tdf.eval(g, inp, ws, out_i64=out)[1]
         passes, dtype, flops_fwd, cell = 1, "int64", 0.0, None
     else:
@@ -171,7 +190,7 @@ def main():
                  "launches_per_step": launches[0] / a.steps, "traffic": measured_traffic(cfg, "steps")}
     roof_tags["frac"] = roof_tags["achieved"] / roof_tags["peak"]
     roof_tags["copy_kernel_GBps"] = copy_gbps   # measured read + write rate of a plain 1 GiB device copy
-    if cfg == 1:
+    if cfg in (1, 6):
         roof = roof_tags
     else:
         i_fwd, i_tail = tdf.PHASES.index("cells_fwd"), tdf.PHASES.index("tail_fwd")
@@ -201,10 +220,10 @@ def main():
                       "firings_per_step": firings, "n_steps_tag_machine": int(st.n_steps),
                       "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth)},
            "phase_ms": phase_ms, "roofline": roof}
-    if cfg != 1:
+    if cfg not in (1, 6):
         rec["roofline_tag_machine"] = roof_tags
     if not a.no_cpu_baseline:
-        trees = a.cpu_trees or {1: 0, 2: 256, 3: 1024, 4: 1024, 5: 2}[cfg]
+        trees = a.cpu_trees or {1: 0, 2: 256, 3: 1024, 4: 1024, 5: 2, 6: 2048}[cfg]
         rec["cpu_baseline"] = cpu_baseline(cfg, trees)
     print(json.dumps(rec))
 

@@ -16,7 +16,7 @@ from .trees import random_split_tree, left_chain_tree, complete_tree, build_fore
 
 BASE_SEED = 20225
 CONFIG_NAMES = {1: "fib_0_20", 2: "treernn_fp32_256", 3: "treernn_bf16_1024_grad",
-                4: "treelstm_bf16_4096_grad", 5: "treernn_bf16_deep_grad"}
+                4: "treelstm_bf16_4096_grad", 5: "treernn_bf16_deep_grad", 6: "gcd_loop_65536"}
 
 
 def round_to_bf16(x):
@@ -39,6 +39,12 @@ def make_config(cfg, n_trees=None, max_leaves=None, seed=None, vocab=None, hidde
     rng = SplitMix64((BASE_SEED if seed is None else seed) + cfg)
     if cfg == 1:
         return {"cfg": 1, "kind": "fib", "args": np.arange(0, 21, dtype=np.int64)}
+    if cfg == 6:
+        # while-loops with data-dependent trip counts: pairs (a, b) uniform in 1..1024 for the
+        # subtractive gcd loop; the caller provisions 64 tags (loop iterations) per instance
+        B = 65536 if n_trees is None else int(n_trees)
+        ab = np.stack([rng.fork(0).randint(1, 1024, B), rng.fork(1).randint(1, 1024, B)], 1).astype(np.int64)
+        return {"cfg": 6, "kind": "gcd_loop", "args": ab, "max_tags": 64 * B}
 
     if cfg == 2:
         B, lo, hi, V, H, bf16, cell = 256, 2, 50, 10000, 128, False, "rnn"
@@ -49,7 +55,7 @@ def make_config(cfg, n_trees=None, max_leaves=None, seed=None, vocab=None, hidde
     elif cfg == 5:
         B, lo, hi, V, H, bf16, cell = 128, 4096, 4096, 10000, 512, True, "rnn"
     else:
-        raise ValueError("cfg must be 1..5")
+        raise ValueError("cfg must be 1..6")
     B = B if n_trees is None else int(n_trees)
     hi = hi if max_leaves is None else int(max_leaves)
     lo = min(lo, hi)

@@ -64,3 +64,27 @@ def test_a_batch_of_loops_with_very_different_trip_counts():
     st, stats = tdf.eval(g, inp, ws, out_i64=out)
     assert out.cpu().tolist() == [n * (n + 1) // 2 for n in ns]      # the closed form the oracle is pinned to
     assert stats.n_tags == n_tags and stats.max_tag_depth == 1
+
+
+def test_workload_6_at_full_size():
+    # the benchmark's loop workload as the benchmark launches it: every output against math.gcd,
+    # the tag count against the trip counts of subtractive Euclid counted here
+    import math
+    from tdf_workloads import make_config
+    c = make_config(6)
+    ab = c["args"]
+    fns, r = programs.gcd_loop()
+    g = tdf.graph_build(fns, r)
+    t_args = torch.tensor(ab, dtype=torch.int64, device=DEV).reshape(-1)
+    inp = tdf.make_inputs(len(ab), args=t_args, n_args=2, max_tags=c["max_tags"], stats_level=0)
+    ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=DEV)
+    out = torch.full((len(ab),), -1, dtype=torch.int64, device=DEV)
+    st, stats = tdf.eval(g, inp, ws, out_i64=out)
+    assert out.cpu().tolist() == [math.gcd(int(a), int(b)) for a, b in ab]
+    trips = 0
+    for a, b in ab.tolist():
+        while a != b:
+            a, b = (a, b - a) if a < b else (a - b, b)
+            trips += 1
+        trips += 1
+    assert stats.n_tags == trips and stats.max_tag_depth == 1
