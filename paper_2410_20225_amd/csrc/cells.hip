@@ -105,15 +105,17 @@ struct GemmArgs {
   int save_gates;
 };
 
-constexpr int GEMM_THREADS = 256;
 constexpr int BM = 128;
 
-// Workgroup tile BM x BN, four waves as 2 x 2, each wave 64 rows x WN column blocks of 32.
-// One LDS stage of BK columns; the next stage travels global -> registers while the current
-// one is multiplied.  LSTM_FWD gives every wave the five gate blocks of the same 32 hidden
+// Workgroup tile BM x BN, NW waves as (NW/2) x 2, each wave 256/NW rows x WN column blocks of
+// 32.  One LDS stage of BK columns; the next stage travels global -> registers while the current
+// one is multiplied.  With eight waves a wave's accumulators fit half the register file, two
+// waves share a SIMD, and one multiplies while the other waits for LDS or memory.  LSTM_FWD gives every wave the five gate blocks of the same 32 hidden
 // units, so the gate epilogue needs no exchange between lanes.
-template <int DT, int MODE>
-__global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
+template <int DT, int MODE, int NW>
+__global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
+  constexpr int GEMM_THREADS = NW * 64;
+  constexpr int MB = 8 / NW;                     // 32-row blocks per wave
   typedef typename TypeOf<DT>::type T;
   typedef El<T> E;
   constexpr int WN = MODE == LSTM_FWD ? 5 : 2;   // 32-wide column blocks per wave
@@ -147,6 +149,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  const int wrow = wm * MB * 32;                 // the wave's first row in the tile
   const int m0 = mt * BM;
   int k_begin = 0, k_end = g.K;
   if (MODE == DW_SPLIT) {
@@ -196,15 +199,15 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
   _Pragma("unroll") for (int c = 0; c < B_CHUNKS; ++c)                                           \
     rb[c] = *reinterpret_cast<const u32x4*>(Bbase + b_off[c] + (K0));
 
-  f32x16 acc[2][WN];
+  f32x16 acc[MB][WN];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
     for (int j = 0; j < WN; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const T* tA = sA + (wm * 64 + (lane & 31)) * LDT;
+  const T* tA = sA + (wrow + (lane & 31)) * LDT;
   const T* tB = sB + (wn * WN * 32 + (lane & 31)) * LDT;
   if (k_begin < k_end) {
     TDF_LOAD_TILE(k_begin)
@@ -226,13 +229,13 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
     }
 #pragma unroll
     for (int ks = 0; ks < E::BK / E::MK; ++ks) {
-      typename E::Frag fa[2], fb[WN];
+      typename E::Frag fa[MB], fb[WN];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) fa[i] = E::frag(tA + i * 32 * LDT, ks, lane);
+      for (int i = 0; i < MB; ++i) fa[i] = E::frag(tA + i * 32 * LDT, ks, lane);
 #pragma unroll
       for (int j = 0; j < WN; ++j) fb[j] = E::frag(tB + j * 32 * LDT, ks, lane);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
         for (int j = 0; j < WN; ++j) acc[i][j] = E::mma(fa[i], fb[j], acc[i][j]);
     }
@@ -253,7 +256,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
   }
   __syncthreads();
   const int col = lane & 31;
-  auto row_of = [&](int i, int r) { return wm * 64 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); };
+  auto row_of = [&](int i, int r) { return wrow + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); };
   if constexpr (MODE == LSTM_FWD) {
     const int jb = nt * 2 + wn;
     if (jb * 32 < g.Hp) {
@@ -261,7 +264,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
       const float bi = g.bias[n], bfl = g.bias[g.Hp + n], bfr = g.bias[2 * g.Hp + n];
       const float bo = g.bias[3 * g.Hp + n], bu = g.bias[4 * g.Hp + n];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < MB; ++i) {
         float cl[16], cr[16];   // children's cell states: all loads in flight before any store
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -301,7 +304,7 @@ __global__ void __launch_bounds__(GEMM_THREADS) k_gemm(GemmArgs g) {
       float bias = 0.f;
       if (MODE == RNN_FWD) bias = g.bias[n];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) {
+      for (int i = 0; i < MB; ++i) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = row_of(i, r), m = m0 + row;
@@ -326,7 +329,19 @@ template <typename T, int MODE> size_t gemm_lds_bytes() {
   return (size_t)(BM + 2 * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
 }
 
-template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
+// Waves per workgroup of the tiled GEMM: TDF_GEMM_WAVES = 4 or 8; else 8 where a level's rows are
+// gathered or scattered (two waves per SIMD hide each other's waits), 4 for the dense split GEMM
+// of the weight gradients (fewer LDS reads per MFMA).
+static int gemm_waves(int mode) {
+  static const int w = [] {
+    const char* e = getenv("TDF_GEMM_WAVES");
+    return e ? atoi(e) : 0;
+  }();
+  if (w == 4 || w == 8) return w;
+  return mode == DW_SPLIT ? 4 : 8;
+}
+
+template <typename T, int MODE, int NW> void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
   if (g.M <= 0) return;
   g.n_tiles_n = n_tiles_n;
   const int n_mt = (g.M + BM - 1) / BM;
@@ -334,12 +349,17 @@ template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int 
   dim3 grid(MODE == DW_SPLIT ? 8 * n_mt * n_tiles_n * ((splits + 7) / 8) : (n_mt + 7) / 8 * 8 * n_tiles_n);
   static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
   if (!lds_opt_in) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE, NW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE>());
     lds_opt_in = true;
   }
   const size_t lds = gemm_lds_bytes<T, MODE>();
-  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE>), grid, dim3(GEMM_THREADS), lds, s, g);
+  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE, NW>), grid, dim3(NW * 64), lds, s, g);
+}
+
+template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
+  if (gemm_waves(MODE) == 4) launch_gemm_nw<T, MODE, 4>(g, n_tiles_n, splits, s);
+  else launch_gemm_nw<T, MODE, 8>(g, n_tiles_n, splits, s);
 }
 
 // ---- small levels ----------------------------------------------------------------------
