@@ -908,15 +908,30 @@ __global__ void k_reduce_dw(VecArgs v, float* dW, int splits) {
   }
 }
 
-// db[n] = sum_q Dz[q][n]: partial sums over 64 tags each come from the transpose of Dz
-// 16 columns per block; 16 groups of partials, each summed in chunk order, meet in LDS
-__global__ void k_db_final(VecArgs v, const float* part, int n_parts, float* db) {
+// db[n] = sum_q Dz[q][n]: partial sums over 64 tags each come from the transpose of Dz.  First
+// every run of DB_RUN partials is summed into its first row (64 columns per block, rows of 256
+// bytes, four groups of rows that meet in LDS in a fixed order), then the rows left are summed.
+constexpr int DB_RUN = 64;
+__global__ void __launch_bounds__(256) k_db_runs(VecArgs v, float* part, int n_parts) {
+  __shared__ float red[4][64];
+  const int c = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int np = blockIdx.x * 64 + c;
+  const int p0 = blockIdx.y * DB_RUN, p1 = min(n_parts, p0 + DB_RUN);
+  float s = 0.f;
+  if (np < v.Np)
+    for (int p = p0 + grp; p < p1; p += 4) s += part[(size_t)p * v.Np + np];
+  red[grp][c] = s;
+  __syncthreads();   // every row of the run has been read before its first row is overwritten
+  if (grp == 0 && np < v.Np) part[(size_t)p0 * v.Np + np] = (red[0][c] + red[1][c]) + (red[2][c] + red[3][c]);
+}
+// 16 columns per block; 16 groups of partials (every `stride`-th row), each summed in order, meet in LDS
+__global__ void k_db_final(VecArgs v, const float* part, int n_parts, int stride, float* db) {
   __shared__ float red[16][17];
   const int c = threadIdx.x & 15, grp = threadIdx.x >> 4;
   const int np = blockIdx.x * 16 + c;
   float s = 0.f;
   if (np < v.Np)
-    for (int p = grp; p < n_parts; p += 16) s += part[(size_t)p * v.Np + np];
+    for (int p = grp; p < n_parts; p += 16) s += part[(size_t)p * stride * v.Np + np];
   red[grp][c] = s;
   __syncthreads();
   if (grp == 0 && np < v.Np) {
@@ -1168,7 +1183,8 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   launch_gemm<T, DW_SPLIT>(g, (v.Kp + 127) / 128, splits, s);
   hipLaunchKernelGGL(k_reduce_dw, dim3(512), dim3(256), 0, s, v, dW, splits);
   const int parts = (int)(v.q_stride / 64);   // written by the transpose of Dz above
-  hipLaunchKernelGGL(k_db_final, dim3((v.Np + 15) / 16), dim3(256), 0, s, v, db_part, parts, db);
+  hipLaunchKernelGGL(k_db_runs, dim3((v.Np + 63) / 64, (parts + DB_RUN - 1) / DB_RUN), dim3(256), 0, s, v, db_part, parts);
+  hipLaunchKernelGGL(k_db_final, dim3((v.Np + 15) / 16), dim3(256), 0, s, v, db_part, (parts + DB_RUN - 1) / DB_RUN, DB_RUN, db);
 }
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {
   if (v.dtype == TDF_BF16) weight_grads_t<__bf16>(v, e, n_q, dW, db, db_part, s);

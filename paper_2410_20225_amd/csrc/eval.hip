@@ -480,7 +480,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         HIP_TRY(hipMemsetAsync(grads->dW, 0, sizeof(float) * (size_t)v.N * 2 * v.H, s));
         HIP_TRY(hipMemsetAsync(grads->db, 0, sizeof(float) * (size_t)v.N, s));
       }
-      end(TDF_PHASE_WEIGHT_GRAD, 6);
+      end(TDF_PHASE_WEIGHT_GRAD, 7);
       HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->join_event, 0));
     }
     HIP_TRY(hipGetLastError());
