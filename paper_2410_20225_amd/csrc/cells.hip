@@ -1159,9 +1159,14 @@ void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c,
   else hipLaunchKernelGGL(k_out_rows<TDF_F32>, dim3(e.n_inst), dim3(128), 0, s, v, e, out_h, out_c);
 }
 
-int vec_dw_splits(uint32_t q_stride) {
-  int s = (int)((q_stride + 4095) / 4096);
-  return s < 1 ? 1 : (s > 64 ? 64 : s);
+// Splits of the reduction over the tags in the weight-gradient GEMM: enough for about 640
+// workgroups, at least 1024 tags each, at most 64 (every split writes a partial dW that the
+// ordered reduction reads again).
+int vec_dw_splits(uint32_t q_stride, int Np, int Kp) {
+  const int tiles = ((Np + BM - 1) / BM) * ((Kp + 127) / 128);
+  const int want = (640 + tiles - 1) / tiles;
+  const int most = (int)std::min<uint32_t>(64u, q_stride / 1024u);
+  return std::max(1, std::min(want, most));
 }
 
 template <typename T> static void weight_grads_t(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db,
@@ -1172,7 +1177,7 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
                      v.DzT, db_part);
   hipLaunchKernelGGL((k_transpose<DtOf<T>::value, true>), dim3(v.q_stride / 64, v.Kp / 64), tb, 0, s, v, e, n_q, v.Kp,
                      v.XT, (float*)nullptr);
-  const int splits = vec_dw_splits(v.q_stride);
+  const int splits = vec_dw_splits(v.q_stride, v.Np, v.Kp);
   int kps = (int)((v.q_stride / 64 + splits - 1) / splits) * 64;
   GemmArgs g{};
   g.M = v.Np; g.N = v.Kp; g.K = (int)v.q_stride;

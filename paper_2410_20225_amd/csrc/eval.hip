@@ -33,7 +33,7 @@ void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, 
 void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s);
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s);
 void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s);
-int vec_dw_splits(uint32_t q_stride);
+int vec_dw_splits(uint32_t q_stride, int Np, int Kp);
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s);
 void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t* count, uint32_t* seg_off,
                     uint32_t* chunk_off, uint32_t* fill, uint32_t* sorted_row, float* part, float* dE,
@@ -222,7 +222,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       size_t off_XT = L.take((size_t)v.Kp * v.q_stride * el);
       size_t off_WpT = L.take((size_t)v.Np * v.Kp * el);
       size_t off_WfT = L.take((size_t)v.Np * v.Kp * el);
-      size_t off_part = L.take((size_t)vec_dw_splits(v.q_stride) * v.Np * v.Kp * 4);
+      size_t off_part = L.take((size_t)vec_dw_splits(v.q_stride, v.Np, v.Kp) * v.Np * v.Kp * 4);
       P.off_db_part = L.take(((size_t)P.max_cells / DB_CHUNK + 2) * v.Np * 4);
       P.off_seg_off = L.take(4 * ((size_t)v.vocab + 2));
       P.off_chunk_off = L.take(4 * ((size_t)v.vocab + 2));
