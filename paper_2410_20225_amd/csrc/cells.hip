@@ -951,35 +951,44 @@ __global__ void k_tok_hist(Engine e, uint32_t n_leaf, uint32_t* count, int vocab
   }
 }
 // single block: exclusive scans of the per-token leaf counts and chunk counts
-__global__ void k_tok_scan(const uint32_t* count, uint32_t* seg_off, uint32_t* chunk_off, int vocab, uint32_t chunk) {
-  __shared__ uint32_t carry[2];
-  __shared__ uint32_t bufa[1024], bufb[1024];
-  if (threadIdx.x == 0) carry[0] = carry[1] = 0;
+__global__ void __launch_bounds__(1024) k_tok_scan(const uint32_t* count, uint32_t* seg_off, uint32_t* chunk_off, int vocab,
+                                                   uint32_t chunk) {
+  // entries 0 .. vocab (one past the end holds the totals); every thread owns a run of consecutive
+  // entries, the runs' sums are scanned over the block (waves by shuffles, wave totals in LDS)
+  __shared__ uint32_t wsum[2][16];
+  const int per = (vocab + 1 + 1023) / 1024;
+  const int lo = threadIdx.x * per, hi = min(lo + per, vocab + 1);
+  uint32_t sa = 0, sb = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t a = i < vocab ? count[i] : 0;
+    sa += a;
+    sb += (a + chunk - 1) / chunk;
+  }
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t ia = sa, ib = sb;   // inclusive scan inside the wave
+  for (int off = 1; off < 64; off <<= 1) {
+    const uint32_t ta = __shfl_up(ia, off), tb = __shfl_up(ib, off);
+    if (lane >= off) {
+      ia += ta;
+      ib += tb;
+    }
+  }
+  if (lane == 63) {
+    wsum[0][wave] = ia;
+    wsum[1][wave] = ib;
+  }
   __syncthreads();
-  for (int base = 0; base <= vocab; base += 1024) {
-    const int i = base + threadIdx.x;
-    const uint32_t a = i < vocab ? count[i] : 0, b = (a + chunk - 1) / chunk;
-    bufa[threadIdx.x] = a;
-    bufb[threadIdx.x] = b;
-    __syncthreads();
-    for (int off = 1; off < 1024; off <<= 1) {
-      const uint32_t ta = threadIdx.x >= (unsigned)off ? bufa[threadIdx.x - off] : 0;
-      const uint32_t tb = threadIdx.x >= (unsigned)off ? bufb[threadIdx.x - off] : 0;
-      __syncthreads();
-      bufa[threadIdx.x] += ta;
-      bufb[threadIdx.x] += tb;
-      __syncthreads();
-    }
-    if (i <= vocab) {
-      seg_off[i] = carry[0] + bufa[threadIdx.x] - a;
-      chunk_off[i] = carry[1] + bufb[threadIdx.x] - b;
-    }
-    __syncthreads();
-    if (threadIdx.x == 1023) {
-      carry[0] += bufa[1023];
-      carry[1] += bufb[1023];
-    }
-    __syncthreads();
+  uint32_t ba = ia - sa, bb = ib - sb;   // exclusive prefix of this thread's run
+  for (int w = 0; w < wave; ++w) {
+    ba += wsum[0][w];
+    bb += wsum[1][w];
+  }
+  for (int i = lo; i < hi; ++i) {
+    const uint32_t a = i < vocab ? count[i] : 0;
+    seg_off[i] = ba;
+    chunk_off[i] = bb;
+    ba += a;
+    bb += (a + chunk - 1) / chunk;
   }
 }
 __global__ void k_tok_scatter(Engine e, uint32_t n_leaf, const uint32_t* seg_off, uint32_t* fill,
@@ -1014,21 +1023,44 @@ __global__ void k_de_partial(VecArgs v, const uint32_t* seg_off, const uint32_t*
     const uint32_t p_hi = min(seg_off[lo + 1], p_lo + chunk);
     for (int n = lane * 4; n < v.Hp; n += 256) {
       float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-      for (uint32_t p = p_lo; p < p_hi; ++p) {
-        const float4 x = *reinterpret_cast<const float4*>(v.dH + (size_t)sorted_row[p] * v.Hp + n);
-        s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+      for (uint32_t p = p_lo; p < p_hi; p += 8) {   // eight rows in flight, added in leaf order
+        uint32_t row[8];
+        float4 x[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) row[j] = sorted_row[min(p + j, p_hi - 1)];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) x[j] = *reinterpret_cast<const float4*>(v.dH + (size_t)row[j] * v.Hp + n);
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+          if (p + j < p_hi) {
+            s.x += x[j].x; s.y += x[j].y; s.z += x[j].z; s.w += x[j].w;
+          }
       }
       *reinterpret_cast<float4*>(part + (size_t)c * v.Hp + n) = s;
     }
   }
 }
-__global__ void k_de_final(VecArgs v, const uint32_t* chunk_off, const float* part, float* dE) {
-  const int tok = blockIdx.x;
+// one wave per token: the token's chunk sums, added in chunk order; rows of tokens without a
+// leaf are written as zeros
+__global__ void __launch_bounds__(256) k_de_final(VecArgs v, const uint32_t* chunk_off, const float* part, float* dE) {
+  const int tok = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (tok >= v.vocab) return;
   const uint32_t c_lo = chunk_off[tok], c_hi = chunk_off[tok + 1];
-  for (int n = threadIdx.x; n < v.H; n += blockDim.x) {
-    float s = 0.f;
-    for (uint32_t c = c_lo; c < c_hi; ++c) s += part[(size_t)c * v.Hp + n];
-    dE[(size_t)tok * v.H + n] = s;
+  if ((v.H & 3) == 0) {
+    for (int n = lane * 4; n < v.H; n += 256) {
+      float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+      for (uint32_t c = c_lo; c < c_hi; ++c) {
+        const float4 x = *reinterpret_cast<const float4*>(part + (size_t)c * v.Hp + n);
+        s.x += x.x; s.y += x.y; s.z += x.z; s.w += x.w;
+      }
+      *reinterpret_cast<float4*>(dE + (size_t)tok * v.H + n) = s;
+    }
+  } else {
+    for (int n = lane; n < v.H; n += 64) {
+      float s = 0.f;
+      for (uint32_t c = c_lo; c < c_hi; ++c) s += part[(size_t)c * v.Hp + n];
+      dE[(size_t)tok * v.H + n] = s;
+    }
   }
 }
 
@@ -1218,7 +1250,7 @@ void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t
   const uint32_t max_chunks = n_leaf / chunk + std::min<uint32_t>((uint32_t)v.vocab, n_leaf) + 1;
   hipLaunchKernelGGL(k_de_partial, dim3(std::min<uint32_t>((max_chunks + 3) / 4, 16384u)), dim3(256), 0, s, v, seg_off,
                      chunk_off, sorted_row, chunk, part);
-  hipLaunchKernelGGL(k_de_final, dim3(v.vocab), dim3(128), 0, s, v, chunk_off, part, dE);
+  hipLaunchKernelGGL(k_de_final, dim3((v.vocab + 3) / 4), dim3(256), 0, s, v, chunk_off, part, dE);
 }
 
 }  // namespace tdf
