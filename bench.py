@@ -27,8 +27,8 @@ COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 # profiles/bench_workload4_hbm_traffic.md), with the hash of the kernel source they were taken on:
 # reported as `traffic` only while that source is unchanged.
 MEASURED_TRAFFIC = {
-    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "121d91d0d2110eb1", 2228715124.3),
-        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "fabaa146e1a56d88", 369899053.7)},
+    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "f187cbf4760121e6", 2236492276.4),
+        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "c0960f1cfed63112", 358262792.8)},
 }
 
 
