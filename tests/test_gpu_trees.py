@@ -94,3 +94,39 @@ def test_state_rows_exhausted_is_reported():
     st, stats = run.run(check=False)
     from paper_2410_20225_amd import tdf
     assert st == tdf.ERR_TABLE_FULL
+
+
+@pytest.mark.parametrize("cfg,ids", [
+    (3, [0, 5, 77, 500, 901, 1023]),                  # TreeRNN, 1024 trees, H = 300
+    (4, [0, 7, 513, 1024, 2047, 3000, 3333, 4095]),   # TreeLSTM, 4096 trees
+    (5, [3, 100]),                                    # a left chain and a complete tree of 4096 leaves
+])
+def test_full_size_workload_on_sampled_trees(cfg, ids):
+    # The workload at the size and in the launch configuration the benchmark times.  The oracle
+    # cannot run all of it, but trees are independent: with dy zero outside a sample, the weight,
+    # bias and embedding gradients of the whole batch are those of the sample alone, and the
+    # sample's losses are the oracle's.
+    c = make_config(cfg)
+    F = c["forest"]
+    B = F.n_trees
+    dy = np.zeros(B)
+    dy[ids] = 1.0 / len(ids)
+    run = TreeRun(c, head=True, grad=True, stats_level=0)
+    st, stats = run.run(dy)
+    assert stats.n_tags == F.n_nodes
+    L = int(F.n_leaves.sum())
+    assert stats.n_leaf_rows == L and stats.n_cell_rows == L - B
+    assert stats.max_tag_depth == int(F.n_leaves.max()) if cfg == 5 else stats.max_tag_depth >= 2
+    sub = dict(c)
+    sub["forest"] = F.subset(ids)
+    sub["labels"] = c["labels"][ids]
+    ref = run_oracle_tree(sub, head=True, grad=True, dy=dy[ids])
+    assert rel_fro(run.out_f32.cpu().numpy()[ids], np.array(ref["out"])) < BF16_TOL
+    assert rel_fro(run.dW.cpu().numpy(), ref["grads"]["dW"]) < BF16_TOL
+    assert rel_fro(run.db.cpu().numpy(), ref["grads"]["db"]) < BF16_TOL
+    dE, dE_ref = run.dE.cpu().numpy(), ref["grads"]["dE"]
+    assert rel_fro(dE, dE_ref) < BF16_TOL
+    untouched = np.ones(c["V"], bool)
+    untouched[np.unique(sub["forest"].token[sub["forest"].token >= 0])] = False
+    assert not dE_ref[untouched].any()
+    assert np.abs(dE[untouched]).max() == 0.0          # rows of tokens outside the sample: exactly zero
