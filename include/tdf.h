@@ -59,7 +59,10 @@ typedef enum {
  * condition which of the two is live: in every iteration exactly one of NEXT (all inputs) and
  * OUT must be.  A LOOP node in another graph supplies the initial values and stands for the
  * value that leaves.  Values of the enclosing graph that the loop reads are loop variables
- * handed on unchanged.  A loop graph belongs to exactly one LOOP node.  */
+ * handed on unchanged.  A loop graph belongs to exactly one LOOP node.  Every iteration is a tag
+ * of its own and counts against max_tags; one loop instance runs at most 2^24 iterations
+ * (TDF_ERR_STEP_LIMIT beyond); a loop that never leaves ends with TDF_ERR_TABLE_FULL or
+ * TDF_ERR_STEP_LIMIT like a recursion without a base case.  */
 typedef enum {
   TDF_OP_IN = 0,      /* formal parameter; imm = parameter index                        */
   TDF_OP_OUT,         /* the function's single output; in[0] = value                    */

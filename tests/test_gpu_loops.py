@@ -88,3 +88,27 @@ def test_workload_6_at_full_size():
             trips += 1
         trips += 1
     assert stats.n_tags == trips and stats.max_tag_depth == 1
+
+
+def test_a_loop_that_never_leaves_is_reported():
+    # while 0 < i: i = i + 1, started at 1: the table fills up, the run ends with an error status
+    T = tdf
+    loop = [(T.OP_IN, [], 0), (T.OP_CONST, [], 0), (T.OP_LT, [(1, 0), (0, 0)], 0), (T.OP_SWITCH, [(2, 0), (0, 0)], 0),
+            (T.OP_CONST, [], 1), (T.OP_ADD, [(3, 0), (4, 0)], 0), (T.OP_NEXT, [(5, 0)], 0), (T.OP_OUT, [(3, 1)], 0)]
+    res = [(T.OP_IN, [], 0), (T.OP_LOOP, [(0, 0)], 1), (T.OP_OUT, [(1, 0)], 0)]
+    g = tdf.graph_build([("result", 1, res), ("W", 1, loop)], 0)
+    t_args = torch.tensor([1, 5, 0, 1], dtype=torch.int64, device=DEV)
+    inp = tdf.make_inputs(4, args=t_args, n_args=1, max_tags=3000)
+    ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=DEV)
+    out = torch.full((4,), -1, dtype=torch.int64, device=DEV)
+    st, stats = tdf.eval(g, inp, ws, out_i64=out, check=False)
+    assert st == tdf.ERR_TABLE_FULL and stats.device_status == tdf.ERR_TABLE_FULL
+    inp = tdf.make_inputs(4, args=t_args, n_args=1, max_tags=100000, step_limit=50)
+    ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=DEV)
+    st, stats = tdf.eval(g, inp, ws, out_i64=out, check=False)
+    assert st in (tdf.ERR_STEP_LIMIT, tdf.ERR_TABLE_FULL)
+    t_args = torch.tensor([0, -3, 0, 0], dtype=torch.int64, device=DEV)      # these leave at once
+    inp = tdf.make_inputs(4, args=t_args, n_args=1, max_tags=64)
+    ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=DEV)
+    st, stats = tdf.eval(g, inp, ws, out_i64=out)
+    assert out.cpu().tolist() == [0, -3, 0, 0] and stats.n_tags == 4
