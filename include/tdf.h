@@ -18,6 +18,11 @@
  *   - Work is enqueued on the caller's HIP stream.  The evaluation calls synchronise that
  *     stream before returning (the step count of a recursion is data dependent and is
  *     read back).
+ *   - The functions may be called from several threads.  Evaluations take turns inside the
+ *     library even when their streams differ: the persistent kernels of one evaluation need
+ *     the whole GPU.  Other work of the caller on other streams of the same GPU should not
+ *     hold compute units for long while an evaluation runs (the evaluation's bounded waits
+ *     would end it with TDF_ERR_DEVICE).
  *   - Every function returns a tdf_status; a message for the last failure on the calling
  *     thread is available from tdf_last_error().  No exception crosses the ABI.
  */

@@ -2,6 +2,7 @@
 // the level-by-level execution of the cell firings, and the reversed schedule of the
 // gradient pass.
 #include <algorithm>
+#include <mutex>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
@@ -568,13 +569,21 @@ extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* i
   return TDF_OK;
 }
 
+// The step kernels and the tail launches are persistent: their workgroups wait for each other at
+// barriers, so all of them must be on the GPU together.  Two evaluations in flight on different
+// streams could each hold a part of the compute units and wait for the rest (the bounded waits
+// would end that with TDF_ERR_DEVICE, not a hang): evaluations of one process take turns.
+static std::mutex g_eval_mutex;
+
 extern "C" tdf_status tdf_eval(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* workspace,
                                size_t workspace_bytes, void* hip_stream, tdf_stats* stats) {
+  std::lock_guard<std::mutex> lock(g_eval_mutex);
   return run(g, in, nullptr, out, nullptr, workspace, workspace_bytes, hip_stream, stats, false);
 }
 
 extern "C" tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out,
                                     tdf_grads* grads, void* workspace, size_t workspace_bytes,
                                     void* hip_stream, tdf_stats* stats) {
+  std::lock_guard<std::mutex> lock(g_eval_mutex);
   return run(g, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, true);
 }

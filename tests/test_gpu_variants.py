@@ -137,3 +137,37 @@ def test_chains_leaning_either_way(follow, monkeypatch):
     want = ref["it"].count_by_op()
     for k in ("merge_entry", "isleaf", "switch", "call_0", "call_1", "return_0", "return_1"):
         assert got[k] == want[k], k
+
+
+def test_evaluations_from_several_threads_take_turns(lstm_case):
+    # Four host threads, each with its own graph, workspace and stream, evaluate at the same time.
+    # The persistent kernels of one evaluation need the whole GPU, so the library lets one
+    # evaluation run at a time; every call must succeed and give the oracle's result.
+    import threading
+    c, dy, ref = lstm_case
+    n = 4
+    streams = [torch.cuda.Stream() for _ in range(n)]
+    runs, errors = [], []
+    for s in streams:
+        with torch.cuda.stream(s):
+            runs.append(TreeRun(c, head=True, grad=True))
+
+    def worker(i):
+        try:
+            with torch.cuda.stream(streams[i]):
+                for _ in range(3):
+                    st, stats = runs[i].run(dy)
+                    assert st == tdf.OK and stats.n_tags == c["forest"].n_nodes
+        except Exception as ex:          # noqa: BLE001 -- reported below, from the main thread
+            errors.append(repr(ex))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(n)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for r in runs:
+        assert rel_fro(r.dW.cpu().numpy(), ref["grads"]["dW"]) < 2e-2
+        assert rel_fro(r.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
