@@ -329,6 +329,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   }
   const bool use_jit = gr->jit.step && gr->jit.small && gr->jit.step_local;
   const int small_block = tag_machine_small_block(G.prog, use_jit);
+  const int test_mixed_dies = getenv("TDF_TEST_MIXED_DIES") ? atoi(getenv("TDF_TEST_MIXED_DIES")) : 0;
   Ctrl hc{};
   uint32_t rounds = 0;
   const uint32_t poll = 2;          // rounds queued between two looks at the control blocks
@@ -385,7 +386,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     // A die-local machine relies on its workgroups sharing one L2.  If the GPU placed them on
     // several dies, the run is void: repeat it with the kernel that synchronises through memory.
-    if (gr->die_local && mixed_dies) {
+    // (TDF_TEST_MIXED_DIES=1 makes the host take this way once per graph, for the tests.)
+    if (gr->die_local && (mixed_dies || test_mixed_dies == 1)) {
       gr->die_local = false;
       continue;
     }
@@ -494,6 +496,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         mixed = mixed || (d.xcc_mask & (d.xcc_mask - 1)) != 0;
         gave_up = gave_up || d.abort != 0;
       }
+      mixed = mixed || test_mixed_dies == 2;   // TDF_TEST_MIXED_DIES=2: the tail launches' way, for the tests
       if (gave_up && !mixed) {
         set_error("device: a workgroup waited too long at a die barrier of the level tail");
         return TDF_ERR_DEVICE;
