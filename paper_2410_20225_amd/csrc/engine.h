@@ -27,7 +27,7 @@ struct alignas(128) Ctrl {
   uint32_t xcc_mask;         // accelerator dies that ran a die-local grid-wide step kernel
   uint32_t prev_count;       // frames of the previous step
   uint32_t peak_count;       // ... and of the largest step so far
-  uint32_t pad0;
+  uint32_t same_steps;       // steps in a row, before this one, with exactly as many frames as their predecessor
   unsigned long long n_tags, n_tokens;
 };
 

@@ -510,12 +510,13 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     // others, so the descent that gets shorter is the one along first calls (f(n-1) of fib, the
     // left spine of a tree).  While the machine's steps still grow, all descents advance together
     // one call per step anyway and a long sweep would only hold the others up: lanes follow only
-    // in a step with exactly as many frames as the step before (chains descending side by side)
-    // or with fewer, once the steps are down to a quarter of the machine's largest (the tail of
-    // a batch, where the deep stragglers decide the number of steps).  Bounded, so that a
+    // in a step with exactly as many frames as the two steps before (chains descending side by
+    // side) or with fewer, once the steps are down to a quarter of the machine's largest (the tail
+    // of a batch, where the deep stragglers decide the number of steps).  Bounded, so that a
     // recursion without a base case still meets the step limit.
     constexpr int FOLLOW_DEPTH = 256;
-    const bool may_follow = kDirect && n <= e.follow_limit && (n == c->prev_count || (n < c->prev_count && n * 4u <= c->peak_count));
+    const bool may_follow = kDirect && n <= e.follow_limit &&
+                            ((n == c->prev_count && c->same_steps >= 1u) || (n < c->prev_count && n * 4u <= c->peak_count));
     for (int follow = 0;; ++follow) {
     bool has_next = false;
     uint32_t nx_frame = 0, nx_bits = 0, nx_slot = 0, nx_depth = 0;
@@ -806,6 +807,7 @@ __device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
   uint32_t status = ld(&c->status);
   {
     const uint32_t n = ld(&c->touched_count[parity]);
+    st(&c->same_steps, n == ld(&c->prev_count) ? ld(&c->same_steps) + 1u : 0u);
     st(&c->prev_count, n);
     if (n > ld(&c->peak_count)) st(&c->peak_count, n);
   }
@@ -933,6 +935,7 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     lc.step = g->step;
     lc.prev_count = ld(&g->prev_count);
     lc.peak_count = ld(&g->peak_count);
+    lc.same_steps = ld(&g->same_steps);
     lc.n_leaf = ld(&g->n_leaf);
     lc.n_cell = ld(&g->n_cell);
     lc.n_head = ld(&g->n_head);
@@ -961,6 +964,7 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     g->step = lc.step;
     st(&g->prev_count, lc.prev_count);
     st(&g->peak_count, lc.peak_count);
+    st(&g->same_steps, lc.same_steps);
     st(&g->n_leaf, lc.n_leaf);
     st(&g->n_cell, lc.n_cell);
     st(&g->n_head, lc.n_head);
