@@ -105,17 +105,17 @@ struct GemmArgs {
   int save_gates;
 };
 
-constexpr int BM = 128;
+constexpr int BM_FULL = 128;   // rows of a workgroup tile; half of it for levels that would not fill the GPU
 
 // Workgroup tile BM x BN, NW waves as (NW/2) x 2, each wave 256/NW rows x WN column blocks of
 // 32.  One LDS stage of BK columns; the next stage travels global -> registers while the current
 // one is multiplied.  With eight waves a wave's accumulators fit half the register file, two
 // waves share a SIMD, and one multiplies while the other waits for LDS or memory.  LSTM_FWD gives every wave the five gate blocks of the same 32 hidden
 // units, so the gate epilogue needs no exchange between lanes.
-template <int DT, int MODE, int NW>
+template <int DT, int MODE, int NW, int BM>
 __global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
   constexpr int GEMM_THREADS = NW * 64;
-  constexpr int MB = 8 / NW;                     // 32-row blocks per wave
+  constexpr int MB = BM / (16 * NW);             // 32-row blocks per wave
   typedef typename TypeOf<DT>::type T;
   typedef El<T> E;
   constexpr int WN = MODE == LSTM_FWD ? 5 : 2;   // 32-wide column blocks per wave
@@ -324,7 +324,7 @@ __global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
   }
 }
 
-template <typename T, int MODE> size_t gemm_lds_bytes() {
+template <typename T, int MODE, int BM> size_t gemm_lds_bytes() {
   constexpr int WN = MODE == LSTM_FWD ? 5 : 2;
   return (size_t)(BM + 2 * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
 }
@@ -341,7 +341,7 @@ static int gemm_waves(int mode) {
   return mode == DW_SPLIT ? 4 : 8;
 }
 
-template <typename T, int MODE, int NW> void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
+template <typename T, int MODE, int NW, int BM> void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
   if (g.M <= 0) return;
   g.n_tiles_n = n_tiles_n;
   const int n_mt = (g.M + BM - 1) / BM;
@@ -349,17 +349,20 @@ template <typename T, int MODE, int NW> void launch_gemm_nw(GemmArgs g, int n_ti
   dim3 grid(MODE == DW_SPLIT ? 8 * n_mt * n_tiles_n * ((splits + 7) / 8) : (n_mt + 7) / 8 * 8 * n_tiles_n);
   static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
   if (!lds_opt_in) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE, NW>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE>());
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE, NW, BM>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE, BM>());
     lds_opt_in = true;
   }
-  const size_t lds = gemm_lds_bytes<T, MODE>();
-  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE, NW>), grid, dim3(NW * 64), lds, s, g);
+  const size_t lds = gemm_lds_bytes<T, MODE, BM>();
+  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE, NW, BM>), grid, dim3(NW * 64), lds, s, g);
 }
 
 template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
-  if (gemm_waves(MODE) == 4) launch_gemm_nw<T, MODE, 4>(g, n_tiles_n, splits, s);
-  else launch_gemm_nw<T, MODE, 8>(g, n_tiles_n, splits, s);
+  // a level whose full tiles would leave compute units without a workgroup gets tiles of half the rows
+  const bool half = MODE != DW_SPLIT && ((g.M + BM_FULL - 1) / BM_FULL) * n_tiles_n < 256;
+  if (half) launch_gemm_nw<T, MODE, 4, 64>(g, n_tiles_n, splits, s);
+  else if (gemm_waves(MODE) == 4) launch_gemm_nw<T, MODE, 4, 128>(g, n_tiles_n, splits, s);
+  else launch_gemm_nw<T, MODE, 8, 128>(g, n_tiles_n, splits, s);
 }
 
 // ---- small levels ----------------------------------------------------------------------
@@ -1195,7 +1198,7 @@ void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c,
 // workgroups, at least 1024 tags each, at most 64 (every split writes a partial dW that the
 // ordered reduction reads again).
 int vec_dw_splits(uint32_t q_stride, int Np, int Kp) {
-  const int tiles = ((Np + BM - 1) / BM) * ((Kp + 127) / 128);
+  const int tiles = ((Np + BM_FULL - 1) / BM_FULL) * ((Kp + 127) / 128);
   const int want = (640 + tiles - 1) / tiles;
   const int most = (int)std::min<uint32_t>(64u, q_stride / 1024u);
   return std::max(1, std::min(want, most));
