@@ -17,6 +17,7 @@ namespace tdf {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // one 16-byte chunk
+typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 namespace {
 
@@ -899,6 +900,150 @@ __global__ void __launch_bounds__(256) k_transpose(VecArgs v, Engine e, uint32_t
   }
 }
 
+// ---- weight gradients without transposed copies (16-bit state) ------------------------------
+// dW[n][k] = sum over the tags q of Dz[q][n] * X[q][k], X[q] = [h_l ; h_r] of cell q.  Both
+// operands are stored with the reduction index q as the slow one, which is the wrong way round for
+// an MFMA operand (a lane wants eight consecutive q of one n).  The LDS transpose load of CDNA4
+// (ds_read_b64_tr_b16) turns a 4 x 16 block [q][n] into lanes-by-n with four q each, so the tiles
+// go into LDS exactly as they lie in memory, Dz rows and gathered h rows, and the transposed copies
+// and their kernels are not needed.  MFMA 16x16x32: lane l holds row (column) l % 16 and k = 8 (l /
+// 16) .. + 7, i.e. two transpose loads; both operands use the same k order.  db[n] = sum_q Dz[q][n]
+// rides along as a product with a block of ones in the workgroups of the first column tile.
+// Tile 128 (n) x 128 (k) per workgroup, four waves as 2 x 2, 64 tags per LDS stage; the split of
+// the reduction and its placement on the dies are those of k_gemm<DW_SPLIT>.
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+constexpr int DWT = 128;        // tile edge
+constexpr int DWQ = 64;         // tags per stage
+constexpr int DWLD = DWT + 16;  // LDS row stride in elements: rows 288 bytes apart
+
+__device__ __forceinline__ bf16x8 tr_frag(const __bf16* tile, int q0, int col0, int lane) {
+  // block [q0 + 8 g .. + 7][col0 .. col0 + 15], g = lane / 16: source lane s of a group points at
+  // tag q0 + 8 g + 4 t + s / 4, columns col0 + 4 (s % 4) .. + 3; it receives column col0 + s of
+  // the tags q0 + 8 g + 4 t + 0 .. 3
+  const int g = lane >> 4, sl = lane & 15;
+  const __bf16* p = tile + (q0 + 8 * g + (sl >> 2)) * DWLD + col0 + 4 * (sl & 3);
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * DWLD));
+  s16x8 v;
+  v[0] = lo[0]; v[1] = lo[1]; v[2] = lo[2]; v[3] = lo[3];
+  v[4] = hi[0]; v[5] = hi[1]; v[6] = hi[2]; v[7] = hi[3];
+  return __builtin_bit_cast(bf16x8, v);
+}
+
+struct DwArgs {
+  const __bf16* Dz;      // [n_q][Np]
+  const __bf16* Hs;      // state rows
+  const uint32_t *q_l, *q_r;
+  uint32_t n_q;
+  int Np, Kp, Hp;
+  int k_per_split, n_splits, n_tiles_n;
+  float* dW_part;        // [splits][Np][Kp]
+  float* db_part;        // [splits][Np]
+};
+
+__global__ void __launch_bounds__(256, 3) k_dw_direct(DwArgs g) {
+  __shared__ __attribute__((aligned(16))) __bf16 sA[DWQ * DWLD];
+  __shared__ __attribute__((aligned(16))) __bf16 sB[DWQ * DWLD];
+  const int n_mt = (g.Np + DWT - 1) / DWT;
+  const int xcd = blockIdx.x & 7, u = blockIdx.x >> 3;
+  const int tiles = n_mt * g.n_tiles_n;
+  const int split = (u / tiles) * 8 + xcd;
+  if (split >= g.n_splits) return;
+  const int mt = (u % tiles) / g.n_tiles_n, nt = (u % tiles) % g.n_tiles_n;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const uint32_t q_begin = (uint32_t)split * (uint32_t)g.k_per_split;
+  const uint32_t q_end = min(g.n_q, q_begin + (uint32_t)g.k_per_split);
+
+  // this thread's four 16-byte chunks of each tile: rows r0 + 16 c, chunk column ch
+  const int r0 = tid >> 4, ch = (tid & 15) * 8;
+  const int a_col = mt * DWT + ch, b_col = nt * DWT + ch;
+  const bool a_ok = a_col < g.Np, b_ok = b_col < g.Kp;
+  const bool b_left = b_col < g.Hp;
+  const int b_off = b_left ? b_col : b_col - g.Hp;
+  u32x4 ra[4], rb[4];
+  uint32_t row_next[4];   // gathered rows of the stage after the one in ra / rb
+  auto load_rows = [&](uint32_t q0) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t q = q0 + r0 + 16 * c;
+      row_next[c] = q < q_end ? (b_left ? g.q_l[q] : g.q_r[q]) : 0u;
+    }
+  };
+  auto load_tile = [&](uint32_t q0) {   // uses row_next, which must hold the rows of q0
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const uint32_t q = q0 + r0 + 16 * c;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      ra[c] = (q < q_end && a_ok) ? *reinterpret_cast<const u32x4*>(g.Dz + (size_t)q * g.Np + a_col) : zero;
+      rb[c] = (q < q_end && b_ok) ? *reinterpret_cast<const u32x4*>(g.Hs + (size_t)row_next[c] * g.Hp + b_off) : zero;
+    }
+  };
+
+  f32x4 acc[4][4], accdb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    accdb[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  }
+  s16x8 ones_bits;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ones_bits[i] = (short)0x3F80;   // bf16 1.0
+  const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
+  const bool with_db = nt == 0 && wn == 0;
+
+  if (q_begin < q_end) {
+    load_rows(q_begin);
+    load_tile(q_begin);
+    if (q_begin + DWQ < q_end) load_rows(q_begin + DWQ);
+  }
+  for (uint32_t q0 = q_begin; q0 < q_end; q0 += DWQ) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      *reinterpret_cast<u32x4*>(sA + (r0 + 16 * c) * DWLD + ch) = ra[c];
+      *reinterpret_cast<u32x4*>(sB + (r0 + 16 * c) * DWLD + ch) = rb[c];
+    }
+    __syncthreads();
+    if (q0 + DWQ < q_end) {
+      load_tile(q0 + DWQ);
+      if (q0 + 2 * DWQ < q_end) load_rows(q0 + 2 * DWQ);
+    }
+#pragma unroll
+    for (int ks = 0; ks < DWQ / 32; ++ks) {
+      bf16x8 fa[4], fb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) fa[i] = tr_frag(sA, ks * 32, wm * 64 + i * 16, lane);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) fb[j] = tr_frag(sB, ks * 32, wn * 64 + j * 16, lane);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        if (with_db) accdb[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa[i], ones, accdb[i], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  // acc[i][j][r]: n = 4 (lane / 16) + r of block i, k = lane % 16 of block j
+  float* C = g.dW_part + (size_t)split * g.Np * g.Kp;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int n = mt * DWT + wm * 64 + i * 16 + 4 * (lane >> 4) + r;
+      if (n >= g.Np) continue;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int k = nt * DWT + wn * 64 + j * 16 + (lane & 15);
+        if (k < g.Kp) C[(size_t)n * g.Kp + k] = acc[i][j][r];
+      }
+      if (with_db && (lane & 15) == 0) g.db_part[(size_t)split * g.Np + n] = accdb[i][r];
+    }
+}
+
 // dW[n][k] = sum over splits, in split order; written in the caller's unpadded layout
 __global__ void k_reduce_dw(VecArgs v, float* dW, int splits) {
   const int R = v.N, K2 = 2 * v.H;
@@ -1204,6 +1349,26 @@ int vec_dw_splits(uint32_t q_stride, int Np, int Kp) {
   return std::max(1, std::min(want, most));
 }
 
+static void weight_grads_direct(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part,
+                                hipStream_t s) {
+  const int splits = vec_dw_splits(v.q_stride, v.Np, v.Kp);
+  DwArgs g{};
+  g.Dz = reinterpret_cast<const __bf16*>(v.Dz);
+  g.Hs = reinterpret_cast<const __bf16*>(v.Hs);
+  g.q_l = e.q_l; g.q_r = e.q_r;
+  g.n_q = n_q;
+  g.Np = v.Np; g.Kp = v.Kp; g.Hp = v.Hp;
+  g.k_per_split = (int)((v.q_stride / 64 + splits - 1) / splits) * 64;
+  g.n_splits = splits;
+  g.n_tiles_n = (v.Kp + DWT - 1) / DWT;
+  g.dW_part = v.dW_part;
+  g.db_part = db_part;
+  const int n_mt = (v.Np + DWT - 1) / DWT;
+  hipLaunchKernelGGL(k_dw_direct, dim3(8 * n_mt * g.n_tiles_n * ((splits + 7) / 8)), dim3(256), 0, s, g);
+  hipLaunchKernelGGL(k_reduce_dw, dim3(512), dim3(256), 0, s, v, dW, splits);
+  hipLaunchKernelGGL(k_db_final, dim3((v.Np + 15) / 16), dim3(256), 0, s, v, db_part, splits, 1, db);
+}
+
 template <typename T> static void weight_grads_t(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db,
                                                  float* db_part, hipStream_t s) {
   // transposed copies so that the reduction over tags is k-contiguous for both operands
@@ -1227,7 +1392,9 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   hipLaunchKernelGGL(k_db_final, dim3((v.Np + 15) / 16), dim3(256), 0, s, v, db_part, (parts + DB_RUN - 1) / DB_RUN, DB_RUN, db);
 }
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {
-  if (v.dtype == TDF_BF16) weight_grads_t<__bf16>(v, e, n_q, dW, db, db_part, s);
+  static const bool transposed = getenv("TDF_DW_TRANSPOSED") != nullptr;   // the older way, also for 16-bit state
+  if (v.dtype == TDF_BF16 && !transposed) weight_grads_direct(v, e, n_q, dW, db, db_part, s);
+  else if (v.dtype == TDF_BF16) weight_grads_t<__bf16>(v, e, n_q, dW, db, db_part, s);
   else weight_grads_t<float>(v, e, n_q, dW, db, db_part, s);
 }
 
