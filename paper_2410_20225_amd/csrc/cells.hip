@@ -108,19 +108,20 @@ struct GemmArgs {
 
 constexpr int BM_FULL = 128;   // rows of a workgroup tile; half of it for levels that would not fill the GPU
 
-// Workgroup tile BM x BN, NW waves as (NW/2) x 2, each wave 256/NW rows x WN column blocks of
-// 32.  One LDS stage of BK columns; the next stage travels global -> registers while the current
+// Workgroup tile BM x BN, NW waves as (NW/WNS) x WNS, each wave BM*WNS/NW rows x WN column blocks
+// of 32.  One LDS stage of BK columns; the next stage travels global -> registers while the current
 // one is multiplied.  With eight waves a wave's accumulators fit half the register file, two
-// waves share a SIMD, and one multiplies while the other waits for LDS or memory.  LSTM_FWD gives every wave the five gate blocks of the same 32 hidden
-// units, so the gate epilogue needs no exchange between lanes.
-template <int DT, int MODE, int NW, int BM>
-__global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
+// waves share a SIMD, and one multiplies while the other waits for LDS or memory.  LSTM_FWD
+// gives every wave the five gate blocks of the same 32 hidden units, so the gate epilogue needs
+// no exchange between lanes; its workgroups are one such block wide (WNS = 1).
+template <int DT, int MODE, int NW, int BM, int WNS>
+__global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) {
   constexpr int GEMM_THREADS = NW * 64;
-  constexpr int MB = BM / (16 * NW);             // 32-row blocks per wave
+  constexpr int MB = BM * WNS / (32 * NW);       // 32-row blocks per wave (waves as NW/WNS x WNS)
   typedef typename TypeOf<DT>::type T;
   typedef El<T> E;
   constexpr int WN = MODE == LSTM_FWD ? 5 : 2;   // 32-wide column blocks per wave
-  constexpr int BN = 2 * WN * 32;                // columns per workgroup
+  constexpr int BN = WNS * WN * 32;              // columns per workgroup
   constexpr int LDT = E::BK + E::PAD;            // LDS row stride
   constexpr int CPR = E::BK / E::CH;             // 16-byte chunks per tile row
   constexpr int A_CHUNKS = BM * CPR / GEMM_THREADS;
@@ -149,7 +150,7 @@ __global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
   }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WNS, wn = wave % WNS;
   const int wrow = wm * MB * 32;                 // the wave's first row in the tile
   const int m0 = mt * BM;
   int k_begin = 0, k_end = g.K;
@@ -177,7 +178,7 @@ __global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
     int brow;
     if (MODE == LSTM_FWD) {
       const int w = row / 160, gate = (row % 160) / 32, jj = row % 32;
-      brow = gate * g.Hp + min(nt * 2 + w, g.Hp / 32 - 1) * 32 + jj;
+      brow = gate * g.Hp + min(nt * WNS + w, g.Hp / 32 - 1) * 32 + jj;
     } else {
       brow = min(nt * BN + row, g.N - 1);
     }
@@ -259,7 +260,7 @@ __global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
   const int col = lane & 31;
   auto row_of = [&](int i, int r) { return wrow + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); };
   if constexpr (MODE == LSTM_FWD) {
-    const int jb = nt * 2 + wn;
+    const int jb = nt * WNS + wn;
     if (jb * 32 < g.Hp) {
       const int n = jb * 32 + col;   // hidden unit
       const float bi = g.bias[n], bfl = g.bias[g.Hp + n], bfr = g.bias[2 * g.Hp + n];
@@ -325,9 +326,9 @@ __global__ void __launch_bounds__(NW * 64) k_gemm(GemmArgs g) {
   }
 }
 
-template <typename T, int MODE, int BM> size_t gemm_lds_bytes() {
+template <typename T, int MODE, int BM, int WNS> size_t gemm_lds_bytes() {
   constexpr int WN = MODE == LSTM_FWD ? 5 : 2;
-  return (size_t)(BM + 2 * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
+  return (size_t)(BM + WNS * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
 }
 
 // Waves per workgroup of the tiled GEMM: TDF_GEMM_WAVES = 4 or 8; else 8 where a level's rows are
@@ -342,7 +343,8 @@ static int gemm_waves(int mode) {
   return mode == DW_SPLIT ? 4 : 8;
 }
 
-template <typename T, int MODE, int NW, int BM> void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
+template <typename T, int MODE, int NW, int BM, int WNS = 2>
+void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
   if (g.M <= 0) return;
   g.n_tiles_n = n_tiles_n;
   const int n_mt = (g.M + BM - 1) / BM;
@@ -350,18 +352,22 @@ template <typename T, int MODE, int NW, int BM> void launch_gemm_nw(GemmArgs g, 
   dim3 grid(MODE == DW_SPLIT ? 8 * n_mt * n_tiles_n * ((splits + 7) / 8) : (n_mt + 7) / 8 * 8 * n_tiles_n);
   static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
   if (!lds_opt_in) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE, NW, BM>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE, BM>());
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE, NW, BM, WNS>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE, BM, WNS>());
     lds_opt_in = true;
   }
-  const size_t lds = gemm_lds_bytes<T, MODE, BM>();
-  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE, NW, BM>), grid, dim3(NW * 64), lds, s, g);
+  const size_t lds = gemm_lds_bytes<T, MODE, BM, WNS>();
+  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE, NW, BM, WNS>), grid, dim3(NW * 64), lds, s, g);
 }
 
 template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
   // a level whose full tiles would leave compute units without a workgroup gets tiles of half the rows
   const bool half = MODE != DW_SPLIT && ((g.M + BM_FULL - 1) / BM_FULL) * n_tiles_n < 256;
-  if (half) launch_gemm_nw<T, MODE, 4, 64>(g, n_tiles_n, splits, s);
+  // LSTM cells: one block of 32 hidden units (x 5 gates) per workgroup, four waves of 32 rows: the
+  // accumulators fit a third of the register file and three workgroups share a compute unit, each
+  // in another phase of its k loop
+  if (MODE == LSTM_FWD) launch_gemm_nw<T, MODE, 4, 128, 1>(g, n_tiles_n * 2, splits, s);
+  else if (half) launch_gemm_nw<T, MODE, 4, 64>(g, n_tiles_n, splits, s);
   else if (gemm_waves(MODE) == 4) launch_gemm_nw<T, MODE, 4, 128>(g, n_tiles_n, splits, s);
   else launch_gemm_nw<T, MODE, 8, 128>(g, n_tiles_n, splits, s);
 }
