@@ -27,8 +27,8 @@ COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 # profiles/bench_workload4_hbm_traffic.md), with the hash of the kernel source they were taken on:
 # reported as `traffic` only while that source is unchanged.
 MEASURED_TRAFFIC = {
-    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "8aa3a0da3e1f1810", 2237558864.4),
-        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "25669e8fa0a715df", 366465627.1)},
+    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "6a8aeb2590885fe6", 2205030931.3),
+        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "25669e8fa0a715df", 366439082.7)},
 }
 
 
