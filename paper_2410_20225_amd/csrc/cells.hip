@@ -446,9 +446,22 @@ __device__ __forceinline__ void load_resident_b(const GemmArgs& g, int ct, Resid
 
 // RES > 0: the weight operands come from `rb` (which holds all chunk steps of this wave: the
 // caller checked steps <= RES); RES == 0: they are fetched here.
+// DX_BWD tiles of the tail launches also form the pre-activation gradients of the children they
+// have just given their dh: a child has one parent, so once the parent's tile has produced dh of
+// (child, unit) everything that dz of (child, unit) needs is final (dc came from the parent's own
+// dz, the rest is forward state).  The separate dz pass over a level, and the barrier after it,
+// are not needed then.  Only children inside the tail are handled (cq >= q_first): the cells of
+// the wide levels get their dz from k_dz as before.
+struct DzFuse {
+  const VecArgs* v;
+  const uint32_t *cq_l, *cq_r;   // position of the children's cells in the sorted log (~0: a leaf), from the level's first cell
+  const uint32_t *q_l, *q_r;     // children rows of every cell of the sorted log
+  uint32_t q_first;              // first cell of the tail in the sorted log
+};
+
 template <int DT, int MODE, int NW, int RES = 0>
 __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int ct, float* part,
-                                                const ResidentB<MODE, RES>* rb = nullptr) {
+                                                const ResidentB<MODE, RES>* rb = nullptr, const DzFuse* fz = nullptr) {
   typedef typename TypeOf<DT>::type T;
   typedef Chunk<T> C;
   constexpr int G = MODE == LSTM_FWD ? 5 : 1;      // 32-wide column blocks per tile
@@ -495,12 +508,48 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
     }
   }
 
+  // fused dz (DX_BWD in the tail): which child cell, and what its dz needs, requested early
+  uint32_t z_q[RPW], z_row[RPW], z_gl[RPW], z_gr[RPW];
+  float z_gate[RPW][5], z_c[RPW], z_dc[RPW], z_h[RPW];
+  const bool z_on = MODE == DX_BWD && fz != nullptr;
+  const bool z_left = unit < g.Hp;
+  const int z_n = z_left ? unit : unit - g.Hp;
+  if (MODE == DX_BWD && z_on) {
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+      const int m = min(m0 + row_of(rr), g.M - 1);
+      z_q[rr] = (z_left ? fz->cq_l : fz->cq_r)[m];
+      z_row[rr] = z_left ? o_l[rr] : o_r[rr];
+    }
+  }
+
   f32x16 acc[G];
 #pragma unroll
   for (int j = 0; j < G; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
   const int steps = kw / C::KC;
+  if (MODE == DX_BWD && z_on) {
+    const VecArgs& v = *fz->v;
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr) {
+      const bool ok = z_q[rr] != 0xFFFFFFFFu && z_q[rr] >= fz->q_first;
+      if (!ok) z_q[rr] = 0xFFFFFFFFu;
+      const uint32_t qc = ok ? z_q[rr] : 0u;   // (cell 0 exists whenever a level has cells: a safe address)
+      const size_t o = (size_t)z_row[rr] * v.Hp + z_n;
+      if (v.cell_kind == 1) {
+        z_h[rr] = to_f(reinterpret_cast<const T*>(v.Hs)[o]);
+      } else {
+        const T* g5 = reinterpret_cast<const T*>(v.gates) + (size_t)qc * v.Np + z_n;
+#pragma unroll
+        for (int k = 0; k < 5; ++k) z_gate[rr][k] = to_f(g5[k * v.Hp]);
+        z_c[rr] = v.Cs[o];
+        z_dc[rr] = v.dC[o];
+        z_gl[rr] = fz->q_l[qc];
+        z_gr[rr] = fz->q_r[qc];
+      }
+    }
+  }
   if constexpr (RES > 0) {
     u32x4 fa[RES];
 #pragma unroll
@@ -588,6 +637,38 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
       if (m >= g.M) continue;
       if (unit < g.Hp) g.C[(size_t)o_l[rr] * g.Hp + unit] = z[0][rr];
       else g.C[(size_t)o_r[rr] * g.Hp + (unit - g.Hp)] = z[0][rr];
+    }
+    if (z_on) {
+      const VecArgs& v = *fz->v;
+      float z_cl[RPW], z_cr[RPW];
+      if (v.cell_kind == 2) {
+#pragma unroll
+        for (int rr = 0; rr < RPW; ++rr) {
+          z_cl[rr] = v.Cs[(size_t)z_gl[rr] * v.Hp + z_n];
+          z_cr[rr] = v.Cs[(size_t)z_gr[rr] * v.Hp + z_n];
+        }
+      }
+#pragma unroll
+      for (int rr = 0; rr < RPW; ++rr) {
+        const int m = m0 + row_of(rr);
+        if (m >= g.M || z_q[rr] == 0xFFFFFFFFu) continue;
+        const float dh = z[0][rr];
+        T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)z_q[rr] * v.Np + z_n;
+        if (v.cell_kind == 1) {
+          dz[0] = from_f<T>(dh * (1.f - z_h[rr] * z_h[rr]));
+        } else {
+          const float gi = z_gate[rr][0], gfl = z_gate[rr][1], gfr = z_gate[rr][2], go = z_gate[rr][3], gu = z_gate[rr][4];
+          const float tc = Act<T>::tanh(z_c[rr]);
+          const float dc = z_dc[rr] + dh * go * (1.f - tc * tc);
+          dz[0] = from_f<T>(dc * gu * gi * (1.f - gi));
+          dz[v.Hp] = from_f<T>(dc * z_cl[rr] * gfl * (1.f - gfl));
+          dz[2 * v.Hp] = from_f<T>(dc * z_cr[rr] * gfr * (1.f - gfr));
+          dz[3 * v.Hp] = from_f<T>(dh * tc * go * (1.f - go));
+          dz[4 * v.Hp] = from_f<T>(dc * gi * (1.f - gu * gu));
+          v.dC[(size_t)z_gl[rr] * v.Hp + z_n] = dc * gfl;
+          v.dC[(size_t)z_gr[rr] * v.Hp + z_n] = dc * gfr;
+        }
+      }
     }
   }
   __syncthreads();   // `part` is free for the workgroup's next tile
@@ -777,6 +858,7 @@ struct TailArgs {
   uint32_t n_dies;
   DieSync* sync;               // [8], zero on entry
   long long spin_ticks;
+  uint32_t q_first;            // first cell of the tail in the sorted log
 };
 
 template <int DT, int MODE, int NW>
@@ -837,22 +919,40 @@ __global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Eng
   for (uint32_t lvl = t.lvl_last; lvl >= t.lvl_first; --lvl) {
     const uint32_t q0 = t.level_off[lvl * LEVEL_KEY_DIES + die];
     const uint32_t cnt = t.level_off[lvl * LEVEL_KEY_DIES + die + 1] - q0;
-    for (uint32_t m = rank; m < cnt; m += G) dz_row<DT>(v, e, q0 + m);
-    if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
+    // (dz of this level's cells: from their parents' tiles, or, for the roots, from k_dz_tail_roots)
     GemmArgs gl = g;
+    DzFuse fz{&v, e.cq_l + q0, e.cq_r + q0, e.q_l, e.q_r, t.q_first};
     gl.M = (int)cnt;
     gl.A = reinterpret_cast<const T*>(g.A) + (size_t)q0 * g.lda;
     gl.l = g.l + q0; gl.r = g.r + q0;
     const uint32_t n_rt = (cnt + 31) / 32;
     if (resident) {
       for (uint32_t rt = rank / n_ct; rt < n_rt; rt += G / n_ct)
-        cell_small_tile<DT, DX_BWD, NW, RES>(gl, (int)rt, (int)(rank % n_ct), part, &rb);
+        cell_small_tile<DT, DX_BWD, NW, RES>(gl, (int)rt, (int)(rank % n_ct), part, &rb, &fz);
     } else {
       for (uint32_t tile = rank; tile < n_rt * n_ct; tile += G)
-        cell_small_tile<DT, DX_BWD, NW>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part);
+        cell_small_tile<DT, DX_BWD, NW, 0>(gl, (int)(tile / n_ct), (int)(tile % n_ct), part,
+                                           (const ResidentB<DX_BWD, 0>*)nullptr, &fz);
     }
     if (!die_barrier(sy, G, gen++, t.spin_ticks, &sh_ok)) return;
   }
+}
+
+// position of every cell's row in the sorted log, then of every cell's children
+__global__ void k_row_q(Engine e, uint32_t n_cell) {
+  for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < n_cell; q += gridDim.x * blockDim.x) e.row_q[e.q_out[q]] = q;
+}
+__global__ void k_child_q(Engine e, uint32_t n_cell) {
+  for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < n_cell; q += gridDim.x * blockDim.x) {
+    e.cq_l[q] = e.row_q[e.q_l[q]];
+    e.cq_r[q] = e.row_q[e.q_r[q]];
+  }
+}
+// dz of the cells of the tail that have no parent: the roots, whose dh came from the head (or the caller)
+template <int DT>
+__global__ void k_dz_tail_roots(VecArgs v, Engine e, const uint32_t* root_rows, uint32_t q_first) {
+  const uint32_t q = e.row_q[root_rows[blockIdx.x]];
+  if (q != 0xFFFFFFFFu && q >= q_first) dz_row<DT>(v, e, q);
 }
 
 // ---- transposes feeding the weight-gradient GEMM (reduction over tags must be k-contiguous) -----
@@ -1326,9 +1426,20 @@ template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, 
     hipLaunchKernelGGL((k_tail_bwd<DtOf<T>::value, 4>), dim3(grid), dim3(256), lds, s, g, v, e, t);
   }
 }
+// After the level sort of a gradient run: where each cell's children are in the sorted log.
+void vec_child_index(const Engine& e, uint32_t n_cell, hipStream_t s) {
+  (void)hipMemsetAsync(e.row_q, 0xFF, sizeof(uint32_t) * ((size_t)e.cap + e.n_inst), s);
+  const int g = (int)std::min<uint32_t>((n_cell + 255) / 256, 2048u);
+  hipLaunchKernelGGL(k_row_q, dim3(std::max(g, 1)), dim3(256), 0, s, e, n_cell);
+  hipLaunchKernelGGL(k_child_q, dim3(std::max(g, 1)), dim3(256), 0, s, e, n_cell);
+}
+
 void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
-                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, hipStream_t s) {
-  TailArgs t{level_off, lvl_first, lvl_last, n_dies, (DieSync*)sync, spin_ticks};
+                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, uint32_t q_first, const uint32_t* root_rows,
+                  hipStream_t s) {
+  TailArgs t{level_off, lvl_first, lvl_last, n_dies, (DieSync*)sync, spin_ticks, q_first};
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_dz_tail_roots<TDF_BF16>, dim3(e.n_inst), dim3(256), 0, s, v, e, root_rows, q_first);
+  else hipLaunchKernelGGL(k_dz_tail_roots<TDF_F32>, dim3(e.n_inst), dim3(256), 0, s, v, e, root_rows, q_first);
   if (v.dtype == TDF_BF16) tail_bwd_t<__bf16>(v, e, t, cus, s); else tail_bwd_t<float>(v, e, t, cus, s);
 }
 

@@ -107,6 +107,8 @@ struct Engine {
   uint32_t *level_count, *level_off, *level_fill;    // [(max_levels + 2) * LEVEL_KEY_DIES]
   uint32_t max_levels;
   uint32_t *q_out, *q_l, *q_r;      // [n_cell], sorted by level
+  uint32_t* row_q;                  // [cap + n_inst]: position of a row's cell in the sorted log, ~0 for leaves (gradient runs)
+  uint32_t *cq_l, *cq_r;            // [n_cell]: row_q of the two children
 };
 
 // The engine as machine d sees it.

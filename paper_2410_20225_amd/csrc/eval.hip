@@ -30,7 +30,9 @@ uint32_t vec_small_level();
 void vec_tail_fwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
                   uint32_t n_dies, void* sync, long long spin_ticks, int cus, int save_gates, hipStream_t s);
 void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
-                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, hipStream_t s);
+                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, uint32_t q_first, const uint32_t* root_rows,
+                  hipStream_t s);
+void vec_child_index(const Engine& e, uint32_t n_cell, hipStream_t s);
 void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s);
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s);
 void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s);
@@ -145,6 +147,8 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_leaf_row = L.take(4 * rc), off_leaf_tok = L.take(4 * rc);
   size_t off_c_out = L.take(4 * rc), off_c_l = L.take(4 * rc), off_c_r = L.take(4 * rc), off_c_lvl = L.take(4 * rc);
   size_t off_q_out = L.take(4 * rc), off_q_l = L.take(4 * rc), off_q_r = L.take(4 * rc);
+  size_t off_row_q = with_grad ? L.take(4 * ((size_t)e.cap + e.n_inst)) : 0;
+  size_t off_cq_l = with_grad ? L.take(4 * rc) : 0, off_cq_r = with_grad ? L.take(4 * rc) : 0;
   // logs of the single machines, merged into the arrays above after the last step
   size_t off_m[6] = {off_leaf_row, off_leaf_tok, off_c_out, off_c_l, off_c_r, off_c_lvl};
   if (e.n_dies > 1)
@@ -177,6 +181,9 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.q_out = (uint32_t*)at(off_q_out);
   e.q_l = (uint32_t*)at(off_q_l);
   e.q_r = (uint32_t*)at(off_q_r);
+  e.row_q = with_grad ? (uint32_t*)at(off_row_q) : nullptr;
+  e.cq_l = with_grad ? (uint32_t*)at(off_cq_l) : nullptr;
+  e.cq_r = with_grad ? (uint32_t*)at(off_cq_r) : nullptr;
   e.left = in->left;
   e.right = in->right;
   e.token = in->token;
@@ -450,9 +457,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       // ---- gradient pass: the level schedule walked backwards -----------------------------
       if (use_tail && hc.n_cell) {
         begin(TDF_PHASE_TAIL_BWD);
+        vec_child_index(e, hc.n_cell, s);
         vec_tail_bwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync + 8 * sizeof(DieSync),
-                     spin_ticks, cus, s);
-        end(TDF_PHASE_TAIL_BWD, 1);
+                     spin_ticks, cus, lvl_begin(tail_first), G.has_head ? e.head_row : e.root_ref, s);
+        end(TDF_PHASE_TAIL_BWD, 5);
       }
       begin(TDF_PHASE_CELLS_BWD);
       for (uint32_t lvl = tail_first - 1; lvl >= 1 && hc.n_cell; --lvl)
