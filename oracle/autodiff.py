@@ -17,7 +17,7 @@ dead, `snd(x, dy)` (the gradient of a Merge input) is dead wherever x was dead, 
 from .graph import Function, Program, INT, FLOAT, VEC
 
 _INT_OPS = ("eq", "lt", "isleaf", "left", "right", "token")
-_VEC_OPS = ("embed", "embed_lstm", "rnn_cell", "lstm_cell", "take_h")
+_VEC_OPS = ("embed", "embed_lstm", "rnn_cell", "lstm_cell", "take_h", "ce_node")
 
 
 def infer_types(program):
@@ -127,5 +127,7 @@ def _add_gradient_nodes(g, ty, diff_params):
             push(nd.ins[0], g.op("take_h_grad", nd.ins[0], dy))
         elif op == "ce_head":
             push(nd.ins[0], g.op("ce_head_grad", nd.ins[0], nd.ins[1], dy))
+        elif op == "ce_node":                       # the node's own loss term joins the gradient of the state
+            push(nd.ins[0], g.op("ce_node_grad", nd.ins[0], nd.ins[1], dy))
         else:
             raise ValueError("no gradient operator for " + op)

@@ -89,6 +89,7 @@ class Interpreter:
         self.max_tag_len = 0
         self.outputs = {}
         self.param_grad = {}
+        self.node_loss = {}            # tree node -> loss term of the ce_node firing there
         self._outer = {}               # name -> ([delta rows], [x rows]) awaiting a flush
 
     # ------------------------------------------------------------------------------
@@ -290,6 +291,19 @@ class Interpreter:
             return ops.ce_head(env["U"], env["u0"], v[0], v[1])
         if op == "ce_head_grad":                    # (h, label, dloss) -> dh
             return ops.ce_head_grad(env["U"], env["u0"], v[0], v[1], v[2])
+        if op == "ce_node":                         # (state, tree node) -> the same state
+            lab = int(env["node_label"][v[1]])
+            if lab >= 0:                            # the loss term of this firing, kept by node
+                h = v[0][: env["U"].shape[1]]
+                self.node_loss[v[1]] = ops.ce_head(env["U"], env["u0"], h, lab)
+            return v[0]
+        if op == "ce_node_grad":                    # (state, tree node, dstate) -> dstate
+            lab = int(env["node_label"][v[1]])
+            ds = np.array(v[2], dtype=np.float64)
+            if lab >= 0:
+                H = env["U"].shape[1]
+                ds[:H] += ops.ce_head_grad(env["U"], env["u0"], v[0][:H], lab, float(env["dnode"][v[1]]))
+            return ds
         if op == "embed_grad":                      # (token, dy) -> sink
             self._add_rows("dE", v[0], v[1])
             return None

@@ -13,6 +13,8 @@ definitions:
                      a state is the pair (h, c), carried as one vector [h; c]
   leaf               h = E[token]   (TreeLSTM: c = 0)
   head               loss = -log softmax(U h + u0)[label]
+  node loss          the same loss at a tree node v with label node_label[v] >= 0, on the h of
+                     the state the node's subtree produced; the state itself goes on unchanged
 """
 import numpy as np
 

@@ -89,9 +89,11 @@ def tak_program():
     return Program([r, f])
 
 
-def tree_program(cell="rnn", head=False):
+def tree_program(cell="rnn", head=False, node_loss=False):
     """f(v) = if isleaf(v) then embed(token(v)) else cell(f(left v), f(right v)).
-    result(v) = f(v), or with `head`: result(v,label) = ce_head(f(v), label)."""
+    result(v) = f(v), or with `head`: result(v,label) = ce_head(f(v), label).
+    With `node_loss` every node of a tree contributes a loss term (fully labelled trees,
+    Section 6): f(v) = ce_node(if ... , v)."""
     f = Function("f", [INT], VEC)
     v = f.param(0)
     leaf, inner = f.switch(f.op("isleaf", v), v)
@@ -99,7 +101,8 @@ def tree_program(cell="rnn", head=False):
     hl = f.call("f", f.op("left", inner))
     hr = f.call("f", f.op("right", inner))
     h = f.op(cell + "_cell", hl, hr)
-    f.output(f.merge(e, h))
+    s = f.merge(e, h)
+    f.output(f.op("ce_node", s, v) if node_loss else s)
     if head:
         r = Function("result", [INT, INT], FLOAT)
         y = r.call("f", r.param(0))

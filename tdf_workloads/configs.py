@@ -93,6 +93,8 @@ def make_config(cfg, n_trees=None, max_leaves=None, seed=None, vocab=None, hidde
         E, W = E.astype(np.float32).astype(np.float64), W.astype(np.float32).astype(np.float64)
     U = U.astype(np.float32).astype(np.float64)
     labels = r_lab.randint(0, 4, B)
+    node_labels = rng.fork(4).randint(0, 4, forest.n_nodes)   # fully labelled trees: one class per node
     return {"cfg": cfg, "kind": "tree" + cell, "cell": cell, "bf16": bf16, "H": H, "V": V,
             "forest": forest, "E": E, "W": W, "b": b, "U": U, "u0": u0, "labels": labels,
+            "node_labels": node_labels,
             "grad": cfg >= 3}
