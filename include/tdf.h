@@ -86,6 +86,9 @@ typedef enum {
   TDF_OP_CE_HEAD,     /* in[0] = row, in[1] = label -> -log softmax(U h + u0)[label]    */
   TDF_OP_LOOP,        /* imm = loop graph index; in[k] = initial value of loop variable k   */
   TDF_OP_NEXT,        /* in a loop graph: in[k] = loop variable k in the next iteration     */
+  TDF_OP_CE_NODE,     /* in[0] = row, in[1] = tree node v -> the same row; the node's loss term
+                         -log softmax(U h + u0)[node_label[v]] goes to out_node_loss[v]
+                         (no term where node_label[v] < 0): fully labelled trees, Section 6 */
   TDF_OP_COUNT
 } tdf_op;
 
@@ -121,7 +124,8 @@ typedef struct {
  * device.  Host only.  Rejected with TDF_ERR_BAD_PROGRAM: undefined callee, arity
  * mismatch, forward reference, more or fewer than one OUT per function, an operator
  * whose inputs are all constants outside `result`, more than 64 nodes in a function, a
- * gradient request for a program without vector operators or with loops, a loop graph that
+ * gradient request for a program without vector operators or with loops, CE_NODE together
+ * with CE_HEAD, a loop graph that
  * is called, is `result`, has two NEXT nodes or belongs to no or several LOOP nodes, a LOOP
  * over a graph without NEXT.  *out is owned by the library
  * until tdf_graph_destroy. */
@@ -180,6 +184,8 @@ typedef struct {
   const int32_t* left;  /* device int32[n_tree_nodes], -1 at a leaf                     */
   const int32_t* right; /* device int32[n_tree_nodes]                                   */
   const int32_t* token; /* device int32[n_tree_nodes], token id at a leaf               */
+  const int32_t* node_label; /* device int32[n_tree_nodes], class of the node's loss term,
+                                < 0: none (CE_NODE; NULL otherwise)                      */
   /* parameters of the vector operators (may be NULL / 0 for integer programs)          */
   int32_t dtype;  /* tdf_dtype of E, W and of the hidden-state rows                     */
   int32_t hidden; /* H                                                                  */
@@ -188,7 +194,7 @@ typedef struct {
   const void* W;  /* device [R x 2H], dtype, row-major; R = H (RNN) or 5H (LSTM)        */
   const float* b; /* device float[R]                                                    */
   int32_t n_classes;
-  const float* U;  /* device float[n_classes x H]   (CE_HEAD)                           */
+  const float* U;  /* device float[n_classes x H]   (CE_HEAD, CE_NODE)                  */
   const float* u0; /* device float[n_classes]                                           */
   /* capacities */
   int64_t max_tags;   /* upper bound on call-context tags (= invocations) of one call   */
@@ -202,11 +208,15 @@ typedef struct {
   float* out_f32;   /* device float[B]: scalar float result (CE_HEAD loss per instance) */
   float* out_h;     /* device float[B x H]: vector result, h of the root                */
   float* out_c;     /* device float[B x H]: TreeLSTM cell state of the root, or NULL    */
+  float* out_node_loss; /* device float[n_tree_nodes]: loss term of every tree node whose
+                           CE_NODE fired, 0 elsewhere (graphs with CE_NODE; else ignored)  */
 } tdf_outputs;      /* only the member matching the result type is written; others may be NULL */
 
 typedef struct {
   const float* dy; /* device: float[B] for a scalar result, float[B x H] (dL/dh of each
-                      root) for a vector result                                         */
+                      root) for a vector result; NULL = zero in a graph with CE_NODE    */
+  const float* dnode; /* device float[n_tree_nodes]: gradient of the objective with respect
+                         to each node's loss term (graphs with CE_NODE; else ignored)     */
 } tdf_seed;
 
 typedef struct {

@@ -104,6 +104,7 @@ struct GemmArgs {
   int n_splits;
   int n_tiles_n;             // column tiles of the launch
   int save_gates;
+  int add_c;                 // DX_BWD: the rows of C already hold a term; the product is added to it
 };
 
 constexpr int BM_FULL = 128;   // rows of a workgroup tile; half of it for levels that would not fill the GPU
@@ -315,8 +316,8 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
             reinterpret_cast<T*>(g.Hs_out)[(size_t)sOut[row] * g.Hp + n] = from_f<T>(Act<T>::tanh(acc[i][j][r] + bias));
           } else if constexpr (MODE == DX_BWD) {
             // column n of [dh_l; dh_r]: each child row has exactly one consumer, plain store
-            if (n < g.Hp) g.C[(size_t)sL[row] * g.Hp + n] = acc[i][j][r];
-            else g.C[(size_t)sR[row] * g.Hp + (n - g.Hp)] = acc[i][j][r];
+            float* c = n < g.Hp ? g.C + (size_t)sL[row] * g.Hp + n : g.C + (size_t)sR[row] * g.Hp + (n - g.Hp);
+            *c = acc[i][j][r] + (g.add_c ? *c : 0.f);
           } else {
             g.C[(size_t)split * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
           }
@@ -635,8 +636,9 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
     for (int rr = 0; rr < RPW; ++rr) {
       const int m = m0 + row_of(rr);
       if (m >= g.M) continue;
-      if (unit < g.Hp) g.C[(size_t)o_l[rr] * g.Hp + unit] = z[0][rr];
-      else g.C[(size_t)o_r[rr] * g.Hp + (unit - g.Hp)] = z[0][rr];
+      float* c = unit < g.Hp ? g.C + (size_t)o_l[rr] * g.Hp + unit : g.C + (size_t)o_r[rr] * g.Hp + (unit - g.Hp);
+      if (g.add_c) z[0][rr] += *c;   // (the sum is also what the children's dz below is formed from)
+      *c = z[0][rr];
     }
     if (z_on) {
       const VecArgs& v = *fz->v;
@@ -786,12 +788,64 @@ __global__ void k_head(VecArgs v, Engine e, const float* dy, int with_grad) {
   }
 }
 
-// vector result: seed dH of each root row with the caller's dy; copy the root rows out
+// Loss terms of the nodes (CE_NODE): one wave per state row.  A row that was marked with a tree
+// node v whose label is a class gets loss[v] = -log softmax(U h + u0)[label]; in a gradient run
+// the row's dh starts as dnode[v] U^T (p - onehot), 0 for rows without a term, and the row's
+// consumer (the parent's input gradient, the caller's dy at a root) adds to it.
+template <int DT>
+__global__ void k_node_ce(VecArgs v, Engine e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label, float* out_loss,
+                          const float* dnode, int with_grad) {
+  typedef typename TypeOf<DT>::type T;
+  const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  const uint32_t n_waves = (gridDim.x * blockDim.x) >> 6;
+  for (uint32_t i = wave; i < n_leaf + n_cell; i += n_waves) {
+    const uint32_t row = i < n_leaf ? e.leaf_row[i] : e.q_out[i - n_leaf];
+    const uint32_t node = e.row_node[row];
+    int label = -1;
+    if (node != 0xFFFFFFFFu) label = node_label[node];
+    if (label >= v.n_classes) label = -1;
+    float* dh = with_grad ? v.dH + (size_t)row * v.Hp : nullptr;
+    if (label < 0) {
+      if (with_grad)
+        for (int n = lane; n < v.Hp; n += 64) dh[n] = 0.f;
+      continue;
+    }
+    const T* h = reinterpret_cast<const T*>(v.Hs) + (size_t)row * v.Hp;
+    float logit[16];
+    float mx = -3.0e38f;
+    for (int c = 0; c < v.n_classes; ++c) {
+      float s = 0.f;
+      for (int n = lane; n < v.H; n += 64) s += v.U[c * v.H + n] * to_f(h[n]);
+      for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+      logit[c] = s + v.u0[c];
+      mx = fmaxf(mx, logit[c]);
+    }
+    float z = 0.f;
+    for (int c = 0; c < v.n_classes; ++c) z += expf(logit[c] - mx);
+    const float lse = mx + logf(z);
+    float own = 0.f;
+    for (int c = 0; c < v.n_classes; ++c) own = c == label ? logit[c] : own;
+    if (lane == 0) out_loss[node] = lse - own;
+    if (with_grad) {
+      const float d = dnode[node];
+      for (int n = lane; n < v.Hp; n += 64) {
+        float s = 0.f;
+        if (n < v.H)
+          for (int c = 0; c < v.n_classes; ++c)
+            s += (expf(logit[c] - lse) - (c == label ? 1.f : 0.f)) * v.U[c * v.H + n];
+        dh[n] = s * d;
+      }
+    }
+  }
+}
+
+// vector result: seed dH of each root row with the caller's dy (none: zero); copy the root rows out
 __global__ void k_seed_dy(VecArgs v, Engine e, const float* dy) {
   const int b = blockIdx.x;
   const uint32_t row = e.root_ref[b];
   for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
-    v.dH[(size_t)row * v.Hp + n] = n < v.H ? dy[(size_t)b * v.H + n] : 0.f;
+    const float own = v.dh_init ? v.dH[(size_t)row * v.Hp + n] : 0.f;
+    v.dH[(size_t)row * v.Hp + n] = own + (dy && n < v.H ? dy[(size_t)b * v.H + n] : 0.f);
     if (v.cell_kind == 2) v.dC[(size_t)row * v.Hp + n] = 0.f;
   }
 }
@@ -1368,6 +1422,7 @@ template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, 
   g.B = v.WpT; g.ldb = v.Np; g.Bf = v.WfT;
   g.Hp = v.Hp; g.l = e.q_l + q0; g.r = e.q_r + q0;
   g.C = v.dH;
+  g.add_c = v.dh_init;
   if (count <= small_level()) launch_cell_small<T, DX_BWD>(g, v.Kp / 32, s);
   else launch_gemm<T, DX_BWD>(g, (v.Kp + 127) / 128, 1, s);
 }
@@ -1416,6 +1471,7 @@ template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, 
   g.B = v.WpT; g.ldb = v.Np; g.Bf = v.WfT;
   g.Hp = v.Hp; g.l = e.q_l; g.r = e.q_r;
   g.C = v.dH;
+  g.add_c = v.dh_init;
   g.n_tiles_n = v.Kp / 32;
   const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
   if (small_tile_waves<T, DX_BWD>(g.K) == 8) {
@@ -1447,6 +1503,16 @@ void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad,
   int blocks = ((int)e.n_inst + 3) / 4;
   if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_head<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
   else hipLaunchKernelGGL(k_head<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
+}
+void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label,
+                   float* out_node_loss, const float* dnode, int with_grad, hipStream_t s) {
+  const uint32_t rows = n_leaf + n_cell;
+  if (!rows) return;
+  const int blocks = (int)std::min<uint32_t>((rows + 3) / 4, 16384u);
+  if (v.dtype == TDF_BF16)
+    hipLaunchKernelGGL(k_node_ce<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf, n_cell, node_label, out_node_loss, dnode, with_grad);
+  else
+    hipLaunchKernelGGL(k_node_ce<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf, n_cell, node_label, out_node_loss, dnode, with_grad);
 }
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s) {
   hipLaunchKernelGGL(k_seed_dy, dim3(e.n_inst), dim3(128), 0, s, v, e, dy);

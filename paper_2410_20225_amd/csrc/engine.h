@@ -109,6 +109,7 @@ struct Engine {
   uint32_t *q_out, *q_l, *q_r;      // [n_cell], sorted by level
   uint32_t* row_q;                  // [cap + n_inst]: position of a row's cell in the sorted log, ~0 for leaves (gradient runs)
   uint32_t *cq_l, *cq_r;            // [n_cell]: row_q of the two children
+  uint32_t* row_node;               // [cap + n_inst]: tree node whose loss term the row gets (CE_NODE), ~0: none
 };
 
 // The engine as machine d sees it.
@@ -243,6 +244,7 @@ struct VecArgs {
   float* dW_part;   // split partial sums [n_split x Np x Kp]
   uint32_t q_stride;
   float* loss;      // [B]
+  int dh_init;      // rows of dH start from the gradient of the row's own loss term (CE_NODE): consumers add to them
 };
 
 }  // namespace tdf

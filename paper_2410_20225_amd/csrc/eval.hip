@@ -34,6 +34,8 @@ void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, 
                   hipStream_t s);
 void vec_child_index(const Engine& e, uint32_t n_cell, hipStream_t s);
 void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s);
+void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label,
+                   float* out_node_loss, const float* dnode, int with_grad, hipStream_t s);
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s);
 void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s);
 int vec_dw_splits(uint32_t q_stride, int Np, int Kp);
@@ -95,7 +97,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   if (P.vec) {
     if (in->hidden < 1 || in->hidden > 8192 || in->vocab < 1) { set_error("bad hidden / vocab"); return TDF_ERR_BAD_ARG; }
     if (in->dtype != TDF_F32 && in->dtype != TDF_BF16) { set_error("bad dtype"); return TDF_ERR_BAD_ARG; }
-    if (G.has_head && (in->n_classes < 1 || in->n_classes > 16)) { set_error("n_classes must be 1..16"); return TDF_ERR_BAD_ARG; }
+    if ((G.has_head || G.has_node_loss) && (in->n_classes < 1 || in->n_classes > 16)) { set_error("n_classes must be 1..16"); return TDF_ERR_BAD_ARG; }
   }
   Layout& L = P.L;
   Engine& e = P.e;
@@ -149,6 +151,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_q_out = L.take(4 * rc), off_q_l = L.take(4 * rc), off_q_r = L.take(4 * rc);
   size_t off_row_q = with_grad ? L.take(4 * ((size_t)e.cap + e.n_inst)) : 0;
   size_t off_cq_l = with_grad ? L.take(4 * rc) : 0, off_cq_r = with_grad ? L.take(4 * rc) : 0;
+  size_t off_row_node = G.has_node_loss ? L.take(4 * ((size_t)e.cap + e.n_inst)) : 0;
   // logs of the single machines, merged into the arrays above after the last step
   size_t off_m[6] = {off_leaf_row, off_leaf_tok, off_c_out, off_c_l, off_c_r, off_c_lvl};
   if (e.n_dies > 1)
@@ -184,6 +187,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.row_q = with_grad ? (uint32_t*)at(off_row_q) : nullptr;
   e.cq_l = with_grad ? (uint32_t*)at(off_cq_l) : nullptr;
   e.cq_r = with_grad ? (uint32_t*)at(off_cq_r) : nullptr;
+  e.row_node = G.has_node_loss ? (uint32_t*)at(off_row_node) : nullptr;
   e.left = in->left;
   e.right = in->right;
   e.token = in->token;
@@ -203,6 +207,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.Kp = 2 * v.Hp;
     v.vocab = in->vocab;
     v.n_classes = in->n_classes;
+    v.dh_init = G.has_node_loss ? 1 : 0;
     v.E = in->E; v.W = in->W; v.b = in->b; v.U = in->U; v.u0 = in->u0;
     const size_t el = in->dtype == TDF_BF16 ? 2 : 4;
     const size_t R = (size_t)e.cap + B;   // one state row per frame
@@ -291,12 +296,14 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       set_error("forest or parameter pointer is NULL");
       return TDF_ERR_BAD_ARG;
     }
-    if (G.has_head && (!in->U || !in->u0)) { set_error("U / u0 is NULL"); return TDF_ERR_BAD_ARG; }
+    if ((G.has_head || G.has_node_loss) && (!in->U || !in->u0)) { set_error("U / u0 is NULL"); return TDF_ERR_BAD_ARG; }
+    if (G.has_node_loss && (!in->node_label || !out->out_node_loss)) { set_error("node_label or out_node_loss is NULL"); return TDF_ERR_BAD_ARG; }
+    if (G.has_node_loss && with_grad && (!dy || !dy->dnode)) { set_error("dnode is NULL"); return TDF_ERR_BAD_ARG; }
   }
   if (G.out_type == T_INT && !out->out_i64) { set_error("out_i64 is NULL"); return TDF_ERR_BAD_ARG; }
   if (G.out_type == T_LOSS && !out->out_f32) { set_error("out_f32 is NULL"); return TDF_ERR_BAD_ARG; }
   if (G.out_type == T_VEC && !out->out_h) { set_error("out_h is NULL"); return TDF_ERR_BAD_ARG; }
-  if (with_grad && (!dy || !dy->dy || !grads || !grads->dW || !grads->db || !grads->dE)) {
+  if (with_grad && (!dy || (!dy->dy && !G.has_node_loss) || !grads || !grads->dW || !grads->db || !grads->dE)) {
     set_error("dy or a gradient buffer is NULL");
     return TDF_ERR_BAD_ARG;
   }
@@ -356,6 +363,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     e.follow_limit = e.small_limit;
     if (const char* w = getenv("TDF_FOLLOW_LIMIT")) e.follow_limit = (uint32_t)std::max(0, atoi(w));
     HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
+    if (e.row_node) HIP_TRY(hipMemsetAsync(e.row_node, 0xFF, sizeof(uint32_t) * ((size_t)e.cap + e.n_inst), s));
     HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
     launch_seed(G.prog, e, s);
     Ctrl hcs[8];
@@ -450,9 +458,16 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       HIP_TRY(hipMemcpyAsync(out->out_f32, v.loss, sizeof(float) * e.n_inst, hipMemcpyDeviceToDevice, s));
     } else if (G.out_type == T_VEC) {
       vec_out_rows(v, e, out->out_h, out->out_c, s);
+      if (G.has_node_loss) {
+        // every state row that has a loss term: the term, and (gradient runs) its gradient as
+        // the initial value of the row's dh, which the row's consumer then adds to
+        HIP_TRY(hipMemsetAsync(out->out_node_loss, 0, sizeof(float) * (size_t)in->n_tree_nodes, s));
+        vec_node_loss(v, e, hc.n_leaf, hc.n_cell, in->node_label, out->out_node_loss, with_grad ? dy->dnode : nullptr,
+                      with_grad, s);
+      }
       if (with_grad) vec_seed_dy(v, e, dy->dy, s);
     }
-    end(TDF_PHASE_HEAD, 2);
+    end(TDF_PHASE_HEAD, G.has_node_loss ? 4 : 2);
     if (with_grad) {
       // ---- gradient pass: the level schedule walked backwards -----------------------------
       if (use_tail && hc.n_cell) {

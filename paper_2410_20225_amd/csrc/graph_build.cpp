@@ -29,7 +29,7 @@ int arity_of(int op, int n_in) {
     case TDF_OP_OUT: case TDF_OP_ID: case TDF_OP_TREE_ISLEAF: case TDF_OP_TREE_LEFT:
     case TDF_OP_TREE_RIGHT: case TDF_OP_TREE_TOKEN: case TDF_OP_EMBED: return 1;
     case TDF_OP_ADD: case TDF_OP_SUB: case TDF_OP_MUL: case TDF_OP_EQ: case TDF_OP_LT:
-    case TDF_OP_SWITCH: case TDF_OP_RNN_CELL: case TDF_OP_LSTM_CELL: case TDF_OP_CE_HEAD: return 2;
+    case TDF_OP_SWITCH: case TDF_OP_RNN_CELL: case TDF_OP_LSTM_CELL: case TDF_OP_CE_HEAD: case TDF_OP_CE_NODE: return 2;
     case TDF_OP_MERGE: case TDF_OP_CALLFN: case TDF_OP_LOOP: case TDF_OP_NEXT: return n_in;
   }
   return -1;
@@ -134,7 +134,7 @@ struct Builder {
             case TDF_OP_IN: case TDF_OP_CONST: case TDF_OP_ADD: case TDF_OP_SUB: case TDF_OP_MUL:
             case TDF_OP_EQ: case TDF_OP_LT: case TDF_OP_TREE_ISLEAF: case TDF_OP_TREE_LEFT:
             case TDF_OP_TREE_RIGHT: case TDF_OP_TREE_TOKEN: t = T_INT; break;
-            case TDF_OP_EMBED: case TDF_OP_RNN_CELL: case TDF_OP_LSTM_CELL: t = T_VEC; break;
+            case TDF_OP_EMBED: case TDF_OP_RNN_CELL: case TDF_OP_LSTM_CELL: case TDF_OP_CE_NODE: t = T_VEC; break;
             case TDF_OP_CE_HEAD: t = T_LOSS; break;
             case TDF_OP_ID: case TDF_OP_OUT: t = in_t(0); break;
             case TDF_OP_SWITCH: t = in_t(1); break;
@@ -161,7 +161,7 @@ struct Builder {
           case TDF_OP_TREE_ISLEAF: case TDF_OP_TREE_LEFT: case TDF_OP_TREE_RIGHT:
           case TDF_OP_TREE_TOKEN: case TDF_OP_EMBED: need(0, T_INT); break;
           case TDF_OP_RNN_CELL: case TDF_OP_LSTM_CELL: need(0, T_VEC); need(1, T_VEC); break;
-          case TDF_OP_CE_HEAD: need(0, T_VEC); need(1, T_INT); break;
+          case TDF_OP_CE_HEAD: case TDF_OP_CE_NODE: need(0, T_VEC); need(1, T_INT); break;
           case TDF_OP_SWITCH: need(0, T_INT); break;
           case TDF_OP_MERGE: for (int k = 0; k < nd.n_in; ++k) need(k, type[f][i]); break;
           case TDF_OP_CALLFN: case TDF_OP_LOOP: case TDF_OP_NEXT:
@@ -179,9 +179,11 @@ struct Builder {
           if (f != P->result_fn) bad("CE_HEAD is only allowed in result");
           G.has_head = true;
         }
+        if (nd.op == TDF_OP_CE_NODE) G.has_node_loss = true;
         if (type[f][i] == T_LOSS && f != P->result_fn) bad("loss values are only allowed in result");
       }
     }
+    if (G.has_head && G.has_node_loss) bad("CE_HEAD and CE_NODE in one program");
     G.out_type = ret_type[P->result_fn];
     G.n_result_params = F(P->result_fn).n_params;
     if (want_grad && G.out_type == T_INT) bad("gradient of an integer program");
@@ -375,6 +377,14 @@ struct Builder {
             push(nd.in[0], s, 0);
             break;
           }
+          case TDF_OP_CE_NODE: {
+            int s = add_snode(TDF_OP_CE_NODE, f, -1, -1, 1, 0);   // (row, node, drow) -> drow plus the term's gradient
+            add_edge(fwd(0), nd.in[0].port, s, 0, 0);
+            add_edge(fwd(1), nd.in[1].port, s, 1, 0);
+            add_edge(dy, dyp, s, 2, 0);
+            push(nd.in[0], s, 0);
+            break;
+          }
           default: bad("no gradient operator for a node on the differentiable path");
         }
       }
@@ -487,6 +497,7 @@ struct Builder {
           case TDF_OP_EMBED: I.op = D_EMBED; break;
           case TDF_OP_RNN_CELL: case TDF_OP_LSTM_CELL: I.op = D_CELL; break;
           case TDF_OP_CE_HEAD: I.op = D_HEAD; break;
+          case TDF_OP_CE_NODE: I.op = D_CE_NODE; break;
         }
         if (I.op == D_EMBED || I.op == D_CELL || I.op == D_HEAD) {
           if (n_stored >= MAX_STORED) bad("too many stored values in a function");

@@ -124,6 +124,12 @@ struct Gen {
           o << "          if (p && !d) r = sw_tree(x, " << val(I, 0) << ", " << (I.op - D_ISLEAF) << ", d);\n";
           o << "          v" << D << " = r; p" << D << " = p; d" << D << " = p && d; live = p && !d;\n";
           break;
+        case D_CE_NODE:
+          o << "          const bool p = on && " << pre(I, 0) << " && " << pre(I, 1) << "; bool d = " << ded(I, 0) << " || " << ded(I, 1)
+            << ";\n";
+          o << "          if (p && !d) sw_ce_node(x, " << val(I, 0) << ", " << val(I, 1) << ", d);\n";
+          o << "          v" << D << " = " << val(I, 0) << "; p" << D << " = p; d" << D << " = p && d; live = p && !d;\n";
+          break;
         case D_SWITCH: {
           const std::string D1 = std::to_string(I.dst + 1);
           o << "          const bool p = on && " << pre(I, 0) << " && " << pre(I, 1) << "; const bool d = " << ded(I, 0) << " || "

@@ -153,6 +153,18 @@ __device__ __forceinline__ long long sw_tree(LaneCtx& x, long long v, int which,
   }
   return which == 0 ? (long long)(x.tc_left < 0) : which == 1 ? x.tc_left : which == 2 ? x.tc_right : x.tc_token;
 }
+// CE_NODE: the row (= frame that produced the state) is marked with the tree node whose loss term
+// it gets; the row reference goes on unchanged.  Repeated by later sweeps of the frame with the
+// same values.
+__device__ __forceinline__ void sw_ce_node(LaneCtx& x, long long row, long long v, bool& dead) {
+  const Engine& e = *x.e;
+  if (v < 0 || v >= e.n_tree_nodes || e.row_node == nullptr) {
+    raise(x.c, TDF_ERR_BAD_ARG);
+    dead = true;
+    return;
+  }
+  e.row_node[(uint32_t)row] = (uint32_t)v;
+}
 // EMBED: the leaf's state row is the row of this frame, level 0.  Whole wave must call.
 __device__ __forceinline__ void sw_embed(LaneCtx& x, bool on, int slot, long long stored, bool ap, bool ad, long long av,
                                          long long& v, bool& p, bool& live) {
@@ -327,6 +339,15 @@ struct InterpSweep {
             long long r = 0;
             if (p && !d) r = sw_tree(x, a.v, I.op - D_ISLEAF, d);
             put(I.dst, r, p, p && d);
+            live = p && !d;
+            break;
+          }
+          case D_CE_NODE: {
+            const Src a = src(0), b = src(1);
+            const bool p = on && a.p && b.p;
+            bool d = a.d || b.d;
+            if (p && !d) sw_ce_node(x, a.v, b.v, d);
+            put(I.dst, a.v, p, p && d);
             live = p && !d;
             break;
           }

@@ -18,7 +18,7 @@ struct Graph {
   int n_labels = 0;
   int n_result_params = 0;
   int cell_kind = 0;        // 0 none, 1 RNN, 2 LSTM
-  bool has_embed = false, has_head = false, want_grad = false;
+  bool has_embed = false, has_head = false, has_node_loss = false, want_grad = false;
   int out_type = T_INT;     // type of result's output
 };
 

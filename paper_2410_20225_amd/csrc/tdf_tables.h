@@ -30,6 +30,7 @@ enum DevOp : uint8_t {
   D_CELL,     // aux = stored slot
   D_HEAD,     // aux = stored slot
   D_NEXT,     // Next of one loop variable: src[0] = value, aux2 = variable
+  D_CE_NODE,  // src[0] = row reference (handed on), src[1] = tree node whose loss term the row gets
 };
 
 constexpr uint8_t SRC_IMM = 0xFF;   // source is the instruction's immediate

@@ -84,9 +84,10 @@ def tak():
     return [r.desc(), f.desc()], 0
 
 
-def tree(cell="rnn", head=False):
+def tree(cell="rnn", head=False, node_loss=False):
     """f(v) = if isleaf(v) then embed(token(v)) else cell(f(left v), f(right v));
-    result(v) = f(v), or result(v, label) = ce_head(f(v), label)."""
+    result(v) = f(v), or result(v, label) = ce_head(f(v), label).  With node_loss every node
+    has a loss term of its own: f(v) = ce_node(if ..., v)."""
     r = _Fn("result", 2 if head else 1)
     y = r.add(T.OP_CALLFN, [r.add(T.OP_IN, imm=0)], imm=1)
     if head:
@@ -100,7 +101,8 @@ def tree(cell="rnn", head=False):
     hl = f.add(T.OP_CALLFN, [f.add(T.OP_TREE_LEFT, [inner])], imm=1)
     hr = f.add(T.OP_CALLFN, [f.add(T.OP_TREE_RIGHT, [inner])], imm=1)
     h = f.add(T.OP_RNN_CELL if cell == "rnn" else T.OP_LSTM_CELL, [hl, hr])
-    f.add(T.OP_OUT, [f.add(T.OP_MERGE, [e, h])])
+    s = f.add(T.OP_MERGE, [e, h])
+    f.add(T.OP_OUT, [f.add(T.OP_CE_NODE, [s, v]) if node_loss else s])
     return [r.desc(), f.desc()], 0
 
 

@@ -22,7 +22,7 @@ ERR_UNSUPPORTED = -7
 F32, BF16 = 0, 1
 (OP_IN, OP_OUT, OP_CONST, OP_ADD, OP_SUB, OP_MUL, OP_EQ, OP_LT, OP_ID, OP_SWITCH, OP_MERGE, OP_CALLFN,
  OP_TREE_ISLEAF, OP_TREE_LEFT, OP_TREE_RIGHT, OP_TREE_TOKEN, OP_EMBED, OP_RNN_CELL, OP_LSTM_CELL,
- OP_CE_HEAD, OP_LOOP, OP_NEXT) = range(22)
+ OP_CE_HEAD, OP_LOOP, OP_NEXT, OP_CE_NODE) = range(23)
 SNODE_MERGE_ENTRY, SNODE_CALL, SNODE_RETURN, SNODE_ENTER, SNODE_NEXT, SNODE_EXIT = 100, 101, 102, 103, 104, 105
 MAX_INPUTS = 4
 STATS_MAX_COUNTS = 256
@@ -64,6 +64,7 @@ class GraphInfo(C.Structure):
 class Inputs(C.Structure):
     _fields_ = [("n_instances", C.c_int32), ("n_args", C.c_int32), ("args", C.c_void_p),
                 ("n_tree_nodes", C.c_int32), ("left", C.c_void_p), ("right", C.c_void_p), ("token", C.c_void_p),
+                ("node_label", C.c_void_p),
                 ("dtype", C.c_int32), ("hidden", C.c_int32), ("vocab", C.c_int32),
                 ("E", C.c_void_p), ("W", C.c_void_p), ("b", C.c_void_p),
                 ("n_classes", C.c_int32), ("U", C.c_void_p), ("u0", C.c_void_p),
@@ -71,11 +72,12 @@ class Inputs(C.Structure):
 
 
 class Outputs(C.Structure):
-    _fields_ = [("out_i64", C.c_void_p), ("out_f32", C.c_void_p), ("out_h", C.c_void_p), ("out_c", C.c_void_p)]
+    _fields_ = [("out_i64", C.c_void_p), ("out_f32", C.c_void_p), ("out_h", C.c_void_p), ("out_c", C.c_void_p),
+                ("out_node_loss", C.c_void_p)]
 
 
 class Seed(C.Structure):
-    _fields_ = [("dy", C.c_void_p)]
+    _fields_ = [("dy", C.c_void_p), ("dnode", C.c_void_p)]
 
 
 class Grads(C.Structure):
@@ -183,9 +185,10 @@ def graph_precompile(graph, arch="gfx950"):
 
 
 def make_inputs(n_instances, args=None, n_args=0, left=None, right=None, token=None, dtype=F32, hidden=0,
-                vocab=0, E=None, W=None, b=None, U=None, u0=None, n_classes=0, max_tags=0, step_limit=0, stats_level=1):
+                vocab=0, E=None, W=None, b=None, U=None, u0=None, n_classes=0, max_tags=0, step_limit=0, stats_level=1,
+                node_label=None):
     n_tree = 0 if left is None else int(left.numel())
-    return Inputs(n_instances, n_args, _ptr(args), n_tree, _ptr(left), _ptr(right), _ptr(token), dtype, hidden,
+    return Inputs(n_instances, n_args, _ptr(args), n_tree, _ptr(left), _ptr(right), _ptr(token), _ptr(node_label), dtype, hidden,
                   vocab, _ptr(E), _ptr(W), _ptr(b), n_classes, _ptr(U), _ptr(u0), max_tags, step_limit, stats_level)
 
 
@@ -201,9 +204,9 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def eval(graph, inputs, workspace, out_i64=None, out_f32=None, out_h=None, out_c=None, check=True):
+def eval(graph, inputs, workspace, out_i64=None, out_f32=None, out_h=None, out_c=None, out_node_loss=None, check=True):
     """Returns (status, Stats)."""
-    outs = Outputs(_ptr(out_i64), _ptr(out_f32), _ptr(out_h), _ptr(out_c))
+    outs = Outputs(_ptr(out_i64), _ptr(out_f32), _ptr(out_h), _ptr(out_c), _ptr(out_node_loss))
     stats = Stats()
     st = lib.tdf_eval(graph.handle, C.byref(inputs), C.byref(outs), _ptr(workspace),
                       workspace.numel() * workspace.element_size(), _stream(), C.byref(stats))
@@ -212,9 +215,10 @@ def eval(graph, inputs, workspace, out_i64=None, out_f32=None, out_h=None, out_c
     return st, stats
 
 
-def eval_grad(graph, inputs, dy, workspace, dW, db, dE, out_f32=None, out_h=None, out_c=None, check=True):
-    outs = Outputs(None, _ptr(out_f32), _ptr(out_h), _ptr(out_c))
-    seed = Seed(_ptr(dy))
+def eval_grad(graph, inputs, dy, workspace, dW, db, dE, out_f32=None, out_h=None, out_c=None, out_node_loss=None,
+              dnode=None, check=True):
+    outs = Outputs(None, _ptr(out_f32), _ptr(out_h), _ptr(out_c), _ptr(out_node_loss))
+    seed = Seed(_ptr(dy), _ptr(dnode))
     grads = Grads(_ptr(dW), _ptr(db), _ptr(dE))
     stats = Stats()
     st = lib.tdf_eval_grad(graph.handle, C.byref(inputs), C.byref(seed), C.byref(outs), C.byref(grads),

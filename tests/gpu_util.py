@@ -37,16 +37,34 @@ def run_oracle_tree(c, head, grad, dy=None):
     return dict(out=out[("out", 0)], grads=it.param_grad, it=it)
 
 
+def run_oracle_node_loss(c, node_labels, dnode=None, dy=None, ids=None):
+    """Per-node losses (and gradients when dnode is given) of the trees `ids` (default: all)."""
+    F = c["forest"]
+    roots = F.roots.tolist() if ids is None else [int(F.roots[b]) for b in ids]
+    prog = oracle_programs.tree_program(c["cell"], node_loss=True)
+    env = oracle_env(c)
+    env["node_label"] = node_labels
+    inputs = {("in", 0): roots}
+    if dnode is not None:
+        prog = oracle.differentiate(prog)
+        env["dnode"] = dnode
+        D = c["H"] * (2 if c["cell"] == "lstm" else 1)
+        inputs[("gin", 0)] = list(np.zeros((len(roots), D)) if dy is None else dy)
+    it = oracle.Interpreter(oracle.transform(prog), env)
+    out = it.run(inputs, len(roots))
+    return dict(out=out[("out", 0)], node_loss=it.node_loss, grads=it.param_grad, it=it)
+
+
 class TreeRun:
     """One workload resident on the GPU plus the buffers of one evaluation."""
 
-    def __init__(self, c, head, grad, max_tags=None, step_limit=0, stats_level=1):
+    def __init__(self, c, head, grad, max_tags=None, step_limit=0, stats_level=1, node_labels=None):
         F = c["forest"]
         self.c, self.head, self.grad = c, head, grad
         self.B, self.H = F.n_trees, c["H"]
         dt = torch.bfloat16 if c["bf16"] else torch.float32
         self.rows = (5 if c["cell"] == "lstm" else 1) * self.H
-        fns, r = gpu_programs.tree(c["cell"], head=head)
+        fns, r = gpu_programs.tree(c["cell"], head=head, node_loss=node_labels is not None)
         self.graph = tdf.graph_build(fns, r, want_grad=grad)
         args = np.stack([F.roots, c["labels"]], 1) if head else F.roots[:, None]
         t = lambda a, d: torch.tensor(np.ascontiguousarray(a), dtype=d, device=DEV)
@@ -55,11 +73,16 @@ class TreeRun:
         self.t_E, self.t_W = t(c["E"], dt), t(c["W"], dt)
         self.t_b, self.t_U, self.t_u0 = t(c["b"], torch.float32), t(c["U"], torch.float32), t(c["u0"], torch.float32)
         self.max_tags = F.n_nodes if max_tags is None else max_tags
+        self.t_node_label = self.out_node_loss = None
+        if node_labels is not None:
+            self.t_node_label = t(node_labels, torch.int32)
+            self.out_node_loss = torch.full((F.n_nodes,), -7.0, dtype=torch.float32, device=DEV)
         self.inputs = tdf.make_inputs(self.B, args=self.t_args, n_args=args.shape[1], left=self.t_left,
                                       right=self.t_right, token=self.t_token,
                                       dtype=tdf.BF16 if c["bf16"] else tdf.F32, hidden=self.H, vocab=c["V"],
                                       E=self.t_E, W=self.t_W, b=self.t_b, U=self.t_U, u0=self.t_u0,
-                                      n_classes=5, max_tags=self.max_tags, step_limit=step_limit, stats_level=stats_level)
+                                      n_classes=5, max_tags=self.max_tags, step_limit=step_limit, stats_level=stats_level,
+                                      node_label=self.t_node_label)
         nbytes = tdf.workspace_size(self.graph, self.inputs, grad)
         self.ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
         self.out_f32 = torch.zeros(self.B, dtype=torch.float32, device=DEV)
@@ -70,14 +93,16 @@ class TreeRun:
             self.db = torch.empty(self.rows, dtype=torch.float32, device=DEV)
             self.dE = torch.empty(c["V"], self.H, dtype=torch.float32, device=DEV)
 
-    def run(self, dy=None, check=True):
+    def run(self, dy=None, check=True, dnode=None):
         if self.grad:
-            self.t_dy = torch.tensor(np.ascontiguousarray(dy), dtype=torch.float32, device=DEV)
+            f32 = lambda a: None if a is None else torch.tensor(np.ascontiguousarray(a), dtype=torch.float32, device=DEV)
+            self.t_dy, self.t_dnode = f32(dy), f32(dnode)
             st, stats = tdf.eval_grad(self.graph, self.inputs, self.t_dy, self.ws, self.dW, self.db, self.dE,
-                                      out_f32=self.out_f32, out_h=self.out_h, out_c=self.out_c, check=check)
+                                      out_f32=self.out_f32, out_h=self.out_h, out_c=self.out_c,
+                                      out_node_loss=self.out_node_loss, dnode=self.t_dnode, check=check)
         else:
             st, stats = tdf.eval(self.graph, self.inputs, self.ws, out_f32=self.out_f32, out_h=self.out_h,
-                                 out_c=self.out_c, check=check)
+                                 out_c=self.out_c, out_node_loss=self.out_node_loss, check=check)
         torch.cuda.synchronize()
         return st, stats
 
@@ -88,7 +113,8 @@ def fire_counts(graph, stats):
              tdf.OP_EQ: "eq", tdf.OP_LT: "lt", tdf.OP_ID: "id", tdf.OP_SWITCH: "switch", tdf.OP_MERGE: "merge",
              tdf.SNODE_MERGE_ENTRY: "merge_entry", tdf.OP_TREE_ISLEAF: "isleaf", tdf.OP_TREE_LEFT: "left",
              tdf.OP_TREE_RIGHT: "right", tdf.OP_TREE_TOKEN: "token", tdf.OP_EMBED: "embed",
-             tdf.OP_RNN_CELL: "rnn_cell", tdf.OP_LSTM_CELL: "lstm_cell", tdf.OP_CE_HEAD: "ce_head"}
+             tdf.OP_RNN_CELL: "rnn_cell", tdf.OP_LSTM_CELL: "lstm_cell", tdf.OP_CE_HEAD: "ce_head",
+             tdf.OP_CE_NODE: "ce_node"}
     out = {}
     for i, n in enumerate(tdf.graph_info(graph)["nodes"]):
         if n["is_grad"] or n["kind"] == tdf.OP_CONST:

@@ -106,6 +106,7 @@ def test_workspace_size_grows_with_capacity():
     ("treernn", lambda: programs.tree("rnn", False), False),
     ("treelstm_head_grad", lambda: programs.tree("lstm", True), True),
     ("ack", programs.ack, False), ("tak", programs.tak, False),
+    ("treelstm_node_loss_grad", lambda: programs.tree("lstm", node_loss=True), True),
 ])
 def test_generated_step_kernels_compile_for_gfx950(name, prog, grad):
     # the firing tables of every workload turn into HIP source that the run-time compiler
@@ -153,6 +154,33 @@ def test_static_graph_of_loops_is_the_oracles(name):
     assert Counter(_KIND_NAMES[n["kind"]] for n in nodes) == Counter(nd.op for nd in sg.nodes)
     assert info["n_labels"] == len(sg.labels)
     assert tdf.graph_precompile(g, "gfx950") > 0
+
+
+def test_node_loss_operator_in_the_static_and_the_joint_graph():
+    # the per-node loss operator sits between the Merge of a node's state and the function output;
+    # its gradient operator takes the two forward inputs and the output gradient (Section 4)
+    import oracle
+    from oracle import programs as oprog
+    from collections import Counter
+    names = dict(_KIND_NAMES)
+    names.update({tdf.OP_TREE_ISLEAF: "isleaf", tdf.OP_TREE_LEFT: "left", tdf.OP_TREE_RIGHT: "right",
+                  tdf.OP_TREE_TOKEN: "token", tdf.OP_EMBED: "embed", tdf.OP_RNN_CELL: "rnn_cell", tdf.OP_CE_NODE: "ce_node"})
+    fns, r = programs.tree("rnn", node_loss=True)
+    info = tdf.graph_info(tdf.graph_build(fns, r))
+    nodes = info["nodes"]
+    got = Counter((names[nodes[e["src"]]["kind"]], names[nodes[e["dst"]]["kind"]], "control" if e["is_control"] else "data")
+                  for e in info["edges"])
+    sg = oracle.transform(oprog.tree_program("rnn", node_loss=True))
+    assert got == Counter((sg.nodes[s].op, sg.nodes[d].op, kind) for s, d, kind in sg.edge_list())
+    joint = tdf.graph_info(tdf.graph_build(fns, r, want_grad=True))
+    g = [i for i, n in enumerate(joint["nodes"]) if n["kind"] == tdf.OP_CE_NODE and n["is_grad"]]
+    assert len(g) == 1
+    ins = sorted((e["dst_slot"], names.get(joint["nodes"][e["src"]]["kind"]), joint["nodes"][e["src"]]["is_grad"])
+                 for e in joint["edges"] if e["dst"] == g[0])
+    assert ins == [(0, "merge", 0), (1, "merge_entry", 0), (2, "merge_entry", 1)]   # state, node, gradient of f's output
+    fns2, r2 = programs.tree("rnn", head=True)
+    with pytest.raises(tdf.TdfError, match="CE_HEAD and CE_NODE"):   # not together with the root-only head
+        tdf.graph_build([fns2[0], fns[1]], r2)
 
 
 def test_malformed_loops_are_rejected():
