@@ -45,7 +45,7 @@ def measured_traffic(cfg, which):
     return nbytes if now == sha else None
 
 
-def cpu_baseline(cfg, budget_trees):
+def cpu_baseline(cfg, budget_trees, node_loss=False):
     """The oracle, as it stands, on the first trees of the same workload."""
     import numpy as np
     import oracle
@@ -74,16 +74,20 @@ def cpu_baseline(cfg, budget_trees):
     c = make_config(cfg)
     F = c["forest"].subset(range(budget_trees))
     grad = c["grad"]
-    prog = oprog.tree_program(c["cell"], head=grad)
+    prog = oprog.tree_program(c["cell"], head=grad and not node_loss, node_loss=node_loss)
     if grad:
         prog = oracle.differentiate(prog)
     env = dict(left=F.left, right=F.right, token=F.token, E=c["E"], W=c["W"], b=c["b"], U=c["U"], u0=c["u0"])
-    it = oracle.Interpreter(oracle.transform(prog), env)
     B = F.n_trees
     inputs = {("in", 0): F.roots.tolist()}
-    if grad:
+    if node_loss:     # the first trees' nodes are the first nodes of the forest
+        env["node_label"] = c["node_labels"][:F.n_nodes]
+        env["dnode"] = np.full(F.n_nodes, 1.0 / F.n_nodes)
+        inputs[("gin", 0)] = list(np.zeros((B, c["H"] * (2 if c["cell"] == "lstm" else 1))))
+    elif grad:
         inputs[("in", 1)] = c["labels"][:B].tolist()
         inputs[("gin", 0)] = [1.0 / B] * B
+    it = oracle.Interpreter(oracle.transform(prog), env)
     t0 = time.perf_counter()
     it.run(inputs, B)
     dt = time.perf_counter() - t0
@@ -100,6 +104,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload 1..6 (default 4: TreeLSTM forward+gradient)")
+    ap.add_argument("--node-loss", action="store_true",
+                    help="workloads 3..5 with a loss term at every tree node instead of the root only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle's sample (0 = auto)")
     a = ap.parse_args()
@@ -114,6 +120,9 @@ def main():
 
     cfg = a.config
     dev = "cuda:0"
+    if a.node_loss and cfg not in (3, 4, 5):
+        print("--node-loss applies to workloads 3, 4 and 5", file=sys.stderr)
+        sys.exit(2)
     if cfg == 1:
         fns, r = programs.fib()
         g = tdf.graph_build(fns, r)
@@ -138,10 +147,15 @@ def main():
         from gpu_util import TreeRun
         c = make_config(cfg)
         grad = c["grad"]
-        run = TreeRun(c, head=grad, grad=grad, stats_level=0)
-        B = run.B
-        dy = np.full(B, 1.0 / B)
-        step = lambda: run.run(dy if grad else None)[1]
+        B = c["forest"].n_trees
+        if a.node_loss:
+            run = TreeRun(c, head=False, grad=True, stats_level=0, node_labels=c["node_labels"])
+            dnode = np.full(c["forest"].n_nodes, 1.0 / c["forest"].n_nodes)
+            step = lambda: run.run(None, dnode=dnode)[1]
+        else:
+            run = TreeRun(c, head=grad, grad=grad, stats_level=0)
+            dy = np.full(B, 1.0 / B)
+            step = lambda: run.run(dy if grad else None)[1]
         passes = 2 if grad else 1
         dtype = "bf16" if c["bf16"] else "f32"
         cell = c["cell"]
@@ -201,7 +215,7 @@ def main():
         roof = {"bound": "mfma", "kernel": "k_gemm + k_tail_fwd <%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
                 "achieved": flops_fwd / (ms * 1e-3) / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
                 "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1),
-                "traffic": measured_traffic(cfg, "cells")}
+                "traffic": None if a.node_loss else measured_traffic(cfg, "cells")}
         # the same, split by level width: one launch per wide level, one launch for the whole narrow tail
         wide_ms, tail_ms = phase[i_fwd] / a.steps, phase[i_tail] / a.steps
         wide_cells = int(st.n_wide_cells)
@@ -216,7 +230,8 @@ def main():
     rec = {"metric": "tagged node firings/sec at 1 GPU", "value": value, "unit": "firings/s", "n_gpus": 1,
            "steps": a.steps, "warmup": a.warmup, "ms_per_step": 1e3 * dt / a.steps, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-           "config": {"workload": "config %d: %s" % (cfg, CONFIG_NAMES[cfg]), "n_tags": n_tags,
+           "config": {"workload": "config %d: %s%s" % (cfg, CONFIG_NAMES[cfg], ", a loss term at every node" if a.node_loss else ""),
+                      "n_tags": n_tags,
                       "firings_per_step": firings, "n_steps_tag_machine": int(st.n_steps),
                       "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth)},
            "phase_ms": phase_ms, "roofline": roof}
@@ -224,7 +239,7 @@ def main():
         rec["roofline_tag_machine"] = roof_tags
     if not a.no_cpu_baseline:
         trees = a.cpu_trees or {1: 0, 2: 256, 3: 1024, 4: 1024, 5: 2, 6: 2048}[cfg]
-        rec["cpu_baseline"] = cpu_baseline(cfg, trees)
+        rec["cpu_baseline"] = cpu_baseline(cfg, trees, a.node_loss)
     print(json.dumps(rec))
 
 

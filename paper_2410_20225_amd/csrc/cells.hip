@@ -104,7 +104,6 @@ struct GemmArgs {
   int n_splits;
   int n_tiles_n;             // column tiles of the launch
   int save_gates;
-  int add_c;                 // DX_BWD: the rows of C already hold a term; the product is added to it
 };
 
 constexpr int BM_FULL = 128;   // rows of a workgroup tile; half of it for levels that would not fill the GPU
@@ -316,8 +315,8 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
             reinterpret_cast<T*>(g.Hs_out)[(size_t)sOut[row] * g.Hp + n] = from_f<T>(Act<T>::tanh(acc[i][j][r] + bias));
           } else if constexpr (MODE == DX_BWD) {
             // column n of [dh_l; dh_r]: each child row has exactly one consumer, plain store
-            float* c = n < g.Hp ? g.C + (size_t)sL[row] * g.Hp + n : g.C + (size_t)sR[row] * g.Hp + (n - g.Hp);
-            *c = acc[i][j][r] + (g.add_c ? *c : 0.f);
+            if (n < g.Hp) g.C[(size_t)sL[row] * g.Hp + n] = acc[i][j][r];
+            else g.C[(size_t)sR[row] * g.Hp + (n - g.Hp)] = acc[i][j][r];
           } else {
             g.C[(size_t)split * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
           }
@@ -511,7 +510,7 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
 
   // fused dz (DX_BWD in the tail): which child cell, and what its dz needs, requested early
   uint32_t z_q[RPW], z_row[RPW], z_gl[RPW], z_gr[RPW];
-  float z_gate[RPW][5], z_c[RPW], z_dc[RPW], z_h[RPW];
+  float z_gate[RPW][5], z_c[RPW], z_dc[RPW], z_h[RPW], z_own[RPW];
   const bool z_on = MODE == DX_BWD && fz != nullptr;
   const bool z_left = unit < g.Hp;
   const int z_n = z_left ? unit : unit - g.Hp;
@@ -538,6 +537,7 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
       if (!ok) z_q[rr] = 0xFFFFFFFFu;
       const uint32_t qc = ok ? z_q[rr] : 0u;   // (cell 0 exists whenever a level has cells: a safe address)
       const size_t o = (size_t)z_row[rr] * v.Hp + z_n;
+      z_own[rr] = v.dHn ? v.dHn[o] : 0.f;   // gradient of the child's own loss term
       if (v.cell_kind == 1) {
         z_h[rr] = to_f(reinterpret_cast<const T*>(v.Hs)[o]);
       } else {
@@ -636,9 +636,8 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
     for (int rr = 0; rr < RPW; ++rr) {
       const int m = m0 + row_of(rr);
       if (m >= g.M) continue;
-      float* c = unit < g.Hp ? g.C + (size_t)o_l[rr] * g.Hp + unit : g.C + (size_t)o_r[rr] * g.Hp + (unit - g.Hp);
-      if (g.add_c) z[0][rr] += *c;   // (the sum is also what the children's dz below is formed from)
-      *c = z[0][rr];
+      if (unit < g.Hp) g.C[(size_t)o_l[rr] * g.Hp + unit] = z[0][rr];
+      else g.C[(size_t)o_r[rr] * g.Hp + (unit - g.Hp)] = z[0][rr];
     }
     if (z_on) {
       const VecArgs& v = *fz->v;
@@ -654,7 +653,7 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
       for (int rr = 0; rr < RPW; ++rr) {
         const int m = m0 + row_of(rr);
         if (m >= g.M || z_q[rr] == 0xFFFFFFFFu) continue;
-        const float dh = z[0][rr];
+        const float dh = z[0][rr] + z_own[rr];
         T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)z_q[rr] * v.Np + z_n;
         if (v.cell_kind == 1) {
           dz[0] = from_f<T>(dh * (1.f - z_h[rr] * z_h[rr]));
@@ -788,52 +787,100 @@ __global__ void k_head(VecArgs v, Engine e, const float* dy, int with_grad) {
   }
 }
 
-// Loss terms of the nodes (CE_NODE): one wave per state row.  A row that was marked with a tree
-// node v whose label is a class gets loss[v] = -log softmax(U h + u0)[label]; in a gradient run
-// the row's dh starts as dnode[v] U^T (p - onehot), 0 for rows without a term, and the row's
-// consumer (the parent's input gradient, the caller's dy at a root) adds to it.
+// Loss terms of the nodes (CE_NODE): sixteen lanes per state row, four rows per wave, U in LDS
+// (padded to the row stride) where it fits.  A row that was marked with a tree node v whose
+// label is a class gets loss[v] = -log softmax(U h + u0)[label]; in a gradient run the row of
+// dHn becomes dnode[v] U^T (p - onehot), 0 for rows without a term.
 template <int DT>
-__global__ void k_node_ce(VecArgs v, Engine e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label, float* out_loss,
-                          const float* dnode, int with_grad) {
+__global__ void __launch_bounds__(256) k_node_ce(VecArgs v, Engine e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label,
+                                                 float* out_loss, const float* dnode, int with_grad, int u_in_lds) {
   typedef typename TypeOf<DT>::type T;
-  const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
-  const uint32_t n_waves = (gridDim.x * blockDim.x) >> 6;
-  for (uint32_t i = wave; i < n_leaf + n_cell; i += n_waves) {
+  constexpr int CH = 16 / (int)sizeof(T);   // elements of a 16-byte chunk of a state row
+  extern __shared__ __attribute__((aligned(16))) float sU[];
+  if (u_in_lds) {
+    for (int i = threadIdx.x; i < v.n_classes * v.Hp; i += blockDim.x) {
+      const int c = i / v.Hp, n = i % v.Hp;
+      sU[i] = n < v.H ? v.U[c * v.H + n] : 0.f;
+    }
+    __syncthreads();
+  }
+  auto u_at4 = [&](int c, int n) -> float4 {   // U[c][n .. n+3], zero beyond H
+    if (u_in_lds) return *reinterpret_cast<const float4*>(sU + c * v.Hp + n);
+    const float* u = v.U + (size_t)c * v.H;
+    return make_float4(n < v.H ? u[n] : 0.f, n + 1 < v.H ? u[n + 1] : 0.f, n + 2 < v.H ? u[n + 2] : 0.f, n + 3 < v.H ? u[n + 3] : 0.f);
+  };
+  const int sub = threadIdx.x & 15;
+  const uint32_t grp = (blockIdx.x * blockDim.x + threadIdx.x) >> 4, n_grp = (gridDim.x * blockDim.x) >> 4;
+  for (uint32_t i = grp; i < n_leaf + n_cell; i += n_grp) {
     const uint32_t row = i < n_leaf ? e.leaf_row[i] : e.q_out[i - n_leaf];
     const uint32_t node = e.row_node[row];
     int label = -1;
     if (node != 0xFFFFFFFFu) label = node_label[node];
     if (label >= v.n_classes) label = -1;
-    float* dh = with_grad ? v.dH + (size_t)row * v.Hp : nullptr;
-    if (label < 0) {
+    float* dh = with_grad ? v.dHn + (size_t)row * v.Hp : nullptr;
+    if (label < 0) {   // (the sixteen lanes of a row take this branch together)
       if (with_grad)
-        for (int n = lane; n < v.Hp; n += 64) dh[n] = 0.f;
+        for (int n = sub * 4; n < v.Hp; n += 64) *reinterpret_cast<float4*>(dh + n) = make_float4(0.f, 0.f, 0.f, 0.f);
       continue;
     }
     const T* h = reinterpret_cast<const T*>(v.Hs) + (size_t)row * v.Hp;
     float logit[16];
-    float mx = -3.0e38f;
-    for (int c = 0; c < v.n_classes; ++c) {
-      float s = 0.f;
-      for (int n = lane; n < v.H; n += 64) s += v.U[c * v.H + n] * to_f(h[n]);
-      for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
-      logit[c] = s + v.u0[c];
-      mx = fmaxf(mx, logit[c]);
+#pragma unroll
+    for (int c = 0; c < 16; ++c) logit[c] = 0.f;
+    for (int n0 = sub * CH; n0 < v.Hp; n0 += 16 * CH) {
+      union { u32x4 raw; T t[CH]; } x;
+      x.raw = *reinterpret_cast<const u32x4*>(h + n0);
+      float xf[CH];
+#pragma unroll
+      for (int j = 0; j < CH; ++j) xf[j] = to_f(x.t[j]);
+#pragma unroll
+      for (int c = 0; c < 16; ++c)
+        if (c < v.n_classes) {
+#pragma unroll
+          for (int j = 0; j < CH; j += 4) {
+            const float4 u = u_at4(c, n0 + j);
+            logit[c] += u.x * xf[j] + u.y * xf[j + 1] + u.z * xf[j + 2] + u.w * xf[j + 3];
+          }
+        }
     }
-    float z = 0.f;
-    for (int c = 0; c < v.n_classes; ++c) z += expf(logit[c] - mx);
+    float mx = -3.0e38f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c)
+      if (c < v.n_classes) {
+        float s = logit[c];
+        for (int off = 8; off > 0; off >>= 1) s += __shfl_xor(s, off);
+        logit[c] = s + v.u0[c];
+        mx = fmaxf(mx, logit[c]);
+      }
+    float z = 0.f, own = 0.f;
+#pragma unroll
+    for (int c = 0; c < 16; ++c)
+      if (c < v.n_classes) {
+        z += expf(logit[c] - mx);
+        own = c == label ? logit[c] : own;
+      }
     const float lse = mx + logf(z);
-    float own = 0.f;
-    for (int c = 0; c < v.n_classes; ++c) own = c == label ? logit[c] : own;
-    if (lane == 0) out_loss[node] = lse - own;
+    if (sub == 0) out_loss[node] = lse - own;
     if (with_grad) {
       const float d = dnode[node];
-      for (int n = lane; n < v.Hp; n += 64) {
-        float s = 0.f;
-        if (n < v.H)
-          for (int c = 0; c < v.n_classes; ++c)
-            s += (expf(logit[c] - lse) - (c == label ? 1.f : 0.f)) * v.U[c * v.H + n];
-        dh[n] = s * d;
+#pragma unroll
+      for (int c = 0; c < 16; ++c)   // logit becomes d (p - onehot)
+        if (c < v.n_classes) logit[c] = d * (expf(logit[c] - lse) - (c == label ? 1.f : 0.f));
+      for (int n0 = sub * CH; n0 < v.Hp; n0 += 16 * CH) {
+        float g[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) g[j] = 0.f;
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+          if (c < v.n_classes) {
+#pragma unroll
+            for (int j = 0; j < CH; j += 4) {
+              const float4 u = u_at4(c, n0 + j);
+              g[j] += logit[c] * u.x; g[j + 1] += logit[c] * u.y; g[j + 2] += logit[c] * u.z; g[j + 3] += logit[c] * u.w;
+            }
+          }
+#pragma unroll
+        for (int j = 0; j < CH; j += 4) *reinterpret_cast<float4*>(dh + n0 + j) = make_float4(g[j], g[j + 1], g[j + 2], g[j + 3]);
       }
     }
   }
@@ -844,8 +891,7 @@ __global__ void k_seed_dy(VecArgs v, Engine e, const float* dy) {
   const int b = blockIdx.x;
   const uint32_t row = e.root_ref[b];
   for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
-    const float own = v.dh_init ? v.dH[(size_t)row * v.Hp + n] : 0.f;
-    v.dH[(size_t)row * v.Hp + n] = own + (dy && n < v.H ? dy[(size_t)b * v.H + n] : 0.f);
+    v.dH[(size_t)row * v.Hp + n] = dy && n < v.H ? dy[(size_t)b * v.H + n] : 0.f;
     if (v.cell_kind == 2) v.dC[(size_t)row * v.Hp + n] = 0.f;
   }
 }
@@ -872,7 +918,7 @@ __device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32
   if (v.cell_kind == 1) {
     for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
       const float h = to_f(reinterpret_cast<const T*>(v.Hs)[o + n]);
-      dz[n] = from_f<T>(v.dH[o + n] * (1.f - h * h));
+      dz[n] = from_f<T>((v.dH[o + n] + (v.dHn ? v.dHn[o + n] : 0.f)) * (1.f - h * h));
     }
   } else {
     const size_t ol = (size_t)e.q_l[q] * v.Hp, orr = (size_t)e.q_r[q] * v.Hp;
@@ -881,7 +927,7 @@ __device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32
       const float gi = to_f(gt[n]), gfl = to_f(gt[v.Hp + n]), gfr = to_f(gt[2 * v.Hp + n]);
       const float go = to_f(gt[3 * v.Hp + n]), gu = to_f(gt[4 * v.Hp + n]);
       const float tc = Act<T>::tanh(v.Cs[o + n]);
-      const float dh = v.dH[o + n];
+      const float dh = v.dH[o + n] + (v.dHn ? v.dHn[o + n] : 0.f);
       const float dc = v.dC[o + n] + dh * go * (1.f - tc * tc);
       const float cl = v.Cs[ol + n], cr = v.Cs[orr + n];
       dz[n] = from_f<T>(dc * gu * gi * (1.f - gi));
@@ -1343,6 +1389,15 @@ __global__ void k_de_partial(VecArgs v, const uint32_t* seg_off, const uint32_t*
           if (p + j < p_hi) {
             s.x += x[j].x; s.y += x[j].y; s.z += x[j].z; s.w += x[j].w;
           }
+        if (v.dHn) {   // the leaves' own loss terms
+#pragma unroll
+          for (int j = 0; j < 8; ++j) x[j] = *reinterpret_cast<const float4*>(v.dHn + (size_t)row[j] * v.Hp + n);
+#pragma unroll
+          for (int j = 0; j < 8; ++j)
+            if (p + j < p_hi) {
+              s.x += x[j].x; s.y += x[j].y; s.z += x[j].z; s.w += x[j].w;
+            }
+        }
       }
       *reinterpret_cast<float4*>(part + (size_t)c * v.Hp + n) = s;
     }
@@ -1422,7 +1477,6 @@ template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, 
   g.B = v.WpT; g.ldb = v.Np; g.Bf = v.WfT;
   g.Hp = v.Hp; g.l = e.q_l + q0; g.r = e.q_r + q0;
   g.C = v.dH;
-  g.add_c = v.dh_init;
   if (count <= small_level()) launch_cell_small<T, DX_BWD>(g, v.Kp / 32, s);
   else launch_gemm<T, DX_BWD>(g, (v.Kp + 127) / 128, 1, s);
 }
@@ -1471,7 +1525,6 @@ template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, 
   g.B = v.WpT; g.ldb = v.Np; g.Bf = v.WfT;
   g.Hp = v.Hp; g.l = e.q_l; g.r = e.q_r;
   g.C = v.dH;
-  g.add_c = v.dh_init;
   g.n_tiles_n = v.Kp / 32;
   const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
   if (small_tile_waves<T, DX_BWD>(g.K) == 8) {
@@ -1508,11 +1561,16 @@ void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t 
                    float* out_node_loss, const float* dnode, int with_grad, hipStream_t s) {
   const uint32_t rows = n_leaf + n_cell;
   if (!rows) return;
-  const int blocks = (int)std::min<uint32_t>((rows + 3) / 4, 16384u);
+  const int blocks = (int)std::min<uint32_t>((rows + 15) / 16, 2048u);
+  const size_t u_bytes = (size_t)v.n_classes * v.Hp * sizeof(float);
+  const int u_in_lds = u_bytes <= 48 * 1024;
+  const size_t lds = u_in_lds ? u_bytes : 0;
   if (v.dtype == TDF_BF16)
-    hipLaunchKernelGGL(k_node_ce<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf, n_cell, node_label, out_node_loss, dnode, with_grad);
+    hipLaunchKernelGGL(k_node_ce<TDF_BF16>, dim3(blocks), dim3(256), lds, s, v, e, n_leaf, n_cell, node_label, out_node_loss, dnode,
+                       with_grad, u_in_lds);
   else
-    hipLaunchKernelGGL(k_node_ce<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf, n_cell, node_label, out_node_loss, dnode, with_grad);
+    hipLaunchKernelGGL(k_node_ce<TDF_F32>, dim3(blocks), dim3(256), lds, s, v, e, n_leaf, n_cell, node_label, out_node_loss, dnode,
+                       with_grad, u_in_lds);
 }
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s) {
   hipLaunchKernelGGL(k_seed_dy, dim3(e.n_inst), dim3(128), 0, s, v, e, dy);

@@ -244,7 +244,8 @@ struct VecArgs {
   float* dW_part;   // split partial sums [n_split x Np x Kp]
   uint32_t q_stride;
   float* loss;      // [B]
-  int dh_init;      // rows of dH start from the gradient of the row's own loss term (CE_NODE): consumers add to them
+  float* dHn;       // [(cap + B) x Hp] gradient of each row's own loss term (CE_NODE, gradient runs; else null):
+                    // whoever reads a row of dH adds the row of dHn
 };
 
 }  // namespace tdf

@@ -207,7 +207,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.Kp = 2 * v.Hp;
     v.vocab = in->vocab;
     v.n_classes = in->n_classes;
-    v.dh_init = G.has_node_loss ? 1 : 0;
+    v.dHn = nullptr;
     v.E = in->E; v.W = in->W; v.b = in->b; v.U = in->U; v.u0 = in->u0;
     const size_t el = in->dtype == TDF_BF16 ? 2 : 4;
     const size_t R = (size_t)e.cap + B;   // one state row per frame
@@ -229,6 +229,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       v.q_stride = (uint32_t)((P.max_cells + 63) / 64 * 64);
       size_t off_dH = L.take(R * v.Hp * 4);
       size_t off_dC = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
+      size_t off_dHn = G.has_node_loss ? L.take(R * v.Hp * 4) : 0;
       size_t off_gates = G.cell_kind == 2 ? L.take((size_t)P.max_cells * v.Np * el) : 0;
       size_t off_Dz = L.take((size_t)P.max_cells * v.Np * el);
       size_t off_DzT = L.take((size_t)v.Np * v.q_stride * el);
@@ -243,6 +244,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       P.off_de_part = L.take(((size_t)e.log_cap / DE_CHUNK + v.vocab + 2) * v.Hp * 4);
       v.dH = (float*)at(off_dH);
       v.dC = G.cell_kind == 2 ? (float*)at(off_dC) : nullptr;
+      v.dHn = G.has_node_loss ? (float*)at(off_dHn) : nullptr;
       v.gates = G.cell_kind == 2 ? at(off_gates) : nullptr;
       v.Dz = at(off_Dz);
       v.DzT = at(off_DzT);
@@ -459,8 +461,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     } else if (G.out_type == T_VEC) {
       vec_out_rows(v, e, out->out_h, out->out_c, s);
       if (G.has_node_loss) {
-        // every state row that has a loss term: the term, and (gradient runs) its gradient as
-        // the initial value of the row's dh, which the row's consumer then adds to
+        // every state row that has a loss term: the term, and (gradient runs) its gradient with
+        // respect to the row, which joins the row's dh where that is read
         HIP_TRY(hipMemsetAsync(out->out_node_loss, 0, sizeof(float) * (size_t)in->n_tree_nodes, s));
         vec_node_loss(v, e, hc.n_leaf, hc.n_cell, in->node_label, out->out_node_loss, with_grad ? dy->dnode : nullptr,
                       with_grad, s);
