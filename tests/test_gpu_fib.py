@@ -62,3 +62,29 @@ def test_capacity_and_step_limit_are_reported_not_faulted():
     assert st == tdf.ERR_STEP_LIMIT
     st, stats, out, _ = _eval_int(fns, r, [18], 10000)                      # and the library still works
     assert out.tolist() == [2584]
+
+
+def test_fourteen_million_tags_in_one_batch():
+    # fib(30), fib(31), fib(32) side by side: far beyond what the oracle can run, so the values are
+    # checked against the Fibonacci numbers and the tag count against 2 F(n+1) - 1 invocations per
+    # instance (the count the oracle is pinned to at small n); the longest tag is fib(32)'s chain
+    # of 32 labels.  Instances of such different sizes also overflow the table part of a single
+    # tag machine, which the library answers by running the batch on one machine.
+    F = [0, 1]
+    while len(F) < 40:
+        F.append(F[-1] + F[-2])
+    ns = [30, 31, 32]
+    want_tags = sum(2 * F[n + 1] - 1 for n in ns)
+    assert want_tags == 14098309
+    fns, r = programs.fib()
+    g = tdf.graph_build(fns, r)
+    t_args = torch.tensor(ns, dtype=torch.int64, device=DEV)
+    inp = tdf.make_inputs(3, args=t_args, n_args=1, max_tags=15_000_000, stats_level=0)
+    ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=DEV)
+    out = torch.full((3,), -1, dtype=torch.int64, device=DEV)
+    for rep in range(2):
+        st, stats = tdf.eval(g, inp, ws, out_i64=out)
+        assert out.cpu().tolist() == [F[n] for n in ns]
+        assert stats.n_tags == want_tags and stats.max_tag_depth == 32
+    del ws
+    torch.cuda.empty_cache()
