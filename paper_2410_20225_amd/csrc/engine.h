@@ -24,6 +24,7 @@ struct alignas(128) Ctrl {
   uint32_t max_probe, max_depth, max_level;
   uint32_t bar_count;        // grid barrier of the grid-wide step kernel: arrivals (monotone)
   uint32_t bar_gen;          // ... and completed barriers
+  uint32_t wbar_count, wbar_gen;   // the same for the device-wide kernel (another number of workgroups)
   uint32_t xcc_mask;         // accelerator dies that ran a die-local grid-wide step kernel
   uint32_t prev_count;       // frames of the previous step
   uint32_t peak_count;       // ... and of the largest step so far
@@ -86,6 +87,8 @@ struct Engine {
   uint32_t touched_cap;
   uint32_t step_limit;
   uint32_t small_limit;             // steps with at most this many touched frames run in one workgroup
+  uint32_t wide_limit;              // 0, or: a machine's steps with more frames than this run in the device-wide kernel
+                                    // on every die's compute units (batches that leave dies without a machine)
   uint32_t follow_limit;            // in single-workgroup steps with at most this many frames a lane goes on with the frame it created
   // forest
   const int32_t *left, *right, *token;

@@ -362,6 +362,11 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     e.small_limit = (uint32_t)small_block;   // one pass of the single workgroup
     if (const char* w = getenv("TDF_SMALL_LIMIT")) e.small_limit = (uint32_t)std::max(1, atoi(w));
+    // Fewer machines than dies (few instances, or the one machine of a batch that overflowed a
+    // part of the table): steps with more frames than one die's lanes take in two passes run on
+    // the whole GPU, at device scope.
+    e.wide_limit = gr->die_local && e.n_dies < XCDS ? 16384u : 0u;
+    if (const char* w = getenv("TDF_WIDE_LIMIT")) e.wide_limit = gr->die_local && e.n_dies < XCDS ? (uint32_t)std::max(0, atoi(w)) : 0u;
     e.follow_limit = e.small_limit;
     if (const char* w = getenv("TDF_FOLLOW_LIMIT")) e.follow_limit = (uint32_t)std::max(0, atoi(w));
     HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));

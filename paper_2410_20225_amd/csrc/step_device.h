@@ -848,6 +848,11 @@ __device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
 // A step is "small" when its frames fit two passes of one workgroup; small steps run in the
 // single-workgroup kernel, the others in the grid-wide kernel.
 __device__ __forceinline__ bool step_is_small(const Engine& e, uint32_t n) { return n <= e.small_limit; }
+// Which of the two grid-wide kernels takes a step that is not small: with wide_limit set, the
+// die-local one up to that many frames and the device-wide one beyond; else whichever is launched.
+template <bool LOCAL> __device__ __forceinline__ bool step_is_other_grids(const Engine& e, uint32_t n) {
+  return e.wide_limit != 0 && (LOCAL ? n > e.wide_limit : n <= e.wide_limit);
+}
 
 constexpr int STEP_BLOCK = 256;    // lanes per workgroup of the grid-wide kernel
 constexpr int LOCAL_BLOCK = 512;   // ... and of its variant that keeps to one accelerator die
@@ -866,7 +871,8 @@ constexpr int GEN_SMALL_BLOCK = 512, GEN_LOCAL_BLOCK = 512;   // launch bounds o
 // machine then execute in that L2 (workgroup scope) instead of in memory, and a step boundary
 // needs no L2 write-back or invalidation, only an invalidation of the per-CU L1.  The dies a
 // machine ran on are recorded in its Ctrl::xcc_mask; the host discards the run if any machine
-// saw more than one.  Not LOCAL: one machine, all workgroups, device scope.
+// saw more than one.  Not LOCAL: device scope, the workgroups dealt evenly to the machines
+// (one machine when the whole evaluation runs this way).
 // Orders this thread's accesses to the control block, which are all atomic loads, stores and
 // read-modify-writes performed in memory.  Die-local runs must not use a device-scope fence
 // for this: it would also write back and invalidate the L2 that the step kernel relies on.
@@ -884,15 +890,21 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
     if (die >= e.n_dies) return;
     G = gridDim.x / XCDS;
     rank = blockIdx.x / XCDS;
+  } else {       // (the host launches a multiple of n_dies workgroups)
+    die = blockIdx.x % e.n_dies;
+    G = gridDim.x / e.n_dies;
+    rank = blockIdx.x / e.n_dies;
   }
   e = die_view(e, die);
   Ctrl* c = e.ctrl;
+  uint32_t* const bar_count = LOCAL ? &c->bar_count : &c->wbar_count;
+  uint32_t* const bar_gen = LOCAL ? &c->bar_gen : &c->wbar_gen;
   // Nothing changes these before the first barrier completes, and a workgroup reads them before
   // it arrives there: all workgroups see the same values and take the same way.
-  uint32_t gen = ld(&c->bar_gen);
+  uint32_t gen = ld(bar_gen);
   uint32_t step = ld(&c->step);
   uint32_t n = ld(&c->touched_count[step & 1]);
-  if (ld(&c->done) || n == 0 || step_is_small(e, n)) return;
+  if (ld(&c->done) || n == 0 || step_is_small(e, n) || step_is_other_grids<LOCAL>(e, n)) return;
   if (LOCAL && threadIdx.x == 0)
     atomicOr(&c->xcc_mask, 1u << xcc_id());
   load_program(P_lds, e.prog);
@@ -902,15 +914,15 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
     if (!LOCAL) __threadfence();   // this step's writes, before the arrival below
     __syncthreads();               // (LOCAL: every wave's stores have reached the shared L2)
     if (threadIdx.x == 0) {
-      const uint32_t arrived = atomicAdd(&c->bar_count, 1u);   // monotone: G per barrier
+      const uint32_t arrived = atomicAdd(bar_count, 1u);   // monotone: G per barrier
       if (arrived == (gen + 1u) * G - 1u) {
         ctrl_fence<LOCAL>();
         advance(e, c, step);
         ctrl_fence<LOCAL>();
-        st(&c->bar_gen, gen + 1u);
+        st(bar_gen, gen + 1u);
       } else {
         const long long t0 = wall_clock64();
-        while (ld(&c->bar_gen) == gen) {
+        while (ld(bar_gen) == gen) {
           __builtin_amdgcn_s_sleep(1);
           if (wall_clock64() - t0 > spin_ticks) {   // a workgroup is missing: give up
             raise(c, TDF_ERR_DEVICE);
@@ -931,7 +943,7 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
     ++gen;
     step = sh[0];
     n = sh[1];
-    const bool stop = sh[2] != 0 || n == 0 || step_is_small(e, n);
+    const bool stop = sh[2] != 0 || n == 0 || step_is_small(e, n) || step_is_other_grids<LOCAL>(e, n);
     __syncthreads();   // sh is written again in the next round
     if (stop) break;
   }

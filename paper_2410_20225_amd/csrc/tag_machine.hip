@@ -199,7 +199,9 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
                         long long spin_ticks, const JitKernels& jit, hipStream_t s) {
   const Sizes z = sizes_of(P);
   const int per_die = cus / (int)XCDS > 0 ? cus / (int)XCDS : 1;
-  const int grid = local ? per_die * (int)XCDS : cus;
+  const int grid = local ? per_die * (int)XCDS : cus / (int)e.n_dies * (int)e.n_dies;
+  const bool also_wide = local && e.wide_limit != 0;   // a third kernel for the steps too wide for one die
+  const int wide_grid = cus / (int)e.n_dies * (int)e.n_dies;
   if (jit.small && jit.step && jit.step_local) {
     Engine ev = e;
     int ms = max_steps;
@@ -213,6 +215,12 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
     if (r == hipSuccess)
       r = hipModuleLaunchKernel((hipFunction_t)(local ? jit.step_local : jit.step), grid, 1, 1, gb, 1, 1,
                                 (unsigned)step_lds_bytes(z, gb, false), s, a_step, nullptr);
+    if (r == hipSuccess && also_wide) {
+      int wb = STEP_BLOCK;
+      while (wb > 64 && step_lds_bytes(z, wb, false) > 64 * 1024) wb >>= 1;
+      r = hipModuleLaunchKernel((hipFunction_t)jit.step, wide_grid, 1, 1, wb, 1, 1, (unsigned)step_lds_bytes(z, wb, false), s, a_step,
+                                nullptr);
+    }
     if (r != hipSuccess) {
       set_error(std::string("launch of a generated step kernel failed: ") + hipGetErrorString(r));
       return TDF_ERR_DEVICE;
@@ -229,8 +237,8 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
     if (local)
       hipLaunchKernelGGL((k_steps_grid<16, true>), dim3(grid), dim3(LOCAL_BLOCK), step_lds_bytes(z, LOCAL_BLOCK, false), s, e,
                          max_steps, spin_ticks);
-    else
-      hipLaunchKernelGGL((k_steps_grid<16, false>), dim3(grid), dim3(STEP_BLOCK), step_lds_bytes(z, STEP_BLOCK, false), s, e,
+    if (!local || also_wide)
+      hipLaunchKernelGGL((k_steps_grid<16, false>), dim3(wide_grid), dim3(STEP_BLOCK), step_lds_bytes(z, STEP_BLOCK, false), s, e,
                          max_steps, spin_ticks);
   } else {
     // the LDS value file limits the workgroup to 128 lanes (at most 90 KB)
@@ -244,8 +252,8 @@ tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool loca
     hipLaunchKernelGGL(k_steps_small<0>, dim3(e.n_dies), dim3(small_block), small_lds, s, e, max_steps);
     if (local)
       hipLaunchKernelGGL((k_steps_grid<0, true>), dim3(grid), dim3(128), grid_lds, s, e, max_steps, spin_ticks);
-    else
-      hipLaunchKernelGGL((k_steps_grid<0, false>), dim3(grid), dim3(128), grid_lds, s, e, max_steps, spin_ticks);
+    if (!local || also_wide)
+      hipLaunchKernelGGL((k_steps_grid<0, false>), dim3(wide_grid), dim3(128), grid_lds, s, e, max_steps, spin_ticks);
   }
   return TDF_OK;
 }

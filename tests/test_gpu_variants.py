@@ -176,3 +176,49 @@ def test_evaluations_from_several_threads_take_turns(lstm_case):
     for r in runs:
         assert rel_fro(r.dW.cpu().numpy(), ref["grads"]["dW"]) < 2e-2
         assert rel_fro(r.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
+
+
+@pytest.mark.parametrize("wide", ["600", "5000", "0", None], ids=["above_600", "above_5000", "off", "default"])
+@pytest.mark.parametrize("jit", [True, False], ids=["generated", "interpreter"])
+def test_few_instances_use_the_whole_gpu_for_wide_steps(wide, jit, monkeypatch):
+    # Three instances are dealt to two tag machines, which leaves six dies without one: a machine's
+    # steps above a limit then run in the device-wide kernel, the others in the die-local and the
+    # single-workgroup kernel.  fib(17), fib(20), fib(19) pass through all three several times.
+    if wide is not None:
+        monkeypatch.setenv("TDF_WIDE_LIMIT", wide)
+    if not jit:
+        monkeypatch.setenv("TDF_NO_JIT", "1")
+    ns = [17, 20, 19]
+    fns, r = programs.fib()
+    g = tdf.graph_build(fns, r)
+    t_args = torch.tensor(ns, dtype=torch.int64, device=DEV)
+    inp = tdf.make_inputs(3, args=t_args, n_args=1, max_tags=41000)
+    ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=DEV)
+    out = torch.full((3,), -1, dtype=torch.int64, device=DEV)
+    it = oracle.Interpreter(oracle.transform(oprog.fib_program()))
+    want = it.run({("in", 0): ns}, 3)[("out", 0)]
+    for rep in range(2):
+        st, stats = tdf.eval(g, inp, ws, out_i64=out)
+        assert out.cpu().tolist() == want
+        assert stats.n_tags == len(it.tags) and stats.max_tag_depth == it.max_tag_len
+        got = fire_counts(g, stats)
+        ref = it.count_by_op()
+        for k in got:
+            assert got[k] == ref[k], k
+
+
+@pytest.mark.parametrize("wide", ["300", None], ids=["above_300", "default"])
+def test_three_large_trees_with_wide_steps(wide, monkeypatch):
+    if wide is not None:
+        monkeypatch.setenv("TDF_WIDE_LIMIT", wide)
+        monkeypatch.setenv("TDF_SMALL_LIMIT", "128")
+    c = make_config(5, n_trees=3, max_leaves=512, hidden=64, vocab=300)   # a left chain and two complete trees
+    B = c["forest"].n_trees
+    dy = np.full(B, 1.0 / B)
+    ref = run_oracle_tree(c, head=True, grad=True, dy=dy)
+    run = TreeRun(c, head=True, grad=True)
+    st, stats = run.run(dy)
+    assert stats.n_tags == c["forest"].n_nodes == len(ref["it"].tags)
+    assert rel_fro(run.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
+    for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
+        assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-2, name
