@@ -27,8 +27,8 @@ COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 # profiles/bench_workload4_hbm_traffic.md), with the hash of the kernel source they were taken on:
 # reported as `traffic` only while that source is unchanged.
 MEASURED_TRAFFIC = {
-    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "7045ff1c163d51c5", 2204955487.5),
-        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "25669e8fa0a715df", 366498868.3)},
+    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "15bb1d12068194bd", 2209341021.6),
+        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "0a784c590ea081b1", 366497769.0)},
 }
 
 
