@@ -433,7 +433,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
     begin(TDF_PHASE_LEAVES);
-    vec_pack_w(v, s);
+    if (G.cell_kind) vec_pack_w(v, s);   // (a program of EMBEDs alone has no W: the pointers may be NULL)
     vec_embed(v, e, hc.n_leaf, s);
     end(TDF_PHASE_LEAVES, 2);
     if (hc.n_cell) {

@@ -122,3 +122,44 @@ def test_full_size_workload_on_sampled_trees():
     assert rel_fro(got[sel], _losses(ref, F.n_nodes)[sel]) < BF16_TOL
     for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
         assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < BF16_TOL, name
+
+
+def test_node_outside_the_forest_is_reported_and_unreached_nodes_have_no_term():
+    # result(v) = ce_node(embed(token(v)), v + k): with k = 0 only the roots (here: leaves) get a
+    # term and every other node of the forest stays at zero; with k far beyond the forest the
+    # device raises an error instead of writing outside its arrays.  The program has no cell, and
+    # no W or b is passed: the library must not touch them.
+    T = tdf
+
+    def program(k):
+        nodes = [(T.OP_IN, [], 0), (T.OP_TREE_TOKEN, [(0, 0)], 0), (T.OP_EMBED, [(1, 0)], 0), (T.OP_CONST, [], k),
+                 (T.OP_ADD, [(0, 0), (3, 0)], 0), (T.OP_CE_NODE, [(2, 0), (4, 0)], 0), (T.OP_OUT, [(5, 0)], 0)]
+        return [("result", 1, nodes)], 0
+
+    c = make_config(3, n_trees=6, max_leaves=5, hidden=32, vocab=50)
+    F = c["forest"]
+    leaves = np.flatnonzero(F.left < 0)[:6].astype(np.int64)   # instances start at leaves: token ids exist there
+    t = lambda a, d: torch.tensor(np.ascontiguousarray(a), dtype=d, device="cuda:0")
+    bufs = dict(args=t(leaves, torch.int64), left=t(F.left, torch.int32), right=t(F.right, torch.int32),
+                token=t(F.token, torch.int32), E=t(c["E"], torch.bfloat16), U=t(c["U"], torch.float32),
+                u0=t(c["u0"], torch.float32), node_label=t(c["node_labels"], torch.int32))
+    out_h = torch.zeros(6, 32, dtype=torch.float32, device="cuda:0")
+    for k, want in ((0, tdf.OK), (10 ** 7, tdf.ERR_BAD_ARG), (-10 ** 7, tdf.ERR_BAD_ARG)):
+        fns, r = program(k)
+        g = tdf.graph_build(fns, r)
+        inp = tdf.make_inputs(6, n_args=1, dtype=tdf.BF16, hidden=32, vocab=c["V"], n_classes=5, max_tags=64, **bufs)
+        ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device="cuda:0")
+        loss = torch.full((F.n_nodes,), -1.0, dtype=torch.float32, device="cuda:0")
+        st, stats = tdf.eval(g, inp, ws, out_h=out_h, out_node_loss=loss, check=False)
+        assert st == want
+        if st == tdf.OK:
+            got = loss.cpu().numpy()
+            h = c["E"][F.token[leaves]]
+            lg = h @ c["U"].T + c["u0"]
+            ref = np.log(np.exp(lg - lg.max(1, keepdims=True)).sum(1)) + lg.max(1) - lg[np.arange(6), c["node_labels"][leaves]]
+            # a library routine's definition of the loss on a single embedding row; the oracle's own
+            # check of this operator is in the tests above
+            assert np.allclose(got[leaves], ref, rtol=2e-2)
+            rest = np.ones(F.n_nodes, bool)
+            rest[leaves] = False
+            assert not got[rest].any()
