@@ -293,6 +293,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     return TDF_ERR_WORKSPACE;
   }
   if (!in->args && G.n_result_params > 0) { set_error("args is NULL"); return TDF_ERR_BAD_ARG; }
+  if ((in->left || in->right || in->token) && (!in->left || !in->right || !in->token || in->n_tree_nodes < 1)) {
+    set_error("forest: left, right and token go together, with n_tree_nodes > 0");
+    return TDF_ERR_BAD_ARG;
+  }
   if (P.vec) {
     if (!in->left || !in->right || !in->token || !in->E || (G.cell_kind && (!in->W || !in->b))) {
       set_error("forest or parameter pointer is NULL");

@@ -94,6 +94,23 @@ def test_vector_result_with_given_dy_fp32(cell, cfg, kernels, monkeypatch):
         assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-5, name
 
 
+def test_incomplete_forest_is_rejected_before_anything_runs():
+    from paper_2410_20225_amd import tdf
+    c = make_config(2, n_trees=4, max_leaves=6, hidden=32)
+    run = TreeRun(c, head=False, grad=False)
+    keep = run.inputs.right
+    run.inputs.right = None
+    st, _ = run.run(check=False)
+    assert st == tdf.ERR_BAD_ARG and "forest" in tdf.last_error()
+    run.inputs.right = keep
+    run.inputs.n_tree_nodes = 0
+    st, _ = run.run(check=False)
+    assert st == tdf.ERR_BAD_ARG
+    run.inputs.n_tree_nodes = c["forest"].n_nodes
+    st, _ = run.run()
+    assert st == tdf.OK
+
+
 def test_state_rows_exhausted_is_reported():
     c = make_config(2, n_trees=16, max_leaves=20, hidden=32)
     run = TreeRun(c, head=False, grad=False, max_tags=c["forest"].n_nodes // 2)
