@@ -12,7 +12,7 @@ from paper_2410_20225_amd import tdf, programs  # noqa: E402
 import oracle  # noqa: E402
 from oracle import programs as oprog  # noqa: E402
 from tdf_workloads import make_config, SplitMix64  # noqa: E402
-from gpu_util import DEV, TreeRun, run_oracle_tree, rel_fro  # noqa: E402
+from gpu_util import DEV, TreeRun, run_oracle_tree, run_oracle_node_loss, rel_fro  # noqa: E402
 
 
 @pytest.mark.parametrize("seed", range(9))
@@ -34,6 +34,36 @@ def test_random_forests(seed):
         assert rel_fro(run.out_f32.cpu().numpy(), np.array(ref["out"])) < 2e-2
         for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
             assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-2, name
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_forests_with_a_loss_term_at_random_nodes(seed):
+    r = SplitMix64(2000 + seed)
+    cfg = [3, 4, 5][seed % 3]
+    n_trees, max_leaves, hidden = (int(r.randint(lo, hi, 1)[0]) for lo, hi in ((1, 300), (1, 70), (8, 160)))
+    if cfg == 5:
+        n_trees, max_leaves = int(r.randint(2, 12, 1)[0]), 2 ** int(r.randint(1, 8, 1)[0])
+    c = make_config(cfg, n_trees=n_trees, max_leaves=max_leaves, hidden=hidden, vocab=300, seed=seed * 11 + 3)
+    F = c["forest"]
+    lab = c["node_labels"].copy()
+    lab[r.uniform(F.n_nodes) < 0.3] = -1                      # three nodes in ten carry no label
+    dnode = r.normal(F.n_nodes) / F.n_nodes
+    D = c["H"] * (2 if c["cell"] == "lstm" else 1)
+    dy = r.normal(F.n_trees * c["H"]).reshape(F.n_trees, c["H"]) / F.n_nodes if seed % 2 else None
+    dy_o = None if dy is None else [np.concatenate([d, np.zeros(D - c["H"])]) for d in dy]
+    ref = run_oracle_node_loss(c, lab, dnode, dy_o)
+    want = np.zeros(F.n_nodes)
+    for v, l in ref["node_loss"].items():
+        want[v] = l
+    run = TreeRun(c, head=False, grad=True, node_labels=lab)
+    for _ in range(3):
+        st, stats = run.run(dy, dnode=dnode)
+        got = run.out_node_loss.cpu().numpy()
+        assert np.array_equal(got == 0.0, want == 0.0)
+        assert rel_fro(got, want) < 2e-2
+        for name, t in (("dW", run.dW), ("db", run.db), ("dE", run.dE)):
+            if name in ref["grads"]:
+                assert rel_fro(t.cpu().numpy(), ref["grads"][name]) < 2e-2, name
 
 
 INT_CASES = [("fib", programs.fib, oprog.fib_program, 1, 0, 17), ("tak", programs.tak, oprog.tak_program, 3, 0, 9),
