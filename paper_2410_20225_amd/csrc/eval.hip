@@ -281,6 +281,23 @@ tdf_status status_from_device(uint32_t st) {
   return (tdf_status)code;
 }
 
+// Layout of tdf_graph::pinned: control blocks, barrier records, firing tables, then level offsets.
+constexpr size_t PIN_CTRL = 0, PIN_SYNC = PIN_CTRL + sizeof(Ctrl) * 8, PIN_PROG = PIN_SYNC + sizeof(DieSync) * 16,
+                 PIN_LEVELS = (PIN_PROG + sizeof(DevProgram) + 255) / 256 * 256;
+// Makes the graph's pinned buffer at least PIN_LEVELS + level_bytes large (contents are lost when it grows).
+tdf_status pinned_reserve(tdf_graph* gr, size_t level_bytes) {
+  const size_t need = PIN_LEVELS + level_bytes;
+  if (gr->pinned_bytes >= need) return TDF_OK;
+  if (gr->pinned) (void)hipHostFree(gr->pinned);
+  gr->pinned = nullptr;
+  gr->pinned_bytes = 0;
+  const size_t bytes = std::max<size_t>(need * 2, 64 * 1024);
+  HIP_TRY(hipHostMalloc(&gr->pinned, bytes, hipHostMallocDefault));
+  gr->pinned_bytes = bytes;
+  memcpy((char*)gr->pinned + PIN_PROG, &gr->g.prog, sizeof(DevProgram));
+  return TDF_OK;
+}
+
 tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out, tdf_grads* grads,
                void* workspace, size_t workspace_bytes, void* hip_stream, tdf_stats* stats, bool with_grad) {
   if (!gr || !out) { set_error("NULL graph or outputs"); return TDF_ERR_BAD_ARG; }
@@ -327,6 +344,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   VecArgs& v = P.v;
   e.out_i64 = (long long*)out->out_i64;
   char* base = (char*)workspace;
+  if (tdf_status ps = pinned_reserve(gr, 0); ps != TDF_OK) return ps;
 
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
   // The grid-wide kernel synchronises its workgroups with a barrier in memory: no more
@@ -375,15 +393,15 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (const char* w = getenv("TDF_FOLLOW_LIMIT")) e.follow_limit = (uint32_t)std::max(0, atoi(w));
     HIP_TRY(hipMemsetAsync(base + P.L.zero_begin, 0, P.L.zero_end - P.L.zero_begin, s));
     if (e.row_node) HIP_TRY(hipMemsetAsync(e.row_node, 0xFF, sizeof(uint32_t) * ((size_t)e.cap + e.n_inst), s));
-    HIP_TRY(hipMemcpyAsync((void*)e.prog, &G.prog, sizeof(DevProgram), hipMemcpyHostToDevice, s));
+    HIP_TRY(hipMemcpyAsync((void*)e.prog, (char*)gr->pinned + PIN_PROG, sizeof(DevProgram), hipMemcpyHostToDevice, s));
     launch_seed(G.prog, e, s);
-    Ctrl hcs[8];
+    const Ctrl* hcs = (const Ctrl*)((char*)gr->pinned + PIN_CTRL);
     for (;;) {
       for (uint32_t i = 0; i < poll; ++i, ++rounds) {
         tdf_status lr = launch_round(G.prog, e, cus, gr->die_local, small_block, max_steps, spin_ticks, gr->jit, s);
         if (lr != TDF_OK) return lr;
       }
-      HIP_TRY(hipMemcpyAsync(hcs, e.ctrl, sizeof(Ctrl) * e.n_dies, hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipMemcpyAsync((void*)hcs, e.ctrl, sizeof(Ctrl) * e.n_dies, hipMemcpyDeviceToHost, s));
       HIP_TRY(hipStreamSynchronize(s));
       bool all_done = true, any_status = false;
       for (uint32_t d = 0; d < e.n_dies; ++d) {
@@ -432,7 +450,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
 
   uint32_t tail_first = 0;
   bool use_tail = false;
-  std::vector<uint32_t> level_off;   // by sort key (level, machine)
+  const uint32_t* level_off = nullptr;   // by sort key (level, machine); in the pinned buffer
   auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
@@ -443,8 +461,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (hc.n_cell) {
       begin(TDF_PHASE_LEVELS);
       launch_levels(e, hc.n_cell, hc.max_level, s);
-      level_off.resize(((size_t)hc.max_level + 2) * LEVEL_KEY_DIES);
-      HIP_TRY(hipMemcpyAsync(level_off.data(), e.level_off, level_off.size() * 4, hipMemcpyDeviceToHost, s));
+      const size_t level_bytes = ((size_t)hc.max_level + 2) * LEVEL_KEY_DIES * sizeof(uint32_t);
+      if (tdf_status ps = pinned_reserve(gr, level_bytes); ps != TDF_OK) return ps;
+      level_off = (const uint32_t*)((char*)gr->pinned + PIN_LEVELS);
+      HIP_TRY(hipMemcpyAsync((void*)level_off, e.level_off, level_bytes, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 3);
       HIP_TRY(hipStreamSynchronize(s));
       // the deep levels, each small, go into one launch in which every die walks its own cells
@@ -521,12 +541,13 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->join_event, 0));
     }
     HIP_TRY(hipGetLastError());
+    const DieSync* ts = (const DieSync*)((char*)gr->pinned + PIN_SYNC);
+    if (use_tail) HIP_TRY(hipMemcpyAsync((void*)ts, base + P.off_tail_sync, sizeof(DieSync) * 16, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     if (use_tail) {
-      DieSync ts[16];
-      HIP_TRY(hipMemcpy(ts, base + P.off_tail_sync, sizeof(ts), hipMemcpyDeviceToHost));
       bool mixed = false, gave_up = false;
-      for (const DieSync& d : ts) {
+      for (int k = 0; k < 16; ++k) {
+        const DieSync& d = ts[k];
         mixed = mixed || (d.xcc_mask & (d.xcc_mask - 1)) != 0;
         gave_up = gave_up || d.abort != 0;
       }
@@ -592,7 +613,9 @@ tdf_graph::~tdf_graph() {
   }
   if (fork_event) (void)hipEventDestroy((hipEvent_t)fork_event);
   if (join_event) (void)hipEventDestroy((hipEvent_t)join_event);
+  if (pinned) (void)hipHostFree(pinned);
 }
+
 
 extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* in, int with_grad, size_t* bytes) {
   if (!g || !bytes) {

@@ -47,5 +47,9 @@ struct tdf_graph {
   void* events[2 * TDF_PHASE_COUNT] = {nullptr};   // hipEvent_t pairs, created on first use
   void* side_stream = nullptr;                     // hipStream_t for work beside the caller's stream
   void* fork_event = nullptr, *join_event = nullptr;
+  // pinned host memory for what an evaluation reads back or sends (control blocks, level offsets,
+  // barrier records, the firing tables): copies to and from pageable memory are staged and slower
+  void* pinned = nullptr;
+  size_t pinned_bytes = 0;
   ~tdf_graph();
 };

@@ -73,7 +73,7 @@ class TreeRun:
         self.t_E, self.t_W = t(c["E"], dt), t(c["W"], dt)
         self.t_b, self.t_U, self.t_u0 = t(c["b"], torch.float32), t(c["U"], torch.float32), t(c["u0"], torch.float32)
         self.max_tags = F.n_nodes if max_tags is None else max_tags
-        self.t_node_label = self.out_node_loss = self.t_dnode = self._dnode_src = None
+        self.t_node_label = self.out_node_loss = self.t_dnode = self._dnode_src = self.t_dy = self._dy_src = None
         if node_labels is not None:
             self.t_node_label = t(node_labels, torch.int32)
             self.out_node_loss = torch.full((F.n_nodes,), -7.0, dtype=torch.float32, device=DEV)
@@ -96,7 +96,8 @@ class TreeRun:
     def run(self, dy=None, check=True, dnode=None):
         if self.grad:
             f32 = lambda a: None if a is None else torch.tensor(np.ascontiguousarray(a), dtype=torch.float32, device=DEV)
-            self.t_dy = f32(dy)
+            if dy is not self._dy_src:         # both stay resident while the caller passes the same arrays
+                self._dy_src, self.t_dy = dy, f32(dy)
             if dnode is not self._dnode_src:   # stays resident while the caller passes the same array
                 self._dnode_src, self.t_dnode = dnode, f32(dnode)
             st, stats = tdf.eval_grad(self.graph, self.inputs, self.t_dy, self.ws, self.dW, self.db, self.dE,
