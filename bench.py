@@ -222,6 +222,16 @@ def main():
         roof["wide_levels"] = {"levels": int(st.n_wide_waves), "cells": wide_cells, "ms": wide_ms,
                                "achieved": per_cell * wide_cells / max(wide_ms, 1e-9) / 1e9,
                                "frac": per_cell * wide_cells / max(wide_ms, 1e-9) / 1e9 / (peak / 1e12)}
+        # the same kernels against the HBM roof: algorithmic bytes per cell (children's h, and c for
+        # the LSTM, read; h, c and, in a gradient run, the five gate activations written)
+        elt = 2 if dtype == "bf16" else 4
+        H = c["H"]
+        cell_bytes = 3 * H * elt + (12 * H + (5 * H * elt if grad or a.node_loss else 0) if cell == "lstm" else 0)
+        roof["against_hbm"] = {"bytes_per_cell": cell_bytes, "flop_per_byte": per_cell / cell_bytes,
+                               "machine_flop_per_byte": peak / PEAK_HBM,
+                               "achieved": cell_bytes * n_cell / (ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
+                               "frac": cell_bytes * n_cell / (ms * 1e-3) / PEAK_HBM,
+                               "wide_levels_frac": cell_bytes * wide_cells / max(wide_ms * 1e-3, 1e-12) / PEAK_HBM}
         roof["narrow_tail"] = {"levels": int(st.n_waves) - int(st.n_wide_waves), "cells": n_cell - wide_cells, "ms": tail_ms,
                                "achieved": per_cell * (n_cell - wide_cells) / max(tail_ms, 1e-9) / 1e9,
                                "frac": per_cell * (n_cell - wide_cells) / max(tail_ms, 1e-9) / 1e9 / (peak / 1e12)}
