@@ -16,7 +16,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 PEAK_BF16 = 2.5e15      # dense bf16 MFMA, FLOP/s
 PEAK_F32 = 157.3e12     # fp32 MFMA / vector
@@ -144,7 +143,7 @@ def main():
         step = lambda: tdf.eval(g, inp, ws, out_i64=out)[1]
         passes, dtype, flops_fwd, cell = 1, "int64", 0.0, None
     else:
-        from gpu_util import TreeRun
+        from paper_2410_20225_amd.harness import TreeRun
         c = make_config(cfg)
         grad = c["grad"]
         B = c["forest"].n_trees

@@ -251,7 +251,9 @@ typedef struct {
   int64_t n_waves;        /* dependency levels of the cell firings                      */
   int64_t n_wide_waves;   /* ... of which the first this many ran one launch per level  */
   int64_t n_wide_cells;   /* cell firings in those levels                               */
-  int64_t n_grad_firings; /* gradient-body firings (one per tag) in tdf_eval_grad       */
+  int64_t n_grad_firings; /* gradient-body firings in tdf_eval_grad, counted on the device: every
+                             gradient body marks its tag's row when it fires (one per tag) */
+  int64_t n_grad_not_once; /* tags whose gradient body fired some other number of times than once */
   int64_t max_tag_depth;  /* longest list of call labels and iteration counters         */
   int64_t table_capacity; /* slots of the tag-hash table                                */
   int64_t max_probe;      /* longest probe sequence                                     */
@@ -259,6 +261,16 @@ typedef struct {
   int64_t phase_launches[TDF_PHASE_COUNT]; /* kernel launches of each phase            */
   int32_t device_status;  /* tdf_status raised on the device                            */
   int32_t n_counts;       /* entries used in fire_count                                 */
+  /* which way the evaluation took */
+  int32_t n_machines;     /* independent tag machines the batch was dealt to (1, 2, 4, 8) */
+  int32_t die_local;      /* 1: every machine kept to one accelerator die, atomics in its L2;
+                             0: device-scope kernels                                    */
+  int32_t generated;      /* 1: step kernels generated for this program at run time; 0: the
+                             table interpreter                                          */
+  int32_t repeats;        /* runs that were discarded and repeated inside this call (a part of
+                             the tag table overflowed, or die-private kernels left their die) */
+  int32_t tail_used;      /* 1: the deep, narrow levels ran in one launch per pass      */
+  int32_t reserved0;
   /* live firings per static-graph node, indexed like tdf_graph_info_t.nodes            */
   int64_t fire_count[TDF_STATS_MAX_COUNTS];
 } tdf_stats;

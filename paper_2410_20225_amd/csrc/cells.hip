@@ -654,6 +654,7 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
         const int m = m0 + row_of(rr);
         if (m >= g.M || z_q[rr] == 0xFFFFFFFFu) continue;
         const float dh = z[0][rr] + z_own[rr];
+        if (z_n == 0) atomicAdd(&v.gmark[z_row[rr]], 1u);   // one lane per child cell: its gradient body fires here
         T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)z_q[rr] * v.Np + z_n;
         if (v.cell_kind == 1) {
           dz[0] = from_f<T>(dh * (1.f - z_h[rr] * z_h[rr]));
@@ -915,6 +916,7 @@ __device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32
   typedef typename TypeOf<DT>::type T;
   const size_t o = (size_t)e.q_out[q] * v.Hp;
   T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)q * v.Np;
+  if (threadIdx.x == 0) atomicAdd(&v.gmark[e.q_out[q]], 1u);   // the gradient body of this tag fires
   if (v.cell_kind == 1) {
     for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
       const float h = to_f(reinterpret_cast<const T*>(v.Hs)[o + n]);
@@ -1053,6 +1055,25 @@ template <int DT>
 __global__ void k_dz_tail_roots(VecArgs v, Engine e, const uint32_t* root_rows, uint32_t q_first) {
   const uint32_t q = e.row_q[root_rows[blockIdx.x]];
   if (q != 0xFFFFFFFFu && q >= q_first) dz_row<DT>(v, e, q);
+}
+
+// Gradient-body firings counted on the device: the marks of all leaf and cell rows, summed, and the
+// number of rows whose mark is not exactly one.  out[0] += sum, out[1] += rows fired other than once.
+__global__ void k_count_grad(VecArgs v, Engine e, uint32_t n_leaf, uint32_t n_cell, unsigned long long* out) {
+  unsigned long long sum = 0, odd = 0;
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_leaf + n_cell; i += gridDim.x * blockDim.x) {
+    const uint32_t m = v.gmark[i < n_leaf ? e.leaf_row[i] : e.q_out[i - n_leaf]];
+    sum += m;
+    odd += m != 1u;
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    sum += __shfl_xor(sum, off);
+    odd += __shfl_xor(odd, off);
+  }
+  if ((threadIdx.x & 63) == 0) {
+    if (sum) atomicAdd(&out[0], sum);
+    if (odd) atomicAdd(&out[1], odd);
+  }
 }
 
 // ---- transposes feeding the weight-gradient GEMM (reduction over tags must be k-contiguous) -----
@@ -1382,6 +1403,9 @@ __global__ void k_de_partial(VecArgs v, const uint32_t* seg_off, const uint32_t*
         float4 x[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) row[j] = sorted_row[min(p + j, p_hi - 1)];
+        if (n == 0)   // (lane 0, first column group) the gradient body of a leaf's tag is its term of dE
+          for (int j = 0; j < 8; ++j)
+            if (p + j < p_hi) atomicAdd(&v.gmark[row[j]], 1u);
 #pragma unroll
         for (int j = 0; j < 8; ++j) x[j] = *reinterpret_cast<const float4*>(v.dH + (size_t)row[j] * v.Hp + n);
 #pragma unroll
@@ -1571,6 +1595,11 @@ void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t 
   else
     hipLaunchKernelGGL(k_node_ce<TDF_F32>, dim3(blocks), dim3(256), lds, s, v, e, n_leaf, n_cell, node_label, out_node_loss, dnode,
                        with_grad, u_in_lds);
+}
+void vec_count_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, unsigned long long* out, hipStream_t s) {
+  const uint32_t n = n_leaf + n_cell;
+  if (!n) return;
+  hipLaunchKernelGGL(k_count_grad, dim3(std::min<uint32_t>((n + 255) / 256, 1024u)), dim3(256), 0, s, v, e, n_leaf, n_cell, out);
 }
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s) {
   hipLaunchKernelGGL(k_seed_dy, dim3(e.n_inst), dim3(128), 0, s, v, e, dy);

@@ -2,8 +2,9 @@
 // MI355X hands the workgroups of a launch to its eight dies in turn, so workgroups i, i + 8,
 // i + 16, ... share a die and its L2.  Work that is private to a die (the instances dealt to
 // one tag machine, and the cells of those instances) can therefore run as a persistent loop
-// with this barrier between dependent phases: stores reach the shared L2 before the arrival, so
-// no L2 write-back or invalidation and no kernel boundary is needed.  The per-CU L1 is NOT
+// with this barrier between dependent phases: every wave drains its stores into the shared L2
+// before its workgroup arrives (s_waitcnt vmcnt(0)), so no L2 write-back or invalidation and no
+// kernel boundary is needed.  The per-CU L1 is NOT
 // invalidated: what crosses the barrier must be data the consumer's CU cannot hold an older copy
 // of (rows written once per launch and read only afterwards), or be read past the L1.  The barrier words themselves are accessed at device scope, so the
 // barrier completes wherever the workgroups run; every wait is bounded.
@@ -31,7 +32,11 @@ __device__ __forceinline__ uint32_t xcc_id() { return __builtin_amdgcn_s_getreg(
 // barriers so far (all workgroups pass the same value).  Returns false if the wait exceeded
 // spin_ticks (100 MHz ticks) or another workgroup had given up: the caller then leaves.
 __device__ inline bool die_barrier(DieSync* sy, uint32_t G, uint32_t gen, long long spin_ticks, uint32_t* sh_ok) {
-  __syncthreads();   // every wave's stores have reached the shared L2 (the barrier waits for them)
+  // Release: each wave waits until the die's L2 has acknowledged all its outstanding stores (on this
+  // architecture stores count in vmcnt; the workgroup barrier by itself does not wait for them), then
+  // the workgroup meets, then one thread announces the arrival.  No L2 write-back is involved.
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
   if (threadIdx.x == 0) {
     bool ok = true;
     // arrive without waiting for the old value; the count itself says when all G have arrived

@@ -93,6 +93,7 @@ struct Engine {
   // forest
   const int32_t *left, *right, *token;
   int32_t n_tree_nodes;
+  int32_t vocab;                    // rows of the embedding table: EMBED rejects token ids beyond it
   // program inputs / outputs
   const long long* args;
   int32_t n_args;
@@ -247,6 +248,7 @@ struct VecArgs {
   float* dW_part;   // split partial sums [n_split x Np x Kp]
   uint32_t q_stride;
   float* loss;      // [B]
+  uint32_t* gmark;  // [(cap + B)] gradient runs: how often the gradient body of a row's tag has fired (cleared per call)
   float* dHn;       // [(cap + B) x Hp] gradient of each row's own loss term (CE_NODE, gradient runs; else null):
                     // whoever reads a row of dH adds the row of dHn
 };

@@ -37,6 +37,7 @@ void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad,
 void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label,
                    float* out_node_loss, const float* dnode, int with_grad, hipStream_t s);
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s);
+void vec_count_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, unsigned long long* out, hipStream_t s);
 void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s);
 int vec_dw_splits(uint32_t q_stride, int Np, int Kp);
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s);
@@ -64,7 +65,7 @@ struct Plan {
   Engine e{};
   VecArgs v{};
   bool vec = false, grad = false;
-  size_t off_ctrl, off_fire, off_frames, off_tail_sync;
+  size_t off_ctrl, off_fire, off_frames, off_tail_sync, off_gcount = 0;
   // embedding-gradient and bias-gradient scratch
   size_t off_tok_count, off_tok_fill, off_seg_off, off_chunk_off, off_sorted, off_de_part, off_db_part;
   uint32_t max_cells;
@@ -132,6 +133,11 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     P.off_tok_fill = L.take(sizeof(uint32_t) * ((size_t)in->vocab + 1));
   }
   P.off_tail_sync = L.take(sizeof(DieSync) * 16);   // forward and gradient tail launches
+  size_t off_gmark = 0;
+  if (P.vec && with_grad) {
+    P.off_gcount = L.take(sizeof(unsigned long long) * 2);
+    off_gmark = L.take(sizeof(uint32_t) * ((size_t)e.cap + B));
+  }
   size_t off_keys = L.take(sizeof(unsigned long long) * (size_t)e.cap);
   L.zero_end = L.total;
   P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));   // headers are written on insertion
@@ -192,6 +198,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.right = in->right;
   e.token = in->token;
   e.n_tree_nodes = in->n_tree_nodes;
+  e.vocab = in->vocab;
   e.args = (const long long*)in->args;
   e.n_args = in->n_args;
 
@@ -208,6 +215,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.vocab = in->vocab;
     v.n_classes = in->n_classes;
     v.dHn = nullptr;
+    v.gmark = with_grad ? (uint32_t*)at(off_gmark) : nullptr;
     v.E = in->E; v.W = in->W; v.b = in->b; v.U = in->U; v.u0 = in->u0;
     const size_t el = in->dtype == TDF_BF16 ? 2 : 4;
     const size_t R = (size_t)e.cap + B;   // one state row per frame
@@ -281,9 +289,10 @@ tdf_status status_from_device(uint32_t st) {
   return (tdf_status)code;
 }
 
-// Layout of tdf_graph::pinned: control blocks, barrier records, firing tables, then level offsets.
+// Layout of tdf_graph::pinned: control blocks, barrier records, firing tables, firing counts, then level offsets.
 constexpr size_t PIN_CTRL = 0, PIN_SYNC = PIN_CTRL + sizeof(Ctrl) * 8, PIN_PROG = PIN_SYNC + sizeof(DieSync) * 16,
-                 PIN_LEVELS = (PIN_PROG + sizeof(DevProgram) + 255) / 256 * 256;
+                 PIN_FIRE = (PIN_PROG + sizeof(DevProgram) + 255) / 256 * 256,
+                 PIN_LEVELS = PIN_FIRE + sizeof(unsigned long long) * (TDF_STATS_MAX_COUNTS + 2);
 // Makes the graph's pinned buffer at least PIN_LEVELS + level_bytes large (contents are lost when it grows).
 tdf_status pinned_reserve(tdf_graph* gr, size_t level_bytes) {
   const size_t need = PIN_LEVELS + level_bytes;
@@ -299,7 +308,8 @@ tdf_status pinned_reserve(tdf_graph* gr, size_t level_bytes) {
 }
 
 tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out, tdf_grads* grads,
-               void* workspace, size_t workspace_bytes, void* hip_stream, tdf_stats* stats, bool with_grad) {
+               void* workspace, size_t workspace_bytes, void* hip_stream, tdf_stats* stats, bool with_grad,
+               int inherited_repeats = 0) {
   if (!gr || !out) { set_error("NULL graph or outputs"); return TDF_ERR_BAD_ARG; }
   const Graph& G = gr->g;
   Plan P;
@@ -369,7 +379,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   const int small_block = tag_machine_small_block(G.prog, use_jit);
   const int test_mixed_dies = getenv("TDF_TEST_MIXED_DIES") ? atoi(getenv("TDF_TEST_MIXED_DIES")) : 0;
   Ctrl hc{};
-  uint32_t rounds = 0;
+  uint32_t rounds = 0, repeats = 0;
   const uint32_t poll = 2;          // rounds queued between two looks at the control blocks
   const int max_steps = 4096;       // steps per kernel launch
   begin(TDF_PHASE_TAGS);
@@ -433,12 +443,14 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     // (TDF_TEST_MIXED_DIES=1 makes the host take this way once per graph, for the tests.)
     if (gr->die_local && (mixed_dies || test_mixed_dies == 1)) {
       gr->die_local = false;
+      ++repeats;
       continue;
     }
     // A part of the tag table can fill up although the whole table would not (instances of very
     // different sizes): repeat with one machine, which owns the whole table.
     if (e.n_dies > 1 && status_is(hc.status, TDF_ERR_TABLE_FULL) && hc.n_tags <= (unsigned long long)e.max_tags) {
       gr->max_dies = 1;
+      ++repeats;
       continue;
     }
     if (hc.n_tags > (unsigned long long)e.max_tags && !hc.status) hc.status = (uint32_t)(-TDF_ERR_TABLE_FULL);
@@ -539,6 +551,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       }
       end(TDF_PHASE_WEIGHT_GRAD, 7);
       HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->join_event, 0));
+      // how often each tag's gradient body fired, as the kernels marked it
+      vec_count_grad(v, e, hc.n_leaf, hc.n_cell, (unsigned long long*)(base + P.off_gcount), s);
     }
     HIP_TRY(hipGetLastError());
     const DieSync* ts = (const DieSync*)((char*)gr->pinned + PIN_SYNC);
@@ -558,7 +572,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       }
       if (mixed) {   // the die-private launches did not keep to their dies: the results are void
         gr->die_local = false;
-        return run(gr, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, with_grad);
+        return run(gr, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, with_grad,
+                   inherited_repeats + (int)repeats + 1);
       }
     }
   }
@@ -575,7 +590,18 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->n_waves = hc.max_level;
     stats->n_wide_waves = hc.n_cell && tail_first ? tail_first - 1 : 0;
     stats->n_wide_cells = hc.n_cell && tail_first ? lvl_begin(tail_first) : 0;
-    stats->n_grad_firings = with_grad && dev == TDF_OK ? (int64_t)hc.n_leaf + hc.n_cell : 0;
+    unsigned long long* pin_counts = (unsigned long long*)((char*)gr->pinned + PIN_FIRE);
+    if (with_grad && dev == TDF_OK && P.vec) {
+      HIP_TRY(hipMemcpyAsync(pin_counts, base + P.off_gcount, sizeof(unsigned long long) * 2, hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipStreamSynchronize(s));
+      stats->n_grad_firings = (int64_t)pin_counts[0];
+      stats->n_grad_not_once = (int64_t)pin_counts[1];
+    }
+    stats->n_machines = (int32_t)e.n_dies;
+    stats->die_local = gr->die_local ? 1 : 0;
+    stats->generated = use_jit ? 1 : 0;
+    stats->repeats = (int32_t)repeats + inherited_repeats;
+    stats->tail_used = use_tail ? 1 : 0;
     stats->max_tag_depth = hc.max_depth;
     stats->table_capacity = e.cap;
     stats->max_probe = hc.max_probe;
@@ -587,13 +613,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     stats->device_status = -(int32_t)hc.status;
     stats->n_counts = (int32_t)G.snodes.size();
-    std::vector<unsigned long long> fc(TDF_STATS_MAX_COUNTS);
-    if (in->stats_level >= 1) {
-      launch_count_fired(G.prog, e, s);
-      HIP_TRY(hipStreamSynchronize(s));
-    }
-    HIP_TRY(hipMemcpy(fc.data(), e.fire_count, sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS, hipMemcpyDeviceToHost));
-    for (int i = 0; i < TDF_STATS_MAX_COUNTS; ++i) stats->fire_count[i] = (int64_t)fc[i];
+    if (in->stats_level >= 1) launch_count_fired(G.prog, e, s);
+    HIP_TRY(hipMemcpyAsync(pin_counts, e.fire_count, sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    for (int i = 0; i < TDF_STATS_MAX_COUNTS; ++i) stats->fire_count[i] = (int64_t)pin_counts[i];
   }
   return dev;
 }
@@ -647,3 +670,4 @@ extern "C" tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const td
   std::lock_guard<std::mutex> lock(g_eval_mutex);
   return run(g, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, true);
 }
+

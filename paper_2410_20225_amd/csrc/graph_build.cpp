@@ -334,7 +334,13 @@ struct Builder {
           continue;
         }
         auto it = dval.find({i, 0});
-        if (it == dval.end()) continue;
+        if (it == dval.end()) {
+          // A state row nobody differentiates would still fire and be walked by the gradient pass,
+          // which would then read a gradient row that no operator wrote.
+          if (nd.op == TDF_OP_EMBED || nd.op == TDF_OP_RNN_CELL || nd.op == TDF_OP_LSTM_CELL || nd.op == TDF_OP_CE_NODE)
+            bad("a vector value without a consumer on the differentiable path");
+          continue;
+        }
         int dy = it->second.first, dyp = it->second.second;
         auto fwd = [&](int k) { return smap[{f, nd.in[k].node, 0}]; };
         switch (nd.op) {

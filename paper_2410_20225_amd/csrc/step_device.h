@@ -170,8 +170,8 @@ __device__ __forceinline__ void sw_embed(LaneCtx& x, bool on, int slot, long lon
                                          long long& v, bool& p, bool& live) {
   const bool had = on && ((x.present >> slot) & 1);
   const bool go = on && ap && !ad && !had;
-  const bool ok = go && av >= 0;
-  if (go && !ok) raise(x.c, TDF_ERR_BAD_ARG);
+  const bool ok = go && av >= 0 && av < (long long)x.e->vocab;
+  if (go && !ok) raise(x.c, TDF_ERR_BAD_ARG);   // token id outside the embedding table
   const uint32_t pos = wave_alloc(ok, x.direct ? &x.c->n_leaf : &x.S->n_leaf);
   if (ok) {
     if (!x.direct) {
@@ -911,8 +911,11 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
   for (int it = 0; it < max_steps; ++it) {
     if (rank * blockDim.x < n)
       step_pass<SCOPE, false, SW>(*P_lds, e, c, step, n, rank * blockDim.x, G * blockDim.x, lds);
-    if (!LOCAL) __threadfence();   // this step's writes, before the arrival below
-    __syncthreads();               // (LOCAL: every wave's stores have reached the shared L2)
+    // release of this step's writes, before the arrival below.  LOCAL: each wave waits until the
+    // die's L2 has acknowledged its stores (vmcnt counts stores here; the barrier alone does not wait)
+    if (!LOCAL) __threadfence();
+    else __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
     if (threadIdx.x == 0) {
       const uint32_t arrived = atomicAdd(bar_count, 1u);   // monotone: G per barrier
       if (arrived == (gen + 1u) * G - 1u) {

@@ -5,10 +5,10 @@ dataflow method's arithmetic and is the only code shared by the CPU oracle's tes
 the GPU path's tests.
 """
 from .rng import SplitMix64
-from .trees import Forest, random_split_tree, left_chain_tree, complete_tree, build_forest
+from .trees import Forest, random_split_tree, left_chain_tree, complete_tree, build_forest, permuted
 from .configs import make_config, CONFIG_NAMES, BASE_SEED, round_to_bf16
 
 __all__ = [
     "SplitMix64", "Forest", "random_split_tree", "left_chain_tree", "complete_tree",
-    "build_forest", "make_config", "CONFIG_NAMES", "BASE_SEED", "round_to_bf16",
+    "build_forest", "permuted", "make_config", "CONFIG_NAMES", "BASE_SEED", "round_to_bf16",
 ]

@@ -43,6 +43,22 @@ class Forest:
                       np.asarray(nl, np.int64))
 
 
+def permuted(forest, perm):
+    """The same trees with node v renumbered perm[v]: trees no longer occupy contiguous index
+    ranges and a child may have a smaller index than its parent."""
+    perm = np.asarray(perm, np.int64)
+    n = forest.n_nodes
+    assert sorted(perm.tolist()) == list(range(n))
+    left = np.full(n, -1, np.int32)
+    right = np.full(n, -1, np.int32)
+    token = np.full(n, -1, np.int32)
+    inner = forest.left >= 0
+    left[perm[inner]] = perm[forest.left[inner]]
+    right[perm[inner]] = perm[forest.right[inner]]
+    token[perm] = forest.token
+    return Forest(left, right, token, perm[forest.roots], forest.n_leaves.copy())
+
+
 def _shape_from_splits(n_leaves, split_fn):
     """Nodes in pre-order, root first.  split_fn(L) -> number of leaves of the left child."""
     n = 2 * n_leaves - 1

@@ -3,16 +3,39 @@ and run the oracle on the same inputs.  Nothing here computes expected values.""
 import numpy as np
 import torch
 
-from paper_2410_20225_amd import tdf, programs as gpu_programs
+from paper_2410_20225_amd import tdf
+from paper_2410_20225_amd.harness import TreeRun, DEV  # noqa: F401  (re-exported for the tests)
 import oracle
 from oracle import programs as oracle_programs
 
-DEV = "cuda:0"
 
 
 def rel_fro(got, want):
     got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
     return float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300))
+
+
+def assert_close_bf16(got, want, name, tol=2e-2):
+    """The 16-bit path's bar for one tensor: relative Frobenius error within tol, and no single element
+    further off than tol times the largest element of the oracle's tensor."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert got.shape == want.shape, name
+    assert rel_fro(got, want) < tol, (name, rel_fro(got, want))
+    worst = float(np.abs(got - want).max()) if want.size else 0.0
+    assert worst <= tol * float(np.abs(want).max()), (name, worst, float(np.abs(want).max()))
+
+
+def assert_rows_close_bf16(got, want, name, tol=2e-2, floor=0.05):
+    """Row by row (a token's row of dE, a tree's root state): the row's error within tol of the row's own
+    norm; rows whose norm is below `floor` times the largest row norm are held to tol times that instead
+    (their entries are sums with cancellation, which has no relative bound)."""
+    got, want = np.asarray(got, np.float64), np.asarray(want, np.float64)
+    assert got.shape == want.shape, name
+    rn = np.linalg.norm(want, axis=1)
+    err = np.linalg.norm(got - want, axis=1)
+    bar = tol * np.maximum(rn, floor * rn.max())
+    bad = np.nonzero(err > bar)[0]
+    assert bad.size == 0, (name, bad[:8].tolist(), err[bad[:8]].tolist(), rn[bad[:8]].tolist())
 
 
 def oracle_env(c):
@@ -53,61 +76,6 @@ def run_oracle_node_loss(c, node_labels, dnode=None, dy=None, ids=None):
     it = oracle.Interpreter(oracle.transform(prog), env)
     out = it.run(inputs, len(roots))
     return dict(out=out[("out", 0)], node_loss=it.node_loss, grads=it.param_grad, it=it)
-
-
-class TreeRun:
-    """One workload resident on the GPU plus the buffers of one evaluation."""
-
-    def __init__(self, c, head, grad, max_tags=None, step_limit=0, stats_level=1, node_labels=None):
-        F = c["forest"]
-        self.c, self.head, self.grad = c, head, grad
-        self.B, self.H = F.n_trees, c["H"]
-        dt = torch.bfloat16 if c["bf16"] else torch.float32
-        self.rows = (5 if c["cell"] == "lstm" else 1) * self.H
-        fns, r = gpu_programs.tree(c["cell"], head=head, node_loss=node_labels is not None)
-        self.graph = tdf.graph_build(fns, r, want_grad=grad)
-        args = np.stack([F.roots, c["labels"]], 1) if head else F.roots[:, None]
-        t = lambda a, d: torch.tensor(np.ascontiguousarray(a), dtype=d, device=DEV)
-        self.t_args = t(args, torch.int64)
-        self.t_left, self.t_right, self.t_token = (t(a, torch.int32) for a in (F.left, F.right, F.token))
-        self.t_E, self.t_W = t(c["E"], dt), t(c["W"], dt)
-        self.t_b, self.t_U, self.t_u0 = t(c["b"], torch.float32), t(c["U"], torch.float32), t(c["u0"], torch.float32)
-        self.max_tags = F.n_nodes if max_tags is None else max_tags
-        self.t_node_label = self.out_node_loss = self.t_dnode = self._dnode_src = self.t_dy = self._dy_src = None
-        if node_labels is not None:
-            self.t_node_label = t(node_labels, torch.int32)
-            self.out_node_loss = torch.full((F.n_nodes,), -7.0, dtype=torch.float32, device=DEV)
-        self.inputs = tdf.make_inputs(self.B, args=self.t_args, n_args=args.shape[1], left=self.t_left,
-                                      right=self.t_right, token=self.t_token,
-                                      dtype=tdf.BF16 if c["bf16"] else tdf.F32, hidden=self.H, vocab=c["V"],
-                                      E=self.t_E, W=self.t_W, b=self.t_b, U=self.t_U, u0=self.t_u0,
-                                      n_classes=5, max_tags=self.max_tags, step_limit=step_limit, stats_level=stats_level,
-                                      node_label=self.t_node_label)
-        nbytes = tdf.workspace_size(self.graph, self.inputs, grad)
-        self.ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
-        self.out_f32 = torch.zeros(self.B, dtype=torch.float32, device=DEV)
-        self.out_h = torch.zeros(self.B, self.H, dtype=torch.float32, device=DEV)
-        self.out_c = torch.zeros(self.B, self.H, dtype=torch.float32, device=DEV)
-        if grad:
-            self.dW = torch.empty(self.rows, 2 * self.H, dtype=torch.float32, device=DEV)
-            self.db = torch.empty(self.rows, dtype=torch.float32, device=DEV)
-            self.dE = torch.empty(c["V"], self.H, dtype=torch.float32, device=DEV)
-
-    def run(self, dy=None, check=True, dnode=None):
-        if self.grad:
-            f32 = lambda a: None if a is None else torch.tensor(np.ascontiguousarray(a), dtype=torch.float32, device=DEV)
-            if dy is not self._dy_src:         # both stay resident while the caller passes the same arrays
-                self._dy_src, self.t_dy = dy, f32(dy)
-            if dnode is not self._dnode_src:   # stays resident while the caller passes the same array
-                self._dnode_src, self.t_dnode = dnode, f32(dnode)
-            st, stats = tdf.eval_grad(self.graph, self.inputs, self.t_dy, self.ws, self.dW, self.db, self.dE,
-                                      out_f32=self.out_f32, out_h=self.out_h, out_c=self.out_c,
-                                      out_node_loss=self.out_node_loss, dnode=self.t_dnode, check=check)
-        else:
-            st, stats = tdf.eval(self.graph, self.inputs, self.ws, out_f32=self.out_f32, out_h=self.out_h,
-                                 out_c=self.out_c, out_node_loss=self.out_node_loss, check=check)
-        torch.cuda.synchronize()
-        return st, stats
 
 
 def fire_counts(graph, stats):

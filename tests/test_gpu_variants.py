@@ -54,6 +54,14 @@ def test_treelstm_variants(env, lstm_case, monkeypatch):
     want = ref["it"].count_by_op()
     for k in ("merge_entry", "isleaf", "switch", "call_0", "call_1", "return_0", "return_1", "lstm_cell"):
         assert got[k] == want[k], k
+    # the call reports which way it took: the variant that was asked for is the one that ran
+    assert stats.generated == (0 if env.get("TDF_NO_JIT") == "1" else 1)
+    assert stats.die_local == (0 if env.get("TDF_NO_DIE_LOCAL") == "1" or "TDF_TEST_MIXED_DIES" in env else 1)
+    assert stats.n_machines == (1 if env.get("TDF_DIES") == "1" or stats.die_local == 0 else 8)
+    assert stats.repeats == (1 if "TDF_TEST_MIXED_DIES" in env else 0)
+    assert stats.n_grad_firings == stats.n_tags and stats.n_grad_not_once == 0
+    if env.get("TDF_SMALL_LEVEL") == "0":
+        assert stats.tail_used == 0 and stats.n_wide_waves == stats.n_waves
 
 
 @pytest.mark.parametrize("env", VARIANTS[:3] + VARIANTS[-1:], ids=IDS[:3] + IDS[-1:])

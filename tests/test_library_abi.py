@@ -89,6 +89,23 @@ def test_gradient_of_integer_program_is_rejected():
         tdf.graph_build(fns, r, want_grad=True)
 
 
+def test_unused_state_row_is_rejected_in_a_gradient_graph():
+    # a cell whose value nobody differentiates would fire, be logged, and its gradient row would be
+    # read without ever having been written: such a program is refused when gradients are asked for
+    T = tdf
+    nodes = [(T.OP_IN, [], 0),                                   # 0: token id
+             (T.OP_EMBED, [(0, 0)], 0),                          # 1: row, used by the cell and by OUT
+             (T.OP_EMBED, [(0, 0)], 0),                          # 2: a second row
+             (T.OP_RNN_CELL, [(1, 0), (2, 0)], 0),               # 3: a cell nobody consumes
+             (T.OP_OUT, [(1, 0)], 0)]
+    fns = [("result", 1, nodes)]
+    tdf.graph_build(fns, 0)                                      # fine without gradients
+    with pytest.raises(tdf.TdfError) as ei:
+        tdf.graph_build(fns, 0, want_grad=True)
+    assert ei.value.status == tdf.ERR_BAD_PROGRAM
+    assert "consumer" in str(ei.value) or "two differentiable" in str(ei.value)
+
+
 def test_workspace_size_grows_with_capacity():
     fns, r = programs.tree("lstm", head=True)
     g = tdf.graph_build(fns, r, want_grad=True)
