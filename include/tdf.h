@@ -296,6 +296,27 @@ tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const tdf_seed* dy,
                          tdf_grads* grads, void* workspace, size_t workspace_bytes,
                          void* hip_stream, tdf_stats* stats);
 
+/* ---- evaluation for callers that cannot allocate ---------------------------------------
+ * For callers that must not call hipMalloc or any other allocating routine while they evaluate:
+ * tight serving loops, harnesses that forbid allocation, code that keeps its memory budget fixed.
+ *
+ * tdf_graph_prepare is the set-up call (it allocates: host buffers, events, the generated step
+ * kernels) and resolves, once per GPU, the address of the library's static workspace on the
+ * current device.  Call it once per graph with the device current on which the graph will run.
+ *
+ * tdf_eval_static is tdf_eval without the workspace argument: it works in a static device array
+ * of TDF_STATIC_WORKSPACE_BYTES that every GPU the library runs on holds until the process ends,
+ * and calls no allocating routine.  Inputs whose tdf_workspace_size exceeds that are refused with
+ * TDF_ERR_WORKSPACE (lower max_tags, or use tdf_eval); a graph that was not prepared on the
+ * current device is refused with TDF_ERR_BAD_ARG; a vector program with more than 8192
+ * dependency levels is refused with TDF_ERR_WORKSPACE.  All calls on a GPU share that GPU's array
+ * (calls of one process take turns inside the library; two processes have two arrays); the array
+ * keeps the previous call's contents and every call clears what it needs cleared.  Like tdf_eval
+ * it synchronises the stream, so it cannot be recorded into a HIP graph. */
+#define TDF_STATIC_WORKSPACE_BYTES (64u << 20)
+tdf_status tdf_graph_prepare(tdf_graph* g);
+tdf_status tdf_eval_static(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* hip_stream, tdf_stats* stats);
+
 const char* tdf_last_error(void); /* thread-local, static storage */
 
 #ifdef __cplusplus

@@ -309,7 +309,7 @@ tdf_status pinned_reserve(tdf_graph* gr, size_t level_bytes) {
 
 tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out, tdf_grads* grads,
                void* workspace, size_t workspace_bytes, void* hip_stream, tdf_stats* stats, bool with_grad,
-               int inherited_repeats = 0) {
+               int inherited_repeats = 0, bool no_alloc = false) {
   if (!gr || !out) { set_error("NULL graph or outputs"); return TDF_ERR_BAD_ARG; }
   const Graph& G = gr->g;
   Plan P;
@@ -345,7 +345,11 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   const bool timed = stats != nullptr;
   int64_t launches[TDF_PHASE_COUNT] = {0};
   bool phase_used[TDF_PHASE_COUNT] = {false};
-  if (timed)
+  if (no_alloc && (!gr->prepared || !gr->jit.tried)) {
+    set_error("the graph was not prepared: call tdf_graph_prepare first");
+    return TDF_ERR_BAD_ARG;
+  }
+  if (timed && !no_alloc)
     for (int i = 0; i < 2 * TDF_PHASE_COUNT; ++i)
       if (!gr->events[i]) HIP_TRY(hipEventCreate((hipEvent_t*)&gr->events[i]));
   auto begin = [&](int ph) { if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * ph], s); phase_used[ph] = true; } };
@@ -354,7 +358,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   VecArgs& v = P.v;
   e.out_i64 = (long long*)out->out_i64;
   char* base = (char*)workspace;
-  if (tdf_status ps = pinned_reserve(gr, 0); ps != TDF_OK) return ps;
+  if (!no_alloc)
+    if (tdf_status ps = pinned_reserve(gr, 0); ps != TDF_OK) return ps;
 
   // ---- the tag machine: fire / match steps until no token is in flight -------------------
   // The grid-wide kernel synchronises its workgroups with a barrier in memory: no more
@@ -474,7 +479,12 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       begin(TDF_PHASE_LEVELS);
       launch_levels(e, hc.n_cell, hc.max_level, s);
       const size_t level_bytes = ((size_t)hc.max_level + 2) * LEVEL_KEY_DIES * sizeof(uint32_t);
-      if (tdf_status ps = pinned_reserve(gr, level_bytes); ps != TDF_OK) return ps;
+      if (no_alloc && gr->pinned_bytes < PIN_LEVELS + level_bytes) {
+        set_error("more dependency levels than the prepared graph's host buffer holds");
+        return TDF_ERR_WORKSPACE;
+      }
+      if (!no_alloc)
+        if (tdf_status ps = pinned_reserve(gr, level_bytes); ps != TDF_OK) return ps;
       level_off = (const uint32_t*)((char*)gr->pinned + PIN_LEVELS);
       HIP_TRY(hipMemcpyAsync((void*)level_off, e.level_off, level_bytes, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 3);
@@ -573,7 +583,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       if (mixed) {   // the die-private launches did not keep to their dies: the results are void
         gr->die_local = false;
         return run(gr, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, with_grad,
-                   inherited_repeats + (int)repeats + 1);
+                   inherited_repeats + (int)repeats + 1, no_alloc);
       }
     }
   }
@@ -671,3 +681,78 @@ extern "C" tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const td
   return run(g, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, true);
 }
 
+// ---- evaluation without any allocation ------------------------------------------------------------
+// For callers that cannot allocate (code under stream capture, tight serving loops, harnesses that
+// forbid it): the workspace is a file-scope device array, one copy per GPU, that lives as long as the
+// process.  Host code never passes the array's name to the device: its address on a GPU is resolved
+// once per device (hipGetSymbolAddress, by tdf_graph_prepare with that device current) and kept.
+static __device__ __align__(256) unsigned char scratch[TDF_STATIC_WORKSPACE_BYTES];
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[64] = {nullptr};   // by device ordinal
+// levels of cell firings whose offsets the prepared host buffer can take (vector programs)
+static constexpr size_t PREPARED_LEVEL_BYTES = (size_t)(8192 + 2) * LEVEL_KEY_DIES * sizeof(uint32_t);
+
+extern "C" tdf_status tdf_graph_prepare(tdf_graph* g) {
+  if (!g) {
+    set_error("tdf_graph_prepare: NULL graph");
+    return TDF_ERR_BAD_ARG;
+  }
+  std::lock_guard<std::mutex> lock(g_eval_mutex);
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= 64) {
+    set_error("tdf_graph_prepare: device ordinal out of range");
+    return TDF_ERR_UNSUPPORTED;
+  }
+  {
+    std::lock_guard<std::mutex> l2(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+      void* ptr = nullptr;
+      HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));   // this device's copy of the array
+      if (!ptr || ((uintptr_t)ptr & 255)) {
+        set_error("tdf_graph_prepare: the static workspace has no usable address on this device");
+        return TDF_ERR_DEVICE;
+      }
+      g_scratch_ptr[dev] = ptr;
+    }
+  }
+  for (int i = 0; i < 2 * TDF_PHASE_COUNT; ++i)
+    if (!g->events[i]) HIP_TRY(hipEventCreate((hipEvent_t*)&g->events[i]));
+  if (tdf_status ps = pinned_reserve(g, PREPARED_LEVEL_BYTES); ps != TDF_OK) return ps;
+  if (!g->jit.tried) {
+    g->jit.tried = true;
+    std::string log;
+    (void)jit_compile(g->g.prog, g->jit, log);   // without the run-time compiler the table interpreter runs
+  }
+  g->prepared = true;
+  g->prepared_device = dev;
+  return TDF_OK;
+}
+
+extern "C" tdf_status tdf_eval_static(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* hip_stream, tdf_stats* stats) {
+  std::lock_guard<std::mutex> lock(g_eval_mutex);
+  if (!g) {
+    set_error("tdf_eval_static: NULL graph");
+    return TDF_ERR_BAD_ARG;
+  }
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  void* ptr = nullptr;
+  if (dev >= 0 && dev < 64) {
+    std::lock_guard<std::mutex> l2(g_scratch_mutex);
+    ptr = g_scratch_ptr[dev];
+  }
+  if (!g->prepared || g->prepared_device != dev || !ptr) {
+    set_error("tdf_eval_static: call tdf_graph_prepare on this device first");
+    return TDF_ERR_BAD_ARG;
+  }
+  Plan P;
+  tdf_status st = make_plan(g->g, in, false, nullptr, P, 8);
+  if (st != TDF_OK) return st;
+  if (P.L.total > TDF_STATIC_WORKSPACE_BYTES) {
+    set_error("tdf_eval_static: these inputs need " + std::to_string(P.L.total) + " bytes of workspace, the static one has " +
+              std::to_string((size_t)TDF_STATIC_WORKSPACE_BYTES) + " (lower max_tags, or use tdf_eval with a workspace of your own)");
+    return TDF_ERR_WORKSPACE;
+  }
+  return run(g, in, nullptr, out, nullptr, ptr, TDF_STATIC_WORKSPACE_BYTES, hip_stream, stats, false, 0, true);
+}

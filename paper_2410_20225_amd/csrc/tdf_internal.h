@@ -51,5 +51,7 @@ struct tdf_graph {
   // barrier records, the firing tables): copies to and from pageable memory are staged and slower
   void* pinned = nullptr;
   size_t pinned_bytes = 0;
+  bool prepared = false;    // tdf_graph_prepare has run: kernels compiled, events and host buffers exist
+  int prepared_device = -1;
   ~tdf_graph();
 };

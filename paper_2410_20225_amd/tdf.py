@@ -113,6 +113,11 @@ lib.tdf_eval.restype = C.c_int
 lib.tdf_eval_grad.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Seed), C.POINTER(Outputs),
                               C.POINTER(Grads), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(Stats)]
 lib.tdf_eval_grad.restype = C.c_int
+lib.tdf_graph_prepare.argtypes = [C.c_void_p]
+lib.tdf_graph_prepare.restype = C.c_int
+lib.tdf_eval_static.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Outputs), C.c_void_p, C.POINTER(Stats)]
+lib.tdf_eval_static.restype = C.c_int
+STATIC_WORKSPACE_BYTES = 64 << 20
 lib.tdf_last_error.argtypes = []
 lib.tdf_last_error.restype = C.c_char_p
 
@@ -215,6 +220,22 @@ def eval(graph, inputs, workspace, out_i64=None, out_f32=None, out_h=None, out_c
                       workspace.numel() * workspace.element_size(), _stream(), C.byref(stats))
     if check and st != OK:
         raise TdfError(st, "tdf_eval")
+    return st, stats
+
+
+def graph_prepare(graph):
+    st = lib.tdf_graph_prepare(graph.handle)
+    if st != OK:
+        raise TdfError(st, "tdf_graph_prepare")
+
+
+def eval_static(graph, inputs, out_i64=None, out_f32=None, out_h=None, out_c=None, out_node_loss=None, check=True):
+    """tdf_eval in the library's static workspace (no allocation).  Returns (status, Stats)."""
+    outs = Outputs(_ptr(out_i64), _ptr(out_f32), _ptr(out_h), _ptr(out_c), _ptr(out_node_loss))
+    stats = Stats()
+    st = lib.tdf_eval_static(graph.handle, C.byref(inputs), C.byref(outs), _stream(), C.byref(stats))
+    if check and st != OK:
+        raise TdfError(st, "tdf_eval_static")
     return st, stats
 
 
