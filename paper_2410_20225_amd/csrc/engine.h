@@ -21,7 +21,8 @@ struct alignas(128) Ctrl {
   uint32_t n_head;           // CE_HEAD firings
   uint32_t status;           // 0, or -(tdf_status) raised on the device
   uint32_t done;
-  uint32_t max_probe, max_depth, max_level;
+  uint32_t n_alloc;          // frames handed out so far: the next free record of this machine's part
+  uint32_t max_depth, max_level;
   uint32_t bar_count;        // grid barrier of the grid-wide step kernel: arrivals (monotone)
   uint32_t bar_gen;          // ... and completed barriers
   uint32_t wbar_count, wbar_gen;   // the same for the device-wide kernel (another number of workgroups)
@@ -32,30 +33,35 @@ struct alignas(128) Ctrl {
   unsigned long long n_tags, n_tokens;
 };
 
-// Frame record = one slot of the tag-hash table = one call-context tag (Section 5.1: a
-// frame holds the label i of the Call_i that created it and a reference to the previous
-// scope).  The key packs (parent frame + 1, iteration counter, label + 1): a tag of the paper
-// is (iteration number, pointer into the frame stack), and a loop scope is pushed on the same
-// stack as a function scope (Section 5.1).  Enter is the push of a scope with counter 0, so the
-// frame of a call is the frame of "iteration 0" of its label; Next keeps parent and label and
-// adds one to the counter; Exit pops like Return.  The keys of all slots
-// are also kept in a dense array of their own, which is what insertions probe (eight slots
-// per 64-byte line); the slot index is the frame id, so inserting a tag and allocating its
-// frame are one compare-and-swap.  The lane that inserts a key writes the frame's header;
-// frames of empty slots hold stale bytes and are never read.
+// Frame record = one call-context tag (Section 5.1: a frame holds the label i of the Call_i that
+// created it and a reference to the previous scope).  The key packs (parent frame + 1, iteration
+// counter, label + 1): a tag of the paper is (iteration number, pointer into the frame stack), and
+// a loop scope is pushed on the same stack as a function scope (Section 5.1).  Enter is the push
+// of a scope with counter 0, so the frame of a call is the frame of "iteration 0" of its label;
+// Next keeps parent and label and adds one to the counter; Exit pops like Return.
+//
+// The match table is keyed by (frame of t, i) and needs no probing: all Call_i tokens of one
+// call come from sweeps of the caller's frame, so the entry for (frame of t, i) is a child link
+// inside that frame's own record, one per call site of its function (and one for the next
+// iteration of a loop).  The first token of a call finds the link empty, takes the next free
+// record of its machine (wave ballot + prefix sum, one counter bump per wave) and writes the
+// link; later tokens of the same call follow the link.  Records are handed out in creation
+// order: frames that are created together, and completed together, share cache lines.  The lane
+// that creates a frame writes its header; records beyond the machine's counter are never read.
 //
 // Tokens delivered during step s set bits in the arrival word of step s+1; the sweep of step
 // s+1 takes that word (exchange with 0) and folds it into present_fn, which only the sweeping
 // lane writes.  The delivery that finds the word empty is the first to reach the frame in that
 // step and puts it on the next list.  Values delivered in one step are read in a later one, so
-// only key and arrived[] are ever accessed concurrently and need atomics.
+// only arrived[] is ever accessed concurrently and needs atomics.
 struct FrameHdr {
   unsigned long long key;     // (parent + 1) << 32 | iteration << 8 | (label + 1)
   unsigned long long fired;   // firing-table entries that have fired live under this tag
   uint32_t present_fn;        // bits 0..23: stored values present; bits 24..31: function
   uint32_t depth;             // length of the tag: call labels and iteration counters below the root
   uint32_t arrived[2];        // same layout as present_fn, by parity of the consuming step
-  // followed by int64 stored[n_stored]
+  // followed by int64 stored[max_stored], then uint32 link[n_links] (frame id + 1 of the scope opened at
+  // each site, 0 = not opened yet)
 };
 static_assert(sizeof(FrameHdr) == 32, "FrameHdr must be 32 bytes");
 
@@ -65,9 +71,9 @@ constexpr uint32_t LEVEL_KEY_DIES = 8;
 //
 // The instances of a batch never exchange tokens (their tags differ in the root), so the batch
 // is dealt to n_dies independent tag machines, instance b to machine b % n_dies.  A machine
-// has its own control block, its own part of the key array (its frames are the slots of that
-// part, plus the root records of its instances), its own touched lists and its own schedule
-// log; nothing it touches during the steps is touched by another machine.  Each machine runs
+// has its own control block, its own part of the frame records (plus the root records of its
+// instances), its own touched lists and its own schedule log; nothing it touches during the
+// steps is touched by another machine.  Each machine runs
 // on one accelerator die (XCD), so its atomics and step boundaries stay inside that die's L2.
 // Kernels receive the description of the whole engine and take the view of their machine
 // (die_view); after the last step the logs of the machines are merged.
@@ -76,13 +82,12 @@ struct Engine {
   Ctrl* ctrl;                       // [n_dies]; in a machine's view: its own block
   uint32_t n_dies;                  // machines: 1, 2, 4 or 8
   uint32_t die;                     // view: this machine
-  uint32_t key_base, part_mask;     // view: first slot of this machine's part of the table; slots per part - 1
+  uint32_t key_base, part;          // view: first frame record of this machine's part; records per part
   // per-machine schedule logs [n_dies][log_cap] (with one machine they are the merged logs below)
   uint32_t *m_leaf_row, *m_leaf_tok, *m_cell_out, *m_cell_l, *m_cell_r, *m_cell_lvl;
   unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
-  unsigned long long* keys;         // [cap] tag-hash table: the key of slot f, 0 = empty (frame f is then unused)
-  char* frames;                     // (cap + B) records of frame_stride bytes
-  uint32_t cap, cap_mask, n_inst, max_tags;
+  char* frames;                     // (cap + B) records of frame_stride bytes: n_dies parts, then the root records
+  uint32_t cap, n_inst, max_tags;   // cap = n_dies * part
   uint32_t* touched;                // per machine two lists of touched_cap frame ids, by step parity
   uint32_t touched_cap;
   uint32_t step_limit;
@@ -121,7 +126,7 @@ inline __host__ __device__ Engine die_view(const Engine& e, uint32_t d) {
   Engine v = e;
   v.die = d;
   v.ctrl = e.ctrl + d;
-  v.key_base = d * (e.part_mask + 1u);
+  v.key_base = d * e.part;
   v.touched = e.touched + (size_t)d * 2 * e.touched_cap;
   const size_t o = (size_t)d * e.log_cap;
   v.leaf_row = e.m_leaf_row + o;
@@ -132,16 +137,14 @@ inline __host__ __device__ Engine die_view(const Engine& e, uint32_t d) {
   v.cell_lvl = e.m_cell_lvl + o;
   return v;
 }
-// Slot `off` places after `slot` in its machine's part of the table (linear probing wraps there).
-inline __device__ uint32_t slot_after(const Engine& e, uint32_t slot, uint32_t off) {
-  return e.key_base + ((slot - e.key_base + off) & e.part_mask);
-}
-
 inline __device__ FrameHdr* frame_at(const Engine& e, int stride, uint32_t f) {
   return reinterpret_cast<FrameHdr*>(e.frames + (size_t)f * stride);
 }
 inline __device__ long long* frame_slots(FrameHdr* h) {
   return reinterpret_cast<long long*>(h + 1);
+}
+inline __device__ uint32_t* frame_links(FrameHdr* h, int links_off) {
+  return reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(h) + links_off);
 }
 
 // ---- wave-level helpers (64-wide wavefronts) ------------------------------------------------
@@ -149,16 +152,6 @@ inline __device__ unsigned lane_id() { return __lane_id(); }
 
 inline __device__ unsigned long long lanemask_lt() {
   return (1ull << lane_id()) - 1ull;
-}
-
-// fmix64 of MurmurHash3 (Appleby, public domain).
-inline __device__ unsigned long long mix64(unsigned long long x) {
-  x ^= x >> 33;
-  x *= 0xff51afd7ed558ccdULL;
-  x ^= x >> 33;
-  x *= 0xc4ceb9fe1a85ec53ULL;
-  x ^= x >> 33;
-  return x;
 }
 
 // Wave-level compaction: lanes with `take` get consecutive positions from *counter.
@@ -171,6 +164,22 @@ inline __device__ uint32_t wave_alloc(bool take, uint32_t* counter) {
   if ((int)lane_id() == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
   base = __shfl(base, leader);
   return base + (uint32_t)__popcll(m & lanemask_lt());
+}
+
+// The same for two requests per lane at once (one counter bump per wave): positions of the first
+// requests, then of the second ones.  SCOPE: memory scope of the bump.
+template <int SCOPE>
+inline __device__ void wave_alloc2(bool take0, bool take1, uint32_t* counter, uint32_t& pos0, uint32_t& pos1) {
+  const unsigned long long m0 = __ballot(take0), m1 = __ballot(take1);
+  pos0 = pos1 = 0;
+  if ((m0 | m1) == 0) return;
+  const int leader = __ffsll((long long)(m0 | m1)) - 1;
+  uint32_t base = 0;
+  if ((int)lane_id() == leader)
+    base = __hip_atomic_fetch_add(counter, (uint32_t)(__popcll(m0) + __popcll(m1)), __ATOMIC_RELAXED, SCOPE);
+  base = __shfl(base, leader);
+  pos0 = base + (uint32_t)__popcll(m0 & lanemask_lt());
+  pos1 = base + (uint32_t)__popcll(m0) + (uint32_t)__popcll(m1 & lanemask_lt());
 }
 
 // Lanes with `take` get unique consecutive positions in counters[key]; lanes of the wave

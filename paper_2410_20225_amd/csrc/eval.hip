@@ -106,14 +106,15 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   const uint32_t T = (uint32_t)in->max_tags;
   e.n_inst = B;
   e.max_tags = T;
-  e.cap = pow2_at_least(2ull * T);
   e.n_dies = dies_for(B, max_dies);
-  // Without vector operators a table slot costs one frame record and no state rows: every
-  // machine's part is then as large as the whole table would be, so that instances of very
+  // Frame records are handed out per machine, each from its own part.  One machine: the part holds
+  // max_tags.  Several: twice a machine's even share; or, where records are small and few (no
+  // vector operators: a record costs no state rows), max_tags each, so that instances of very
   // different sizes (fib(20) beside fib(3)) cannot overflow a part.
-  if (!P.vec && (uint64_t)e.cap * e.n_dies <= (1ull << 26)) e.cap *= e.n_dies;
-  e.cap_mask = e.cap - 1;
-  e.part_mask = e.cap / e.n_dies - 1;
+  e.part = T;
+  if (e.n_dies > 1 && !(!P.vec && (uint64_t)T * e.n_dies <= (1ull << 24)))
+    e.part = std::min<uint64_t>(T, 2ull * ((T + e.n_dies - 1) / e.n_dies) + 64);
+  e.cap = e.part * e.n_dies;
   e.die = 0;
   e.key_base = 0;
   e.step_limit = in->step_limit > 0 ? (uint32_t)in->step_limit : (1u << 20);
@@ -138,7 +139,6 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     P.off_gcount = L.take(sizeof(unsigned long long) * 2);
     off_gmark = L.take(sizeof(uint32_t) * ((size_t)e.cap + B));
   }
-  size_t off_keys = L.take(sizeof(unsigned long long) * (size_t)e.cap);
   L.zero_end = L.total;
   P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));   // headers are written on insertion
   // --- the rest is written before it is read
@@ -169,7 +169,6 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.level_count = (uint32_t*)at(off_lcount);
   e.level_fill = (uint32_t*)at(off_lfill);
   e.level_off = (uint32_t*)at(off_loff);
-  e.keys = (unsigned long long*)at(off_keys);
   e.frames = at(P.off_frames);
   e.touched = (uint32_t*)at(off_touched);
   e.root_ref = (uint32_t*)at(off_root);
@@ -434,7 +433,6 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       hc.n_leaf += c.n_leaf; hc.n_cell += c.n_cell; hc.n_head += c.n_head;
       hc.n_tags += c.n_tags; hc.n_tokens += c.n_tokens;
       hc.step = std::max(hc.step, c.step);
-      hc.max_probe = std::max(hc.max_probe, c.max_probe);
       hc.max_depth = std::max(hc.max_depth, c.max_depth);
       hc.max_level = std::max(hc.max_level, c.max_level);
       if (!hc.status) hc.status = c.status;
@@ -614,7 +612,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->tail_used = use_tail ? 1 : 0;
     stats->max_tag_depth = hc.max_depth;
     stats->table_capacity = e.cap;
-    stats->max_probe = hc.max_probe;
+    stats->max_probe = hc.n_tags > e.n_inst ? 1 : 0;   // the match table is addressed without collisions
     for (int ph = 0; ph < TDF_PHASE_COUNT; ++ph) {
       float ms = 0.f;
       if (phase_used[ph] && hipEventElapsedTime(&ms, (hipEvent_t)gr->events[2 * ph], (hipEvent_t)gr->events[2 * ph + 1]) == hipSuccess)

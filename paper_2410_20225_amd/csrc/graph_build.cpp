@@ -404,7 +404,7 @@ struct Builder {
     D.n_fn = P->n_functions;
     D.result_fn = P->result_fn;
     D.n_labels = G.n_labels;
-    int n_instr = 0, max_stored = 0;
+    int n_instr = 0, max_stored = 0, max_sites = 0;
     for (int f = 0; f < P->n_functions; ++f) {
       const auto& fn = F(f);
       std::map<std::pair<int, int>, int> val;   // (node, port) -> value id
@@ -526,15 +526,26 @@ struct Builder {
       for (int q = first; q < n_instr; ++q)
         n_emit += D.instr[q].op == D_CALL || D.instr[q].op == D_OUT || D.instr[q].op == D_NEXT;
       D.fn[f].n_emit = (uint8_t)n_emit;
-      int n_cl = 0;
-      for (int q = first; q < n_instr && n_cl < 6; ++q)
-        if (D.instr[q].op == D_CALL && D.instr[q].aux2 == 0) D.fn[f].call_labels[n_cl++] = D.instr[q].aux;
-      D.fn[f].n_call_labels = (uint8_t)n_cl;
+      // the scopes a frame of f opens (one child link each): its call / loop sites in table order,
+      // then the next iteration of a loop graph
+      int n_sites = 0;
+      bool has_next = false;
+      for (int q = first; q < n_instr; ++q) {
+        if (D.instr[q].op == D_CALL && D.instr[q].aux2 == 0) D.label_site[D.instr[q].aux] = (uint8_t)n_sites++;
+        has_next = has_next || D.instr[q].op == D_NEXT;
+      }
+      D.fn[f].next_site = (uint8_t)n_sites;
+      if (has_next) ++n_sites;
+      if (n_sites > MAX_SITES) bad("more than 8 call and loop sites in a function");
+      D.fn[f].n_sites = (uint8_t)n_sites;
+      if (n_sites > max_sites) max_sites = n_sites;
       if (n_stored > max_stored) max_stored = n_stored;
     }
-    // a frame never straddles a 128-byte line: 64 bytes if it fits, else whole lines
-    const int frame_bytes = 32 + 8 * max_stored;
-    D.frame_stride = frame_bytes <= 64 ? 64 : (frame_bytes + 127) / 128 * 128;
+    // frame record: 32-byte header, the stored values, the child links; records are handed out in
+    // creation order, so neighbours are created and completed together
+    D.links_off = 32 + 8 * max_stored;
+    D.n_links = max_sites;
+    D.frame_stride = (D.links_off + 4 * max_sites + 31) / 32 * 32;
     if ((int)G.snodes.size() > TDF_STATS_MAX_COUNTS) bad("static graph too large for tdf_stats");
   }
 };

@@ -5,9 +5,10 @@
 //           (Section 2.2: all inputs hold tokens with the same tag).  Dead values (hiatons)
 //           propagate; Switch, Merge and dead calls follow the paper's equations.
 //   match   the tokens a sweep emits are delivered right after it:
-//           Call_i  <t,d> -> <i:t,d>: find-or-insert the key (frame of t, tag length, i) in
-//                   the tag-hash table (Section 3; Section 5.1: a new frame that stores the
-//                   label i) and write the argument into that frame;
+//           Call_i  <t,d> -> <i:t,d>: find-or-insert the entry (frame of t, i) of the match
+//                   table, which is the child link of call site i in the frame of t (Section 3;
+//                   Section 5.1: a new frame that stores the label i), and write the argument
+//                   into that frame;
 //           Return_i <i:t,d> -> <t,d>: the frame's own key names its label i and the frame of
 //                   t, which is the label check of Section 5.1 (only the Return_i of the call
 //                   that created the frame produces output); the value goes to the caller's
@@ -68,7 +69,7 @@ template <int SCOPE> __device__ __forceinline__ unsigned long long a_cas(unsigne
 // Per-workgroup staging of one pass.
 struct Stage {
   uint32_t n_touched, n_leaf, n_cell, n_head, n_tags, n_tokens;
-  uint32_t max_probe, max_depth, max_level;
+  uint32_t max_depth, max_level;
   uint32_t base_touched, base_leaf, base_cell;
 };
 
@@ -112,6 +113,7 @@ struct LaneCtx {
   uint32_t present;
   int n_pend;
   long long sv[8];         // the first eight stored values, loaded before the sweep
+  uint32_t links[MAX_SITES];   // the frame's child links (frame id + 1, 0 = scope not opened), loaded before the sweep
   uint32_t mx_level;       // largest cell level this lane produced in the pass
   long long tc_v;          // forest entries of the last node looked at
   int tc_left, tc_right, tc_token;
@@ -431,9 +433,9 @@ struct InterpSweep {
 
 // A token emitted by a sweep, while it is being delivered.
 struct Emission {
-  bool has, is_call;   // is_call: the token opens or finds a frame by key (Call_i, Enter, Next)
-  uint32_t target, slot, bits, callee, depth;
-  unsigned long long ckey, res;
+  bool has, is_call;   // is_call: the token opens or finds a scope (Call_i, Enter, Next)
+  uint32_t target, slot, bits, callee, depth, site, res;
+  unsigned long long ckey;
   long long val;
 };
 
@@ -463,6 +465,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
   uint32_t* stg_touched = pend_meta + (size_t)z.max_emit * RB;         // [max_emit * RB]
   Stage* S = reinterpret_cast<Stage*>(stg_touched + (size_t)z.max_emit * RB);
   const int stride = (int)uni((uint32_t)P.frame_stride);
+  const int links_off = (int)uni((uint32_t)P.links_off), n_links = (int)uni((uint32_t)P.n_links);
   const uint32_t* cur_list = e.touched + (size_t)(step & 1) * e.touched_cap;
   uint32_t* next_list = e.touched + (size_t)((step & 1) ^ 1) * e.touched_cap;
   uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
@@ -497,7 +500,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     FrameHdr* h = frame_at(e, stride, x.frame);
     x.slots = frame_slots(h);
     x.fired = 0; x.present = 0; x.myfn = -1; x.n_pend = 0; x.tc_v = -1; x.mx_level = 0;
-    uint32_t mx_probe = 0, mx_depth = 0;
+    uint32_t mx_depth = 0;
     x.tc_left = x.tc_right = x.tc_token = 0;
     unsigned long long key = 0;
     uint32_t depth = 0, pf_in = 0;
@@ -513,6 +516,9 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       x.myfn = (int)(pf >> 24);
     }
     unsigned long long fired_in = x.fired;
+#pragma unroll
+    for (int k = 0; k < MAX_SITES; ++k)
+      x.links[k] = (x.active && k < n_links) ? ld_shared<kCoherent>(&frame_links(h, links_off)[k]) : 0u;
     // stored values (meaningful where the present bit is set), all loads in flight at once
 #pragma unroll
     for (int k = 0; k < 8; ++k) x.sv[k] = (x.active && k < n_st) ? ld_shared<kCoherent>(&x.slots[k]) : 0;
@@ -549,10 +555,12 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     // ---- match: deliver the emitted tokens, two at a time so that their atomics overlap ------
     for (int e0 = 0; __ballot(x.active && e0 < x.n_pend) != 0; e0 += 2) {
       Emission em[2];
+      bool fresh[2];   // the token opens its scope: a new frame record is taken
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         Emission& m = em[q];
         m = Emission{};
+        fresh[q] = false;
         m.has = x.active && e0 + q < x.n_pend;
         if (m.has) {
           const uint32_t meta = pend_meta[(e0 + q) * RB + tid];
@@ -564,6 +572,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               m.callee = (uint32_t)x.myfn;
               m.ckey = key + 0x100ull;
               m.depth = depth;
+              m.site = P.fn[x.myfn].next_site;
               if (((key >> 8) & 0xFFFFFFull) == 0xFFFFFFull) {   // the counter has 24 bits
                 raise(c, TDF_ERR_STEP_LIMIT);
                 m.has = false;
@@ -572,10 +581,16 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
               m.callee = P.label_callee[label];
               m.ckey = ((unsigned long long)(x.frame + 1u) << 32) | (label + 1u);
               m.depth = depth + 1u;
+              m.site = P.label_site[label];
             }
-            m.target = e.key_base + ((uint32_t)mix64(m.ckey) & e.part_mask);
             m.slot = param;
             m.bits = (1u << param) | (m.callee << 24);
+            // the match: the entry for (frame of t, i) is this frame's link of the site
+            uint32_t link = 0;
+#pragma unroll
+            for (int k = 0; k < MAX_SITES; ++k) link = (uint32_t)k == m.site ? x.links[k] : link;
+            m.target = link - 1u;
+            fresh[q] = m.has && link == 0u;
           } else {
             m.target = (uint32_t)(key >> 32) - 1u;
             m.slot = P.label_ret_slot[(((uint32_t)key & 0xFFu) - 1u) & (MAX_LABELS - 1)];
@@ -589,130 +604,74 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       }
       // two parameters of one call: the second token follows the first into its frame
       const bool same_call = em[0].has && em[1].has && em[0].is_call && em[1].is_call && em[0].ckey == em[1].ckey;
+      if (same_call) fresh[1] = false;
+      // new scopes take the machine's next free records: one counter bump per wave
+      {
+        uint32_t pos[2];
+        wave_alloc2<kDirect ? __HIP_MEMORY_SCOPE_WORKGROUP : SCOPE>(fresh[0], fresh[1], &c->n_alloc, pos[0], pos[1]);
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {   // both atomics in flight
-        Emission& m = em[q];
-        if (m.has) {
-          if (m.is_call) {
-            if (!(q == 1 && same_call)) m.res = a_cas<SCOPE>(&e.keys[m.target], 0ull, m.ckey);
-          } else {
-            FrameHdr* th = frame_at(e, stride, m.target);
-            frame_slots(th)[m.slot] = m.val;                    // read in a later step only
-            m.res = a_or<SCOPE>(&th->arrived[word], m.bits);
+        for (int q = 0; q < 2; ++q)
+          if (fresh[q]) {
+            if (pos[q] < e.part) {
+              em[q].target = e.key_base + pos[q];
+#pragma unroll
+              for (int k = 0; k < MAX_SITES; ++k)
+                if ((uint32_t)k == em[q].site) x.links[k] = em[q].target + 1u;
+              frame_links(h, links_off)[em[q].site] = em[q].target + 1u;   // read again by later sweeps of this frame
+            } else {
+              raise(c, TDF_ERR_TABLE_FULL);
+              em[q].has = false;
+              fresh[q] = false;
+            }
           }
+        if (same_call) {
+          em[1].has = em[0].has;       // em[0] failed only if the machine's part is full
+          em[1].target = em[0].target;
         }
       }
-      // collisions at the home slot: linear probing, eight key slots per round trip.  First one
-      // round for both tokens at once (load the next eight keys, claim the first empty one) ...
-      bool need[2], found[2], ins[2];
-      uint32_t probes[2];
-      unsigned long long w[2][8], claim[2];
-      int cj[2];
 #pragma unroll
-      for (int q = 0; q < 2; ++q) {
-        const Emission& m = em[q];
-        const bool own = m.has && m.is_call && !(q == 1 && same_call);
-        ins[q] = own && m.res == 0;
-        found[q] = own && (m.res == 0 || m.res == m.ckey);
-        need[q] = own && !found[q];
-        probes[q] = 1;
-        cj[q] = 8;
-        claim[q] = 1;
-      }
-      if (__ballot(need[0] || need[1]) != 0) {
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-          if (need[q]) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) w[q][j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[slot_after(e, em[q].target, 1u + j)]);
-          }
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-          if (need[q]) {
-#pragma unroll
-            for (int j = 7; j >= 0; --j)
-              if (w[q][j] == 0 || w[q][j] == em[q].ckey) {   // ends at the first such slot
-                cj[q] = j;
-                claim[q] = w[q][j];
-              }
-            if (cj[q] < 8 && claim[q] == 0)
-              claim[q] = a_cas<SCOPE>(&e.keys[slot_after(e, em[q].target, 1u + cj[q])], 0ull, em[q].ckey);
-          }
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-          if (need[q] && cj[q] < 8 && (claim[q] == 0 || claim[q] == em[q].ckey)) {
-            ins[q] = claim[q] == 0;
-            found[q] = true;
-            need[q] = false;
-            em[q].target = slot_after(e, em[q].target, 1u + cj[q]);
-            probes[q] = 2 + cj[q];
-          }
+      for (int q = 0; q < 2; ++q) {   // values and arrival bits, both tokens' atomics in flight
+        Emission& m = em[q];
+        if (m.has) {
+          FrameHdr* th = frame_at(e, stride, m.target);
+          frame_slots(th)[m.slot] = m.val;                    // read in a later step only
+          if (!m.is_call) m.res = a_or<SCOPE>(&th->arrived[word], m.bits);
+        }
       }
 #pragma unroll
       for (int q = 0; q < 2; ++q) {
         Emission& m = em[q];
         bool first_tok = false;
         if (m.has && m.is_call) {
-          if (q == 1 && same_call) {
-            found[1] = em[0].has;       // em[0] failed only if the table is full
-            m.target = em[0].target;
+          FrameHdr* th = frame_at(e, stride, m.target);
+          const bool inserted = fresh[q];
+          if (inserted) {
+            uint32_t* tl = frame_links(th, links_off);
+            for (int k = 0; k < n_links; ++k) tl[k] = 0u;     // no scope opened from the new frame yet
           }
-          // ... then, rarely (a lost race, or eight occupied slots in a row), one token at a time
-          const uint32_t probe_limit = e.part_mask < 8192u ? e.part_mask + 1u : 8192u;
-          while (need[q] && probes[q] < probe_limit) {
-            unsigned long long v[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = a_ld<__HIP_MEMORY_SCOPE_AGENT>(&e.keys[slot_after(e, m.target, 1u + j)]);
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              if (!need[q]) break;
-              if (v[j] == 0) {   // looked empty: claim it, or learn who did
-                v[j] = a_cas<SCOPE>(&e.keys[slot_after(e, m.target, 1u + j)], 0ull, m.ckey);
-                ins[q] = v[j] == 0;
-              }
-              if (ins[q] || v[j] == m.ckey) {
-                found[q] = true;
-                need[q] = false;
-                m.target = slot_after(e, m.target, 1u + j);
-                probes[q] += j + 1;
-              }
-            }
-            if (need[q]) {
-              m.target = slot_after(e, m.target, 8u);
-              probes[q] += 8;
-            }
-          }
-          const bool inserted = ins[q];
-          if (found[q]) {
-            FrameHdr* th = frame_at(e, stride, m.target);
-            frame_slots(th)[m.slot] = m.val;
-            if (inserted && may_follow && !has_next && follow + 1 < FOLLOW_DEPTH && P.fn[m.callee].n_params == 1) {
-              // the frame this lane goes on with: complete header, nothing pending, not listed
-              th->key = m.ckey;
-              th->fired = 0;
-              th->present_fn = m.bits;
-              th->depth = m.depth;
-              th->arrived[0] = 0;
-              th->arrived[1] = 0;
-              has_next = true;
-              nx_frame = m.target; nx_bits = m.bits; nx_slot = m.slot; nx_key = m.ckey; nx_val = m.val; nx_depth = m.depth;
-            } else if (inserted) {
-              // a fresh frame: nobody else can reach it in this step, so its creator writes the header
-              th->key = m.ckey;
-              th->fired = 0;
-              th->present_fn = 0;
-              th->depth = m.depth;
-              th->arrived[word ^ 1] = 0;
-              // an atomic, not a store: further parameters of the same call follow with atomics on
-              // this word in this very step, and only atomics on one address keep their order
-              (void)a_exch<SCOPE>(&th->arrived[word], m.bits);
-              first_tok = true;
-            } else {
-              first_tok = a_or<SCOPE>(&th->arrived[word], m.bits) == 0;
-            }
+          if (inserted && may_follow && !has_next && follow + 1 < FOLLOW_DEPTH && P.fn[m.callee].n_params == 1) {
+            // the frame this lane goes on with: complete header, nothing pending, not listed
+            th->key = m.ckey;
+            th->fired = 0;
+            th->present_fn = m.bits;
+            th->depth = m.depth;
+            th->arrived[0] = 0;
+            th->arrived[1] = 0;
+            has_next = true;
+            nx_frame = m.target; nx_bits = m.bits; nx_slot = m.slot; nx_key = m.ckey; nx_val = m.val; nx_depth = m.depth;
+          } else if (inserted) {
+            // a fresh frame: nobody else can reach it in this step, so its creator writes the header
+            th->key = m.ckey;
+            th->fired = 0;
+            th->present_fn = 0;
+            th->depth = m.depth;
+            th->arrived[word ^ 1] = 0;
+            // an atomic, not a store: further parameters of the same call follow with atomics on
+            // this word in this very step, and only atomics on one address keep their order
+            (void)a_exch<SCOPE>(&th->arrived[word], m.bits);
+            first_tok = true;
           } else {
-            raise(c, TDF_ERR_TABLE_FULL);
-            m.has = false;
+            first_tok = a_or<SCOPE>(&th->arrived[word], m.bits) == 0;
           }
         } else if (m.has) {
           first_tok = m.res == 0;   // the arrival word was empty: first token for that frame in this step
@@ -723,12 +682,9 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
           else if (pos < e.touched_cap) next_list[pos] = m.target;
           else raise(c, TDF_ERR_TABLE_FULL);
         }
-        cnt_tags += (uint32_t)__popcll(__ballot(ins[q]));
+        cnt_tags += (uint32_t)__popcll(__ballot(fresh[q]));
         cnt_tokens += (uint32_t)__popcll(__ballot(m.has));
-        if (ins[q]) {
-          mx_probe = probes[q] > mx_probe ? probes[q] : mx_probe;
-          mx_depth = em[q].depth > mx_depth ? em[q].depth : mx_depth;
-        }
+        if (fresh[q]) mx_depth = em[q].depth > mx_depth ? em[q].depth : mx_depth;
       }
     }
     if (x.active) {
@@ -752,6 +708,8 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     x.n_pend = 0;
     x.tc_v = -1;
 #pragma unroll
+    for (int k = 0; k < MAX_SITES; ++k) x.links[k] = 0u;
+#pragma unroll
     for (int k = 0; k < 8; ++k) x.sv[k] = (has_next && (uint32_t)k == nx_slot) ? nx_val : 0;
     if (SW::kLdsValues) {
 #pragma unroll
@@ -761,10 +719,9 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     }
     }   // follow
     {   // per-wave maxima of the pass
-      const uint32_t wl = wave_umax(x.mx_level), wp = wave_umax(mx_probe), wd = wave_umax(mx_depth);
+      const uint32_t wl = wave_umax(x.mx_level), wd = wave_umax(mx_depth);
       if ((tid & 63) == 0) {
         if (wl) atomicMax(kDirect ? &c->max_level : &S->max_level, wl);
-        if (wp) atomicMax(kDirect ? &c->max_probe : &S->max_probe, wp);
         if (wd) atomicMax(kDirect ? &c->max_depth : &S->max_depth, wd);
         if (!kDirect) {
           if (cnt_tags) atomicAdd(&S->n_tags, cnt_tags);
@@ -783,7 +740,6 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       if (S->n_head) atomicAdd(&c->n_head, S->n_head);
       if (S->n_tags) atomicAdd(&c->n_tags, (unsigned long long)S->n_tags);
       if (S->n_tokens) atomicAdd(&c->n_tokens, (unsigned long long)S->n_tokens);
-      if (S->max_probe > c->max_probe) atomicMax(&c->max_probe, S->max_probe);
       if (S->max_depth > c->max_depth) atomicMax(&c->max_depth, S->max_depth);
       if (S->max_level > c->max_level) atomicMax(&c->max_level, S->max_level);
       if (S->base_touched + S->n_touched > e.touched_cap || S->base_leaf + S->n_leaf > e.log_cap ||
@@ -977,7 +933,7 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     lc.n_head = ld(&g->n_head);
     lc.status = ld(&g->status);
     lc.done = g->done;
-    lc.max_probe = ld(&g->max_probe);
+    lc.n_alloc = ld(&g->n_alloc);
     lc.max_depth = ld(&g->max_depth);
     lc.max_level = ld(&g->max_level);
     lc.bar_count = lc.bar_gen = 0;
@@ -1006,7 +962,7 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     st(&g->n_head, lc.n_head);
     st(&g->status, lc.status);
     g->done = lc.done;
-    st(&g->max_probe, lc.max_probe);
+    st(&g->n_alloc, lc.n_alloc);
     st(&g->max_depth, lc.max_depth);
     st(&g->max_level, lc.max_level);
     st(&g->n_tags, lc.n_tags);

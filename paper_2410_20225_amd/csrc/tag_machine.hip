@@ -25,6 +25,7 @@ __global__ void k_seed(DevProgram P, Engine e) {
   h->fired = 0;
   h->present_fn = ((1u << np) - 1u) | ((uint32_t)P.result_fn << 24);
   h->arrived[0] = h->arrived[1] = 0;
+  for (int k = 0; k < P.n_links; ++k) frame_links(h, P.links_off)[k] = 0u;
   // instance b belongs to machine b % n_dies
   const uint32_t d = b % e.n_dies, pos = b / e.n_dies;
   e.touched[(size_t)d * 2 * e.touched_cap + pos] = f;
@@ -74,7 +75,7 @@ __global__ void k_count_fired(DevProgram P, Engine e) {
   __syncthreads();
   const uint32_t total = e.cap + e.n_inst;
   for (uint32_t f = blockIdx.x * blockDim.x + threadIdx.x; f < total; f += gridDim.x * blockDim.x) {
-    if (f < e.cap && e.keys[f] == 0) continue;   // empty slot: the frame holds stale bytes
+    if (f < e.cap && f % e.part >= e.ctrl[f / e.part].n_alloc) continue;   // not handed out: the record holds stale bytes
     const FrameHdr* h = frame_at(e, P.frame_stride, f);
     unsigned long long fired = h->fired;
     if (fired == 0) continue;

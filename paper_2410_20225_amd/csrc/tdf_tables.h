@@ -48,6 +48,7 @@ constexpr int MAX_INSTR = 176;
 constexpr int MAX_LABELS = 32;
 constexpr int MAX_VALUES = 64;   // per function
 constexpr int MAX_STORED = 24;   // per function
+constexpr int MAX_SITES = 8;     // per function: call sites, loop sites, next iteration
 
 enum ValueType : uint8_t { T_INT = 0, T_VEC = 1, T_LOSS = 2 };
 
@@ -55,16 +56,20 @@ struct DevFn {
   uint16_t first, count;   // instruction range
   uint8_t n_values, n_stored, out_type, n_params;
   uint8_t n_emit;          // entries that emit a token (Call_i per parameter, function output)
-  uint8_t n_call_labels;   // distinct call labels in the body (capped at 6), for prefetching
-  uint8_t call_labels[6];
+  uint8_t n_sites;         // scopes a frame of this function can open: its call and loop sites, plus
+                           // the next iteration if it is a loop graph (at most MAX_SITES)
+  uint8_t next_site;       // loop graphs: the site of the next iteration (= number of call sites)
+  uint8_t pad[5];
 };
 
 // Lives in the workspace; every workgroup of a step kernel copies it into LDS.
 struct DevProgram {
   int32_t n_fn, result_fn, n_labels, frame_stride;   // frame_stride in bytes
+  int32_t links_off, n_links;           // frame record: byte offset and number of the child links (program-wide)
   DevFn fn[MAX_FN];
   uint8_t label_callee[MAX_LABELS];     // function entered by Call_i
   uint8_t label_ret_slot[MAX_LABELS];   // stored slot of Return_i's value in the caller's frame
+  uint8_t label_site[MAX_LABELS];       // which of the caller's child links belongs to the scope opened by Call_i
   uint16_t stat_idx[MAX_INSTR];         // static-graph node counted when the instruction fires live
   Instr instr[MAX_INSTR];
 };
