@@ -92,7 +92,8 @@ struct GemmArgs {
   // gathered A rows for the forward cells: row m = [Hs[l[m]]; Hs[r[m]]]
   const void* Hs;
   int Hp;
-  const uint32_t *out, *l, *r;   // already offset to the level's first cell
+  uint32_t out0;             // state row of the level's first cell: cell m of the level writes row out0 + m
+  const uint32_t *l, *r;     // children's rows, already offset to the level's first cell
   const float* bias;
   void* Hs_out;              // state rows written by the forward cells
   float* Cs;                 // LSTM cell state rows
@@ -252,7 +253,7 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
   uint32_t* sR = sL + BM;
   if (MODE != DW_SPLIT && tid < BM) {
     const int m = min(m0 + tid, g.M - 1);
-    if (MODE != DX_BWD) sOut[tid] = g.out[m];
+    if (MODE != DX_BWD) sOut[tid] = g.out0 + (uint32_t)m;
     sL[tid] = g.l[m];
     sR[tid] = g.r[m];
   }
@@ -454,8 +455,8 @@ __device__ __forceinline__ void load_resident_b(const GemmArgs& g, int ct, Resid
 // the wide levels get their dz from k_dz as before.
 struct DzFuse {
   const VecArgs* v;
-  const uint32_t *cq_l, *cq_r;   // position of the children's cells in the sorted log (~0: a leaf), from the level's first cell
   const uint32_t *q_l, *q_r;     // children rows of every cell of the sorted log
+  uint32_t row0;                 // first cell row: a child row below it is a leaf, else it is cell (row - row0)
   uint32_t q_first;              // first cell of the tail in the sorted log
 };
 
@@ -482,7 +483,7 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
 #pragma unroll
   for (int rr = 0; rr < RPW; ++rr) {
     const int m = min(m0 + row_of(rr), g.M - 1);
-    if (MODE != DX_BWD) o_out[rr] = g.out[m];
+    if (MODE != DX_BWD) o_out[rr] = g.out0 + (uint32_t)m;
     if (MODE != RNN_FWD) { o_l[rr] = g.l[m]; o_r[rr] = g.r[m]; }
   }
   // operand bases (elements)
@@ -518,8 +519,8 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
       const int m = min(m0 + row_of(rr), g.M - 1);
-      z_q[rr] = (z_left ? fz->cq_l : fz->cq_r)[m];
       z_row[rr] = z_left ? o_l[rr] : o_r[rr];
+      z_q[rr] = z_row[rr] >= fz->row0 ? z_row[rr] - fz->row0 : 0xFFFFFFFFu;   // a leaf has no cell
     }
   }
 
@@ -744,7 +745,7 @@ __global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
   const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   const int n_waves = (gridDim.x * blockDim.x) >> 6;
   for (uint32_t i = wave; i < n_leaf; i += n_waves) {
-    const uint32_t row = e.leaf_row[i], tok = e.leaf_tok[i];
+    const uint32_t row = i, tok = e.leaf_tok[i];   // (token ids were checked when the leaf fired)
     const T* src = reinterpret_cast<const T*>(v.E) + (size_t)(tok < (uint32_t)v.vocab ? tok : 0) * v.H;
     T* dst = reinterpret_cast<T*>(v.Hs) + (size_t)row * v.Hp;
     for (int n = lane; n < v.Hp; n += 64) dst[n] = n < v.H ? src[n] : from_f<T>(0.f);
@@ -813,8 +814,8 @@ __global__ void __launch_bounds__(256) k_node_ce(VecArgs v, Engine e, uint32_t n
   const int sub = threadIdx.x & 15;
   const uint32_t grp = (blockIdx.x * blockDim.x + threadIdx.x) >> 4, n_grp = (gridDim.x * blockDim.x) >> 4;
   for (uint32_t i = grp; i < n_leaf + n_cell; i += n_grp) {
-    const uint32_t row = i < n_leaf ? e.leaf_row[i] : e.q_out[i - n_leaf];
-    const uint32_t node = e.row_node[row];
+    const uint32_t row = i;
+    const uint32_t node = e.node_of_row[row];
     int label = -1;
     if (node != 0xFFFFFFFFu) label = node_label[node];
     if (label >= v.n_classes) label = -1;
@@ -914,9 +915,9 @@ __global__ void k_out_rows(VecArgs v, Engine e, float* out_h, float* out_c) {
 template <int DT>
 __device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32_t q) {
   typedef typename TypeOf<DT>::type T;
-  const size_t o = (size_t)e.q_out[q] * v.Hp;
+  const size_t o = (size_t)(e.row0 + q) * v.Hp;
   T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)q * v.Np;
-  if (threadIdx.x == 0) atomicAdd(&v.gmark[e.q_out[q]], 1u);   // the gradient body of this tag fires
+  if (threadIdx.x == 0) atomicAdd(&v.gmark[e.row0 + q], 1u);   // the gradient body of this tag fires
   if (v.cell_kind == 1) {
     for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
       const float h = to_f(reinterpret_cast<const T*>(v.Hs)[o + n]);
@@ -986,7 +987,7 @@ __global__ void __launch_bounds__(NW * 64) k_tail_fwd(GemmArgs g, TailArgs t) {
     const uint32_t cnt = t.level_off[lvl * LEVEL_KEY_DIES + die + 1] - q0;
     GemmArgs gl = g;
     gl.M = (int)cnt;
-    gl.out = g.out + q0; gl.l = g.l + q0; gl.r = g.r + q0;
+    gl.out0 = g.out0 + q0; gl.l = g.l + q0; gl.r = g.r + q0;
     gl.gates = g.gates ? reinterpret_cast<T*>(g.gates) + (size_t)q0 * g.ldg : nullptr;
     const uint32_t n_rt = (cnt + 31) / 32;
     if (resident) {
@@ -1023,7 +1024,7 @@ __global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Eng
     const uint32_t cnt = t.level_off[lvl * LEVEL_KEY_DIES + die + 1] - q0;
     // (dz of this level's cells: from their parents' tiles, or, for the roots, from k_dz_tail_roots)
     GemmArgs gl = g;
-    DzFuse fz{&v, e.cq_l + q0, e.cq_r + q0, e.q_l, e.q_r, t.q_first};
+    DzFuse fz{&v, e.q_l, e.q_r, e.row0, t.q_first};
     gl.M = (int)cnt;
     gl.A = reinterpret_cast<const T*>(g.A) + (size_t)q0 * g.lda;
     gl.l = g.l + q0; gl.r = g.r + q0;
@@ -1040,21 +1041,35 @@ __global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Eng
   }
 }
 
-// position of every cell's row in the sorted log, then of every cell's children
-__global__ void k_row_q(Engine e, uint32_t n_cell) {
-  for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < n_cell; q += gridDim.x * blockDim.x) e.row_q[e.q_out[q]] = q;
+// ---- numbering of the state rows by the sorted schedule ------------------------------------------
+// Leaf i of the leaf log gets row i, the cell at position q of the level-sorted log row n_leaf + q;
+// then every reference to a producing frame (children of the cells, roots, head rows, loss-term
+// marks) is translated to rows once.
+__global__ void k_number_rows(Engine e, uint32_t n_leaf, uint32_t n_cell) {
+  for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_leaf + n_cell; i += gridDim.x * blockDim.x) {
+    const uint32_t f = i < n_leaf ? e.leaf_row[i] : e.q_out[i - n_leaf];
+    e.row_of[f] = i;
+    if (e.node_of_row) e.node_of_row[i] = e.row_node[f];
+  }
 }
-__global__ void k_child_q(Engine e, uint32_t n_cell) {
-  for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < n_cell; q += gridDim.x * blockDim.x) {
-    e.cq_l[q] = e.row_q[e.q_l[q]];
-    e.cq_r[q] = e.row_q[e.q_r[q]];
+__global__ void k_translate_rows(Engine e, uint32_t n_cell, int has_head, int has_root) {
+  const uint32_t n = n_cell > e.n_inst ? n_cell : e.n_inst;
+  for (uint32_t q = blockIdx.x * blockDim.x + threadIdx.x; q < n; q += gridDim.x * blockDim.x) {
+    if (q < n_cell) {
+      e.q_l[q] = e.row_of[e.q_l[q]];
+      e.q_r[q] = e.row_of[e.q_r[q]];
+    }
+    if (q < e.n_inst) {
+      if (has_head) e.head_row[q] = e.row_of[e.head_row[q]];
+      if (has_root) e.root_ref[q] = e.row_of[e.root_ref[q]];
+    }
   }
 }
 // dz of the cells of the tail that have no parent: the roots, whose dh came from the head (or the caller)
 template <int DT>
 __global__ void k_dz_tail_roots(VecArgs v, Engine e, const uint32_t* root_rows, uint32_t q_first) {
-  const uint32_t q = e.row_q[root_rows[blockIdx.x]];
-  if (q != 0xFFFFFFFFu && q >= q_first) dz_row<DT>(v, e, q);
+  const uint32_t row = root_rows[blockIdx.x];
+  if (row >= e.row0 && row - e.row0 >= q_first) dz_row<DT>(v, e, row - e.row0);
 }
 
 // Gradient-body firings counted on the device: the marks of all leaf and cell rows, summed, and the
@@ -1062,7 +1077,7 @@ __global__ void k_dz_tail_roots(VecArgs v, Engine e, const uint32_t* root_rows, 
 __global__ void k_count_grad(VecArgs v, Engine e, uint32_t n_leaf, uint32_t n_cell, unsigned long long* out) {
   unsigned long long sum = 0, odd = 0;
   for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_leaf + n_cell; i += gridDim.x * blockDim.x) {
-    const uint32_t m = v.gmark[i < n_leaf ? e.leaf_row[i] : e.q_out[i - n_leaf]];
+    const uint32_t m = v.gmark[i];
     sum += m;
     odd += m != 1u;
   }
@@ -1373,13 +1388,12 @@ __global__ void k_tok_scatter(Engine e, uint32_t n_leaf, const uint32_t* seg_off
     const uint32_t t = i < n_leaf ? e.leaf_tok[i] : 0xFFFFFFFFu;
     const bool on = t < (uint32_t)vocab;
     const uint32_t rank = wave_alloc_keyed(on, t, fill);
-    if (on) sorted_row[seg_off[t] + rank] = e.leaf_row[i];
+    if (on) sorted_row[seg_off[t] + rank] = i;   // leaf i has row i
   }
 }
-struct TokenSink {   // leaf rows grouped by token
-  const uint32_t* leaf_row;
+struct TokenSink {   // leaf rows grouped by token (leaf i has row i)
   uint32_t* sorted_row;
-  __device__ void operator()(uint32_t i, uint32_t pos) const { sorted_row[pos] = leaf_row[i]; }
+  __device__ void operator()(uint32_t i, uint32_t pos) const { sorted_row[pos] = i; }
 };
 // one wave per chunk of at most `chunk` leaves of one token: partial[chunk] = sum of their dH rows
 __global__ void k_de_partial(VecArgs v, const uint32_t* seg_off, const uint32_t* chunk_off,
@@ -1474,7 +1488,7 @@ template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, 
   g.M = (int)count; g.N = v.Np; g.K = v.Kp;
   g.B = v.Wp; g.ldb = v.Kp; g.Bf = v.Wf;
   g.Hs = v.Hs; g.Hp = v.Hp;
-  g.out = e.q_out + q0; g.l = e.q_l + q0; g.r = e.q_r + q0;
+  g.out0 = e.row0 + q0; g.l = e.q_l + q0; g.r = e.q_r + q0;
   g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
   g.gates = v.gates ? reinterpret_cast<T*>(v.gates) + (size_t)q0 * v.Np : nullptr;
   g.ldg = v.Np; g.save_gates = save_gates && v.gates;
@@ -1518,7 +1532,7 @@ template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, 
   g.N = v.Np; g.K = v.Kp;
   g.B = v.Wp; g.ldb = v.Kp; g.Bf = v.Wf;
   g.Hs = v.Hs; g.Hp = v.Hp;
-  g.out = e.q_out; g.l = e.q_l; g.r = e.q_r;
+  g.out0 = e.row0; g.l = e.q_l; g.r = e.q_r;
   g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
   g.gates = v.gates; g.ldg = v.Np; g.save_gates = save_gates && v.gates;
   g.n_tiles_n = v.Hp / 32;
@@ -1559,12 +1573,12 @@ template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, 
     hipLaunchKernelGGL((k_tail_bwd<DtOf<T>::value, 4>), dim3(grid), dim3(256), lds, s, g, v, e, t);
   }
 }
-// After the level sort of a gradient run: where each cell's children are in the sorted log.
-void vec_child_index(const Engine& e, uint32_t n_cell, hipStream_t s) {
-  (void)hipMemsetAsync(e.row_q, 0xFF, sizeof(uint32_t) * ((size_t)e.cap + e.n_inst), s);
-  const int g = (int)std::min<uint32_t>((n_cell + 255) / 256, 2048u);
-  hipLaunchKernelGGL(k_row_q, dim3(std::max(g, 1)), dim3(256), 0, s, e, n_cell);
-  hipLaunchKernelGGL(k_child_q, dim3(std::max(g, 1)), dim3(256), 0, s, e, n_cell);
+// After the level sort: rows numbered by the sorted schedule, references translated.
+void vec_number_rows(const Engine& e, uint32_t n_leaf, uint32_t n_cell, int has_head, int has_root, hipStream_t s) {
+  const int g1 = (int)std::min<uint32_t>((n_leaf + n_cell + 255) / 256, 2048u);
+  hipLaunchKernelGGL(k_number_rows, dim3(std::max(g1, 1)), dim3(256), 0, s, e, n_leaf, n_cell);
+  const int g2 = (int)std::min<uint32_t>((std::max(n_cell, e.n_inst) + 255) / 256, 2048u);
+  hipLaunchKernelGGL(k_translate_rows, dim3(std::max(g2, 1)), dim3(256), 0, s, e, n_cell, has_head, has_root);
 }
 
 void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
@@ -1681,7 +1695,7 @@ void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t
     hipLaunchKernelGGL(k_bucket_count, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.leaf_tok, n_leaf, n_keys, count);
     hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);
     hipLaunchKernelGGL(k_bucket_place<TokenSink>, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.leaf_tok, n_leaf, n_keys,
-                       seg_off, fill, TokenSink{e.leaf_row, sorted_row});
+                       seg_off, fill, TokenSink{sorted_row});
   } else {
     hipLaunchKernelGGL(k_tok_hist, dim3(g), dim3(256), 0, s, e, n_leaf, count, v.vocab);
     hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);

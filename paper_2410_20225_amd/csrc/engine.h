@@ -104,8 +104,8 @@ struct Engine {
   int32_t n_args;
   long long* out_i64;
   uint32_t* root_ref;               // [B] row of the vector result of instance b
-  // schedule log written by the step kernels; a vector value lives in the state row of the
-  // frame that produced it (row id = frame id)
+  // schedule log written by the step kernels; a vector value is named by the frame that produced it
+  // until the rows are numbered
   uint32_t log_cap;                 // entries of the leaf / cell logs (0: no vector operators)
   uint32_t *leaf_row, *leaf_tok;    // [n_leaf]
   uint32_t *cell_out, *cell_l, *cell_r, *cell_lvl;   // [n_cell], in firing order; cell_lvl holds the sort key
@@ -115,10 +115,15 @@ struct Engine {
   // the sorted log, and inside it the cells of every machine (die) are contiguous too.
   uint32_t *level_count, *level_off, *level_fill;    // [(max_levels + 2) * LEVEL_KEY_DIES]
   uint32_t max_levels;
-  uint32_t *q_out, *q_l, *q_r;      // [n_cell], sorted by level
-  uint32_t* row_q;                  // [cap + n_inst]: position of a row's cell in the sorted log, ~0 for leaves (gradient runs)
-  uint32_t *cq_l, *cq_r;            // [n_cell]: row_q of the two children
-  uint32_t* row_node;               // [cap + n_inst]: tree node whose loss term the row gets (CE_NODE), ~0: none
+  uint32_t *q_out, *q_l, *q_r;      // [n_cell], sorted by level: producing frame, then (after the rows are numbered) the children's rows
+  // State rows are numbered by the sorted schedule, not by frame: leaf i of the leaf log has row i,
+  // the cell at position q of the sorted log has row row0 + q (row0 = number of leaves).  Every
+  // level then reads scattered child rows but writes one contiguous block, and the state arrays
+  // hold only rows that exist.
+  uint32_t row0;                    // first cell row (set by the host once the tag machine has finished)
+  uint32_t* row_of;                 // [cap + n_inst]: row of the value a frame produced (valid for logged frames)
+  uint32_t* row_node;               // [cap + n_inst]: tree node whose loss term the frame's row gets (CE_NODE), ~0: none
+  uint32_t* node_of_row;            // [rows]: the same by row
 };
 
 // The engine as machine d sees it.
@@ -240,13 +245,13 @@ struct VecArgs {
   const void* W;
   const float* b;
   const float *U, *u0;
-  void* Hs;         // state rows [(cap + B) x Hp], dtype, indexed by frame id
-  float* Cs;        // LSTM cell state [(cap + B) x Hp]
+  void* Hs;         // state rows [rows x Hp], dtype (rows: capacity max_tags)
+  float* Cs;        // LSTM cell state [rows x Hp]
   void* Wp;         // packed W [Np x Kp], dtype (k contiguous)
   float* bp;        // [Np]
   // gradient side
-  float* dH;        // [(cap + B) x Hp]
-  float* dC;        // [(cap + B) x Hp]
+  float* dH;        // [rows x Hp]
+  float* dC;        // [rows x Hp]
   void* gates;      // LSTM activations (i,f_l,f_r,o,u) [n_cell x Np], dtype, by level order q
   void* Dz;         // pre-activation gradients [n_cell x Np], dtype, by q
   void* DzT;        // [Np x q_stride]
@@ -257,8 +262,8 @@ struct VecArgs {
   float* dW_part;   // split partial sums [n_split x Np x Kp]
   uint32_t q_stride;
   float* loss;      // [B]
-  uint32_t* gmark;  // [(cap + B)] gradient runs: how often the gradient body of a row's tag has fired (cleared per call)
-  float* dHn;       // [(cap + B) x Hp] gradient of each row's own loss term (CE_NODE, gradient runs; else null):
+  uint32_t* gmark;  // [rows] gradient runs: how often the gradient body of a row's tag has fired (cleared per call)
+  float* dHn;       // [rows x Hp] gradient of each row's own loss term (CE_NODE, gradient runs; else null):
                     // whoever reads a row of dH adds the row of dHn
 };
 

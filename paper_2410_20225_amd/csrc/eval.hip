@@ -32,7 +32,7 @@ void vec_tail_fwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, 
 void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
                   uint32_t n_dies, void* sync, long long spin_ticks, int cus, uint32_t q_first, const uint32_t* root_rows,
                   hipStream_t s);
-void vec_child_index(const Engine& e, uint32_t n_cell, hipStream_t s);
+void vec_number_rows(const Engine& e, uint32_t n_leaf, uint32_t n_cell, int has_head, int has_root, hipStream_t s);
 void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s);
 void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label,
                    float* out_node_loss, const float* dnode, int with_grad, hipStream_t s);
@@ -137,7 +137,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_gmark = 0;
   if (P.vec && with_grad) {
     P.off_gcount = L.take(sizeof(unsigned long long) * 2);
-    off_gmark = L.take(sizeof(uint32_t) * ((size_t)e.cap + B));
+    off_gmark = L.take(sizeof(uint32_t) * ((size_t)T + 64));
   }
   L.zero_end = L.total;
   P.off_frames = L.take((size_t)G.prog.frame_stride * ((size_t)e.cap + B));   // headers are written on insertion
@@ -155,9 +155,9 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_leaf_row = L.take(4 * rc), off_leaf_tok = L.take(4 * rc);
   size_t off_c_out = L.take(4 * rc), off_c_l = L.take(4 * rc), off_c_r = L.take(4 * rc), off_c_lvl = L.take(4 * rc);
   size_t off_q_out = L.take(4 * rc), off_q_l = L.take(4 * rc), off_q_r = L.take(4 * rc);
-  size_t off_row_q = with_grad ? L.take(4 * ((size_t)e.cap + e.n_inst)) : 0;
-  size_t off_cq_l = with_grad ? L.take(4 * rc) : 0, off_cq_r = with_grad ? L.take(4 * rc) : 0;
+  size_t off_row_of = P.vec ? L.take(4 * ((size_t)e.cap + e.n_inst)) : 0;
   size_t off_row_node = G.has_node_loss ? L.take(4 * ((size_t)e.cap + e.n_inst)) : 0;
+  size_t off_node_of_row = G.has_node_loss ? L.take(4 * ((size_t)T + 64)) : 0;
   // logs of the single machines, merged into the arrays above after the last step
   size_t off_m[6] = {off_leaf_row, off_leaf_tok, off_c_out, off_c_l, off_c_r, off_c_lvl};
   if (e.n_dies > 1)
@@ -189,10 +189,10 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.q_out = (uint32_t*)at(off_q_out);
   e.q_l = (uint32_t*)at(off_q_l);
   e.q_r = (uint32_t*)at(off_q_r);
-  e.row_q = with_grad ? (uint32_t*)at(off_row_q) : nullptr;
-  e.cq_l = with_grad ? (uint32_t*)at(off_cq_l) : nullptr;
-  e.cq_r = with_grad ? (uint32_t*)at(off_cq_r) : nullptr;
+  e.row0 = 0;
+  e.row_of = P.vec ? (uint32_t*)at(off_row_of) : nullptr;
   e.row_node = G.has_node_loss ? (uint32_t*)at(off_row_node) : nullptr;
+  e.node_of_row = G.has_node_loss ? (uint32_t*)at(off_node_of_row) : nullptr;
   e.left = in->left;
   e.right = in->right;
   e.token = in->token;
@@ -217,7 +217,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.gmark = with_grad ? (uint32_t*)at(off_gmark) : nullptr;
     v.E = in->E; v.W = in->W; v.b = in->b; v.U = in->U; v.u0 = in->u0;
     const size_t el = in->dtype == TDF_BF16 ? 2 : 4;
-    const size_t R = (size_t)e.cap + B;   // one state row per frame
+    const size_t R = (size_t)T + 64;      // one state row per leaf and per cell firing (at most one per tag)
     if (R * (size_t)((in->hidden + 63) / 64 * 64) >= (1ull << 32)) { set_error("max_tags x hidden too large for 32-bit row offsets"); return TDF_ERR_BAD_ARG; }
     size_t off_Hs = L.take(R * v.Hp * el);
     size_t off_Cs = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
@@ -469,6 +469,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
+    e.row0 = hc.n_leaf;   // leaf i has row i, the cell at position q of the sorted log row n_leaf + q
     begin(TDF_PHASE_LEAVES);
     if (G.cell_kind) vec_pack_w(v, s);   // (a program of EMBEDs alone has no W: the pointers may be NULL)
     vec_embed(v, e, hc.n_leaf, s);
@@ -476,6 +477,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (hc.n_cell) {
       begin(TDF_PHASE_LEVELS);
       launch_levels(e, hc.n_cell, hc.max_level, s);
+      vec_number_rows(e, hc.n_leaf, hc.n_cell, G.has_head, G.out_type == T_VEC, s);
       const size_t level_bytes = ((size_t)hc.max_level + 2) * LEVEL_KEY_DIES * sizeof(uint32_t);
       if (no_alloc && gr->pinned_bytes < PIN_LEVELS + level_bytes) {
         set_error("more dependency levels than the prepared graph's host buffer holds");
@@ -485,7 +487,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         if (tdf_status ps = pinned_reserve(gr, level_bytes); ps != TDF_OK) return ps;
       level_off = (const uint32_t*)((char*)gr->pinned + PIN_LEVELS);
       HIP_TRY(hipMemcpyAsync((void*)level_off, e.level_off, level_bytes, hipMemcpyDeviceToHost, s));
-      end(TDF_PHASE_LEVELS, 3);
+      end(TDF_PHASE_LEVELS, 5);
       HIP_TRY(hipStreamSynchronize(s));
       // the deep levels, each small, go into one launch in which every die walks its own cells
       tail_first = hc.max_level + 1;
@@ -503,6 +505,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         end(TDF_PHASE_TAIL_FWD, 1);
       }
     }
+    if (!hc.n_cell) vec_number_rows(e, hc.n_leaf, 0, G.has_head, G.out_type == T_VEC, s);   // leaves only
     begin(TDF_PHASE_HEAD);
     if (G.has_head) {
       vec_head(v, e, with_grad ? dy->dy : nullptr, with_grad, s);
@@ -523,10 +526,9 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       // ---- gradient pass: the level schedule walked backwards -----------------------------
       if (use_tail && hc.n_cell) {
         begin(TDF_PHASE_TAIL_BWD);
-        vec_child_index(e, hc.n_cell, s);
         vec_tail_bwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync + 8 * sizeof(DieSync),
                      spin_ticks, cus, lvl_begin(tail_first), G.has_head ? e.head_row : e.root_ref, s);
-        end(TDF_PHASE_TAIL_BWD, 5);
+        end(TDF_PHASE_TAIL_BWD, 2);
       }
       begin(TDF_PHASE_CELLS_BWD);
       for (uint32_t lvl = tail_first - 1; lvl >= 1 && hc.n_cell; --lvl)
