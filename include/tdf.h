@@ -251,6 +251,7 @@ typedef struct {
   int64_t n_waves;        /* dependency levels of the cell firings                      */
   int64_t n_wide_waves;   /* ... of which the first this many ran one launch per level  */
   int64_t n_wide_cells;   /* cell firings in those levels                               */
+  int64_t deep_cells;     /* cell firings of the deep instances (see deep_split)        */
   int64_t n_grad_firings; /* gradient-body firings in tdf_eval_grad, counted on the device: every
                              gradient body marks its tag's row when it fires (one per tag) */
   int64_t n_grad_not_once; /* tags whose gradient body fired some other number of times than once */
@@ -269,8 +270,10 @@ typedef struct {
                              table interpreter                                          */
   int32_t repeats;        /* runs that were discarded and repeated inside this call (a part of
                              the tag table overflowed, or die-private kernels left their die) */
-  int32_t tail_used;      /* 1: the deep, narrow levels ran in one launch per pass      */
-  int32_t reserved0;
+  int32_t tail_used;      /* 1: narrow levels ran in one launch per pass                */
+  int32_t deep_split;     /* 1: the deep instances (root level >= 32) ran apart from the others,
+                             all their levels in one launch per pass; 2: ... on a second
+                             stream, beside the others                                   */
   /* live firings per static-graph node, indexed like tdf_graph_info_t.nodes            */
   int64_t fire_count[TDF_STATS_MAX_COUNTS];
 } tdf_stats;

@@ -756,10 +756,11 @@ __global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
 
 // ---- classification head: loss_b = -log softmax(U h + u0)[label]; dh = U^T (p - onehot) dloss ---
 template <int DT>
-__global__ void k_head(VecArgs v, Engine e, const float* dy, int with_grad) {
+__global__ void k_head(VecArgs v, Engine e, const float* dy, int with_grad, int cls) {
   typedef typename TypeOf<DT>::type T;
   const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   if (wave >= (int)e.n_inst) return;
+  if (cls >= 0 && (int)e.inst_class[wave] != cls) return;   // only the instances of one class
   const uint32_t row = e.head_row[wave];
   const int label = (int)e.head_label[wave];
   const T* h = reinterpret_cast<const T*>(v.Hs) + (size_t)row * v.Hp;
@@ -972,6 +973,9 @@ __global__ void __launch_bounds__(NW * 64) k_tail_fwd(GemmArgs g, TailArgs t) {
   float* part = reinterpret_cast<float*>(smem);
   const uint32_t die = blockIdx.x % XCDS, rank = blockIdx.x / XCDS, G = gridDim.x / XCDS;
   if (die >= t.n_dies) return;
+  // A level here is one link of a dependency chain: these waves are bound by latency, and other
+  // kernels (the wide levels of other instances) may share the compute unit: issue before them.
+  __builtin_amdgcn_s_setprio(3);
   DieSync* sy = t.sync + die;
   if (threadIdx.x == 0) atomicOr(&sy->xcc_mask, 1u << xcc_id());
   const int n_ct = g.n_tiles_n;
@@ -1011,6 +1015,9 @@ __global__ void __launch_bounds__(NW * 64) k_tail_bwd(GemmArgs g, VecArgs v, Eng
   float* part = reinterpret_cast<float*>(smem);
   const uint32_t die = blockIdx.x % XCDS, rank = blockIdx.x / XCDS, G = gridDim.x / XCDS;
   if (die >= t.n_dies) return;
+  // A level here is one link of a dependency chain: these waves are bound by latency, and other
+  // kernels (the wide levels of other instances) may share the compute unit: issue before them.
+  __builtin_amdgcn_s_setprio(3);
   DieSync* sy = t.sync + die;
   if (threadIdx.x == 0) atomicOr(&sy->xcc_mask, 1u << xcc_id());
   const int n_ct = g.n_tiles_n;
@@ -1526,7 +1533,7 @@ uint32_t vec_small_level() { return small_level(); }
 
 // The levels lvl_first .. lvl_last in one launch, every die walking its own cells (k_tail_fwd).
 // level_off: device array of first cells by sort key; sync: eight zeroed DieSync records.
-template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, const TailArgs& t, int cus, int save_gates,
+template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, const TailArgs& t, int per_die, int save_gates,
                                              hipStream_t s) {
   GemmArgs g{};
   g.N = v.Np; g.K = v.Kp;
@@ -1536,7 +1543,7 @@ template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, 
   g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
   g.gates = v.gates; g.ldg = v.Np; g.save_gates = save_gates && v.gates;
   g.n_tiles_n = v.Hp / 32;
-  const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
+  const int grid = std::max(per_die, 1) * (int)XCDS;
   if (v.cell_kind == 2) {
     const size_t lds = (size_t)4 * 5 * 16 * 64 * sizeof(float);
     (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_tail_fwd<DtOf<T>::value, LSTM_FWD, 4>),
@@ -1550,13 +1557,14 @@ template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, 
     hipLaunchKernelGGL((k_tail_fwd<DtOf<T>::value, RNN_FWD, 4>), dim3(grid), dim3(256), lds, s, g, t);
   }
 }
+// per_die: workgroups per accelerator die (all of one launch must be resident together)
 void vec_tail_fwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
-                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, int save_gates, hipStream_t s) {
+                  uint32_t n_dies, void* sync, long long spin_ticks, int per_die, int save_gates, hipStream_t s) {
   TailArgs t{level_off, lvl_first, lvl_last, n_dies, (DieSync*)sync, spin_ticks};
-  if (v.dtype == TDF_BF16) tail_fwd_t<__bf16>(v, e, t, cus, save_gates, s); else tail_fwd_t<float>(v, e, t, cus, save_gates, s);
+  if (v.dtype == TDF_BF16) tail_fwd_t<__bf16>(v, e, t, per_die, save_gates, s); else tail_fwd_t<float>(v, e, t, per_die, save_gates, s);
 }
 
-template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, const TailArgs& t, int cus, hipStream_t s) {
+template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, const TailArgs& t, int per_die, hipStream_t s) {
   GemmArgs g{};
   g.N = v.Kp; g.K = v.Np;
   g.A = v.Dz; g.lda = v.Np;
@@ -1564,7 +1572,7 @@ template <typename T> static void tail_bwd_t(const VecArgs& v, const Engine& e, 
   g.Hp = v.Hp; g.l = e.q_l; g.r = e.q_r;
   g.C = v.dH;
   g.n_tiles_n = v.Kp / 32;
-  const int grid = std::max(cus / (int)XCDS, 1) * (int)XCDS;
+  const int grid = std::max(per_die, 1) * (int)XCDS;
   if (small_tile_waves<T, DX_BWD>(g.K) == 8) {
     const size_t lds = (size_t)8 * 16 * 64 * sizeof(float);
     hipLaunchKernelGGL((k_tail_bwd<DtOf<T>::value, 8>), dim3(grid), dim3(512), lds, s, g, v, e, t);
@@ -1582,18 +1590,19 @@ void vec_number_rows(const Engine& e, uint32_t n_leaf, uint32_t n_cell, int has_
 }
 
 void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
-                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, uint32_t q_first, const uint32_t* root_rows,
+                  uint32_t n_dies, void* sync, long long spin_ticks, int per_die, uint32_t q_first, const uint32_t* root_rows,
                   hipStream_t s) {
   TailArgs t{level_off, lvl_first, lvl_last, n_dies, (DieSync*)sync, spin_ticks, q_first};
   if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_dz_tail_roots<TDF_BF16>, dim3(e.n_inst), dim3(256), 0, s, v, e, root_rows, q_first);
   else hipLaunchKernelGGL(k_dz_tail_roots<TDF_F32>, dim3(e.n_inst), dim3(256), 0, s, v, e, root_rows, q_first);
-  if (v.dtype == TDF_BF16) tail_bwd_t<__bf16>(v, e, t, cus, s); else tail_bwd_t<float>(v, e, t, cus, s);
+  if (v.dtype == TDF_BF16) tail_bwd_t<__bf16>(v, e, t, per_die, s); else tail_bwd_t<float>(v, e, t, per_die, s);
 }
 
-void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s) {
+// cls < 0: every instance; else only the instances of that class (Engine::inst_class)
+void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, int cls, hipStream_t s) {
   int blocks = ((int)e.n_inst + 3) / 4;
-  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_head<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
-  else hipLaunchKernelGGL(k_head<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad);
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_head<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad, cls);
+  else hipLaunchKernelGGL(k_head<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, dy, with_grad, cls);
 }
 void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label,
                    float* out_node_loss, const float* dnode, int with_grad, hipStream_t s) {

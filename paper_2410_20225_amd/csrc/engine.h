@@ -104,6 +104,8 @@ struct Engine {
   int32_t n_args;
   long long* out_i64;
   uint32_t* root_ref;               // [B] row of the vector result of instance b
+  uint32_t* root_lvl;               // [B] dependency level of that row: the height of instance b's recursion
+  uint32_t* inst_class;             // [B] 1: a deep instance, scheduled apart (set after the tag machine; null: one class)
   // schedule log written by the step kernels; a vector value is named by the frame that produced it
   // until the rows are numbered
   uint32_t log_cap;                 // entries of the leaf / cell logs (0: no vector operators)

@@ -19,7 +19,8 @@ void launch_seed(const DevProgram& P, const Engine& e, hipStream_t s);
 tdf_status launch_round(const DevProgram& P, const Engine& e, int cus, bool local, int small_block, int max_steps,
                         long long spin_ticks, const JitKernels& jit, hipStream_t s);
 int tag_machine_small_block(const DevProgram& P, bool jit);
-void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStream_t s);
+void launch_levels(const Engine& e, uint32_t n_cell, uint32_t n_keys, hipStream_t s);
+void launch_class_keys(const DevProgram& P, const Engine& e, uint32_t n_cell, uint32_t deep_level, uint32_t deep_base, hipStream_t s);
 void launch_merge_logs(const Engine& e, const uint32_t* leaf_off, const uint32_t* cell_off, hipStream_t s);
 void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s);
 void vec_pack_w(const VecArgs& v, hipStream_t s);
@@ -28,12 +29,12 @@ void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count
 void vec_cell_bwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s);
 uint32_t vec_small_level();
 void vec_tail_fwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
-                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, int save_gates, hipStream_t s);
+                  uint32_t n_dies, void* sync, long long spin_ticks, int per_die, int save_gates, hipStream_t s);
 void vec_tail_bwd(const VecArgs& v, const Engine& e, const uint32_t* level_off, uint32_t lvl_first, uint32_t lvl_last,
-                  uint32_t n_dies, void* sync, long long spin_ticks, int cus, uint32_t q_first, const uint32_t* root_rows,
+                  uint32_t n_dies, void* sync, long long spin_ticks, int per_die, uint32_t q_first, const uint32_t* root_rows,
                   hipStream_t s);
 void vec_number_rows(const Engine& e, uint32_t n_leaf, uint32_t n_cell, int has_head, int has_root, hipStream_t s);
-void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, hipStream_t s);
+void vec_head(const VecArgs& v, const Engine& e, const float* dy, int with_grad, int cls, hipStream_t s);
 void vec_node_loss(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t n_cell, const int32_t* node_label,
                    float* out_node_loss, const float* dnode, int with_grad, hipStream_t s);
 void vec_seed_dy(const VecArgs& v, const Engine& e, const float* dy, hipStream_t s);
@@ -147,7 +148,9 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   size_t off_root = L.take(sizeof(uint32_t) * B);
   size_t off_hrow = L.take(sizeof(uint32_t) * B);
   size_t off_hlab = L.take(sizeof(uint32_t) * B);
-  const size_t level_keys = ((size_t)e.max_levels + 2) * LEVEL_KEY_DIES;   // cleared as far as used, after the steps
+  size_t off_rlvl = L.take(sizeof(uint32_t) * B);
+  size_t off_icls = L.take(sizeof(uint32_t) * B);
+  const size_t level_keys = (2 * (size_t)e.max_levels + 4) * LEVEL_KEY_DIES;   // two classes of instances; cleared as far as used, after the steps
   size_t off_lcount = L.take(sizeof(uint32_t) * level_keys);
   size_t off_lfill = L.take(sizeof(uint32_t) * level_keys);
   size_t off_loff = L.take(sizeof(uint32_t) * level_keys);
@@ -174,6 +177,8 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.root_ref = (uint32_t*)at(off_root);
   e.head_row = (uint32_t*)at(off_hrow);
   e.head_label = (uint32_t*)at(off_hlab);
+  e.root_lvl = (uint32_t*)at(off_rlvl);
+  e.inst_class = (uint32_t*)at(off_icls);
   e.leaf_row = (uint32_t*)at(off_leaf_row);
   e.leaf_tok = (uint32_t*)at(off_leaf_tok);
   e.cell_out = (uint32_t*)at(off_c_out);
@@ -464,21 +469,44 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   tdf_status dev = status_from_device(hc.status);
 
   uint32_t tail_first = 0;
-  bool use_tail = false;
-  const uint32_t* level_off = nullptr;   // by sort key (level, machine); in the pinned buffer
+  bool use_tail = false;   // the narrow levels run in one launch per pass on the caller's stream
+  bool deep = false;       // deep instances run apart from the others, all their levels in one launch per pass
+  bool deep_beside = false;   // ... on the side stream, beside the others
+  uint32_t sh_last = 0, deep_base = 0, q_deep0 = 0, n_wide_levels = 0;
+  const uint32_t* level_off = nullptr;   // by sort key; in the pinned buffer
   auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
     e.row0 = hc.n_leaf;   // leaf i has row i, the cell at position q of the sorted log row n_leaf + q
+    if (!gr->side_stream && with_grad && !no_alloc) {
+      HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
+      for (void** ev : {&gr->fork_event, &gr->join_event, &gr->fork_deep, &gr->join_deep})
+        HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)ev, hipEventDisableTiming));
+    }
+    hipStream_t s2 = (hipStream_t)gr->side_stream;
+    auto begin2 = [&](int ph) { if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * ph], s2); phase_used[ph] = true; } };
+    auto end2 = [&](int ph, int64_t n) { if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * ph + 1], s2); launches[ph] += n; };
     begin(TDF_PHASE_LEAVES);
     if (G.cell_kind) vec_pack_w(v, s);   // (a program of EMBEDs alone has no W: the pointers may be NULL)
     vec_embed(v, e, hc.n_leaf, s);
     end(TDF_PHASE_LEAVES, 2);
+    // Instances never exchange values, so instances whose recursion is deep (long chains: many
+    // levels of a few cells each, bound by latency) can run beside the others (few levels of many
+    // cells each, bound by throughput) instead of after them.  An instance is deep if its root's
+    // level is at least deep_level; its cells get sort keys behind all keys of the shallow ones.
+    uint32_t deep_level = 32;
+    if (const char* w = getenv("TDF_DEEP_LEVEL")) deep_level = (uint32_t)std::max(0, atoi(w));
+    const bool want_deep = with_grad && s2 && gr->die_local && !G.has_node_loss && deep_level > 0 && hc.max_level >= deep_level &&
+                           hc.n_cell > 0;
+    const int deep_wgs = getenv("TDF_DEEP_WGS") ? std::max(1, atoi(getenv("TDF_DEEP_WGS"))) : 16;   // workgroups per die
     if (hc.n_cell) {
       begin(TDF_PHASE_LEVELS);
-      launch_levels(e, hc.n_cell, hc.max_level, s);
+      deep_base = want_deep ? deep_level * LEVEL_KEY_DIES : 0;
+      const uint32_t n_keys = deep_base + (hc.max_level + 2) * LEVEL_KEY_DIES;
+      if (want_deep) launch_class_keys(G.prog, e, hc.n_cell, deep_level, deep_base, s);
+      launch_levels(e, hc.n_cell, n_keys, s);
       vec_number_rows(e, hc.n_leaf, hc.n_cell, G.has_head, G.out_type == T_VEC, s);
-      const size_t level_bytes = ((size_t)hc.max_level + 2) * LEVEL_KEY_DIES * sizeof(uint32_t);
+      const size_t level_bytes = (size_t)n_keys * sizeof(uint32_t);
       if (no_alloc && gr->pinned_bytes < PIN_LEVELS + level_bytes) {
         set_error("more dependency levels than the prepared graph's host buffer holds");
         return TDF_ERR_WORKSPACE;
@@ -487,20 +515,63 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         if (tdf_status ps = pinned_reserve(gr, level_bytes); ps != TDF_OK) return ps;
       level_off = (const uint32_t*)((char*)gr->pinned + PIN_LEVELS);
       HIP_TRY(hipMemcpyAsync((void*)level_off, e.level_off, level_bytes, hipMemcpyDeviceToHost, s));
-      end(TDF_PHASE_LEVELS, 5);
+      end(TDF_PHASE_LEVELS, 6);
       HIP_TRY(hipStreamSynchronize(s));
-      // the deep levels, each small, go into one launch in which every die walks its own cells
-      tail_first = hc.max_level + 1;
+      sh_last = want_deep ? std::min(hc.max_level, deep_level - 1) : hc.max_level;
+      q_deep0 = want_deep ? level_off[deep_base] : hc.n_cell;   // the shallow instances' cells come first
+      deep = want_deep && q_deep0 < hc.n_cell;
+      // Side by side only where the shallow instances' levels are worth about as much time as the deep
+      // ones' chain (a level of the chain costs some microseconds whatever it holds, a wide level
+      // costs its arithmetic); else the deep instances follow on the caller's stream with every
+      // compute unit.  TDF_DEEP_BESIDE=0/1 forces either.
+      bool beside = false;
+      if (deep) {
+        const double t_wide = 3.0 * 2.0 * (double)q_deep0 * v.N * (2.0 * v.H) / 4.5e14;
+        const double t_chain = 16e-6 * hc.max_level;
+        beside = t_wide >= 0.4 * t_chain;
+        if (const char* w = getenv("TDF_DEEP_BESIDE")) beside = w[0] == '1';
+      }
+      hipStream_t sd = beside ? s2 : s;   // the deep instances' stream
+      const int deep_per_die = beside ? deep_wgs : cus / (int)XCDS;
+      auto begin_d = [&](int ph) { if (beside) begin2(ph); else begin(ph); };
+      auto end_d = [&](int ph, int64_t n) { if (beside) end2(ph, n); else end(ph, n); };
+      deep_beside = deep && beside;
+      if (deep && beside) {
+        // ---- the deep instances: forward, head and gradient pass in one chain on the side stream
+        HIP_TRY(hipEventRecord((hipEvent_t)gr->fork_deep, s));
+        HIP_TRY(hipStreamWaitEvent(s2, (hipEvent_t)gr->fork_deep, 0));
+      }
+      auto deep_chain = [&]() -> tdf_status {
+        begin_d(TDF_PHASE_TAIL_FWD);
+        vec_tail_fwd(v, e, e.level_off + deep_base, 1, hc.max_level, e.n_dies, base + P.off_tail_sync, spin_ticks, deep_per_die,
+                     with_grad, sd);
+        end_d(TDF_PHASE_TAIL_FWD, 1);
+        if (G.has_head) vec_head(v, e, dy->dy, 1, 1, sd);
+        begin_d(TDF_PHASE_TAIL_BWD);
+        vec_tail_bwd(v, e, e.level_off + deep_base, 1, hc.max_level, e.n_dies, base + P.off_tail_sync + 8 * sizeof(DieSync),
+                     spin_ticks, deep_per_die, q_deep0, G.has_head ? e.head_row : e.root_ref, sd);
+        end_d(TDF_PHASE_TAIL_BWD, 2);
+        if (beside) HIP_TRY(hipEventRecord((hipEvent_t)gr->join_deep, s2));
+        return TDF_OK;
+      };
+      if (deep && G.out_type == T_VEC && !G.has_head) vec_seed_dy(v, e, dy->dy, s);   // (root rows of both classes)
+      if (deep)
+        if (tdf_status ds = deep_chain(); ds != TDF_OK) return ds;   // beside: on the side stream; else first, on the caller's
+      // ---- the (other) instances on the caller's stream: wide levels one launch each; the narrow
+      // levels behind them in one launch in which every die walks its own cells (unless the side
+      // stream already runs such a launch)
+      tail_first = sh_last + 1;
       while (tail_first > 1 && lvl_begin(tail_first) - lvl_begin(tail_first - 1) <= vec_small_level()) --tail_first;
-      use_tail = gr->die_local && hc.max_level + 1 - tail_first >= 4;
-      if (!use_tail) tail_first = hc.max_level + 1;
+      use_tail = !deep && gr->die_local && sh_last + 1 - tail_first >= 4;
+      if (!use_tail) tail_first = sh_last + 1;
+      n_wide_levels = tail_first - 1;
       begin(TDF_PHASE_CELLS_FWD);
       for (uint32_t lvl = 1; lvl < tail_first; ++lvl)
         vec_cell_fwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), with_grad, s);
       end(TDF_PHASE_CELLS_FWD, tail_first - 1);
       if (use_tail) {
         begin(TDF_PHASE_TAIL_FWD);
-        vec_tail_fwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync, spin_ticks, cus,
+        vec_tail_fwd(v, e, e.level_off, tail_first, sh_last, e.n_dies, base + P.off_tail_sync, spin_ticks, cus / (int)XCDS,
                      with_grad, s);
         end(TDF_PHASE_TAIL_FWD, 1);
       }
@@ -508,10 +579,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (!hc.n_cell) vec_number_rows(e, hc.n_leaf, 0, G.has_head, G.out_type == T_VEC, s);   // leaves only
     begin(TDF_PHASE_HEAD);
     if (G.has_head) {
-      vec_head(v, e, with_grad ? dy->dy : nullptr, with_grad, s);
-      HIP_TRY(hipMemcpyAsync(out->out_f32, v.loss, sizeof(float) * e.n_inst, hipMemcpyDeviceToDevice, s));
+      vec_head(v, e, with_grad ? dy->dy : nullptr, with_grad, deep ? 0 : -1, s);
     } else if (G.out_type == T_VEC) {
-      vec_out_rows(v, e, out->out_h, out->out_c, s);
       if (G.has_node_loss) {
         // every state row that has a loss term: the term, and (gradient runs) its gradient with
         // respect to the row, which joins the row's dh where that is read
@@ -519,29 +588,29 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         vec_node_loss(v, e, hc.n_leaf, hc.n_cell, in->node_label, out->out_node_loss, with_grad ? dy->dnode : nullptr,
                       with_grad, s);
       }
-      if (with_grad) vec_seed_dy(v, e, dy->dy, s);
+      if (with_grad && !deep) vec_seed_dy(v, e, dy->dy, s);
     }
     end(TDF_PHASE_HEAD, G.has_node_loss ? 4 : 2);
     if (with_grad) {
       // ---- gradient pass: the level schedule walked backwards -----------------------------
       if (use_tail && hc.n_cell) {
         begin(TDF_PHASE_TAIL_BWD);
-        vec_tail_bwd(v, e, e.level_off, tail_first, hc.max_level, e.n_dies, base + P.off_tail_sync + 8 * sizeof(DieSync),
-                     spin_ticks, cus, lvl_begin(tail_first), G.has_head ? e.head_row : e.root_ref, s);
+        vec_tail_bwd(v, e, e.level_off, tail_first, sh_last, e.n_dies, base + P.off_tail_sync + 8 * sizeof(DieSync),
+                     spin_ticks, cus / (int)XCDS, lvl_begin(tail_first), G.has_head ? e.head_row : e.root_ref, s);
         end(TDF_PHASE_TAIL_BWD, 2);
       }
       begin(TDF_PHASE_CELLS_BWD);
       for (uint32_t lvl = tail_first - 1; lvl >= 1 && hc.n_cell; --lvl)
         vec_cell_bwd(v, e, lvl_begin(lvl), lvl_begin(lvl + 1) - lvl_begin(lvl), s);
       end(TDF_PHASE_CELLS_BWD, 2ll * (tail_first - 1));
+      if (deep_beside) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->join_deep, 0));   // both classes' gradients are complete
+    }
+    // results of `result`, once every instance's root exists
+    if (G.has_head) HIP_TRY(hipMemcpyAsync(out->out_f32, v.loss, sizeof(float) * e.n_inst, hipMemcpyDeviceToDevice, s));
+    else if (G.out_type == T_VEC) vec_out_rows(v, e, out->out_h, out->out_c, s);
+    if (with_grad) {
       // The embedding gradient and the weight gradients depend on the gradient pass only, not on
       // each other: the former runs on a second stream beside the latter.
-      if (!gr->side_stream) {
-        HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
-        HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)&gr->fork_event, hipEventDisableTiming));
-        HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)&gr->join_event, hipEventDisableTiming));
-      }
-      hipStream_t s2 = (hipStream_t)gr->side_stream;
       HIP_TRY(hipEventRecord((hipEvent_t)gr->fork_event, s));
       HIP_TRY(hipStreamWaitEvent(s2, (hipEvent_t)gr->fork_event, 0));
       if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * TDF_PHASE_EMBED_GRAD], s2); phase_used[TDF_PHASE_EMBED_GRAD] = true; }
@@ -566,9 +635,9 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     HIP_TRY(hipGetLastError());
     const DieSync* ts = (const DieSync*)((char*)gr->pinned + PIN_SYNC);
-    if (use_tail) HIP_TRY(hipMemcpyAsync((void*)ts, base + P.off_tail_sync, sizeof(DieSync) * 16, hipMemcpyDeviceToHost, s));
+    if (use_tail || deep) HIP_TRY(hipMemcpyAsync((void*)ts, base + P.off_tail_sync, sizeof(DieSync) * 16, hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
-    if (use_tail) {
+    if (use_tail || deep) {
       bool mixed = false, gave_up = false;
       for (int k = 0; k < 16; ++k) {
         const DieSync& d = ts[k];
@@ -598,8 +667,9 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->n_leaf_rows = hc.n_leaf;
     stats->n_cell_rows = hc.n_cell;
     stats->n_waves = hc.max_level;
-    stats->n_wide_waves = hc.n_cell && tail_first ? tail_first - 1 : 0;
+    stats->n_wide_waves = hc.n_cell ? n_wide_levels : 0;
     stats->n_wide_cells = hc.n_cell && tail_first ? lvl_begin(tail_first) : 0;
+    stats->deep_cells = deep ? (int64_t)(hc.n_cell - q_deep0) : 0;
     unsigned long long* pin_counts = (unsigned long long*)((char*)gr->pinned + PIN_FIRE);
     if (with_grad && dev == TDF_OK && P.vec) {
       HIP_TRY(hipMemcpyAsync(pin_counts, base + P.off_gcount, sizeof(unsigned long long) * 2, hipMemcpyDeviceToHost, s));
@@ -611,7 +681,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->die_local = gr->die_local ? 1 : 0;
     stats->generated = use_jit ? 1 : 0;
     stats->repeats = (int32_t)repeats + inherited_repeats;
-    stats->tail_used = use_tail ? 1 : 0;
+    stats->tail_used = use_tail || deep ? 1 : 0;
+    stats->deep_split = deep ? (deep_beside ? 2 : 1) : 0;
     stats->max_tag_depth = hc.max_depth;
     stats->table_capacity = e.cap;
     stats->max_probe = hc.n_tags > e.n_inst ? 1 : 0;   // the match table is addressed without collisions
@@ -644,8 +715,8 @@ tdf_graph::~tdf_graph() {
     (void)hipStreamSynchronize((hipStream_t)side_stream);
     (void)hipStreamDestroy((hipStream_t)side_stream);
   }
-  if (fork_event) (void)hipEventDestroy((hipEvent_t)fork_event);
-  if (join_event) (void)hipEventDestroy((hipEvent_t)join_event);
+  for (void* ev : {fork_event, join_event, fork_deep, join_deep})
+    if (ev) (void)hipEventDestroy((hipEvent_t)ev);
   if (pinned) (void)hipHostFree(pinned);
 }
 

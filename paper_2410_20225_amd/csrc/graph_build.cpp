@@ -545,7 +545,11 @@ struct Builder {
     // creation order, so neighbours are created and completed together
     D.links_off = 32 + 8 * max_stored;
     D.n_links = max_sites;
-    D.frame_stride = (D.links_off + 4 * max_sites + 31) / 32 * 32;
+    // programs with vector operators also keep the instance (the root of the tag) in every frame:
+    // the data plane schedules deep instances apart from the others
+    const bool vec = G.has_embed || G.cell_kind != 0;
+    D.inst_off = vec ? D.links_off + 4 * max_sites : 0;
+    D.frame_stride = (D.links_off + 4 * max_sites + (vec ? 4 : 0) + 31) / 32 * 32;
     if ((int)G.snodes.size() > TDF_STATS_MAX_COUNTS) bad("static graph too large for tdf_stats");
   }
 };

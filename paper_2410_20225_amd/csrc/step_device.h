@@ -114,6 +114,7 @@ struct LaneCtx {
   int n_pend;
   long long sv[8];         // the first eight stored values, loaded before the sweep
   uint32_t links[MAX_SITES];   // the frame's child links (frame id + 1, 0 = scope not opened), loaded before the sweep
+  uint32_t inst;           // instance the tag belongs to (programs with vector operators)
   uint32_t mx_level;       // largest cell level this lane produced in the pass
   long long tc_v;          // forest entries of the last node looked at
   int tc_left, tc_right, tc_token;
@@ -135,7 +136,10 @@ __device__ __forceinline__ void sw_result(LaneCtx& x, bool go, int type, long lo
   if (go) {
     const uint32_t b = x.frame - x.e->cap;
     if (type == T_INT) { if (x.e->out_i64) x.e->out_i64[b] = v; }
-    else if (type == T_VEC) x.e->root_ref[b] = (uint32_t)v;
+    else if (type == T_VEC) {
+      x.e->root_ref[b] = (uint32_t)v;
+      x.e->root_lvl[b] = (uint32_t)(v >> 32);
+    }
   }
 }
 // forest accessors at node index v: which = 0 isleaf, 1 left, 2 right, 3 token; sets `dead` and
@@ -228,6 +232,7 @@ __device__ __forceinline__ void sw_head(LaneCtx& x, bool on, int slot, bool ap, 
   if (go) {
     const uint32_t inst = x.frame - x.e->cap;
     x.e->head_row[inst] = (uint32_t)av;
+    x.e->root_lvl[inst] = (uint32_t)(av >> 32);
     x.e->head_label[inst] = (uint32_t)bv;
     x.slots[slot] = inst;
     x.present |= 1u << slot;
@@ -466,6 +471,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
   Stage* S = reinterpret_cast<Stage*>(stg_touched + (size_t)z.max_emit * RB);
   const int stride = (int)uni((uint32_t)P.frame_stride);
   const int links_off = (int)uni((uint32_t)P.links_off), n_links = (int)uni((uint32_t)P.n_links);
+  const int inst_off = (int)uni((uint32_t)P.inst_off);
   const uint32_t* cur_list = e.touched + (size_t)(step & 1) * e.touched_cap;
   uint32_t* next_list = e.touched + (size_t)((step & 1) ^ 1) * e.touched_cap;
   uint32_t* next_count = &c->touched_count[(step & 1) ^ 1];
@@ -519,6 +525,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
 #pragma unroll
     for (int k = 0; k < MAX_SITES; ++k)
       x.links[k] = (x.active && k < n_links) ? ld_shared<kCoherent>(&frame_links(h, links_off)[k]) : 0u;
+    x.inst = (x.active && inst_off) ? ld_shared<kCoherent>(frame_links(h, inst_off)) : 0u;
     // stored values (meaningful where the present bit is set), all loads in flight at once
 #pragma unroll
     for (int k = 0; k < 8; ++k) x.sv[k] = (x.active && k < n_st) ? ld_shared<kCoherent>(&x.slots[k]) : 0;
@@ -648,6 +655,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
           if (inserted) {
             uint32_t* tl = frame_links(th, links_off);
             for (int k = 0; k < n_links; ++k) tl[k] = 0u;     // no scope opened from the new frame yet
+            if (inst_off) *frame_links(th, inst_off) = x.inst;   // same instance as the scope that opens it
           }
           if (inserted && may_follow && !has_next && follow + 1 < FOLLOW_DEPTH && P.fn[m.callee].n_params == 1) {
             // the frame this lane goes on with: complete header, nothing pending, not listed

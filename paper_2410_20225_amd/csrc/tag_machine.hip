@@ -26,6 +26,7 @@ __global__ void k_seed(DevProgram P, Engine e) {
   h->present_fn = ((1u << np) - 1u) | ((uint32_t)P.result_fn << 24);
   h->arrived[0] = h->arrived[1] = 0;
   for (int k = 0; k < P.n_links; ++k) frame_links(h, P.links_off)[k] = 0u;
+  if (P.inst_off) *frame_links(h, P.inst_off) = b;
   // instance b belongs to machine b % n_dies
   const uint32_t d = b % e.n_dies, pos = b / e.n_dies;
   e.touched[(size_t)d * 2 * e.touched_cap + pos] = f;
@@ -113,11 +114,11 @@ struct LevelSink {   // the level-sorted copy of the cell log
   }
 };
 
-__global__ void k_level_scan(Engine e, uint32_t max_level) {
-  // single block; levels 1..max_level
+__global__ void k_level_scan(Engine e, uint32_t n_keys) {
+  // single block; exclusive scan over the sort keys
   __shared__ uint32_t carry;
   __shared__ uint32_t buf[1024];
-  const uint32_t L = (max_level + 2) * LEVEL_KEY_DIES;
+  const uint32_t L = n_keys;
   if (threadIdx.x == 0) carry = 0;
   __syncthreads();
   for (uint32_t base = 0; base < L; base += 1024) {
@@ -274,8 +275,24 @@ void launch_count_fired(const DevProgram& P, const Engine& e, hipStream_t s) {
   hipLaunchKernelGGL(k_count_fired, dim3(grid_for(e.cap + e.n_inst, 256, 1024)), dim3(256), 0, s, P, e);
 }
 
-void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStream_t s) {
-  const uint32_t n_keys = (max_level + 2) * LEVEL_KEY_DIES;
+// Deep instances apart: an instance whose recursion is at least deep_level high gets its cells' sort
+// keys moved behind all keys of the other instances (key + deep_base), so the sorted log holds first
+// the shallow instances' cells by (level, machine), then the deep instances' by (level, machine).
+__global__ void k_class_keys(Engine e, DevProgram P, uint32_t n_cell, uint32_t deep_level, uint32_t deep_base) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < e.n_inst) e.inst_class[i] = e.root_lvl[i] >= deep_level ? 1u : 0u;
+  for (uint32_t j = i; j < n_cell; j += gridDim.x * blockDim.x) {
+    const uint32_t inst = *frame_links(frame_at(e, P.frame_stride, e.cell_out[j]), P.inst_off);
+    if (inst < e.n_inst && e.root_lvl[inst] >= deep_level) e.cell_lvl[j] += deep_base;
+  }
+}
+void launch_class_keys(const DevProgram& P, const Engine& e, uint32_t n_cell, uint32_t deep_level, uint32_t deep_base, hipStream_t s) {
+  const uint32_t n = n_cell > e.n_inst ? n_cell : e.n_inst;
+  hipLaunchKernelGGL(k_class_keys, dim3(grid_for(n, 256, 1 << 20)), dim3(256), 0, s, e, P, n_cell, deep_level, deep_base);
+}
+
+// Counting sort of the cell log by sort key (n_keys keys); level_off[k] = first cell of key k.
+void launch_levels(const Engine& e, uint32_t n_cell, uint32_t n_keys, hipStream_t s) {
   (void)hipMemsetAsync(e.level_count, 0, sizeof(uint32_t) * n_keys, s);
   (void)hipMemsetAsync(e.level_fill, 0, sizeof(uint32_t) * n_keys, s);
   if (bucket_fits(n_keys)) {
@@ -284,14 +301,14 @@ void launch_levels(const Engine& e, uint32_t n_cell, uint32_t max_level, hipStre
     bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_place<LevelSink>), n_keys);
     hipLaunchKernelGGL(k_bucket_count, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.cell_lvl, n_cell, n_keys,
                        e.level_count);
-    hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e, max_level);
+    hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e, n_keys);
     hipLaunchKernelGGL(k_bucket_place<LevelSink>, dim3(BUCKET_BLOCKS), dim3(BUCKET_THREADS), lds, s, e.cell_lvl, n_cell,
                        n_keys, e.level_off, e.level_fill, LevelSink{e});
     return;
   }
   int g = grid_for(n_cell, 256, 2048);
   hipLaunchKernelGGL(k_level_hist, dim3(g), dim3(256), 0, s, e, n_cell);
-  hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e, max_level);
+  hipLaunchKernelGGL(k_level_scan, dim3(1), dim3(1024), 0, s, e, n_keys);
   hipLaunchKernelGGL(k_level_scatter, dim3(g), dim3(256), 0, s, e, n_cell);
 }
 

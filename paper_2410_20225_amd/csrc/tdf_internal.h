@@ -46,7 +46,8 @@ struct tdf_graph {
   uint32_t max_dies = 8;    // tag machines a batch is dealt to (set to 1 after a part of the table overflowed)
   void* events[2 * TDF_PHASE_COUNT] = {nullptr};   // hipEvent_t pairs, created on first use
   void* side_stream = nullptr;                     // hipStream_t for work beside the caller's stream
-  void* fork_event = nullptr, *join_event = nullptr;
+  void* fork_event = nullptr, *join_event = nullptr;   // embedding gradient beside the weight gradients
+  void* fork_deep = nullptr, *join_deep = nullptr;     // deep instances beside the others
   // pinned host memory for what an evaluation reads back or sends (control blocks, level offsets,
   // barrier records, the firing tables): copies to and from pageable memory are staged and slower
   void* pinned = nullptr;

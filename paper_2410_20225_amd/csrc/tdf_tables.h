@@ -66,6 +66,8 @@ struct DevFn {
 struct DevProgram {
   int32_t n_fn, result_fn, n_labels, frame_stride;   // frame_stride in bytes
   int32_t links_off, n_links;           // frame record: byte offset and number of the child links (program-wide)
+  int32_t inst_off, pad0;               // frame record: byte offset of the instance index the tag belongs to
+                                        // (programs with vector operators; 0: not kept)
   DevFn fn[MAX_FN];
   uint8_t label_callee[MAX_LABELS];     // function entered by Call_i
   uint8_t label_ret_slot[MAX_LABELS];   // stored slot of Return_i's value in the caller's frame
