@@ -197,7 +197,11 @@ typedef struct {
   const float* U;  /* device float[n_classes x H]   (CE_HEAD, CE_NODE)                  */
   const float* u0; /* device float[n_classes]                                           */
   /* capacities */
-  int64_t max_tags;   /* upper bound on call-context tags (= invocations) of one call   */
+  int64_t max_tags;   /* capacity in call-context tags (= invocations and loop iterations).
+                         tdf_eval of a program without vector operators with stats_level 0
+                         gives a frame back when its tag has finished (Section 5.1: Return_i
+                         deallocates), and max_tags bounds the tags alive at once; in every
+                         other case all frames are kept and it bounds all tags of the call */
   int32_t step_limit; /* 0 = default (1<<20)                                            */
   int32_t stats_level; /* 0: counters and phase times; 1: also tdf_stats.fire_count (one
                           extra pass over the frame table after the evaluation)           */
@@ -256,8 +260,11 @@ typedef struct {
                              gradient body marks its tag's row when it fires (one per tag) */
   int64_t n_grad_not_once; /* tags whose gradient body fired some other number of times than once */
   int64_t max_tag_depth;  /* longest list of call labels and iteration counters         */
-  int64_t table_capacity; /* slots of the tag-hash table                                */
-  int64_t max_probe;      /* longest probe sequence                                     */
+  int64_t table_capacity; /* frame records the machines could hand out (all parts)      */
+  int64_t max_probe;      /* accesses to find a tag's frame: 1 (the match table has no collisions) */
+  int64_t peak_frames;    /* frame records ever handed out: with frames given back, the largest
+                             number of tags alive at once (summed over the machines)    */
+  int64_t frames_reclaimed; /* 1: frames were given back as their tags finished        */
   double phase_ms[TDF_PHASE_COUNT];        /* device time of each phase                */
   int64_t phase_launches[TDF_PHASE_COUNT]; /* kernel launches of each phase            */
   int32_t device_status;  /* tdf_status raised on the device                            */

@@ -82,10 +82,12 @@ class Interpreter:
         self.fire_count = [0] * len(self.g.nodes)
         self.tags = set()              # call-context tags created (entry Merge firings)
         self.iter_tags = set()         # (loop graph, tag) of every iteration entered
+        self._entered_iters = set()    # the same tags without the graph
         self.fwd_body = {}             # tag -> live firings of the function's result value
         self.bwd_body = {}             # tag -> live firings of the gradient entry
         self.dropped = 0               # Return_i label mismatches
         self.rounds = 0
+        self.peak_live_tags = 0        # most tags alive in one round (only with track_live)
         self.max_tag_len = 0
         self.outputs = {}
         self.param_grad = {}
@@ -164,6 +166,7 @@ class Interpreter:
                 self.fire_count[j] += 1
                 if op == "merge_entry" and nd.attr["kind"] == "loop":
                     self.iter_tags.add((nd.fn, tag))
+                    self._entered_iters.add(tag)
                     self.max_tag_len = max(self.max_tag_len, len(tag) - 1)
                 elif op == "merge_entry":
                     self.tags.add(tag)
@@ -345,9 +348,26 @@ class Interpreter:
             xs.clear()
 
     # ------------------------------------------------------------------------------
-    def run(self, inputs, n_instances, max_rounds=10 ** 7):
+    def _live_tags(self):
+        """Tags below the root that some node still holds an unconsumed token of: a pending operand of
+        a node that has not fired, or a node about to fire.  (Section 5.1: the frame of a tag is needed
+        exactly that long; Return_i deallocates it.)  A Merge keeps its record after firing only to
+        ignore later arrivals: that is not a token."""
+        live = set()
+        for (j, tag), rec in self.slots.items():
+            if len(tag) > 1 and not (rec[3] and self.g.nodes[j].op in ("merge", "merge_entry")):
+                live.add(tag)
+        for j, tag in self.ready:
+            if len(tag) > 1:
+                live.add(tag)
+        # only scopes that were really entered: a dead Call sends a dead control token under the tag
+        # of a call that never happens, and no frame exists for it
+        return {t for t in live if t in self.tags or t in self._entered_iters}
+
+    def run(self, inputs, n_instances, max_rounds=10 ** 7, track_live=False):
         """inputs: {("in"|"gin", k): sequence indexed by instance}.  Returns
-        {("out"|"gout", k): list indexed by instance}."""
+        {("out"|"gout", k): list indexed by instance}.  track_live: also record in peak_live_tags the
+        largest number of tags alive in one round (slow: every round looks at every pending token)."""
         self.reset()
         for (kind, k), seq in inputs.items():
             j = self.g.inputs[(kind, k)]
@@ -365,6 +385,8 @@ class Interpreter:
         while self.ready:
             if self.rounds >= max_rounds:
                 raise RuntimeError("round limit exceeded")
+            if track_live:
+                self.peak_live_tags = max(self.peak_live_tags, len(self._live_tags()))
             batch, self.ready = self.ready, []
             self.rounds += 1
             for j, tag in batch:

@@ -332,17 +332,10 @@ template <typename T, int MODE, int BM, int WNS> size_t gemm_lds_bytes() {
   return (size_t)(BM + WNS * WN * 32) * (El<T>::BK + El<T>::PAD) * sizeof(T);
 }
 
-// Waves per workgroup of the tiled GEMM: TDF_GEMM_WAVES = 4 or 8; else 8 where a level's rows are
-// gathered or scattered (two waves per SIMD hide each other's waits), 4 for the dense split GEMM
-// of the weight gradients (fewer LDS reads per MFMA).
-static int gemm_waves(int mode) {
-  static const int w = [] {
-    const char* e = getenv("TDF_GEMM_WAVES");
-    return e ? atoi(e) : 0;
-  }();
-  if (w == 4 || w == 8) return w;
-  return mode == DW_SPLIT ? 4 : 8;
-}
+// Waves per workgroup of the tiled GEMM: 8 where a level's rows are gathered or scattered (two waves
+// per SIMD hide each other's waits), 4 for the dense split GEMM of the weight gradients (fewer LDS
+// reads per MFMA).
+static int gemm_waves(int mode) { return mode == DW_SPLIT ? 4 : 8; }
 
 template <typename T, int MODE, int NW, int BM, int WNS = 2>
 void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
@@ -1684,10 +1677,10 @@ template <typename T> static void weight_grads_t(const VecArgs& v, const Engine&
   hipLaunchKernelGGL(k_db_runs, dim3((v.Np + 63) / 64, (parts + DB_RUN - 1) / DB_RUN), dim3(256), 0, s, v, db_part, parts);
   hipLaunchKernelGGL(k_db_final, dim3((v.Np + 15) / 16), dim3(256), 0, s, v, db_part, (parts + DB_RUN - 1) / DB_RUN, DB_RUN, db);
 }
+// 16-bit state: operands as they lie in memory, transposed by the LDS transpose loads; fp32 (which has
+// no such load): transposed copies first.
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s) {
-  static const bool transposed = getenv("TDF_DW_TRANSPOSED") != nullptr;   // the older way, also for 16-bit state
-  if (v.dtype == TDF_BF16 && !transposed) weight_grads_direct(v, e, n_q, dW, db, db_part, s);
-  else if (v.dtype == TDF_BF16) weight_grads_t<__bf16>(v, e, n_q, dW, db, db_part, s);
+  if (v.dtype == TDF_BF16) weight_grads_direct(v, e, n_q, dW, db, db_part, s);
   else weight_grads_t<float>(v, e, n_q, dW, db, db_part, s);
 }
 

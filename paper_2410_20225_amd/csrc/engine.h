@@ -22,6 +22,10 @@ struct alignas(128) Ctrl {
   uint32_t status;           // 0, or -(tdf_status) raised on the device
   uint32_t done;
   uint32_t n_alloc;          // frames handed out so far: the next free record of this machine's part
+  // Frames given back by finished tags (forward evaluation of integer programs): a ring of frame
+  // ids.  A step takes from the head only what was given back before the step began (up to
+  // free_limit) and gives back at the tail, so takers and givers never meet on an entry.
+  uint32_t free_head, free_tail, free_limit;   // monotone counters, ring index = counter % part
   uint32_t max_depth, max_level;
   uint32_t bar_count;        // grid barrier of the grid-wide step kernel: arrivals (monotone)
   uint32_t bar_gen;          // ... and completed barriers
@@ -87,6 +91,8 @@ struct Engine {
   uint32_t *m_leaf_row, *m_leaf_tok, *m_cell_out, *m_cell_l, *m_cell_r, *m_cell_lvl;
   unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
   char* frames;                     // (cap + B) records of frame_stride bytes: n_dies parts, then the root records
+  uint32_t* free_ring;              // per machine `part` frame ids (see Ctrl::free_head); null: frames are kept until the call ends
+  uint32_t reclaim;                 // 1: a frame is given back once its tag has finished (Section 5.1: Return_i deallocates)
   uint32_t cap, n_inst, max_tags;   // cap = n_dies * part
   uint32_t* touched;                // per machine two lists of touched_cap frame ids, by step parity
   uint32_t touched_cap;
@@ -135,6 +141,7 @@ inline __host__ __device__ Engine die_view(const Engine& e, uint32_t d) {
   v.ctrl = e.ctrl + d;
   v.key_base = d * e.part;
   v.touched = e.touched + (size_t)d * 2 * e.touched_cap;
+  v.free_ring = e.free_ring ? e.free_ring + (size_t)d * e.part : nullptr;
   const size_t o = (size_t)d * e.log_cap;
   v.leaf_row = e.m_leaf_row + o;
   v.leaf_tok = e.m_leaf_tok + o;
@@ -173,20 +180,38 @@ inline __device__ uint32_t wave_alloc(bool take, uint32_t* counter) {
   return base + (uint32_t)__popcll(m & lanemask_lt());
 }
 
-// The same for two requests per lane at once (one counter bump per wave): positions of the first
-// requests, then of the second ones.  SCOPE: memory scope of the bump.
+// Frame records for the new scopes of a wave (two requests per lane at once).  With `ring` set,
+// frames that finished tags gave back before this step are taken first (one bump of the ring's head
+// per wave), the rest comes from the machine's part (one bump of its counter).  f0 / f1: record index
+// inside the part, or >= part where the part is exhausted.
 template <int SCOPE>
-inline __device__ void wave_alloc2(bool take0, bool take1, uint32_t* counter, uint32_t& pos0, uint32_t& pos1) {
+inline __device__ void wave_take_frames(bool take0, bool take1, uint32_t* n_alloc, uint32_t* free_head, const uint32_t* free_limit,
+                                        const uint32_t* ring, uint32_t part, uint32_t& f0, uint32_t& f1) {
   const unsigned long long m0 = __ballot(take0), m1 = __ballot(take1);
-  pos0 = pos1 = 0;
+  f0 = f1 = 0;
   if ((m0 | m1) == 0) return;
   const int leader = __ffsll((long long)(m0 | m1)) - 1;
-  uint32_t base = 0;
-  if ((int)lane_id() == leader)
-    base = __hip_atomic_fetch_add(counter, (uint32_t)(__popcll(m0) + __popcll(m1)), __ATOMIC_RELAXED, SCOPE);
+  const uint32_t n = (uint32_t)(__popcll(m0) + __popcll(m1));
+  uint32_t h = 0, got = 0, base = 0;
+  if ((int)lane_id() == leader) {
+    if (ring) {
+      const uint32_t limit = __hip_atomic_load(free_limit, __ATOMIC_RELAXED, SCOPE);
+      if ((int)(limit - __hip_atomic_load(free_head, __ATOMIC_RELAXED, SCOPE)) > 0) {
+        h = __hip_atomic_fetch_add(free_head, n, __ATOMIC_RELAXED, SCOPE);
+        const int avail = (int)(limit - h);
+        got = avail <= 0 ? 0u : ((uint32_t)avail < n ? (uint32_t)avail : n);
+      }
+    }
+    if (got < n) base = __hip_atomic_fetch_add(n_alloc, n - got, __ATOMIC_RELAXED, SCOPE);
+  }
+  h = __shfl(h, leader);
+  got = __shfl(got, leader);
   base = __shfl(base, leader);
-  pos0 = base + (uint32_t)__popcll(m0 & lanemask_lt());
-  pos1 = base + (uint32_t)__popcll(m0) + (uint32_t)__popcll(m1 & lanemask_lt());
+  const uint32_t r0 = (uint32_t)__popcll(m0 & lanemask_lt());
+  const uint32_t r1 = (uint32_t)__popcll(m0) + (uint32_t)__popcll(m1 & lanemask_lt());
+  // (ring entries were written in earlier steps, maybe by another compute unit: read past the L1)
+  if (take0) f0 = r0 < got ? __hip_atomic_load(&ring[(h + r0) % part], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : base + (r0 - got);
+  if (take1) f1 = r1 < got ? __hip_atomic_load(&ring[(h + r1) % part], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : base + (r1 - got);
 }
 
 // Lanes with `take` get unique consecutive positions in counters[key]; lanes of the wave
@@ -205,6 +230,17 @@ inline __device__ uint32_t wave_alloc_keyed(bool take, uint32_t key, uint32_t* c
     todo &= ~same;
   }
   return pos;
+}
+
+template <int SCOPE>
+inline __device__ uint32_t wave_alloc_scoped(bool take, uint32_t* counter) {
+  unsigned long long m = __ballot(take);
+  if (m == 0) return 0;
+  int leader = __ffsll((long long)m) - 1;
+  uint32_t base = 0;
+  if ((int)lane_id() == leader) base = __hip_atomic_fetch_add(counter, (uint32_t)__popcll(m), __ATOMIC_RELAXED, SCOPE);
+  base = __shfl(base, leader);
+  return base + (uint32_t)__popcll(m & lanemask_lt());
 }
 
 inline __device__ void wave_count32(bool take, uint32_t* counter) {

@@ -145,6 +145,11 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   // --- the rest is written before it is read
   size_t off_prog = L.take(sizeof(DevProgram));
   size_t off_touched = L.take(sizeof(uint32_t) * 2 * (size_t)e.touched_cap * e.n_dies);
+  // Frames are given back as their tags finish where nothing reads them afterwards: no vector
+  // operators (state rows are read after the steps), no gradient pass (it meets the retained
+  // forward values), no per-node firing counts (they are taken from the frames after the run).
+  e.reclaim = !P.vec && !with_grad && in->stats_level == 0 ? 1u : 0u;
+  size_t off_ring = e.reclaim ? L.take(sizeof(uint32_t) * (size_t)e.cap) : 0;
   size_t off_root = L.take(sizeof(uint32_t) * B);
   size_t off_hrow = L.take(sizeof(uint32_t) * B);
   size_t off_hlab = L.take(sizeof(uint32_t) * B);
@@ -174,6 +179,7 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.level_off = (uint32_t*)at(off_loff);
   e.frames = at(P.off_frames);
   e.touched = (uint32_t*)at(off_touched);
+  e.free_ring = e.reclaim ? (uint32_t*)at(off_ring) : nullptr;
   e.root_ref = (uint32_t*)at(off_root);
   e.head_row = (uint32_t*)at(off_hrow);
   e.head_label = (uint32_t*)at(off_hlab);
@@ -238,14 +244,18 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
     v.bp = (float*)at(off_bp);
     v.loss = (float*)at(off_loss);
     if (with_grad) {
+      // In a gradient graph every state row has exactly one consumer, so a cell consumes two rows of
+      // its own: at most half of the rows are cells.
+      P.max_cells = e.log_cap / 2 + 64;
       v.q_stride = (uint32_t)((P.max_cells + 63) / 64 * 64);
       size_t off_dH = L.take(R * v.Hp * 4);
       size_t off_dC = G.cell_kind == 2 ? L.take(R * v.Hp * 4) : 0;
       size_t off_dHn = G.has_node_loss ? L.take(R * v.Hp * 4) : 0;
       size_t off_gates = G.cell_kind == 2 ? L.take((size_t)P.max_cells * v.Np * el) : 0;
       size_t off_Dz = L.take((size_t)P.max_cells * v.Np * el);
-      size_t off_DzT = L.take((size_t)v.Np * v.q_stride * el);
-      size_t off_XT = L.take((size_t)v.Kp * v.q_stride * el);
+      // transposed copies of the weight-gradient operands: the fp32 path only
+      size_t off_DzT = in->dtype == TDF_F32 ? L.take((size_t)v.Np * v.q_stride * el) : 0;
+      size_t off_XT = in->dtype == TDF_F32 ? L.take((size_t)v.Kp * v.q_stride * el) : 0;
       size_t off_WpT = L.take((size_t)v.Np * v.Kp * el);
       size_t off_WfT = L.take((size_t)v.Np * v.Kp * el);
       size_t off_part = L.take((size_t)vec_dw_splits(v.q_stride, v.Np, v.Kp) * v.Np * v.Kp * 4);
@@ -259,8 +269,8 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
       v.dHn = G.has_node_loss ? (float*)at(off_dHn) : nullptr;
       v.gates = G.cell_kind == 2 ? at(off_gates) : nullptr;
       v.Dz = at(off_Dz);
-      v.DzT = at(off_DzT);
-      v.XT = at(off_XT);
+      v.DzT = off_DzT ? at(off_DzT) : nullptr;
+      v.XT = off_XT ? at(off_XT) : nullptr;
       v.WpT = at(off_WpT);
       v.WfT = at(off_WfT);
       v.dW_part = (float*)at(off_part);
@@ -437,6 +447,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       const Ctrl& c = hcs[d];
       hc.n_leaf += c.n_leaf; hc.n_cell += c.n_cell; hc.n_head += c.n_head;
       hc.n_tags += c.n_tags; hc.n_tokens += c.n_tokens;
+      hc.n_alloc += c.n_alloc;
       hc.step = std::max(hc.step, c.step);
       hc.max_depth = std::max(hc.max_depth, c.max_depth);
       hc.max_level = std::max(hc.max_level, c.max_level);
@@ -456,16 +467,17 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     // A part of the tag table can fill up although the whole table would not (instances of very
     // different sizes): repeat with one machine, which owns the whole table.
-    if (e.n_dies > 1 && status_is(hc.status, TDF_ERR_TABLE_FULL) && hc.n_tags <= (unsigned long long)e.max_tags) {
+    if (e.n_dies > 1 && status_is(hc.status, TDF_ERR_TABLE_FULL) && (e.reclaim || hc.n_tags <= (unsigned long long)e.max_tags)) {
       gr->max_dies = 1;
       ++repeats;
       continue;
     }
-    if (hc.n_tags > (unsigned long long)e.max_tags && !hc.status) hc.status = (uint32_t)(-TDF_ERR_TABLE_FULL);
+    if (!e.reclaim && hc.n_tags > (unsigned long long)e.max_tags && !hc.status) hc.status = (uint32_t)(-TDF_ERR_TABLE_FULL);
     if (!hc.status) launch_merge_logs(e, leaf_off, cell_off, s);
     break;
   }
   end(TDF_PHASE_TAGS, 2 + 2ll * rounds);
+  if (!hc.status && P.vec && with_grad && hc.n_cell > P.max_cells) hc.status = (uint32_t)(-TDF_ERR_TABLE_FULL);
   tdf_status dev = status_from_device(hc.status);
 
   uint32_t tail_first = 0;
@@ -685,6 +697,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->deep_split = deep ? (deep_beside ? 2 : 1) : 0;
     stats->max_tag_depth = hc.max_depth;
     stats->table_capacity = e.cap;
+    stats->peak_frames = (int64_t)hc.n_alloc;
+    stats->frames_reclaimed = e.reclaim ? 1 : 0;
     stats->max_probe = hc.n_tags > e.n_inst ? 1 : 0;   // the match table is addressed without collisions
     for (int ph = 0; ph < TDF_PHASE_COUNT; ++ph) {
       float ms = 0.f;

@@ -77,7 +77,7 @@ struct Gen {
     o << "      if (__ballot(on) != 0) {\n";
     for (int v = 0; v < fn.n_values; ++v)
       o << "        long long v" << v << " = 0; bool p" << v << " = false, d" << v << " = false;\n";
-    o << "        bool live = false;\n";
+    o << "        bool live = false, all_in = true;\n";
     for (int ip = 0; ip < fn.count; ++ip) {
       const Instr& I = P.instr[fn.first + ip];
       const std::string bit = "(1ull << " + std::to_string(ip) + ")";
@@ -86,7 +86,7 @@ struct Gen {
       switch (I.op) {
         case D_IN:
           o << "          p" << D << " = on && ((x.present >> " << (int)I.aux << ") & 1); v" << D << " = x.sv[" << (int)I.aux
-            << "]; live = p" << D << ";\n";
+            << "]; live = p" << D << "; all_in = all_in && p" << D << ";\n";
           break;
         case D_RET: {
           std::string all_p = "true", any_d = "false";
@@ -101,6 +101,7 @@ struct Gen {
           o << "          const bool is_dead = on && !p && " << (any_arg ? "true" : "false") << " && (" << all_p << ") && (" << any_d
             << ");\n";
           o << "          v" << D << " = x.sv[" << (int)I.aux << "]; p" << D << " = p || is_dead; d" << D << " = is_dead; live = p;\n";
+          o << "          all_in = all_in && p" << D << ";\n";
           break;
         }
         case D_ADD: case D_SUB: case D_MUL: case D_EQ: case D_LT: {
@@ -183,6 +184,7 @@ struct Gen {
       o << "          if (live) x.fired |= " << bit << ";\n";
       o << "        }\n";
     }
+    o << "        if (on) x.complete = all_in;\n";
     o << "      }\n    }\n";
   }
 

@@ -115,6 +115,9 @@ struct LaneCtx {
   long long sv[8];         // the first eight stored values, loaded before the sweep
   uint32_t links[MAX_SITES];   // the frame's child links (frame id + 1, 0 = scope not opened), loaded before the sweep
   uint32_t inst;           // instance the tag belongs to (programs with vector operators)
+  bool complete;           // set by the sweep: every value that reaches this tag from another tag (parameters,
+                           // results of its calls and loops) has arrived or is known never to come, so
+                           // everything in the body has fired and no token can reach the frame any more
   uint32_t mx_level;       // largest cell level this lane produced in the pass
   long long tc_v;          // forest entries of the last node looked at
   int tc_left, tc_right, tc_token;
@@ -282,6 +285,7 @@ struct InterpSweep {
       const int first_i = (int)uni(P.fn[f].first), count = (int)uni(P.fn[f].count);
       const bool is_result = f == x.result_fn;
       unsigned long long pres = 0, dead = 0;   // over value ids
+      bool all_in = true;                       // every D_IN / D_RET entry is resolved
       Instr I_next = fetch(P, first_i);
       for (int ip = 0; ip < count; ++ip) {
         const Instr I = I_next;
@@ -303,6 +307,7 @@ struct InterpSweep {
             const bool p = on && ((x.present >> I.aux) & 1);
             put(I.dst, rd_st(I.aux), p, false);
             live = p;
+            all_in = all_in && p;
             break;
           }
           case D_RET: {
@@ -317,6 +322,7 @@ struct InterpSweep {
             const bool is_dead = on && !p && any_arg && all_p && any_d;   // the call never happened
             put(I.dst, rd_st(I.aux), p || is_dead, is_dead);
             live = p;
+            all_in = all_in && (p || is_dead);
             break;
           }
           case D_ADD: case D_SUB: case D_MUL: case D_EQ: case D_LT: {
@@ -432,6 +438,7 @@ struct InterpSweep {
         }
         if (live) x.fired |= ibit;   // counted after the run, from the fired masks
       }
+      if (on) x.complete = all_in;
     }
   }
 };
@@ -557,6 +564,7 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
     unsigned long long nx_key = 0;
     long long nx_val = 0;
 
+    x.complete = false;
     SW::run(x, P);   // ---- fire
 
     // ---- match: deliver the emitted tokens, two at a time so that their atomics overlap ------
@@ -615,7 +623,8 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       // new scopes take the machine's next free records: one counter bump per wave
       {
         uint32_t pos[2];
-        wave_alloc2<kDirect ? __HIP_MEMORY_SCOPE_WORKGROUP : SCOPE>(fresh[0], fresh[1], &c->n_alloc, pos[0], pos[1]);
+        wave_take_frames<kDirect ? __HIP_MEMORY_SCOPE_WORKGROUP : SCOPE>(fresh[0], fresh[1], &c->n_alloc, &c->free_head, &c->free_limit,
+                                                                         e.reclaim ? e.free_ring : nullptr, e.part, pos[0], pos[1]);
 #pragma unroll
         for (int q = 0; q < 2; ++q)
           if (fresh[q]) {
@@ -699,6 +708,14 @@ __device__ void step_pass(const DevProgram& P, const Engine& e, Ctrl* c, uint32_
       if (x.fired != fired_in) h->fired = x.fired;
       const uint32_t pf_out = x.present | ((uint32_t)x.myfn << 24);
       if (pf_out != pf_in) h->present_fn = pf_out;
+    }
+    if (e.reclaim) {
+      // Section 5.1: Return_i deallocates the frame.  A tag whose sweep found everything resolved has
+      // fired all it ever will (its Return token left above) and can receive nothing more: its frame
+      // goes back to the machine, for scopes opened from the next step on.  (Root records stay.)
+      const bool give = x.active && x.complete && x.frame < e.cap;
+      const uint32_t pos = wave_alloc_scoped<kDirect ? __HIP_MEMORY_SCOPE_WORKGROUP : SCOPE>(give, &c->free_tail);
+      if (give) e.free_ring[pos % e.part] = x.frame - e.key_base;
     }
     if (!kDirect || __ballot(has_next) == 0) break;
     // go on with the frame just created
@@ -798,7 +815,15 @@ __device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
   }
   st(&c->touched_count[parity], 0u);
   st(&c->step, step + 1);
-  if (ld(&c->n_tags) > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
+  if (e.reclaim) {
+    // what this step gave back may be taken from the next step on; a head that ran past the limit
+    // (takers found the ring empty) goes back to it
+    const uint32_t limit = ld(&c->free_limit);
+    if ((int)(ld(&c->free_head) - limit) > 0) st(&c->free_head, limit);
+    st(&c->free_limit, ld(&c->free_tail));
+  }
+  // (with frames given back, max_tags bounds the tags alive at once: the part overflows instead)
+  if (!e.reclaim && ld(&c->n_tags) > e.max_tags && status == 0) status = (uint32_t)(-TDF_ERR_TABLE_FULL);
   if (step + 1 >= e.step_limit && next != 0 && status == 0) status = (uint32_t)(-TDF_ERR_STEP_LIMIT);
   if (status != 0) {
     st(&c->status, status);
@@ -942,6 +967,9 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     lc.status = ld(&g->status);
     lc.done = g->done;
     lc.n_alloc = ld(&g->n_alloc);
+    lc.free_head = ld(&g->free_head);
+    lc.free_tail = ld(&g->free_tail);
+    lc.free_limit = ld(&g->free_limit);
     lc.max_depth = ld(&g->max_depth);
     lc.max_level = ld(&g->max_level);
     lc.bar_count = lc.bar_gen = 0;
@@ -971,6 +999,9 @@ __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_ld
     st(&g->status, lc.status);
     g->done = lc.done;
     st(&g->n_alloc, lc.n_alloc);
+    st(&g->free_head, lc.free_head);
+    st(&g->free_tail, lc.free_tail);
+    st(&g->free_limit, lc.free_limit);
     st(&g->max_depth, lc.max_depth);
     st(&g->max_level, lc.max_level);
     st(&g->n_tags, lc.n_tags);

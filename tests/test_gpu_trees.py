@@ -143,15 +143,13 @@ def test_token_id_outside_the_vocabulary_is_an_error():
     assert st == tdf.ERR_BAD_ARG and "token" in tdf.last_error()
 
 
-@pytest.mark.parametrize("kernels", ["default", "tiled_gemm_only", "tiled_gemm_four_waves"])
+@pytest.mark.parametrize("kernels", ["default", "tiled_gemm_only"])
 @pytest.mark.parametrize("cell,cfg", [("rnn", 3), ("lstm", 4)])
 def test_vector_result_with_given_dy_fp32(cell, cfg, kernels, monkeypatch):
     # no head: the caller supplies dL/dh of every root; fp32 end to end, also with every level
     # through the tiled GEMM (fp32 MFMA, ragged tiles: H = 48 is padded to 64)
     if kernels != "default":
         monkeypatch.setenv("TDF_SMALL_LEVEL", "0")
-    if kernels == "tiled_gemm_four_waves":
-        monkeypatch.setenv("TDF_GEMM_WAVES", "4")
     c = make_config(cfg, n_trees=24, max_leaves=20, hidden=48, vocab=200)
     c["bf16"] = False
     B, H = c["forest"].n_trees, c["H"]

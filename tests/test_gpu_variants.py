@@ -1,11 +1,11 @@
 """GPU parity of the library's alternative code paths, each forced by its environment switch:
 the table interpreter instead of generated step kernels, grid-wide steps synchronised through
-memory instead of one die's L2, every level through the tiled GEMM (eight waves, four waves) or
-through the small-level kernel, and every step through the grid-wide kernel (on eight machines and on one) or through
-the single-workgroup kernel, the weight gradients from transposed copies of their operands (the fp32 way) instead of
-transposing LDS loads, the repetition of a run whose die-private kernels did not keep to their dies (the host is told
-they did not), and steps in which no lane goes on with the frame it created.  Same bars as the main parity tests: integers and counts bit-exact, bf16
-within rel 2e-2 (Frobenius)."""
+memory instead of one die's L2, every level through the tiled GEMM or through the small-level
+kernel, every step through the grid-wide kernel (on eight machines and on one) or through the
+single-workgroup kernel, the repetition of a run whose die-private kernels did not keep to their
+dies (the host is told they did not), and steps in which no lane goes on with the frame it
+created.  Every case asserts through tdf_stats that the requested path is the one that ran.  Same
+bars as the main parity tests: integers and counts bit-exact, bf16 within rel 2e-2 (Frobenius)."""
 import numpy as np
 import pytest
 import torch
@@ -21,11 +21,11 @@ from gpu_util import DEV, TreeRun, run_oracle_tree, rel_fro, fire_counts  # noqa
 VARIANTS = [{"TDF_NO_JIT": "1"}, {"TDF_NO_DIE_LOCAL": "1"}, {"TDF_NO_JIT": "1", "TDF_NO_DIE_LOCAL": "1"},
             {"TDF_SMALL_LEVEL": "0"}, {"TDF_SMALL_LEVEL": "100000000"},
             {"TDF_SMALL_LIMIT": "1"}, {"TDF_SMALL_LIMIT": "1", "TDF_DIES": "1"}, {"TDF_SMALL_LIMIT": "100000000"},
-            {"TDF_SMALL_LEVEL": "0", "TDF_GEMM_WAVES": "4"}, {"TDF_TEST_MIXED_DIES": "1"}, {"TDF_TEST_MIXED_DIES": "2"},
-            {"TDF_DW_TRANSPOSED": "1"}, {"TDF_FOLLOW_LIMIT": "0"}]
+            {"TDF_TEST_MIXED_DIES": "1"}, {"TDF_TEST_MIXED_DIES": "2"},
+            {"TDF_FOLLOW_LIMIT": "0"}]
 IDS = ["interpreter", "device_scope", "interpreter_device_scope", "tiled_gemm_only", "small_level_only",
-       "grid_kernel_only", "grid_kernel_only_one_machine", "single_workgroup_only", "tiled_gemm_four_waves",
-       "repeat_after_machines_left_their_dies", "repeat_after_tail_left_its_dies", "weight_grads_from_transposed_copies",
+       "grid_kernel_only", "grid_kernel_only_one_machine", "single_workgroup_only",
+       "repeat_after_machines_left_their_dies", "repeat_after_tail_left_its_dies",
        "no_follow"]
 
 
