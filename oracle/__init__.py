@@ -12,4 +12,4 @@ differences and closed-form gradients.  No part of the oracle is "parity unpinne
 from .graph import Function, Program, transform, INT, FLOAT, VEC
 from .interp import Interpreter, DEAD
 from .autodiff import differentiate
-from . import programs, ops
+from . import programs, ops, ops_bf16

@@ -40,7 +40,7 @@ accumulated in float64 in firing order (the paper leaves the cross-tag sum impli
 parameters are input nodes visible under every tag).
 """
 import numpy as np
-from . import ops
+from . import ops, ops_bf16
 from .graph import TWO_PORT_OPS
 
 
@@ -282,10 +282,11 @@ class Interpreter:
             return env["E"][v[0]].astype(np.float64)
         if op == "embed_lstm":
             return ops.lstm_leaf(env["E"][v[0]].astype(np.float64))
+        cells = ops_bf16 if env.get("round_bf16") else ops   # diagnostic: the roundings of a 16-bit state path
         if op == "rnn_cell":
-            return ops.rnn_cell(env["W"], env["b"], v[0], v[1])
+            return cells.rnn_cell(env["W"], env["b"], v[0], v[1])
         if op == "lstm_cell":
-            return ops.lstm_cell(env["W"], env["b"], v[0], v[1])
+            return cells.lstm_cell(env["W"], env["b"], v[0], v[1])
         if op == "take_h":
             return v[0][: v[0].shape[0] // 2]
         if op == "take_h_grad":                     # (s, dh) -> ds
@@ -314,11 +315,11 @@ class Interpreter:
             self._add_rows("dE", v[0], v[1][: v[1].shape[0] // 2])
             return None
         if op == "rnn_cell_grad":                   # (h_l, h_r, dh) -> (dh_l, dh_r)
-            dl, dr, delta, x = ops.rnn_cell_grad(env["W"], env["b"], v[0], v[1], v[2])
+            dl, dr, delta, x = cells.rnn_cell_grad(env["W"], env["b"], v[0], v[1], v[2])
             self._add_outer("dW", "db", delta, x)
             return (dl, dr)
         if op == "lstm_cell_grad":
-            dl, dr, dz, x = ops.lstm_cell_grad(env["W"], env["b"], v[0], v[1], v[2])
+            dl, dr, dz, x = cells.lstm_cell_grad(env["W"], env["b"], v[0], v[1], v[2])
             self._add_outer("dW", "db", dz, x)
             return (dl, dr)
         raise ValueError("unknown op " + op)

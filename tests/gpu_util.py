@@ -43,14 +43,17 @@ def oracle_env(c):
     return dict(left=F.left, right=F.right, token=F.token, E=c["E"], W=c["W"], b=c["b"], U=c["U"], u0=c["u0"])
 
 
-def run_oracle_tree(c, head, grad, dy=None):
-    """Returns dict with out (list per instance), grads, interpreter."""
+def run_oracle_tree(c, head, grad, dy=None, round_bf16=False):
+    """Returns dict with out (list per instance), grads, interpreter.  round_bf16: the oracle's
+    diagnostic variant with the roundings of a 16-bit state path (oracle/ops_bf16.py)."""
     F = c["forest"]
     B = F.n_trees
     prog = oracle_programs.tree_program(c["cell"], head=head)
     if grad:
         prog = oracle.differentiate(prog)
-    it = oracle.Interpreter(oracle.transform(prog), oracle_env(c))
+    env = oracle_env(c)
+    env["round_bf16"] = round_bf16
+    it = oracle.Interpreter(oracle.transform(prog), env)
     inputs = {("in", 0): F.roots.tolist()}
     if head:
         inputs[("in", 1)] = c["labels"].tolist()

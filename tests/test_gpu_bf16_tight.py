@@ -1,0 +1,93 @@
+"""The 16-bit path held to tighter bars than the workload's 2e-2:
+
+* against the oracle's diagnostic variant that rounds where a 16-bit state path stores (h in
+  bfloat16, c in float32, kept gate activations and pre-activation gradients in bfloat16).  What is
+  left is accumulation order, the activations' last bits, and the rounding decisions those last
+  bits flip on near-ties (one unit of the 8-bit mantissa each).  Where the state is carried in a
+  float32 c (TreeLSTM) the flips stay local: bar 1e-3.  Where it is carried in the rounded h itself
+  (TreeRNN) every level hands its flips on: bar 3e-3 for sentence-sized trees, 8e-3 for chains
+  255 cells deep, which is no tighter than the workload's own bar would need but still shows that
+  nothing beyond rounding is lost;
+* the matrix products alone: on a forest of two-leaf trees every product of the path is a plain
+  GEMM of bfloat16 operands that the test can read back (the leaves' embedding rows, the roots' h),
+  so the float32 outputs are compared with float64 products of those same operands.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from tdf_workloads import make_config, SplitMix64  # noqa: E402
+from tdf_workloads.trees import build_forest, complete_tree  # noqa: E402
+from oracle.ops_bf16 import bf16  # noqa: E402
+from gpu_util import TreeRun, run_oracle_tree, rel_fro  # noqa: E402
+
+@pytest.mark.parametrize("cfg,n_trees,max_leaves,hidden,vocab,TIGHT", [
+    (3, 96, 60, 300, 2000, 3e-3),
+    (4, 128, 128, 256, 3000, 1e-3),
+    (5, 4, 256, 512, 500, 8e-3),
+])
+def test_against_the_rounding_oracle(cfg, n_trees, max_leaves, hidden, vocab, TIGHT):
+    c = make_config(cfg, n_trees=n_trees, max_leaves=max_leaves, hidden=hidden, vocab=vocab)
+    B = c["forest"].n_trees
+    dy = np.full(B, 1.0 / B)
+    run = TreeRun(c, head=True, grad=True)
+    run.run(dy)
+    ref = run_oracle_tree(c, head=True, grad=True, dy=dy, round_bf16=True)
+    plain = run_oracle_tree(c, head=True, grad=True, dy=dy)
+    errs = {}
+    for name, got, want, base in (("loss", run.out_f32, np.array(ref["out"]), np.array(plain["out"])),
+                                  ("dW", run.dW, ref["grads"]["dW"], plain["grads"]["dW"]),
+                                  ("db", run.db, ref["grads"]["db"], plain["grads"]["db"]),
+                                  ("dE", run.dE, ref["grads"]["dE"], plain["grads"]["dE"])):
+        g = got.cpu().numpy()
+        errs[name] = (rel_fro(g, want), rel_fro(g, base))
+        assert errs[name][0] < TIGHT, (name, errs[name])
+    print({k: ("%.1e vs rounding oracle, %.1e vs plain" % v) for k, v in errs.items()})
+    # no head: the root states themselves
+    run = TreeRun(c, head=False, grad=False)
+    run.run()
+    want = np.stack(run_oracle_tree(c, head=False, grad=False, round_bf16=True)["out"])
+    H = c["H"]
+    assert rel_fro(run.out_h.cpu().numpy(), want[:, :H]) < TIGHT
+    if c["cell"] == "lstm":
+        assert rel_fro(run.out_c.cpu().numpy(), want[:, H:]) < TIGHT
+
+
+def test_matrix_products_alone_against_float64_products():
+    # 3000 two-leaf TreeRNN trees, H = 128, distinct tokens: one level of 3000 cells (the tiled GEMM
+    # and its gradient kernels), dy given per root.  With x_b = [E[t_l]; E[t_r]] (bfloat16 values):
+    #   h_b    = bf16(tanh(W x_b + b))            forward product
+    #   d_b    = bf16(dy_b (1 - h_b^2))           formed from the h the GPU returned
+    #   dW     = sum_b d_b x_b^T,  db = sum_b d_b                weight-gradient product
+    #   dE[t]  = (W^T d_b) half of the leaf with token t         input-gradient product
+    B, H = 3000, 128
+    c = make_config(3, n_trees=B, max_leaves=2, hidden=H, vocab=2 * B)
+    rng = SplitMix64(99)
+    shapes = [complete_tree(2) for _ in range(B)]
+    toks = iter(np.argsort(rng.uniform(2 * B), kind="stable").reshape(B, 2))
+    c["forest"] = build_forest(shapes, lambda n: next(toks))
+    c["b"] = np.asarray(bf16(rng.normal(H) * 0.1))
+    F = c["forest"]
+    dy = rng.normal(B * H).reshape(B, H)
+    run = TreeRun(c, head=False, grad=True)
+    st, stats = run.run(dy)
+    assert stats.n_wide_waves == 1 and stats.n_cell_rows == B
+    E, W, b = c["E"], c["W"], c["b"]
+    tl, tr = F.token[F.left[F.roots]], F.token[F.right[F.roots]]
+    X = np.concatenate([E[tl], E[tr]], 1)                       # [B, 2H], bfloat16 values
+    h_gpu = run.out_h.cpu().numpy().astype(np.float64)
+    h_ref = bf16(np.tanh(X @ W.T + b))
+    # forward: the same bfloat16 value, up to one unit in the last of its 8 bits where tanh's last
+    # bits decide a rounding
+    ulp = np.maximum(np.abs(h_ref), 2.0 ** -126) * 2.0 ** -7
+    assert np.all(np.abs(h_gpu - h_ref) <= ulp * 1.01)
+    assert np.mean(h_gpu != h_ref) < 0.02
+    D = bf16(dy.astype(np.float32).astype(np.float64) * (1.0 - h_gpu * h_gpu))   # the operand the gradient products used
+    fl32 = 2e-6                                                 # float32 accumulation over 3000 / 256 terms
+    assert rel_fro(run.dW.cpu().numpy(), D.T @ X) < fl32
+    assert rel_fro(run.db.cpu().numpy(), D.sum(0)) < fl32
+    dX = D @ W                                                  # [B, 2H]
+    dE = run.dE.cpu().numpy()
+    assert rel_fro(dE[tl], dX[:, :H]) < fl32 and rel_fro(dE[tr], dX[:, H:]) < fl32
