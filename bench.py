@@ -105,6 +105,8 @@ def main():
     ap.add_argument("--config", type=int, default=4, help="workload 1..6 (default 4: TreeLSTM forward+gradient)")
     ap.add_argument("--node-loss", action="store_true",
                     help="workloads 3..5 with a loss term at every tree node instead of the root only")
+    ap.add_argument("--scale", type=int, default=1,
+                    help="workloads 2..5: this many times the workload's trees, same recipe (saturation sweep; the headline is --scale 1)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle's sample (0 = auto)")
     a = ap.parse_args()
@@ -144,7 +146,11 @@ def main():
         passes, dtype, flops_fwd, cell = 1, "int64", 0.0, None
     else:
         from paper_2410_20225_amd.harness import TreeRun
-        c = make_config(cfg)
+        if a.scale != 1:
+            base_trees = {2: 256, 3: 1024, 4: 4096, 5: 128}[cfg]
+            c = make_config(cfg, n_trees=base_trees * a.scale)
+        else:
+            c = make_config(cfg)
         grad = c["grad"]
         B = c["forest"].n_trees
         if a.node_loss:
@@ -182,14 +188,31 @@ def main():
     torch.cuda.synchronize()
     phase = np.zeros(len(tdf.PHASES))
     launches = np.zeros(len(tdf.PHASES))
+    span_ms = 0.0
     t0 = time.perf_counter()
     for _ in range(a.steps):
         st = step()
         phase += np.array(list(st.phase_ms))
         launches += np.array(list(st.phase_launches))
+        span_ms += st.fwd_cells_span_ms
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     n_tags = int(st.n_tags)
+    # one more evaluation, outside the timed region, with the tag machines' step records switched on
+    widest = []
+    if cfg in (1, 6):
+        inp.stats_level = 2
+        ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=dev)
+        st2 = step()
+    else:
+        run.inputs.stats_level = 2
+        run.ws = torch.empty(tdf.workspace_size(run.graph, run.inputs, run.grad), dtype=torch.uint8, device=dev)
+        st2 = step()
+    for k in range(8):
+        if st2.wide_step_frames[k] > 0 and st2.wide_step_us[k] > 0:
+            fr, cr, us = int(st2.wide_step_frames[k]), int(st2.wide_step_created[k]), float(st2.wide_step_us[k])
+            widest.append({"frames": fr, "tags_created": cr, "us": round(us, 2),
+                           "useful_GBps": round(72.0 * max(cr, fr // 3) / (us * 1e-6) / 1e9, 2)})
     firings = n_tags * passes
     value = firings * a.steps / dt
     phase_ms = {n: round(float(p) / a.steps, 4) for n, p in zip(tdf.PHASES, phase)}
@@ -203,15 +226,20 @@ def main():
                  "launches_per_step": launches[0] / a.steps, "traffic": measured_traffic(cfg, "steps")}
     roof_tags["frac"] = roof_tags["achieved"] / roof_tags["peak"]
     roof_tags["copy_kernel_GBps"] = copy_gbps   # measured read + write rate of a plain 1 GiB device copy
+    # the widest steps of a single tag machine (one of up to eight running side by side): frames that
+    # received a token, tags the step created, duration; useful bytes = 72 B per tag created
+    roof_tags["widest_steps_of_one_machine"] = widest
     if cfg in (1, 6):
         roof = roof_tags
     else:
         i_fwd, i_tail = tdf.PHASES.index("cells_fwd"), tdf.PHASES.index("tail_fwd")
-        ms = (phase[i_fwd] + phase[i_tail]) / a.steps
+        # forward cell kernels of all levels.  Where deep instances run beside the others the two groups of
+        # launches overlap: the time is the span from the first launch to the last end over both streams
+        ms = span_ms / a.steps if st.deep_split == 2 else (phase[i_fwd] + phase[i_tail]) / a.steps
         n_launch = (launches[i_fwd] + launches[i_tail]) / a.steps
         peak = PEAK_BF16 if dtype == "bf16" else PEAK_F32
         per_cell = 2.0 * rows * 2 * c["H"]
-        roof = {"bound": "mfma", "kernel": "k_gemm + k_tail_fwd <%s,%s_FWD> (all levels)" % (dtype, cell.upper()),
+        roof = {"bound": "mfma", "kernel": "k_gemm + k_cell_small + k_tail_fwd <%s,%s_FWD> (forward cells of all levels)" % (dtype, cell.upper()),
                 "achieved": flops_fwd / (ms * 1e-3) / 1e12, "peak": peak / 1e12, "unit": "TFLOP/s",
                 "launches_per_step": n_launch, "avg_launch_us": 1e3 * ms / max(n_launch, 1),
                 "traffic": None if a.node_loss else measured_traffic(cfg, "cells")}
@@ -242,7 +270,12 @@ def main():
            "config": {"workload": "config %d: %s%s" % (cfg, CONFIG_NAMES[cfg], ", a loss term at every node" if a.node_loss else ""),
                       "n_tags": n_tags,
                       "firings_per_step": firings, "n_steps_tag_machine": int(st.n_steps),
-                      "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth)},
+                      "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth), "scale": a.scale,
+                      # which way the evaluation took
+                      "n_machines": int(st.n_machines), "die_local": int(st.die_local), "generated_step_kernels": int(st.generated),
+                      "repeats": int(st.repeats), "tail_used": int(st.tail_used), "deep_split": int(st.deep_split),
+                      "deep_cells": int(st.deep_cells), "frames_reclaimed": int(st.frames_reclaimed),
+                      "peak_frames": int(st.peak_frames)},
            "phase_ms": phase_ms, "roofline": roof}
     if cfg not in (1, 6):
         rec["roofline_tag_machine"] = roof_tags

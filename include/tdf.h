@@ -204,7 +204,8 @@ typedef struct {
                          other case all frames are kept and it bounds all tags of the call */
   int32_t step_limit; /* 0 = default (1<<20)                                            */
   int32_t stats_level; /* 0: counters and phase times; 1: also tdf_stats.fire_count (one
-                          extra pass over the frame table after the evaluation)           */
+                          extra pass over the frame table after the evaluation); 2: also the
+                          size and duration of the tag machines' widest steps              */
 } tdf_inputs;
 
 typedef struct {
@@ -267,6 +268,13 @@ typedef struct {
   int64_t frames_reclaimed; /* 1: frames were given back as their tags finished        */
   double phase_ms[TDF_PHASE_COUNT];        /* device time of each phase                */
   int64_t phase_launches[TDF_PHASE_COUNT]; /* kernel launches of each phase            */
+  double fwd_cells_span_ms; /* first launch to last end of the forward cell kernels, over both
+                               streams where deep instances run beside the others          */
+  /* stats_level 2: the eight widest steps of the tag machines (a step of one machine): frames
+     that received a token, frames created by the step, duration                              */
+  int64_t wide_step_frames[8];
+  int64_t wide_step_created[8];
+  double wide_step_us[8];
   int32_t device_status;  /* tdf_status raised on the device                            */
   int32_t n_counts;       /* entries used in fire_count                                 */
   /* which way the evaluation took */

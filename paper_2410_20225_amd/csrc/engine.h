@@ -70,6 +70,7 @@ struct FrameHdr {
 static_assert(sizeof(FrameHdr) == 32, "FrameHdr must be 32 bytes");
 
 constexpr uint32_t LEVEL_KEY_DIES = 8;
+constexpr uint32_t STEP_LOG_CAP = 8192;   // steps per machine whose size and time are recorded on request
 
 // Pointers into the workspace and to the caller's buffers, passed to kernels by value.
 //
@@ -91,6 +92,8 @@ struct Engine {
   uint32_t *m_leaf_row, *m_leaf_tok, *m_cell_out, *m_cell_l, *m_cell_r, *m_cell_lvl;
   unsigned long long* fire_count;   // [TDF_STATS_MAX_COUNTS]
   char* frames;                     // (cap + B) records of frame_stride bytes: n_dies parts, then the root records
+  uint4* step_log;                  // per machine STEP_LOG_CAP records {frames of the step, frames handed out so far, 100 MHz clock
+                                    // at the step's end, 0}, or null (statistics level 2)
   uint32_t* free_ring;              // per machine `part` frame ids (see Ctrl::free_head); null: frames are kept until the call ends
   uint32_t reclaim;                 // 1: a frame is given back once its tag has finished (Section 5.1: Return_i deallocates)
   uint32_t cap, n_inst, max_tags;   // cap = n_dies * part
@@ -142,6 +145,7 @@ inline __host__ __device__ Engine die_view(const Engine& e, uint32_t d) {
   v.key_base = d * e.part;
   v.touched = e.touched + (size_t)d * 2 * e.touched_cap;
   v.free_ring = e.free_ring ? e.free_ring + (size_t)d * e.part : nullptr;
+  v.step_log = e.step_log ? e.step_log + (size_t)d * STEP_LOG_CAP : nullptr;
   const size_t o = (size_t)d * e.log_cap;
   v.leaf_row = e.m_leaf_row + o;
   v.leaf_tok = e.m_leaf_tok + o;

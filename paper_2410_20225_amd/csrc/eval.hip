@@ -180,6 +180,8 @@ tdf_status make_plan(const Graph& G, const tdf_inputs* in, bool with_grad, char*
   e.frames = at(P.off_frames);
   e.touched = (uint32_t*)at(off_touched);
   e.free_ring = e.reclaim ? (uint32_t*)at(off_ring) : nullptr;
+  size_t off_slog = in->stats_level >= 2 ? L.take(sizeof(uint4) * STEP_LOG_CAP * (size_t)e.n_dies) : 0;
+  e.step_log = in->stats_level >= 2 ? (uint4*)at(off_slog) : nullptr;
   e.root_ref = (uint32_t*)at(off_root);
   e.head_row = (uint32_t*)at(off_hrow);
   e.head_label = (uint32_t*)at(off_hlab);
@@ -705,6 +707,35 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       if (phase_used[ph] && hipEventElapsedTime(&ms, (hipEvent_t)gr->events[2 * ph], (hipEvent_t)gr->events[2 * ph + 1]) == hipSuccess)
         stats->phase_ms[ph] = ms;
       stats->phase_launches[ph] = launches[ph];
+    }
+    if (phase_used[TDF_PHASE_CELLS_FWD]) {   // forward cell kernels on both streams: first launch to last end
+      float a = 0.f, b = 0.f;
+      (void)hipEventElapsedTime(&a, (hipEvent_t)gr->events[2 * TDF_PHASE_CELLS_FWD], (hipEvent_t)gr->events[2 * TDF_PHASE_CELLS_FWD + 1]);
+      if (phase_used[TDF_PHASE_TAIL_FWD] &&
+          hipEventElapsedTime(&b, (hipEvent_t)gr->events[2 * TDF_PHASE_CELLS_FWD], (hipEvent_t)gr->events[2 * TDF_PHASE_TAIL_FWD + 1]) != hipSuccess)
+        b = 0.f;
+      stats->fwd_cells_span_ms = std::max(a, b);
+    }
+    if (e.step_log && !no_alloc && dev == TDF_OK) {
+      // the widest steps of the tag machines: frames, frames created, duration
+      std::vector<uint4> log((size_t)STEP_LOG_CAP * e.n_dies);
+      HIP_TRY(hipMemcpy(log.data(), e.step_log, log.size() * sizeof(uint4), hipMemcpyDeviceToHost));
+      struct Rec { uint32_t frames, created; double us; };
+      std::vector<Rec> recs;
+      const Ctrl* hcs2 = (const Ctrl*)((char*)gr->pinned + PIN_CTRL);
+      for (uint32_t d = 0; d < e.n_dies; ++d) {
+        const uint32_t n_steps = std::min<uint32_t>(hcs2[d].step, STEP_LOG_CAP);
+        for (uint32_t k = 1; k < n_steps; ++k) {
+          const uint4 &a = log[(size_t)d * STEP_LOG_CAP + k - 1], &b = log[(size_t)d * STEP_LOG_CAP + k];
+          recs.push_back(Rec{b.x, b.y - a.y, (double)(uint32_t)(b.z - a.z) / 100.0});
+        }
+      }
+      std::sort(recs.begin(), recs.end(), [](const Rec& x, const Rec& y) { return x.frames > y.frames; });
+      for (size_t k = 0; k < recs.size() && k < 8; ++k) {
+        stats->wide_step_frames[k] = recs[k].frames;
+        stats->wide_step_created[k] = recs[k].created;
+        stats->wide_step_us[k] = recs[k].us;
+      }
     }
     stats->device_status = -(int32_t)hc.status;
     stats->n_counts = (int32_t)G.snodes.size();

@@ -813,6 +813,8 @@ __device__ inline void advance(const Engine& e, Ctrl* c, uint32_t step) {
     st(&c->prev_count, n);
     if (n > ld(&c->peak_count)) st(&c->peak_count, n);
   }
+  if (e.step_log && step < STEP_LOG_CAP)
+    e.step_log[step] = make_uint4(ld(&c->touched_count[parity]), ld(&c->n_alloc), (uint32_t)wall_clock64(), 0u);
   st(&c->touched_count[parity], 0u);
   st(&c->step, step + 1);
   if (e.reclaim) {

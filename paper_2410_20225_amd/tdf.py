@@ -91,6 +91,8 @@ class Stats(C.Structure):
                 ("n_grad_firings", C.c_int64), ("n_grad_not_once", C.c_int64),
                 ("max_tag_depth", C.c_int64), ("table_capacity", C.c_int64),
                 ("max_probe", C.c_int64), ("peak_frames", C.c_int64), ("frames_reclaimed", C.c_int64), ("phase_ms", C.c_double * len(PHASES)), ("phase_launches", C.c_int64 * len(PHASES)),
+                ("fwd_cells_span_ms", C.c_double), ("wide_step_frames", C.c_int64 * 8), ("wide_step_created", C.c_int64 * 8),
+                ("wide_step_us", C.c_double * 8),
                 ("device_status", C.c_int32), ("n_counts", C.c_int32),
                 ("n_machines", C.c_int32), ("die_local", C.c_int32), ("generated", C.c_int32),
                 ("repeats", C.c_int32), ("tail_used", C.c_int32), ("deep_split", C.c_int32),

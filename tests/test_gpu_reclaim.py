@@ -99,7 +99,7 @@ def test_frames_given_back_in_every_kind_of_scope(name):
     gpu_prog, oracle_prog, args = cases[name]
     n_args = len(args[0])
     it = oracle.Interpreter(oracle.transform(oracle_prog()))
-    want = it.run({("in", k): [a[k] for a in args] for k in range(n_args)}, len(args), track_live=True)[("out", 0)]
+    want = it.run({("in", k): [a[k] for a in args] for k in range(n_args)}, len(args))[("out", 0)]
     total = len(it.tags) + len(it.iter_tags)
     fns, r = gpu_prog()
     st, kept, out_kept = _run(fns, r, args, n_args, total + 8, stats_level=1)
