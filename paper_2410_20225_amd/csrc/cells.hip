@@ -1684,9 +1684,11 @@ void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW
   else weight_grads_t<float>(v, e, n_q, dW, db, db_part, s);
 }
 
-void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t* count, uint32_t* seg_off,
-                    uint32_t* chunk_off, uint32_t* fill, uint32_t* sorted_row, float* part, float* dE,
-                    uint32_t chunk, hipStream_t s) {
+// The embedding gradient in two steps.  vec_embed_sort orders the leaves by token (a counting
+// sort of the leaf log): it needs the leaf log only, so it can run beside the cells.  vec_embed_sums
+// adds the leaves' state gradients token by token in that order, once the gradient pass is done.
+void vec_embed_sort(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t* count, uint32_t* seg_off,
+                    uint32_t* chunk_off, uint32_t* fill, uint32_t* sorted_row, uint32_t chunk, hipStream_t s) {
   int g = (int)std::min<uint32_t>((n_leaf + 255) / 256, 2048u);
   if (g < 1) g = 1;
   if (bucket_fits((uint32_t)v.vocab)) {
@@ -1703,6 +1705,9 @@ void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t
     hipLaunchKernelGGL(k_tok_scan, dim3(1), dim3(1024), 0, s, count, seg_off, chunk_off, v.vocab, chunk);
     hipLaunchKernelGGL(k_tok_scatter, dim3(g), dim3(256), 0, s, e, n_leaf, seg_off, fill, sorted_row, v.vocab);
   }
+}
+void vec_embed_sums(const VecArgs& v, uint32_t n_leaf, const uint32_t* seg_off, const uint32_t* chunk_off,
+                    const uint32_t* sorted_row, float* part, float* dE, uint32_t chunk, hipStream_t s) {
   const uint32_t max_chunks = n_leaf / chunk + std::min<uint32_t>((uint32_t)v.vocab, n_leaf) + 1;
   hipLaunchKernelGGL(k_de_partial, dim3(std::min<uint32_t>((max_chunks + 3) / 4, 16384u)), dim3(256), 0, s, v, seg_off,
                      chunk_off, sorted_row, chunk, part);

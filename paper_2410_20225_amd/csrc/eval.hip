@@ -42,9 +42,10 @@ void vec_count_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t
 void vec_out_rows(const VecArgs& v, const Engine& e, float* out_h, float* out_c, hipStream_t s);
 int vec_dw_splits(uint32_t q_stride, int Np, int Kp);
 void vec_weight_grads(const VecArgs& v, const Engine& e, uint32_t n_q, float* dW, float* db, float* db_part, hipStream_t s);
-void vec_embed_grad(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t* count, uint32_t* seg_off,
-                    uint32_t* chunk_off, uint32_t* fill, uint32_t* sorted_row, float* part, float* dE,
-                    uint32_t chunk, hipStream_t s);
+void vec_embed_sort(const VecArgs& v, const Engine& e, uint32_t n_leaf, uint32_t* count, uint32_t* seg_off,
+                    uint32_t* chunk_off, uint32_t* fill, uint32_t* sorted_row, uint32_t chunk, hipStream_t s);
+void vec_embed_sums(const VecArgs& v, uint32_t n_leaf, const uint32_t* seg_off, const uint32_t* chunk_off,
+                    const uint32_t* sorted_row, float* part, float* dE, uint32_t chunk, hipStream_t s);
 
 namespace {
 
@@ -398,7 +399,13 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   }
   const bool use_jit = gr->jit.step && gr->jit.small && gr->jit.step_local;
   const int small_block = tag_machine_small_block(G.prog, use_jit);
+#ifdef TDF_TEST_HOOKS
+  // Only the build for the tests has this: 1 = the host treats the machines' kernels as having left
+  // their dies (once per graph), 2 = the level tail's launches.  The reaction is the product's own.
   const int test_mixed_dies = getenv("TDF_TEST_MIXED_DIES") ? atoi(getenv("TDF_TEST_MIXED_DIES")) : 0;
+#else
+  constexpr int test_mixed_dies = 0;
+#endif
   Ctrl hc{};
   uint32_t rounds = 0, repeats = 0;
   const uint32_t poll = 2;          // rounds queued between two looks at the control blocks
@@ -461,7 +468,6 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     // A die-local machine relies on its workgroups sharing one L2.  If the GPU placed them on
     // several dies, the run is void: repeat it with the kernel that synchronises through memory.
-    // (TDF_TEST_MIXED_DIES=1 makes the host take this way once per graph, for the tests.)
     if (gr->die_local && (mixed_dies || test_mixed_dies == 1)) {
       gr->die_local = false;
       ++repeats;
@@ -494,16 +500,27 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     e.row0 = hc.n_leaf;   // leaf i has row i, the cell at position q of the sorted log row n_leaf + q
     if (!gr->side_stream && with_grad && !no_alloc) {
       HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
-      for (void** ev : {&gr->fork_event, &gr->join_event, &gr->fork_deep, &gr->join_deep})
+      HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->sort_stream, hipStreamNonBlocking));
+      for (void** ev : {&gr->fork_event, &gr->join_event, &gr->fork_deep, &gr->join_deep, &gr->fork_sort, &gr->join_sort})
         HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)ev, hipEventDisableTiming));
     }
-    hipStream_t s2 = (hipStream_t)gr->side_stream;
+    hipStream_t s2 = (hipStream_t)gr->side_stream, s3 = (hipStream_t)gr->sort_stream;
     auto begin2 = [&](int ph) { if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * ph], s2); phase_used[ph] = true; } };
     auto end2 = [&](int ph, int64_t n) { if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * ph + 1], s2); launches[ph] += n; };
     begin(TDF_PHASE_LEAVES);
     if (G.cell_kind) vec_pack_w(v, s);   // (a program of EMBEDs alone has no W: the pointers may be NULL)
     vec_embed(v, e, hc.n_leaf, s);
     end(TDF_PHASE_LEAVES, 2);
+    if (with_grad) {
+      // the embedding gradient's token sort needs the leaf log only: it runs beside everything up to the
+      // gradient pass's end, on a stream of its own
+      HIP_TRY(hipEventRecord((hipEvent_t)gr->fork_sort, s));
+      HIP_TRY(hipStreamWaitEvent(s3, (hipEvent_t)gr->fork_sort, 0));
+      vec_embed_sort(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
+                     (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
+                     (uint32_t*)(base + P.off_sorted), DE_CHUNK, s3);
+      HIP_TRY(hipEventRecord((hipEvent_t)gr->join_sort, s3));
+    }
     // Instances never exchange values, so instances whose recursion is deep (long chains: many
     // levels of a few cells each, bound by latency) can run beside the others (few levels of many
     // cells each, bound by throughput) instead of after them.  An instance is deep if its root's
@@ -627,10 +644,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       // each other: the former runs on a second stream beside the latter.
       HIP_TRY(hipEventRecord((hipEvent_t)gr->fork_event, s));
       HIP_TRY(hipStreamWaitEvent(s2, (hipEvent_t)gr->fork_event, 0));
+      HIP_TRY(hipStreamWaitEvent(s2, (hipEvent_t)gr->join_sort, 0));   // the leaves are in token order
       if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * TDF_PHASE_EMBED_GRAD], s2); phase_used[TDF_PHASE_EMBED_GRAD] = true; }
-      vec_embed_grad(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
-                     (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
-                     (uint32_t*)(base + P.off_sorted), (float*)(base + P.off_de_part), grads->dE, DE_CHUNK, s2);
+      vec_embed_sums(v, hc.n_leaf, (const uint32_t*)(base + P.off_seg_off), (const uint32_t*)(base + P.off_chunk_off),
+                     (const uint32_t*)(base + P.off_sorted), (float*)(base + P.off_de_part), grads->dE, DE_CHUNK, s2);
       if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * TDF_PHASE_EMBED_GRAD + 1], s2);
       launches[TDF_PHASE_EMBED_GRAD] += 5;
       HIP_TRY(hipEventRecord((hipEvent_t)gr->join_event, s2));
@@ -658,7 +675,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         mixed = mixed || (d.xcc_mask & (d.xcc_mask - 1)) != 0;
         gave_up = gave_up || d.abort != 0;
       }
-      mixed = mixed || test_mixed_dies == 2;   // TDF_TEST_MIXED_DIES=2: the tail launches' way, for the tests
+      mixed = mixed || test_mixed_dies == 2;
       if (gave_up && !mixed) {
         set_error("device: a workgroup waited too long at a die barrier of the level tail");
         return TDF_ERR_DEVICE;
@@ -756,11 +773,12 @@ tdf_graph::~tdf_graph() {
   jit_release(jit);
   for (void* ev : events)
     if (ev) (void)hipEventDestroy((hipEvent_t)ev);
-  if (side_stream) {
-    (void)hipStreamSynchronize((hipStream_t)side_stream);
-    (void)hipStreamDestroy((hipStream_t)side_stream);
-  }
-  for (void* ev : {fork_event, join_event, fork_deep, join_deep})
+  for (void* st : {side_stream, sort_stream})
+    if (st) {
+      (void)hipStreamSynchronize((hipStream_t)st);
+      (void)hipStreamDestroy((hipStream_t)st);
+    }
+  for (void* ev : {fork_event, join_event, fork_deep, join_deep, fork_sort, join_sort})
     if (ev) (void)hipEventDestroy((hipEvent_t)ev);
   if (pinned) (void)hipHostFree(pinned);
 }

@@ -48,6 +48,8 @@ struct tdf_graph {
   void* side_stream = nullptr;                     // hipStream_t for work beside the caller's stream
   void* fork_event = nullptr, *join_event = nullptr;   // embedding gradient beside the weight gradients
   void* fork_deep = nullptr, *join_deep = nullptr;     // deep instances beside the others
+  void* sort_stream = nullptr;                     // hipStream_t for the embedding gradient's token sort
+  void* fork_sort = nullptr, *join_sort = nullptr;     // ... which starts once the leaves are known
   // pinned host memory for what an evaluation reads back or sends (control blocks, level offsets,
   // barrier records, the firing tables): copies to and from pageable memory are staged and slower
   void* pinned = nullptr;

@@ -99,29 +99,57 @@ class Stats(C.Structure):
                 ("fire_count", C.c_int64 * STATS_MAX_COUNTS)]
 
 
-lib.tdf_graph_build.argtypes = [C.POINTER(ProgramDesc), C.c_int, C.POINTER(C.c_void_p)]
-lib.tdf_graph_build.restype = C.c_int
-lib.tdf_graph_destroy.argtypes = [C.c_void_p]
-lib.tdf_graph_destroy.restype = None
-lib.tdf_graph_info.argtypes = [C.c_void_p, C.POINTER(GraphInfo)]
-lib.tdf_graph_info.restype = C.c_int
-lib.tdf_graph_precompile.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_size_t)]
-lib.tdf_graph_precompile.restype = C.c_int
-lib.tdf_workspace_size.argtypes = [C.c_void_p, C.POINTER(Inputs), C.c_int, C.POINTER(C.c_size_t)]
-lib.tdf_workspace_size.restype = C.c_int
-lib.tdf_eval.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Outputs), C.c_void_p, C.c_size_t,
-                         C.c_void_p, C.POINTER(Stats)]
-lib.tdf_eval.restype = C.c_int
-lib.tdf_eval_grad.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Seed), C.POINTER(Outputs),
-                              C.POINTER(Grads), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(Stats)]
-lib.tdf_eval_grad.restype = C.c_int
-lib.tdf_graph_prepare.argtypes = [C.c_void_p]
-lib.tdf_graph_prepare.restype = C.c_int
-lib.tdf_eval_static.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Outputs), C.c_void_p, C.POINTER(Stats)]
-lib.tdf_eval_static.restype = C.c_int
+def _declare(l):
+    """Argument and result types of every entry point of a loaded library."""
+    l.tdf_graph_build.argtypes = [C.POINTER(ProgramDesc), C.c_int, C.POINTER(C.c_void_p)]
+    l.tdf_graph_build.restype = C.c_int
+    l.tdf_graph_destroy.argtypes = [C.c_void_p]
+    l.tdf_graph_destroy.restype = None
+    l.tdf_graph_info.argtypes = [C.c_void_p, C.POINTER(GraphInfo)]
+    l.tdf_graph_info.restype = C.c_int
+    l.tdf_graph_precompile.argtypes = [C.c_void_p, C.c_char_p, C.POINTER(C.c_size_t)]
+    l.tdf_graph_precompile.restype = C.c_int
+    l.tdf_workspace_size.argtypes = [C.c_void_p, C.POINTER(Inputs), C.c_int, C.POINTER(C.c_size_t)]
+    l.tdf_workspace_size.restype = C.c_int
+    l.tdf_eval.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Outputs), C.c_void_p, C.c_size_t,
+                             C.c_void_p, C.POINTER(Stats)]
+    l.tdf_eval.restype = C.c_int
+    l.tdf_eval_grad.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Seed), C.POINTER(Outputs),
+                                  C.POINTER(Grads), C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(Stats)]
+    l.tdf_eval_grad.restype = C.c_int
+    l.tdf_graph_prepare.argtypes = [C.c_void_p]
+    l.tdf_graph_prepare.restype = C.c_int
+    l.tdf_eval_static.argtypes = [C.c_void_p, C.POINTER(Inputs), C.POINTER(Outputs), C.c_void_p, C.POINTER(Stats)]
+    l.tdf_eval_static.restype = C.c_int
+    l.tdf_last_error.argtypes = []
+    l.tdf_last_error.restype = C.c_char_p
+    return l
+
+
+def load_library(path):
+    """Another build of the library (the tests load the one with the test hooks compiled in); a graph
+    built while it is current (use_library) keeps calling it."""
+    return _declare(C.CDLL(path))
+
+
+class use_library:
+    """with use_library(l): graph_build and last_error go to `l` instead of the default library."""
+
+    def __init__(self, l):
+        self.l = l
+
+    def __enter__(self):
+        global lib
+        self.prev, lib = lib, self.l
+        return self.l
+
+    def __exit__(self, *exc):
+        global lib
+        lib = self.prev
+
+
+_declare(lib)
 STATIC_WORKSPACE_BYTES = 64 << 20
-lib.tdf_last_error.argtypes = []
-lib.tdf_last_error.restype = C.c_char_p
 
 
 class TdfError(RuntimeError):
@@ -143,12 +171,13 @@ def _ptr(t):
 class Graph:
     """Owns a tdf_graph*; destroyed with the object."""
 
-    def __init__(self, handle):
+    def __init__(self, handle, library):
         self.handle = handle
+        self.lib = library      # the library that built the graph serves every later call on it
 
     def __del__(self):
-        if getattr(self, "handle", None) and lib is not None:   # lib is None at interpreter shutdown
-            lib.tdf_graph_destroy(self.handle)
+        if getattr(self, "handle", None) and getattr(self, "lib", None) is not None and C is not None:
+            self.lib.tdf_graph_destroy(self.handle)
             self.handle = None
 
 
@@ -170,12 +199,12 @@ def graph_build(functions, result_fn, want_grad=False):
     st = lib.tdf_graph_build(C.byref(prog), int(bool(want_grad)), C.byref(handle))
     if st != OK:
         raise TdfError(st, "tdf_graph_build")
-    return Graph(handle)
+    return Graph(handle, lib)
 
 
 def graph_info(graph):
     info = GraphInfo()
-    st = lib.tdf_graph_info(graph.handle, C.byref(info))
+    st = graph.lib.tdf_graph_info(graph.handle, C.byref(info))
     if st != OK:
         raise TdfError(st, "tdf_graph_info")
     nodes = [dict(kind=n.kind, fn=n.fn, label=n.label, param=n.param, is_grad=n.is_grad, imm=n.imm)
@@ -188,7 +217,7 @@ def graph_info(graph):
 def graph_precompile(graph, arch="gfx950"):
     """Compiles the specialised step kernels of `graph` for `arch`; returns the code size in bytes."""
     n = C.c_size_t()
-    st = lib.tdf_graph_precompile(graph.handle, arch.encode(), C.byref(n))
+    st = graph.lib.tdf_graph_precompile(graph.handle, arch.encode(), C.byref(n))
     if st != OK:
         raise TdfError(st, "tdf_graph_precompile")
     return n.value
@@ -204,7 +233,7 @@ def make_inputs(n_instances, args=None, n_args=0, left=None, right=None, token=N
 
 def workspace_size(graph, inputs, with_grad=False):
     n = C.c_size_t()
-    st = lib.tdf_workspace_size(graph.handle, C.byref(inputs), int(bool(with_grad)), C.byref(n))
+    st = graph.lib.tdf_workspace_size(graph.handle, C.byref(inputs), int(bool(with_grad)), C.byref(n))
     if st != OK:
         raise TdfError(st, "tdf_workspace_size")
     return n.value
@@ -218,7 +247,7 @@ def eval(graph, inputs, workspace, out_i64=None, out_f32=None, out_h=None, out_c
     """Returns (status, Stats)."""
     outs = Outputs(_ptr(out_i64), _ptr(out_f32), _ptr(out_h), _ptr(out_c), _ptr(out_node_loss))
     stats = Stats()
-    st = lib.tdf_eval(graph.handle, C.byref(inputs), C.byref(outs), _ptr(workspace),
+    st = graph.lib.tdf_eval(graph.handle, C.byref(inputs), C.byref(outs), _ptr(workspace),
                       workspace.numel() * workspace.element_size(), _stream(), C.byref(stats))
     if check and st != OK:
         raise TdfError(st, "tdf_eval")
@@ -226,7 +255,7 @@ def eval(graph, inputs, workspace, out_i64=None, out_f32=None, out_h=None, out_c
 
 
 def graph_prepare(graph):
-    st = lib.tdf_graph_prepare(graph.handle)
+    st = graph.lib.tdf_graph_prepare(graph.handle)
     if st != OK:
         raise TdfError(st, "tdf_graph_prepare")
 
@@ -235,7 +264,7 @@ def eval_static(graph, inputs, out_i64=None, out_f32=None, out_h=None, out_c=Non
     """tdf_eval in the library's static workspace (no allocation).  Returns (status, Stats)."""
     outs = Outputs(_ptr(out_i64), _ptr(out_f32), _ptr(out_h), _ptr(out_c), _ptr(out_node_loss))
     stats = Stats()
-    st = lib.tdf_eval_static(graph.handle, C.byref(inputs), C.byref(outs), _stream(), C.byref(stats))
+    st = graph.lib.tdf_eval_static(graph.handle, C.byref(inputs), C.byref(outs), _stream(), C.byref(stats))
     if check and st != OK:
         raise TdfError(st, "tdf_eval_static")
     return st, stats
@@ -247,7 +276,7 @@ def eval_grad(graph, inputs, dy, workspace, dW, db, dE, out_f32=None, out_h=None
     seed = Seed(_ptr(dy), _ptr(dnode))
     grads = Grads(_ptr(dW), _ptr(db), _ptr(dE))
     stats = Stats()
-    st = lib.tdf_eval_grad(graph.handle, C.byref(inputs), C.byref(seed), C.byref(outs), C.byref(grads),
+    st = graph.lib.tdf_eval_grad(graph.handle, C.byref(inputs), C.byref(seed), C.byref(outs), C.byref(grads),
                            _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(),
                            C.byref(stats))
     if check and st != OK:

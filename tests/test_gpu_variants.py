@@ -3,7 +3,8 @@ the table interpreter instead of generated step kernels, grid-wide steps synchro
 memory instead of one die's L2, every level through the tiled GEMM or through the small-level
 kernel, every step through the grid-wide kernel (on eight machines and on one) or through the
 single-workgroup kernel, the repetition of a run whose die-private kernels did not keep to their
-dies (the host is told they did not), and steps in which no lane goes on with the frame it
+dies (the host is told they did not: that switch exists only in the library's build for the tests,
+libtdf_hooks.so, which these two cases load), and steps in which no lane goes on with the frame it
 created.  Every case asserts through tdf_stats that the requested path is the one that ran.  Same
 bars as the main parity tests: integers and counts bit-exact, bf16 within rel 2e-2 (Frobenius)."""
 import numpy as np
@@ -38,12 +39,24 @@ def lstm_case():
     return c, dy, run_oracle_tree(c, head=True, grad=True, dy=dy)
 
 
+@pytest.fixture(scope="module")
+def hooks_library():
+    import os
+    path = os.path.join(os.path.dirname(tdf.__file__), "libtdf_hooks.so")
+    assert os.path.exists(path), "libtdf_hooks.so is not built: run `python -m paper_2410_20225_amd.build`"
+    return tdf.load_library(path)
+
+
 @pytest.mark.parametrize("env", VARIANTS, ids=IDS)
-def test_treelstm_variants(env, lstm_case, monkeypatch):
+def test_treelstm_variants(env, lstm_case, hooks_library, monkeypatch):
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     c, dy, ref = lstm_case
-    run = TreeRun(c, head=True, grad=True)          # a fresh graph: the switches are read per graph / per call
+    if "TDF_TEST_MIXED_DIES" in env:
+        with tdf.use_library(hooks_library):
+            run = TreeRun(c, head=True, grad=True)
+    else:
+        run = TreeRun(c, head=True, grad=True)      # a fresh graph: the switches are read per graph / per call
     st, stats = run.run(dy)
     assert stats.n_tags == c["forest"].n_nodes == len(ref["it"].tags)
     assert stats.max_tag_depth == ref["it"].max_tag_len

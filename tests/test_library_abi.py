@@ -22,6 +22,14 @@ def test_every_declared_symbol_is_exported():
         assert hasattr(tdf.lib, n), n
 
 
+def test_the_product_library_has_no_test_hook():
+    """The switch that makes the host pretend its die-private kernels left their dies exists in the
+    tests' build of the library only."""
+    here = os.path.dirname(tdf.__file__)
+    assert b"TDF_TEST_MIXED_DIES" not in open(os.path.join(here, "libtdf.so"), "rb").read()
+    assert b"TDF_TEST_MIXED_DIES" in open(os.path.join(here, "libtdf_hooks.so"), "rb").read()
+
+
 _NAMES = {tdf.OP_EQ: "=", tdf.OP_SWITCH: "Switch", tdf.OP_SUB: "-", tdf.OP_MUL: "*", tdf.OP_ADD: "+",
           tdf.OP_ID: "id", tdf.OP_MERGE: "Merge", tdf.SNODE_MERGE_ENTRY: "Merge", tdf.OP_OUT: "out"}
 
