@@ -97,6 +97,7 @@ struct GemmArgs {
   const float* bias;
   void* Hs_out;              // state rows written by the forward cells
   float* Cs;                 // LSTM cell state rows
+  uint32_t leaf_rows;        // rows below this one are leaves: their cell state is zero and is not stored
   void* gates;               // LSTM activations, row m of this level
   size_t ldg;
   float* C;                  // fp32 output (DX_BWD: dH; DW_SPLIT: partial tiles)
@@ -272,8 +273,8 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = row_of(i, r);
-          cl[r] = g.Cs[(size_t)sL[row] * g.Hp + n];
-          cr[r] = g.Cs[(size_t)sR[row] * g.Hp + n];
+          cl[r] = sL[row] >= g.leaf_rows ? g.Cs[(size_t)sL[row] * g.Hp + n] : 0.f;
+          cr[r] = sR[row] >= g.leaf_rows ? g.Cs[(size_t)sR[row] * g.Hp + n] : 0.f;
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -497,8 +498,8 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
   if (MODE == LSTM_FWD) {
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
-      cl[rr] = g.Cs[(size_t)o_l[rr] * g.Hp + unit];
-      cr[rr] = g.Cs[(size_t)o_r[rr] * g.Hp + unit];
+      cl[rr] = o_l[rr] >= g.leaf_rows ? g.Cs[(size_t)o_l[rr] * g.Hp + unit] : 0.f;
+      cr[rr] = o_r[rr] >= g.leaf_rows ? g.Cs[(size_t)o_r[rr] * g.Hp + unit] : 0.f;
     }
   }
 
@@ -639,8 +640,8 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
       if (v.cell_kind == 2) {
 #pragma unroll
         for (int rr = 0; rr < RPW; ++rr) {
-          z_cl[rr] = v.Cs[(size_t)z_gl[rr] * v.Hp + z_n];
-          z_cr[rr] = v.Cs[(size_t)z_gr[rr] * v.Hp + z_n];
+          z_cl[rr] = z_gl[rr] >= fz->row0 ? v.Cs[(size_t)z_gl[rr] * v.Hp + z_n] : 0.f;   // (a leaf's cell state is zero)
+          z_cr[rr] = z_gr[rr] >= fz->row0 ? v.Cs[(size_t)z_gr[rr] * v.Hp + z_n] : 0.f;
         }
       }
 #pragma unroll
@@ -661,8 +662,8 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
           dz[2 * v.Hp] = from_f<T>(dc * z_cr[rr] * gfr * (1.f - gfr));
           dz[3 * v.Hp] = from_f<T>(dh * tc * go * (1.f - go));
           dz[4 * v.Hp] = from_f<T>(dc * gi * (1.f - gu * gu));
-          v.dC[(size_t)z_gl[rr] * v.Hp + z_n] = dc * gfl;
-          v.dC[(size_t)z_gr[rr] * v.Hp + z_n] = dc * gfr;
+          if (z_gl[rr] >= fz->row0) v.dC[(size_t)z_gl[rr] * v.Hp + z_n] = dc * gfl;   // (a leaf has no use for dc)
+          if (z_gr[rr] >= fz->row0) v.dC[(size_t)z_gr[rr] * v.Hp + z_n] = dc * gfr;
         }
       }
     }
@@ -742,8 +743,6 @@ __global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
     const T* src = reinterpret_cast<const T*>(v.E) + (size_t)(tok < (uint32_t)v.vocab ? tok : 0) * v.H;
     T* dst = reinterpret_cast<T*>(v.Hs) + (size_t)row * v.Hp;
     for (int n = lane; n < v.Hp; n += 64) dst[n] = n < v.H ? src[n] : from_f<T>(0.f);
-    if (v.cell_kind == 2)
-      for (int n = lane; n < v.Hp; n += 64) v.Cs[(size_t)row * v.Hp + n] = 0.f;
   }
 }
 
@@ -899,7 +898,7 @@ __global__ void k_out_rows(VecArgs v, Engine e, float* out_h, float* out_c) {
   const uint32_t row = e.root_ref[b];
   for (int n = threadIdx.x; n < v.H; n += blockDim.x) {
     if (out_h) out_h[(size_t)b * v.H + n] = to_f(reinterpret_cast<const T*>(v.Hs)[(size_t)row * v.Hp + n]);
-    if (out_c && v.cell_kind == 2) out_c[(size_t)b * v.H + n] = v.Cs[(size_t)row * v.Hp + n];
+    if (out_c && v.cell_kind == 2) out_c[(size_t)b * v.H + n] = row >= e.row0 ? v.Cs[(size_t)row * v.Hp + n] : 0.f;
   }
 }
 
@@ -918,6 +917,7 @@ __device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32
       dz[n] = from_f<T>((v.dH[o + n] + (v.dHn ? v.dHn[o + n] : 0.f)) * (1.f - h * h));
     }
   } else {
+    const bool cell_l = e.q_l[q] >= e.row0, cell_r = e.q_r[q] >= e.row0;   // a leaf child: c = 0, no use for dc
     const size_t ol = (size_t)e.q_l[q] * v.Hp, orr = (size_t)e.q_r[q] * v.Hp;
     const T* gt = reinterpret_cast<const T*>(v.gates) + (size_t)q * v.Np;
     for (int n = threadIdx.x; n < v.Hp; n += blockDim.x) {
@@ -926,14 +926,14 @@ __device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32
       const float tc = Act<T>::tanh(v.Cs[o + n]);
       const float dh = v.dH[o + n] + (v.dHn ? v.dHn[o + n] : 0.f);
       const float dc = v.dC[o + n] + dh * go * (1.f - tc * tc);
-      const float cl = v.Cs[ol + n], cr = v.Cs[orr + n];
+      const float cl = cell_l ? v.Cs[ol + n] : 0.f, cr = cell_r ? v.Cs[orr + n] : 0.f;
       dz[n] = from_f<T>(dc * gu * gi * (1.f - gi));
       dz[v.Hp + n] = from_f<T>(dc * cl * gfl * (1.f - gfl));
       dz[2 * v.Hp + n] = from_f<T>(dc * cr * gfr * (1.f - gfr));
       dz[3 * v.Hp + n] = from_f<T>(dh * tc * go * (1.f - go));
       dz[4 * v.Hp + n] = from_f<T>(dc * gi * (1.f - gu * gu));
-      v.dC[ol + n] = dc * gfl;
-      v.dC[orr + n] = dc * gfr;
+      if (cell_l) v.dC[ol + n] = dc * gfl;
+      if (cell_r) v.dC[orr + n] = dc * gfr;
     }
   }
 }
@@ -1489,7 +1489,7 @@ template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, 
   g.B = v.Wp; g.ldb = v.Kp; g.Bf = v.Wf;
   g.Hs = v.Hs; g.Hp = v.Hp;
   g.out0 = e.row0 + q0; g.l = e.q_l + q0; g.r = e.q_r + q0;
-  g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
+  g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs; g.leaf_rows = e.row0;
   g.gates = v.gates ? reinterpret_cast<T*>(v.gates) + (size_t)q0 * v.Np : nullptr;
   g.ldg = v.Np; g.save_gates = save_gates && v.gates;
   if (count <= small_level()) {
@@ -1533,7 +1533,7 @@ template <typename T> static void tail_fwd_t(const VecArgs& v, const Engine& e, 
   g.B = v.Wp; g.ldb = v.Kp; g.Bf = v.Wf;
   g.Hs = v.Hs; g.Hp = v.Hp;
   g.out0 = e.row0; g.l = e.q_l; g.r = e.q_r;
-  g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs;
+  g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs; g.leaf_rows = e.row0;
   g.gates = v.gates; g.ldg = v.Np; g.save_gates = save_gates && v.gates;
   g.n_tiles_n = v.Hp / 32;
   const int grid = std::max(per_die, 1) * (int)XCDS;

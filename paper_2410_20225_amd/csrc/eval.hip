@@ -501,7 +501,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (!gr->side_stream && with_grad && !no_alloc) {
       HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
       HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->sort_stream, hipStreamNonBlocking));
-      for (void** ev : {&gr->fork_event, &gr->join_event, &gr->fork_deep, &gr->join_deep, &gr->fork_sort, &gr->join_sort})
+      for (void** ev : {&gr->fork_event, &gr->join_event, &gr->fork_deep, &gr->join_deep, &gr->fork_sort, &gr->join_sort, &gr->leaves_done})
         HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)ev, hipEventDisableTiming));
     }
     hipStream_t s2 = (hipStream_t)gr->side_stream, s3 = (hipStream_t)gr->sort_stream;
@@ -509,13 +509,16 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     auto end2 = [&](int ph, int64_t n) { if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * ph + 1], s2); launches[ph] += n; };
     begin(TDF_PHASE_LEAVES);
     if (G.cell_kind) vec_pack_w(v, s);   // (a program of EMBEDs alone has no W: the pointers may be NULL)
-    vec_embed(v, e, hc.n_leaf, s);
+    if (!with_grad) vec_embed(v, e, hc.n_leaf, s);
     end(TDF_PHASE_LEAVES, 2);
     if (with_grad) {
-      // the embedding gradient's token sort needs the leaf log only: it runs beside everything up to the
-      // gradient pass's end, on a stream of its own
+      // Gradient runs have a third stream.  The leaves' rows do not wait for the level sort, nor it for
+      // them: they are written there, beside the sort on the caller's stream, and so is the embedding
+      // gradient's token sort, which needs the leaf log only and has until the gradient pass's end.
       HIP_TRY(hipEventRecord((hipEvent_t)gr->fork_sort, s));
       HIP_TRY(hipStreamWaitEvent(s3, (hipEvent_t)gr->fork_sort, 0));
+      vec_embed(v, e, hc.n_leaf, s3);
+      HIP_TRY(hipEventRecord((hipEvent_t)gr->leaves_done, s3));
       vec_embed_sort(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
                      (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
                      (uint32_t*)(base + P.off_sorted), DE_CHUNK, s3);
@@ -548,6 +551,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       HIP_TRY(hipMemcpyAsync((void*)level_off, e.level_off, level_bytes, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 6);
       HIP_TRY(hipStreamSynchronize(s));
+      if (with_grad) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->leaves_done, 0));   // the cells read the leaves' rows
       sh_last = want_deep ? std::min(hc.max_level, deep_level - 1) : hc.max_level;
       q_deep0 = want_deep ? level_off[deep_base] : hc.n_cell;   // the shallow instances' cells come first
       deep = want_deep && q_deep0 < hc.n_cell;
@@ -607,7 +611,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
         end(TDF_PHASE_TAIL_FWD, 1);
       }
     }
-    if (!hc.n_cell) vec_number_rows(e, hc.n_leaf, 0, G.has_head, G.out_type == T_VEC, s);   // leaves only
+    if (!hc.n_cell) {   // leaves only
+      vec_number_rows(e, hc.n_leaf, 0, G.has_head, G.out_type == T_VEC, s);
+      if (with_grad) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->leaves_done, 0));
+    }
     begin(TDF_PHASE_HEAD);
     if (G.has_head) {
       vec_head(v, e, with_grad ? dy->dy : nullptr, with_grad, deep ? 0 : -1, s);
@@ -650,6 +657,9 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
                      (const uint32_t*)(base + P.off_sorted), (float*)(base + P.off_de_part), grads->dE, DE_CHUNK, s2);
       if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * TDF_PHASE_EMBED_GRAD + 1], s2);
       launches[TDF_PHASE_EMBED_GRAD] += 5;
+      // how often each tag's gradient body fired, as the kernels marked it (the cells' marks are complete
+      // since the gradient pass, the leaves' since the sums just above)
+      vec_count_grad(v, e, hc.n_leaf, hc.n_cell, (unsigned long long*)(base + P.off_gcount), s2);
       HIP_TRY(hipEventRecord((hipEvent_t)gr->join_event, s2));
       begin(TDF_PHASE_WEIGHT_GRAD);
       if (hc.n_cell) {
@@ -661,8 +671,6 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       }
       end(TDF_PHASE_WEIGHT_GRAD, 7);
       HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->join_event, 0));
-      // how often each tag's gradient body fired, as the kernels marked it
-      vec_count_grad(v, e, hc.n_leaf, hc.n_cell, (unsigned long long*)(base + P.off_gcount), s);
     }
     HIP_TRY(hipGetLastError());
     const DieSync* ts = (const DieSync*)((char*)gr->pinned + PIN_SYNC);
@@ -778,7 +786,7 @@ tdf_graph::~tdf_graph() {
       (void)hipStreamSynchronize((hipStream_t)st);
       (void)hipStreamDestroy((hipStream_t)st);
     }
-  for (void* ev : {fork_event, join_event, fork_deep, join_deep, fork_sort, join_sort})
+  for (void* ev : {fork_event, join_event, fork_deep, join_deep, fork_sort, join_sort, leaves_done})
     if (ev) (void)hipEventDestroy((hipEvent_t)ev);
   if (pinned) (void)hipHostFree(pinned);
 }

@@ -50,6 +50,7 @@ struct tdf_graph {
   void* fork_deep = nullptr, *join_deep = nullptr;     // deep instances beside the others
   void* sort_stream = nullptr;                     // hipStream_t for the embedding gradient's token sort
   void* fork_sort = nullptr, *join_sort = nullptr;     // ... which starts once the leaves are known
+  void* leaves_done = nullptr;                     // the leaves' rows, written on that stream too
   // pinned host memory for what an evaluation reads back or sends (control blocks, level offsets,
   // barrier records, the firing tables): copies to and from pageable memory are staged and slower
   void* pinned = nullptr;
