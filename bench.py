@@ -26,8 +26,8 @@ COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 # profiles/bench_workload4_hbm_traffic.md), with the hash of the kernel source they were taken on:
 # reported as `traffic` only while that source is unchanged.
 MEASURED_TRAFFIC = {
-    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "15bb1d12068194bd", 2209341021.6),
-        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "0a784c590ea081b1", 366497769.0)},
+    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "303709f9efb4ec2b", 1899922849.6),
+        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "4280448b1f431a4f", 337804018.2)},
 }
 
 
@@ -107,6 +107,9 @@ def main():
                     help="workloads 3..5 with a loss term at every tree node instead of the root only")
     ap.add_argument("--scale", type=int, default=1,
                     help="workloads 2..5: this many times the workload's trees, same recipe (saturation sweep; the headline is --scale 1)")
+    ap.add_argument("--fib", type=str, default="",
+                    help="workload 1 with these arguments instead of 0..20, e.g. 30,31,32 (a large batch for the tag machine "
+                         "alone; frames are kept, as in the counter runs of the same batch)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle's sample (0 = auto)")
     a = ap.parse_args()
@@ -127,10 +130,15 @@ def main():
     if cfg == 1:
         fns, r = programs.fib()
         g = tdf.graph_build(fns, r)
-        args = torch.arange(0, 21, dtype=torch.int64, device=dev)
-        inp = tdf.make_inputs(21, args=args, n_args=1, max_tags=57291, stats_level=0)
+        ns = [int(x) for x in a.fib.split(",")] if a.fib else list(range(21))
+        fibs = [0, 1]
+        while len(fibs) < max(ns) + 2:
+            fibs.append(fibs[-1] + fibs[-2])
+        n_calls = sum(2 * fibs[n + 1] - 1 for n in ns)   # invocations of fib(n): 2 F(n+1) - 1
+        args = torch.tensor(ns, dtype=torch.int64, device=dev)
+        inp = tdf.make_inputs(len(ns), args=args, n_args=1, max_tags=n_calls, stats_level=1 if a.fib else 0)
         ws = torch.empty(tdf.workspace_size(g, inp), dtype=torch.uint8, device=dev)
-        out = torch.zeros(21, dtype=torch.int64, device=dev)
+        out = torch.zeros(len(ns), dtype=torch.int64, device=dev)
         step = lambda: tdf.eval(g, inp, ws, out_i64=out)[1]
         passes, dtype, flops_fwd, cell = 1, "int64", 0.0, None
     elif cfg == 6:
@@ -253,7 +261,12 @@ def main():
         # the LSTM, read; h, c and, in a gradient run, the five gate activations written)
         elt = 2 if dtype == "bf16" else 4
         H = c["H"]
-        cell_bytes = 3 * H * elt + (12 * H + (5 * H * elt if grad or a.node_loss else 0) if cell == "lstm" else 0)
+        # (a leaf has no cell state: c is read only for the children that are cells, and every cell but an
+        # instance's root is the child of exactly one cell)
+        F = c["forest"]
+        n_root_cells = int((F.left[F.roots] >= 0).sum())
+        c_read = 4.0 * H * max(n_cell - n_root_cells, 0) / max(n_cell, 1)
+        cell_bytes = 3 * H * elt + (4 * H + c_read + (5 * H * elt if grad or a.node_loss else 0) if cell == "lstm" else 0)
         roof["against_hbm"] = {"bytes_per_cell": cell_bytes, "flop_per_byte": per_cell / cell_bytes,
                                "machine_flop_per_byte": peak / PEAK_HBM,
                                "achieved": cell_bytes * n_cell / (ms * 1e-3) / 1e9, "peak": PEAK_HBM / 1e9, "unit": "GB/s",
@@ -267,7 +280,8 @@ def main():
     rec = {"metric": "tagged node firings/sec at 1 GPU", "value": value, "unit": "firings/s", "n_gpus": 1,
            "steps": a.steps, "warmup": a.warmup, "ms_per_step": 1e3 * dt / a.steps, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-           "config": {"workload": "config %d: %s%s" % (cfg, CONFIG_NAMES[cfg], ", a loss term at every node" if a.node_loss else ""),
+           "config": {"workload": "config %d: %s%s%s" % (cfg, CONFIG_NAMES[cfg], ", a loss term at every node" if a.node_loss else "",
+                                                        ", arguments %s" % a.fib if (cfg == 1 and a.fib) else ""),
                       "n_tags": n_tags,
                       "firings_per_step": firings, "n_steps_tag_machine": int(st.n_steps),
                       "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth), "scale": a.scale,
@@ -279,7 +293,7 @@ def main():
            "phase_ms": phase_ms, "roofline": roof}
     if cfg not in (1, 6):
         rec["roofline_tag_machine"] = roof_tags
-    if not a.no_cpu_baseline:
+    if not a.no_cpu_baseline and not (cfg == 1 and a.fib):   # (the oracle does not finish a batch of that size)
         trees = a.cpu_trees or {1: 0, 2: 256, 3: 1024, 4: 1024, 5: 2, 6: 2048}[cfg]
         rec["cpu_baseline"] = cpu_baseline(cfg, trees, a.node_loss)
     print(json.dumps(rec))

@@ -235,13 +235,15 @@ typedef struct {
 /* Phases of one evaluation, timed on the caller's stream with HIP events. */
 enum {
   TDF_PHASE_TAGS = 0,    /* tag machine: clear, seed, all match/fire steps                 */
-  TDF_PHASE_LEAVES,      /* weight packing and EMBED rows                                  */
+  TDF_PHASE_LEAVES,      /* weight packing and EMBED rows (gradient runs write the rows on
+                            a stream of their own, beside the level sort: outside this bracket) */
   TDF_PHASE_LEVELS,      /* bucketing of the cell firings by dependency level              */
   TDF_PHASE_CELLS_FWD,   /* cell GEMMs of the wide levels, one launch per level            */
   TDF_PHASE_HEAD,        /* head / result rows / gradient seeds                            */
   TDF_PHASE_CELLS_BWD,   /* gradient bodies of the cells of the wide levels, in reverse    */
   TDF_PHASE_WEIGHT_GRAD, /* dW, db                                                         */
-  TDF_PHASE_EMBED_GRAD,  /* dE (runs beside the weight gradients)                          */
+  TDF_PHASE_EMBED_GRAD,  /* dE: the per-token sums (beside the weight gradients; the token
+                            sort ran earlier, beside the cells)                            */
   TDF_PHASE_TAIL_FWD,    /* cells of the deep, narrow levels: one launch for all of them   */
   TDF_PHASE_TAIL_BWD,    /* ... and their gradient bodies                                  */
   TDF_PHASE_COUNT

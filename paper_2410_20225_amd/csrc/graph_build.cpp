@@ -184,6 +184,35 @@ struct Builder {
       }
     }
     if (G.has_head && G.has_node_loss) bad("CE_HEAD and CE_NODE in one program");
+    // A vector value is named by the frame (the tag) that produced it, so a tag may produce one: two
+    // operators that make state rows must lie on opposite sides of a Switch.  side[t][i]: the switches
+    // whose true (t = 0) / false (t = 1) output node i cannot be live without; a Merge is live with
+    // any one of its inputs and keeps only what all of them share.
+    for (int f = 0; f < nf; ++f) {
+      const auto& fn = F(f);
+      std::vector<uint64_t> side[2] = {std::vector<uint64_t>(fn.n_nodes, 0), std::vector<uint64_t>(fn.n_nodes, 0)};
+      std::vector<int> makers;
+      for (int i = 0; i < fn.n_nodes; ++i) {
+        const auto& nd = fn.nodes[i];
+        for (int t = 0; t < 2; ++t) {
+          uint64_t m = nd.op == TDF_OP_MERGE ? ~0ull : 0ull;
+          for (int k = 0; k < nd.n_in; ++k) {
+            const auto& r = nd.in[k];
+            uint64_t from = side[t][r.node];
+            if (fn.nodes[r.node].op == TDF_OP_SWITCH && r.port == t) from |= 1ull << r.node;
+            m = nd.op == TDF_OP_MERGE ? (m & from) : (m | from);
+          }
+          side[t][i] = nd.n_in ? m : 0ull;
+        }
+        if (nd.op == TDF_OP_EMBED || nd.op == TDF_OP_RNN_CELL || nd.op == TDF_OP_LSTM_CELL) makers.push_back(i);
+      }
+      for (size_t a = 0; a < makers.size(); ++a)
+        for (size_t b = a + 1; b < makers.size(); ++b) {
+          const int i = makers[a], j = makers[b];
+          if (((side[0][i] & side[1][j]) | (side[1][i] & side[0][j])) == 0)
+            bad("two operators that make a vector value can fire under one tag: put each in a function of its own");
+        }
+    }
     G.out_type = ret_type[P->result_fn];
     G.n_result_params = F(P->result_fn).n_params;
     if (want_grad && G.out_type == T_INT) bad("gradient of an integer program");

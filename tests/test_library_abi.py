@@ -101,17 +101,35 @@ def test_unused_state_row_is_rejected_in_a_gradient_graph():
     # a cell whose value nobody differentiates would fire, be logged, and its gradient row would be
     # read without ever having been written: such a program is refused when gradients are asked for
     T = tdf
+    g = ("g", 1, [(T.OP_IN, [], 0), (T.OP_EMBED, [(0, 0)], 0), (T.OP_OUT, [(1, 0)], 0)])
     nodes = [(T.OP_IN, [], 0),                                   # 0: token id
-             (T.OP_EMBED, [(0, 0)], 0),                          # 1: row, used by the cell and by OUT
-             (T.OP_EMBED, [(0, 0)], 0),                          # 2: a second row
+             (T.OP_CALLFN, [(0, 0)], 1),                         # 1: row, used by the cell and by OUT
+             (T.OP_CALLFN, [(0, 0)], 1),                         # 2: a second row
              (T.OP_RNN_CELL, [(1, 0), (2, 0)], 0),               # 3: a cell nobody consumes
              (T.OP_OUT, [(1, 0)], 0)]
-    fns = [("result", 1, nodes)]
+    fns = [("result", 1, nodes), g]
     tdf.graph_build(fns, 0)                                      # fine without gradients
     with pytest.raises(tdf.TdfError) as ei:
         tdf.graph_build(fns, 0, want_grad=True)
     assert ei.value.status == tdf.ERR_BAD_PROGRAM
     assert "consumer" in str(ei.value) or "two differentiable" in str(ei.value)
+
+
+def test_two_vector_values_under_one_tag_are_rejected():
+    # a state row is named by the tag that produced it: operators that make rows must exclude each
+    # other (the two sides of a Switch, as in the tree function) or sit in functions of their own
+    T = tdf
+    nodes = [(T.OP_IN, [], 0),
+             (T.OP_EMBED, [(0, 0)], 0),
+             (T.OP_EMBED, [(0, 0)], 0),
+             (T.OP_RNN_CELL, [(1, 0), (2, 0)], 0),
+             (T.OP_OUT, [(3, 0)], 0)]
+    with pytest.raises(tdf.TdfError) as ei:
+        tdf.graph_build([("result", 1, nodes)], 0)
+    assert ei.value.status == tdf.ERR_BAD_PROGRAM and "one tag" in str(ei.value)
+    for cell in ("rnn", "lstm"):                                 # embed and cell on opposite sides of the Switch
+        for kw in ({}, {"head": True}, {"node_loss": True}):
+            tdf.graph_build(*programs.tree(cell, **kw))
 
 
 def test_workspace_size_grows_with_capacity():
