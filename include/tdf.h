@@ -13,11 +13,14 @@
  * Conventions
  *   - "device" pointers are HIP device memory on the current device, owned by the caller
  *     for the whole call; "host" pointers are ordinary process memory.
- *   - The library allocates no device memory.  All transient device state lives in the
- *     caller's workspace (tdf_workspace_size bytes, 256-byte aligned).
- *   - Work is enqueued on the caller's HIP stream.  The evaluation calls synchronise that
- *     stream before returning (the step count of a recursion is data dependent and is
- *     read back).
+ *   - The evaluation calls allocate no device memory.  All transient device state lives in
+ *     the caller's workspace (tdf_workspace_size bytes, 256-byte aligned); tdf_eval_static
+ *     uses a fixed array inside the library instead (see there).
+ *   - Work is enqueued on the caller's HIP stream; gradient evaluations also use two
+ *     streams that the graph owns (default priority), ordered against the caller's by
+ *     events, and join them before returning.  The evaluation calls synchronise the
+ *     caller's stream before returning (the step count of a recursion is data dependent
+ *     and is read back).
  *   - The functions may be called from several threads.  Evaluations take turns inside the
  *     library even when their streams differ: the persistent kernels of one evaluation need
  *     the whole GPU.  Other work of the caller on other streams of the same GPU should not
