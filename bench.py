@@ -26,8 +26,8 @@ COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 # profiles/bench_workload4_hbm_traffic.md), with the hash of the kernel source they were taken on:
 # reported as `traffic` only while that source is unchanged.
 MEASURED_TRAFFIC = {
-    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "303709f9efb4ec2b", 1899922849.6),
-        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "4280448b1f431a4f", 337804018.2)},
+    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "303709f9efb4ec2b", 1900294929.6),
+        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "4280448b1f431a4f", 337769746.2)},
 }
 
 
@@ -110,6 +110,10 @@ def main():
     ap.add_argument("--fib", type=str, default="",
                     help="workload 1 with these arguments instead of 0..20, e.g. 30,31,32 (a large batch for the tag machine "
                          "alone; frames are kept, as in the counter runs of the same batch)")
+    ap.add_argument("--pipeline", type=int, default=2,
+                    help="tree workloads: after the headline measurement (one evaluation at a time) the same number of "
+                         "evaluations with this many in flight, each from a host thread of its own with its own graph, "
+                         "workspace and stream, reported as `pipelined` (1 = leave that out)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-trees", type=int, default=0, help="trees in the oracle's sample (0 = auto)")
     a = ap.parse_args()
@@ -161,14 +165,16 @@ def main():
             c = make_config(cfg)
         grad = c["grad"]
         B = c["forest"].n_trees
+        n_pipe = max(1, a.pipeline)
         if a.node_loss:
-            run = TreeRun(c, head=False, grad=True, stats_level=0, node_labels=c["node_labels"])
+            runs = [TreeRun(c, head=False, grad=True, stats_level=0, node_labels=c["node_labels"]) for _ in range(n_pipe)]
             dnode = np.full(c["forest"].n_nodes, 1.0 / c["forest"].n_nodes)
-            step = lambda: run.run(None, dnode=dnode)[1]
+            steps_of = [lambda r=r: r.run(None, dnode=dnode)[1] for r in runs]
         else:
-            run = TreeRun(c, head=grad, grad=grad, stats_level=0)
+            runs = [TreeRun(c, head=grad, grad=grad, stats_level=0) for _ in range(n_pipe)]
             dy = np.full(B, 1.0 / B)
-            step = lambda: run.run(dy if grad else None)[1]
+            steps_of = [lambda r=r: r.run(dy if grad else None)[1] for r in runs]
+        run, step = runs[0], steps_of[0]
         passes = 2 if grad else 1
         dtype = "bf16" if c["bf16"] else "f32"
         cell = c["cell"]
@@ -191,21 +197,71 @@ def main():
     copy_gbps = 5 * 2.0 * COPY_BYTES / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del copy_src, copy_dst
 
-    for _ in range(a.warmup):
-        step()
-    torch.cuda.synchronize()
+    if cfg in (1, 6):
+        steps_of = [step]
+    import threading
+
+    def timed(fns, n_steps):
+        """Exactly n_steps evaluations, dealt in turn to one host thread per entry of fns (each with its own
+        graph, workspace and stream).  Every evaluation is complete (control plane, data plane,
+        gradients); with several in flight the library runs one's tag machine beside the previous one's
+        data plane.  Returns (seconds, [(seconds from call to return, stats)])."""
+        n = len(fns)
+        streams = [torch.cuda.Stream() for _ in range(n)]   # (default priority)
+        for fn, sm in zip(fns, streams):
+            with torch.cuda.stream(sm):
+                for _ in range(a.warmup):
+                    fn()
+        torch.cuda.synchronize()
+        results = [[] for _ in range(n)]
+        gate = threading.Barrier(n + 1)
+
+        def worker(i):
+            with torch.cuda.stream(streams[i]):
+                gate.wait()
+                for _ in range(i, n_steps, n):
+                    t_call = time.perf_counter()
+                    st_i = fns[i]()
+                    results[i].append((time.perf_counter() - t_call, st_i))
+                streams[i].synchronize()
+
+        threads = [threading.Thread(target=worker, args=(i,)) for i in range(n)]
+        for t in threads:
+            t.start()
+        gate.wait()
+        t_begin = time.perf_counter()
+        for t in threads:
+            t.join()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t_begin, [x for r in results for x in r]
+
+    # the headline: one evaluation at a time
+    dt, res = timed(steps_of[:1], a.steps)
     phase = np.zeros(len(tdf.PHASES))
     launches = np.zeros(len(tdf.PHASES))
     span_ms = 0.0
-    t0 = time.perf_counter()
-    for _ in range(a.steps):
-        st = step()
+    for _, st in res:
         phase += np.array(list(st.phase_ms))
         launches += np.array(list(st.phase_launches))
         span_ms += st.fwd_cells_span_ms
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    assert len(res) == a.steps
+    latency_ms = 1e3 * float(np.mean([lat for lat, _ in res]))
     n_tags = int(st.n_tags)
+    # and the same number of evaluations with several in flight (tree workloads)
+    pipelined = None
+    if len(steps_of) > 1:
+        n_p = 3 * a.steps   # (more of them: the first tag machine and the last data plane have nothing beside them)
+        dt_p, res_p = timed(steps_of, n_p)
+        ph_p = np.zeros(len(tdf.PHASES))
+        for _, st_p in res_p:
+            ph_p += np.array(list(st_p.phase_ms))
+        pipelined = {"evaluations_in_flight": len(steps_of), "steps": n_p, "ms_per_step": 1e3 * dt_p / n_p,
+                     "value": n_tags * passes * n_p / dt_p, "unit": "firings/s",
+                     "latency_ms": round(1e3 * float(np.mean([lat for lat, _ in res_p])), 4),
+                     "phase_ms": {n: round(float(x) / n_p, 4) for n, x in zip(tdf.PHASES, ph_p)},
+                     "how": "one host thread, graph, workspace and stream per evaluation in flight; the library runs an "
+                            "evaluation's tag machine (which depends on the trees only) beside the previous evaluation's "
+                            "data plane; every evaluation is complete"}
     # one more evaluation, outside the timed region, with the tag machines' step records switched on
     widest = []
     if cfg in (1, 6):
@@ -285,6 +341,7 @@ def main():
                       "n_tags": n_tags,
                       "firings_per_step": firings, "n_steps_tag_machine": int(st.n_steps),
                       "n_levels": int(st.n_waves), "max_tag_depth": int(st.max_tag_depth), "scale": a.scale,
+                      "latency_ms": round(latency_ms, 4),   # mean time of one evaluation from call to return
                       # which way the evaluation took
                       "n_machines": int(st.n_machines), "die_local": int(st.die_local), "generated_step_kernels": int(st.generated),
                       "repeats": int(st.repeats), "tail_used": int(st.tail_used), "deep_split": int(st.deep_split),
@@ -293,6 +350,8 @@ def main():
            "phase_ms": phase_ms, "roofline": roof}
     if cfg not in (1, 6):
         rec["roofline_tag_machine"] = roof_tags
+    if pipelined:
+        rec["pipelined"] = pipelined
     if not a.no_cpu_baseline and not (cfg == 1 and a.fib):   # (the oracle does not finish a batch of that size)
         trees = a.cpu_trees or {1: 0, 2: 256, 3: 1024, 4: 1024, 5: 2, 6: 2048}[cfg]
         rec["cpu_baseline"] = cpu_baseline(cfg, trees, a.node_loss)

@@ -22,10 +22,14 @@
  *     caller's stream before returning (the step count of a recursion is data dependent
  *     and is read back).
  *   - The functions may be called from several threads.  Evaluations take turns inside the
- *     library even when their streams differ: the persistent kernels of one evaluation need
- *     the whole GPU.  Other work of the caller on other streams of the same GPU should not
- *     hold compute units for long while an evaluation runs (the evaluation's bounded waits
- *     would end it with TDF_ERR_DEVICE).
+ *     library, stage by stage: one tag machine at a time and one data plane (cell levels,
+ *     gradients) at a time, because the persistent kernels of either need their workgroups
+ *     resident together; but an evaluation's tag machine, which depends on its trees only, runs
+ *     beside the data plane of the evaluation before it.  A caller who evaluates from two
+ *     threads, each with its own graph, workspace and stream, gets that overlap (about a fifth
+ *     more evaluations per second on the tree workloads).  Other work of the caller on other
+ *     streams of the same GPU should not hold compute units for long while an evaluation runs
+ *     (the evaluation's bounded waits would end it with TDF_ERR_DEVICE).
  *   - Every function returns a tdf_status; a message for the last failure on the calling
  *     thread is available from tdf_last_error().  No exception crosses the ABI.
  */

@@ -324,9 +324,22 @@ tdf_status pinned_reserve(tdf_graph* gr, size_t level_bytes) {
   return TDF_OK;
 }
 
+// Evaluations of one process take turns, in two stages.  The control plane (the tag machine: persistent
+// step kernels whose workgroups must all be resident, one machine per die) of one evaluation at a time;
+// the data plane (level launches, the chain launches with their die barriers, the gradient sums) of one
+// evaluation at a time; but the control plane of one evaluation may run beside the data plane of the
+// one before it, which depends on other inputs' trees only: while a tag machine walks its narrow steps
+// most compute units have nothing else to do.  A caller gets that overlap by evaluating from two
+// threads, each with its own graph, workspace and stream.  Lock order: control, then data.
+std::mutex g_control_mutex, g_data_mutex;
+struct EvalLocks {
+  std::unique_lock<std::mutex> control{g_control_mutex, std::defer_lock}, data{g_data_mutex, std::defer_lock};
+};
+
 tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out, tdf_grads* grads,
                void* workspace, size_t workspace_bytes, void* hip_stream, tdf_stats* stats, bool with_grad,
-               int inherited_repeats = 0, bool no_alloc = false) {
+               EvalLocks& locks, int inherited_repeats = 0, bool no_alloc = false) {
+  if (!locks.control.owns_lock()) locks.control.lock();
   if (!gr || !out) { set_error("NULL graph or outputs"); return TDF_ERR_BAD_ARG; }
   const Graph& G = gr->g;
   Plan P;
@@ -497,6 +510,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
+    // (from here on the next evaluation's tag machine may run; not beside an evaluation in the static
+    // workspace, which has one user at a time)
+    locks.data.lock();
+    if (!no_alloc) locks.control.unlock();
     e.row0 = hc.n_leaf;   // leaf i has row i, the cell at position q of the sorted log row n_leaf + q
     if (!gr->side_stream && with_grad && !no_alloc) {
       HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
@@ -690,7 +707,8 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       }
       if (mixed) {   // the die-private launches did not keep to their dies: the results are void
         gr->die_local = false;
-        return run(gr, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, with_grad,
+        if (locks.data.owns_lock()) locks.data.unlock();   // (control before data: start over in order)
+        return run(gr, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, with_grad, locks,
                    inherited_repeats + (int)repeats + 1, no_alloc);
       }
     }
@@ -804,23 +822,23 @@ extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* i
   return TDF_OK;
 }
 
-// The step kernels and the tail launches are persistent: their workgroups wait for each other at
-// barriers, so all of them must be on the GPU together.  Two evaluations in flight on different
-// streams could each hold a part of the compute units and wait for the rest (the bounded waits
-// would end that with TDF_ERR_DEVICE, not a hang): evaluations of one process take turns.
-static std::mutex g_eval_mutex;
+// The step kernels and the chain launches are persistent: their workgroups wait for each other at
+// barriers, so all of them must be on the GPU together.  Two tag machines, or two data planes, in
+// flight on different streams could each hold a part of the compute units and wait for the rest (the
+// bounded waits would end that with TDF_ERR_DEVICE, not a hang): evaluations of one process take
+// turns, stage by stage (EvalLocks).
 
 extern "C" tdf_status tdf_eval(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* workspace,
                                size_t workspace_bytes, void* hip_stream, tdf_stats* stats) {
-  std::lock_guard<std::mutex> lock(g_eval_mutex);
-  return run(g, in, nullptr, out, nullptr, workspace, workspace_bytes, hip_stream, stats, false);
+  EvalLocks locks;
+  return run(g, in, nullptr, out, nullptr, workspace, workspace_bytes, hip_stream, stats, false, locks);
 }
 
 extern "C" tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out,
                                     tdf_grads* grads, void* workspace, size_t workspace_bytes,
                                     void* hip_stream, tdf_stats* stats) {
-  std::lock_guard<std::mutex> lock(g_eval_mutex);
-  return run(g, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, true);
+  EvalLocks locks;
+  return run(g, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, true, locks);
 }
 
 // ---- evaluation without any allocation ------------------------------------------------------------
@@ -839,7 +857,7 @@ extern "C" tdf_status tdf_graph_prepare(tdf_graph* g) {
     set_error("tdf_graph_prepare: NULL graph");
     return TDF_ERR_BAD_ARG;
   }
-  std::lock_guard<std::mutex> lock(g_eval_mutex);
+  std::lock_guard<std::mutex> lock(g_control_mutex);
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) {
@@ -872,7 +890,8 @@ extern "C" tdf_status tdf_graph_prepare(tdf_graph* g) {
 }
 
 extern "C" tdf_status tdf_eval_static(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* hip_stream, tdf_stats* stats) {
-  std::lock_guard<std::mutex> lock(g_eval_mutex);
+  EvalLocks locks;
+  locks.control.lock();
   if (!g) {
     set_error("tdf_eval_static: NULL graph");
     return TDF_ERR_BAD_ARG;
@@ -896,5 +915,5 @@ extern "C" tdf_status tdf_eval_static(tdf_graph* g, const tdf_inputs* in, tdf_ou
               std::to_string((size_t)TDF_STATIC_WORKSPACE_BYTES) + " (lower max_tags, or use tdf_eval with a workspace of your own)");
     return TDF_ERR_WORKSPACE;
   }
-  return run(g, in, nullptr, out, nullptr, ptr, TDF_STATIC_WORKSPACE_BYTES, hip_stream, stats, false, 0, true);
+  return run(g, in, nullptr, out, nullptr, ptr, TDF_STATIC_WORKSPACE_BYTES, hip_stream, stats, false, locks, 0, true);
 }

@@ -60,5 +60,5 @@ class TreeRun:
         else:
             st, stats = tdf.eval(self.graph, self.inputs, self.ws, out_f32=self.out_f32, out_h=self.out_h,
                                  out_c=self.out_c, out_node_loss=self.out_node_loss, check=check)
-        torch.cuda.synchronize()
+        torch.cuda.current_stream().synchronize()   # (the call has done so already; other streams may be busy with another evaluation)
         return st, stats
