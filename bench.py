@@ -14,6 +14,13 @@ import os
 import sys
 import time
 
+# Two evaluations in flight use six streams (the caller's and the graph's two, each); HIP multiplexes
+# streams onto GPU_MAX_HW_QUEUES hardware queues (4 unless set), and streams that share a queue run one
+# after the other: which ones do would depend on the order in which they were created.  Eight queues give
+# every stream its own.  (Read when the HIP runtime starts, so before torch is imported.)
+if int(os.environ.get("GPU_MAX_HW_QUEUES", "4") or 4) < 8:
+    os.environ["GPU_MAX_HW_QUEUES"] = "8"
+
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 

@@ -26,10 +26,11 @@
  *     gradients) at a time, because the persistent kernels of either need their workgroups
  *     resident together; but an evaluation's tag machine, which depends on its trees only, runs
  *     beside the data plane of the evaluation before it.  A caller who evaluates from two
- *     threads, each with its own graph, workspace and stream, gets that overlap (about a fifth
- *     more evaluations per second on the tree workloads).  Other work of the caller on other
- *     streams of the same GPU should not hold compute units for long while an evaluation runs
- *     (the evaluation's bounded waits would end it with TDF_ERR_DEVICE).
+ *     threads, each with its own graph, workspace and stream, gets that overlap (about a third
+ *     more evaluations per second on the tree workloads; the streams should not share a
+ *     hardware queue: GPU_MAX_HW_QUEUES of the HIP runtime, 4 unless set).  Other work of the
+ *     caller on other streams of the same GPU should not hold compute units for long while an
+ *     evaluation runs (the evaluation's bounded waits would end it with TDF_ERR_DEVICE).
  *   - Every function returns a tdf_status; a message for the last failure on the calling
  *     thread is available from tdf_last_error().  No exception crosses the ABI.
  */

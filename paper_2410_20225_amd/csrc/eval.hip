@@ -329,8 +329,10 @@ tdf_status pinned_reserve(tdf_graph* gr, size_t level_bytes) {
 // the data plane (level launches, the chain launches with their die barriers, the gradient sums) of one
 // evaluation at a time; but the control plane of one evaluation may run beside the data plane of the
 // one before it, which depends on other inputs' trees only: while a tag machine walks its narrow steps
-// most compute units have nothing else to do.  A caller gets that overlap by evaluating from two
-// threads, each with its own graph, workspace and stream.  Lock order: control, then data.
+// most compute units have nothing else to do.  The data stage ends with the gradient pass: the sums that
+// follow it (weight and embedding gradients) are ordinary launches and run beside the next data plane.
+// A caller gets that overlap by evaluating from two threads, each with its own graph, workspace and
+// stream.  Lock order: control, then data.
 std::mutex g_control_mutex, g_data_mutex;
 struct EvalLocks {
   std::unique_lock<std::mutex> control{g_control_mutex, std::defer_lock}, data{g_data_mutex, std::defer_lock};
@@ -692,6 +694,13 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     HIP_TRY(hipGetLastError());
     const DieSync* ts = (const DieSync*)((char*)gr->pinned + PIN_SYNC);
     if (use_tail || deep) HIP_TRY(hipMemcpyAsync((void*)ts, base + P.off_tail_sync, sizeof(DieSync) * 16, hipMemcpyDeviceToHost, s));
+    if (with_grad && !no_alloc && locks.data.owns_lock()) {
+      // Once the gradient pass is through (the event that the embedding gradient was forked at), what is
+      // left of this evaluation are the weight and embedding sums: ordinary launches, no workgroups that
+      // wait for each other.  The next evaluation's data plane may start beside them.
+      HIP_TRY(hipEventSynchronize((hipEvent_t)gr->fork_event));
+      locks.data.unlock();
+    }
     HIP_TRY(hipStreamSynchronize(s));
     if (use_tail || deep) {
       bool mixed = false, gave_up = false;

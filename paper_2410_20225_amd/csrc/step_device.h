@@ -875,6 +875,7 @@ template <bool LOCAL> __device__ __forceinline__ void ctrl_fence() {
 template <bool LOCAL, class SW>
 __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* lds, DevProgram* P_lds, uint32_t* sh) {
   constexpr int SCOPE = LOCAL ? __HIP_MEMORY_SCOPE_WORKGROUP : __HIP_MEMORY_SCOPE_AGENT;
+  __builtin_amdgcn_s_setprio(3);   // (as in steps_small)
   uint32_t G = gridDim.x, rank = blockIdx.x, die = 0;
   if (LOCAL) {   // workgroup i runs on die i % 8 and serves machine i % 8
     die = blockIdx.x % XCDS;
@@ -949,6 +950,9 @@ __device__ void steps_grid(Engine e, int max_steps, long long spin_ticks, char* 
 template <class SW>
 __device__ void steps_small(Engine e, int max_steps, char* lds, DevProgram* P_lds, Ctrl* lc_) {
   e = die_view(e, blockIdx.x);   // one workgroup per machine
+  // A step is a chain of dependent round trips; another evaluation's data plane may share the compute
+  // unit (two evaluations in flight): issue before its waves.
+  __builtin_amdgcn_s_setprio(3);
   Ctrl& lc = *lc_;
   Ctrl* g = e.ctrl;
   {
