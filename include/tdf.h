@@ -25,7 +25,8 @@
  *     library, stage by stage: one tag machine at a time and one data plane (cell levels,
  *     gradients) at a time, because the persistent kernels of either need their workgroups
  *     resident together; but an evaluation's tag machine, which depends on its trees only, runs
- *     beside the data plane of the evaluation before it.  A caller who evaluates from two
+ *     beside the data plane of the evaluation before it.  Evaluations on one graph never
+ *     overlap (the graph owns streams, events and a host buffer).  A caller who evaluates from two
  *     threads, each with its own graph, workspace and stream, gets that overlap (about a third
  *     more evaluations per second on the tree workloads; the streams should not share a
  *     hardware queue: GPU_MAX_HW_QUEUES of the HIP runtime, 4 unless set).  Other work of the

@@ -839,6 +839,8 @@ extern "C" tdf_status tdf_workspace_size(const tdf_graph* g, const tdf_inputs* i
 
 extern "C" tdf_status tdf_eval(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* workspace,
                                size_t workspace_bytes, void* hip_stream, tdf_stats* stats) {
+  if (!g) { set_error("NULL graph"); return TDF_ERR_BAD_ARG; }
+  std::lock_guard<std::mutex> own(g->busy);   // (before the stage locks: graph, control, data)
   EvalLocks locks;
   return run(g, in, nullptr, out, nullptr, workspace, workspace_bytes, hip_stream, stats, false, locks);
 }
@@ -846,6 +848,8 @@ extern "C" tdf_status tdf_eval(tdf_graph* g, const tdf_inputs* in, tdf_outputs* 
 extern "C" tdf_status tdf_eval_grad(tdf_graph* g, const tdf_inputs* in, const tdf_seed* dy, tdf_outputs* out,
                                     tdf_grads* grads, void* workspace, size_t workspace_bytes,
                                     void* hip_stream, tdf_stats* stats) {
+  if (!g) { set_error("NULL graph"); return TDF_ERR_BAD_ARG; }
+  std::lock_guard<std::mutex> own(g->busy);
   EvalLocks locks;
   return run(g, in, dy, out, grads, workspace, workspace_bytes, hip_stream, stats, true, locks);
 }
@@ -866,7 +870,7 @@ extern "C" tdf_status tdf_graph_prepare(tdf_graph* g) {
     set_error("tdf_graph_prepare: NULL graph");
     return TDF_ERR_BAD_ARG;
   }
-  std::lock_guard<std::mutex> lock(g_control_mutex);
+  std::lock_guard<std::mutex> own(g->busy);
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
   if (dev < 0 || dev >= 64) {
@@ -899,12 +903,13 @@ extern "C" tdf_status tdf_graph_prepare(tdf_graph* g) {
 }
 
 extern "C" tdf_status tdf_eval_static(tdf_graph* g, const tdf_inputs* in, tdf_outputs* out, void* hip_stream, tdf_stats* stats) {
-  EvalLocks locks;
-  locks.control.lock();
   if (!g) {
     set_error("tdf_eval_static: NULL graph");
     return TDF_ERR_BAD_ARG;
   }
+  std::lock_guard<std::mutex> own(g->busy);
+  EvalLocks locks;
+  locks.control.lock();
   int dev = 0;
   HIP_TRY(hipGetDevice(&dev));
   void* ptr = nullptr;

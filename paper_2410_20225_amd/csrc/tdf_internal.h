@@ -2,6 +2,7 @@
 #pragma once
 #include <stdint.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -55,6 +56,7 @@ struct tdf_graph {
   // barrier records, the firing tables): copies to and from pageable memory are staged and slower
   void* pinned = nullptr;
   size_t pinned_bytes = 0;
+  std::mutex busy;          // one evaluation at a time uses the graph's streams, events and host buffer
   bool prepared = false;    // tdf_graph_prepare has run: kernels compiled, events and host buffers exist
   int prepared_device = -1;
   ~tdf_graph();

@@ -108,3 +108,25 @@ def test_an_integer_program_beside_a_tree_network():
     assert len(seen) == 10
     for values, n_tags in seen:
         assert values == fib and n_tags == sum(2 * f - 1 for f in fib[1:] + [fib[-1] + fib[-2]])
+
+
+def test_one_graph_from_two_threads_takes_turns():
+    # a graph owns streams, events and a host buffer: two threads that share it do not overlap
+    c = make_config(3, n_trees=200, max_leaves=24, hidden=64, vocab=300)
+    B = c["forest"].n_trees
+    dy = np.full(B, 1.0 / B)
+    run = TreeRun(c, head=True, grad=True)
+    st, stats = run.run(dy)
+    want = {k: getattr(run, k).clone() for k in ("out_f32", "dW", "db", "dE")}
+    counts = []
+
+    def loop():
+        for _ in range(5):
+            st_i, s_i = run.run(dy)
+            counts.append((s_i.n_tags, s_i.n_grad_firings, s_i.n_grad_not_once))
+
+    _in_threads([loop, loop])
+    assert counts == [(stats.n_tags, stats.n_tags, 0)] * 10
+    assert torch.equal(run.out_f32, want["out_f32"])
+    for k in ("dW", "db", "dE"):
+        assert rel_fro(getattr(run, k).cpu().numpy(), want[k].cpu().numpy()) < 1e-5, k
