@@ -413,7 +413,11 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     if (!jit_compile(G.prog, gr->jit, log) && getenv("TDF_JIT_VERBOSE")) fprintf(stderr, "tdf: no generated kernels: %s\n", log.c_str());
   }
   const bool use_jit = gr->jit.step && gr->jit.small && gr->jit.step_local;
-  const int small_block = tag_machine_small_block(G.prog, use_jit);
+  int small_block = tag_machine_small_block(G.prog, use_jit);
+  // A batch of few instances (deep ones, or it would not be worth a GPU) has narrow steps: half the lanes
+  // do, and a workgroup of 256 finds room on a compute unit beside a chain workgroup of the evaluation
+  // before this one (two evaluations in flight), where one of 512 does not.
+  if (use_jit && P.vec && in->n_instances <= 128 && !getenv("TDF_SMALL_BLOCK")) small_block = std::min(small_block, 256);
 #ifdef TDF_TEST_HOOKS
   // Only the build for the tests has this: 1 = the host treats the machines' kernels as having left
   // their dies (once per graph), 2 = the level tail's launches.  The reaction is the product's own.
