@@ -516,10 +516,12 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
-    // (from here on the next evaluation's tag machine may run; not beside an evaluation in the static
-    // workspace, which has one user at a time)
-    locks.data.lock();
-    if (!no_alloc) locks.control.unlock();
+    // From here on the next evaluation's tag machine may run (not beside an evaluation in the static
+    // workspace, which has one user at a time).  The leaves' rows and the sorts of the schedule are
+    // ordinary launches: they do not wait for the data stage, which begins with the first cell launch.
+    if (no_alloc) locks.data.lock();
+    else locks.control.unlock();
+    auto enter_data_stage = [&]() { if (!locks.data.owns_lock()) locks.data.lock(); };
     e.row0 = hc.n_leaf;   // leaf i has row i, the cell at position q of the sorted log row n_leaf + q
     if (!gr->side_stream && with_grad && !no_alloc) {
       HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
@@ -574,6 +576,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       HIP_TRY(hipMemcpyAsync((void*)level_off, e.level_off, level_bytes, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 6);
       HIP_TRY(hipStreamSynchronize(s));
+      enter_data_stage();
       if (with_grad) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->leaves_done, 0));   // the cells read the leaves' rows
       sh_last = want_deep ? std::min(hc.max_level, deep_level - 1) : hc.max_level;
       q_deep0 = want_deep ? level_off[deep_base] : hc.n_cell;   // the shallow instances' cells come first
@@ -635,6 +638,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       }
     }
     if (!hc.n_cell) {   // leaves only
+      enter_data_stage();
       vec_number_rows(e, hc.n_leaf, 0, G.has_head, G.out_type == T_VEC, s);
       if (with_grad) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->leaves_done, 0));
     }
