@@ -248,15 +248,19 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
 #undef TDF_LOAD_TILE
 
   // ---- epilogue.  acc[i][j][r]: row = i*32 + (r/4)*8 + (lane/32)*4 + r%4, column = lane%32
-  // Row indices of the tile go through LDS so that no store waits on an index load.
+  // The element offsets of the tile's rows (row index x Hp: below 2^32, the host checks) go through
+  // LDS, so that no store waits on an index load and no lane multiplies; LSTM_FWD marks a child
+  // that is a leaf (no stored cell state) with NO_ROW, which no multiple of Hp equals.
+  constexpr uint32_t NO_ROW = 0xffffffffu;
   uint32_t* sOut = reinterpret_cast<uint32_t*>(smem);
   uint32_t* sL = sOut + BM;
   uint32_t* sR = sL + BM;
   if (MODE != DW_SPLIT && tid < BM) {
     const int m = min(m0 + tid, g.M - 1);
-    if (MODE != DX_BWD) sOut[tid] = g.out0 + (uint32_t)m;
-    sL[tid] = g.l[m];
-    sR[tid] = g.r[m];
+    if (MODE != DX_BWD) sOut[tid] = (g.out0 + (uint32_t)m) * (uint32_t)g.Hp;
+    const uint32_t l = g.l[m], r = g.r[m];
+    sL[tid] = MODE == LSTM_FWD && l < g.leaf_rows ? NO_ROW : l * (uint32_t)g.Hp;
+    sR[tid] = MODE == LSTM_FWD && r < g.leaf_rows ? NO_ROW : r * (uint32_t)g.Hp;
   }
   __syncthreads();
   const int col = lane & 31;
@@ -265,6 +269,8 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
     const int jb = nt * WNS + wn;
     if (jb * 32 < g.Hp) {
       const int n = jb * 32 + col;   // hidden unit
+      // gate rows of the lane's first cell; the other rows lie whole multiples of ldg further on
+      T* const gates0 = reinterpret_cast<T*>(g.gates) + (size_t)(m0 + wrow + (lane >> 5) * 4) * g.ldg + n;
       const float bi = g.bias[n], bfl = g.bias[g.Hp + n], bfr = g.bias[2 * g.Hp + n];
       const float bo = g.bias[3 * g.Hp + n], bu = g.bias[4 * g.Hp + n];
 #pragma unroll
@@ -273,8 +279,8 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = row_of(i, r);
-          cl[r] = sL[row] >= g.leaf_rows ? g.Cs[(size_t)sL[row] * g.Hp + n] : 0.f;
-          cr[r] = sR[row] >= g.leaf_rows ? g.Cs[(size_t)sR[row] * g.Hp + n] : 0.f;
+          cl[r] = sL[row] != NO_ROW ? g.Cs[sL[row] + (uint32_t)n] : 0.f;
+          cr[r] = sR[row] != NO_ROW ? g.Cs[sR[row] + (uint32_t)n] : 0.f;
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -286,16 +292,16 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
           const float go = Act<T>::sigmoid(acc[i][3][r] + bo);
           const float gu = Act<T>::tanh(acc[i][4][r] + bu);
           const float c = gi * gu + gfl * cl[r] + gfr * cr[r];
-          const size_t o = (size_t)sOut[row] * g.Hp + n;
+          const uint32_t o = sOut[row] + (uint32_t)n;
           g.Cs[o] = c;
           reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh(c));
           if (g.save_gates) {
-            T* gr = reinterpret_cast<T*>(g.gates) + (size_t)m * g.ldg;
-            gr[n] = from_f<T>(gi);
-            gr[g.Hp + n] = from_f<T>(gfl);
-            gr[2 * g.Hp + n] = from_f<T>(gfr);
-            gr[3 * g.Hp + n] = from_f<T>(go);
-            gr[4 * g.Hp + n] = from_f<T>(gu);
+            T* gr = gates0 + (size_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * g.ldg;
+            gr[0] = from_f<T>(gi);
+            gr[g.Hp] = from_f<T>(gfl);
+            gr[2 * g.Hp] = from_f<T>(gfr);
+            gr[3 * g.Hp] = from_f<T>(go);
+            gr[4 * g.Hp] = from_f<T>(gu);
           }
         }
       }
@@ -314,11 +320,11 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
           const int row = row_of(i, r), m = m0 + row;
           if (m >= g.M) continue;
           if constexpr (MODE == RNN_FWD) {
-            reinterpret_cast<T*>(g.Hs_out)[(size_t)sOut[row] * g.Hp + n] = from_f<T>(Act<T>::tanh(acc[i][j][r] + bias));
+            reinterpret_cast<T*>(g.Hs_out)[sOut[row] + (uint32_t)n] = from_f<T>(Act<T>::tanh(acc[i][j][r] + bias));
           } else if constexpr (MODE == DX_BWD) {
             // column n of [dh_l; dh_r]: each child row has exactly one consumer, plain store
-            if (n < g.Hp) g.C[(size_t)sL[row] * g.Hp + n] = acc[i][j][r];
-            else g.C[(size_t)sR[row] * g.Hp + (n - g.Hp)] = acc[i][j][r];
+            if (n < g.Hp) g.C[sL[row] + (uint32_t)n] = acc[i][j][r];
+            else g.C[sR[row] + (uint32_t)(n - g.Hp)] = acc[i][j][r];
           } else {
             g.C[(size_t)split * g.M * g.ldc + (size_t)m * g.ldc + n] = acc[i][j][r];
           }
@@ -937,9 +943,67 @@ __device__ __forceinline__ void dz_row(const VecArgs& v, const Engine& e, uint32
     }
   }
 }
+// The same for a whole level, four hidden units per lane (8- and 16-byte accesses; the padded width is a
+// multiple of 64): a group of Hp / 4 lanes (at most 256) per cell, 256 / group cells per workgroup.
+template <typename T> __device__ __forceinline__ f32x4 load4(const T* p);
+template <> __device__ __forceinline__ f32x4 load4<float>(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+template <> __device__ __forceinline__ f32x4 load4<__bf16>(const __bf16* p) {
+  typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+  const bf16x4 w = *reinterpret_cast<const bf16x4*>(p);
+  return f32x4{(float)w[0], (float)w[1], (float)w[2], (float)w[3]};
+}
+template <typename T> __device__ __forceinline__ void store4(T* p, f32x4 x);
+template <> __device__ __forceinline__ void store4<float>(float* p, f32x4 x) { *reinterpret_cast<f32x4*>(p) = x; }
+template <> __device__ __forceinline__ void store4<__bf16>(__bf16* p, f32x4 x) {
+  typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+  bf16x4 w;
+  w[0] = (__bf16)x[0]; w[1] = (__bf16)x[1]; w[2] = (__bf16)x[2]; w[3] = (__bf16)x[3];
+  *reinterpret_cast<bf16x4*>(p) = w;
+}
 template <int DT>
-__global__ void k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
-  if (blockIdx.x < count) dz_row<DT>(v, e, q0 + blockIdx.x);
+__global__ void __launch_bounds__(256) k_dz(VecArgs v, Engine e, uint32_t q0, uint32_t count) {
+  typedef typename TypeOf<DT>::type T;
+  const int group = min(256, v.Hp / 4), per_block = 256 / group;
+  const int gi = threadIdx.x / group, gl = threadIdx.x % group;
+  const uint32_t k = blockIdx.x * per_block + gi;
+  if (gi >= per_block || k >= count) return;
+  const uint32_t q = q0 + k;
+  const size_t o = (size_t)(e.row0 + q) * v.Hp;
+  T* dz = reinterpret_cast<T*>(v.Dz) + (size_t)q * v.Np;
+  if (gl == 0) atomicAdd(&v.gmark[e.row0 + q], 1u);   // the gradient body of this tag fires
+  if (v.cell_kind == 1) {
+    for (int n = gl * 4; n < v.Hp; n += group * 4) {
+      const f32x4 h = load4<T>(reinterpret_cast<const T*>(v.Hs) + o + n);
+      f32x4 dh = load4<float>(v.dH + o + n);
+      if (v.dHn) dh += load4<float>(v.dHn + o + n);
+      store4<T>(dz + n, dh * (1.f - h * h));
+    }
+  } else {
+    const bool cell_l = e.q_l[q] >= e.row0, cell_r = e.q_r[q] >= e.row0;   // a leaf child: c = 0, no use for dc
+    const size_t ol = (size_t)e.q_l[q] * v.Hp, orr = (size_t)e.q_r[q] * v.Hp;
+    const T* gt = reinterpret_cast<const T*>(v.gates) + (size_t)q * v.Np;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    for (int n = gl * 4; n < v.Hp; n += group * 4) {
+      const f32x4 gi4 = load4<T>(gt + n), gfl = load4<T>(gt + v.Hp + n), gfr = load4<T>(gt + 2 * v.Hp + n);
+      const f32x4 go = load4<T>(gt + 3 * v.Hp + n), gu = load4<T>(gt + 4 * v.Hp + n);
+      const f32x4 c = load4<float>(v.Cs + o + n);
+      f32x4 dh = load4<float>(v.dH + o + n);
+      if (v.dHn) dh += load4<float>(v.dHn + o + n);
+      const f32x4 dc_in = load4<float>(v.dC + o + n);
+      const f32x4 cl = cell_l ? load4<float>(v.Cs + ol + n) : zero, cr = cell_r ? load4<float>(v.Cs + orr + n) : zero;
+      f32x4 tc;
+#pragma unroll
+      for (int t = 0; t < 4; ++t) tc[t] = Act<T>::tanh(c[t]);
+      const f32x4 dc = dc_in + dh * go * (1.f - tc * tc);
+      store4<T>(dz + n, dc * gu * gi4 * (1.f - gi4));
+      store4<T>(dz + v.Hp + n, dc * cl * gfl * (1.f - gfl));
+      store4<T>(dz + 2 * v.Hp + n, dc * cr * gfr * (1.f - gfr));
+      store4<T>(dz + 3 * v.Hp + n, dh * tc * go * (1.f - go));
+      store4<T>(dz + 4 * v.Hp + n, dc * gi4 * (1.f - gu * gu));
+      if (cell_l) store4<float>(v.dC + ol + n, dc * gfl);
+      if (cell_r) store4<float>(v.dC + orr + n, dc * gfr);
+    }
+  }
 }
 
 // ---- the tail of the level schedule in one launch ------------------------------------------------
@@ -1508,7 +1572,8 @@ void vec_cell_fwd(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count
 
 template <typename T> static void cell_bwd_t(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count, hipStream_t s) {
   if (!count) return;
-  hipLaunchKernelGGL(k_dz<DtOf<T>::value>, dim3(count), dim3(256), 0, s, v, e, q0, count);
+  const int per_block = 256 / std::min(256, v.Hp / 4);
+  hipLaunchKernelGGL(k_dz<DtOf<T>::value>, dim3((count + per_block - 1) / per_block), dim3(256), 0, s, v, e, q0, count);
   GemmArgs g{};
   g.M = (int)count; g.N = v.Kp; g.K = v.Np;
   g.A = reinterpret_cast<const T*>(v.Dz) + (size_t)q0 * v.Np; g.lda = v.Np;
