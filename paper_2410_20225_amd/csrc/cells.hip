@@ -7,6 +7,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "bucket.h"
 #include "die_sync.h"
@@ -64,11 +65,18 @@ template <typename T> __device__ __forceinline__ T from_f(float x) { return (T)x
 
 // Activations.  The fp32 path uses the accurate library functions; the bf16 path, whose
 // results are rounded to 8 bits of mantissa anyway, uses the hardware exponential.
+// sigmoid_b / tanh_b take the accumulator and a bias prepared by pre_sigmoid / pre_tanh: the bf16
+// path folds the bias and the exponent's scale into one multiply-add.
 template <typename T> struct Act {
   static __device__ __forceinline__ float sigmoid(float x) { return 1.0f / (1.0f + expf(-x)); }
   static __device__ __forceinline__ float tanh(float x) { return tanhf(x); }
+  static __device__ __forceinline__ float pre_sigmoid(float b) { return b; }
+  static __device__ __forceinline__ float pre_tanh(float b) { return b; }
+  static __device__ __forceinline__ float sigmoid_b(float acc, float pb) { return sigmoid(acc + pb); }
+  static __device__ __forceinline__ float tanh_b(float acc, float pb) { return tanh(acc + pb); }
 };
 template <> struct Act<__bf16> {
+  static constexpr float LOG2E = 1.4426950408889634f;
   static __device__ __forceinline__ float sigmoid(float x) {
     return __builtin_amdgcn_rcpf(1.0f + __expf(-x));
   }
@@ -76,6 +84,16 @@ template <> struct Act<__bf16> {
     const float xc = fminf(fmaxf(x, -15.f), 15.f);
     const float e = __expf(2.0f * xc);
     return (e - 1.0f) * __builtin_amdgcn_rcpf(e + 1.0f);
+  }
+  static __device__ __forceinline__ float pre_sigmoid(float b) { return -LOG2E * b; }
+  static __device__ __forceinline__ float pre_tanh(float b) { return 2.0f * LOG2E * b; }
+  // 1 / (1 + 2^(-log2e (acc + b)))
+  static __device__ __forceinline__ float sigmoid_b(float acc, float pb) {
+    return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(fmaf(acc, -LOG2E, pb)));
+  }
+  // 1 - 2 / (1 + 2^(2 log2e (acc + b))): the exponential's overflow and underflow give exactly 1 and -1
+  static __device__ __forceinline__ float tanh_b(float acc, float pb) {
+    return fmaf(-2.0f, __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(fmaf(acc, 2.0f * LOG2E, pb))), 1.0f);
   }
 };
 
@@ -106,6 +124,7 @@ struct GemmArgs {
   int n_splits;
   int n_tiles_n;             // column tiles of the launch
   int save_gates;
+  int narrow;                // LSTM_FWD: state rows and this level's gate rows end below 4 GiB
 };
 
 constexpr int BM_FULL = 128;   // rows of a workgroup tile; half of it for levels that would not fill the GPU
@@ -116,7 +135,7 @@ constexpr int BM_FULL = 128;   // rows of a workgroup tile; half of it for level
 // waves share a SIMD, and one multiplies while the other waits for LDS or memory.  LSTM_FWD
 // gives every wave the five gate blocks of the same 32 hidden units, so the gate epilogue needs
 // no exchange between lanes; its workgroups are one such block wide (WNS = 1).
-template <int DT, int MODE, int NW, int BM, int WNS>
+template <int DT, int MODE, int NW, int BM, int WNS, bool NARROW = false>
 __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) {
   constexpr int GEMM_THREADS = NW * 64;
   constexpr int MB = BM * WNS / (32 * NW);       // 32-row blocks per wave (waves as NW/WNS x WNS)
@@ -249,59 +268,72 @@ __global__ void __launch_bounds__(NW * 64, WNS == 1 ? 3 : 1) k_gemm(GemmArgs g) 
 
   // ---- epilogue.  acc[i][j][r]: row = i*32 + (r/4)*8 + (lane/32)*4 + r%4, column = lane%32
   // The element offsets of the tile's rows (row index x Hp: below 2^32, the host checks) go through
-  // LDS, so that no store waits on an index load and no lane multiplies; LSTM_FWD marks a child
-  // that is a leaf (no stored cell state) with NO_ROW, which no multiple of Hp equals.
-  constexpr uint32_t NO_ROW = 0xffffffffu;
+  // LDS, so that no store waits on an index load and no lane multiplies.  LSTM_FWD: a child that is
+  // a leaf has no stored cell state; it reads row 0 of Cs instead, a leaf's row that k_embed zeroes.
   uint32_t* sOut = reinterpret_cast<uint32_t*>(smem);
   uint32_t* sL = sOut + BM;
   uint32_t* sR = sL + BM;
   if (MODE != DW_SPLIT && tid < BM) {
     const int m = min(m0 + tid, g.M - 1);
-    if (MODE != DX_BWD) sOut[tid] = (g.out0 + (uint32_t)m) * (uint32_t)g.Hp;
+    if (MODE == RNN_FWD) sOut[tid] = (g.out0 + (uint32_t)m) * (uint32_t)g.Hp;
     const uint32_t l = g.l[m], r = g.r[m];
-    sL[tid] = MODE == LSTM_FWD && l < g.leaf_rows ? NO_ROW : l * (uint32_t)g.Hp;
-    sR[tid] = MODE == LSTM_FWD && r < g.leaf_rows ? NO_ROW : r * (uint32_t)g.Hp;
+    sL[tid] = MODE == LSTM_FWD && l < g.leaf_rows ? 0u : l * (uint32_t)g.Hp;
+    sR[tid] = MODE == LSTM_FWD && r < g.leaf_rows ? 0u : r * (uint32_t)g.Hp;
   }
   __syncthreads();
   const int col = lane & 31;
   auto row_of = [&](int i, int r) { return wrow + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); };
   if constexpr (MODE == LSTM_FWD) {
+    // Byte offsets: 32 bits wide where every array of the launch ends below 4 GiB (NARROW, checked by
+    // the host: an address is then a uniform base plus one 32-bit register), else 64.
+    typedef typename std::conditional<NARROW, uint32_t, size_t>::type Off;
     const int jb = nt * WNS + wn;
     if (jb * 32 < g.Hp) {
       const int n = jb * 32 + col;   // hidden unit
-      // gate rows of the lane's first cell; the other rows lie whole multiples of ldg further on
-      T* const gates0 = reinterpret_cast<T*>(g.gates) + (size_t)(m0 + wrow + (lane >> 5) * 4) * g.ldg + n;
-      const float bi = g.bias[n], bfl = g.bias[g.Hp + n], bfr = g.bias[2 * g.Hp + n];
-      const float bo = g.bias[3 * g.Hp + n], bu = g.bias[4 * g.Hp + n];
+      const float bi = Act<T>::pre_sigmoid(g.bias[n]), bfl = Act<T>::pre_sigmoid(g.bias[g.Hp + n]);
+      const float bfr = Act<T>::pre_sigmoid(g.bias[2 * g.Hp + n]), bo = Act<T>::pre_sigmoid(g.bias[3 * g.Hp + n]);
+      const float bu = Act<T>::pre_tanh(g.bias[4 * g.Hp + n]);
+      const char* const cs_in = reinterpret_cast<const char*>(g.Cs);
+      char* const cs = reinterpret_cast<char*>(g.Cs);
+      char* const hs = reinterpret_cast<char*>(g.Hs_out);
+      // the five gate blocks of a row lie Hp elements apart: five uniform bases, one lane offset
+      char* gt[5];
+#pragma unroll
+      for (int k = 0; k < 5; ++k) gt[k] = reinterpret_cast<char*>(g.gates) + (size_t)k * g.Hp * sizeof(T);
+      // The lane's first row of the tile; its other rows lie whole multiples of a row further on, and
+      // those multiples are uniform values (kept apart from the lane's own offset: one add per access).
+      const int row0 = wrow + (lane >> 5) * 4;
+      const Off out_b = ((Off)(g.out0 + (uint32_t)(m0 + row0)) * (Off)g.Hp + (Off)n) * (Off)4;   // bytes into Cs
+      const Off gate_b = ((Off)(m0 + row0) * (Off)g.ldg + (Off)n) * (Off)sizeof(T);              // bytes into gates
 #pragma unroll
       for (int i = 0; i < MB; ++i) {
         float cl[16], cr[16];   // children's cell states: all loads in flight before any store
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int row = row_of(i, r);
-          cl[r] = sL[row] != NO_ROW ? g.Cs[sL[row] + (uint32_t)n] : 0.f;
-          cr[r] = sR[row] != NO_ROW ? g.Cs[sR[row] + (uint32_t)n] : 0.f;
+          cl[r] = *reinterpret_cast<const float*>(cs_in + (Off)(sL[row] + (uint32_t)n) * (Off)4);
+          cr[r] = *reinterpret_cast<const float*>(cs_in + (Off)(sR[row] + (uint32_t)n) * (Off)4);
         }
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int row = row_of(i, r), m = m0 + row;
-          if (m >= g.M) continue;
-          const float gi = Act<T>::sigmoid(acc[i][0][r] + bi);
-          const float gfl = Act<T>::sigmoid(acc[i][1][r] + bfl);
-          const float gfr = Act<T>::sigmoid(acc[i][2][r] + bfr);
-          const float go = Act<T>::sigmoid(acc[i][3][r] + bo);
-          const float gu = Act<T>::tanh(acc[i][4][r] + bu);
+          const int d = i * 32 + (r >> 2) * 8 + (r & 3);   // row of the tile = row0 + d
+          if (m0 + row0 + d >= g.M) continue;
+          const float gi = Act<T>::sigmoid_b(acc[i][0][r], bi);
+          const float gfl = Act<T>::sigmoid_b(acc[i][1][r], bfl);
+          const float gfr = Act<T>::sigmoid_b(acc[i][2][r], bfr);
+          const float go = Act<T>::sigmoid_b(acc[i][3][r], bo);
+          const float gu = Act<T>::tanh_b(acc[i][4][r], bu);
           const float c = gi * gu + gfl * cl[r] + gfr * cr[r];
-          const uint32_t o = sOut[row] + (uint32_t)n;
-          g.Cs[o] = c;
-          reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh(c));
+          const Off o = out_b + (Off)(uint32_t)__builtin_amdgcn_readfirstlane(d * g.Hp * 4);
+          *reinterpret_cast<float*>(cs + o) = c;
+          *reinterpret_cast<T*>(hs + o / (Off)(4 / sizeof(T))) = from_f<T>(go * Act<T>::tanh_b(c, 0.f));
           if (g.save_gates) {
-            T* gr = gates0 + (size_t)(i * 32 + (r >> 2) * 8 + (r & 3)) * g.ldg;
-            gr[0] = from_f<T>(gi);
-            gr[g.Hp] = from_f<T>(gfl);
-            gr[2 * g.Hp] = from_f<T>(gfr);
-            gr[3 * g.Hp] = from_f<T>(go);
-            gr[4 * g.Hp] = from_f<T>(gu);
+            const Off go_b = gate_b + (Off)(uint32_t)__builtin_amdgcn_readfirstlane(d * (int)g.ldg * (int)sizeof(T));
+            *reinterpret_cast<T*>(gt[0] + go_b) = from_f<T>(gi);
+            *reinterpret_cast<T*>(gt[1] + go_b) = from_f<T>(gfl);
+            *reinterpret_cast<T*>(gt[2] + go_b) = from_f<T>(gfr);
+            *reinterpret_cast<T*>(gt[3] + go_b) = from_f<T>(go);
+            *reinterpret_cast<T*>(gt[4] + go_b) = from_f<T>(gu);
           }
         }
       }
@@ -344,7 +376,7 @@ template <typename T, int MODE, int BM, int WNS> size_t gemm_lds_bytes() {
 // reads per MFMA).
 static int gemm_waves(int mode) { return mode == DW_SPLIT ? 4 : 8; }
 
-template <typename T, int MODE, int NW, int BM, int WNS = 2>
+template <typename T, int MODE, int NW, int BM, int WNS = 2, bool NARROW = false>
 void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
   if (g.M <= 0) return;
   g.n_tiles_n = n_tiles_n;
@@ -353,12 +385,12 @@ void launch_gemm_nw(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
   dim3 grid(MODE == DW_SPLIT ? 8 * n_mt * n_tiles_n * ((splits + 7) / 8) : (n_mt + 7) / 8 * 8 * n_tiles_n);
   static bool lds_opt_in = false;   // tiles above 64 KiB of LDS need an explicit opt-in
   if (!lds_opt_in) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE, NW, BM, WNS>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&k_gemm<DtOf<T>::value, MODE, NW, BM, WNS, NARROW>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)gemm_lds_bytes<T, MODE, BM, WNS>());
     lds_opt_in = true;
   }
   const size_t lds = gemm_lds_bytes<T, MODE, BM, WNS>();
-  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE, NW, BM, WNS>), grid, dim3(NW * 64), lds, s, g);
+  hipLaunchKernelGGL((k_gemm<DtOf<T>::value, MODE, NW, BM, WNS, NARROW>), grid, dim3(NW * 64), lds, s, g);
 }
 
 template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int splits, hipStream_t s) {
@@ -367,7 +399,8 @@ template <typename T, int MODE> void launch_gemm(GemmArgs g, int n_tiles_n, int 
   // LSTM cells: one block of 32 hidden units (x 5 gates) per workgroup, four waves of 32 rows: the
   // accumulators fit a third of the register file and three workgroups share a compute unit, each
   // in another phase of its k loop
-  if (MODE == LSTM_FWD) launch_gemm_nw<T, MODE, 4, 128, 1>(g, n_tiles_n * 2, splits, s);
+  if (MODE == LSTM_FWD && g.narrow) launch_gemm_nw<T, MODE, 4, 128, 1, true>(g, n_tiles_n * 2, splits, s);
+  else if (MODE == LSTM_FWD) launch_gemm_nw<T, MODE, 4, 128, 1>(g, n_tiles_n * 2, splits, s);
   else if (half) launch_gemm_nw<T, MODE, 4, 64>(g, n_tiles_n, splits, s);
   else if (gemm_waves(MODE) == 4) launch_gemm_nw<T, MODE, 4, 128>(g, n_tiles_n, splits, s);
   else launch_gemm_nw<T, MODE, 8, 128>(g, n_tiles_n, splits, s);
@@ -749,6 +782,9 @@ __global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
     const T* src = reinterpret_cast<const T*>(v.E) + (size_t)(tok < (uint32_t)v.vocab ? tok : 0) * v.H;
     T* dst = reinterpret_cast<T*>(v.Hs) + (size_t)row * v.Hp;
     for (int n = lane; n < v.Hp; n += 64) dst[n] = n < v.H ? src[n] : from_f<T>(0.f);
+    // leaves have no cell state; row 0, a leaf's, is kept zero for the cells that read a leaf child's
+    if (i == 0 && v.cell_kind == 2)
+      for (int n = lane; n < v.Hp; n += 64) v.Cs[n] = 0.f;
   }
 }
 
@@ -1556,6 +1592,8 @@ template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, 
   g.bias = v.bp; g.Hs_out = v.Hs; g.Cs = v.Cs; g.leaf_rows = e.row0;
   g.gates = v.gates ? reinterpret_cast<T*>(v.gates) + (size_t)q0 * v.Np : nullptr;
   g.ldg = v.Np; g.save_gates = save_gates && v.gates;
+  g.narrow = !v.wide_offsets && (uint64_t)(e.row0 + q0 + count) * (uint64_t)v.Hp * 4u < (1ull << 32) &&
+             (uint64_t)count * (uint64_t)v.Np * sizeof(T) < (1ull << 32);
   if (count <= small_level()) {
     if (v.cell_kind == 2) launch_cell_small<T, LSTM_FWD>(g, v.Hp / 32, s);
     else launch_cell_small<T, RNN_FWD>(g, v.Hp / 32, s);

@@ -307,6 +307,7 @@ struct VecArgs {
   uint32_t* gmark;  // [rows] gradient runs: how often the gradient body of a row's tag has fired (cleared per call)
   float* dHn;       // [rows x Hp] gradient of each row's own loss term (CE_NODE, gradient runs; else null):
                     // whoever reads a row of dH adds the row of dHn
+  int wide_offsets; // only the build for the tests sets it: kernels with a 32-bit and a 64-bit offset path take the latter
 };
 
 }  // namespace tdf

@@ -419,6 +419,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   // before this one (two evaluations in flight), where one of 512 does not.
   if (use_jit && P.vec && in->n_instances <= 128 && !getenv("TDF_SMALL_BLOCK")) small_block = std::min(small_block, 256);
 #ifdef TDF_TEST_HOOKS
+  v.wide_offsets = getenv("TDF_TEST_WIDE_OFFSETS") != nullptr;   // a path that otherwise needs arrays of 4 GiB
   // Only the build for the tests has this: 1 = the host treats the machines' kernels as having left
   // their dies (once per graph), 2 = the level tail's launches.  The reaction is the product's own.
   const int test_mixed_dies = getenv("TDF_TEST_MIXED_DIES") ? atoi(getenv("TDF_TEST_MIXED_DIES")) : 0;

@@ -23,11 +23,12 @@ VARIANTS = [{"TDF_NO_JIT": "1"}, {"TDF_NO_DIE_LOCAL": "1"}, {"TDF_NO_JIT": "1", 
             {"TDF_SMALL_LEVEL": "0"}, {"TDF_SMALL_LEVEL": "100000000"},
             {"TDF_SMALL_LIMIT": "1"}, {"TDF_SMALL_LIMIT": "1", "TDF_DIES": "1"}, {"TDF_SMALL_LIMIT": "100000000"},
             {"TDF_TEST_MIXED_DIES": "1"}, {"TDF_TEST_MIXED_DIES": "2"},
-            {"TDF_FOLLOW_LIMIT": "0"}]
+            {"TDF_FOLLOW_LIMIT": "0"},
+            {"TDF_SMALL_LEVEL": "0", "TDF_TEST_WIDE_OFFSETS": "1"}]
 IDS = ["interpreter", "device_scope", "interpreter_device_scope", "tiled_gemm_only", "small_level_only",
        "grid_kernel_only", "grid_kernel_only_one_machine", "single_workgroup_only",
        "repeat_after_machines_left_their_dies", "repeat_after_tail_left_its_dies",
-       "no_follow"]
+       "no_follow", "tiled_gemm_with_64_bit_offsets"]
 
 
 @pytest.fixture(scope="module")
@@ -52,7 +53,7 @@ def test_treelstm_variants(env, lstm_case, hooks_library, monkeypatch):
     for k, v in env.items():
         monkeypatch.setenv(k, v)
     c, dy, ref = lstm_case
-    if "TDF_TEST_MIXED_DIES" in env:
+    if any(k.startswith("TDF_TEST_") for k in env):   # switches that only the build for the tests reads
         with tdf.use_library(hooks_library):
             run = TreeRun(c, head=True, grad=True)
     else:
@@ -77,7 +78,7 @@ def test_treelstm_variants(env, lstm_case, hooks_library, monkeypatch):
         assert stats.tail_used == 0 and stats.n_wide_waves == stats.n_waves
 
 
-@pytest.mark.parametrize("env", VARIANTS[:3] + VARIANTS[-1:], ids=IDS[:3] + IDS[-1:])
+@pytest.mark.parametrize("env", VARIANTS[:3] + VARIANTS[-2:-1], ids=IDS[:3] + IDS[-2:-1])
 def test_fib_variants(env, monkeypatch):
     for k, v in env.items():
         monkeypatch.setenv(k, v)
