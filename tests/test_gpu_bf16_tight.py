@@ -55,6 +55,26 @@ def test_against_the_rounding_oracle(cfg, n_trees, max_leaves, hidden, vocab, TI
         assert rel_fro(run.out_c.cpu().numpy(), want[:, H:]) < TIGHT
 
 
+def test_wide_lstm_levels_at_the_full_width():
+    # levels of more than 1024 cells at the workload's own width of 256 (the tiled kernels with a ragged last
+    # tile), all four outputs at the bar of the rounding oracle
+    c = make_config(4, n_trees=400, max_leaves=40, hidden=256, vocab=1000)
+    B = c["forest"].n_trees
+    dy = np.full(B, 1.0 / B)
+    run = TreeRun(c, head=True, grad=True)
+    st, stats = run.run(dy)
+    assert stats.n_grad_firings == stats.n_tags and stats.n_grad_not_once == 0
+    ref = run_oracle_tree(c, head=True, grad=True, dy=dy, round_bf16=True)
+    for name, got, want in (("loss", run.out_f32, np.array(ref["out"])), ("dW", run.dW, ref["grads"]["dW"]),
+                            ("db", run.db, ref["grads"]["db"]), ("dE", run.dE, ref["grads"]["dE"])):
+        assert rel_fro(got.cpu().numpy(), want) < 1e-3, name
+    # a second evaluation in the same workspace gives the same sums (nothing of the first is left over)
+    first = {k: getattr(run, k).clone() for k in ("dW", "db", "dE")}
+    run.run(dy)
+    for k, t in first.items():
+        assert rel_fro(getattr(run, k).cpu().numpy(), t.cpu().numpy()) < 1e-5, k
+
+
 def test_matrix_products_alone_against_float64_products():
     # 3000 two-leaf TreeRNN trees, H = 128, distinct tokens: one level of 3000 cells (the tiled GEMM
     # and its gradient kernels), dy given per root.  With x_b = [E[t_l]; E[t_r]] (bfloat16 values):
