@@ -23,11 +23,14 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_the_product_library_has_no_test_hook():
-    """The switch that makes the host pretend its die-private kernels left their dies exists in the
-    tests' build of the library only."""
+    """The switches that make the host pretend its die-private kernels left their dies, or take the
+    64-bit offsets of large workspaces on a small one, exist in the tests' build of the library only."""
     here = os.path.dirname(tdf.__file__)
-    assert b"TDF_TEST_MIXED_DIES" not in open(os.path.join(here, "libtdf.so"), "rb").read()
-    assert b"TDF_TEST_MIXED_DIES" in open(os.path.join(here, "libtdf_hooks.so"), "rb").read()
+    product = open(os.path.join(here, "libtdf.so"), "rb").read()
+    hooks = open(os.path.join(here, "libtdf_hooks.so"), "rb").read()
+    for name in (b"TDF_TEST_MIXED_DIES", b"TDF_TEST_WIDE_OFFSETS"):
+        assert name not in product and name in hooks, name
+    assert b"TDF_TEST_" not in product
 
 
 _NAMES = {tdf.OP_EQ: "=", tdf.OP_SWITCH: "Switch", tdf.OP_SUB: "-", tdf.OP_MUL: "*", tdf.OP_ADD: "+",
