@@ -1259,12 +1259,11 @@ constexpr int DWT = 128;        // tile edge
 constexpr int DWQ = 64;         // tags per stage
 constexpr int DWLD = DWT + 16;  // LDS row stride in elements: rows 288 bytes apart
 
-__device__ __forceinline__ bf16x8 tr_frag(const __bf16* tile, int q0, int col0, int lane) {
-  // block [q0 + 8 g .. + 7][col0 .. col0 + 15], g = lane / 16: source lane s of a group points at
-  // tag q0 + 8 g + 4 t + s / 4, columns col0 + 4 (s % 4) .. + 3; it receives column col0 + s of
-  // the tags q0 + 8 g + 4 t + 0 .. 3
-  const int g = lane >> 4, sl = lane & 15;
-  const __bf16* p = tile + (q0 + 8 * g + (sl >> 2)) * DWLD + col0 + 4 * (sl & 3);
+// One MFMA operand from a tile stored as it lies in memory ([tag][column], DWLD elements per row), read
+// transposed: `p` is the lane's own place in the block [8 g .. 8 g + 7][16 columns] (g = lane / 16; source
+// lane s of a group points at tag 8 g + 4 t + s / 4, columns 4 (s % 4) .. + 3, and receives column s of
+// the tags 8 g + 4 t + 0 .. 3), the same for every block of the tile up to a constant offset.
+__device__ __forceinline__ bf16x8 tr_frag(const __bf16* p) {
   typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)p);
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + 4 * DWLD));
@@ -1299,29 +1298,49 @@ __global__ void __launch_bounds__(256, 3) k_dw_direct(DwArgs g) {
   const uint32_t q_begin = (uint32_t)split * (uint32_t)g.k_per_split;
   const uint32_t q_end = min(g.n_q, q_begin + (uint32_t)g.k_per_split);
 
-  // this thread's four 16-byte chunks of each tile: rows r0 + 16 c, chunk column ch
+  // This thread's four 16-byte chunks of each tile: rows r0 + 16 c, chunk column ch.  A chunk whose
+  // columns lie beyond the matrix reads the last valid columns instead (its products are never stored),
+  // so the loads of a whole stage need no predicate; only the last, partial stage of a split checks
+  // its tags.  The addresses advance by one stage per pass (no multiplication per chunk).
   const int r0 = tid >> 4, ch = (tid & 15) * 8;
-  const int a_col = mt * DWT + ch, b_col = nt * DWT + ch;
-  const bool a_ok = a_col < g.Np, b_ok = b_col < g.Kp;
+  // Rows are 72 banks apart, so the rows of two neighbouring groups of 16 lanes (8 tags apart) would start
+  // in the same bank: the tile is stored with column bit 6 flipped in every other block of eight tags, which
+  // sends those groups to different halves of the banks.  A wave's 64 columns keep to one half of the tile's
+  // 128, so the flip is part of the lane's base address and costs the reads nothing.
+  const int ch_lds = ch ^ (((r0 >> 3) & 1) << 6);
+  const int fg = lane >> 4, fs = lane & 15;
+  const __bf16* const a_lane = sA + (8 * fg + (fs >> 2)) * DWLD + 4 * (fs & 3) + (((wm ^ fg) & 1) << 6);
+  const __bf16* const b_lane = sB + (8 * fg + (fs >> 2)) * DWLD + 4 * (fs & 3) + (((wn ^ fg) & 1) << 6);
+  const int a_col = min(mt * DWT + ch, g.Np - 8), b_col = min(nt * DWT + ch, g.Kp - 8);
   const bool b_left = b_col < g.Hp;
-  const int b_off = b_left ? b_col : b_col - g.Hp;
+  const uint32_t b_off = (uint32_t)(b_left ? b_col : b_col - g.Hp);
+  const uint32_t* const b_rows = b_left ? g.q_l : g.q_r;
   u32x4 ra[4], rb[4];
   uint32_t row_next[4];   // gathered rows of the stage after the one in ra / rb
-  auto load_rows = [&](uint32_t q0) {
+  const __bf16* pa = g.Dz + (size_t)(q_begin + r0) * g.Np + a_col;   // chunk c = 0 of the stage to be loaded next
+  const size_t a_step = (size_t)16 * g.Np;
+  auto load_rows = [&](uint32_t q0, bool full) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const uint32_t q = q0 + r0 + 16 * c;
-      row_next[c] = q < q_end ? (b_left ? g.q_l[q] : g.q_r[q]) : 0u;
+      row_next[c] = (full || q < q_end) ? b_rows[q] : 0u;
     }
   };
-  auto load_tile = [&](uint32_t q0) {   // uses row_next, which must hold the rows of q0
+  auto load_tile = [&](uint32_t q0, bool full) {   // uses row_next, which must hold the rows of q0
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const uint32_t q = q0 + r0 + 16 * c;
       const u32x4 zero = {0u, 0u, 0u, 0u};
-      ra[c] = (q < q_end && a_ok) ? *reinterpret_cast<const u32x4*>(g.Dz + (size_t)q * g.Np + a_col) : zero;
-      rb[c] = (q < q_end && b_ok) ? *reinterpret_cast<const u32x4*>(g.Hs + (size_t)row_next[c] * g.Hp + b_off) : zero;
+      const uint32_t hs_off = row_next[c] * (uint32_t)g.Hp + b_off;   // (rows x Hp stays below 2^32: the host checks)
+      if (full) {
+        ra[c] = *reinterpret_cast<const u32x4*>(pa + c * a_step);
+        rb[c] = *reinterpret_cast<const u32x4*>(g.Hs + hs_off);
+      } else {
+        ra[c] = q < q_end ? *reinterpret_cast<const u32x4*>(pa + c * a_step) : zero;
+        rb[c] = q < q_end ? *reinterpret_cast<const u32x4*>(g.Hs + hs_off) : zero;
+      }
     }
+    pa += 4 * a_step;
   };
 
   f32x4 acc[4][4], accdb[4];
@@ -1337,29 +1356,31 @@ __global__ void __launch_bounds__(256, 3) k_dw_direct(DwArgs g) {
   const bf16x8 ones = __builtin_bit_cast(bf16x8, ones_bits);
   const bool with_db = nt == 0 && wn == 0;
 
+  // a stage is full if all its DWQ tags belong to the split (uniform for the workgroup)
+  auto is_full = [&](uint32_t q0) { return q0 + DWQ <= q_end; };
   if (q_begin < q_end) {
-    load_rows(q_begin);
-    load_tile(q_begin);
-    if (q_begin + DWQ < q_end) load_rows(q_begin + DWQ);
+    load_rows(q_begin, is_full(q_begin));
+    load_tile(q_begin, is_full(q_begin));
+    if (q_begin + DWQ < q_end) load_rows(q_begin + DWQ, is_full(q_begin + DWQ));
   }
   for (uint32_t q0 = q_begin; q0 < q_end; q0 += DWQ) {
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
-      *reinterpret_cast<u32x4*>(sA + (r0 + 16 * c) * DWLD + ch) = ra[c];
-      *reinterpret_cast<u32x4*>(sB + (r0 + 16 * c) * DWLD + ch) = rb[c];
+      *reinterpret_cast<u32x4*>(sA + (r0 + 16 * c) * DWLD + ch_lds) = ra[c];
+      *reinterpret_cast<u32x4*>(sB + (r0 + 16 * c) * DWLD + ch_lds) = rb[c];
     }
     __syncthreads();
     if (q0 + DWQ < q_end) {
-      load_tile(q0 + DWQ);
-      if (q0 + 2 * DWQ < q_end) load_rows(q0 + 2 * DWQ);
+      load_tile(q0 + DWQ, is_full(q0 + DWQ));
+      if (q0 + 2 * DWQ < q_end) load_rows(q0 + 2 * DWQ, is_full(q0 + 2 * DWQ));
     }
 #pragma unroll
     for (int ks = 0; ks < DWQ / 32; ++ks) {
       bf16x8 fa[4], fb[4];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) fa[i] = tr_frag(sA, ks * 32, wm * 64 + i * 16, lane);
+      for (int i = 0; i < 4; ++i) fa[i] = tr_frag(a_lane + ks * 32 * DWLD + i * 16);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fb[j] = tr_frag(sB, ks * 32, wn * 64 + j * 16, lane);
+      for (int j = 0; j < 4; ++j) fb[j] = tr_frag(b_lane + ks * 32 * DWLD + j * 16);
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
 #pragma unroll
