@@ -49,6 +49,8 @@ def test_treernn_fp32_forward(n_trees, max_leaves, hidden):
     (3, 5, 4, 24, 30),           # tiny: a single ragged tile
     (3, 7, 1, 40, 30),           # single-leaf trees: no cell fires, the head reads leaves' rows, dW = db = 0
     (4, 300, 1, 64, 50),         # the same for the TreeLSTM, repeated tokens
+    (4, 1, 30, 64, 50),          # a batch of one tree
+    (4, 20, 12, 1100, 100),      # a padded width above 1024: the gradient kernels' lanes take several runs of units
 ])
 def test_bf16_forward_backward(cfg, n_trees, max_leaves, hidden, vocab):
     c = make_config(cfg, n_trees=n_trees, max_leaves=max_leaves, hidden=hidden, vocab=vocab)
