@@ -537,8 +537,9 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
   if (MODE == LSTM_FWD) {
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
-      cl[rr] = o_l[rr] >= g.leaf_rows ? g.Cs[(size_t)o_l[rr] * g.Hp + unit] : 0.f;
-      cr[rr] = o_r[rr] >= g.leaf_rows ? g.Cs[(size_t)o_r[rr] * g.Hp + unit] : 0.f;
+      // (a leaf child has no stored cell state: it reads row 0, a leaf's row that k_embed keeps zero)
+      cl[rr] = g.Cs[(o_l[rr] >= g.leaf_rows ? o_l[rr] : 0u) * (uint32_t)g.Hp + (uint32_t)unit];
+      cr[rr] = g.Cs[(o_r[rr] >= g.leaf_rows ? o_r[rr] : 0u) * (uint32_t)g.Hp + (uint32_t)unit];
     }
   }
 
@@ -633,21 +634,22 @@ __device__ __forceinline__ void cell_small_tile(const GemmArgs& g, int rt, int c
     }
 
   if constexpr (MODE == LSTM_FWD) {
-    const float bi = g.bias[unit], bfl = g.bias[g.Hp + unit], bfr = g.bias[2 * g.Hp + unit];
-    const float bo = g.bias[3 * g.Hp + unit], bu = g.bias[4 * g.Hp + unit];
+    const float bi = Act<T>::pre_sigmoid(g.bias[unit]), bfl = Act<T>::pre_sigmoid(g.bias[g.Hp + unit]);
+    const float bfr = Act<T>::pre_sigmoid(g.bias[2 * g.Hp + unit]), bo = Act<T>::pre_sigmoid(g.bias[3 * g.Hp + unit]);
+    const float bu = Act<T>::pre_tanh(g.bias[4 * g.Hp + unit]);
 #pragma unroll
     for (int rr = 0; rr < RPW; ++rr) {
       const int m = m0 + row_of(rr);
       if (m >= g.M) continue;
-      const float gi = Act<T>::sigmoid(z[0][rr] + bi);
-      const float gfl = Act<T>::sigmoid(z[1][rr] + bfl);
-      const float gfr = Act<T>::sigmoid(z[2][rr] + bfr);
-      const float go = Act<T>::sigmoid(z[3][rr] + bo);
-      const float gu = Act<T>::tanh(z[4][rr] + bu);
+      const float gi = Act<T>::sigmoid_b(z[0][rr], bi);
+      const float gfl = Act<T>::sigmoid_b(z[1][rr], bfl);
+      const float gfr = Act<T>::sigmoid_b(z[2][rr], bfr);
+      const float go = Act<T>::sigmoid_b(z[3][rr], bo);
+      const float gu = Act<T>::tanh_b(z[4][rr], bu);
       const float c = gi * gu + gfl * cl[rr] + gfr * cr[rr];
       const size_t o = (size_t)o_out[rr] * g.Hp + unit;
       g.Cs[o] = c;
-      reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh(c));
+      reinterpret_cast<T*>(g.Hs_out)[o] = from_f<T>(go * Act<T>::tanh_b(c, 0.f));
       if (g.save_gates) {
         T* gr = reinterpret_cast<T*>(g.gates) + (size_t)m * g.ldg;
         gr[unit] = from_f<T>(gi);
