@@ -430,6 +430,21 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   uint32_t rounds = 0, repeats = 0;
   const uint32_t poll = 2;          // rounds queued between two looks at the control blocks
   const int max_steps = 4096;       // steps per kernel launch
+  // Gradient runs have two more streams.  The packed copies of W depend on the caller's inputs only: they
+  // are made on one of them, beside the tag machine (again after it, should the plan change meanwhile).
+  if (P.vec && !gr->side_stream && with_grad && !no_alloc) {
+    HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
+    HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->sort_stream, hipStreamNonBlocking));
+    for (void** ev : {&gr->fork_event, &gr->join_event, &gr->fork_deep, &gr->join_deep, &gr->fork_sort, &gr->join_sort, &gr->leaves_done})
+      HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)ev, hipEventDisableTiming));
+  }
+  bool w_packed = false;
+  if (P.vec && G.cell_kind && with_grad && !no_alloc) {
+    HIP_TRY(hipEventRecord((hipEvent_t)gr->fork_sort, s));
+    HIP_TRY(hipStreamWaitEvent((hipStream_t)gr->sort_stream, (hipEvent_t)gr->fork_sort, 0));
+    vec_pack_w(v, (hipStream_t)gr->sort_stream);
+    w_packed = true;
+  }
   begin(TDF_PHASE_TAGS);
   for (;;) {
     // several machines only where each keeps to its own die; the device-scope kernel runs one
@@ -438,6 +453,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       P = Plan();
       st = make_plan(G, in, with_grad, (char*)workspace, P, want_dies);
       if (st != TDF_OK) return st;
+      w_packed = false;   // (the packed weights lie elsewhere now)
       e.out_i64 = (long long*)out->out_i64;
     }
     e.small_limit = (uint32_t)small_block;   // one pass of the single workgroup
@@ -514,6 +530,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
   bool deep_beside = false;   // ... on the side stream, beside the others
   uint32_t sh_last = 0, deep_base = 0, q_deep0 = 0, n_wide_levels = 0;
   const uint32_t* level_off = nullptr;   // by sort key; in the pinned buffer
+  bool gcount_fetched = false;
   auto lvl_begin = [&](uint32_t lvl) { return level_off[(size_t)lvl * LEVEL_KEY_DIES]; };
   if (dev == TDF_OK && P.vec) {
     // ---- vector operators: leaves at once, cells level by level --------------------------
@@ -524,17 +541,11 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     else locks.control.unlock();
     auto enter_data_stage = [&]() { if (!locks.data.owns_lock()) locks.data.lock(); };
     e.row0 = hc.n_leaf;   // leaf i has row i, the cell at position q of the sorted log row n_leaf + q
-    if (!gr->side_stream && with_grad && !no_alloc) {
-      HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->side_stream, hipStreamNonBlocking));
-      HIP_TRY(hipStreamCreateWithFlags((hipStream_t*)&gr->sort_stream, hipStreamNonBlocking));
-      for (void** ev : {&gr->fork_event, &gr->join_event, &gr->fork_deep, &gr->join_deep, &gr->fork_sort, &gr->join_sort, &gr->leaves_done})
-        HIP_TRY(hipEventCreateWithFlags((hipEvent_t*)ev, hipEventDisableTiming));
-    }
     hipStream_t s2 = (hipStream_t)gr->side_stream, s3 = (hipStream_t)gr->sort_stream;
     auto begin2 = [&](int ph) { if (timed) { (void)hipEventRecord((hipEvent_t)gr->events[2 * ph], s2); phase_used[ph] = true; } };
     auto end2 = [&](int ph, int64_t n) { if (timed) (void)hipEventRecord((hipEvent_t)gr->events[2 * ph + 1], s2); launches[ph] += n; };
     begin(TDF_PHASE_LEAVES);
-    if (G.cell_kind) vec_pack_w(v, s);   // (a program of EMBEDs alone has no W: the pointers may be NULL)
+    if (G.cell_kind && !w_packed) vec_pack_w(v, s);   // (a program of EMBEDs alone has no W: the pointers may be NULL)
     if (!with_grad) vec_embed(v, e, hc.n_leaf, s);
     end(TDF_PHASE_LEAVES, 2);
     if (with_grad) {
@@ -545,11 +556,17 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       HIP_TRY(hipStreamWaitEvent(s3, (hipEvent_t)gr->fork_sort, 0));
       vec_embed(v, e, hc.n_leaf, s3);
       HIP_TRY(hipEventRecord((hipEvent_t)gr->leaves_done, s3));
+    }
+    // (the token sort is put on its stream only after the level sort is on the caller's: the host's time
+    // for its launches is not in the way of the first cell launch then)
+    auto token_sort = [&]() -> tdf_status {
+      if (!with_grad) return TDF_OK;
       vec_embed_sort(v, e, hc.n_leaf, (uint32_t*)(base + P.off_tok_count), (uint32_t*)(base + P.off_seg_off),
                      (uint32_t*)(base + P.off_chunk_off), (uint32_t*)(base + P.off_tok_fill),
                      (uint32_t*)(base + P.off_sorted), DE_CHUNK, s3);
       HIP_TRY(hipEventRecord((hipEvent_t)gr->join_sort, s3));
-    }
+      return TDF_OK;
+    };
     // Instances never exchange values, so instances whose recursion is deep (long chains: many
     // levels of a few cells each, bound by latency) can run beside the others (few levels of many
     // cells each, bound by throughput) instead of after them.  An instance is deep if its root's
@@ -576,6 +593,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       level_off = (const uint32_t*)((char*)gr->pinned + PIN_LEVELS);
       HIP_TRY(hipMemcpyAsync((void*)level_off, e.level_off, level_bytes, hipMemcpyDeviceToHost, s));
       end(TDF_PHASE_LEVELS, 6);
+      if (tdf_status ts_ = token_sort(); ts_ != TDF_OK) return ts_;
       HIP_TRY(hipStreamSynchronize(s));
       enter_data_stage();
       if (with_grad) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->leaves_done, 0));   // the cells read the leaves' rows
@@ -639,6 +657,7 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
       }
     }
     if (!hc.n_cell) {   // leaves only
+      if (tdf_status ts_ = token_sort(); ts_ != TDF_OK) return ts_;
       enter_data_stage();
       vec_number_rows(e, hc.n_leaf, 0, G.has_head, G.out_type == T_VEC, s);
       if (with_grad) HIP_TRY(hipStreamWaitEvent(s, (hipEvent_t)gr->leaves_done, 0));
@@ -703,6 +722,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     HIP_TRY(hipGetLastError());
     const DieSync* ts = (const DieSync*)((char*)gr->pinned + PIN_SYNC);
     if (use_tail || deep) HIP_TRY(hipMemcpyAsync((void*)ts, base + P.off_tail_sync, sizeof(DieSync) * 16, hipMemcpyDeviceToHost, s));
+    if (stats && with_grad) {   // (with the same synchronisation: how often the gradient bodies fired)
+      HIP_TRY(hipMemcpyAsync((char*)gr->pinned + PIN_FIRE, base + P.off_gcount, sizeof(unsigned long long) * 2, hipMemcpyDeviceToHost, s));
+      gcount_fetched = true;
+    }
     if (with_grad && !no_alloc && locks.data.owns_lock()) {
       // Once the gradient pass is through (the event that the embedding gradient was forked at), what is
       // left of this evaluation are the weight and embedding sums: ordinary launches, no workgroups that
@@ -747,8 +770,10 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     stats->deep_cells = deep ? (int64_t)(hc.n_cell - q_deep0) : 0;
     unsigned long long* pin_counts = (unsigned long long*)((char*)gr->pinned + PIN_FIRE);
     if (with_grad && dev == TDF_OK && P.vec) {
-      HIP_TRY(hipMemcpyAsync(pin_counts, base + P.off_gcount, sizeof(unsigned long long) * 2, hipMemcpyDeviceToHost, s));
-      HIP_TRY(hipStreamSynchronize(s));
+      if (!gcount_fetched) {
+        HIP_TRY(hipMemcpyAsync(pin_counts, base + P.off_gcount, sizeof(unsigned long long) * 2, hipMemcpyDeviceToHost, s));
+        HIP_TRY(hipStreamSynchronize(s));
+      }
       stats->n_grad_firings = (int64_t)pin_counts[0];
       stats->n_grad_not_once = (int64_t)pin_counts[1];
     }
