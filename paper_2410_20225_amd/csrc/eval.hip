@@ -825,10 +825,12 @@ tdf_status run(tdf_graph* gr, const tdf_inputs* in, const tdf_seed* dy, tdf_outp
     }
     stats->device_status = -(int32_t)hc.status;
     stats->n_counts = (int32_t)G.snodes.size();
-    if (in->stats_level >= 1) launch_count_fired(G.prog, e, s);
-    HIP_TRY(hipMemcpyAsync(pin_counts, e.fire_count, sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS, hipMemcpyDeviceToHost, s));
-    HIP_TRY(hipStreamSynchronize(s));
-    for (int i = 0; i < TDF_STATS_MAX_COUNTS; ++i) stats->fire_count[i] = (int64_t)pin_counts[i];
+    if (in->stats_level >= 1) {   // (below that level the counts are not taken: fire_count stays zero, no read-back)
+      launch_count_fired(G.prog, e, s);
+      HIP_TRY(hipMemcpyAsync(pin_counts, e.fire_count, sizeof(unsigned long long) * TDF_STATS_MAX_COUNTS, hipMemcpyDeviceToHost, s));
+      HIP_TRY(hipStreamSynchronize(s));
+      for (int i = 0; i < TDF_STATS_MAX_COUNTS; ++i) stats->fire_count[i] = (int64_t)pin_counts[i];
+    }
   }
   return dev;
 }

@@ -293,8 +293,13 @@ void launch_class_keys(const DevProgram& P, const Engine& e, uint32_t n_cell, ui
 
 // Counting sort of the cell log by sort key (n_keys keys); level_off[k] = first cell of key k.
 void launch_levels(const Engine& e, uint32_t n_cell, uint32_t n_keys, hipStream_t s) {
-  (void)hipMemsetAsync(e.level_count, 0, sizeof(uint32_t) * n_keys, s);
-  (void)hipMemsetAsync(e.level_fill, 0, sizeof(uint32_t) * n_keys, s);
+  // (the two arrays lie one behind the other in the workspace: one fill)
+  if (e.level_fill > e.level_count) {
+    (void)hipMemsetAsync(e.level_count, 0, (size_t)((char*)(e.level_fill + n_keys) - (char*)e.level_count), s);
+  } else {
+    (void)hipMemsetAsync(e.level_count, 0, sizeof(uint32_t) * n_keys, s);
+    (void)hipMemsetAsync(e.level_fill, 0, sizeof(uint32_t) * n_keys, s);
+  }
   if (bucket_fits(n_keys)) {
     const size_t lds = (size_t)n_keys * 4;
     bucket_lds_opt_in(reinterpret_cast<const void*>(&k_bucket_count), n_keys);
