@@ -773,20 +773,31 @@ __global__ void k_pack_w(VecArgs v) {
   }
 }
 
-// ---- leaves: state row = E[token], zero padding, zero cell state -----------------------------
+// ---- leaves: state row = E[token], zero padding; no cell state (row 0 of Cs is kept zero in its place) ----
+// A group of `lpl` lanes (a power of two, at least the row's 16-byte chunks up to 64) copies one leaf's row
+// in 16-byte chunks where the rows of E are aligned for that (H a multiple of the chunk), else element by
+// element.
 template <int DT>
-__global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf) {
+__global__ void k_embed(VecArgs v, Engine e, uint32_t n_leaf, int lpl) {
   typedef typename TypeOf<DT>::type T;
-  const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
-  const int n_waves = (gridDim.x * blockDim.x) >> 6;
-  for (uint32_t i = wave; i < n_leaf; i += n_waves) {
-    const uint32_t row = i, tok = e.leaf_tok[i];   // (token ids were checked when the leaf fired)
+  constexpr int EPC = 16 / (int)sizeof(T);
+  const uint32_t tid = blockIdx.x * blockDim.x + threadIdx.x, n_threads = gridDim.x * blockDim.x;
+  if (v.cell_kind == 2 && tid < (uint32_t)v.Hp) v.Cs[tid] = 0.f;   // (Hp <= 8192 <= threads of the launch: see vec_embed)
+  const uint32_t group = tid / (uint32_t)lpl, n_groups = n_threads / (uint32_t)lpl;
+  const int gl = (int)(tid % (uint32_t)lpl);
+  const bool chunks = v.H % EPC == 0 && reinterpret_cast<uintptr_t>(v.E) % 16 == 0;
+  for (uint32_t i = group; i < n_leaf; i += n_groups) {
+    const uint32_t tok = e.leaf_tok[i];   // (token ids were checked when the leaf fired)
     const T* src = reinterpret_cast<const T*>(v.E) + (size_t)(tok < (uint32_t)v.vocab ? tok : 0) * v.H;
-    T* dst = reinterpret_cast<T*>(v.Hs) + (size_t)row * v.Hp;
-    for (int n = lane; n < v.Hp; n += 64) dst[n] = n < v.H ? src[n] : from_f<T>(0.f);
-    // leaves have no cell state; row 0, a leaf's, is kept zero for the cells that read a leaf child's
-    if (i == 0 && v.cell_kind == 2)
-      for (int n = lane; n < v.Hp; n += 64) v.Cs[n] = 0.f;
+    T* dst = reinterpret_cast<T*>(v.Hs) + (size_t)i * v.Hp;   // leaf i has row i
+    if (chunks) {
+      for (int n = gl * EPC; n < v.Hp; n += lpl * EPC) {
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4*>(dst + n) = n < v.H ? *reinterpret_cast<const u32x4*>(src + n) : zero;
+      }
+    } else {
+      for (int n = gl; n < v.Hp; n += lpl) dst[n] = n < v.H ? src[n] : from_f<T>(0.f);
+    }
   }
 }
 
@@ -1600,9 +1611,14 @@ void vec_pack_w(const VecArgs& v, hipStream_t s) {
 
 void vec_embed(const VecArgs& v, const Engine& e, uint32_t n_leaf, hipStream_t s) {
   if (!n_leaf) return;
-  int blocks = (int)std::min<uint32_t>((n_leaf + 3) / 4, 8192u);
-  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_embed<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
-  else hipLaunchKernelGGL(k_embed<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf);
+  const int epc = v.dtype == TDF_BF16 ? 8 : 4;
+  int lpl = 1;   // lanes per leaf: the row's 16-byte chunks rounded up to a power of two, at most 64
+  while (lpl < 64 && lpl * epc < v.Hp) lpl *= 2;
+  const uint32_t per_block = 256u / (uint32_t)lpl;
+  // at least 8192 threads, so that the first Hp of them can clear row 0 of Cs
+  const int blocks = (int)std::min<uint32_t>(std::max<uint32_t>((n_leaf + per_block - 1) / per_block, 32u), 8192u);
+  if (v.dtype == TDF_BF16) hipLaunchKernelGGL(k_embed<TDF_BF16>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf, lpl);
+  else hipLaunchKernelGGL(k_embed<TDF_F32>, dim3(blocks), dim3(256), 0, s, v, e, n_leaf, lpl);
 }
 
 template <typename T> static void cell_fwd_t(const VecArgs& v, const Engine& e, uint32_t q0, uint32_t count,
