@@ -33,8 +33,8 @@ COPY_BYTES = 1 << 30    # calibration copy: 1 GiB read + 1 GiB written
 # profiles/bench_workload4_hbm_traffic.md), with the hash of the kernel source they were taken on:
 # reported as `traffic` only while that source is unchanged.
 MEASURED_TRAFFIC = {
-    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "6b2258973b2e3bc1", 1926414834.0),
-        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "2fd8b76edf21f18c", 337793113.8)},
+    4: {"cells": ("paper_2410_20225_amd/csrc/cells.hip", "dda69c6299073a74", 1925062852.9),
+        "steps": ("paper_2410_20225_amd/csrc/step_device.h", "2fd8b76edf21f18c", 337757515.5)},
 }
 
 
